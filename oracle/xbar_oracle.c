@@ -1,0 +1,343 @@
+/*
+ * TEST INFRASTRUCTURE -- scalar CPU oracle of the non-ideal crossbar training operations.
+ *
+ * This file is the plain, slow, obviously-correct statement of what the GPU library must compute.
+ * It is only ever used by the tests, by the smoke check and by the "cpu_baseline" leg of the
+ * benchmark.  It shares no code, header, table or constant with the HIP path (the parameter struct
+ * below is re-typed by hand), every floating-point step is IEEE double, every integer step is
+ * int64, all loops are scalar and run in index order.
+ *
+ * What is modelled (TxSim, arXiv 2002.11151):
+ *   Sec. IV    -- a layer is DAC model -> crossbar array model -> ADC model, in the forward and in
+ *                 the backward pass; inputs are scaled before the DAC and outputs after the ADC.
+ *   Sec. IV-A  -- non-ideal conductance matrix generator: weights are mapped to one or more
+ *                 limited-precision devices (bit slices), partitioned into crossbar instances,
+ *                 split into a positive and a negative array whose currents are subtracted,
+ *                 process variation is applied per device, then the wire-parasitic model
+ *                 converts ideal into non-ideal conductances and the instances are stitched.
+ *   Sec. IV-B  -- three-stage model: digital inputs -> voltages, voltages x non-ideal
+ *                 conductances -> column currents, currents -> ADC codes.
+ *   Sec. IV-C  -- update model: gradient -> scale -> ideal conductance change -> state dependent
+ *                 write non-linearity (factor v) -> Gaussian write noise (factor gamma) ->
+ *                 times learning rate, subtracted from the stored conductance.
+ *   Sec. IV-D  -- approximate analytical model (shortest path per device, series resistance of
+ *                 source, row wire, column wire and sense) and the stored distortion profile
+ *                 D = (G_ideal - G_nonideal) / G_ideal of interpolated FCM.
+ *   Sec. V     -- default parameters (Rmin 100 kOhm, Rmax 1 MOhm, 1 Ohm / 4.6 Ohm wire per cell,
+ *                 2-bit devices, bit-streamed inputs).
+ *
+ * Readings taken where the paper is silent are listed next to the code that takes them.
+ * PARITY UNPINNED (no printed value or formula survives in the paper text): the shape of the
+ * update non-linearity (Eq. 1 is an image), the DAC transfer table, the units of gamma.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* flag bits (same numeric values as the library's, typed again here on purpose) */
+#define XO_VARIATION    1u
+#define XO_WIRE_AAM     2u
+#define XO_WIRE_PROFILE 4u
+#define XO_UPD_NL       8u
+#define XO_UPD_NOISE    16u
+#define XO_DAC_LUT      32u
+#define XO_INPUT_SIGNED 64u
+
+#define XO_STREAM_VARIATION 1u
+#define XO_STREAM_WRITE     2u
+
+typedef struct xo_config {
+  uint32_t struct_size, abi_version;
+  int32_t xbar_rows, xbar_cols;
+  int32_t weight_bits, slice_bits;
+  int32_t input_bits, stream_bits;
+  int32_t adc_bits;
+  uint32_t flags;
+  float r_min, r_max;
+  float v_max;
+  float r_row, r_col;
+  float r_source, r_sense;
+  float var_sigma;
+  float upd_nl_v, upd_noise_gamma;
+  float adc_fs_fwd, adc_fs_bwd;
+  float dac_lut[16];
+  uint64_t seed;
+} xo_config;
+
+/* ------------------------------------------------------------------------------------------- */
+/* Counter-based random numbers: Philox-4x32 with 10 rounds (Salmon et al., SC'11), written from */
+/* the published round function; then Box-Muller.  The paper only says "Gaussian".              */
+/* ------------------------------------------------------------------------------------------- */
+void xo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+    uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    uint32_t n1 = (uint32_t)p1;
+    uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Standard normal number i of (seed, stream, step).  Four consecutive i share one Philox block:
+ * words (0,1) give numbers 0 and 1 (cosine and sine branch), words (2,3) give numbers 2 and 3. */
+double xo_normal(uint64_t seed, uint32_t stream, uint64_t step, uint64_t i) {
+  uint64_t blk = i >> 2;
+  uint32_t ctr[4] = {(uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step, (uint32_t)(step >> 32)};
+  uint32_t key[2] = {(uint32_t)seed ^ (0x9E3779B9u * stream),
+                     (uint32_t)(seed >> 32) ^ (0xBB67AE85u * stream)};
+  uint32_t w[4];
+  xo_philox4x32_10(ctr, key, w);
+  int pair = (int)((i & 3u) >> 1);
+  double u1 = ((double)w[2 * pair] + 0.5) * (1.0 / 4294967296.0);
+  double u2 = ((double)w[2 * pair + 1] + 0.5) * (1.0 / 4294967296.0);
+  double r = sqrt(-2.0 * log(u1));
+  double th = 6.283185307179586476925286766559 * u2;
+  return (i & 1u) ? r * sin(th) : r * cos(th);
+}
+
+/* ------------------------------------------------------------------------------------------- */
+static double clampd(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+/* Sec. IV-A, first generator step: a weight becomes a signed integer of weight_bits magnitude
+ * bits (the sign selects the positive or the negative array).  Rounding: half to even.        */
+int64_t xo_quantize_weight(float w, float w_max, int weight_bits) {
+  double qw = (double)((1ll << weight_bits) - 1);
+  return (int64_t)rint(clampd((double)w / (double)w_max, -1.0, 1.0) * qw);
+}
+
+/* Digits of a magnitude, least significant slice first: one digit per limited-precision device. */
+void xo_digits(uint64_t mag, int digit_bits, int n_digits, int32_t* d) {
+  for (int s = 0; s < n_digits; ++s)
+    d[s] = (int32_t)((mag >> (digit_bits * s)) & ((1ull << digit_bits) - 1));
+}
+
+/* Sec. IV: inputs are scaled, then quantised to input_bits magnitude bits (half to even).
+ * Unsigned inputs clamp to [0,1], signed ones to [-1,1].                                        */
+int64_t xo_quantize_input(float x, float x_scale, int input_bits, int is_signed) {
+  double qa = (double)((1ll << input_bits) - 1);
+  return (int64_t)rint(clampd((double)x / (double)x_scale, is_signed ? -1.0 : 0.0, 1.0) * qa);
+}
+
+/* ADC of Sec. IV-B with the identity transfer curve: a signed mid-tread quantiser that saturates.
+ * The gain is the single-precision quotient Q / full_scale (the precision the converter
+ * decision is defined in); the product with the current and the rounding are done exactly.    */
+int64_t xo_adc(double current, float full_scale, int adc_bits) {
+  int64_t q = (1ll << (adc_bits - 1)) - 1;
+  float gain = (float)q / full_scale;
+  double c = rint(current * (double)gain);
+  if (c > (double)q) c = (double)q;
+  if (c < -(double)q) c = -(double)q;
+  return (int64_t)c;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* Non-ideal conductance matrix generator (Sec. IV-A, IV-D).                                    */
+/* Output: U[s][ki][ni] = (G+ - G-) / dG, the stitched signed plane of slice s in units of one  */
+/* device level, for the weights W[ki][ni] that sit at absolute positions (k_idx[ki], n_idx[ni]) */
+/* of a K_full x N_full layer (NULL index arrays mean the identity).                            */
+/* profile: D[s][pol][k][n] over the full layer (pol 0 = positive array), or NULL.              */
+/* ------------------------------------------------------------------------------------------- */
+int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_t* k_idx,
+              const int32_t* n_idx, int K_full, int N_full, float w_max, uint64_t step,
+              const float* profile, double* U) {
+  const int R = cfg->xbar_rows, C = cfg->xbar_cols;
+  const int S = cfg->weight_bits / cfg->slice_bits;
+  const int levels = (1 << cfg->slice_bits) - 1;
+  const double g_min = 1.0 / (double)cfg->r_max;
+  const double g_max = 1.0 / (double)cfg->r_min;
+  const double dg = (g_max - g_min) / (double)levels;
+  const uint32_t array_ni = cfg->flags & (XO_VARIATION | XO_WIRE_AAM | XO_WIRE_PROFILE);
+  int32_t d[64];
+  if (S > 64) return -1;
+  for (int ki = 0; ki < Ks; ++ki) {
+    for (int ni = 0; ni < Ns; ++ni) {
+      const int64_t k = k_idx ? k_idx[ki] : ki;
+      const int64_t n = n_idx ? n_idx[ni] : ni;
+      const int64_t q = xo_quantize_weight(W[(size_t)ki * Ns + ni], w_max, cfg->weight_bits);
+      const int sign = (q > 0) - (q < 0);
+      xo_digits((uint64_t)(q < 0 ? -q : q), cfg->slice_bits, S, d);
+      for (int s = 0; s < S; ++s) {
+        double* out = &U[((size_t)s * Ks + ki) * Ns + ni];
+        if (!array_ni) {            /* ideal arrays: the pair difference is the digit itself */
+          *out = (double)(sign * d[s]);
+          continue;
+        }
+        /* the array that carries the sign of the weight holds the digit, the other one rests
+         * at the lowest conductance                                                          */
+        double g[2];
+        g[0] = g_min + (sign > 0 ? d[s] * dg : 0.0);
+        g[1] = g_min + (sign < 0 ? d[s] * dg : 0.0);
+        for (int pol = 0; pol < 2; ++pol) {
+          if (cfg->flags & XO_VARIATION) {   /* independent multiplicative Gaussian per device */
+            uint64_t dev = (((uint64_t)k * (uint64_t)N_full + (uint64_t)n) * (uint64_t)S + s) * 2 + pol;
+            g[pol] *= 1.0 + (double)cfg->var_sigma * xo_normal(cfg->seed, XO_STREAM_VARIATION, step, dev);
+          }
+          if (cfg->flags & XO_WIRE_AAM) {    /* single shortest path through device (i, j)     */
+            int i = (int)(k % R), j = (int)(n % C);
+            double rho = (double)cfg->r_source + (double)(j + 1) * (double)cfg->r_row +
+                         (double)(R - i) * (double)cfg->r_col + (double)cfg->r_sense;
+            g[pol] = g[pol] / (1.0 + rho * g[pol]);
+          } else if (cfg->flags & XO_WIRE_PROFILE) {   /* stored distortion, Sec. IV-D          */
+            double dist = (double)profile[(((size_t)s * 2 + pol) * K_full + k) * N_full + n];
+            g[pol] = g[pol] * (1.0 - dist);
+          }
+        }
+        *out = (g[0] - g[1]) / dg;
+      }
+    }
+  }
+  return 0;
+}
+
+/* DAC of Sec. IV-B: digit of one streaming cycle -> row voltage in units of one input level. */
+static double dac(const xo_config* cfg, int digit) {
+  if (cfg->flags & XO_DAC_LUT) return (double)cfg->dac_lut[digit] * (double)((1 << cfg->stream_bits) - 1);
+  return (double)digit;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* One VMM pass through the tiles (Sec. IV, IV-B).                                              */
+/*   transposed == 0 (forward):  in[M][L_in = K], out[M][L_out = Ns]; U[s][K][Ns];             */
+/*                               the contraction runs over the rows of one row tile,            */
+/*                               results of the row tiles are added digitally.                  */
+/*   transposed == 1 (backward): in[M][L_in = N], out[M][L_out = Ks]; U[s][Ks][N];             */
+/*                               the same devices are driven from the columns, currents are     */
+/*                               read on the rows, contraction over the columns of one column   */
+/*                               tile, results of the column tiles are added digitally.         */
+/* Every (tile, slice, cycle, phase) current gets its own ADC conversion, then shift-and-add.   */
+/* codes (optional): [phase][cycle][slice][tile][m][out] as int32; acc (optional): the integer  */
+/* shift-and-add result per output before the final scaling.                                    */
+/* ------------------------------------------------------------------------------------------- */
+static int vmm(const xo_config* cfg, const double* U, int Ks, int Ns, int transposed, const float* in,
+               float* out, int M, float in_scale, float w_max, int is_signed, float adc_fs,
+               int32_t* codes, int64_t* acc_out) {
+  const int S = cfg->weight_bits / cfg->slice_bits;
+  const int B = cfg->input_bits / cfg->stream_bits;
+  const int P = is_signed ? 2 : 1;
+  const int L_in = transposed ? Ns : Ks;
+  const int L_out = transposed ? Ks : Ns;
+  const int tile = transposed ? cfg->xbar_cols : cfg->xbar_rows;
+  const int T = (L_in + tile - 1) / tile;
+  const int64_t q_adc = (1ll << (cfg->adc_bits - 1)) - 1;
+  const double lsb = (double)adc_fs / (double)q_adc;
+  const double qa = (double)((1ll << cfg->input_bits) - 1);
+  const double qw = (double)((1ll << cfg->weight_bits) - 1);
+  const double scale = lsb * (double)in_scale * (double)w_max / (qa * qw);
+  int64_t* a = (int64_t*)malloc(sizeof(int64_t) * (size_t)L_in);
+  if (!a) return -2;
+  for (int m = 0; m < M; ++m) {
+    for (int l = 0; l < L_in; ++l)
+      a[l] = xo_quantize_input(in[(size_t)m * L_in + l], in_scale, cfg->input_bits, is_signed);
+    for (int o = 0; o < L_out; ++o) {
+      int64_t acc = 0;
+      for (int p = 0; p < P; ++p)
+        for (int b = 0; b < B; ++b)
+          for (int s = 0; s < S; ++s)
+            for (int t = 0; t < T; ++t) {
+              int l0 = t * tile, l1 = l0 + tile < L_in ? l0 + tile : L_in;
+              double current = 0.0;
+              for (int l = l0; l < l1; ++l) {
+                int64_t mag = p == 0 ? (a[l] > 0 ? a[l] : 0) : (a[l] < 0 ? -a[l] : 0);
+                int digit = (int)((mag >> (cfg->stream_bits * b)) & ((1 << cfg->stream_bits) - 1));
+                double u = transposed ? U[((size_t)s * Ks + o) * Ns + l] : U[((size_t)s * Ks + l) * Ns + o];
+                current += dac(cfg, digit) * u;
+              }
+              int64_t code = xo_adc(current, adc_fs, cfg->adc_bits);
+              if (codes)
+                codes[(((((size_t)p * B + b) * S + s) * T + t) * M + m) * L_out + o] = (int32_t)code;
+              int64_t weight = 1ll << (cfg->slice_bits * s + cfg->stream_bits * b);
+              acc += (p == 0 ? 1 : -1) * weight * code;
+            }
+      if (acc_out) acc_out[(size_t)m * L_out + o] = acc;
+      out[(size_t)m * L_out + o] = (float)((double)acc * scale);
+    }
+  }
+  free(a);
+  return 0;
+}
+
+int xo_fwd_planes(const xo_config* cfg, const double* U, const float* X, float* Y, int M, int K, int Ns,
+                  float w_max, float x_scale, int32_t* codes, int64_t* acc) {
+  return vmm(cfg, U, K, Ns, 0, X, Y, M, x_scale, w_max, (cfg->flags & XO_INPUT_SIGNED) != 0,
+             cfg->adc_fs_fwd, codes, acc);
+}
+
+int xo_bwd_planes(const xo_config* cfg, const double* U, const float* dY, float* dX, int M, int Ks, int N,
+                  float w_max, float g_scale, int32_t* codes, int64_t* acc) {
+  return vmm(cfg, U, Ks, N, 1, dY, dX, M, g_scale, w_max, 1, cfg->adc_fs_bwd, codes, acc);
+}
+
+/* Forward VMM of a whole layer: Y[M][N] from W[K][N] and X[M][K]. */
+int xo_fwd(const xo_config* cfg, const float* W, const float* X, float* Y, int M, int K, int N, float w_max,
+           float x_scale, uint64_t step, const float* profile, int32_t* codes, int64_t* acc) {
+  double* U = (double*)malloc(sizeof(double) * (size_t)(cfg->weight_bits / cfg->slice_bits) * K * N);
+  if (!U) return -2;
+  int rc = xo_planes(cfg, W, K, N, NULL, NULL, K, N, w_max, step, profile, U);
+  if (!rc) rc = xo_fwd_planes(cfg, U, X, Y, M, K, N, w_max, x_scale, codes, acc);
+  free(U);
+  return rc;
+}
+
+/* Backward VMM of a whole layer: dX[M][K] from W[K][N] and dY[M][N], same device draw as the
+ * forward pass of the same step.                                                               */
+int xo_bwd(const xo_config* cfg, const float* W, const float* dY, float* dX, int M, int K, int N, float w_max,
+           float g_scale, uint64_t step, const float* profile, int32_t* codes, int64_t* acc) {
+  double* U = (double*)malloc(sizeof(double) * (size_t)(cfg->weight_bits / cfg->slice_bits) * K * N);
+  if (!U) return -2;
+  int rc = xo_planes(cfg, W, K, N, NULL, NULL, K, N, w_max, step, profile, U);
+  if (!rc) rc = xo_bwd_planes(cfg, U, dY, dX, M, K, N, w_max, g_scale, codes, acc);
+  free(U);
+  return rc;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* Update model (Sec. IV-C).  W[Ks][Ns] in place; X[M][Ks], dY[M][Ns] hold the columns of the   */
+/* activations / errors that belong to the weights at absolute (k_idx, n_idx) of a layer with   */
+/* N_full columns (NULL = identity).  grad (optional) receives sum_m X dY.                     */
+/*                                                                                               */
+/* Readings: the differential pair is one effective device with normalised state                 */
+/* g = W / w_max in [-1, 1], x = (g + 1) / 2; all conductance changes are in units of            */
+/* (Gmax - Gmin).  delta = grad_scale * grad is the ideal change.  The written change is         */
+/* delta * exp(-v x) when the conductance goes up and delta * exp(-v (1 - x)) when it goes down  */
+/* (direction = sign of -lr * delta): saturating, asymmetric, equal to the ideal change at v = 0.*/
+/* Write noise: Gaussian, sigma = gamma * sqrt(|delta|) in the same units, added before the      */
+/* learning rate.  The state is clamped to the device range afterwards.                          */
+/* ------------------------------------------------------------------------------------------- */
+int xo_update(const xo_config* cfg, float* W, const float* X, const float* dY, int M, int Ks, int Ns,
+              const int32_t* k_idx, const int32_t* n_idx, int N_full, float w_max, float grad_scale, float lr,
+              uint64_t step, double* grad_out) {
+  for (int ki = 0; ki < Ks; ++ki)
+    for (int ni = 0; ni < Ns; ++ni) {
+      double grad = 0.0;
+      for (int m = 0; m < M; ++m) grad += (double)X[(size_t)m * Ks + ki] * (double)dY[(size_t)m * Ns + ni];
+      if (grad_out) grad_out[(size_t)ki * Ns + ni] = grad;
+      const uint64_t k = k_idx ? (uint64_t)k_idx[ki] : (uint64_t)ki;
+      const uint64_t n = n_idx ? (uint64_t)n_idx[ni] : (uint64_t)ni;
+      const double g = (double)W[(size_t)ki * Ns + ni] / (double)w_max;
+      const double delta = (double)grad_scale * grad;
+      double written = delta;
+      if (cfg->flags & XO_UPD_NL) {
+        double x = clampd(0.5 * (g + 1.0), 0.0, 1.0);
+        double change = -(double)lr * delta;
+        if (change > 0.0) written = delta * exp(-(double)cfg->upd_nl_v * x);
+        else if (change < 0.0) written = delta * exp(-(double)cfg->upd_nl_v * (1.0 - x));
+      }
+      if (cfg->flags & XO_UPD_NOISE) {
+        double sigma = (double)cfg->upd_noise_gamma * sqrt(fabs(delta));
+        written += sigma * xo_normal(cfg->seed, XO_STREAM_WRITE, step, k * (uint64_t)N_full + n);
+      }
+      const double g_new = clampd(g - (double)lr * written, -1.0, 1.0);
+      W[(size_t)ki * Ns + ni] = (float)((double)w_max * g_new);
+    }
+  return 0;
+}
+
+unsigned xo_config_size(void) { return (unsigned)sizeof(xo_config); }

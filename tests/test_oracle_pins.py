@@ -1,0 +1,503 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test checks the oracle against something other than itself: a published known-answer vector, a
+closed form, a textbook special case (integer matmul, plain SGD, series resistors), the exact circuit
+solution of a small tile, statistics of the random draws, or a brute-force re-derivation on tiny
+inputs.  The paper prints no numeric worked example, so there are no paper-value fixtures.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy import stats
+
+import workloads
+from oracle import nodal
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+# ------------------------------------------------------------------------------------------------
+# random numbers
+# ------------------------------------------------------------------------------------------------
+def test_philox_known_answers(xo):
+    n = 0
+    for line in open(os.path.join(GOLDEN, "philox4x32_10_kat.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        w = [int(t, 16) for t in line.split()]
+        assert xo.philox4x32_10(w[0:4], w[4:6]) == w[6:10]
+        n += 1
+    assert n == 2
+
+
+def test_normal_moments_and_distribution(xo):
+    z = xo.normals(seed=7, stream=xo.STREAM_WRITE, step=3, i0=0, count=200000)
+    assert abs(z.mean()) < 4 / math.sqrt(z.size)
+    assert abs(z.var() - 1.0) < 0.02
+    assert abs(stats.skew(z)) < 0.03 and abs(stats.kurtosis(z)) < 0.06
+    assert stats.kstest(z, "norm").pvalue > 1e-3
+    # the four numbers of one block and neighbouring blocks are uncorrelated
+    for lag in (1, 2, 3, 4):
+        assert abs(np.corrcoef(z[:-lag], z[lag:])[0, 1]) < 0.01
+
+
+def test_normal_keying(xo):
+    a = xo.normals(1, 1, 0, 0, 64)
+    assert np.array_equal(a, xo.normals(1, 1, 0, 0, 64))          # reproducible
+    for other in (xo.normals(2, 1, 0, 0, 64), xo.normals(1, 2, 0, 0, 64), xo.normals(1, 1, 1, 0, 64),
+                  xo.normals(1 + (1 << 32), 1, 0, 0, 64), xo.normals(1, 1, 1 << 32, 0, 64),
+                  xo.normals(1, 1, 0, 1 << 34, 64)):
+        assert not np.any(a == other)                            # every key part matters
+
+
+# ------------------------------------------------------------------------------------------------
+# encodings
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("digit_bits,n_digits", [(2, 8), (1, 16), (4, 4), (2, 4), (4, 2), (1, 8)])
+def test_digit_recombination_is_identity(xo, digit_bits, n_digits):
+    top = 1 << (digit_bits * n_digits)
+    values = range(top) if top <= 65536 else range(0, top, 7)
+    for v in values:
+        d = xo.digits(v, digit_bits, n_digits)
+        assert all(0 <= x < (1 << digit_bits) for x in d)
+        assert sum(x << (digit_bits * s) for s, x in enumerate(d)) == v
+
+
+def test_weight_quantiser_grid_ties_clamp(xo):
+    for bits in (8, 16):
+        qw = (1 << bits) - 1
+        for j in (-qw, -3, -1, 0, 1, 2, 77, qw):               # grid points map to themselves
+            assert xo.quantize_weight(np.float32(j / qw * 0.5), 0.5, bits) == j
+    # exact ties round to even: w/w_max * 255 = 0.5, 1.5, 2.5 with w_max = 255
+    assert [xo.quantize_weight(x, 255.0, 8) for x in (0.5, 1.5, 2.5, -0.5, -1.5)] == [0, 2, 2, 0, -2]
+    assert xo.quantize_weight(9.0, 1.0, 8) == 255 and xo.quantize_weight(-9.0, 1.0, 8) == -255
+
+
+def test_input_quantiser(xo):
+    assert [xo.quantize_input(x, 255.0, 8, True) for x in (0.5, 1.5, -2.5, 300.0, -300.0)] == [0, 2, -2, 255, -255]
+    assert [xo.quantize_input(x, 255.0, 8, False) for x in (-7.0, 3.0, 300.0)] == [0, 3, 255]
+    assert xo.quantize_input(1.0, 1.0, 4, False) == 15
+
+
+def test_adc_closed_form(xo):
+    # lsb = 2: odd currents sit exactly between two codes -> even code; saturation at +-Q
+    q = 127
+    for cur, code in ((0, 0), (1, 0), (2, 1), (3, 2), (5, 2), (7, 4), (-3, -2), (253, 126), (254, 127),
+                      (255, 127), (1000, 127), (-255, -127), (-1e9, -127)):
+        assert xo.adc(float(cur), 2.0 * q, 8) == code
+    # lsb = 128/127: current 64 is an exact tie between 63 and 64
+    assert xo.adc(64.0, 128.0, 8) == 64 and xo.adc(192.0, 128.0, 8) == 127
+    # ramp across the clip point, lsb = 1
+    for bits in (4, 6, 8, 12):
+        q = (1 << (bits - 1)) - 1
+        for cur in range(-q - 5, q + 6):
+            assert xo.adc(float(cur), float(q), bits) == max(-q, min(q, cur))
+        assert xo.adc(0.49, float(q), bits) == 0 and xo.adc(0.51, float(q), bits) == 1
+
+
+# ------------------------------------------------------------------------------------------------
+# ideal crossbars: exact integer arithmetic
+# ------------------------------------------------------------------------------------------------
+def _ideal_cfg(xo, R, C, stream_bits, slice_bits, weight_bits, signed, adc_bits=None):
+    worst = max(R, C) * ((1 << stream_bits) - 1) * ((1 << slice_bits) - 1)
+    adc_bits = adc_bits or (int(math.ceil(math.log2(worst + 1))) + 1)
+    q = (1 << (adc_bits - 1)) - 1
+    return xo.make_config(xbar_rows=R, xbar_cols=C, weight_bits=weight_bits, slice_bits=slice_bits,
+                          input_bits=8, stream_bits=stream_bits, adc_bits=adc_bits,
+                          flags=xo.INPUT_SIGNED if signed else 0, adc_fs_fwd=float(q), adc_fs_bwd=float(q))
+
+
+def _int_grid_tensors(rng, M, K, N, wbits, signed):
+    """Tensors that sit exactly on the quantiser grids, so the integers are known without quantising."""
+    qw, qa = (1 << wbits) - 1, 255
+    q = rng.integers(-qw, qw + 1, size=(K, N))
+    a = rng.integers(-qa if signed else 0, qa + 1, size=(M, K))
+    w_max, x_scale = 1.0, 1.0
+    W = (q.astype(np.float64) / qw).astype(np.float32)
+    X = (a.astype(np.float64) / qa).astype(np.float32)
+    return q, a, W, X, w_max, x_scale
+
+
+@pytest.mark.parametrize("R,C,sb,slb,wb,signed,M,K,N", [
+    (8, 8, 1, 2, 8, False, 5, 19, 11),
+    (8, 4, 4, 2, 8, True, 3, 8, 9),
+    (16, 16, 2, 1, 8, True, 4, 40, 17),
+    (64, 64, 4, 2, 8, True, 6, 150, 70),
+    (128, 128, 1, 2, 16, False, 3, 147, 64),
+])
+def test_fwd_ideal_full_precision_is_integer_matmul(xo, R, C, sb, slb, wb, signed, M, K, N):
+    rng = np.random.default_rng(R + K)
+    cfg = _ideal_cfg(xo, R, C, sb, slb, wb, signed)
+    q, a, W, X, w_max, x_scale = _int_grid_tensors(rng, M, K, N, wb, signed)
+    Y, acc = xo.fwd(cfg, W, X, w_max, x_scale, want_acc=True)
+    assert np.array_equal(acc, a @ q)                              # textbook integer matmul
+    ref = (a @ q).astype(np.float64) / (255.0 * ((1 << wb) - 1))
+    assert np.allclose(Y, ref, rtol=1e-6, atol=0)
+
+
+@pytest.mark.parametrize("R,C,sb,slb,wb,M,K,N", [(8, 4, 1, 2, 8, 5, 19, 11), (64, 64, 4, 2, 8, 4, 70, 150),
+                                                (16, 32, 2, 2, 16, 3, 33, 65)])
+def test_bwd_ideal_full_precision_is_transposed_integer_matmul(xo, R, C, sb, slb, wb, M, K, N):
+    rng = np.random.default_rng(C + N)
+    cfg = _ideal_cfg(xo, R, C, sb, slb, wb, True)
+    q, _, W, _, w_max, _ = _int_grid_tensors(rng, M, K, N, wb, True)
+    e = rng.integers(-255, 256, size=(M, N))
+    dY = (e.astype(np.float64) / 255 * 0.01).astype(np.float32)
+    dX, acc = xo.bwd(cfg, W, dY, w_max, 0.01, want_acc=True)
+    assert np.array_equal(acc, e @ q.T)
+    assert np.allclose(dX, (e @ q.T) * (0.01 / (255.0 * ((1 << wb) - 1))), rtol=1e-6, atol=0)
+
+
+def test_fwd_ideal_adc_code_closed_form(xo):
+    # all rows driven with the same digit a, all devices of a column hold the same digit d:
+    # tile current = rows_in_tile * a * d exactly, code = clamp(rne(I / lsb))
+    R, K, N, M = 16, 40, 4, 1
+    cfg = xo.make_config(xbar_rows=R, xbar_cols=R, weight_bits=2, slice_bits=2, input_bits=4, stream_bits=4,
+                         adc_bits=6, adc_fs_fwd=62.0, adc_fs_bwd=62.0)     # Q = 31, lsb = 2
+    for a in (1, 5, 15):
+        for d in (-3, -1, 0, 2, 3):
+            W = np.full((K, N), d / 3.0, dtype=np.float32)
+            X = np.full((M, K), a / 15.0, dtype=np.float32)
+            Y, codes, acc = xo.fwd(cfg, W, X, 1.0, 1.0, want_codes=True, want_acc=True)
+            rows = [16, 16, 8]                                       # ragged last tile has 8 rows
+            expect = []
+            for r in rows:
+                cur = r * a * d
+                half = cur / 2.0
+                c = math.floor(half) if half - math.floor(half) < 0.5 else math.ceil(half)
+                if half - math.floor(half) == 0.5:
+                    c = math.floor(half) if math.floor(half) % 2 == 0 else math.ceil(half)
+                expect.append(max(-31, min(31, c)))
+            assert codes.shape == (1, 1, 1, 3, M, N)
+            assert [int(codes[0, 0, 0, t, 0, 0]) for t in range(3)] == expect
+            assert int(acc[0, 0]) == sum(expect)
+            assert Y[0, 0] == np.float32(sum(expect) * 2.0 / (15 * 3))
+
+
+def test_fwd_ideal_monotone_in_adc_bits(xo):
+    rng = np.random.default_rng(5)
+    g = workloads.Gemm("t", 96, 40, 6, False, 1)
+    W, X, _ = workloads.layer_tensors_np(g, 11)
+    w_max, x_scale = float(np.abs(W).max()), float(X.max())
+    errs = []
+    for bits in (4, 6, 8, 10, 14):
+        q = (1 << (bits - 1)) - 1
+        cfg = xo.make_config(xbar_rows=32, xbar_cols=32, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=4,
+                             adc_bits=bits, adc_fs_fwd=32.0 * 15 * 3, adc_fs_bwd=32.0 * 15 * 3)
+        Y = xo.fwd(cfg, W, X, w_max, x_scale)
+        errs.append(np.linalg.norm(Y - X.astype(np.float64) @ W.astype(np.float64)))
+    assert all(errs[i + 1] <= errs[i] * 1.05 for i in range(len(errs) - 1)) and errs[-1] < 0.05 * errs[0]
+
+
+# ------------------------------------------------------------------------------------------------
+# non-ideal arrays
+# ------------------------------------------------------------------------------------------------
+def _device_g(cfg, d):
+    g_min, g_max = 1.0 / cfg.r_max, 1.0 / cfg.r_min
+    return g_min + d * (g_max - g_min) / ((1 << cfg.slice_bits) - 1)
+
+
+def test_aam_single_cell_is_series_resistors(xo):
+    cfg = xo.make_config(xbar_rows=1, xbar_cols=1, weight_bits=2, slice_bits=2, flags=xo.WIRE_AAM,
+                         r_row=30.0, r_col=500.0, r_source=1e3, r_sense=2e3, r_min=1e4, r_max=1e5)
+    dg = (1 / 1e4 - 1 / 1e5) / 3
+    for d in (1, 2, 3):
+        U = xo.planes(cfg, np.array([[d / 3.0]], dtype=np.float32), 1.0)
+        series = lambda g: 1.0 / (1.0 / g + 1e3 + 30.0 + 500.0 + 2e3)
+        expect = (series(_device_g(cfg, d)) - series(_device_g(cfg, 0))) / dg
+        assert abs(U[0, 0, 0] - expect) < 1e-12 * abs(expect)
+        Un = xo.planes(cfg, np.array([[-d / 3.0]], dtype=np.float32), 1.0)
+        assert Un[0, 0, 0] == -U[0, 0, 0]
+        # and the exact circuit solution of a single cell is that same series connection
+        E = nodal.effective_conductance([[_device_g(cfg, d)]], 30.0, 500.0, 1e3, 2e3)
+        assert abs(E[0, 0] - series(_device_g(cfg, d))) < 1e-12 * E[0, 0]
+
+
+def test_aam_without_wire_resistance_is_ideal(xo):
+    rng = np.random.default_rng(2)
+    W = rng.uniform(-1, 1, size=(20, 12)).astype(np.float32)
+    ideal = xo.make_config(xbar_rows=8, xbar_cols=8)
+    aam0 = xo.make_config(xbar_rows=8, xbar_cols=8, flags=xo.WIRE_AAM, r_row=0.0, r_col=0.0)
+    assert np.allclose(xo.planes(aam0, W, 1.0), xo.planes(ideal, W, 1.0), rtol=0, atol=1e-12)
+
+
+def test_aam_geometry_against_path_enumeration(xo):
+    # plane value of device (i, j) inside every tile, re-derived by walking the path cell by cell
+    R, C, K, N = 4, 3, 10, 7
+    cfg = xo.make_config(xbar_rows=R, xbar_cols=C, weight_bits=4, slice_bits=2, flags=xo.WIRE_AAM,
+                         r_row=2.0, r_col=7.0, r_source=11.0, r_sense=13.0, r_min=1e3, r_max=1e4)
+    rng = np.random.default_rng(3)
+    qv = rng.integers(-15, 16, size=(K, N))
+    U = xo.planes(cfg, (qv / 15.0).astype(np.float32), 1.0)
+    dg = (1e-3 - 1e-4) / 3
+    for k in range(K):
+        for n in range(N):
+            i, j = k % R, n % C
+            path = 11.0 + 13.0
+            for _ in range(j + 1):          # row-wire cells from the driver up to and including column j
+                path += 2.0
+            for _ in range(i, R):           # column-wire cells from row i down to the sense end
+                path += 7.0
+            for s in range(2):
+                d = (abs(int(qv[k, n])) >> (2 * s)) & 3
+                on = 1.0 / (1.0 / _device_g(cfg, d) + path)
+                off = 1.0 / (1.0 / _device_g(cfg, 0) + path)
+                expect = math.copysign(1.0, qv[k, n]) * (on - off) / dg if qv[k, n] else 0.0
+                assert abs(U[s, k, n] - expect) < 1e-12
+
+
+@pytest.mark.parametrize("R,C", [(2, 2), (4, 4), (8, 8), (8, 3)])
+def test_aam_converges_to_exact_circuit_for_high_device_resistance(xo, R, C):
+    # Sec. IV-D: negligible error when the device resistance range is far above the wire
+    # resistance, considerable error when it is low.
+    rng = np.random.default_rng(R * 10 + C)
+    d = rng.integers(0, 4, size=(R, C))
+    errs = []
+    for r_min in (1e3, 1e4, 1e5, 1e6):
+        cfg = xo.make_config(xbar_rows=R, xbar_cols=C, weight_bits=2, slice_bits=2, flags=xo.WIRE_AAM,
+                             r_min=r_min, r_max=10 * r_min, r_row=1.0, r_col=4.6)
+        dg = (1 / r_min - 0.1 / r_min) / 3
+        U = xo.planes(cfg, (d / 3.0).astype(np.float32), 1.0)[0]
+        G = _device_g(cfg, d.astype(np.float64))
+        E_on = nodal.effective_conductance(G, 1.0, 4.6)
+        E_off = nodal.effective_conductance(np.full((R, C), _device_g(cfg, 0)), 1.0, 4.6)
+        exact = (E_on - E_off) / dg
+        errs.append(np.abs(U - exact).max())
+    assert all(errs[i + 1] < errs[i] * 0.2 for i in range(3))
+    assert errs[-1] < 1e-3 * R * C / 64 + 1e-5
+
+
+def test_nodal_solver_basics():
+    # two cells on one column: hand-solved ladder.  Row drivers 1 V each, r_row a, r_col b.
+    g1, g2, a, b = 1e-3, 2e-3, 5.0, 7.0
+    E = nodal.effective_conductance([[g1], [g2]], a, b)
+    # unknown column node voltages v1 (row 0), v2 (row 1): KCL by hand
+    r1, r2 = 1 / g1 + a, 1 / g2 + a
+    A = np.array([[1 / r1 + 1 / b, -1 / b], [-1 / b, 1 / r2 + 1 / b + 1 / b]])
+    for drive in ((1.0, 0.0), (0.0, 1.0)):
+        v = np.linalg.solve(A, np.array([drive[0] / r1, drive[1] / r2]))
+        assert abs(v[1] / b - (E[0, 0] * drive[0] + E[1, 0] * drive[1])) < 1e-15
+    rng = np.random.default_rng(0)
+    G = rng.uniform(1e-6, 1e-5, size=(3, 4))
+    # with wires of (almost) zero resistance the map is G itself
+    assert np.allclose(nodal.effective_conductance(G, 1e-9, 1e-9), G, rtol=1e-6)
+
+
+def test_profile_mode_round_trip(xo):
+    # D = (G_ideal - G_nonideal) / G_ideal taken from the analytical model reproduces its planes
+    R, C, K, N, S = 8, 8, 20, 13, 4
+    rng = np.random.default_rng(9)
+    W = rng.uniform(-1, 1, size=(K, N)).astype(np.float32)
+    aam = xo.make_config(xbar_rows=R, xbar_cols=C, flags=xo.WIRE_AAM, r_min=1e4, r_max=1e5)
+    prof = xo.make_config(xbar_rows=R, xbar_cols=C, flags=xo.WIRE_PROFILE, r_min=1e4, r_max=1e5)
+    D = np.zeros((S, 2, K, N), dtype=np.float32)
+    for k in range(K):
+        for n in range(N):
+            rho = (n % C + 1) * 1.0 + (R - k % R) * 4.6
+            qv = xo.quantize_weight(W[k, n], 1.0, 8)
+            for s in range(S):
+                d = (abs(qv) >> (2 * s)) & 3
+                for pol in range(2):
+                    g = _device_g(aam, d if (qv > 0) == (pol == 0) and qv != 0 else 0)
+                    D[s, pol, k, n] = (g - g / (1 + rho * g)) / g
+    Ua, Up = xo.planes(aam, W, 1.0), xo.planes(prof, W, 1.0, profile=D)
+    assert np.allclose(Ua, Up, rtol=0, atol=3e-6)                    # D is stored in single precision
+    zero = xo.planes(prof, W, 1.0, profile=np.zeros_like(D))
+    assert np.allclose(zero, xo.planes(xo.make_config(xbar_rows=R, xbar_cols=C), W, 1.0), atol=1e-12)
+
+
+def test_variation_statistics(xo):
+    K, N = 64, 64
+    W = np.full((K, N), 2.0 / 3.0, dtype=np.float32)                  # single slice, digit 2 everywhere
+    cfg = xo.make_config(xbar_rows=64, xbar_cols=64, weight_bits=2, slice_bits=2, flags=xo.VARIATION,
+                         var_sigma=0.1, seed=5)
+    dg = (1e-5 - 1e-6) / 3
+    U = xo.planes(cfg, W, 1.0, step=1)[0]
+    res = (U - 2.0).ravel()
+    sd = 0.1 * math.sqrt(_device_g(cfg, 2) ** 2 + _device_g(cfg, 0) ** 2) / dg
+    assert abs(res.mean()) < 4 * sd / math.sqrt(res.size)
+    assert abs(res.std() / sd - 1) < 0.05
+    assert stats.kstest(res / sd, "norm").pvalue > 1e-3
+    assert np.array_equal(U, xo.planes(cfg, W, 1.0, step=1)[0])       # same step: same draw
+    assert not np.any(U == xo.planes(cfg, W, 1.0, step=2)[0])         # resampled per step
+    # sub-block addressed by absolute indices sees the same devices
+    k_idx, n_idx = np.array([3, 17, 40]), np.array([0, 5, 63, 21])
+    Usub = xo.planes(cfg, W[np.ix_(k_idx, n_idx)], 1.0, step=1, k_idx=k_idx, n_idx=n_idx, K_full=K, N_full=N)[0]
+    assert np.array_equal(Usub, U[np.ix_(k_idx, n_idx)])
+
+
+def test_nonideal_bwd_is_fwd_through_transposed_tiles(xo):
+    # reciprocity: the backward pass drives the same devices from the other side
+    R, C, K, N, M = 8, 16, 21, 37, 5
+    rng = np.random.default_rng(4)
+    W = rng.normal(0, 0.3, size=(K, N)).astype(np.float32)
+    dY = rng.normal(0, 0.01, size=(M, N)).astype(np.float32)
+    kw = dict(weight_bits=8, slice_bits=2, input_bits=8, stream_bits=2, adc_bits=8, var_sigma=0.05,
+              adc_fs_fwd=70.0, adc_fs_bwd=90.0, seed=3)
+    cfg = xo.make_config(xbar_rows=R, xbar_cols=C, flags=xo.WIRE_AAM | xo.VARIATION, **kw)
+    U = xo.planes(cfg, W, 1.0, step=2)
+    dX, codes = xo.bwd_planes(cfg, U, dY, 1.0, 0.04, want_codes=True)
+    kw["adc_fs_fwd"] = 90.0
+    swapped = xo.make_config(xbar_rows=C, xbar_cols=R, flags=xo.INPUT_SIGNED, **kw)
+    Y2, codes2 = xo.fwd_planes(swapped, np.ascontiguousarray(U.transpose(0, 2, 1)), dY, 1.0, 0.04, want_codes=True)
+    assert np.array_equal(dX, Y2) and np.array_equal(codes, codes2)
+    # and it is close to the exact product when the ADC is fine enough
+    fine = xo.make_config(xbar_rows=R, xbar_cols=C, flags=0, **dict(kw, adc_bits=12, adc_fs_bwd=16 * 3 * 3.0))
+    dXf = xo.bwd(fine, W, dY, 1.0, 0.04)
+    ref = dY.astype(np.float64) @ W.astype(np.float64).T
+    assert np.linalg.norm(dXf - ref) < 0.05 * np.linalg.norm(ref)
+
+
+def test_tiny_fwd_brute_force(xo):
+    """Everything at once on a 2-tile problem, re-derived device by device with exact fractions of
+    the physical quantities (series path per device, two arrays, subtract, threshold search)."""
+    R, C, K, N, M = 4, 4, 6, 5, 3
+    cfg = xo.make_config(xbar_rows=R, xbar_cols=C, weight_bits=4, slice_bits=2, input_bits=4, stream_bits=2,
+                         adc_bits=5, flags=xo.WIRE_AAM | xo.INPUT_SIGNED, r_min=2e3, r_max=2e4, r_row=3.0,
+                         r_col=9.0, adc_fs_fwd=20.0, adc_fs_bwd=20.0)
+    rng = np.random.default_rng(12)
+    qv = rng.integers(-15, 16, size=(K, N))
+    av = rng.integers(-15, 16, size=(M, K))
+    W, X = (qv / 15.0).astype(np.float32), (av / 15.0).astype(np.float32)
+    Y, codes, acc = xo.fwd(cfg, W, X, 1.0, 1.0, want_codes=True, want_acc=True)
+    g_lo, g_hi = 1 / 2e4, 1 / 2e3
+    dg = (g_hi - g_lo) / 3
+    gain = float(np.float32(15.0) / np.float32(20.0))
+    total = np.zeros((M, N))
+    for m in range(M):
+        for n in range(N):
+            for p, sgn in ((0, 1), (1, -1)):
+                for b in range(2):
+                    for s in range(2):
+                        for t in range(2):
+                            cur = 0.0
+                            for k in range(t * R, min(K, t * R + R)):
+                                a = av[m, k] * sgn
+                                dig_in = ((a if a > 0 else 0) >> (2 * b)) & 3
+                                dig_w = (abs(int(qv[k, n])) >> (2 * s)) & 3
+                                rho = (n % C + 1) * 3.0 + (R - k % R) * 9.0
+                                r_act = 1.0 / (g_lo + dig_w * dg) + rho
+                                r_rest = 1.0 / g_lo + rho
+                                i_pos = dig_in / (r_act if qv[k, n] > 0 else r_rest)
+                                i_neg = dig_in / (r_act if qv[k, n] < 0 else r_rest)
+                                cur += (i_pos - i_neg) / dg
+                            x = cur * gain
+                            code = min(range(-15, 16), key=lambda c: (abs(x - c), c % 2))   # nearest, even on ties
+                            assert codes[p, b, s, t, m, n] == code
+                            total[m, n] += sgn * (1 << (2 * s + 2 * b)) * code
+    assert np.array_equal(acc, total.astype(np.int64))
+    assert np.allclose(Y, total * (20.0 / 15) / (15 * 15), rtol=1e-6, atol=0)
+
+
+def test_dac_table(xo):
+    # a linear table equals the ideal DAC; a scaled table scales the currents
+    rng = np.random.default_rng(6)
+    W = rng.uniform(-1, 1, size=(16, 8)).astype(np.float32)
+    X = rng.uniform(0, 1, size=(4, 16)).astype(np.float32)
+    kw = dict(xbar_rows=8, xbar_cols=8, input_bits=8, stream_bits=2, adc_bits=12, adc_fs_fwd=8 * 9.0)
+    base = xo.fwd(xo.make_config(**kw), W, X, 1.0, 1.0)
+    lin = xo.fwd(xo.make_config(flags=xo.DAC_LUT, dac_lut=[0, 1 / 3, 2 / 3, 1.0], **kw), W, X, 1.0, 1.0)
+    assert np.array_equal(base, lin)
+    half = xo.fwd(xo.make_config(flags=xo.DAC_LUT, dac_lut=[0, 1 / 6, 2 / 6, 0.5], **dict(kw, adc_fs_fwd=4 * 9.0)),
+                  W, X, 1.0, 1.0, want_codes=True)[1]
+    full = xo.fwd(xo.make_config(**kw), W, X, 1.0, 1.0, want_codes=True)[1]
+    assert np.abs(half - full).max() <= 1
+
+
+def test_adc_range_rule_rarely_saturates(xo):
+    # the stand-in ADC range of the workload recipe clips only a small fraction of conversions
+    g = workloads.Gemm("t", 256, 48, 8, False, 1)
+    W, X, _ = workloads.layer_tensors_np(g, 3)
+    kw = workloads.config_kwargs("resnet50")
+    kw["flags"] = kw["flags"] & ~(workloads.NI_UPD_NL | workloads.NI_UPD_NOISE)
+    cfg = xo.make_config(**kw)
+    codes = xo.fwd(cfg, W, X, float(np.abs(W).max()), float(X.max()), want_codes=True)[1]
+    assert (np.abs(codes) == 127).mean() < 0.01
+
+
+# ------------------------------------------------------------------------------------------------
+# update model
+# ------------------------------------------------------------------------------------------------
+def _upd_tensors(seed, M=7, K=9, N=5):
+    rng = np.random.default_rng(seed)
+    W = rng.uniform(-0.4, 0.4, size=(K, N)).astype(np.float32)
+    X = rng.uniform(0, 1, size=(M, K)).astype(np.float32)
+    dY = rng.normal(0, 0.01, size=(M, N)).astype(np.float32)
+    return W, X, dY
+
+
+def test_update_ideal_is_plain_sgd(xo):
+    W, X, dY = _upd_tensors(0)
+    cfg = xo.make_config(flags=0)
+    W2, grad = xo.update(cfg, W, X, dY, w_max=0.5, grad_scale=2.0, lr=0.1, want_grad=True)
+    ref_grad = X.astype(np.float64).T @ dY.astype(np.float64)
+    assert np.allclose(grad, ref_grad, rtol=1e-13, atol=1e-18)
+    ref = W.astype(np.float64) - 0.5 * 0.1 * 2.0 * ref_grad        # dW = -lr * w_max * grad_scale * grad
+    assert np.allclose(W2, ref, rtol=0, atol=1e-7)
+    # the switched-off factors must not matter
+    cfg0 = xo.make_config(flags=xo.UPD_NL | xo.UPD_NOISE, upd_nl_v=0.0, upd_noise_gamma=0.0)
+    assert np.array_equal(W2, xo.update(cfg0, W, X, dY, 0.5, 2.0, 0.1))
+
+
+def test_update_clamps_to_device_range(xo):
+    W, X, dY = _upd_tensors(1)
+    W2 = xo.update(xo.make_config(flags=0), W, X, dY * 1e4, w_max=0.5, grad_scale=50.0, lr=1.0)
+    assert np.abs(W2).max() <= 0.5 and (np.abs(W2) == 0.5).any()
+
+
+def test_update_nonlinearity_closed_forms(xo):
+    v = 0.7
+    cfg = xo.make_config(flags=xo.UPD_NL, upd_nl_v=v)
+    X = np.ones((1, 1), dtype=np.float32)
+    lr, gs, w_max = 0.25, 1.0, 1.0
+    for g0, x in ((-1.0, 0.0), (1.0, 1.0), (0.0, 0.5), (0.5, 0.75)):
+        for grad in (0.2, -0.2):
+            W = np.array([[g0]], dtype=np.float32)
+            dY = np.array([[grad]], dtype=np.float32)
+            W2 = xo.update(cfg, W, X, dY, w_max, gs, lr)
+            delta = float(np.float32(grad))
+            up = -lr * delta > 0
+            factor = math.exp(-v * x) if up else math.exp(-v * (1 - x))
+            expect = min(1.0, max(-1.0, g0 - lr * delta * factor))
+            assert abs(float(W2[0, 0]) - expect) < 1e-7
+    # mirror symmetry: state g with gradient d moves like state -g with gradient -d, mirrored
+    for g0 in (-0.6, 0.1, 0.8):
+        a = xo.update(cfg, np.array([[g0]], np.float32), X, np.array([[0.3]], np.float32), 1.0, 1.0, 0.2)
+        b = xo.update(cfg, np.array([[-g0]], np.float32), X, np.array([[-0.3]], np.float32), 1.0, 1.0, 0.2)
+        assert abs(float(a[0, 0]) + float(b[0, 0])) < 1e-7
+    # small v barely matters, large v does (the paper's sensitivity trend)
+    W, Xr, dY = _upd_tensors(2)
+    sgd = xo.update(xo.make_config(flags=0), W, Xr, dY, 0.5, 1.0, 0.5)
+    small = xo.update(xo.make_config(flags=xo.UPD_NL, upd_nl_v=0.01), W, Xr, dY, 0.5, 1.0, 0.5)
+    large = xo.update(xo.make_config(flags=xo.UPD_NL, upd_nl_v=1.0), W, Xr, dY, 0.5, 1.0, 0.5)
+    step = np.abs(sgd - W).max()
+    assert np.abs(small - sgd).max() < 0.011 * step < np.abs(large - sgd).max()
+
+
+def test_update_noise_statistics(xo):
+    K, N, M = 100, 80, 1
+    gamma, lr, gs = 5.0, 0.01, 1.0
+    cfg = xo.make_config(flags=xo.UPD_NOISE, upd_noise_gamma=gamma, seed=9)
+    W = np.zeros((K, N), dtype=np.float32)
+    X = np.ones((M, K), dtype=np.float32)
+    for grad in (1e-4, 4e-4):
+        dY = np.full((M, N), grad, dtype=np.float32)
+        W2 = xo.update(cfg, W, X, dY, 1.0, gs, lr, step=4)
+        delta = float(np.float32(grad))
+        dev = (W2.astype(np.float64) - (0.0 - lr * delta)).ravel()
+        sd = lr * gamma * math.sqrt(delta)                           # sigma grows like sqrt(|delta|)
+        assert abs(dev.mean()) < 4 * sd / 100
+        assert abs(dev.std() / sd - 1) < 0.03
+        assert stats.kstest(dev / sd, "norm").pvalue > 1e-3
+    # weight (k, n) of a layer with N columns consumes normal number k * N + n of the write stream
+    z = xo.normals(9, xo.STREAM_WRITE, 4, 0, K * N).reshape(K, N)
+    assert np.allclose(dev.reshape(K, N) / sd, z, rtol=0, atol=2e-4)
+    assert np.array_equal(W2, xo.update(cfg, W, X, dY, 1.0, gs, lr, step=4))
+    assert not np.any(W2 == xo.update(cfg, W, X, dY, 1.0, gs, lr, step=5))
+    # a sub-block addressed by absolute indices draws the same numbers
+    k_idx, n_idx = np.array([5, 50, 99]), np.array([0, 7, 78, 33])
+    sub = xo.update(cfg, W[np.ix_(k_idx, n_idx)], X[:, k_idx], dY[:, n_idx], 1.0, gs, lr, step=4,
+                    k_idx=k_idx, n_idx=n_idx, N_full=N)
+    assert np.array_equal(sub, W2[np.ix_(k_idx, n_idx)])
