@@ -493,7 +493,7 @@ def test_update_noise_statistics(xo):
         assert stats.kstest(dev / sd, "norm").pvalue > 1e-3
     # weight (k, n) of a layer with N columns consumes normal number k * N + n of the write stream
     z = xo.normals(9, xo.STREAM_WRITE, 4, 0, K * N).reshape(K, N)
-    assert np.allclose(dev.reshape(K, N) / sd, z, rtol=0, atol=2e-4)
+    assert np.allclose(-dev.reshape(K, N) / sd, z, rtol=0, atol=2e-4)   # W = g - lr * (delta + sigma z)
     assert np.array_equal(W2, xo.update(cfg, W, X, dY, 1.0, gs, lr, step=4))
     assert not np.any(W2 == xo.update(cfg, W, X, dY, 1.0, gs, lr, step=5))
     # a sub-block addressed by absolute indices draws the same numbers
