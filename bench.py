@@ -1,0 +1,210 @@
+"""Benchmark of the crossbar-emulation hot path on one MI355X.
+
+A step is one pass of the whole path over every layer GEMM of the workload: conductance-plane
+generation, forward VMM, backward VMM and weight update, through the C ABI, with all inputs already
+resident in HBM.  Prints one JSON line: emulated crossbar GMAC/s (fwd + bwd + update), the roofline of
+the dominant kernel (the fused MFMA contraction + ADC + shift-and-add), measured live with HIP events
+around every launch of that kernel in the timed region, and the CPU oracle timed on the host cores on
+a bounded sample of the same workload.
+"""
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
+
+
+class HipEvents:
+    """hipEvent_t pairs created straight from the HIP runtime (the library records them on the stream
+    it launches on)."""
+
+    def __init__(self):
+        self.hip = C.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [C.POINTER(C.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [C.POINTER(C.c_float), C.c_void_p, C.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [C.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [C.c_void_p]
+        self.pool = []
+
+    def pair(self):
+        a, b = C.c_void_p(), C.c_void_p()
+        assert self.hip.hipEventCreate(C.byref(a)) == 0 and self.hip.hipEventCreate(C.byref(b)) == 0
+        self.pool.append((a, b))
+        return a.value, b.value
+
+    def elapsed_ms(self, a, b):
+        ms = C.c_float()
+        assert self.hip.hipEventSynchronize(C.c_void_p(b)) == 0
+        assert self.hip.hipEventElapsedTime(C.byref(ms), C.c_void_p(a), C.c_void_p(b)) == 0
+        return ms.value
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="resnet50", choices=["fc256", "mlp", "resnet20", "resnet50", "vgg16"])
+    ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
+    ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
+    ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box has one); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import workloads
+    from paper_2002_11151_amd import xbar as xb
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    device = torch.device("cuda:0")
+    xb.lib()
+
+    default_batch = {"fc256": 64, "mlp": 128, "resnet20": 128, "resnet50": 64, "vgg16": 128}[args.workload]
+    batch = args.batch or default_batch
+    gemms = workloads.GEMMS[args.workload](batch) if args.workload in ("fc256", "mlp") else \
+        workloads.GEMMS[args.workload](batch, merge=True)
+    kw = workloads.config_kwargs(args.workload)
+    if args.ideal:
+        kw["flags"] &= ~(workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE)
+    S_w, S_in = kw["weight_bits"] // kw["slice_bits"], kw["input_bits"] // kw["stream_bits"]
+    terms = 2 if kw["flags"] & (workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE) else 1
+
+    # ---- resident tensors, one set per distinct shape ------------------------------------------
+    layers = []
+    max_planes = max_ws = max_out = 0
+    for i, g in enumerate(gemms):
+        flags = kw["flags"] | (workloads.INPUT_SIGNED if g.signed_input else 0)
+        cfg = xb.make_config(**dict(kw, flags=flags))
+        W, X, dY = workloads.layer_tensors_torch(g, seed=i, device=device)
+        w_max = 2.0 * float(W.abs().max())          # head-room: the weights move during the run
+        layers.append(dict(g=g, cfg=cfg, W=W, X=X, dY=dY, w_max=w_max, x_scale=float(X.abs().max()),
+                           g_scale=float(dY.abs().max()), macs=workloads.macs(g, S_w, S_in)))
+        max_planes = max(max_planes, xb.planes_bytes(cfg, g.K, g.N))
+        max_ws = max(max_ws, *(xb.workspace_bytes(cfg, op, g.M, g.K, g.N) for op in (0, 1, 2)))
+        max_out = max(max_out, g.M * g.N, g.M * g.K)
+    planes = torch.empty(max_planes, dtype=torch.uint8, device=device)
+    ws = torch.empty(max_ws, dtype=torch.uint8, device=device)
+    out = torch.empty(max_out, dtype=torch.float32, device=device)
+
+    events = HipEvents()
+    vmm_records = []          # (layer index, 'fwd'|'bwd', event pair)
+
+    def step(step_no, timed):
+        for li, L in enumerate(layers):
+            g, cfg = L["g"], L["cfg"]
+            for rep in range(g.count):
+                s = step_no * 64 + rep
+                xb.tile(cfg, L["W"], L["w_max"], s, planes=planes)
+                if timed:
+                    ev = events.pair()
+                    xb.trace_next_vmm(*ev)
+                    vmm_records.append((li, "fwd", ev))
+                xb.fwd(cfg, planes, L["X"], g.N, L["w_max"], L["x_scale"], ws=ws, out=out[:g.M * g.N].view(g.M, g.N))
+                if timed:
+                    ev = events.pair()
+                    xb.trace_next_vmm(*ev)
+                    vmm_records.append((li, "bwd", ev))
+                xb.bwd(cfg, planes, L["dY"], g.K, L["w_max"], L["g_scale"], ws=ws, out=out[:g.M * g.K].view(g.M, g.K))
+                xb.update(cfg, L["W"], L["X"], L["dY"], L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws)
+
+    for w in range(args.warmup):
+        step(w, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(args.warmup + k, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    tot = {k: sum(L["macs"][k] * L["g"].count for L in layers) for k in ("fwd", "bwd", "upd", "logical")}
+    emulated = tot["fwd"] + tot["bwd"] + tot["upd"]
+    ms_per_step = elapsed / args.steps * 1e3
+    value = emulated / (elapsed / args.steps) / 1e9
+
+    # ---- roofline of the contraction kernel ------------------------------------------------------
+    vmm_ms = 0.0
+    vmm_flops = 0.0
+    per_layer = {}
+    for li, kind, (a, b) in vmm_records:
+        ms = events.elapsed_ms(a, b)
+        vmm_ms += ms
+        fl = 2.0 * layers[li]["macs"][kind]
+        vmm_flops += fl
+        d = per_layer.setdefault((li, kind), [0.0, 0.0, 0])
+        d[0] += ms
+        d[1] += fl
+        d[2] += 1
+    achieved = vmm_flops / (vmm_ms * 1e-3) / 1e12 if vmm_ms > 0 else 0.0
+    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / FP16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                "kernel": "vmm_kernel (MFMA contraction + ADC + shift-and-add, fwd and bwd launches)",
+                "operand_terms": terms, "issued_frac": round(terms * achieved / FP16_MFMA_PEAK_TFLOPS, 4),
+                "launches": len(vmm_records), "avg_launch_ms": round(vmm_ms / max(1, len(vmm_records)), 4),
+                "kernel_time_share": round(vmm_ms / (elapsed * 1e3), 4)}
+    if args.per_layer:
+        for (li, kind), (ms, fl, n) in sorted(per_layer.items()):
+            g = layers[li]["g"]
+            print("%-10s %s K=%5d N=%5d M=%7d x%d  %8.3f ms/launch  %7.1f TFLOP/s useful" %
+                  (g.name, kind, g.K, g.N, g.M, g.count, ms / n, fl / (ms * 1e-3) / 1e12), file=sys.stderr)
+
+    # ---- CPU oracle on a bounded sample ------------------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import xbar_oracle as xo
+        threads = min(16, os.cpu_count() or 1)
+        rows = args.cpu_rows or threads
+        done = 0
+        t_cpu = 0.0
+        for L in layers:
+            g = L["g"]
+            m = min(rows, g.M)
+            flags = kw["flags"] | (workloads.INPUT_SIGNED if g.signed_input else 0)
+            co = xo.make_config(**dict(kw, flags=flags))
+            W = L["W"].cpu().numpy()
+            X = L["X"][:m].cpu().numpy()
+            dY = L["dY"][:m].cpu().numpy()
+            t1 = time.perf_counter()
+            U = xo.planes(co, W, L["w_max"], 0)
+            xo.rows_parallel(lambda u, x: xo.fwd_planes(co, u, x, L["w_max"], L["x_scale"]), U, X, threads)
+            xo.rows_parallel(lambda u, x: xo.bwd_planes(co, u, x, L["w_max"], L["g_scale"]), U, dY, threads)
+            xo.update(co, W, X, dY, L["w_max"], 1.0 / L["w_max"], 0.01, 0)
+            t_cpu += time.perf_counter() - t1
+            mm = workloads.macs(g._replace(M=m), S_w, S_in)
+            done += mm["fwd"] + mm["bwd"] + mm["upd"]
+        cpu = {"value": round(done / t_cpu / 1e9, 4), "unit": "emulated GMAC/s", "cores": threads, "kind": "oracle",
+               "sample": "%d batch rows of each of the %d distinct layer shapes, fwd+bwd+update, %.1f s" %
+                         (rows, len(layers), t_cpu)}
+
+    line = {
+        "metric": "emulated crossbar GMAC/s (fwd+bwd+update)", "value": round(value, 1), "unit": "GMAC/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 operands, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "%s layer GEMMs (%d GEMMs, %d distinct shapes), batch %d, %dx%d crossbars, "
+                               "%d-bit weights in %d slices, %d-bit inputs in %d cycles, %d-bit ADC, %s" %
+                               (args.workload, sum(g.count for g in gemms), len(gemms), batch, kw["xbar_rows"],
+                                kw["xbar_cols"], kw["weight_bits"], S_w, kw["input_bits"], S_in, kw["adc_bits"],
+                                "ideal arrays" if terms == 1 else "wire parasitics (AAM) + write non-linearity + noise"),
+                   "emulated_macs_per_step": emulated, "logical_macs_per_step": tot["logical"]},
+        "logical_gmacs": round(tot["logical"] / (elapsed / args.steps) / 1e9, 1),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

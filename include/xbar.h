@@ -1,0 +1,156 @@
+/*
+ * xbar -- functional emulation of non-ideal resistive-crossbar training operations on one MI355X.
+ *
+ * C ABI of the GPU library.  Plain pointers and sizes only; every tensor pointer is a DEVICE pointer
+ * to row-major contiguous memory that the caller owns (allocate it with any HIP allocator, e.g. a
+ * torch tensor) and that must be 16-byte aligned.  The library never allocates or frees device
+ * memory and never synchronises: every call only enqueues kernels on the HIP stream that is passed
+ * in (NULL = the default stream) and returns.  Scratch memory comes from the caller (`ws`); its
+ * contents are undefined after a call and two calls that share one workspace must be ordered on one
+ * stream.  Return value: XBAR_OK or a negative XBAR_E* code; no exception crosses this boundary and
+ * the library keeps no state between calls.
+ *
+ * A layer is the GEMM  Y[M x N] = X[M x K] . W[K x N]:  K = fan-in = crossbar rows, N = fan-out =
+ * crossbar columns, M = batch (times output positions after im2col).  The weight matrix is cut into
+ * crossbar instances of xbar_rows x xbar_cols devices; every weight is stored as
+ * S_w = weight_bits / slice_bits devices of slice_bits each (least significant slice first) in a
+ * positive or a negative array; inputs are streamed in S_in = input_bits / stream_bits cycles of
+ * stream_bits each; signed inputs are applied in two phases (positive part, negative part).
+ * Model after TxSim (arXiv 2002.11151): Sec. IV (layer = DAC -> array -> ADC, forward and
+ * backward), Sec. IV-A (non-ideal conductance matrix generator), Sec. IV-B (three-stage model),
+ * Sec. IV-C (update model), Sec. IV-D (approximate analytical wire model, stored distortion
+ * profile), Sec. V (parameter values).
+ */
+#ifndef XBAR_H_
+#define XBAR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define XBAR_ABI_VERSION 1u
+
+/* flags */
+#define XBAR_NI_VARIATION    1u   /* per-device multiplicative Gaussian process variation (Sec. IV-A)   */
+#define XBAR_NI_WIRE_AAM     2u   /* wire parasitics, approximate analytical model (Sec. IV-D)          */
+#define XBAR_NI_WIRE_PROFILE 4u   /* wire parasitics from a stored distortion profile (Sec. IV-D)       */
+#define XBAR_NI_UPD_NL       8u   /* state-dependent write non-linearity (Sec. IV-C)                    */
+#define XBAR_NI_UPD_NOISE    16u  /* Gaussian write noise (Sec. IV-C)                                   */
+#define XBAR_DAC_LUT         32u  /* DAC levels from dac_lut instead of equidistant (Sec. IV-B)         */
+#define XBAR_INPUT_SIGNED    64u  /* forward inputs are signed (two phases); backward always is         */
+
+/* status codes */
+#define XBAR_OK          0
+#define XBAR_EINVAL     -1   /* bad parameter struct (sizes, bit widths, NaN/negative physical values) */
+#define XBAR_ESHAPE     -2   /* M, K or N not positive, or too large for 32-bit indexing              */
+#define XBAR_EALIGN     -3   /* a pointer is NULL or not 16-byte aligned                              */
+#define XBAR_EWORKSPACE -4   /* workspace / plane buffer smaller than the size query says             */
+#define XBAR_EHIP       -5   /* a HIP call failed (kernel launch)                                     */
+#define XBAR_ENOTSUP    -6   /* valid in the model, not implemented by the GPU kernels                */
+
+/* operations, for xbar_workspace_bytes */
+#define XBAR_OP_FWD    0
+#define XBAR_OP_BWD    1
+#define XBAR_OP_UPDATE 2
+
+/* Parameter struct: plain data, caller-owned, read during the call only (Sec. IV lists the three
+ * input groups; Sec. V and VI-B give the values used in the paper, quoted below as "paper:"). */
+typedef struct xbar_config {
+  uint32_t struct_size;   /* sizeof(xbar_config) */
+  uint32_t abi_version;   /* XBAR_ABI_VERSION */
+  int32_t xbar_rows;      /* R: 64, 128 or 256 (multiple of 16 in 16..256)       paper: 64            */
+  int32_t xbar_cols;      /* C: same range                                       paper: 64            */
+  int32_t weight_bits;    /* magnitude bits of a weight, 1..16; the sign selects the array            */
+  int32_t slice_bits;     /* bits per device, divides weight_bits, 1..4          paper: 2             */
+  int32_t input_bits;     /* magnitude bits of an input, 1..8                                         */
+  int32_t stream_bits;    /* bits per DAC cycle, divides input_bits              paper: 1             */
+  int32_t adc_bits;       /* 2..16, signed mid-tread converter with Q = 2^(adc_bits-1) - 1 codes/side */
+  uint32_t flags;         /* XBAR_NI_* | XBAR_DAC_LUT | XBAR_INPUT_SIGNED                             */
+  float r_min, r_max;     /* device resistance range in Ohm                      paper: 1e5, 1e6      */
+  float v_max;            /* input voltage range in V (results do not depend on it) paper: 1          */
+  float r_row, r_col;     /* wire resistance per cell in Ohm                     paper: 1, 4.6        */
+  float r_source, r_sense;/* driver / sense resistance in Ohm (paper names them, gives no value)      */
+  float var_sigma;        /* relative standard deviation of the device variation                      */
+  float upd_nl_v;         /* write non-linearity factor v                        paper: 0.01          */
+  float upd_noise_gamma;  /* write noise factor gamma                            paper: 5             */
+  float adc_fs_fwd;       /* ADC full scale of the forward pass, in units of (one input level) x      */
+  float adc_fs_bwd;       /*   (one device level); same for the backward pass.  Code = clamp(         */
+                          /*   rne(I * gain), -Q, Q) with gain = float(Q) / adc_fs in single          */
+                          /*   precision; LSB = adc_fs / Q.                                           */
+  float dac_lut[16];      /* voltage of DAC level i divided by v_max, used with XBAR_DAC_LUT          */
+  uint64_t seed;          /* key of the counter-based random numbers (Philox-4x32-10 + Box-Muller)    */
+} xbar_config;
+
+/* Host-only checks of the parameter struct (no GPU needed). */
+int xbar_config_validate(const xbar_config* cfg);
+const char* xbar_strerror(int code);
+uint32_t xbar_abi_version(void);
+
+/*
+ * Non-ideal conductance matrix generator (Sec. IV-A, Sec. IV-D): weights -> bit-sliced conductance
+ * planes per crossbar tile, stitched as U = (G+ - G-) / (one device level), in the operand layout of
+ * the contraction kernels (one copy for the forward, one for the backward direction).
+ *   W        [K][N] float, read only (the preserved ideal copy of Sec. IV-A)
+ *   w_max    weights are clamped to [-w_max, w_max] and quantised to weight_bits magnitude bits,
+ *            q = rne(clamp(W / w_max) * (2^weight_bits - 1)), evaluated in double precision
+ *   step     keys the variation draw: the same (seed, step) gives the same devices
+ *   profile  [S_w][2][K][N] float distortion D (index 1: 0 = positive array), G <- G (1 - D);
+ *            required with XBAR_NI_WIRE_PROFILE, ignored otherwise
+ *   planes   output, xbar_planes_bytes(cfg, K, N) bytes, opaque
+ * Device (slice s, array pol) of weight (k, n) uses normal number ((k N + n) S_w + s) 2 + pol of
+ * the variation stream.  Rows / columns beyond K / N hold no device.
+ */
+size_t xbar_planes_bytes(const xbar_config* cfg, int K, int N);
+int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max, uint64_t step,
+              const float* profile, void* planes, size_t planes_bytes, void* hip_stream);
+
+/* Bytes of scratch memory that xbar_fwd / xbar_bwd / xbar_update need for this shape. */
+size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N);
+
+/*
+ * Forward VMM (Sec. IV, IV-B): Y[M][N] from X[M][K] through the planes of xbar_tile.
+ *   a = rne(clamp(X / x_scale, lo, 1) * (2^input_bits - 1)) in double precision, lo = -1 with
+ *   XBAR_INPUT_SIGNED else 0; every (row tile, slice, cycle, phase) column current is converted by
+ *   its own ADC, the codes are shifted and added over slices, cycles, phases and row tiles in
+ *   integers, and Y = float(double(sum) * lsb * x_scale * w_max / ((2^input_bits-1)(2^weight_bits-1))).
+ *   codes: NULL, or int16 [phase][cycle][slice][row tile][M][N] receiving every ADC code (testing).
+ */
+int xbar_fwd(const xbar_config* cfg, const void* planes, const float* X, float* Y, int M, int K, int N,
+             float w_max, float x_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream);
+
+/*
+ * Backward VMM (Sec. IV: same procedure as forward): dX[M][K] from dY[M][N]; the same devices are
+ * driven from the columns and read on the rows, one ADC conversion per (column tile, slice, cycle,
+ * phase), accumulated over column tiles.  dY / g_scale is quantised like a signed forward input.
+ *   codes: NULL, or int16 [phase][cycle][slice][column tile][M][K].
+ */
+int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float* dX, int M, int K, int N,
+             float w_max, float g_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream);
+
+/*
+ * Weight update (Sec. IV-C): W[K][N] in place from X[M][K] and dY[M][N].
+ *   grad = sum_m X[m][k] dY[m][n];  delta = grad_scale * grad (ideal change, in units of Gmax-Gmin,
+ *   state g = W / w_max in [-1, 1]);  write non-linearity: delta * exp(-v x) when the conductance
+ *   rises, delta * exp(-v (1 - x)) when it falls, x = (g + 1) / 2;  write noise:
+ *   + gamma sqrt(|delta|) * normal number (k N + n) of the write stream of `step`;
+ *   g <- clamp(g - lr * written, -1, 1);  W <- w_max g.
+ */
+int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N,
+                float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes,
+                void* hip_stream);
+
+/*
+ * Instrumentation for the benchmark (no part of the method): one-shot, per host thread.  The next
+ * xbar_fwd or xbar_bwd call of this thread records the HIP event `before` on its stream right before
+ * the contraction kernel (the dominant kernel; the input quantiser runs before it, the output
+ * scaling after it) and `after` right behind it.  Both are hipEvent_t handles owned by the caller.
+ */
+void xbar_trace_next_vmm(void* before, void* after);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XBAR_H_ */

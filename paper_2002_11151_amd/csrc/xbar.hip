@@ -1,0 +1,873 @@
+// xbar: emulation of non-ideal resistive-crossbar training operations on MI355X (gfx950).
+// HIP kernels and the C-ABI entry points declared in include/xbar.h.
+//
+// Method: TxSim (arXiv 2002.11151) Sec. IV (DAC -> array -> ADC per layer, forward and backward),
+// Sec. IV-A (non-ideal conductance matrix generator), Sec. IV-C (update model), Sec. IV-D
+// (approximate analytical wire model / stored distortion profile).
+//
+// Kernel plan
+//   tile_planes     weights -> quantise -> bit slices -> device conductances -> variation -> wire model
+//                   -> stitched signed planes U, written as fp16 MFMA B-operand fragments
+//                   (one term when U is an exact digit, hi + lo terms when U is a real number)
+//   quantize_input  activations / errors -> integer magnitudes, written as MFMA A-operand fragments
+//                   that keep the raw 8-bit magnitude in each 16-bit lane
+//   vmm             per (tile, slice, cycle, phase): MFMA contraction (fp16 operands, fp32
+//                   accumulate) + ADC + shift-and-add fused in registers
+//   vmm_finish      sum of the integer partial results over tile chunks -> scaled fp32 output
+//   grad_gemm       X^T dY with fp32 MFMA, split over the batch
+//   update_write    batch-partial sum -> non-linear, noisy conductance write, in place
+//
+// Operand trick of vmm: a 16-bit lane that holds the integer field `digit << shift` (shift < 10) is,
+// read as fp16, the subnormal number digit * 2^(shift-24).  The matrix cores of gfx950 take fp16
+// subnormals exactly, so one AND with a digit mask turns the raw magnitudes into the A operand of
+// any streaming cycle; the power of two is folded into the ADC gain.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "xbar.h"
+
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr uint32_t kMagicBits = 0x4B400000u;  // bits of 1.5 * 2^23: adding it rounds to an integer (RNE)
+constexpr float kMagic = 12582912.0f;
+constexpr int kStreamVariation = 1, kStreamWrite = 2;
+
+// ---------------------------------------------------------------------------------------------
+// host-side geometry shared by the entry points
+// ---------------------------------------------------------------------------------------------
+struct Derived {
+  int S_w, S_in, terms, q_adc;
+  uint32_t array_ni;
+};
+
+inline Derived derive(const xbar_config* c) {
+  Derived d;
+  d.S_w = c->weight_bits / c->slice_bits;
+  d.S_in = c->input_bits / c->stream_bits;
+  d.array_ni = c->flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE);
+  d.terms = d.array_ni ? 2 : 1;
+  d.q_adc = (1 << (c->adc_bits - 1)) - 1;
+  return d;
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Plane buffer: forward copy then backward copy.  One copy is
+// [tile][output patch of 32][slice][term][k-step of 16][64 lanes][8 halves].
+struct PlaneGeom {
+  int tile, ks, T, OP;          // contraction tile length, k-steps per tile, tiles, output patches
+  size_t bytes;
+};
+
+inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N, bool transposed) {
+  PlaneGeom g;
+  g.tile = transposed ? c->xbar_cols : c->xbar_rows;
+  g.ks = g.tile / 16;
+  g.T = cdiv(transposed ? N : K, g.tile);
+  g.OP = cdiv(transposed ? K : N, 32);
+  g.bytes = (size_t)g.T * g.OP * d.S_w * d.terms * g.ks * 1024;
+  return g;
+}
+
+// ---------------------------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+    c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Standard normal number i of (seed, stream, step): four consecutive i share one Philox block,
+// words (0,1) -> numbers 0,1 (cosine, sine branch of Box-Muller), words (2,3) -> numbers 2,3.
+struct NormalStream {
+  uint32_t k0, k1, s0, s1;
+  uint64_t cached_blk;
+  uint32_t w[4];
+  __device__ NormalStream(uint64_t seed, uint32_t stream, uint64_t step) {
+    k0 = (uint32_t)seed ^ (0x9E3779B9u * stream);
+    k1 = (uint32_t)(seed >> 32) ^ (0xBB67AE85u * stream);
+    s0 = (uint32_t)step;
+    s1 = (uint32_t)(step >> 32);
+    cached_blk = ~0ull;
+  }
+  __device__ double get(uint64_t i) {
+    const uint64_t blk = i >> 2;
+    if (blk != cached_blk) {
+      philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), s0, s1, k0, k1, w);
+      cached_blk = blk;
+    }
+    const bool second = (i & 2u) != 0;
+    const double u1 = ((double)(second ? w[2] : w[0]) + 0.5) * (1.0 / 4294967296.0);
+    const double u2 = ((double)(second ? w[3] : w[1]) + 0.5) * (1.0 / 4294967296.0);
+    const double r = ::sqrt(-2.0 * ::log(u1));
+    const double th = 6.283185307179586476925286766559 * u2;
+    return (i & 1u) ? r * ::sin(th) : r * ::cos(th);
+  }
+};
+
+__device__ __forceinline__ double clampd(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+// ---------------------------------------------------------------------------------------------
+// generator: weights -> operand planes (Sec. IV-A, IV-D)
+// ---------------------------------------------------------------------------------------------
+struct TileArgs {
+  const float* W;
+  const float* profile;
+  uint16_t* planes;  // start of this copy
+  int K, N, R, C, S_w, slice_bits, weight_bits, terms;
+  int tile, ks, T, OP;
+  uint32_t flags;
+  double g_min, dg, var_sigma, r_row, r_col, r_source, r_sense, hi_scale, hi_inv_scale;
+  float w_max;
+  uint64_t seed, step;
+  long long n_threads;
+};
+
+// Signed plane value of slice s of weight (k, n), in units of one device level.
+__device__ __forceinline__ double plane_value(const TileArgs& a, NormalStream& rng, int sign, int digit, int s, int k,
+                                              int n) {
+  if (!(a.flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE))) return (double)(sign * digit);
+  double g[2];
+  g[0] = a.g_min + (sign > 0 ? digit * a.dg : 0.0);
+  g[1] = a.g_min + (sign < 0 ? digit * a.dg : 0.0);
+#pragma unroll
+  for (int pol = 0; pol < 2; ++pol) {
+    if (a.flags & XBAR_NI_VARIATION) {
+      const uint64_t dev = (((uint64_t)k * (uint64_t)a.N + (uint64_t)n) * (uint64_t)a.S_w + (uint64_t)s) * 2 + pol;
+      g[pol] *= 1.0 + a.var_sigma * rng.get(dev);
+    }
+    if (a.flags & XBAR_NI_WIRE_AAM) {
+      const int i = k % a.R, j = n % a.C;
+      const double rho = a.r_source + (double)(j + 1) * a.r_row + (double)(a.R - i) * a.r_col + a.r_sense;
+      g[pol] = g[pol] / (1.0 + rho * g[pol]);
+    } else if (a.flags & XBAR_NI_WIRE_PROFILE) {
+      const double dist = (double)a.profile[(((size_t)s * 2 + pol) * a.K + k) * a.N + n];
+      g[pol] = g[pol] * (1.0 - dist);
+    }
+  }
+  return (g[0] - g[1]) / a.dg;
+}
+
+// One thread produces the 8 consecutive contraction-index entries of one output column that make up
+// one 16-byte operand chunk, for every slice and term.
+//   TRANSPOSED = false: contraction index k (rows), output index n;  = true: contraction n, output k.
+template <bool TRANSPOSED>
+__global__ __launch_bounds__(256) void tile_planes_kernel(TileArgs a) {
+  const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (tid >= a.n_threads) return;
+  // thread -> (chunk of 8 along the contraction, output index); output index fastest within 32
+  const int out_len_pad = a.OP * 32;
+  const int o = (int)(tid % out_len_pad);
+  const int cg = (int)(tid / out_len_pad);        // global 8-chunk along the contraction
+  const int c0 = cg * 8;
+  const int t = c0 / a.tile;
+  const int within = c0 - t * a.tile;
+  const int j = within / 16, half = (within % 16) / 8;
+  const int lane = (o % 32) + 32 * half;
+  const int op = o / 32;
+  const int Lc = TRANSPOSED ? a.N : a.K;          // contraction length
+  const int Lo = TRANSPOSED ? a.K : a.N;
+
+  NormalStream rng(a.seed, kStreamVariation, a.step);
+  const double qw = (double)((1u << a.weight_bits) - 1);
+  const uint32_t dmask = (1u << a.slice_bits) - 1;
+
+  int sign[8];
+  uint32_t mag[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int c = c0 + e;
+    sign[e] = 0;
+    mag[e] = 0;
+    if (c < Lc && o < Lo) {
+      const int k = TRANSPOSED ? o : c, n = TRANSPOSED ? c : o;
+      const double q = ::rint(clampd((double)a.W[(size_t)k * a.N + n] / (double)a.w_max, -1.0, 1.0) * qw);
+      sign[e] = (q > 0.0) - (q < 0.0);
+      mag[e] = (uint32_t)::fabs(q);
+    }
+  }
+  const size_t blk0 = ((size_t)t * a.OP + op) * a.S_w;
+  for (int s = 0; s < a.S_w; ++s) {
+    union { u32x4 v; _Float16 h[8]; } hi, lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int c = c0 + e;
+      double u = 0.0;
+      if (c < Lc && o < Lo) {
+        const int k = TRANSPOSED ? o : c, n = TRANSPOSED ? c : o;
+        u = plane_value(a, rng, sign[e], (int)((mag[e] >> (a.slice_bits * s)) & dmask), s, k, n);
+      }
+      // leading term on the grid 2^-hi_frac (coarser where fp16 cannot hold it), residual in fp16
+      const _Float16 h = a.terms == 2 ? (_Float16)(::rint(u * a.hi_scale) * a.hi_inv_scale) : (_Float16)u;
+      hi.h[e] = h;
+      lo.h[e] = (_Float16)(u - (double)h);
+    }
+    const size_t chunk = ((blk0 + s) * a.terms * a.ks + j) * 64 + lane;   // in 16-byte units
+    reinterpret_cast<u32x4*>(a.planes)[chunk] = hi.v;
+    if (a.terms == 2) reinterpret_cast<u32x4*>(a.planes)[chunk + (size_t)a.ks * 64] = lo.v;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// input quantiser (Sec. IV: inputs are scaled and sent to the DAC)
+// ---------------------------------------------------------------------------------------------
+struct QuantArgs {
+  const float* X;
+  uint16_t* A;       // [phase][MP][T][ks][64][8]
+  int M, L, MP, T, ks, tile, P, input_bits;
+  float scale;
+  long long n_threads;
+};
+
+__global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
+  const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (tid >= a.n_threads) return;
+  const int lane = (int)(tid & 63);
+  const long long blk = tid >> 6;                  // (mp, t, j)
+  const int j = (int)(blk % a.ks);
+  const int t = (int)((blk / a.ks) % a.T);
+  const int mp = (int)(blk / ((long long)a.ks * a.T));
+  const int m = mp * 32 + (lane & 31);
+  const int l0 = t * a.tile + j * 16 + (lane >> 5) * 8;
+  const double qa = (double)((1u << a.input_bits) - 1);
+  const double lo = a.P == 2 ? -1.0 : 0.0;
+  union { u32x4 v; uint16_t h[8]; } pos, neg;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int l = l0 + e;
+    int q = 0;
+    if (m < a.M && l < a.L && l < (t + 1) * a.tile)
+      q = (int)::rint(clampd((double)a.X[(size_t)m * a.L + l] / (double)a.scale, lo, 1.0) * qa);
+    pos.h[e] = (uint16_t)(q > 0 ? q : 0);
+    neg.h[e] = (uint16_t)(q < 0 ? -q : 0);
+  }
+  u32x4* out = reinterpret_cast<u32x4*>(a.A);
+  out[(size_t)blk * 64 + lane] = pos.v;
+  if (a.P == 2) out[((size_t)a.MP * a.T * a.ks + (size_t)blk) * 64 + lane] = neg.v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// crossbar-tile contraction + ADC + shift-and-add (Sec. IV-B), forward and backward
+// ---------------------------------------------------------------------------------------------
+struct VmmArgs {
+  const u32x4* A;      // quantised input fragments
+  const u32x4* B;      // plane fragments of this direction
+  void* part;          // [nchunk][M][Lout] int32 (narrow) or int64 (wide)
+  int16_t* codes;      // optional [P][S_in][S_w][T][M][Lout]
+  int M, Lin, Lout, MP, OP, MB, T, P, VT;
+  int S_w, S_in, slice_bits, stream_bits, ks, tile;
+  int vt_per_chunk, nchunk, SG;
+  int total_wg, per_xcd;
+  float gain;          // float(Q) / adc_fs
+  float clamp_lo, clamp_hi;   // kMagic -+ Q
+  uint32_t bias_per_vt;       // kMagicBits * sum of all shift weights, mod 2^32
+};
+
+template <int PM, int KSMAX, int TERMS, bool WIDE, bool CODES, bool FULL>
+__device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* lds, const u32x4 (&raw)[PM][KSMAX],
+                                               int nk, int ns, int sg0, int p, int t, int lane, int mp0,
+                                               int op, uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
+  const uint32_t digit_mask = ((1u << a.stream_bits) - 1u) * 0x00010001u;
+  const float vmagic = kMagic;
+  for (int b = 0; b < a.S_in; ++b) {
+    const int in_shift = a.stream_bits * b;
+    const uint32_t mask = digit_mask << in_shift;
+    // operand lanes hold digit * 2^(in_shift - 24); undo that power of two in the ADC gain
+    const float gain_b = ldexpf(p ? -a.gain : a.gain, 24 - in_shift);
+    half8 ab[PM][KSMAX];
+#pragma unroll
+    for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+      for (int j = 0; j < KSMAX; ++j) {
+        u32x4 v = raw[pm][j] & mask;
+        ab[pm][j] = __builtin_bit_cast(half8, v);
+      }
+    for (int sl = 0; sl < ns; ++sl) {
+      const int s = sg0 + sl;
+      const int sh = a.slice_bits * s + in_shift;
+      float16v acc[PM];
+#pragma unroll
+      for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[pm][r] = 0.0f;
+      const u32x4* bbase = lds + (size_t)sl * TERMS * a.ks * 64 + lane;
+      // Residual term first, in a pass of its own: while the accumulator is still small the matrix
+      // core keeps all bits of the small products.  The leading term follows; it sits on a fixed
+      // binary grid, so its products add without rounding.
+      if (TERMS == 2) {
+#pragma unroll
+        for (int j = 0; j < KSMAX; ++j) {
+          if (FULL || j < nk) {
+            const half8 bl = __builtin_bit_cast(half8, bbase[(a.ks + j) * 64]);
+#pragma unroll
+            for (int pm = 0; pm < PM; ++pm)
+              acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][j], bl, acc[pm], 0, 0, 0);
+          }
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < KSMAX; ++j) {
+        if (FULL || j < nk) {
+          const half8 bh = __builtin_bit_cast(half8, bbase[j * 64]);
+#pragma unroll
+          for (int pm = 0; pm < PM; ++pm)
+            acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][j], bh, acc[pm], 0, 0, 0);
+        }
+      }
+      // ADC: code = clamp(rne(I * gain)); shift-and-add in integers
+#pragma unroll
+      for (int pm = 0; pm < PM; ++pm) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float f = __builtin_fmaf(acc[pm][r], gain_b, vmagic);
+          f = __builtin_amdgcn_fmed3f(f, a.clamp_lo, a.clamp_hi);
+          const uint32_t bits = __builtin_bit_cast(uint32_t, f);
+          if (WIDE) {
+            y64[pm][r] += (long long)((int)(bits - kMagicBits)) << sh;
+          } else {
+            y[pm][r] = (bits << sh) + y[pm][r];
+          }
+          if (CODES) {
+            const int m = (mp0 + pm) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            const int o = op * 32 + (lane & 31);
+            if (m < a.M && o < a.Lout) {
+              int code = (int)(bits - kMagicBits);
+              if (p) code = -code;
+              a.codes[(((((size_t)p * a.S_in + b) * a.S_w + s) * a.T + t) * a.M + m) * a.Lout + o] = (int16_t)code;
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int PM, int KSMAX, int TERMS, bool WIDE, bool CODES>
+__global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
+  extern __shared__ u32x4 lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  // consecutive block ids go to different XCDs; give each XCD a contiguous range of logical work so
+  // that blocks sharing the same planes share one L2
+  const int logical = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
+  if (logical >= a.total_wg) return;
+  const int mb = logical % a.MB;
+  const int grp = logical / a.MB;
+  const int op = grp % a.OP;
+  const int chunk = grp / a.OP;
+  const int mp0 = (mb * nw + wave) * PM;
+
+  uint32_t y[PM][16];
+  long long y64[PM][16];
+#pragma unroll
+  for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      y[pm][r] = 0;
+      y64[pm][r] = 0;
+    }
+
+  const int vt0 = chunk * a.vt_per_chunk;
+  const int vt1 = min(a.VT, vt0 + a.vt_per_chunk);
+  for (int vt = vt0; vt < vt1; ++vt) {
+    const int p = vt / a.T, t = vt - p * a.T;
+    const int rows = min(a.tile, a.Lin - t * a.tile);
+    const int nk = (rows + 15) >> 4;
+    u32x4 raw[PM][KSMAX];
+#pragma unroll
+    for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+      for (int j = 0; j < KSMAX; ++j) {
+        u32x4 v = {0, 0, 0, 0};
+        if (j < nk && mp0 + pm < a.MP)
+          v = a.A[((((size_t)p * a.MP + mp0 + pm) * a.T + t) * a.ks + j) * 64 + lane];
+        raw[pm][j] = v;
+      }
+    for (int sg0 = 0; sg0 < a.S_w; sg0 += a.SG) {
+      const int ns = min(a.SG, a.S_w - sg0);
+      __syncthreads();
+      const u32x4* src = a.B + (((size_t)t * a.OP + op) * a.S_w + sg0) * TERMS * a.ks * 64;
+      const int n16 = ns * TERMS * a.ks * 64;
+      for (int i = threadIdx.x; i < n16; i += blockDim.x) {
+        const int j = (i >> 6) % a.ks;
+        if (j < nk) lds[i] = src[i];
+      }
+      __syncthreads();
+      if (nk == KSMAX)
+        vmm_tile_group<PM, KSMAX, TERMS, WIDE, CODES, true>(a, lds, raw, nk, ns, sg0, p, t, lane, mp0, op, y, y64);
+      else
+        vmm_tile_group<PM, KSMAX, TERMS, WIDE, CODES, false>(a, lds, raw, nk, ns, sg0, p, t, lane, mp0, op, y, y64);
+    }
+  }
+  // partial result of this chunk
+  const uint32_t bias = a.bias_per_vt * (uint32_t)(vt1 - vt0);
+#pragma unroll
+  for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = (mp0 + pm) * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+      const int o = op * 32 + (lane & 31);
+      if (m < a.M && o < a.Lout && mp0 + pm < a.MP) {
+        const size_t idx = ((size_t)chunk * a.M + m) * a.Lout + o;
+        if (WIDE) reinterpret_cast<long long*>(a.part)[idx] = y64[pm][r];
+        else reinterpret_cast<int32_t*>(a.part)[idx] = (int32_t)(y[pm][r] - bias);
+      }
+    }
+}
+
+struct FinishArgs {
+  const void* part;
+  float* out;
+  long long n;   // M * Lout
+  int nchunk, wide;
+  double scale;
+};
+
+__global__ __launch_bounds__(256) void vmm_finish_kernel(FinishArgs a) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.n) return;
+  long long sum = 0;
+  for (int c = 0; c < a.nchunk; ++c)
+    sum += a.wide ? reinterpret_cast<const long long*>(a.part)[(size_t)c * a.n + i]
+                  : (long long)reinterpret_cast<const int32_t*>(a.part)[(size_t)c * a.n + i];
+  a.out[i] = (float)((double)sum * a.scale);
+}
+
+// ---------------------------------------------------------------------------------------------
+// update model (Sec. IV-C)
+// ---------------------------------------------------------------------------------------------
+struct GradArgs {
+  const float* X;   // [M][K]
+  const float* D;   // [M][N]
+  float* part;      // [mchunks][K][N]
+  int M, K, N, KB, NB, m_per_chunk;
+};
+
+constexpr int kGradMS = 16;   // batch rows per LDS stage
+
+// 128 x 128 tile of X^T dY per block, 4 waves as 2 x 2, each wave 64 x 64 = 2 x 2 MFMA tiles.
+__global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
+  __shared__ float xs[kGradMS][128];
+  __shared__ float ds[kGradMS][128];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wk = wave >> 1, wn = wave & 1;
+  const int kb = blockIdx.x % a.KB, nb = blockIdx.x / a.KB;
+  const int k0 = kb * 128, n0 = nb * 128;
+  const int m_begin = blockIdx.y * a.m_per_chunk;
+  const int m_end = min(a.M, m_begin + a.m_per_chunk);
+  float16v acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  float px[8], pd[8];
+  auto prefetch = [&](int m0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i = tid + e * 256;
+      const int row = i >> 7, col = i & 127;
+      const int m = m0 + row;
+      px[e] = (m < m_end && k0 + col < a.K) ? a.X[(size_t)m * a.K + k0 + col] : 0.0f;
+      pd[e] = (m < m_end && n0 + col < a.N) ? a.D[(size_t)m * a.N + n0 + col] : 0.0f;
+    }
+  };
+  prefetch(m_begin);
+  for (int m0 = m_begin; m0 < m_end; m0 += kGradMS) {
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int i = tid + e * 256;
+      xs[i >> 7][i & 127] = px[e];
+      ds[i >> 7][i & 127] = pd[e];
+    }
+    __syncthreads();
+    if (m0 + kGradMS < m_end) prefetch(m0 + kGradMS);
+#pragma unroll
+    for (int mm = 0; mm < kGradMS; mm += 2) {
+      const int row = mm + (lane >> 5);
+      const float a0 = xs[row][wk * 64 + (lane & 31)];
+      const float a1 = xs[row][wk * 64 + 32 + (lane & 31)];
+      const float b0 = ds[row][wn * 64 + (lane & 31)];
+      const float b1 = ds[row][wn * 64 + 32 + (lane & 31)];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+  }
+  float* out = a.part + (size_t)blockIdx.y * a.K * a.N;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int k = k0 + wk * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+        if (k < a.K && n < a.N) out[(size_t)k * a.N + n] = acc[i][j][r];
+      }
+}
+
+struct WriteArgs {
+  float* W;
+  const float* part;
+  long long n;      // K * N
+  int mchunks;
+  uint32_t flags;
+  double w_max, grad_scale, lr, v, gamma;
+  uint64_t seed, step;
+};
+
+__global__ __launch_bounds__(256) void update_write_kernel(WriteArgs a) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= a.n) return;
+  double grad = 0.0;
+  for (int c = 0; c < a.mchunks; ++c) grad += (double)a.part[(size_t)c * a.n + i];
+  const double g = (double)a.W[i] / a.w_max;
+  const double delta = a.grad_scale * grad;
+  double written = delta;
+  if (a.flags & XBAR_NI_UPD_NL) {
+    const double x = clampd(0.5 * (g + 1.0), 0.0, 1.0);
+    const double change = -a.lr * delta;
+    if (change > 0.0) written = delta * ::exp(-a.v * x);
+    else if (change < 0.0) written = delta * ::exp(-a.v * (1.0 - x));
+  }
+  if (a.flags & XBAR_NI_UPD_NOISE) {
+    NormalStream rng(a.seed, kStreamWrite, a.step);
+    written += a.gamma * ::sqrt(::fabs(delta)) * rng.get((uint64_t)i);
+  }
+  const double g_new = clampd(g - a.lr * written, -1.0, 1.0);
+  a.W[i] = (float)(a.w_max * g_new);
+}
+
+// ---------------------------------------------------------------------------------------------
+// host dispatch
+// ---------------------------------------------------------------------------------------------
+inline bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool finite_pos(float x) { return std::isfinite(x) && x > 0.0f; }
+inline bool finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
+
+int check_shape(int M, int K, int N) {
+  if (M <= 0 || K <= 0 || N <= 0) return XBAR_ESHAPE;
+  if ((long long)M * K >= (1ll << 31) || (long long)M * N >= (1ll << 31) || (long long)K * N >= (1ll << 31))
+    return XBAR_ESHAPE;
+  return XBAR_OK;
+}
+
+thread_local hipEvent_t g_trace_before = nullptr, g_trace_after = nullptr;
+
+struct VmmPlan {
+  PlaneGeom g;
+  int Lin, Lout, MP, P, VT, vt_per_chunk, nchunk, wide, pm, nw, MB, SG;
+  uint32_t bias_per_vt;
+  size_t a_bytes, part_bytes, ws_bytes, lds_bytes;
+};
+
+VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bool transposed) {
+  VmmPlan p;
+  p.g = plane_geom(c, d, K, N, transposed);
+  p.Lin = transposed ? N : K;
+  p.Lout = transposed ? K : N;
+  p.MP = cdiv(M, 32);
+  p.P = (transposed || (c->flags & XBAR_INPUT_SIGNED)) ? 2 : 1;
+  p.VT = p.P * p.g.T;
+  // sum of the shift-and-add weights of one virtual tile
+  unsigned long long wsum = 0;
+  for (int s = 0; s < d.S_w; ++s)
+    for (int b = 0; b < d.S_in; ++b) wsum += 1ull << (c->slice_bits * s + c->stream_bits * b);
+  p.bias_per_vt = (uint32_t)((unsigned long long)kMagicBits * wsum);
+  const unsigned long long per_vt = wsum * (unsigned long long)d.q_adc;
+  const unsigned long long fit = per_vt ? ((1ull << 31) - 1) / per_vt : (1ull << 31);
+  p.wide = fit < 1;
+  p.pm = p.g.ks > 8 ? 1 : 2;
+  p.nw = std::min(4, std::max(1, cdiv(p.MP, p.pm)));
+  p.MB = cdiv(p.MP, p.pm * p.nw);
+  const int groups = p.g.OP * p.MB;
+  int want_chunks = std::max(1, cdiv(2048, groups));      // enough blocks to fill 256 CUs several times
+  int per = std::max(1, cdiv(p.VT, want_chunks));
+  if (!p.wide) per = (int)std::min<unsigned long long>((unsigned long long)per, fit);
+  p.vt_per_chunk = per;
+  p.nchunk = cdiv(p.VT, per);
+  const int slice_kb = d.terms * p.g.ks;                   // KiB of operand per slice and output patch
+  p.SG = std::max(1, std::min(d.S_w, 64 / slice_kb));
+  p.lds_bytes = (size_t)p.SG * slice_kb * 1024;
+  p.a_bytes = align256((size_t)p.P * p.MP * p.g.T * p.g.ks * 1024);
+  p.part_bytes = align256((size_t)p.nchunk * M * p.Lout * (p.wide ? 8 : 4));
+  p.ws_bytes = p.a_bytes + p.part_bytes;
+  return p;
+}
+
+struct UpdPlan {
+  int KB, NB, mchunks, m_per_chunk;
+  size_t ws_bytes;
+};
+
+UpdPlan plan_update(int M, int K, int N) {
+  UpdPlan p;
+  p.KB = cdiv(K, 128);
+  p.NB = cdiv(N, 128);
+  const int tiles = p.KB * p.NB;
+  int want = std::max(1, cdiv(1024, tiles));
+  int per = std::max(kGradMS, cdiv(cdiv(M, want), kGradMS) * kGradMS);
+  p.m_per_chunk = per;
+  p.mchunks = cdiv(M, per);
+  p.ws_bytes = align256((size_t)p.mchunks * K * N * sizeof(float));
+  return p;
+}
+
+template <int PM, int KSMAX, int TERMS>
+hipError_t launch_vmm_variant(const VmmArgs& a, const VmmPlan& p, bool codes, hipStream_t st) {
+  const dim3 grid((unsigned)(a.per_xcd * 8)), block((unsigned)(p.nw * 64));
+  void (*k)(VmmArgs);
+  if (p.wide) k = codes ? vmm_kernel<PM, KSMAX, TERMS, true, true> : vmm_kernel<PM, KSMAX, TERMS, true, false>;
+  else k = codes ? vmm_kernel<PM, KSMAX, TERMS, false, true> : vmm_kernel<PM, KSMAX, TERMS, false, false>;
+  if (p.lds_bytes > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)p.lds_bytes);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k, grid, block, p.lds_bytes, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_vmm(const VmmArgs& a, const VmmPlan& p, int terms, bool codes, hipStream_t st) {
+  const int ks = p.g.ks;
+  if (ks <= 4) return terms == 2 ? launch_vmm_variant<2, 4, 2>(a, p, codes, st) : launch_vmm_variant<2, 4, 1>(a, p, codes, st);
+  if (ks <= 8) return terms == 2 ? launch_vmm_variant<2, 8, 2>(a, p, codes, st) : launch_vmm_variant<2, 8, 1>(a, p, codes, st);
+  return terms == 2 ? launch_vmm_variant<1, 16, 2>(a, p, codes, st) : launch_vmm_variant<1, 16, 1>(a, p, codes, st);
+}
+
+int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* out, int M, int K, int N,
+            float w_max, float in_scale, void* ws, size_t ws_bytes, int16_t* codes, void* stream, bool transposed) {
+  int rc = xbar_config_validate(cfg);
+  if (rc) return rc;
+  if ((rc = check_shape(M, K, N))) return rc;
+  if (!aligned16(planes) || !aligned16(in) || !aligned16(out) || !aligned16(ws)) return XBAR_EALIGN;
+  if (codes && (reinterpret_cast<uintptr_t>(codes) & 1u)) return XBAR_EALIGN;
+  if (!finite_pos(w_max) || !finite_pos(in_scale)) return XBAR_EINVAL;
+  if (cfg->flags & XBAR_DAC_LUT) return XBAR_ENOTSUP;
+  const Derived d = derive(cfg);
+  const VmmPlan p = plan_vmm(cfg, d, M, K, N, transposed);
+  if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const float adc_fs = transposed ? cfg->adc_fs_bwd : cfg->adc_fs_fwd;
+
+  QuantArgs qa;
+  qa.X = in;
+  qa.A = reinterpret_cast<uint16_t*>(ws);
+  qa.M = M; qa.L = p.Lin; qa.MP = p.MP; qa.T = p.g.T; qa.ks = p.g.ks; qa.tile = p.g.tile; qa.P = p.P;
+  qa.input_bits = cfg->input_bits;
+  qa.scale = in_scale;
+  qa.n_threads = (long long)p.MP * p.g.T * p.g.ks * 64;
+  hipLaunchKernelGGL(quantize_input_kernel, dim3((unsigned)((qa.n_threads + 255) / 256)), dim3(256), 0, st, qa);
+  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+
+  const PlaneGeom gf = plane_geom(cfg, d, K, N, false);
+  VmmArgs a;
+  a.A = reinterpret_cast<const u32x4*>(ws);
+  a.B = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(planes) + (transposed ? align256(gf.bytes) : 0));
+  a.part = reinterpret_cast<char*>(ws) + p.a_bytes;
+  a.codes = codes;
+  a.M = M; a.Lin = p.Lin; a.Lout = p.Lout; a.MP = p.MP; a.OP = p.g.OP; a.MB = p.MB; a.T = p.g.T; a.P = p.P;
+  a.VT = p.VT; a.S_w = d.S_w; a.S_in = d.S_in; a.slice_bits = cfg->slice_bits; a.stream_bits = cfg->stream_bits;
+  a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.SG = p.SG;
+  a.total_wg = p.nchunk * p.g.OP * p.MB;
+  a.per_xcd = cdiv(a.total_wg, 8);
+  a.gain = (float)d.q_adc / adc_fs;
+  a.clamp_lo = kMagic - (float)d.q_adc;
+  a.clamp_hi = kMagic + (float)d.q_adc;
+  a.bias_per_vt = p.bias_per_vt;
+  hipEvent_t ev0 = g_trace_before, ev1 = g_trace_after;
+  g_trace_before = g_trace_after = nullptr;
+  if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return XBAR_EHIP;
+  if (launch_vmm(a, p, d.terms, codes != nullptr, st) != hipSuccess) return XBAR_EHIP;
+  if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return XBAR_EHIP;
+
+  FinishArgs f;
+  f.part = a.part;
+  f.out = out;
+  f.n = (long long)M * p.Lout;
+  f.nchunk = p.nchunk;
+  f.wide = p.wide;
+  const double lsb = (double)adc_fs / (double)d.q_adc;
+  const double qa_max = (double)((1u << cfg->input_bits) - 1), qw_max = (double)((1u << cfg->weight_bits) - 1);
+  f.scale = lsb * (double)in_scale * (double)w_max / (qa_max * qw_max);
+  hipLaunchKernelGGL(vmm_finish_kernel, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
+  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+  return XBAR_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+uint32_t xbar_abi_version(void) { return XBAR_ABI_VERSION; }
+
+void xbar_trace_next_vmm(void* before, void* after) {
+  g_trace_before = reinterpret_cast<hipEvent_t>(before);
+  g_trace_after = reinterpret_cast<hipEvent_t>(after);
+}
+
+const char* xbar_strerror(int code) {
+  switch (code) {
+    case XBAR_OK: return "ok";
+    case XBAR_EINVAL: return "invalid parameter struct or scalar argument";
+    case XBAR_ESHAPE: return "M, K, N must be positive and each matrix below 2^31 elements";
+    case XBAR_EALIGN: return "null or misaligned pointer (16 bytes required)";
+    case XBAR_EWORKSPACE: return "workspace or plane buffer too small";
+    case XBAR_EHIP: return "HIP kernel launch failed";
+    case XBAR_ENOTSUP: return "not supported by the GPU kernels";
+    default: return "unknown xbar status";
+  }
+}
+
+int xbar_config_validate(const xbar_config* c) {
+  if (!c) return XBAR_EINVAL;
+  if (c->struct_size != sizeof(xbar_config) || c->abi_version != XBAR_ABI_VERSION) return XBAR_EINVAL;
+  if (c->xbar_rows < 16 || c->xbar_rows > 256 || c->xbar_rows % 16) return XBAR_EINVAL;
+  if (c->xbar_cols < 16 || c->xbar_cols > 256 || c->xbar_cols % 16) return XBAR_EINVAL;
+  if (c->slice_bits < 1 || c->slice_bits > 4) return XBAR_EINVAL;
+  if (c->weight_bits < 1 || c->weight_bits > 16 || c->weight_bits % c->slice_bits) return XBAR_EINVAL;
+  if (c->input_bits < 1 || c->input_bits > 8) return XBAR_EINVAL;
+  if (c->stream_bits < 1 || c->stream_bits > c->input_bits || c->input_bits % c->stream_bits) return XBAR_EINVAL;
+  if (c->adc_bits < 2 || c->adc_bits > 16) return XBAR_EINVAL;
+  if (c->flags & ~0x7Fu) return XBAR_EINVAL;
+  if ((c->flags & XBAR_NI_WIRE_AAM) && (c->flags & XBAR_NI_WIRE_PROFILE)) return XBAR_EINVAL;
+  if (!finite_pos(c->r_min) || !finite_pos(c->r_max) || !(c->r_max > c->r_min)) return XBAR_EINVAL;
+  if (!finite_pos(c->v_max)) return XBAR_EINVAL;
+  if (!finite_nonneg(c->r_row) || !finite_nonneg(c->r_col) || !finite_nonneg(c->r_source) ||
+      !finite_nonneg(c->r_sense))
+    return XBAR_EINVAL;
+  if (!finite_nonneg(c->var_sigma) || !finite_nonneg(c->upd_nl_v) || !finite_nonneg(c->upd_noise_gamma))
+    return XBAR_EINVAL;
+  if (!finite_pos(c->adc_fs_fwd) || !finite_pos(c->adc_fs_bwd)) return XBAR_EINVAL;
+  if (c->flags & XBAR_DAC_LUT)
+    for (int i = 0; i < (1 << c->stream_bits) && i < 16; ++i)
+      if (!std::isfinite(c->dac_lut[i])) return XBAR_EINVAL;
+  return XBAR_OK;
+}
+
+size_t xbar_planes_bytes(const xbar_config* cfg, int K, int N) {
+  if (xbar_config_validate(cfg) || check_shape(1, K, N)) return 0;
+  const Derived d = derive(cfg);
+  return align256(plane_geom(cfg, d, K, N, false).bytes) + align256(plane_geom(cfg, d, K, N, true).bytes);
+}
+
+size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N) {
+  if (xbar_config_validate(cfg) || check_shape(M, K, N)) return 0;
+  const Derived d = derive(cfg);
+  if (op == XBAR_OP_FWD) return plan_vmm(cfg, d, M, K, N, false).ws_bytes;
+  if (op == XBAR_OP_BWD) return plan_vmm(cfg, d, M, K, N, true).ws_bytes;
+  if (op == XBAR_OP_UPDATE) return plan_update(M, K, N).ws_bytes;
+  return 0;
+}
+
+int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max, uint64_t step, const float* profile,
+              void* planes, size_t planes_bytes, void* hip_stream) {
+  int rc = xbar_config_validate(cfg);
+  if (rc) return rc;
+  if ((rc = check_shape(1, K, N))) return rc;
+  if (!aligned16(W) || !aligned16(planes)) return XBAR_EALIGN;
+  if ((cfg->flags & XBAR_NI_WIRE_PROFILE) && !aligned16(profile)) return XBAR_EALIGN;
+  if (!finite_pos(w_max)) return XBAR_EINVAL;
+  if (planes_bytes < xbar_planes_bytes(cfg, K, N)) return XBAR_EWORKSPACE;
+  const Derived d = derive(cfg);
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  size_t offset = 0;
+  for (int dir = 0; dir < 2; ++dir) {
+    const PlaneGeom g = plane_geom(cfg, d, K, N, dir == 1);
+    TileArgs a;
+    a.W = W;
+    a.profile = profile;
+    a.planes = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(planes) + offset);
+    a.K = K; a.N = N; a.R = cfg->xbar_rows; a.C = cfg->xbar_cols; a.S_w = d.S_w;
+    a.slice_bits = cfg->slice_bits; a.weight_bits = cfg->weight_bits; a.terms = d.terms;
+    a.tile = g.tile; a.ks = g.ks; a.T = g.T; a.OP = g.OP;
+    a.flags = cfg->flags;
+    a.g_min = 1.0 / (double)cfg->r_max;
+    a.dg = (1.0 / (double)cfg->r_min - a.g_min) / (double)((1 << cfg->slice_bits) - 1);
+    a.var_sigma = (double)cfg->var_sigma;
+    a.r_row = (double)cfg->r_row;
+    a.r_col = (double)cfg->r_col;
+    a.r_source = (double)cfg->r_source;
+    a.r_sense = (double)cfg->r_sense;
+    {  // |U| < 2^slice_bits: fp16 holds multiples of 2^-(11 - slice_bits) below that bound exactly
+      const int hi_frac = 11 - cfg->slice_bits;
+      a.hi_scale = std::ldexp(1.0, hi_frac);
+      a.hi_inv_scale = std::ldexp(1.0, -hi_frac);
+    }
+    a.w_max = w_max;
+    a.seed = cfg->seed;
+    a.step = step;
+    // every k-step that the contraction reads is written whole, padding included
+    const int Lc = dir == 1 ? N : K;
+    const long long chunks = (long long)cdiv(Lc, 16) * 2;
+    a.n_threads = chunks * g.OP * 32;
+    const unsigned blocks = (unsigned)((a.n_threads + 255) / 256);
+    if (dir == 0) hipLaunchKernelGGL(tile_planes_kernel<false>, dim3(blocks), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(tile_planes_kernel<true>, dim3(blocks), dim3(256), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+    offset += align256(g.bytes);
+  }
+  return XBAR_OK;
+}
+
+int xbar_fwd(const xbar_config* cfg, const void* planes, const float* X, float* Y, int M, int K, int N, float w_max,
+             float x_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream) {
+  return run_vmm(cfg, planes, X, Y, M, K, N, w_max, x_scale, ws, ws_bytes, codes, hip_stream, false);
+}
+
+int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float* dX, int M, int K, int N, float w_max,
+             float g_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream) {
+  return run_vmm(cfg, planes, dY, dX, M, K, N, w_max, g_scale, ws, ws_bytes, codes, hip_stream, true);
+}
+
+int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
+                float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = xbar_config_validate(cfg);
+  if (rc) return rc;
+  if ((rc = check_shape(M, K, N))) return rc;
+  if (!aligned16(W) || !aligned16(X) || !aligned16(dY) || !aligned16(ws)) return XBAR_EALIGN;
+  if (!finite_pos(w_max) || !std::isfinite(grad_scale) || !std::isfinite(lr)) return XBAR_EINVAL;
+  const UpdPlan p = plan_update(M, K, N);
+  if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  GradArgs g;
+  g.X = X; g.D = dY; g.part = reinterpret_cast<float*>(ws);
+  g.M = M; g.K = K; g.N = N; g.KB = p.KB; g.NB = p.NB; g.m_per_chunk = p.m_per_chunk;
+  hipLaunchKernelGGL(grad_gemm_kernel, dim3((unsigned)(p.KB * p.NB), (unsigned)p.mchunks), dim3(256), 0, st, g);
+  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+  WriteArgs w;
+  w.W = W; w.part = g.part; w.n = (long long)K * N; w.mchunks = p.mchunks; w.flags = cfg->flags;
+  w.w_max = (double)w_max; w.grad_scale = (double)grad_scale; w.lr = (double)lr;
+  w.v = (double)cfg->upd_nl_v; w.gamma = (double)cfg->upd_noise_gamma;
+  w.seed = cfg->seed; w.step = step;
+  hipLaunchKernelGGL(update_write_kernel, dim3((unsigned)((w.n + 255) / 256)), dim3(256), 0, st, w);
+  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+  return XBAR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,193 @@
+"""Thin binding of the C-ABI library (include/xbar.h): argument marshalling only.
+
+Every step of the path runs in the HIP kernels of libxbar.so; torch is used for device memory and
+for the current stream.  There is no CPU fallback: if the library is missing, every call raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libxbar.so")
+
+NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED = 1, 2, 4, 8, 16, 32, 64
+OP_FWD, OP_BWD, OP_UPDATE = 0, 1, 2
+ABI_VERSION = 1
+
+
+class XbarError(RuntimeError):
+    pass
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("struct_size", C.c_uint32), ("abi_version", C.c_uint32),
+        ("xbar_rows", C.c_int32), ("xbar_cols", C.c_int32),
+        ("weight_bits", C.c_int32), ("slice_bits", C.c_int32),
+        ("input_bits", C.c_int32), ("stream_bits", C.c_int32),
+        ("adc_bits", C.c_int32), ("flags", C.c_uint32),
+        ("r_min", C.c_float), ("r_max", C.c_float), ("v_max", C.c_float),
+        ("r_row", C.c_float), ("r_col", C.c_float),
+        ("r_source", C.c_float), ("r_sense", C.c_float),
+        ("var_sigma", C.c_float),
+        ("upd_nl_v", C.c_float), ("upd_noise_gamma", C.c_float),
+        ("adc_fs_fwd", C.c_float), ("adc_fs_bwd", C.c_float),
+        ("dac_lut", C.c_float * 16),
+        ("seed", C.c_uint64),
+    ]
+
+
+def make_config(**kw):
+    """Parameter struct with the values the paper states (Sec. V, Sec. VI-B) unless overridden."""
+    c = Config()
+    c.struct_size = C.sizeof(Config)
+    c.abi_version = ABI_VERSION
+    d = dict(xbar_rows=64, xbar_cols=64, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=1,
+             adc_bits=8, flags=0, r_min=1e5, r_max=1e6, v_max=1.0, r_row=1.0, r_col=4.6, r_source=0.0,
+             r_sense=0.0, var_sigma=0.0, upd_nl_v=0.01, upd_noise_gamma=5.0, adc_fs_fwd=64.0,
+             adc_fs_bwd=64.0, seed=0)
+    d.update(kw)
+    lut = d.pop("dac_lut", None)
+    for k, v in d.items():
+        setattr(c, k, v)
+    levels = max(1, (1 << max(0, min(4, c.stream_bits))) - 1)
+    for i in range(16):
+        c.dac_lut[i] = (lut[i] if lut is not None and i < len(lut) else (i / levels if i <= levels else 0.0))
+    return c
+
+
+_lib = None
+
+_SIGNATURES = {
+    "xbar_abi_version": (C.c_uint32, []),
+    "xbar_strerror": (C.c_char_p, [C.c_int]),
+    "xbar_config_validate": (C.c_int, [C.POINTER(Config)]),
+    "xbar_planes_bytes": (C.c_size_t, [C.POINTER(Config), C.c_int, C.c_int]),
+    "xbar_workspace_bytes": (C.c_size_t, [C.POINTER(Config), C.c_int, C.c_int, C.c_int, C.c_int]),
+    "xbar_tile": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_uint64, C.c_void_p,
+                            C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_fwd": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                           C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "xbar_bwd": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                           C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "xbar_trace_next_vmm": (None, [C.c_void_p, C.c_void_p]),
+    "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                              C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
+}
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise XbarError("libxbar.so is not built (run `python -c 'import __graft_entry__ as g; g.build()'`); "
+                            "there is no fallback path")
+        _lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            f = getattr(_lib, name)
+            f.restype, f.argtypes = res, args
+        if _lib.xbar_abi_version() != ABI_VERSION:
+            raise XbarError("libxbar.so has a different ABI version")
+    return _lib
+
+
+def strerror(code):
+    return lib().xbar_strerror(code).decode()
+
+
+def _check(code):
+    if code != 0:
+        raise XbarError("xbar error %d: %s" % (code, strerror(code)))
+
+
+def trace_next_vmm(before, after):
+    """xbar_trace_next_vmm: hipEvent_t handles (integers) recorded around the next contraction kernel."""
+    lib().xbar_trace_next_vmm(C.c_void_p(before), C.c_void_p(after))
+
+
+def validate(cfg):
+    return lib().xbar_config_validate(C.byref(cfg))
+
+
+def planes_bytes(cfg, K, N):
+    return lib().xbar_planes_bytes(C.byref(cfg), K, N)
+
+
+def workspace_bytes(cfg, op, M, K, N):
+    return lib().xbar_workspace_bytes(C.byref(cfg), op, M, K, N)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype=torch.float32):
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), "need a contiguous %s CUDA tensor" % dtype
+    return C.c_void_p(t.data_ptr())
+
+
+def _buffer(nbytes, buf, device):
+    if buf is None:
+        buf = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=device)
+    assert buf.is_cuda and buf.dtype == torch.uint8 and buf.is_contiguous()
+    return buf
+
+
+def tile(cfg, W, w_max, step=0, profile=None, planes=None):
+    """xbar_tile: planes of W[K][N] (float32 CUDA tensor).  Returns the opaque plane buffer."""
+    K, N = W.shape
+    nbytes = planes_bytes(cfg, K, N)
+    if nbytes == 0:
+        _check(validate(cfg) or -2)
+    planes = _buffer(nbytes, planes, W.device)
+    prof = None if profile is None else _dev(profile)
+    _check(lib().xbar_tile(C.byref(cfg), _dev(W), K, N, w_max, step, prof, C.c_void_p(planes.data_ptr()),
+                           planes.numel(), _stream()))
+    return planes
+
+
+def _vmm(fn, op, cfg, planes, inp, out_cols, K, N, w_max, in_scale, ws, out, want_codes):
+    M = inp.shape[0]
+    nbytes = workspace_bytes(cfg, op, M, K, N)
+    if nbytes == 0:
+        _check(validate(cfg) or -2)
+    ws = _buffer(nbytes, ws, inp.device)
+    if out is None:
+        out = torch.empty((M, out_cols), dtype=torch.float32, device=inp.device)
+    codes = None
+    if want_codes:
+        P = 2 if (op == OP_BWD or cfg.flags & INPUT_SIGNED) else 1
+        tile_len = cfg.xbar_cols if op == OP_BWD else cfg.xbar_rows
+        lin = N if op == OP_BWD else K
+        T = (lin + tile_len - 1) // tile_len
+        codes = torch.zeros((P, cfg.input_bits // cfg.stream_bits, cfg.weight_bits // cfg.slice_bits, T, M, out_cols),
+                            dtype=torch.int16, device=inp.device)
+    _check(fn(C.byref(cfg), C.c_void_p(planes.data_ptr()), _dev(inp), _dev(out), M, K, N, w_max, in_scale,
+              C.c_void_p(ws.data_ptr()), ws.numel(), None if codes is None else C.c_void_p(codes.data_ptr()),
+              _stream()))
+    return (out, codes) if want_codes else out
+
+
+def fwd(cfg, planes, X, N, w_max, x_scale, ws=None, out=None, want_codes=False):
+    """xbar_fwd: Y[M][N] from X[M][K] through the planes of tile()."""
+    return _vmm(lib().xbar_fwd, OP_FWD, cfg, planes, X, N, X.shape[1], N, w_max, x_scale, ws, out, want_codes)
+
+
+def bwd(cfg, planes, dY, K, w_max, g_scale, ws=None, out=None, want_codes=False):
+    """xbar_bwd: dX[M][K] from dY[M][N] through the same planes."""
+    return _vmm(lib().xbar_bwd, OP_BWD, cfg, planes, dY, K, K, dY.shape[1], w_max, g_scale, ws, out, want_codes)
+
+
+def update(cfg, W, X, dY, w_max, grad_scale, lr, step=0, ws=None):
+    """xbar_update: W[K][N] in place from X[M][K] and dY[M][N]."""
+    K, N = W.shape
+    M = X.shape[0]
+    assert X.shape == (M, K) and dY.shape == (M, N)
+    nbytes = workspace_bytes(cfg, OP_UPDATE, M, K, N)
+    if nbytes == 0:
+        _check(validate(cfg) or -2)
+    ws = _buffer(nbytes, ws, W.device)
+    _check(lib().xbar_update(C.byref(cfg), _dev(W), _dev(X), _dev(dY), M, K, N, w_max, grad_scale, lr, step,
+                             C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return W

@@ -1,0 +1,278 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars (the benchmark spec): with the array non-idealities off the integer path is bit-exact; otherwise ADC
+codes differ by at most 1 LSB on at most 1e-4 of the conversions and layer outputs agree to a relative
+L2 error of 1e-3.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def xb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import xbar
+    xbar.lib()
+    return xbar
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def both_configs(xo, xb, **kw):
+    return xo.make_config(**kw), xb.make_config(**kw)
+
+
+def rel_l2(a, b):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def check_codes(got, want):
+    diff = np.abs(got.astype(np.int64) - want.astype(np.int64))
+    assert diff.max() <= 1, "ADC code off by more than 1 LSB"
+    frac = float((diff > 0).mean())
+    assert frac <= 1e-4, "fraction of differing ADC codes %.3g" % frac
+    return frac
+
+
+def gpu_fwd(xb, cfg, W, X, w_max, x_scale, step=0, profile=None, codes=True):
+    planes = xb.tile(cfg, dev(W), w_max, step, None if profile is None else dev(profile))
+    out = xb.fwd(cfg, planes, dev(X), W.shape[1], w_max, x_scale, want_codes=codes)
+    torch.cuda.synchronize()
+    return (out[0].cpu().numpy(), out[1].cpu().numpy()) if codes else out.cpu().numpy()
+
+
+def gpu_bwd(xb, cfg, W, dY, w_max, g_scale, step=0, profile=None, codes=True):
+    planes = xb.tile(cfg, dev(W), w_max, step, None if profile is None else dev(profile))
+    out = xb.bwd(cfg, planes, dev(dY), W.shape[0], w_max, g_scale, want_codes=codes)
+    torch.cuda.synchronize()
+    return (out[0].cpu().numpy(), out[1].cpu().numpy()) if codes else out.cpu().numpy()
+
+
+def full_precision_adc(R, C, sb, slb):
+    worst = max(R, C) * ((1 << sb) - 1) * ((1 << slb) - 1)
+    bits = int(math.ceil(math.log2(worst + 1))) + 1
+    return bits, float((1 << (bits - 1)) - 1)
+
+
+IDEAL_CASES = [
+    # R, C, stream_bits, slice_bits, weight_bits, signed, M, K, N, adc_bits (None = lossless)
+    (64, 64, 4, 2, 8, True, 64, 256, 256, None),
+    (64, 64, 4, 2, 8, True, 37, 150, 70, 8),
+    (128, 128, 1, 2, 16, False, 70, 147, 64, 8),
+    (128, 128, 1, 2, 16, True, 33, 300, 100, None),
+    (128, 64, 2, 1, 8, False, 130, 129, 33, 6),
+    (256, 256, 1, 2, 16, False, 40, 520, 48, 8),
+    (16, 32, 4, 4, 8, True, 5, 40, 70, 7),
+    (128, 128, 8, 2, 4, False, 3, 1, 1, 8),
+]
+
+
+@pytest.mark.parametrize("R,C,sb,slb,wb,signed,M,K,N,adc_bits", IDEAL_CASES)
+def test_ideal_fwd_bwd_bit_exact(xo, xb, R, C, sb, slb, wb, signed, M, K, N, adc_bits):
+    g = workloads.Gemm("t", K, N, M, signed, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=K * 7 + N)
+    if adc_bits is None:
+        adc_bits, fs = full_precision_adc(R, C, sb, slb)
+        fs_f = fs_b = fs
+    else:
+        fs_f, fs_b = workloads.adc_full_scale(R, sb, slb), workloads.adc_full_scale(C, sb, slb) * 0.75
+    co, cg = both_configs(xo, xb, xbar_rows=R, xbar_cols=C, weight_bits=wb, slice_bits=slb, input_bits=8,
+                          stream_bits=sb, adc_bits=adc_bits, flags=xo.INPUT_SIGNED if signed else 0,
+                          adc_fs_fwd=fs_f, adc_fs_bwd=fs_b)
+    w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    Yo, codes_o = xo.fwd(co, W, X, w_max, x_scale, want_codes=True)
+    Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale)
+    assert np.array_equal(codes_g, codes_o)
+    assert np.array_equal(Yg, Yo)
+    dXo, codes_o = xo.bwd(co, W, dY, w_max, g_scale, want_codes=True)
+    dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, g_scale)
+    assert np.array_equal(codes_g, codes_o)
+    assert np.array_equal(dXg, dXo)
+
+
+def test_ideal_lossless_is_integer_matmul(xo, xb):
+    # non-idealities off, converters at full precision: the textbook integer product, exactly
+    R = C = 128
+    bits, fs = full_precision_adc(R, C, 1, 2)
+    _, cg = both_configs(xo, xb, xbar_rows=R, xbar_cols=C, weight_bits=16, slice_bits=2, input_bits=8,
+                         stream_bits=1, adc_bits=bits, flags=xb.INPUT_SIGNED, adc_fs_fwd=fs, adc_fs_bwd=fs)
+    rng = np.random.default_rng(0)
+    M, K, N = 96, 700, 130
+    q = rng.integers(-65535, 65536, size=(K, N))
+    a = rng.integers(-255, 256, size=(M, K))
+    W, X = (q / 65535.0).astype(np.float32), (a / 255.0).astype(np.float32)
+    Yg = gpu_fwd(xb, cg, W, X, 1.0, 1.0, codes=False)
+    ref = ((a @ q).astype(np.float64) * (1.0 / (255.0 * 65535.0))).astype(np.float32)
+    assert np.array_equal(Yg, ref)
+
+
+NONIDEAL_CASES = [
+    # name, R, C, sb, slb, wb, signed, M, K, N, flags, var_sigma
+    ("aam_c1", 64, 64, 4, 2, 8, True, 64, 256, 256, "aam", 0.0),
+    ("aam_ragged", 128, 128, 1, 2, 16, False, 70, 300, 100, "aam", 0.0),
+    ("aam_var", 128, 128, 1, 2, 16, True, 45, 147, 64, "aam+var", 0.1),
+    ("var_only", 64, 128, 2, 2, 8, False, 33, 130, 200, "var", 0.05),
+    ("aam_256", 256, 256, 1, 2, 16, False, 40, 520, 48, "aam+var", 0.1),
+    ("profile", 128, 128, 4, 2, 8, True, 20, 200, 96, "profile", 0.0),
+]
+
+
+@pytest.mark.parametrize("name,R,C,sb,slb,wb,signed,M,K,N,ni,var_sigma", NONIDEAL_CASES)
+def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, var_sigma):
+    g = workloads.Gemm("t", K, N, M, signed, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=K + 3 * N)
+    flags = (xo.INPUT_SIGNED if signed else 0)
+    flags |= xo.WIRE_AAM if "aam" in ni else 0
+    flags |= xo.VARIATION if "var" in ni else 0
+    flags |= xo.WIRE_PROFILE if "profile" in ni else 0
+    profile = None
+    if "profile" in ni:
+        rng = np.random.default_rng(5)
+        profile = rng.uniform(0.0, 0.02, size=(wb // slb, 2, K, N)).astype(np.float32)
+    co, cg = both_configs(xo, xb, xbar_rows=R, xbar_cols=C, weight_bits=wb, slice_bits=slb, input_bits=8,
+                          stream_bits=sb, adc_bits=8, flags=flags, var_sigma=var_sigma, seed=11,
+                          adc_fs_fwd=workloads.adc_full_scale(R, sb, slb),
+                          adc_fs_bwd=workloads.adc_full_scale(C, sb, slb))
+    w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    Yo, codes_o = xo.fwd(co, W, X, w_max, x_scale, step=3, profile=profile, want_codes=True)
+    Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=3, profile=profile)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(Yg, Yo) <= 1e-3
+    dXo, codes_o = xo.bwd(co, W, dY, w_max, g_scale, step=3, profile=profile, want_codes=True)
+    dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=3, profile=profile)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(dXg, dXo) <= 1e-3
+    # a different step redraws the devices
+    if "var" in ni:
+        Y2 = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=4, codes=False)
+        assert not np.array_equal(Y2, Yg)
+
+
+UPDATE_CASES = [
+    # M, K, N, flags
+    (64, 256, 256, "ideal"), (64, 256, 256, "nl+noise"), (100, 147, 64, "nl+noise"), (3000, 70, 300, "nl"),
+    (17, 1, 1, "noise"), (515, 129, 130, "nl+noise"),
+]
+
+
+@pytest.mark.parametrize("M,K,N,kind", UPDATE_CASES)
+def test_update(xo, xb, M, K, N, kind):
+    g = workloads.Gemm("t", K, N, M, False, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=M + K)
+    flags = (xo.UPD_NL if "nl" in kind else 0) | (xo.UPD_NOISE if "noise" in kind else 0)
+    co, cg = both_configs(xo, xb, flags=flags, upd_nl_v=0.3, upd_noise_gamma=5.0, seed=21)
+    w_max = float(np.abs(W).max())
+    lr, gs = 0.01, 1.0 / w_max
+    Wo = xo.update(co, W, X, dY, w_max, gs, lr, step=7)
+    Wg = dev(W.copy())
+    xb.update(cg, Wg, dev(X), dev(dY), w_max, gs, lr, step=7)
+    torch.cuda.synchronize()
+    Wg = Wg.cpu().numpy()
+    # compare the applied changes, not the weights (the change is small against the weight)
+    assert rel_l2(Wg - W, Wo - W) <= 1e-3
+    assert np.abs(Wg - Wo).max() <= 1e-5 * w_max
+    assert np.abs(Wg).max() <= w_max
+
+
+def test_config1_fc256_step(xo, xb):
+    """First benchmark configuration, whole: one fwd + bwd + update step of a 256x256 layer."""
+    g = workloads.fc256_gemms(64)[0]
+    rng = np.random.default_rng(0)
+    W = rng.normal(0, 0.05, size=(g.K, g.N)).astype(np.float32)
+    X = rng.uniform(-1, 1, size=(g.M, g.K)).astype(np.float32)
+    dY = rng.normal(0, 0.01, size=(g.M, g.N)).astype(np.float32)
+    kw = workloads.config_kwargs("fc256")
+    kw["flags"] |= workloads.INPUT_SIGNED
+    co, cg = both_configs(xo, xb, **kw)
+    w_max, x_scale, g_scale = float(np.abs(W).max()), 1.0, float(np.abs(dY).max())
+    Yo, cf = xo.fwd(co, W, X, w_max, x_scale, want_codes=True)
+    dXo, cb = xo.bwd(co, W, dY, w_max, g_scale, want_codes=True)
+    Wo = xo.update(co, W, X, dY, w_max, 1.0 / w_max, 0.01, step=0)
+    Yg, cfg_ = gpu_fwd(xb, cg, W, X, w_max, x_scale)
+    dXg, cbg = gpu_bwd(xb, cg, W, dY, w_max, g_scale)
+    Wg = dev(W.copy())
+    xb.update(cg, Wg, dev(X), dev(dY), w_max, 1.0 / w_max, 0.01, step=0)
+    torch.cuda.synchronize()
+    check_codes(cfg_, cf)
+    check_codes(cbg, cb)
+    assert rel_l2(Yg, Yo) <= 1e-3 and rel_l2(dXg, dXo) <= 1e-3
+    assert rel_l2(Wg.cpu().numpy() - W, Wo - W) <= 1e-3
+    # sanity of the model itself: the emulated product tracks the exact one
+    assert rel_l2(Yo, X.astype(np.float64) @ W.astype(np.float64)) < 0.2
+
+
+def test_config2_mlp_ten_sgd_steps(xo, xb):
+    """Second configuration: 784-500-10 MLP, ReLU, softmax cross-entropy, 10 SGD steps (lr 0.01) with
+    emulated forward, backward and update; the digital peripherals (ReLU, loss) run in numpy.  The
+    oracle drives the trajectory; every emulated operation of every step is repeated by the GPU path
+    on the identical inputs and compared.  (Two free-running trajectories drift apart: one ADC code
+    that flips in the most significant slice moves an output by a visible amount, and the write
+    noise gamma sqrt(|delta|) amplifies that.)"""
+    gem = workloads.mlp_gemms(128)
+    rng = np.random.default_rng(1)
+    W = [(rng.standard_normal((g.K, g.N)) * math.sqrt(2.0 / g.K)).astype(np.float32) for g in gem]
+    W0 = [w.copy() for w in W]
+    X0 = rng.uniform(0, 1, size=(128, 784)).astype(np.float32)
+    labels = rng.integers(0, 10, size=128)
+    co, cg = both_configs(xo, xb, **workloads.config_kwargs("mlp"))
+    lr = 0.01
+    w_max = [2.0 * float(np.abs(w).max()) for w in W]       # head-room so that weights can move
+    losses, worst = [], 0.0
+    for step in range(10):
+        acts, x = [], X0
+        for l in range(2):
+            acts.append(x)
+            xs = max(float(np.abs(x).max()), 1e-12)
+            y = xo.fwd(co, W[l], x, w_max[l], xs, step=step)
+            yg = gpu_fwd(xb, cg, W[l], x, w_max[l], xs, step=step, codes=False)
+            worst = max(worst, rel_l2(yg, y))
+            x = np.maximum(y, 0) if l == 0 else y
+        z = x - x.max(axis=1, keepdims=True)
+        p = np.exp(z) / np.exp(z).sum(axis=1, keepdims=True)
+        losses.append(float(-np.log(p[np.arange(128), labels]).mean()))
+        p[np.arange(128), labels] -= 1
+        d = (p / 128).astype(np.float32)
+        for l in (1, 0):
+            gs = max(float(np.abs(d).max()), 1e-30)
+            if l > 0:
+                dx = xo.bwd(co, W[l], d, w_max[l], gs, step=step)
+                dxg = gpu_bwd(xb, cg, W[l], d, w_max[l], gs, step=step, codes=False)
+                worst = max(worst, rel_l2(dxg, dx))
+            Wn = xo.update(co, W[l], acts[l], d, w_max[l], 1.0 / w_max[l], lr, step=step)
+            Wd = dev(W[l])
+            xb.update(cg, Wd, dev(acts[l]), dev(d), w_max[l], 1.0 / w_max[l], lr, step=step)
+            worst = max(worst, rel_l2(Wd.cpu().numpy() - W[l], Wn - W[l]))
+            W[l] = Wn
+            if l > 0:
+                d = (dx * (acts[l] > 0)).astype(np.float32)
+    assert worst <= 1e-3, worst
+    assert all(not np.array_equal(W[l], W0[l]) for l in range(2))
+    assert np.isfinite(losses).all()
+
+
+def test_error_paths_on_device(xo, xb):
+    cg = xb.make_config()
+    W = torch.zeros((64, 64), device="cuda")
+    planes = xb.tile(cg, W, 1.0)
+    X = torch.zeros((4, 64), device="cuda")
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(xb.XbarError, match="workspace"):
+        xb.fwd(cg, planes, X, 64, 1.0, 1.0, ws=small)
+    with pytest.raises(xb.XbarError, match="workspace"):
+        xb.tile(cg, W, 1.0, planes=small)
+    lut = xb.make_config(flags=xb.DAC_LUT)
+    with pytest.raises(xb.XbarError, match="not supported"):
+        xb.fwd(lut, planes, X, 64, 1.0, 1.0)
+    torch.cuda.synchronize()

@@ -1,0 +1,109 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the header
+declares, validates parameter structs and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def xb():
+    from paper_2002_11151_amd import xbar
+    if not os.path.exists(xbar.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    xbar.lib()
+    return xbar
+
+
+def test_exports_every_declared_symbol(xb):
+    header = open(os.path.join(ROOT, "include", "xbar.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(xbar_[a-z_]+)\s*\(", header))
+    assert {"xbar_fwd", "xbar_bwd", "xbar_update", "xbar_tile", "xbar_config_validate", "xbar_planes_bytes",
+            "xbar_workspace_bytes", "xbar_strerror", "xbar_abi_version", "xbar_trace_next_vmm"} <= names
+    lib = C.CDLL(xb.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layout_matches(xb):
+    # the library checks struct_size itself: a good struct validates, a truncated one does not
+    c = xb.make_config()
+    assert xb.validate(c) == 0
+    c.struct_size -= 4
+    assert xb.validate(c) == -1
+    c = xb.make_config()
+    c.abi_version = 99
+    assert xb.validate(c) == -1
+
+
+@pytest.mark.parametrize("kw", [
+    dict(xbar_rows=60), dict(xbar_rows=8), dict(xbar_cols=512), dict(weight_bits=7, slice_bits=2),
+    dict(weight_bits=32, slice_bits=2), dict(slice_bits=5, weight_bits=10), dict(input_bits=9),
+    dict(input_bits=8, stream_bits=3), dict(stream_bits=0), dict(adc_bits=1), dict(adc_bits=17),
+    dict(flags=1 << 9), dict(flags=2 | 4), dict(r_min=0.0), dict(r_min=2e6), dict(r_max=float("nan")),
+    dict(r_row=-1.0), dict(var_sigma=float("inf")), dict(adc_fs_fwd=0.0), dict(adc_fs_bwd=-3.0),
+    dict(upd_noise_gamma=-1.0),
+])
+def test_validate_rejects(xb, kw):
+    assert xb.validate(xb.make_config(**kw)) == -1
+
+
+@pytest.mark.parametrize("kw", [
+    dict(), dict(xbar_rows=128, xbar_cols=256, weight_bits=16), dict(slice_bits=1, weight_bits=16),
+    dict(stream_bits=8), dict(slice_bits=4, weight_bits=16, adc_bits=16), dict(flags=127 & ~4),
+    dict(xbar_rows=16, xbar_cols=48),
+])
+def test_validate_accepts(xb, kw):
+    assert xb.validate(xb.make_config(**kw)) == 0
+
+
+def test_size_queries(xb):
+    c = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=xb.NI_WIRE_AAM)
+    ideal = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2)
+    # forward copy: ceil(K/128) tiles x ceil(N/32) patches x 8 slices x 2 terms x 8 KiB, same for backward
+    K, N = 147, 64
+    fwd = 2 * 2 * 8 * 2 * 8 * 1024
+    bwd = 1 * 5 * 8 * 2 * 8 * 1024
+    assert xb.planes_bytes(c, K, N) == fwd + bwd
+    assert xb.planes_bytes(ideal, K, N) == (fwd + bwd) // 2
+    assert xb.planes_bytes(c, 0, N) == 0 and xb.planes_bytes(c, K, -1) == 0
+    for op in (xb.OP_FWD, xb.OP_BWD, xb.OP_UPDATE):
+        small, big = xb.workspace_bytes(c, op, 64, K, N), xb.workspace_bytes(c, op, 6400, K, N)
+        assert 0 < small <= big
+        assert xb.workspace_bytes(c, op, 0, K, N) == 0
+    assert xb.workspace_bytes(c, 7, 64, K, N) == 0
+    assert xb.workspace_bytes(c, xb.OP_FWD, 1 << 20, 1 << 12, 8) == 0     # M*K reaches 2^31
+
+
+def test_argument_checks_precede_any_device_work(xb):
+    lib = xb.lib()
+    c = xb.make_config()
+    ok = C.c_void_p(0x1000)          # aligned, never dereferenced: every call below fails validation first
+    odd = C.c_void_p(0x1004)
+    big = 1 << 40
+    assert lib.xbar_tile(C.byref(c), ok, 0, 64, 1.0, 0, None, ok, big, None) == -2
+    assert lib.xbar_tile(C.byref(c), odd, 64, 64, 1.0, 0, None, ok, big, None) == -3
+    assert lib.xbar_tile(C.byref(c), ok, 64, 64, 1.0, 0, None, None, big, None) == -3
+    assert lib.xbar_tile(C.byref(c), ok, 64, 64, 0.0, 0, None, ok, big, None) == -1
+    assert lib.xbar_tile(C.byref(c), ok, 64, 64, 1.0, 0, None, ok, 16, None) == -4
+    prof = xb.make_config(flags=xb.NI_WIRE_PROFILE)
+    assert lib.xbar_tile(C.byref(prof), ok, 64, 64, 1.0, 0, None, ok, big, None) == -3
+    for fn in (lib.xbar_fwd, lib.xbar_bwd):
+        assert fn(C.byref(c), ok, ok, ok, -1, 64, 64, 1.0, 1.0, ok, big, None, None) == -2
+        assert fn(C.byref(c), ok, odd, ok, 4, 64, 64, 1.0, 1.0, ok, big, None, None) == -3
+        assert fn(C.byref(c), ok, ok, ok, 4, 64, 64, 1.0, float("nan"), ok, big, None, None) == -1
+        assert fn(C.byref(c), ok, ok, ok, 4, 64, 64, 1.0, 1.0, ok, 16, None, None) == -4
+        bad = xb.make_config(adc_bits=40)
+        assert fn(C.byref(bad), ok, ok, ok, 4, 64, 64, 1.0, 1.0, ok, big, None, None) == -1
+    assert lib.xbar_update(C.byref(c), ok, ok, ok, 4, 64, 0, 1.0, 1.0, 0.1, 0, ok, big, None) == -2
+    assert lib.xbar_update(C.byref(c), ok, ok, odd, 4, 64, 64, 1.0, 1.0, 0.1, 0, ok, big, None) == -3
+    assert lib.xbar_update(C.byref(c), ok, ok, ok, 4, 64, 64, 1.0, 1.0, 0.1, 0, ok, 16, None) == -4
+    assert lib.xbar_update(C.byref(c), ok, ok, ok, 4, 64, 64, -1.0, 1.0, 0.1, 0, ok, big, None) == -1
+    for code in range(-6, 1):
+        assert xb.strerror(code) and "unknown" not in xb.strerror(code)
+    assert "unknown" in xb.strerror(-99)
