@@ -274,33 +274,39 @@ struct VmmArgs {
   int16_t* codes;      // optional [P][S_in][S_w][T][M][Lout]
   int M, Lin, Lout, MP, OP, MB, T, P, VT;
   int S_w, S_in, slice_bits, stream_bits, ks, tile;
-  int vt_per_chunk, nchunk, SG;
+  int vt_per_chunk, nchunk, lds_kb;
   int total_wg, per_xcd;
   float gain;          // float(Q) / adc_fs
   float clamp_lo, clamp_hi;   // kMagic -+ Q
   uint32_t bias_per_vt;       // kMagicBits * sum of all shift weights, mod 2^32
 };
 
-template <int PM, int KSMAX, int TERMS, bool WIDE, bool CODES, bool FULL>
+// One staged slice group of one virtual tile: all streaming cycles x the staged slices.
+// NK = k-steps (of 16) of this tile, a compile-time constant so that the fragment registers are
+// addressed statically and no guard sits between the matrix instructions.
+template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES>
 __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* lds, const u32x4 (&raw)[PM][KSMAX],
-                                               int nk, int ns, int sg0, int p, int t, int lane, int mp0,
-                                               int op, uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
+                                               int ns, int sg0, int p, int t, int lane, int mp0, int op,
+                                               uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
   const uint32_t digit_mask = ((1u << a.stream_bits) - 1u) * 0x00010001u;
   const float vmagic = kMagic;
+  const float clamp_lo = a.clamp_lo, clamp_hi = a.clamp_hi;
+  constexpr int NF = TERMS * NK;          // fragments per slice: residual term first, then leading term
   for (int b = 0; b < a.S_in; ++b) {
     const int in_shift = a.stream_bits * b;
     const uint32_t mask = digit_mask << in_shift;
     // operand lanes hold digit * 2^(in_shift - 24); undo that power of two in the ADC gain
     const float gain_b = ldexpf(p ? -a.gain : a.gain, 24 - in_shift);
-    half8 ab[PM][KSMAX];
+    half8 ab[PM][NK];
 #pragma unroll
     for (int pm = 0; pm < PM; ++pm)
 #pragma unroll
-      for (int j = 0; j < KSMAX; ++j) {
+      for (int j = 0; j < NK; ++j) {
         u32x4 v = raw[pm][j] & mask;
         ab[pm][j] = __builtin_bit_cast(half8, v);
       }
-    for (int sl = 0; sl < ns; ++sl) {
+    const u32x4* bptr = lds + lane;
+    for (int sl = 0; sl < ns; ++sl, bptr += NF * 64) {
       const int s = sg0 + sl;
       const int sh = a.slice_bits * s + in_shift;
       float16v acc[PM];
@@ -308,29 +314,20 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
       for (int pm = 0; pm < PM; ++pm)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[pm][r] = 0.0f;
-      const u32x4* bbase = lds + (size_t)sl * TERMS * a.ks * 64 + lane;
       // Residual term first, in a pass of its own: while the accumulator is still small the matrix
       // core keeps all bits of the small products.  The leading term follows; it sits on a fixed
-      // binary grid, so its products add without rounding.
-      if (TERMS == 2) {
+      // binary grid, so its products add without rounding.  Fragments are fetched two ahead.
+      u32x4 f0 = bptr[0], f1 = NF > 1 ? bptr[64] : f0;
 #pragma unroll
-        for (int j = 0; j < KSMAX; ++j) {
-          if (FULL || j < nk) {
-            const half8 bl = __builtin_bit_cast(half8, bbase[(a.ks + j) * 64]);
+      for (int i = 0; i < NF; ++i) {
+        const u32x4 cur = f0;
+        f0 = f1;
+        if (i + 2 < NF) f1 = bptr[(i + 2) * 64];
+        const int j = i % NK;
+        const half8 bf = __builtin_bit_cast(half8, cur);
 #pragma unroll
-            for (int pm = 0; pm < PM; ++pm)
-              acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][j], bl, acc[pm], 0, 0, 0);
-          }
-        }
-      }
-#pragma unroll
-      for (int j = 0; j < KSMAX; ++j) {
-        if (FULL || j < nk) {
-          const half8 bh = __builtin_bit_cast(half8, bbase[j * 64]);
-#pragma unroll
-          for (int pm = 0; pm < PM; ++pm)
-            acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][j], bh, acc[pm], 0, 0, 0);
-        }
+        for (int pm = 0; pm < PM; ++pm)
+          acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][j], bf, acc[pm], 0, 0, 0);
       }
       // ADC: code = clamp(rne(I * gain)); shift-and-add in integers
 #pragma unroll
@@ -338,7 +335,7 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           float f = __builtin_fmaf(acc[pm][r], gain_b, vmagic);
-          f = __builtin_amdgcn_fmed3f(f, a.clamp_lo, a.clamp_hi);
+          f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
           const uint32_t bits = __builtin_bit_cast(uint32_t, f);
           if (WIDE) {
             y64[pm][r] += (long long)((int)(bits - kMagicBits)) << sh;
@@ -357,6 +354,39 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
         }
       }
     }
+  }
+}
+
+// One virtual tile (phase, contraction tile): load the raw magnitudes, then loop over slice groups:
+// stage the plane fragments of the group in LDS (compact: only the NK used k-steps), compute.
+template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES>
+__device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, int t, int lane, int mp0, int op,
+                                         uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
+  u32x4 raw[PM][KSMAX];
+#pragma unroll
+  for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+    for (int j = 0; j < NK; ++j) {
+      u32x4 v = {0, 0, 0, 0};
+      if (mp0 + pm < a.MP) v = a.A[((((size_t)p * a.MP + mp0 + pm) * a.T + t) * a.ks + j) * 64 + lane];
+      raw[pm][j] = v;
+    }
+  constexpr int NF = TERMS * NK;
+  const int sg = min(a.S_w, a.lds_kb / NF);            // slices per staged group
+  for (int sg0 = 0; sg0 < a.S_w; sg0 += sg) {
+    const int ns = min(sg, a.S_w - sg0);
+    const u32x4* src = a.B + (((size_t)t * a.OP + op) * a.S_w + sg0) * TERMS * a.ks * 64;
+    __syncthreads();                                   // everyone is done with the previous group
+    // global [slice][term][ks][64] -> LDS [slice][term * NK + j][64]; one 1 KiB fragment per wave pass
+    for (int f = threadIdx.x >> 6; f < ns * NF; f += blockDim.x >> 6) {
+      const int sl = f / NF, r = f - sl * NF;
+      const int term = r / NK, j = r - term * NK;
+      // LDS order within a slice: residual term (global term 1) first when there are two terms
+      const int gterm = TERMS == 2 ? 1 - term : 0;
+      lds[f * 64 + lane] = src[((sl * TERMS + gterm) * a.ks + j) * 64 + lane];
+    }
+    __syncthreads();
+    vmm_tile_group<PM, KSMAX, NK, TERMS, WIDE, CODES>(a, lds, raw, ns, sg0, p, t, lane, mp0, op, y, y64);
   }
 }
 
@@ -390,31 +420,17 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
     const int p = vt / a.T, t = vt - p * a.T;
     const int rows = min(a.tile, a.Lin - t * a.tile);
     const int nk = (rows + 15) >> 4;
-    u32x4 raw[PM][KSMAX];
-#pragma unroll
-    for (int pm = 0; pm < PM; ++pm)
-#pragma unroll
-      for (int j = 0; j < KSMAX; ++j) {
-        u32x4 v = {0, 0, 0, 0};
-        if (j < nk && mp0 + pm < a.MP)
-          v = a.A[((((size_t)p * a.MP + mp0 + pm) * a.T + t) * a.ks + j) * 64 + lane];
-        raw[pm][j] = v;
-      }
-    for (int sg0 = 0; sg0 < a.S_w; sg0 += a.SG) {
-      const int ns = min(a.SG, a.S_w - sg0);
-      __syncthreads();
-      const u32x4* src = a.B + (((size_t)t * a.OP + op) * a.S_w + sg0) * TERMS * a.ks * 64;
-      const int n16 = ns * TERMS * a.ks * 64;
-      for (int i = threadIdx.x; i < n16; i += blockDim.x) {
-        const int j = (i >> 6) % a.ks;
-        if (j < nk) lds[i] = src[i];
-      }
-      __syncthreads();
-      if (nk == KSMAX)
-        vmm_tile_group<PM, KSMAX, TERMS, WIDE, CODES, true>(a, lds, raw, nk, ns, sg0, p, t, lane, mp0, op, y, y64);
-      else
-        vmm_tile_group<PM, KSMAX, TERMS, WIDE, CODES, false>(a, lds, raw, nk, ns, sg0, p, t, lane, mp0, op, y, y64);
+#define XBAR_NK_CASE(n) \
+  case n:               \
+    if constexpr (n <= KSMAX) vmm_tile<PM, KSMAX, n, TERMS, WIDE, CODES>(a, lds, p, t, lane, mp0, op, y, y64); \
+    break;
+    switch (nk) {
+      XBAR_NK_CASE(1) XBAR_NK_CASE(2) XBAR_NK_CASE(3) XBAR_NK_CASE(4) XBAR_NK_CASE(5) XBAR_NK_CASE(6)
+      XBAR_NK_CASE(7) XBAR_NK_CASE(8) XBAR_NK_CASE(9) XBAR_NK_CASE(10) XBAR_NK_CASE(11) XBAR_NK_CASE(12)
+      XBAR_NK_CASE(13) XBAR_NK_CASE(14) XBAR_NK_CASE(15) XBAR_NK_CASE(16)
+      default: break;
     }
+#undef XBAR_NK_CASE
   }
   // partial result of this chunk
   const uint32_t bias = a.bias_per_vt * (uint32_t)(vt1 - vt0);
@@ -578,7 +594,7 @@ thread_local hipEvent_t g_trace_before = nullptr, g_trace_after = nullptr;
 
 struct VmmPlan {
   PlaneGeom g;
-  int Lin, Lout, MP, P, VT, vt_per_chunk, nchunk, wide, pm, nw, MB, SG;
+  int Lin, Lout, MP, P, VT, vt_per_chunk, nchunk, wide, pm, nw, MB, lds_kb;
   uint32_t bias_per_vt;
   size_t a_bytes, part_bytes, ws_bytes, lds_bytes;
 };
@@ -606,11 +622,11 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   int want_chunks = std::max(1, cdiv(2048, groups));      // enough blocks to fill 256 CUs several times
   int per = std::max(1, cdiv(p.VT, want_chunks));
   if (!p.wide) per = (int)std::min<unsigned long long>((unsigned long long)per, fit);
-  p.vt_per_chunk = per;
   p.nchunk = cdiv(p.VT, per);
+  p.vt_per_chunk = cdiv(p.VT, p.nchunk);                  // same number of chunks, evenly filled
   const int slice_kb = d.terms * p.g.ks;                   // KiB of operand per slice and output patch
-  p.SG = std::max(1, std::min(d.S_w, 64 / slice_kb));
-  p.lds_bytes = (size_t)p.SG * slice_kb * 1024;
+  p.lds_kb = std::max(slice_kb, std::min(d.S_w * slice_kb, 64));   // staged slice group, at most 64 KiB
+  p.lds_bytes = (size_t)p.lds_kb * 1024;
   p.a_bytes = align256((size_t)p.P * p.MP * p.g.T * p.g.ks * 1024);
   p.part_bytes = align256((size_t)p.nchunk * M * p.Lout * (p.wide ? 8 : 4));
   p.ws_bytes = p.a_bytes + p.part_bytes;
@@ -652,7 +668,6 @@ hipError_t launch_vmm_variant(const VmmArgs& a, const VmmPlan& p, bool codes, hi
 
 hipError_t launch_vmm(const VmmArgs& a, const VmmPlan& p, int terms, bool codes, hipStream_t st) {
   const int ks = p.g.ks;
-  if (ks <= 4) return terms == 2 ? launch_vmm_variant<2, 4, 2>(a, p, codes, st) : launch_vmm_variant<2, 4, 1>(a, p, codes, st);
   if (ks <= 8) return terms == 2 ? launch_vmm_variant<2, 8, 2>(a, p, codes, st) : launch_vmm_variant<2, 8, 1>(a, p, codes, st);
   return terms == 2 ? launch_vmm_variant<1, 16, 2>(a, p, codes, st) : launch_vmm_variant<1, 16, 1>(a, p, codes, st);
 }
@@ -690,7 +705,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.codes = codes;
   a.M = M; a.Lin = p.Lin; a.Lout = p.Lout; a.MP = p.MP; a.OP = p.g.OP; a.MB = p.MB; a.T = p.g.T; a.P = p.P;
   a.VT = p.VT; a.S_w = d.S_w; a.S_in = d.S_in; a.slice_bits = cfg->slice_bits; a.stream_bits = cfg->stream_bits;
-  a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.SG = p.SG;
+  a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.lds_kb = p.lds_kb;
   a.total_wg = p.nchunk * p.g.OP * p.MB;
   a.per_xcd = cdiv(a.total_wg, 8);
   a.gain = (float)d.q_adc / adc_fs;
