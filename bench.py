@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
+    ap.add_argument("--only", default=None, help="comma-separated layer names: run just these (profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one); use --gpus 1", file=sys.stderr)
@@ -77,6 +78,9 @@ def main():
     batch = args.batch or default_batch
     gemms = workloads.GEMMS[args.workload](batch) if args.workload in ("fc256", "mlp") else \
         workloads.GEMMS[args.workload](batch, merge=True)
+    if args.only:
+        gemms = [g for g in gemms if g.name in args.only.split(",")]
+        assert gemms, "no such layer"
     kw = workloads.config_kwargs(args.workload)
     if args.ideal:
         kw["flags"] &= ~(workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE)

@@ -35,10 +35,12 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr uint32_t kMagicBits = 0x4B400000u;  // bits of 1.5 * 2^23: adding it rounds to an integer (RNE)
 constexpr float kMagic = 12582912.0f;
 constexpr int kStreamVariation = 1, kStreamWrite = 2;
+constexpr bool kBarrierPerMfma = false;   // scheduling fence after every MFMA (true) or every fragment (false)
 
 // ---------------------------------------------------------------------------------------------
 // host-side geometry shared by the entry points
@@ -231,7 +233,7 @@ __global__ __launch_bounds__(256) void tile_planes_kernel(TileArgs a) {
 // ---------------------------------------------------------------------------------------------
 struct QuantArgs {
   const float* X;
-  uint16_t* A;       // [phase][MP][T][ks][64][8]
+  uint8_t* A;        // [phase][MP][T][ks][64 lanes][8 bytes]
   int M, L, MP, T, ks, tile, P, input_bits;
   float scale;
   long long n_threads;
@@ -249,17 +251,17 @@ __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
   const int l0 = t * a.tile + j * 16 + (lane >> 5) * 8;
   const double qa = (double)((1u << a.input_bits) - 1);
   const double lo = a.P == 2 ? -1.0 : 0.0;
-  union { u32x4 v; uint16_t h[8]; } pos, neg;
+  union { u32x2 v; uint8_t h[8]; } pos, neg;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const int l = l0 + e;
     int q = 0;
     if (m < a.M && l < a.L && l < (t + 1) * a.tile)
       q = (int)::rint(clampd((double)a.X[(size_t)m * a.L + l] / (double)a.scale, lo, 1.0) * qa);
-    pos.h[e] = (uint16_t)(q > 0 ? q : 0);
-    neg.h[e] = (uint16_t)(q < 0 ? -q : 0);
+    pos.h[e] = (uint8_t)(q > 0 ? q : 0);
+    neg.h[e] = (uint8_t)(q < 0 ? -q : 0);
   }
-  u32x4* out = reinterpret_cast<u32x4*>(a.A);
+  u32x2* out = reinterpret_cast<u32x2*>(a.A);
   out[(size_t)blk * 64 + lane] = pos.v;
   if (a.P == 2) out[((size_t)a.MP * a.T * a.ks + (size_t)blk) * 64 + lane] = neg.v;
 }
@@ -268,7 +270,7 @@ __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
 // crossbar-tile contraction + ADC + shift-and-add (Sec. IV-B), forward and backward
 // ---------------------------------------------------------------------------------------------
 struct VmmArgs {
-  const u32x4* A;      // quantised input fragments
+  const u32x2* A;      // quantised input fragments, 8 magnitudes (bytes) per lane
   const u32x4* B;      // plane fragments of this direction
   void* part;          // [nchunk][M][Lout] int32 (narrow) or int64 (wide)
   int16_t* codes;      // optional [P][S_in][S_w][T][M][Lout]
@@ -281,55 +283,181 @@ struct VmmArgs {
   uint32_t bias_per_vt;       // kMagicBits * sum of all shift weights, mod 2^32
 };
 
-// One staged slice group of one virtual tile: all streaming cycles x the staged slices.
-// NK = k-steps (of 16) of this tile, a compile-time constant so that the fragment registers are
-// addressed statically and no guard sits between the matrix instructions.
-template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES>
-__device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* lds, const u32x4 (&raw)[PM][KSMAX],
-                                               int ns, int sg0, int p, int t, int lane, int mp0, int op,
-                                               uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
-  const uint32_t digit_mask = ((1u << a.stream_bits) - 1u) * 0x00010001u;
+// Asynchronous 16-byte-per-lane copy global -> LDS: `lds_wave_base` is the same for the whole wave.
+__device__ __forceinline__ void copy16_global_to_lds(const u32x4* g, u32x4* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// A operand of one streaming cycle from the raw magnitudes: mask the digit, then spread the bytes
+// into 16-bit lanes (2 AND + 4 byte permutes per 16-byte fragment).
+__device__ __forceinline__ half8 digit_fragment(const u32x2 raw, uint32_t mask8) {
+  const uint32_t m0 = raw.x & mask8, m1 = raw.y & mask8;
+  u32x4 v;
+  v.x = __builtin_amdgcn_perm(0u, m0, 0x0C010C00u);
+  v.y = __builtin_amdgcn_perm(0u, m0, 0x0C030C02u);
+  v.z = __builtin_amdgcn_perm(0u, m1, 0x0C010C00u);
+  v.w = __builtin_amdgcn_perm(0u, m1, 0x0C030C02u);
+  return __builtin_bit_cast(half8, v);
+}
+
+// Contraction of one (slice, cycle): residual-term pass first (while the accumulator is small the
+// matrix core keeps all bits of the small products), then the leading term, which sits on a fixed
+// binary grid so that its products add without rounding.  Fragments are fetched two ahead.
+template <int PM, int NK, int TERMS>
+__device__ __forceinline__ void vmm_contract(const half8 (&ab)[PM][NK], const u32x4* bptr, float16v (&acc)[PM]) {
+  constexpr int NF = TERMS * NK;
+  u32x4 f0 = bptr[0], f1 = NF > 1 ? bptr[64] : f0;
+#pragma unroll
+  for (int i = 0; i < NF; ++i) {
+    const u32x4 cur = f0;
+    f0 = f1;
+    if (i + 2 < NF) f1 = bptr[(i + 2) * 64];
+    const half8 bf = __builtin_bit_cast(half8, cur);
+#pragma unroll
+    for (int pm = 0; pm < PM; ++pm) {
+      if (i == 0) {
+        const float16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][0], bf, zero, 0, 0, 0);
+      } else {
+        acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][i % NK], bf, acc[pm], 0, 0, 0);
+      }
+    }
+  }
+}
+
+// ADC + shift-and-add of one (slice, cycle): code = clamp(rne(I * gain)), y += code << sh.
+// Three VALU operations per conversion: fma with 1.5 * 2^23 (rounds to nearest even in the mantissa),
+// med3 (saturation), shift-add of the raw float bits (the accumulated constant is removed later).
+template <int PM>
+__device__ __forceinline__ void vmm_adc_narrow(const float16v (&acc)[PM], float gain_b, float clamp_lo, float clamp_hi,
+                                               int sh, uint32_t (&y)[PM][16]) {
   const float vmagic = kMagic;
+#pragma unroll
+  for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float f = __builtin_fmaf(acc[pm][r], gain_b, vmagic);
+      f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
+      y[pm][r] = (__builtin_bit_cast(uint32_t, f) << sh) + y[pm][r];
+    }
+}
+
+// Contraction of one (slice, cycle) with the ADC / shift-and-add of the PREVIOUS (slice, cycle)
+// woven in between the matrix instructions: after the MFMAs of each fragment a fixed share of the
+// previous result is converted.  On gfx950 up to ~5 VALU operations issued between two MFMAs of the
+// same wave run in the shadow of the matrix pipe, whereas VALU work that sits in a block of its own
+// does not overlap reliably; scheduling barriers keep the compiler from regrouping the pattern.
+template <int PM, int NK, int TERMS, bool DO_ADC>
+__device__ __forceinline__ void vmm_contract_adc(const half8 (&ab)[PM][NK], const u32x4* bptr, float16v (&acc)[PM],
+                                                 const float16v (&old)[PM], float gain_old, float clamp_lo,
+                                                 float clamp_hi, int sh_old, uint32_t (&y)[PM][16]) {
+  constexpr int NF = TERMS * NK;
+  constexpr int NV = 16 * PM;                       // conversions of the previous result
+  const float vmagic = kMagic;
+  constexpr int PF = NF < 2 ? NF : 2;               // fragments in flight from LDS
+  u32x4 fr[PF];
+#pragma unroll
+  for (int i = 0; i < PF; ++i) fr[i] = bptr[i * 64];
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < NF; ++i) {
+    const u32x4 cur = fr[i % PF];
+    if (i + PF < NF) fr[i % PF] = bptr[(i + PF) * 64];
+    const half8 bf = __builtin_bit_cast(half8, cur);
+#pragma unroll
+    for (int pm = 0; pm < PM; ++pm) {
+      if (i == 0) {
+        const float16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][0], bf, zero, 0, 0, 0);
+      } else {
+        acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][i % NK], bf, acc[pm], 0, 0, 0);
+      }
+      // the share of the previous result that rides in the shadow of this matrix instruction
+      if (DO_ADC) {
+        constexpr int NQ = NF * PM;
+        const int q = i * PM + pm;
+#pragma unroll
+        for (int v = (q * NV) / NQ; v < ((q + 1) * NV) / NQ; ++v) {
+          const int vp = v / 16, r = v % 16;
+          float f = __builtin_fmaf(old[vp][r], gain_old, vmagic);
+          f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
+          y[vp][r] = (__builtin_bit_cast(uint32_t, f) << sh_old) + y[vp][r];
+        }
+      }
+      if (kBarrierPerMfma) __builtin_amdgcn_sched_barrier(0);
+    }
+    if (!kBarrierPerMfma) __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Software-pipelined slice group (fast path: 32-bit accumulators, no code tap, even slice count).
+template <int PM, int KSMAX, int NK, int TERMS>
+__device__ __forceinline__ void vmm_tile_group_pipelined(const VmmArgs& a, const u32x4* lds,
+                                                         const u32x2 (&raw)[PM][KSMAX], int ns, int sg0, int p,
+                                                         int lane, uint32_t (&y)[PM][16]) {
+  constexpr int NF = TERMS * NK;
+  const uint32_t digit_mask8 = ((1u << a.stream_bits) - 1u) * 0x01010101u;
   const float clamp_lo = a.clamp_lo, clamp_hi = a.clamp_hi;
-  constexpr int NF = TERMS * NK;          // fragments per slice: residual term first, then leading term
+  const float gain_p = p ? -a.gain : a.gain;
+  const u32x4* bbase = lds + lane;
+  half8 ab[PM][NK];
+  float16v acc0[PM], acc1[PM];
+  int sh_prev = 0;
+  float gain_prev = 0.f;
   for (int b = 0; b < a.S_in; ++b) {
     const int in_shift = a.stream_bits * b;
-    const uint32_t mask = digit_mask << in_shift;
+    const uint32_t mask8 = digit_mask8 << in_shift;
     // operand lanes hold digit * 2^(in_shift - 24); undo that power of two in the ADC gain
+    const float gain_b = ldexpf(gain_p, 24 - in_shift);
+#pragma unroll
+    for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+      for (int j = 0; j < NK; ++j) ab[pm][j] = digit_fragment(raw[pm][j], mask8);
+    for (int sl = 0; sl < ns; sl += 2) {
+      const int sh0 = a.slice_bits * (sg0 + sl) + in_shift;
+      const int sh1 = sh0 + a.slice_bits;
+      // even slice -> acc0, while the ADC of the previous odd slice (acc1) runs
+      if (b == 0 && sl == 0)
+        vmm_contract_adc<PM, NK, TERMS, false>(ab, bbase + (size_t)sl * NF * 64, acc0, acc1, gain_prev, clamp_lo,
+                                               clamp_hi, sh_prev, y);
+      else
+        vmm_contract_adc<PM, NK, TERMS, true>(ab, bbase + (size_t)sl * NF * 64, acc0, acc1, gain_prev, clamp_lo,
+                                              clamp_hi, sh_prev, y);
+      // odd slice -> acc1, while the ADC of the even slice (acc0) runs
+      vmm_contract_adc<PM, NK, TERMS, true>(ab, bbase + (size_t)(sl + 1) * NF * 64, acc1, acc0, gain_b, clamp_lo,
+                                            clamp_hi, sh0, y);
+      sh_prev = sh1;
+      gain_prev = gain_b;
+    }
+  }
+  vmm_adc_narrow<PM>(acc1, gain_prev, clamp_lo, clamp_hi, sh_prev, y);   // drain
+}
+
+// General slice group (64-bit accumulators and / or ADC code tap, any slice count): same arithmetic,
+// no software pipelining.
+template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES>
+__device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* lds, const u32x2 (&raw)[PM][KSMAX],
+                                               int ns, int sg0, int p, int t, int lane, int mp0, int op,
+                                               uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
+  constexpr int NF = TERMS * NK;
+  const uint32_t digit_mask8 = ((1u << a.stream_bits) - 1u) * 0x01010101u;
+  const float vmagic = kMagic;
+  const float clamp_lo = a.clamp_lo, clamp_hi = a.clamp_hi;
+  for (int b = 0; b < a.S_in; ++b) {
+    const int in_shift = a.stream_bits * b;
+    const uint32_t mask8 = digit_mask8 << in_shift;
     const float gain_b = ldexpf(p ? -a.gain : a.gain, 24 - in_shift);
     half8 ab[PM][NK];
 #pragma unroll
     for (int pm = 0; pm < PM; ++pm)
 #pragma unroll
-      for (int j = 0; j < NK; ++j) {
-        u32x4 v = raw[pm][j] & mask;
-        ab[pm][j] = __builtin_bit_cast(half8, v);
-      }
-    const u32x4* bptr = lds + lane;
-    for (int sl = 0; sl < ns; ++sl, bptr += NF * 64) {
+      for (int j = 0; j < NK; ++j) ab[pm][j] = digit_fragment(raw[pm][j], mask8);
+    for (int sl = 0; sl < ns; ++sl) {
       const int s = sg0 + sl;
       const int sh = a.slice_bits * s + in_shift;
       float16v acc[PM];
-#pragma unroll
-      for (int pm = 0; pm < PM; ++pm)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[pm][r] = 0.0f;
-      // Residual term first, in a pass of its own: while the accumulator is still small the matrix
-      // core keeps all bits of the small products.  The leading term follows; it sits on a fixed
-      // binary grid, so its products add without rounding.  Fragments are fetched two ahead.
-      u32x4 f0 = bptr[0], f1 = NF > 1 ? bptr[64] : f0;
-#pragma unroll
-      for (int i = 0; i < NF; ++i) {
-        const u32x4 cur = f0;
-        f0 = f1;
-        if (i + 2 < NF) f1 = bptr[(i + 2) * 64];
-        const int j = i % NK;
-        const half8 bf = __builtin_bit_cast(half8, cur);
-#pragma unroll
-        for (int pm = 0; pm < PM; ++pm)
-          acc[pm] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ab[pm][j], bf, acc[pm], 0, 0, 0);
-      }
-      // ADC: code = clamp(rne(I * gain)); shift-and-add in integers
+      vmm_contract<PM, NK, TERMS>(ab, lds + lane + (size_t)sl * NF * 64, acc);
 #pragma unroll
       for (int pm = 0; pm < PM; ++pm) {
 #pragma unroll
@@ -362,12 +490,12 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
 template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES>
 __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, int t, int lane, int mp0, int op,
                                          uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
-  u32x4 raw[PM][KSMAX];
+  u32x2 raw[PM][KSMAX];
 #pragma unroll
   for (int pm = 0; pm < PM; ++pm)
 #pragma unroll
     for (int j = 0; j < NK; ++j) {
-      u32x4 v = {0, 0, 0, 0};
+      u32x2 v = {0, 0};
       if (mp0 + pm < a.MP) v = a.A[((((size_t)p * a.MP + mp0 + pm) * a.T + t) * a.ks + j) * 64 + lane];
       raw[pm][j] = v;
     }
@@ -378,15 +506,23 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
     const u32x4* src = a.B + (((size_t)t * a.OP + op) * a.S_w + sg0) * TERMS * a.ks * 64;
     __syncthreads();                                   // everyone is done with the previous group
     // global [slice][term][ks][64] -> LDS [slice][term * NK + j][64]; one 1 KiB fragment per wave pass
-    for (int f = threadIdx.x >> 6; f < ns * NF; f += blockDim.x >> 6) {
+    // Each wave copies whole 1 KiB fragments straight from global memory into LDS (no registers in
+    // between, all copies of a wave in flight at once): lane l of the wave supplies the address of
+    // its 16 bytes, the hardware writes them at fragment base + 16 l.
+    const int nwv = blockDim.x >> 6, nfr = ns * NF;
+    for (int f = threadIdx.x >> 6; f < nfr; f += nwv) {
       const int sl = f / NF, r = f - sl * NF;
       const int term = r / NK, j = r - term * NK;
       // LDS order within a slice: residual term (global term 1) first when there are two terms
       const int gterm = TERMS == 2 ? 1 - term : 0;
-      lds[f * 64 + lane] = src[((sl * TERMS + gterm) * a.ks + j) * 64 + lane];
+      copy16_global_to_lds(src + ((sl * TERMS + gterm) * a.ks + j) * 64 + lane, lds + f * 64);
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    vmm_tile_group<PM, KSMAX, NK, TERMS, WIDE, CODES>(a, lds, raw, ns, sg0, p, t, lane, mp0, op, y, y64);
+    if (!WIDE && !CODES && (ns & 1) == 0)
+      vmm_tile_group_pipelined<PM, KSMAX, NK, TERMS>(a, lds, raw, ns, sg0, p, lane, y);
+    else
+      vmm_tile_group<PM, KSMAX, NK, TERMS, WIDE, CODES>(a, lds, raw, ns, sg0, p, t, lane, mp0, op, y, y64);
   }
 }
 
@@ -627,7 +763,7 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   const int slice_kb = d.terms * p.g.ks;                   // KiB of operand per slice and output patch
   p.lds_kb = std::max(slice_kb, std::min(d.S_w * slice_kb, 64));   // staged slice group, at most 64 KiB
   p.lds_bytes = (size_t)p.lds_kb * 1024;
-  p.a_bytes = align256((size_t)p.P * p.MP * p.g.T * p.g.ks * 1024);
+  p.a_bytes = align256((size_t)p.P * p.MP * p.g.T * p.g.ks * 512);
   p.part_bytes = align256((size_t)p.nchunk * M * p.Lout * (p.wide ? 8 : 4));
   p.ws_bytes = p.a_bytes + p.part_bytes;
   return p;
@@ -689,7 +825,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
 
   QuantArgs qa;
   qa.X = in;
-  qa.A = reinterpret_cast<uint16_t*>(ws);
+  qa.A = reinterpret_cast<uint8_t*>(ws);
   qa.M = M; qa.L = p.Lin; qa.MP = p.MP; qa.T = p.g.T; qa.ks = p.g.ks; qa.tile = p.g.tile; qa.P = p.P;
   qa.input_bits = cfg->input_bits;
   qa.scale = in_scale;
@@ -699,7 +835,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
 
   const PlaneGeom gf = plane_geom(cfg, d, K, N, false);
   VmmArgs a;
-  a.A = reinterpret_cast<const u32x4*>(ws);
+  a.A = reinterpret_cast<const u32x2*>(ws);
   a.B = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(planes) + (transposed ? align256(gf.bytes) : 0));
   a.part = reinterpret_cast<char*>(ws) + p.a_bytes;
   a.codes = codes;
