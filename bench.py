@@ -57,6 +57,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
+    ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA sustained-rate probe")
     ap.add_argument("--only", default=None, help="comma-separated layer names: run just these (profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -159,6 +160,19 @@ def main():
                 "operand_terms": terms, "issued_frac": round(terms * achieved / FP16_MFMA_PEAK_TFLOPS, 4),
                 "launches": len(vmm_records), "avg_launch_ms": round(vmm_ms / max(1, len(vmm_records)), 4),
                 "kernel_time_share": round(vmm_ms / (elapsed * 1e3), 4)}
+    # sustained rate of the bare matrix instruction (power limited), as context for the fraction above
+    if not args.no_mfma_probe:
+        probe = {}
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for mode, key in ((0, "dense_random_operands"), (1, "emulation_like_operands")):
+            xb.probe_mfma_rate(mode, 2000, ws)
+            torch.cuda.synchronize()
+            e0.record()
+            flops = xb.probe_mfma_rate(mode, 100000, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            probe[key] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+        roofline["sustained_mfma_tflops_bare_instruction"] = probe
     if args.per_layer:
         for (li, kind), (ms, fl, n) in sorted(per_layer.items()):
             g = layers[li]["g"]

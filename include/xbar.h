@@ -8,7 +8,7 @@
  * in (NULL = the default stream) and returns.  Scratch memory comes from the caller (`ws`); its
  * contents are undefined after a call and two calls that share one workspace must be ordered on one
  * stream.  Return value: XBAR_OK or a negative XBAR_E* code; no exception crosses this boundary and
- * the library keeps no state between calls.
+ * the library keeps no state between calls (the one-shot instrumentation hook at the end aside).
  *
  * A layer is the GEMM  Y[M x N] = X[M x K] . W[K x N]:  K = fan-in = crossbar rows, N = fan-out =
  * crossbar columns, M = batch (times output positions after im2col).  The weight matrix is cut into
@@ -149,6 +149,17 @@ int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* d
  * scaling after it) and `after` right behind it.  Both are hipEvent_t handles owned by the caller.
  */
 void xbar_trace_next_vmm(void* before, void* after);
+
+/*
+ * Instrumentation for the benchmark (no part of the method): enqueues a kernel that does nothing but
+ * dependent-chain fp16 matrix instructions (the instruction the contraction uses, v_mfma_f32_32x32x16_f16)
+ * on register-resident operands, 2 waves per SIMD on every CU, so that the caller can time the matrix
+ * rate the chip sustains (it is power limited well below the nominal peak once operands toggle).
+ *   mode 0: both operands pseudo-random fp16;  mode 1: A operand = sparse single-bit patterns as in
+ *   the emulation, B pseudo-random.   iters: loop count; the kernel issues 16 * iters MFMAs per wave
+ *   on 2048 waves, i.e. 2 * 16 * iters * 2048 * 16384 flops.   out: 2 MiB of device scratch.
+ */
+int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -169,7 +169,7 @@ __device__ __forceinline__ double plane_value(const TileArgs& a, NormalStream& r
 }
 
 // One thread produces the 8 consecutive contraction-index entries of one output column that make up
-// one 16-byte operand chunk, for every slice and term.
+// one 16-byte operand chunk of one slice (blockIdx.y), for every term.
 //   TRANSPOSED = false: contraction index k (rows), output index n;  = true: contraction n, output k.
 template <bool TRANSPOSED>
 __global__ __launch_bounds__(256) void tile_planes_kernel(TileArgs a) {
@@ -207,25 +207,24 @@ __global__ __launch_bounds__(256) void tile_planes_kernel(TileArgs a) {
     }
   }
   const size_t blk0 = ((size_t)t * a.OP + op) * a.S_w;
-  for (int s = 0; s < a.S_w; ++s) {
-    union { u32x4 v; _Float16 h[8]; } hi, lo;
+  const int s = blockIdx.y;                         // one slice per grid row: short serial chains
+  union { u32x4 v; _Float16 h[8]; } hi, lo;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int c = c0 + e;
-      double u = 0.0;
-      if (c < Lc && o < Lo) {
-        const int k = TRANSPOSED ? o : c, n = TRANSPOSED ? c : o;
-        u = plane_value(a, rng, sign[e], (int)((mag[e] >> (a.slice_bits * s)) & dmask), s, k, n);
-      }
-      // leading term on the grid 2^-hi_frac (coarser where fp16 cannot hold it), residual in fp16
-      const _Float16 h = a.terms == 2 ? (_Float16)(::rint(u * a.hi_scale) * a.hi_inv_scale) : (_Float16)u;
-      hi.h[e] = h;
-      lo.h[e] = (_Float16)(u - (double)h);
+  for (int e = 0; e < 8; ++e) {
+    const int c = c0 + e;
+    double u = 0.0;
+    if (c < Lc && o < Lo) {
+      const int k = TRANSPOSED ? o : c, n = TRANSPOSED ? c : o;
+      u = plane_value(a, rng, sign[e], (int)((mag[e] >> (a.slice_bits * s)) & dmask), s, k, n);
     }
-    const size_t chunk = ((blk0 + s) * a.terms * a.ks + j) * 64 + lane;   // in 16-byte units
-    reinterpret_cast<u32x4*>(a.planes)[chunk] = hi.v;
-    if (a.terms == 2) reinterpret_cast<u32x4*>(a.planes)[chunk + (size_t)a.ks * 64] = lo.v;
+    // leading term on the grid 2^-hi_frac (coarser where fp16 cannot hold it), residual in fp16
+    const _Float16 h = a.terms == 2 ? (_Float16)(::rint(u * a.hi_scale) * a.hi_inv_scale) : (_Float16)u;
+    hi.h[e] = h;
+    lo.h[e] = (_Float16)(u - (double)h);
   }
+  const size_t chunk = ((blk0 + s) * a.terms * a.ks + j) * 64 + lane;   // in 16-byte units
+  reinterpret_cast<u32x4*>(a.planes)[chunk] = hi.v;
+  if (a.terms == 2) reinterpret_cast<u32x4*>(a.planes)[chunk + (size_t)a.ks * 64] = lo.v;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -242,28 +241,51 @@ struct QuantArgs {
 __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
   const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (tid >= a.n_threads) return;
+  // one wave = 32 rows x one pair of k-steps (32 consecutive inputs of a row = one 128-byte line)
   const int lane = (int)(tid & 63);
-  const long long blk = tid >> 6;                  // (mp, t, j)
-  const int j = (int)(blk % a.ks);
-  const int t = (int)((blk / a.ks) % a.T);
-  const int mp = (int)(blk / ((long long)a.ks * a.T));
+  const long long wv = tid >> 6;                    // (mp, t, jp)
+  const int npair = (a.ks + 1) >> 1;
+  const int jp = (int)(wv % npair);
+  const int t = (int)((wv / npair) % a.T);
+  const int mp = (int)(wv / ((long long)npair * a.T));
   const int m = mp * 32 + (lane & 31);
-  const int l0 = t * a.tile + j * 16 + (lane >> 5) * 8;
   const double qa = (double)((1u << a.input_bits) - 1);
   const double lo = a.P == 2 ? -1.0 : 0.0;
-  union { u32x2 v; uint8_t h[8]; } pos, neg;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int l = l0 + e;
-    int q = 0;
-    if (m < a.M && l < a.L && l < (t + 1) * a.tile)
-      q = (int)::rint(clampd((double)a.X[(size_t)m * a.L + l] / (double)a.scale, lo, 1.0) * qa);
-    pos.h[e] = (uint8_t)(q > 0 ? q : 0);
-    neg.h[e] = (uint8_t)(q < 0 ? -q : 0);
-  }
+  const double scale = (double)a.scale;
   u32x2* out = reinterpret_cast<u32x2*>(a.A);
-  out[(size_t)blk * 64 + lane] = pos.v;
-  if (a.P == 2) out[((size_t)a.MP * a.T * a.ks + (size_t)blk) * 64 + lane] = neg.v;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int j = 2 * jp + h;
+    if (j >= a.ks) break;
+    const int l0 = t * a.tile + j * 16 + (lane >> 5) * 8;
+    const int lend = min(a.L, (t + 1) * a.tile);
+    float x[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = 0.0f;
+    if (m < a.M) {
+      const float* row = a.X + (size_t)m * a.L;
+      if ((a.L & 3) == 0 && l0 + 8 <= lend) {
+        const float4 v0 = *reinterpret_cast<const float4*>(row + l0);
+        const float4 v1 = *reinterpret_cast<const float4*>(row + l0 + 4);
+        x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
+        x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if (l0 + e < lend) x[e] = row[l0 + e];
+      }
+    }
+    union { u32x2 v; uint8_t b[8]; } pos, neg;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int q = (int)::rint(clampd((double)x[e] / scale, lo, 1.0) * qa);
+      pos.b[e] = (uint8_t)(q > 0 ? q : 0);
+      neg.b[e] = (uint8_t)(q < 0 ? -q : 0);
+    }
+    const size_t blk = ((size_t)mp * a.T + t) * a.ks + j;
+    out[blk * 64 + lane] = pos.v;
+    if (a.P == 2) out[((size_t)a.MP * a.T * a.ks + blk) * 64 + lane] = neg.v;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -281,6 +303,8 @@ struct VmmArgs {
   float gain;          // float(Q) / adc_fs
   float clamp_lo, clamp_hi;   // kMagic -+ Q
   uint32_t bias_per_vt;       // kMagicBits * sum of all shift weights, mod 2^32
+  float* out;                 // final output, written directly when there is a single chunk
+  double scale;               // lsb * in_scale * w_max / (Qa * Qw)
 };
 
 // Asynchronous 16-byte-per-lane copy global -> LDS: `lds_wave_base` is the same for the whole wave.
@@ -578,8 +602,14 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
       const int o = op * 32 + (lane & 31);
       if (m < a.M && o < a.Lout && mp0 + pm < a.MP) {
         const size_t idx = ((size_t)chunk * a.M + m) * a.Lout + o;
-        if (WIDE) reinterpret_cast<long long*>(a.part)[idx] = y64[pm][r];
-        else reinterpret_cast<int32_t*>(a.part)[idx] = (int32_t)(y[pm][r] - bias);
+        if (a.nchunk == 1) {   // nothing to add up across chunks: scale and store the result itself
+          const long long sum = WIDE ? y64[pm][r] : (long long)(int32_t)(y[pm][r] - bias);
+          a.out[idx] = (float)((double)sum * a.scale);
+        } else if (WIDE) {
+          reinterpret_cast<long long*>(a.part)[idx] = y64[pm][r];
+        } else {
+          reinterpret_cast<int32_t*>(a.part)[idx] = (int32_t)(y[pm][r] - bias);
+        }
       }
     }
 }
@@ -713,6 +743,36 @@ __global__ __launch_bounds__(256) void update_write_kernel(WriteArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// instrumentation: sustained matrix-instruction rate
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters, int mode) {
+  uint32_t x = threadIdx.x * 2654435761u + 12345u;
+  union { half8 h; uint32_t u[4]; } ua, ub;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+    // two fp16 values in [-4, 4) per word; sign, exponent and mantissa bits all toggle
+    ua.u[i] = mode == 1 ? (x & 0x00010001u) : ((x & 0x83ff83ffu) | 0x3c003c00u);
+    x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+    ub.u[i] = (x & 0x83ff83ffu) | 0x3c003c00u;
+  }
+  float16v c0, c1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) c0[r] = c1[r] = 0.0f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      c0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ua.h, ub.h, c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ua.h, ub.h, c1, 0, 0, 0);
+    }
+  }
+  float s = 0.0f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s += c0[r] + c1[r];
+  out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host dispatch
 // ---------------------------------------------------------------------------------------------
 inline bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -829,7 +889,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   qa.M = M; qa.L = p.Lin; qa.MP = p.MP; qa.T = p.g.T; qa.ks = p.g.ks; qa.tile = p.g.tile; qa.P = p.P;
   qa.input_bits = cfg->input_bits;
   qa.scale = in_scale;
-  qa.n_threads = (long long)p.MP * p.g.T * p.g.ks * 64;
+  qa.n_threads = (long long)p.MP * p.g.T * ((p.g.ks + 1) / 2) * 64;
   hipLaunchKernelGGL(quantize_input_kernel, dim3((unsigned)((qa.n_threads + 255) / 256)), dim3(256), 0, st, qa);
   if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
 
@@ -848,23 +908,29 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.clamp_lo = kMagic - (float)d.q_adc;
   a.clamp_hi = kMagic + (float)d.q_adc;
   a.bias_per_vt = p.bias_per_vt;
+  a.out = out;
+  {
+    const double lsb = (double)adc_fs / (double)d.q_adc;
+    const double qa_max = (double)((1u << cfg->input_bits) - 1), qw_max = (double)((1u << cfg->weight_bits) - 1);
+    a.scale = lsb * (double)in_scale * (double)w_max / (qa_max * qw_max);
+  }
   hipEvent_t ev0 = g_trace_before, ev1 = g_trace_after;
   g_trace_before = g_trace_after = nullptr;
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return XBAR_EHIP;
   if (launch_vmm(a, p, d.terms, codes != nullptr, st) != hipSuccess) return XBAR_EHIP;
   if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return XBAR_EHIP;
 
-  FinishArgs f;
-  f.part = a.part;
-  f.out = out;
-  f.n = (long long)M * p.Lout;
-  f.nchunk = p.nchunk;
-  f.wide = p.wide;
-  const double lsb = (double)adc_fs / (double)d.q_adc;
-  const double qa_max = (double)((1u << cfg->input_bits) - 1), qw_max = (double)((1u << cfg->weight_bits) - 1);
-  f.scale = lsb * (double)in_scale * (double)w_max / (qa_max * qw_max);
-  hipLaunchKernelGGL(vmm_finish_kernel, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
-  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+  if (p.nchunk > 1) {
+    FinishArgs f;
+    f.part = a.part;
+    f.out = out;
+    f.n = (long long)M * p.Lout;
+    f.nchunk = p.nchunk;
+    f.wide = p.wide;
+    f.scale = a.scale;
+    hipLaunchKernelGGL(vmm_finish_kernel, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
+    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+  }
   return XBAR_OK;
 }
 
@@ -876,6 +942,15 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
 extern "C" {
 
 uint32_t xbar_abi_version(void) { return XBAR_ABI_VERSION; }
+
+int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void* hip_stream) {
+  if (mode < 0 || mode > 1 || iters <= 0 || iters > (1 << 24)) return XBAR_EINVAL;
+  if (!aligned16(out)) return XBAR_EALIGN;
+  if (out_bytes < (size_t)512 * 256 * sizeof(float)) return XBAR_EWORKSPACE;
+  hipLaunchKernelGGL(mfma_probe_kernel, dim3(512), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
+                     reinterpret_cast<float*>(out), iters, mode);
+  return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
+}
 
 void xbar_trace_next_vmm(void* before, void* after) {
   g_trace_before = reinterpret_cast<hipEvent_t>(before);
@@ -978,8 +1053,8 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
     const long long chunks = (long long)cdiv(Lc, 16) * 2;
     a.n_threads = chunks * g.OP * 32;
     const unsigned blocks = (unsigned)((a.n_threads + 255) / 256);
-    if (dir == 0) hipLaunchKernelGGL(tile_planes_kernel<false>, dim3(blocks), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL(tile_planes_kernel<true>, dim3(blocks), dim3(256), 0, st, a);
+    if (dir == 0) hipLaunchKernelGGL(tile_planes_kernel<false>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(tile_planes_kernel<true>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
     offset += align256(g.bytes);
   }

@@ -72,6 +72,7 @@ _SIGNATURES = {
     "xbar_bwd": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                            C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "xbar_trace_next_vmm": (None, [C.c_void_p, C.c_void_p]),
+    "xbar_probe_mfma_rate": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                               C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
@@ -104,6 +105,12 @@ def _check(code):
 def trace_next_vmm(before, after):
     """xbar_trace_next_vmm: hipEvent_t handles (integers) recorded around the next contraction kernel."""
     lib().xbar_trace_next_vmm(C.c_void_p(before), C.c_void_p(after))
+
+
+def probe_mfma_rate(mode, iters, scratch):
+    """xbar_probe_mfma_rate: enqueue the pure-MFMA probe; returns the flops it performs."""
+    _check(lib().xbar_probe_mfma_rate(mode, iters, C.c_void_p(scratch.data_ptr()), scratch.numel(), _stream()))
+    return 2.0 * 16 * iters * 2048 * 16384
 
 
 def validate(cfg):

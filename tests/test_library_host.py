@@ -24,7 +24,7 @@ def test_exports_every_declared_symbol(xb):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(xbar_[a-z_]+)\s*\(", header))
     assert {"xbar_fwd", "xbar_bwd", "xbar_update", "xbar_tile", "xbar_config_validate", "xbar_planes_bytes",
-            "xbar_workspace_bytes", "xbar_strerror", "xbar_abi_version", "xbar_trace_next_vmm"} <= names
+            "xbar_workspace_bytes", "xbar_strerror", "xbar_abi_version", "xbar_trace_next_vmm", "xbar_probe_mfma_rate"} <= names
     lib = C.CDLL(xb.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
