@@ -45,7 +45,7 @@ extern "C" {
 /* status codes */
 #define XBAR_OK          0
 #define XBAR_EINVAL     -1   /* bad parameter struct (sizes, bit widths, NaN/negative physical values) */
-#define XBAR_ESHAPE     -2   /* M, K or N not positive, or too large for 32-bit indexing              */
+#define XBAR_ESHAPE     -2   /* M, K or N not positive, K*N >= 2^31, or M*K / M*N >= 2^38             */
 #define XBAR_EALIGN     -3   /* a pointer is NULL or not 16-byte aligned                              */
 #define XBAR_EWORKSPACE -4   /* workspace / plane buffer smaller than the size query says             */
 #define XBAR_EHIP       -5   /* a HIP call failed (kernel launch)                                     */
@@ -155,8 +155,8 @@ void xbar_trace_next_vmm(void* before, void* after);
  * dependent-chain fp16 matrix instructions (the instruction the contraction uses, v_mfma_f32_32x32x16_f16)
  * on register-resident operands, 2 waves per SIMD on every CU, so that the caller can time the matrix
  * rate the chip sustains (it is power limited well below the nominal peak once operands toggle).
- *   mode 0: both operands pseudo-random fp16;  mode 1: A operand = sparse single-bit patterns as in
- *   the emulation, B pseudo-random.   iters: loop count; the kernel issues 16 * iters MFMAs per wave
+ *   mode 0: both operands pseudo-random fp16;  mode 1: B operand = sparse single-bit patterns as in
+ *   the emulation, A pseudo-random.   iters: loop count; the kernel issues 16 * iters MFMAs per wave
  *   on 2048 waves, i.e. 2 * 16 * iters * 2048 * 16384 flops.   out: 2 MiB of device scratch.
  */
 int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void* hip_stream);

@@ -1,6 +1,7 @@
-"""GPU parity at the full sizes of the benchmarked configuration (ResNet-50 layer GEMMs, batch 64), in
-the launch configuration bench.py times: the HIP path runs the whole layer, the oracle recomputes
-sampled batch rows (forward, backward) and a sampled block of weights (update) one by one."""
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times (ResNet-50 layer GEMMs at batch 64 = the benchmarked workload; one layer each of the ResNet-20
+and VGG-16 configurations): the HIP path runs the whole layer, the oracle recomputes sampled batch
+rows (forward, backward) and a sampled block of weights (update) one by one."""
 import numpy as np
 import pytest
 
@@ -10,7 +11,9 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-LAYERS = ["conv1_7x7", "s1b0_1x1b", "s4b0_3x3"]
+LAYERS = [("resnet50", 64, "conv1_7x7"), ("resnet50", 64, "s1b0_1x1b"), ("resnet50", 64, "s4b0_3x3"),
+          ("resnet20", 128, "s1b0_a"),        # 16 output columns: half-empty output patch, 4-bit cycles
+          ("vgg16", 128, "conv1_2")]          # 6.4 M rows (M*K > 2^31), 256x256 tiles, device variation
 
 
 @pytest.fixture(scope="module")
@@ -27,11 +30,11 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-@pytest.mark.parametrize("name", LAYERS)
-def test_resnet50_layer_full_size_sampled(xo, xb, name):
-    gemms = {g.name: (i, g) for i, g in enumerate(workloads.resnet50_gemms(64, merge=True))}
+@pytest.mark.parametrize("workload,batch,name", LAYERS)
+def test_layer_full_size_sampled(xo, xb, workload, batch, name):
+    gemms = {g.name: (i, g) for i, g in enumerate(workloads.GEMMS[workload](batch, merge=True))}
     idx, g = gemms[name]
-    kw = workloads.config_kwargs("resnet50")
+    kw = workloads.config_kwargs(workload)
     kw["flags"] |= workloads.INPUT_SIGNED if g.signed_input else 0
     co, cg = xo.make_config(**kw), xb.make_config(**kw)
     W, X, dY = workloads.layer_tensors_torch(g, seed=idx, device="cuda")
@@ -55,7 +58,9 @@ def test_resnet50_layer_full_size_sampled(xo, xb, name):
     assert rel_l2(Y[rt].cpu().numpy(), Yo) <= 1e-3
     assert rel_l2(dX[rt].cpu().numpy(), dXo) <= 1e-3
     # every element within one top-slice LSB of the oracle (a flipped code moves one output by at most that)
-    lsb_f = kw["adc_fs_fwd"] / 127 * xs * w_max / (255 * 65535.0) * 2 ** 21
+    q_adc = (1 << (kw["adc_bits"] - 1)) - 1
+    top_shift = kw["weight_bits"] - kw["slice_bits"] + kw["input_bits"] - kw["stream_bits"]
+    lsb_f = kw["adc_fs_fwd"] / q_adc * xs * w_max / (255.0 * ((1 << kw["weight_bits"]) - 1)) * 2 ** top_shift
     assert np.abs(Y[rt].cpu().numpy() - Yo).max() <= 1.01 * lsb_f
 
     k_idx = np.sort(rng.choice(g.K, size=min(6, g.K), replace=False))

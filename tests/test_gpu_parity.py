@@ -96,10 +96,12 @@ def test_ideal_fwd_bwd_bit_exact(xo, xb, R, C, sb, slb, wb, signed, M, K, N, adc
     Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale)
     assert np.array_equal(codes_g, codes_o)
     assert np.array_equal(Yg, Yo)
+    assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, x_scale, codes=False), Yo)      # production launch
     dXo, codes_o = xo.bwd(co, W, dY, w_max, g_scale, want_codes=True)
     dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, g_scale)
     assert np.array_equal(codes_g, codes_o)
     assert np.array_equal(dXg, dXo)
+    assert np.array_equal(gpu_bwd(xb, cg, W, dY, w_max, g_scale, codes=False), dXo)
 
 
 def test_ideal_lossless_is_integer_matmul(xo, xb):
@@ -150,10 +152,13 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
     Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=3, profile=profile)
     check_codes(codes_g, codes_o)
     assert rel_l2(Yg, Yo) <= 1e-3
+    # the production launch (no code tap: software-pipelined, 32-bit accumulators) gives the same bits
+    assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, x_scale, step=3, profile=profile, codes=False), Yg)
     dXo, codes_o = xo.bwd(co, W, dY, w_max, g_scale, step=3, profile=profile, want_codes=True)
     dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=3, profile=profile)
     check_codes(codes_g, codes_o)
     assert rel_l2(dXg, dXo) <= 1e-3
+    assert np.array_equal(gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=3, profile=profile, codes=False), dXg)
     # a different step redraws the devices
     if "var" in ni:
         Y2 = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=4, codes=False)

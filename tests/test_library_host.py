@@ -77,7 +77,9 @@ def test_size_queries(xb):
         assert 0 < small <= big
         assert xb.workspace_bytes(c, op, 0, K, N) == 0
     assert xb.workspace_bytes(c, 7, 64, K, N) == 0
-    assert xb.workspace_bytes(c, xb.OP_FWD, 1 << 20, 1 << 12, 8) == 0     # M*K reaches 2^31
+    assert xb.workspace_bytes(c, xb.OP_FWD, 1 << 20, 1 << 12, 8) > 0      # activations may exceed 2^31 elements
+    assert xb.workspace_bytes(c, xb.OP_FWD, 8, 1 << 16, 1 << 15) == 0     # K*N reaches 2^31
+    assert xb.workspace_bytes(c, xb.OP_FWD, 1 << 30, 1 << 8, 8) == 0      # M*K reaches 2^38
 
 
 def test_argument_checks_precede_any_device_work(xb):
