@@ -891,7 +891,13 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   if (!aligned16(planes) || !aligned16(in) || !aligned16(out) || !aligned16(ws)) return XBAR_EALIGN;
   if (codes && (reinterpret_cast<uintptr_t>(codes) & 1u)) return XBAR_EALIGN;
   if (!finite_pos(w_max) || !finite_pos(in_scale)) return XBAR_EINVAL;
-  if (cfg->flags & XBAR_DAC_LUT) return XBAR_ENOTSUP;
+  // DAC level table: with 1-bit cycles (the paper's streaming scheme) and a zero level at 0 V the
+  // table is one factor on every current, which goes into the ADC gain; other tables are not built.
+  float dac_gain = 1.0f;
+  if (cfg->flags & XBAR_DAC_LUT) {
+    if (cfg->stream_bits != 1 || cfg->dac_lut[0] != 0.0f) return XBAR_ENOTSUP;
+    dac_gain = cfg->dac_lut[1];
+  }
   const Derived d = derive(cfg);
   const VmmPlan p = plan_vmm(cfg, d, M, K, N, transposed);
   if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
@@ -919,7 +925,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.lds_kb = p.lds_kb;
   a.total_wg = p.nchunk * p.g.OP * p.MB;
   a.per_xcd = cdiv(a.total_wg, 8);
-  a.gain = (float)d.q_adc / adc_fs;
+  a.gain = (float)d.q_adc / adc_fs * dac_gain;
   a.clamp_lo = kMagic - (float)d.q_adc;
   a.clamp_hi = kMagic + (float)d.q_adc;
   a.bias_per_vt = p.bias_per_vt;

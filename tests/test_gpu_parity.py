@@ -76,6 +76,8 @@ IDEAL_CASES = [
     (256, 256, 1, 2, 16, False, 40, 520, 48, 8),
     (16, 32, 4, 4, 8, True, 5, 40, 70, 7),
     (128, 128, 8, 2, 4, False, 3, 1, 1, 8),
+    (128, 128, 1, 2, 6, True, 50, 260, 40, 8),          # 3 slices: odd group, unpipelined path
+    (32, 48, 1, 1, 5, False, 20, 70, 100, 6),           # 5 one-bit slices, 32-row / 48-column tiles
 ]
 
 
@@ -128,6 +130,9 @@ NONIDEAL_CASES = [
     ("var_only", 64, 128, 2, 2, 8, False, 33, 130, 200, "var", 0.05),
     ("aam_256", 256, 256, 1, 2, 16, False, 40, 520, 48, "aam+var", 0.1),
     ("profile", 128, 128, 4, 2, 8, True, 20, 200, 96, "profile", 0.0),
+    ("odd_slices", 128, 128, 1, 2, 6, True, 40, 200, 70, "aam", 0.0),        # 3 slices: unpipelined path
+    ("slice4", 64, 64, 2, 4, 8, False, 30, 100, 50, "aam+var", 0.05),        # 16-level devices
+    ("in4", 128, 128, 2, 2, 8, False, 33, 129, 31, "aam", 0.0),
 ]
 
 
@@ -267,6 +272,24 @@ def test_config2_mlp_ten_sgd_steps(xo, xb):
     assert np.isfinite(losses).all()
 
 
+def test_one_bit_dac_level_table(xo, xb):
+    """1-bit streaming with a non-ideal 'one' level (the paper streams inputs through 1-bit DACs)."""
+    g = workloads.Gemm("t", 300, 100, 40, True, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=77)
+    kw = dict(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, input_bits=8, stream_bits=1, adc_bits=8,
+              flags=xo.WIRE_AAM | xo.INPUT_SIGNED | xo.DAC_LUT, dac_lut=[0.0, 0.93], adc_fs_fwd=64.0, adc_fs_bwd=64.0)
+    co, cg = both_configs(xo, xb, **kw)
+    w_max, xs, gs = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    Yo, codes_o = xo.fwd(co, W, X, w_max, xs, want_codes=True)
+    Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, xs)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(Yg, Yo) <= 1e-3
+    dXo = xo.bwd(co, W, dY, w_max, gs)
+    assert rel_l2(gpu_bwd(xb, cg, W, dY, w_max, gs, codes=False), dXo) <= 1e-3
+    base = xo.fwd(xo.make_config(**dict(kw, flags=xo.WIRE_AAM | xo.INPUT_SIGNED)), W, X, w_max, xs)
+    assert not np.array_equal(base, Yo)
+
+
 def test_error_paths_on_device(xo, xb):
     cg = xb.make_config()
     W = torch.zeros((64, 64), device="cuda")
@@ -277,7 +300,7 @@ def test_error_paths_on_device(xo, xb):
         xb.fwd(cg, planes, X, 64, 1.0, 1.0, ws=small)
     with pytest.raises(xb.XbarError, match="workspace"):
         xb.tile(cg, W, 1.0, planes=small)
-    lut = xb.make_config(flags=xb.DAC_LUT)
+    lut = xb.make_config(flags=xb.DAC_LUT, stream_bits=2, dac_lut=[0.0, 0.3, 0.7, 1.0])
     with pytest.raises(xb.XbarError, match="not supported"):
         xb.fwd(lut, planes, X, 64, 1.0, 1.0)
     torch.cuda.synchronize()
