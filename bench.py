@@ -19,6 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
+# HBM bytes per vmm_kernel launch (average over the 108 launches of a step) of the default workload, from
+# the FETCH_SIZE / WRITE_SIZE counter runs recorded in profiles/vmm_kernel_resnet50_batch64.txt
+VMM_TRAFFIC_BYTES_RESNET50_B64 = 436560 * 1024
 
 
 class HipEvents:
@@ -58,6 +61,8 @@ def main():
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA sustained-rate probe")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="run one 1 GiB device-to-device copy first (known size, to scale HBM byte counters)")
     ap.add_argument("--only", default=None, help="comma-separated layer names: run just these (profiling)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -104,6 +109,14 @@ def main():
     planes = torch.empty(max_planes, dtype=torch.uint8, device=device)
     ws = torch.empty(max_ws, dtype=torch.uint8, device=device)
     out = torch.empty(max_out, dtype=torch.float32, device=device)
+
+    if args.calib_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=device).normal_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                     # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     events = HipEvents()
     vmm_records = []          # (layer index, 'fwd'|'bwd', event pair)
@@ -173,6 +186,8 @@ def main():
             torch.cuda.synchronize()
             probe[key] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
         roofline["sustained_mfma_tflops_bare_instruction"] = probe
+    if args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal:
+        roofline["traffic"] = VMM_TRAFFIC_BYTES_RESNET50_B64
     if args.per_layer:
         for (li, kind), (ms, fl, n) in sorted(per_layer.items()):
             g = layers[li]["g"]
