@@ -562,10 +562,11 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
   // that blocks sharing the same planes share one L2
   const int logical = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
   if (logical >= a.total_wg) return;
-  const int mb = logical % a.MB;
-  const int grp = logical / a.MB;
-  const int op = grp % a.OP;
-  const int chunk = grp / a.OP;
+  // chunk is the fastest index: every XCD then gets the same mix of (slightly unequal) chunks
+  const int chunk = logical % a.nchunk;
+  const int grp = logical / a.nchunk;
+  const int mb = grp % a.MB;
+  const int op = grp / a.MB;
   const int mp0 = (mb * nw + wave) * PM;
 
   uint32_t y[PM][16];
@@ -578,8 +579,10 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
       y64[pm][r] = 0;
     }
 
-  const int vt0 = chunk * a.vt_per_chunk;
-  const int vt1 = min(a.VT, vt0 + a.vt_per_chunk);
+  // virtual tiles spread evenly over the chunks: the first VT % nchunk chunks get one more
+  const int vt_base = a.VT / a.nchunk, vt_rem = a.VT - vt_base * a.nchunk;
+  const int vt0 = chunk * vt_base + min(chunk, vt_rem);
+  const int vt1 = vt0 + vt_base + (chunk < vt_rem ? 1 : 0);
   for (int vt = vt0; vt < vt1; ++vt) {
     const int p = vt / a.T, t = vt - p * a.T;
     const int rows = min(a.tile, a.Lin - t * a.tile);
