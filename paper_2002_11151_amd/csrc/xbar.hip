@@ -652,6 +652,9 @@ struct GradArgs {
 constexpr int kGradMS = 16;   // batch rows per LDS stage
 
 // 128 x 128 tile of X^T dY per block, 4 waves as 2 x 2, each wave 64 x 64 = 2 x 2 MFMA tiles.
+// When the layer has at most 64 rows (SPLIT_K) or columns (SPLIT_N) the waves that would work on
+// padding take a share of the batch rows of every stage instead and write a partial sum of their own.
+template <bool SPLIT_K, bool SPLIT_N>
 __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   __shared__ float xs[kGradMS][128];
   __shared__ float ds[kGradMS][128];
@@ -661,6 +664,9 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   const int k0 = kb * 128, n0 = nb * 128;
   const int m_begin = blockIdx.y * a.m_per_chunk;
   const int m_end = min(a.M, m_begin + a.m_per_chunk);
+  constexpr int PARTS = (SPLIT_K ? 2 : 1) * (SPLIT_N ? 2 : 1);     // batch shares per stage
+  const int share = (SPLIT_K ? wk : 0) * (SPLIT_N ? 2 : 1) + (SPLIT_N ? wn : 0);
+  const int koff = SPLIT_K ? 0 : wk * 64, noff = SPLIT_N ? 0 : wn * 64;
   float16v acc[2][2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -692,27 +698,27 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     __syncthreads();
     if (m0 + kGradMS < m_end) prefetch(m0 + kGradMS);
 #pragma unroll
-    for (int mm = 0; mm < kGradMS; mm += 2) {
-      const int row = mm + (lane >> 5);
-      const float a0 = xs[row][wk * 64 + (lane & 31)];
-      const float a1 = xs[row][wk * 64 + 32 + (lane & 31)];
-      const float b0 = ds[row][wn * 64 + (lane & 31)];
-      const float b1 = ds[row][wn * 64 + 32 + (lane & 31)];
+    for (int q = 0; q < kGradMS / PARTS; q += 2) {
+      const int row = share * (kGradMS / PARTS) + q + (lane >> 5);
+      const float a0 = xs[row][koff + (lane & 31)];
+      const float a1 = xs[row][koff + 32 + (lane & 31)];
+      const float b0 = ds[row][noff + (lane & 31)];
+      const float b1 = ds[row][noff + 32 + (lane & 31)];
       acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
       acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
       acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
       acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
     }
   }
-  float* out = a.part + (size_t)blockIdx.y * a.K * a.N;
+  float* out = a.part + ((size_t)blockIdx.y * PARTS + share) * a.K * a.N;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int k = k0 + wk * 64 + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        const int n = n0 + wn * 64 + j * 32 + (lane & 31);
+        const int k = k0 + koff + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int n = n0 + noff + j * 32 + (lane & 31);
         if (k < a.K && n < a.N) out[(size_t)k * a.N + n] = acc[i][j][r];
       }
 }
@@ -848,7 +854,7 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
 }
 
 struct UpdPlan {
-  int KB, NB, mchunks, m_per_chunk;
+  int KB, NB, mchunks, m_per_chunk, parts;   // parts: partial sums per batch chunk (padding waves reused)
   size_t ws_bytes;
 };
 
@@ -861,7 +867,8 @@ UpdPlan plan_update(int M, int K, int N) {
   int per = std::max(kGradMS, cdiv(cdiv(M, want), kGradMS) * kGradMS);
   p.m_per_chunk = per;
   p.mchunks = cdiv(M, per);
-  p.ws_bytes = align256((size_t)p.mchunks * K * N * sizeof(float));
+  p.parts = (K <= 64 ? 2 : 1) * (N <= 64 ? 2 : 1);
+  p.ws_bytes = align256((size_t)p.mchunks * p.parts * K * N * sizeof(float));
   return p;
 }
 
@@ -1108,10 +1115,16 @@ int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* d
   GradArgs g;
   g.X = X; g.D = dY; g.part = reinterpret_cast<float*>(ws);
   g.M = M; g.K = K; g.N = N; g.KB = p.KB; g.NB = p.NB; g.m_per_chunk = p.m_per_chunk;
-  hipLaunchKernelGGL(grad_gemm_kernel, dim3((unsigned)(p.KB * p.NB), (unsigned)p.mchunks), dim3(256), 0, st, g);
+  {
+    const dim3 grid((unsigned)(p.KB * p.NB), (unsigned)p.mchunks), block(256);
+    if (K <= 64 && N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, true>), grid, block, 0, st, g);
+    else if (K <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, false>), grid, block, 0, st, g);
+    else if (N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<false, true>), grid, block, 0, st, g);
+    else hipLaunchKernelGGL((grad_gemm_kernel<false, false>), grid, block, 0, st, g);
+  }
   if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   WriteArgs w;
-  w.W = W; w.part = g.part; w.n = (long long)K * N; w.mchunks = p.mchunks; w.flags = cfg->flags;
+  w.W = W; w.part = g.part; w.n = (long long)K * N; w.mchunks = p.mchunks * p.parts; w.flags = cfg->flags;
   w.w_max = (double)w_max; w.grad_scale = (double)grad_scale; w.lr = (double)lr;
   w.v = (double)cfg->upd_nl_v; w.gamma = (double)cfg->upd_noise_gamma;
   w.seed = cfg->seed; w.step = step;
