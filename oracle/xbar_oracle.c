@@ -21,8 +21,10 @@
  *                 write non-linearity (factor v) -> Gaussian write noise (factor gamma) ->
  *                 times learning rate, subtracted from the stored conductance.
  *   Sec. IV-D  -- approximate analytical model (shortest path per device, series resistance of
- *                 source, row wire, column wire and sense) and the stored distortion profile
- *                 D = (G_ideal - G_nonideal) / G_ideal of interpolated FCM.
+ *                 source, row wire, column wire and sense; optionally all first-order paths, i.e.
+ *                 the wire drops caused by every device that shares the row or the column) and
+ *                 the stored distortion profile D = (G_ideal - G_nonideal) / G_ideal of
+ *                 interpolated FCM.
  *   Sec. V     -- default parameters (Rmin 100 kOhm, Rmax 1 MOhm, 1 Ohm / 4.6 Ohm wire per cell,
  *                 2-bit devices, bit-streamed inputs).
  *
@@ -43,6 +45,7 @@
 #define XO_UPD_NOISE    16u
 #define XO_DAC_LUT      32u
 #define XO_INPUT_SIGNED 64u
+#define XO_WIRE_AAM2    128u
 
 #define XO_STREAM_VARIATION 1u
 #define XO_STREAM_WRITE     2u
@@ -145,6 +148,19 @@ int64_t xo_adc(double current, float full_scale, int adc_bits) {
 /* of a K_full x N_full layer (NULL index arrays mean the identity).                            */
 /* profile: D[s][pol][k][n] over the full layer (pol 0 = positive array), or NULL.              */
 /* ------------------------------------------------------------------------------------------- */
+/* Device conductance before the wire model: digit -> level of the array that carries the sign of
+ * the weight (the other array rests at the lowest conductance), then process variation.          */
+static void device_pair(const xo_config* cfg, int sign, int digit, uint64_t k, uint64_t n, int s, int S,
+                        int N_full, uint64_t step, double g_min, double dg, double g[2]) {
+  g[0] = g_min + (sign > 0 ? digit * dg : 0.0);
+  g[1] = g_min + (sign < 0 ? digit * dg : 0.0);
+  if (cfg->flags & XO_VARIATION)       /* independent multiplicative Gaussian per device */
+    for (int pol = 0; pol < 2; ++pol) {
+      uint64_t dev = ((k * (uint64_t)N_full + n) * (uint64_t)S + (uint64_t)s) * 2 + (uint64_t)pol;
+      g[pol] *= 1.0 + (double)cfg->var_sigma * xo_normal(cfg->seed, XO_STREAM_VARIATION, step, dev);
+    }
+}
+
 int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_t* k_idx,
               const int32_t* n_idx, int K_full, int N_full, float w_max, uint64_t step,
               const float* profile, double* U) {
@@ -154,9 +170,55 @@ int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_
   const double g_min = 1.0 / (double)cfg->r_max;
   const double g_max = 1.0 / (double)cfg->r_min;
   const double dg = (g_max - g_min) / (double)levels;
-  const uint32_t array_ni = cfg->flags & (XO_VARIATION | XO_WIRE_AAM | XO_WIRE_PROFILE);
+  const uint32_t array_ni = cfg->flags & (XO_VARIATION | XO_WIRE_AAM | XO_WIRE_PROFILE | XO_WIRE_AAM2);
   int32_t d[64];
   if (S > 64) return -1;
+  if (cfg->flags & XO_WIRE_AAM2) {
+    /* All first-order paths (Sec. IV-D: "considering more ... paths"): the voltage at a device
+     * drops by the current of EVERY device on its row through the row-wire segments they share
+     * with it, and rises on the column side by the current of every device on its column through
+     * the shared column segments:
+     *   a_ij = sum_j' G_ij' (r_source + (min(j,j') + 1) r_row)
+     *   b_ij = sum_i' G_i'j ((R - max(i,i')) r_col + r_sense)
+     *   G_ni = G / (1 + a + b)          (the j' = j and i' = i terms alone give the single-path model)
+     * Needs whole tiles, so no sub-matrix addressing here.                                          */
+    if (k_idx || n_idx || Ks != K_full || Ns != N_full) return -3;
+    double* G = (double*)malloc(sizeof(double) * 2 * (size_t)R * C);
+    if (!G) return -2;
+    for (int s = 0; s < S; ++s)
+      for (int k0 = 0; k0 < Ks; k0 += R)
+        for (int n0 = 0; n0 < Ns; n0 += C) {
+          const int rows = k0 + R < Ks ? R : Ks - k0, cols = n0 + C < Ns ? C : Ns - n0;
+          for (int i = 0; i < rows; ++i)
+            for (int j = 0; j < cols; ++j) {
+              const int64_t q = xo_quantize_weight(W[(size_t)(k0 + i) * Ns + n0 + j], w_max, cfg->weight_bits);
+              xo_digits((uint64_t)(q < 0 ? -q : q), cfg->slice_bits, S, d);
+              double g[2];
+              device_pair(cfg, (q > 0) - (q < 0), d[s], (uint64_t)(k0 + i), (uint64_t)(n0 + j), s, S, N_full, step,
+                          g_min, dg, g);
+              G[((size_t)0 * R + i) * C + j] = g[0];
+              G[((size_t)1 * R + i) * C + j] = g[1];
+            }
+          for (int i = 0; i < rows; ++i)
+            for (int j = 0; j < cols; ++j) {
+              double e[2];
+              for (int pol = 0; pol < 2; ++pol) {
+                const double* Gp = G + (size_t)pol * R * C;
+                double a = 0.0, b = 0.0;
+                for (int jj = 0; jj < cols; ++jj)
+                  a += Gp[(size_t)i * C + jj] *
+                       ((double)cfg->r_source + (double)((j < jj ? j : jj) + 1) * (double)cfg->r_row);
+                for (int ii = 0; ii < rows; ++ii)
+                  b += Gp[(size_t)ii * C + j] *
+                       ((double)(R - (i > ii ? i : ii)) * (double)cfg->r_col + (double)cfg->r_sense);
+                e[pol] = Gp[(size_t)i * C + j] / (1.0 + a + b);
+              }
+              U[((size_t)s * Ks + k0 + i) * Ns + n0 + j] = (e[0] - e[1]) / dg;
+            }
+        }
+    free(G);
+    return 0;
+  }
   for (int ki = 0; ki < Ks; ++ki) {
     for (int ni = 0; ni < Ns; ++ni) {
       const int64_t k = k_idx ? k_idx[ki] : ki;
@@ -170,16 +232,9 @@ int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_
           *out = (double)(sign * d[s]);
           continue;
         }
-        /* the array that carries the sign of the weight holds the digit, the other one rests
-         * at the lowest conductance                                                          */
         double g[2];
-        g[0] = g_min + (sign > 0 ? d[s] * dg : 0.0);
-        g[1] = g_min + (sign < 0 ? d[s] * dg : 0.0);
+        device_pair(cfg, sign, d[s], (uint64_t)k, (uint64_t)n, s, S, N_full, step, g_min, dg, g);
         for (int pol = 0; pol < 2; ++pol) {
-          if (cfg->flags & XO_VARIATION) {   /* independent multiplicative Gaussian per device */
-            uint64_t dev = (((uint64_t)k * (uint64_t)N_full + (uint64_t)n) * (uint64_t)S + s) * 2 + pol;
-            g[pol] *= 1.0 + (double)cfg->var_sigma * xo_normal(cfg->seed, XO_STREAM_VARIATION, step, dev);
-          }
           if (cfg->flags & XO_WIRE_AAM) {    /* single shortest path through device (i, j)     */
             int i = (int)(k % R), j = (int)(n % C);
             double rho = (double)cfg->r_source + (double)(j + 1) * (double)cfg->r_row +

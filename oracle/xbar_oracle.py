@@ -11,7 +11,7 @@ import numpy as np
 
 from . import build as _build
 
-VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED = 1, 2, 4, 8, 16, 32, 64
+VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED, WIRE_AAM2 = 1, 2, 4, 8, 16, 32, 64, 128
 STREAM_VARIATION, STREAM_WRITE = 1, 2
 
 
@@ -138,7 +138,7 @@ def planes(cfg, W, w_max, step=0, profile=None, k_idx=None, n_idx=None, K_full=N
     rc = lib().xo_planes(C.byref(cfg), _p(W, C.c_float), Ks, Ns, _p(k_idx, C.c_int32), _p(n_idx, C.c_int32),
                          K_full, N_full, C.c_float(w_max), C.c_uint64(step), _p(prof, C.c_float),
                          _p(U, C.c_double))
-    assert rc == 0
+    assert rc == 0, rc
     return U
 
 

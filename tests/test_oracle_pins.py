@@ -269,6 +269,99 @@ def test_aam_converges_to_exact_circuit_for_high_device_resistance(xo, R, C):
     assert errs[-1] < 1e-3 * R * C / 64 + 1e-5
 
 
+def _exact_plane(cfg, d, rows=None, cols=None, scale=1.0):
+    """(E+ - E-) / dG of the exact circuit for non-negative digits d on one tile (absent devices: G = 0)."""
+    R, C = cfg.xbar_rows, cfg.xbar_cols
+    Gp = np.zeros((R, C))
+    Gn = np.zeros((R, C))
+    rows, cols = rows or R, cols or C
+    Gp[:rows, :cols] = _device_g(cfg, d.astype(np.float64))
+    Gn[:rows, :cols] = _device_g(cfg, 0)
+    dg = _device_g(cfg, 1) - _device_g(cfg, 0)
+    wires = (cfg.r_row * scale, cfg.r_col * scale, cfg.r_source * scale, cfg.r_sense * scale)
+    E = nodal.effective_conductance(Gp, *wires) - nodal.effective_conductance(Gn, *wires)
+    return (E / dg)[:rows, :cols]
+
+
+def test_aam2_single_cell_and_isolated_devices_equal_single_path_model(xo):
+    kw = dict(weight_bits=2, slice_bits=2, r_row=30.0, r_col=500.0, r_source=1e3, r_sense=2e3, r_min=1e4)
+    for d in (1, 2, 3):
+        W = np.array([[d / 3.0]], dtype=np.float32)
+        one = xo.planes(xo.make_config(xbar_rows=1, xbar_cols=1, r_max=1e5, flags=xo.WIRE_AAM, **kw), W, 1.0)
+        two = xo.planes(xo.make_config(xbar_rows=1, xbar_cols=1, r_max=1e5, flags=xo.WIRE_AAM2, **kw), W, 1.0)
+        assert abs(one[0, 0, 0] - two[0, 0, 0]) < 1e-12
+    # one conducting device per row and per column (the others practically open): nothing is shared
+    R = 6
+    perm = np.random.default_rng(5).permutation(R)
+    W = np.zeros((R, R), dtype=np.float32)
+    W[np.arange(R), perm] = 1.0
+    one = xo.planes(xo.make_config(xbar_rows=R, xbar_cols=R, r_max=1e16, flags=xo.WIRE_AAM, **kw), W, 1.0)
+    two = xo.planes(xo.make_config(xbar_rows=R, xbar_cols=R, r_max=1e16, flags=xo.WIRE_AAM2, **kw), W, 1.0)
+    assert np.abs(one - two).max() < 1e-9 and np.abs(two).max() > 0.5
+
+
+def test_aam2_without_wire_resistance_is_ideal(xo):
+    rng = np.random.default_rng(2)
+    W = rng.uniform(-1, 1, size=(20, 12)).astype(np.float32)
+    ideal = xo.make_config(xbar_rows=8, xbar_cols=8)
+    aam0 = xo.make_config(xbar_rows=8, xbar_cols=8, flags=xo.WIRE_AAM2, r_row=0.0, r_col=0.0)
+    assert np.allclose(xo.planes(aam0, W, 1.0), xo.planes(ideal, W, 1.0), rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("R,C,rows,cols", [(5, 7, 5, 7), (8, 4, 8, 4), (6, 6, 4, 5)])
+def test_aam2_first_order_coefficients_match_exact_circuit(xo, R, C, rows, cols):
+    # With all wire resistances scaled by eps, d(plane)/d(eps) at 0 of the exact circuit holds the
+    # weight of every shared segment (row prefix, column suffix, source, sense): a wrong index or a
+    # dropped term anywhere changes it by O(1).  Partial tile: absent devices carry no current.
+    rng = np.random.default_rng(R * 100 + C)
+    d = rng.integers(0, 4, size=(rows, cols))
+    base = dict(xbar_rows=R, xbar_cols=C, weight_bits=2, slice_bits=2, r_min=1e3, r_max=1e4)
+    wires = dict(r_row=2.0, r_col=7.0, r_source=11.0, r_sense=13.0)
+    eps = 1e-4
+    cfg = xo.make_config(flags=xo.WIRE_AAM2, **base, **{k: v * eps for k, v in wires.items()})
+    U = xo.planes(cfg, (d / 3.0).astype(np.float32), 1.0)[0]
+    ref = xo.make_config(**base, **wires)
+    slope_model = (U - d) / eps
+    slope_exact = (_exact_plane(ref, d, rows, cols, scale=eps) - d) / eps
+    assert np.abs(slope_exact).max() > 0.05
+    assert np.abs(slope_model - slope_exact).max() < 2e-3 * np.abs(slope_exact).max()
+
+
+@pytest.mark.parametrize("R,C", [(8, 8), (16, 16), (12, 5)])
+def test_aam2_error_is_second_order_and_far_below_single_path_model(xo, R, C):
+    rng = np.random.default_rng(R + C)
+    d = rng.integers(0, 4, size=(R, C))
+    W = (d / 3.0).astype(np.float32)
+    errs2, errs1 = [], []
+    for scale in (4.0, 2.0, 1.0):
+        kw = dict(xbar_rows=R, xbar_cols=C, weight_bits=2, slice_bits=2, r_min=1e4, r_max=1e5,
+                  r_row=1.0 * scale, r_col=4.6 * scale, r_source=3.0 * scale, r_sense=2.0 * scale)
+        exact = _exact_plane(xo.make_config(**kw), d)
+        errs2.append(np.abs(xo.planes(xo.make_config(flags=xo.WIRE_AAM2, **kw), W, 1.0)[0] - exact).max())
+        errs1.append(np.abs(xo.planes(xo.make_config(flags=xo.WIRE_AAM, **kw), W, 1.0)[0] - exact).max())
+    assert errs2[0] / errs2[1] > 3.0 and errs2[1] / errs2[2] > 3.0       # ~ eps^2
+    assert 1.6 < errs1[1] / errs1[2] < 2.4                               # single path: first order remains
+    assert errs2[2] < 0.05 * errs1[2]
+
+
+def test_aam2_signed_weights_and_slices(xo):
+    # sign symmetry and slice independence: each slice / polarity array is its own circuit
+    R = C = 6
+    rng = np.random.default_rng(9)
+    q = rng.integers(-15, 16, size=(R, C))
+    cfg = xo.make_config(xbar_rows=R, xbar_cols=C, weight_bits=4, slice_bits=2, flags=xo.WIRE_AAM2,
+                         r_min=1e4, r_max=1e5, r_row=5.0, r_col=9.0)
+    U = xo.planes(cfg, (q / 15.0).astype(np.float32), 1.0)
+    assert np.array_equal(xo.planes(cfg, (-q / 15.0).astype(np.float32), 1.0), -U)
+    dg = _device_g(cfg, 1) - _device_g(cfg, 0)
+    for s in range(2):
+        dig = (np.abs(q) >> (2 * s)) & 3
+        Gp = _device_g(cfg, np.where(q > 0, dig, 0).astype(np.float64))
+        Gn = _device_g(cfg, np.where(q < 0, dig, 0).astype(np.float64))
+        exact = (nodal.effective_conductance(Gp, 5.0, 9.0) - nodal.effective_conductance(Gn, 5.0, 9.0)) / dg
+        assert np.abs(U[s] - exact).max() < 2e-4
+
+
 def test_nodal_solver_basics():
     # two cells on one column: hand-solved ladder.  Row drivers 1 V each, r_row a, r_col b.
     g1, g2, a, b = 1e-3, 2e-3, 5.0, 7.0
