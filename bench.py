@@ -59,6 +59,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
+    ap.add_argument("--all-paths", action="store_true",
+                    help="wire model with every first-order path instead of the shortest path per device")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA sustained-rate probe")
     ap.add_argument("--calib-copy", action="store_true",
@@ -90,8 +92,11 @@ def main():
     kw = workloads.config_kwargs(args.workload)
     if args.ideal:
         kw["flags"] &= ~(workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE)
+    if args.all_paths and kw["flags"] & workloads.NI_WIRE_AAM:
+        kw["flags"] = (kw["flags"] & ~workloads.NI_WIRE_AAM) | workloads.NI_WIRE_AAM2
     S_w, S_in = kw["weight_bits"] // kw["slice_bits"], kw["input_bits"] // kw["stream_bits"]
-    terms = 2 if kw["flags"] & (workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE) else 1
+    terms = 2 if kw["flags"] & (workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE |
+                                workloads.NI_WIRE_AAM2) else 1
 
     # ---- resident tensors, one set per distinct shape ------------------------------------------
     layers = []
@@ -186,7 +191,7 @@ def main():
             torch.cuda.synchronize()
             probe[key] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
         roofline["sustained_mfma_tflops_bare_instruction"] = probe
-    if args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal:
+    if args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal and not args.all_paths:
         roofline["traffic"] = VMM_TRAFFIC_BYTES_RESNET50_B64
     if args.per_layer:
         for (li, kind), (ms, fl, n) in sorted(per_layer.items()):
@@ -231,7 +236,8 @@ def main():
                                "%d-bit weights in %d slices, %d-bit inputs in %d cycles, %d-bit ADC, %s" %
                                (args.workload, sum(g.count for g in gemms), len(gemms), batch, kw["xbar_rows"],
                                 kw["xbar_cols"], kw["weight_bits"], S_w, kw["input_bits"], S_in, kw["adc_bits"],
-                                "ideal arrays" if terms == 1 else "wire parasitics (AAM) + write non-linearity + noise"),
+                                "ideal arrays" if terms == 1 else "wire parasitics (%s) + write non-linearity + noise" %
+                                ("AAM, all first-order paths" if kw["flags"] & workloads.NI_WIRE_AAM2 else "AAM")),
                    "emulated_macs_per_step": emulated, "logical_macs_per_step": tot["logical"]},
         "logical_gmacs": round(tot["logical"] / (elapsed / args.steps) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu,

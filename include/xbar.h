@@ -42,6 +42,10 @@ extern "C" {
 #define XBAR_DAC_LUT         32u  /* DAC levels from dac_lut instead of equidistant (Sec. IV-B); the GPU
                                      kernels take it for 1-bit cycles with dac_lut[0] == 0, else ENOTSUP */
 #define XBAR_INPUT_SIGNED    64u  /* forward inputs are signed (two phases); backward always is         */
+#define XBAR_NI_WIRE_AAM2    128u /* wire parasitics, analytical model with every first-order path: the
+                                     drops that all devices of a row / column cause on the wire segments
+                                     they share (Sec. IV-D: more paths than the shortest one); at most one
+                                     of the three wire flags                                             */
 
 /* status codes */
 #define XBAR_OK          0
@@ -101,6 +105,9 @@ uint32_t xbar_abi_version(void);
  *   profile  [S_w][2][K][N] float distortion D (index 1: 0 = positive array), G <- G (1 - D);
  *            required with XBAR_NI_WIRE_PROFILE, ignored otherwise
  *   planes   output, xbar_planes_bytes(cfg, K, N) bytes, opaque
+ * With XBAR_NI_WIRE_AAM2 the plane buffer also holds (16 S_w + 4) K N bytes of scratch (the size query
+ * includes them); tile (i, j) indices count from the tile's first row / column, devices beyond K / N
+ * carry no current.
  * Device (slice s, array pol) of weight (k, n) uses normal number ((k N + n) S_w + s) 2 + pol of
  * the variation stream.  Rows / columns beyond K / N hold no device.
  */

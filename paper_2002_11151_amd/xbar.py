@@ -11,7 +11,8 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libxbar.so")
 
-NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED = 1, 2, 4, 8, 16, 32, 64
+NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2 = (
+    1, 2, 4, 8, 16, 32, 64, 128)
 OP_FWD, OP_BWD, OP_UPDATE = 0, 1, 2
 ABI_VERSION = 1
 

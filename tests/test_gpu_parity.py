@@ -133,6 +133,12 @@ NONIDEAL_CASES = [
     ("odd_slices", 128, 128, 1, 2, 6, True, 40, 200, 70, "aam", 0.0),        # 3 slices: unpipelined path
     ("slice4", 64, 64, 2, 4, 8, False, 30, 100, 50, "aam+var", 0.05),        # 16-level devices
     ("in4", 128, 128, 2, 2, 8, False, 33, 129, 31, "aam", 0.0),
+    # every first-order path: whole and ragged tiles, 1..4 column chunks of 64 per wave scan
+    ("aam2_c1", 64, 64, 4, 2, 8, True, 64, 256, 256, "aam2", 0.0),
+    ("aam2_ragged", 128, 128, 1, 2, 16, False, 70, 300, 100, "aam2", 0.0),
+    ("aam2_var_256", 256, 256, 1, 2, 16, True, 40, 520, 300, "aam2+var", 0.1),
+    ("aam2_narrow", 128, 48, 2, 2, 8, False, 33, 129, 100, "aam2+var", 0.05),
+    ("aam2_wide", 32, 208, 1, 4, 8, True, 20, 70, 420, "aam2", 0.0),
 ]
 
 
@@ -141,7 +147,9 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
     g = workloads.Gemm("t", K, N, M, signed, 1)
     W, X, dY = workloads.layer_tensors_np(g, seed=K + 3 * N)
     flags = (xo.INPUT_SIGNED if signed else 0)
+    ni = ni.split("+")
     flags |= xo.WIRE_AAM if "aam" in ni else 0
+    flags |= xo.WIRE_AAM2 if "aam2" in ni else 0
     flags |= xo.VARIATION if "var" in ni else 0
     flags |= xo.WIRE_PROFILE if "profile" in ni else 0
     profile = None

@@ -45,7 +45,7 @@ def test_struct_layout_matches(xb):
     dict(xbar_rows=60), dict(xbar_rows=8), dict(xbar_cols=512), dict(weight_bits=7, slice_bits=2),
     dict(weight_bits=32, slice_bits=2), dict(slice_bits=5, weight_bits=10), dict(input_bits=9),
     dict(input_bits=8, stream_bits=3), dict(stream_bits=0), dict(adc_bits=1), dict(adc_bits=17),
-    dict(flags=1 << 9), dict(flags=2 | 4), dict(r_min=0.0), dict(r_min=2e6), dict(r_max=float("nan")),
+    dict(flags=1 << 9), dict(flags=2 | 4), dict(flags=2 | 128), dict(flags=4 | 128), dict(r_min=0.0), dict(r_min=2e6), dict(r_max=float("nan")),
     dict(r_row=-1.0), dict(var_sigma=float("inf")), dict(adc_fs_fwd=0.0), dict(adc_fs_bwd=-3.0),
     dict(upd_noise_gamma=-1.0),
 ])
@@ -56,7 +56,7 @@ def test_validate_rejects(xb, kw):
 @pytest.mark.parametrize("kw", [
     dict(), dict(xbar_rows=128, xbar_cols=256, weight_bits=16), dict(slice_bits=1, weight_bits=16),
     dict(stream_bits=8), dict(slice_bits=4, weight_bits=16, adc_bits=16), dict(flags=127 & ~4),
-    dict(xbar_rows=16, xbar_cols=48),
+    dict(xbar_rows=16, xbar_cols=48), dict(flags=128 | 1 | 8 | 16 | 64),
 ])
 def test_validate_accepts(xb, kw):
     assert xb.validate(xb.make_config(**kw)) == 0
@@ -71,6 +71,8 @@ def test_size_queries(xb):
     bwd = 1 * 5 * 8 * 2 * 8 * 1024
     assert xb.planes_bytes(c, K, N) == fwd + bwd
     assert xb.planes_bytes(ideal, K, N) == (fwd + bwd) // 2
+    all_paths = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=xb.NI_WIRE_AAM2)
+    assert xb.planes_bytes(all_paths, K, N) == fwd + bwd + 16 * 8 * K * N + 4 * K * N      # scratch behind the planes
     assert xb.planes_bytes(c, 0, N) == 0 and xb.planes_bytes(c, K, -1) == 0
     for op in (xb.OP_FWD, xb.OP_BWD, xb.OP_UPDATE):
         small, big = xb.workspace_bytes(c, op, 64, K, N), xb.workspace_bytes(c, op, 6400, K, N)
