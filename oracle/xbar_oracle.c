@@ -161,6 +161,31 @@ static void device_pair(const xo_config* cfg, int sign, int digit, uint64_t k, u
     }
 }
 
+/* Conductances of every device before the wire model (after variation): G[S][2][K][N], array index
+ * 0 = positive.  Input of the circuit-level crossbar model (Sec. IV-A: non-ideal conductance matrix
+ * generator), whose linear solve lives in oracle/nodal.py.                                          */
+int xo_device_conductances(const xo_config* cfg, const float* W, int K, int N, float w_max, uint64_t step,
+                           double* G) {
+  const int S = cfg->weight_bits / cfg->slice_bits;
+  const int levels = (1 << cfg->slice_bits) - 1;
+  const double g_min = 1.0 / (double)cfg->r_max;
+  const double dg = (1.0 / (double)cfg->r_min - g_min) / (double)levels;
+  int32_t d[64];
+  if (S > 64) return -1;
+  for (int k = 0; k < K; ++k)
+    for (int n = 0; n < N; ++n) {
+      const int64_t q = xo_quantize_weight(W[(size_t)k * N + n], w_max, cfg->weight_bits);
+      xo_digits((uint64_t)(q < 0 ? -q : q), cfg->slice_bits, S, d);
+      for (int s = 0; s < S; ++s) {
+        double g[2];
+        device_pair(cfg, (q > 0) - (q < 0), d[s], (uint64_t)k, (uint64_t)n, s, S, N, step, g_min, dg, g);
+        G[(((size_t)s * 2 + 0) * K + k) * N + n] = g[0];
+        G[(((size_t)s * 2 + 1) * K + k) * N + n] = g[1];
+      }
+    }
+  return 0;
+}
+
 int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_t* k_idx,
               const int32_t* n_idx, int K_full, int N_full, float w_max, uint64_t step,
               const float* profile, double* U) {

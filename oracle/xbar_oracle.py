@@ -142,6 +142,17 @@ def planes(cfg, W, w_max, step=0, profile=None, k_idx=None, n_idx=None, K_full=N
     return U
 
 
+def device_conductances(cfg, W, w_max, step=0):
+    """G[S][2][K][N]: conductance of every device before the wire model (array 0 = positive)."""
+    W = _f32(W)
+    K, N = W.shape
+    G = np.zeros((n_slices(cfg), 2, K, N), dtype=np.float64)
+    rc = lib().xo_device_conductances(C.byref(cfg), _p(W, C.c_float), K, N, C.c_float(w_max), C.c_uint64(step),
+                                      _p(G, C.c_double))
+    assert rc == 0, rc
+    return G
+
+
 def _tiles(cfg, length, transposed):
     t = cfg.xbar_cols if transposed else cfg.xbar_rows
     return (length + t - 1) // t

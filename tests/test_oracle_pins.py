@@ -378,6 +378,63 @@ def test_nodal_solver_basics():
     assert np.allclose(nodal.effective_conductance(G, 1e-9, 1e-9), G, rtol=1e-6)
 
 
+def test_sparse_nodal_solver_equals_dense_and_is_reciprocal():
+    rng = np.random.default_rng(4)
+    for R, C in ((1, 1), (2, 5), (12, 9), (16, 16)):
+        G = rng.uniform(1e-6, 1e-4, size=(R, C))
+        G[rng.random(size=(R, C)) < 0.2] = 0.0          # absent devices
+        wires = (1.5, 4.6, 3.0, 2.0)
+        dense = nodal.effective_conductance(G, *wires)
+        sparse = nodal.effective_conductance_sparse(G, *wires)
+        assert np.abs(dense - sparse).max() <= 1e-12 * np.abs(dense).max()
+        # reciprocity of a passive network: drive the columns from the sense end and read the rows at
+        # the driver end (wires and terminations swap roles, both index directions reverse)
+        swapped = nodal.effective_conductance_sparse(G[::-1, ::-1].T, wires[1], wires[0], wires[3], wires[2])
+        assert np.abs(swapped[::-1, ::-1].T - sparse).max() <= 1e-12 * np.abs(sparse).max()
+
+
+def test_fcm_profile_closed_forms_and_layout(xo):
+    from oracle import fcm
+    # one device per tile: series connection
+    kw = dict(weight_bits=4, slice_bits=2, r_row=30.0, r_col=500.0, r_source=1e3, r_sense=2e3, r_min=1e4, r_max=1e5)
+    cfg = xo.make_config(xbar_rows=1, xbar_cols=1, **kw)
+    q = np.array([[7, -9], [0, 15]])
+    D = fcm.fcm_profile(cfg, (q / 15.0).astype(np.float32), 1.0)
+    rho = 1e3 + 30.0 + 500.0 + 2e3
+    for k in range(2):
+        for n in range(2):
+            for s in range(2):
+                dig = (abs(int(q[k, n])) >> (2 * s)) & 3
+                for pol in range(2):
+                    on = (q[k, n] > 0) if pol == 0 else (q[k, n] < 0)
+                    g = _device_g(cfg, dig if on else 0)
+                    assert abs(D[s, pol, k, n] - (1.0 - 1.0 / (1.0 + rho * g))) < 1e-12
+    # stored profile applied by the generator == exact circuit, tile by tile (ragged: 7 x 5 in 4 x 4 tiles)
+    rng = np.random.default_rng(8)
+    cfg = xo.make_config(xbar_rows=4, xbar_cols=4, flags=xo.WIRE_PROFILE, **kw)
+    q = rng.integers(-15, 16, size=(7, 5))
+    W = (q / 15.0).astype(np.float32)
+    D = fcm.fcm_profile(cfg, W, 1.0)
+    U = xo.planes(cfg, W, 1.0, profile=D.astype(np.float32))
+    dg = _device_g(cfg, 1) - _device_g(cfg, 0)
+    for s in range(2):
+        dig = (np.abs(q) >> (2 * s)) & 3
+        for k0 in range(0, 7, 4):
+            for n0 in range(0, 5, 4):
+                E = []
+                for sign in (1, -1):
+                    tile = np.zeros((4, 4))
+                    blk = np.where(sign * q > 0, dig, 0)[k0:k0 + 4, n0:n0 + 4]
+                    tile[:blk.shape[0], :blk.shape[1]] = _device_g(cfg, blk.astype(np.float64))
+                    E.append(nodal.effective_conductance(tile, 30.0, 500.0, 1e3, 2e3)[:blk.shape[0], :blk.shape[1]])
+                want = (E[0] - E[1]) / dg
+                got = U[s, k0:k0 + 4, n0:n0 + 4]
+                assert np.abs(got - want).max() < 1e-6     # profile passes through float32
+    # no wire resistance to speak of: no distortion
+    cfg0 = xo.make_config(xbar_rows=4, xbar_cols=4, weight_bits=4, slice_bits=2, r_row=1e-9, r_col=1e-9)
+    assert np.abs(fcm.fcm_profile(cfg0, W, 1.0)).max() < 1e-10
+
+
 def test_profile_mode_round_trip(xo):
     # D = (G_ideal - G_nonideal) / G_ideal taken from the analytical model reproduces its planes
     R, C, K, N, S = 8, 8, 20, 13, 4
