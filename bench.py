@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
     ap.add_argument("--all-paths", action="store_true",
                     help="wire model with every first-order path instead of the shortest path per device")
+    ap.add_argument("--fcm-refresh", action="store_true",
+                    help="also time one refresh of the circuit-level distortion profile of every layer "
+                         "(reported as fcm_refresh_ms; not part of the step)")
     ap.add_argument("--per-layer", action="store_true", help="print a per-layer table to stderr")
     ap.add_argument("--no-mfma-probe", action="store_true", help="skip the bare-MFMA sustained-rate probe")
     ap.add_argument("--calib-copy", action="store_true",
@@ -193,6 +196,21 @@ def main():
         roofline["sustained_mfma_tflops_bare_instruction"] = probe
     if args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal and not args.all_paths:
         roofline["traffic"] = VMM_TRAFFIC_BYTES_RESNET50_B64
+    fcm_refresh_ms = None
+    if args.fcm_refresh:
+        # one circuit-level solve of every layer (Sec. IV-D: done every L iterations, its profile reused between)
+        fcm_ws = torch.empty(max(xb.workspace_bytes(L["cfg"], xb.OP_FCM, 1, L["g"].K, L["g"].N) for L in layers),
+                             dtype=torch.uint8, device=device)
+        prof = torch.empty(max(S_w * 2 * L["g"].K * L["g"].N for L in layers), dtype=torch.float32, device=device)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for L in layers:
+            g = L["g"]
+            for rep in range(g.count):
+                xb.fcm_profile(L["cfg"], L["W"], L["w_max"], rep, fcm_ws, prof[:S_w * 2 * g.K * g.N].view(S_w, 2, g.K, g.N))
+        torch.cuda.synchronize()
+        fcm_refresh_ms = round((time.perf_counter() - t0) * 1e3, 1)
+        del fcm_ws, prof
     if args.per_layer:
         for (li, kind), (ms, fl, n) in sorted(per_layer.items()):
             g = layers[li]["g"]
@@ -242,6 +260,8 @@ def main():
         "logical_gmacs": round(tot["logical"] / (elapsed / args.steps) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu,
     }
+    if fcm_refresh_ms is not None:
+        line["fcm_refresh_ms"] = fcm_refresh_ms
     print(json.dumps(line))
 
 

@@ -60,6 +60,7 @@ extern "C" {
 #define XBAR_OP_FWD    0
 #define XBAR_OP_BWD    1
 #define XBAR_OP_UPDATE 2
+#define XBAR_OP_FCM    3   /* pass M = 1 */
 
 /* Parameter struct: plain data, caller-owned, read during the call only (Sec. IV lists the three
  * input groups; Sec. V and VI-B give the values used in the paper, quoted below as "paper:"). */
@@ -149,6 +150,24 @@ int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float*
 int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N,
                 float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes,
                 void* hip_stream);
+
+/*
+ * Circuit-level crossbar model (Sec. IV-A: Ohm's and Kirchhoff's laws solved for every crossbar
+ * instance; Sec. IV-D: its result kept as the distortion profile D = (G_ideal - G_nonideal) / G_ideal
+ * and reused for the following iterations).  For every crossbar tile, slice and array the exact
+ * linear map from row voltages to sensed column currents is computed (wire geometry as in the
+ * analytical model: driver at the column-0 end of every row wire through r_source, sense at the far
+ * end of every column wire through r_sense, r_row / r_col per cell; devices beyond K / N absent);
+ * entry (i, j) of that map is the non-ideal conductance of device (i, j).
+ *   W, w_max, step  as for xbar_tile (the variation draw of `step` is included when its flag is set;
+ *                   the wire flags of cfg are ignored)
+ *   profile         output [S_w][2][K][N] float, the input format of XBAR_NI_WIRE_PROFILE
+ *   ws              xbar_workspace_bytes(cfg, XBAR_OP_FCM, 1, K, N) bytes
+ * Iterative solve (conjugate gradients on the device currents, relative residual 1e-11, at most 500
+ * iterations per driven row); cost grows with R times the number of devices.
+ */
+int xbar_fcm_profile(const xbar_config* cfg, const float* W, int K, int N, float w_max, uint64_t step,
+                     float* profile, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Instrumentation for the benchmark (no part of the method): one-shot, per host thread.  The next

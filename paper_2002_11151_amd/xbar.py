@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(HERE, "libxbar.so")
 
 NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2 = (
     1, 2, 4, 8, 16, 32, 64, 128)
-OP_FWD, OP_BWD, OP_UPDATE = 0, 1, 2
+OP_FWD, OP_BWD, OP_UPDATE, OP_FCM = 0, 1, 2, 3
 ABI_VERSION = 1
 
 
@@ -74,6 +74,8 @@ _SIGNATURES = {
                            C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "xbar_trace_next_vmm": (None, [C.c_void_p, C.c_void_p]),
     "xbar_probe_mfma_rate": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_fcm_profile": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_uint64, C.c_void_p,
+                                   C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                               C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
@@ -199,3 +201,17 @@ def update(cfg, W, X, dY, w_max, grad_scale, lr, step=0, ws=None):
     _check(lib().xbar_update(C.byref(cfg), _dev(W), _dev(X), _dev(dY), M, K, N, w_max, grad_scale, lr, step,
                              C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return W
+
+
+def fcm_profile(cfg, W, w_max, step=0, ws=None, profile=None):
+    """xbar_fcm_profile: distortion profile [S_w][2][K][N] of the circuit-level model for W[K][N]."""
+    K, N = W.shape
+    nbytes = workspace_bytes(cfg, OP_FCM, 1, K, N)
+    if nbytes == 0:
+        _check(validate(cfg) or -2)
+    ws = _buffer(nbytes, ws, W.device)
+    if profile is None:
+        profile = torch.empty((cfg.weight_bits // cfg.slice_bits, 2, K, N), dtype=torch.float32, device=W.device)
+    _check(lib().xbar_fcm_profile(C.byref(cfg), _dev(W), K, N, w_max, step, _dev(profile), C.c_void_p(ws.data_ptr()),
+                                  ws.numel(), _stream()))
+    return profile

@@ -178,6 +178,42 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
         assert not np.array_equal(Y2, Yg)
 
 
+FCM_CASES = [
+    # name, R, C, wb, slb, K, N, r_min, var_sigma
+    ("small_ragged_var", 16, 16, 8, 2, 40, 50, 1e5, 0.1),
+    ("tiles_64", 64, 64, 8, 2, 130, 70, 1e5, 0.0),
+    ("one_full_tile", 128, 128, 2, 2, 128, 128, 1e5, 0.0),
+    ("wide_tile", 32, 208, 4, 4, 50, 230, 1e4, 0.05),
+    ("low_resistance", 32, 32, 4, 2, 64, 40, 1e3, 0.0),          # wires matter: many more solver iterations
+]
+
+
+@pytest.mark.parametrize("name,R,C,wb,slb,K,N,r_min,var_sigma", FCM_CASES)
+def test_circuit_model_profile(xo, xb, name, R, C, wb, slb, K, N, r_min, var_sigma):
+    from oracle import fcm
+    g = workloads.Gemm("t", K, N, 24, True, 1)
+    W, X, _ = workloads.layer_tensors_np(g, seed=K + 5 * N)
+    flags = xo.INPUT_SIGNED | (xo.VARIATION if var_sigma else 0)
+    kw = dict(xbar_rows=R, xbar_cols=C, weight_bits=wb, slice_bits=slb, input_bits=8, stream_bits=2, adc_bits=8,
+              var_sigma=var_sigma, seed=21, r_min=r_min, r_max=10 * r_min, r_source=2.0, r_sense=3.0,
+              adc_fs_fwd=workloads.adc_full_scale(R, 2, slb), adc_fs_bwd=workloads.adc_full_scale(C, 2, slb))
+    co, cg = both_configs(xo, xb, flags=flags, **kw)
+    w_max = float(np.abs(W).max())
+    Do = fcm.fcm_profile(co, W, w_max, step=5)
+    Dg = xb.fcm_profile(cg, dev(W), w_max, step=5)
+    torch.cuda.synchronize()
+    Dg = Dg.cpu().numpy()
+    assert Do.max() > (1e-2 if r_min < 1e5 else 1e-4)                   # there is distortion to compare
+    assert np.abs(Dg - Do).max() <= 2e-7                                # float32 storage of D
+    # interpolated use (Sec. IV-D): the stored profile feeds the generator on the following steps
+    co, cg = both_configs(xo, xb, flags=flags | xo.WIRE_PROFILE, **kw)
+    x_scale = float(np.abs(X).max())
+    Yo, codes_o = xo.fwd(co, W, X, w_max, x_scale, step=6, profile=Do.astype(np.float32), want_codes=True)
+    Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=6, profile=Dg)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(Yg, Yo) <= 1e-3
+
+
 UPDATE_CASES = [
     # M, K, N, flags
     (64, 256, 256, "ideal"), (64, 256, 256, "nl+noise"), (100, 147, 64, "nl+noise"), (3000, 70, 300, "nl"),

@@ -79,6 +79,10 @@ def test_size_queries(xb):
         assert 0 < small <= big
         assert xb.workspace_bytes(c, op, 0, K, N) == 0
     assert xb.workspace_bytes(c, 7, 64, K, N) == 0
+    # circuit-level model: 5 crossbar-sized fp64 vectors per resident block, at most 2048 blocks
+    items = 2 * 1 * 8 * 2                                   # (row tiles x column tiles) x slices x arrays
+    assert xb.workspace_bytes(c, xb.OP_FCM, 1, K, N) % (5 * 128 * 128 * 8) == 0
+    assert items * 5 * 128 * 128 * 8 <= xb.workspace_bytes(c, xb.OP_FCM, 1, K, N) <= 2048 * 5 * 128 * 128 * 8
     assert xb.workspace_bytes(c, xb.OP_FWD, 1 << 20, 1 << 12, 8) > 0      # activations may exceed 2^31 elements
     assert xb.workspace_bytes(c, xb.OP_FWD, 8, 1 << 16, 1 << 15) == 0     # K*N reaches 2^31
     assert xb.workspace_bytes(c, xb.OP_FWD, 1 << 30, 1 << 8, 8) == 0      # M*K reaches 2^38
@@ -108,6 +112,10 @@ def test_argument_checks_precede_any_device_work(xb):
     assert lib.xbar_update(C.byref(c), ok, ok, odd, 4, 64, 64, 1.0, 1.0, 0.1, 0, ok, big, None) == -3
     assert lib.xbar_update(C.byref(c), ok, ok, ok, 4, 64, 64, 1.0, 1.0, 0.1, 0, ok, 16, None) == -4
     assert lib.xbar_update(C.byref(c), ok, ok, ok, 4, 64, 64, -1.0, 1.0, 0.1, 0, ok, big, None) == -1
+    assert lib.xbar_fcm_profile(C.byref(c), ok, 64, 0, 1.0, 0, ok, ok, big, None) == -2
+    assert lib.xbar_fcm_profile(C.byref(c), ok, 64, 64, 1.0, 0, odd, ok, big, None) == -3
+    assert lib.xbar_fcm_profile(C.byref(c), ok, 64, 64, float("inf"), 0, ok, ok, big, None) == -1
+    assert lib.xbar_fcm_profile(C.byref(c), ok, 64, 64, 1.0, 0, ok, ok, 16, None) == -4
     for code in range(-6, 1):
         assert xb.strerror(code) and "unknown" not in xb.strerror(code)
     assert "unknown" in xb.strerror(-99)
