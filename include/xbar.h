@@ -152,6 +152,35 @@ int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* d
                 void* hip_stream);
 
 /*
+ * Convolution layers (Sec. IV: a layer's kernels are the columns of its weight matrix, one output
+ * position applies one input patch to the rows).  Activations are NHWC float tensors; the weight
+ * matrix W[K][N] has K = k_h k_w in_c rows ordered (kh, kw, c) with c fastest and N = output
+ * channels; M = batch x out_h x out_w.  The patches are gathered on the fly by the input stage (no
+ * im2col matrix is materialised in the forward pass or the update); positions outside the image read 0.
+ *   xbar_conv_fwd     Y[batch][out_h][out_w][N]  from X[batch][in_h][in_w][in_c]; codes as xbar_fwd
+ *   xbar_conv_bwd     dX (shape of X) from dY (shape of Y): xbar_bwd gives the error of every patch
+ *                     element into the workspace, every input pixel then adds up, in fp32, the errors
+ *                     of the patches it belongs to (a digital accumulation)
+ *   xbar_conv_update  W in place from X and dY, as xbar_update on the patch matrix
+ * out_h must equal (in_h + 2 pad - k_h) / stride + 1 (likewise out_w), else XBAR_ESHAPE.
+ * xbar_conv_workspace_bytes: op = XBAR_OP_FWD / XBAR_OP_BWD / XBAR_OP_UPDATE.
+ */
+typedef struct xbar_conv_geom {
+  int32_t batch, in_h, in_w, in_c;
+  int32_t k_h, k_w, stride, pad;
+  int32_t out_h, out_w;
+} xbar_conv_geom;
+
+size_t xbar_conv_workspace_bytes(const xbar_config* cfg, int op, const xbar_conv_geom* geom, int N);
+int xbar_conv_fwd(const xbar_config* cfg, const void* planes, const float* X, float* Y, const xbar_conv_geom* geom,
+                  int N, float w_max, float x_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream);
+int xbar_conv_bwd(const xbar_config* cfg, const void* planes, const float* dY, float* dX, const xbar_conv_geom* geom,
+                  int N, float w_max, float g_scale, void* ws, size_t ws_bytes, void* hip_stream);
+int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const float* dY, const xbar_conv_geom* geom,
+                     int N, float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes,
+                     void* hip_stream);
+
+/*
  * Circuit-level crossbar model (Sec. IV-A: Ohm's and Kirchhoff's laws solved for every crossbar
  * instance; Sec. IV-D: its result kept as the distortion profile D = (G_ideal - G_nonideal) / G_ideal
  * and reused for the following iterations).  For every crossbar tile, slice and array the exact

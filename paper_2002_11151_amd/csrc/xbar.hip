@@ -420,14 +420,45 @@ __global__ __launch_bounds__(256) void wire_cols_kernel(WireArgs a) {
 // ---------------------------------------------------------------------------------------------
 // input quantiser (Sec. IV: inputs are scaled and sent to the DAC)
 // ---------------------------------------------------------------------------------------------
+// Convolution as a crossbar layer (Sec. IV: the kernels of a layer are unrolled into the columns of
+// the weight matrix, every output position applies one input patch to the rows): input X in NHWC,
+// row m = (b, oh, ow) of the layer's input matrix is the patch of that output position and its
+// contraction index is l = (kh KW + kw) C + c.  Positions outside the image read 0 V.
+struct ConvGeom {
+  int H, W, C, KH, KW, stride, pad, OH, OW;
+};
+
+struct ConvRow {       // patch of one output position: element (kh, kw, c) is X[off + (kh W + kw) C + c]
+  long long off;
+  int ih0, iw0;
+};
+
+__device__ __forceinline__ ConvRow conv_row(const ConvGeom& g, int m) {
+  const int ow = m % g.OW, t = m / g.OW;
+  const int oh = t % g.OH, b = t / g.OH;
+  ConvRow r;
+  r.ih0 = oh * g.stride - g.pad;
+  r.iw0 = ow * g.stride - g.pad;
+  r.off = (((long long)b * g.H + r.ih0) * g.W + r.iw0) * g.C;
+  return r;
+}
+
+__device__ __forceinline__ float conv_fetch(const float* X, const ConvGeom& g, const ConvRow& r, int kh, int kw, int c) {
+  const int ih = r.ih0 + kh, iw = r.iw0 + kw;
+  if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return 0.0f;
+  return X[r.off + ((long long)kh * g.W + kw) * g.C + c];
+}
+
 struct QuantArgs {
   const float* X;
   uint8_t* A;        // [phase][MP][T][ks][64 lanes][8 bytes]
   int M, L, MP, T, ks, tile, P, input_bits;
   float scale;
   long long n_threads;
+  ConvGeom conv;     // used by the CONV instantiation only
 };
 
+template <bool CONV>
 __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
   const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (tid >= a.n_threads) return;
@@ -452,7 +483,21 @@ __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
     float x[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = 0.0f;
-    if (m < a.M) {
+    if (CONV) {
+      if (m < a.M) {
+        const ConvRow cr = conv_row(a.conv, m);
+        int c = l0 % a.conv.C, kk = l0 / a.conv.C;
+        int kw = kk % a.conv.KW, kh = kk / a.conv.KW;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          if (l0 + e < lend) x[e] = conv_fetch(a.X, a.conv, cr, kh, kw, c);
+          if (++c == a.conv.C) {
+            c = 0;
+            if (++kw == a.conv.KW) { kw = 0; ++kh; }
+          }
+        }
+      }
+    } else if (m < a.M) {
       const float* row = a.X + (size_t)m * a.L;
       if ((a.L & 3) == 0 && l0 + 8 <= lend) {
         const float4 v0 = *reinterpret_cast<const float4*>(row + l0);
@@ -833,10 +878,11 @@ __global__ __launch_bounds__(256) void vmm_finish_kernel(FinishArgs a) {
 // update model (Sec. IV-C)
 // ---------------------------------------------------------------------------------------------
 struct GradArgs {
-  const float* X;   // [M][K]
+  const float* X;   // [M][K], or the NHWC image with CONV
   const float* D;   // [M][N]
   float* part;      // [mchunks][K][N]
   int M, K, N, KB, NB, m_per_chunk;
+  ConvGeom conv;
 };
 
 constexpr int kGradMS = 16;   // batch rows per LDS stage
@@ -844,10 +890,11 @@ constexpr int kGradMS = 16;   // batch rows per LDS stage
 // 128 x 128 tile of X^T dY per block, 4 waves as 2 x 2, each wave 64 x 64 = 2 x 2 MFMA tiles.
 // When the layer has at most 64 rows (SPLIT_K) or columns (SPLIT_N) the waves that would work on
 // padding take a share of the batch rows of every stage instead and write a partial sum of their own.
-template <bool SPLIT_K, bool SPLIT_N>
+template <bool SPLIT_K, bool SPLIT_N, bool CONV>
 __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   __shared__ float xs[kGradMS][128];
   __shared__ float ds[kGradMS][128];
+  __shared__ ConvRow crow[2][kGradMS];               // patches of the rows of the stage being fetched
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wk = wave >> 1, wn = wave & 1;
   const int kb = blockIdx.x % a.KB, nb = blockIdx.x / a.KB;
@@ -866,18 +913,34 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   float px[8], pd[8];
-  auto prefetch = [&](int m0) {
+  // this thread always fetches contraction column k0 + (tid & 127): its kernel position is fixed
+  int ckh = 0, ckw = 0, cc = 0;
+  if (CONV) {
+    const int k = min(k0 + (tid & 127), a.K - 1);
+    cc = k % a.conv.C;
+    ckw = (k / a.conv.C) % a.conv.KW;
+    ckh = (k / a.conv.C) / a.conv.KW;
+  }
+  int stage = 0;
+  auto stage_rows = [&](int m0, int buf) {            // CONV: the first threads decompose the stage's rows
+    if (CONV && tid < kGradMS) crow[buf][tid] = conv_row(a.conv, min(m0 + tid, a.M - 1));
+  };
+  auto prefetch = [&](int m0, int buf) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int i = tid + e * 256;
       const int row = i >> 7, col = i & 127;
       const int m = m0 + row;
-      px[e] = (m < m_end && k0 + col < a.K) ? a.X[(size_t)m * a.K + k0 + col] : 0.0f;
+      if (CONV) px[e] = (m < m_end && k0 + col < a.K) ? conv_fetch(a.X, a.conv, crow[buf][row], ckh, ckw, cc) : 0.0f;
+      else px[e] = (m < m_end && k0 + col < a.K) ? a.X[(size_t)m * a.K + k0 + col] : 0.0f;
       pd[e] = (m < m_end && n0 + col < a.N) ? a.D[(size_t)m * a.N + n0 + col] : 0.0f;
     }
   };
-  prefetch(m_begin);
-  for (int m0 = m_begin; m0 < m_end; m0 += kGradMS) {
+  stage_rows(m_begin, 0);
+  if (CONV) __syncthreads();
+  prefetch(m_begin, 0);
+  for (int m0 = m_begin; m0 < m_end; m0 += kGradMS, stage ^= 1) {
+    if (m0 + kGradMS < m_end) stage_rows(m0 + kGradMS, stage ^ 1);
     __syncthreads();
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -886,7 +949,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       ds[i >> 7][i & 127] = pd[e];
     }
     __syncthreads();
-    if (m0 + kGradMS < m_end) prefetch(m0 + kGradMS);
+    if (m0 + kGradMS < m_end) prefetch(m0 + kGradMS, stage ^ 1);
 #pragma unroll
     for (int q = 0; q < kGradMS / PARTS; q += 2) {
       const int row = share * (kGradMS / PARTS) + q + (lane >> 5);
@@ -911,6 +974,43 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
         const int n = n0 + noff + j * 32 + (lane & 31);
         if (k < a.K && n < a.N) out[(size_t)k * a.N + n] = acc[i][j][r];
       }
+}
+
+// Backward pass of a convolution layer: the crossbars give the error of every patch element
+// (dXcol[M][K]); an input pixel collects, digitally, the errors of every patch it belongs to.
+struct Col2imArgs {
+  const float* col;  // [M][K]
+  float* dX;         // NHWC
+  ConvGeom conv;
+  int B, K;
+  long long n;
+};
+
+__global__ __launch_bounds__(256) void col2im_kernel(Col2imArgs a) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (t >= a.n) return;
+  const ConvGeom& g = a.conv;
+  const int c = (int)(t % g.C);
+  long long u = t / g.C;
+  const int iw = (int)(u % g.W);
+  u /= g.W;
+  const int ih = (int)(u % g.H), b = (int)(u / g.H);
+  float sum = 0.0f;
+  for (int kh = 0; kh < g.KH; ++kh) {
+    const int oy = ih + g.pad - kh;
+    if (oy < 0 || oy % g.stride) continue;
+    const int oh = oy / g.stride;
+    if (oh >= g.OH) continue;
+    for (int kw = 0; kw < g.KW; ++kw) {
+      const int ox = iw + g.pad - kw;
+      if (ox < 0 || ox % g.stride) continue;
+      const int ow = ox / g.stride;
+      if (ow >= g.OW) continue;
+      const long long m = ((long long)b * g.OH + oh) * g.OW + ow;
+      sum += a.col[m * a.K + (kh * g.KW + kw) * g.C + c];
+    }
+  }
+  a.dX[t] = sum;
 }
 
 struct WriteArgs {
@@ -1544,7 +1644,8 @@ hipError_t launch_vmm(const VmmArgs& a, const VmmPlan& p, int terms, bool codes,
 }
 
 int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* out, int M, int K, int N,
-            float w_max, float in_scale, void* ws, size_t ws_bytes, int16_t* codes, void* stream, bool transposed) {
+            float w_max, float in_scale, void* ws, size_t ws_bytes, int16_t* codes, void* stream, bool transposed,
+            const ConvGeom* conv = nullptr) {
   int rc = xbar_config_validate(cfg);
   if (rc) return rc;
   if ((rc = check_shape(M, K, N))) return rc;
@@ -1571,7 +1672,12 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   qa.input_bits = cfg->input_bits;
   qa.scale = in_scale;
   qa.n_threads = (long long)p.MP * p.g.T * ((p.g.ks + 1) / 2) * 64;
-  hipLaunchKernelGGL(quantize_input_kernel, dim3((unsigned)((qa.n_threads + 255) / 256)), dim3(256), 0, st, qa);
+  if (conv) {
+    qa.conv = *conv;
+    hipLaunchKernelGGL(quantize_input_kernel<true>, dim3((unsigned)((qa.n_threads + 255) / 256)), dim3(256), 0, st, qa);
+  } else {
+    hipLaunchKernelGGL(quantize_input_kernel<false>, dim3((unsigned)((qa.n_threads + 255) / 256)), dim3(256), 0, st, qa);
+  }
   if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
 
   const PlaneGeom gf = plane_geom(cfg, d, K, N, false);
@@ -1612,6 +1718,66 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
     hipLaunchKernelGGL(vmm_finish_kernel, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   }
+  return XBAR_OK;
+}
+
+// Checks a convolution geometry and derives the layer's matrix shape: M = batch x output positions,
+// K = kernel height x kernel width x input channels.
+int conv_dims(const xbar_conv_geom* q, ConvGeom* g, int* M, int* K) {
+  if (!q) return XBAR_EINVAL;
+  if (q->batch <= 0 || q->in_h <= 0 || q->in_w <= 0 || q->in_c <= 0 || q->k_h <= 0 || q->k_w <= 0 || q->stride <= 0 ||
+      q->pad < 0 || q->out_h <= 0 || q->out_w <= 0)
+    return XBAR_ESHAPE;
+  if (q->in_h + 2 * q->pad < q->k_h || q->in_w + 2 * q->pad < q->k_w) return XBAR_ESHAPE;
+  if (q->out_h != (q->in_h + 2 * q->pad - q->k_h) / q->stride + 1 ||
+      q->out_w != (q->in_w + 2 * q->pad - q->k_w) / q->stride + 1)
+    return XBAR_ESHAPE;
+  const long long m = (long long)q->batch * q->out_h * q->out_w, k = (long long)q->k_h * q->k_w * q->in_c;
+  const long long pixels = (long long)q->batch * q->in_h * q->in_w * q->in_c;
+  if (m >= (1ll << 31) || k >= (1ll << 31) || pixels >= (1ll << 38)) return XBAR_ESHAPE;
+  g->H = q->in_h; g->W = q->in_w; g->C = q->in_c; g->KH = q->k_h; g->KW = q->k_w;
+  g->stride = q->stride; g->pad = q->pad; g->OH = q->out_h; g->OW = q->out_w;
+  *M = (int)m;
+  *K = (int)k;
+  return XBAR_OK;
+}
+
+int run_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
+               float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream, const ConvGeom* conv) {
+  int rc = xbar_config_validate(cfg);
+  if (rc) return rc;
+  if ((rc = check_shape(M, K, N))) return rc;
+  if (!aligned16(W) || !aligned16(X) || !aligned16(dY) || !aligned16(ws)) return XBAR_EALIGN;
+  if (!finite_pos(w_max) || !std::isfinite(grad_scale) || !std::isfinite(lr)) return XBAR_EINVAL;
+  const UpdPlan p = plan_update(M, K, N);
+  if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  GradArgs g;
+  g.X = X; g.D = dY; g.part = reinterpret_cast<float*>(ws);
+  g.M = M; g.K = K; g.N = N; g.KB = p.KB; g.NB = p.NB; g.m_per_chunk = p.m_per_chunk;
+  {
+    const dim3 grid((unsigned)(p.KB * p.NB), (unsigned)p.mchunks), block(256);
+    if (conv) {
+      g.conv = *conv;
+      if (K <= 64 && N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, true, true>), grid, block, 0, st, g);
+      else if (K <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, false, true>), grid, block, 0, st, g);
+      else if (N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<false, true, true>), grid, block, 0, st, g);
+      else hipLaunchKernelGGL((grad_gemm_kernel<false, false, true>), grid, block, 0, st, g);
+    } else {
+      if (K <= 64 && N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, true, false>), grid, block, 0, st, g);
+      else if (K <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, false, false>), grid, block, 0, st, g);
+      else if (N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<false, true, false>), grid, block, 0, st, g);
+      else hipLaunchKernelGGL((grad_gemm_kernel<false, false, false>), grid, block, 0, st, g);
+    }
+  }
+  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+  WriteArgs w;
+  w.W = W; w.part = g.part; w.n = (long long)K * N; w.mchunks = p.mchunks * p.parts; w.flags = cfg->flags;
+  w.w_max = (double)w_max; w.grad_scale = (double)grad_scale; w.lr = (double)lr;
+  w.v = (double)cfg->upd_nl_v; w.gamma = (double)cfg->upd_noise_gamma;
+  w.seed = cfg->seed; w.step = step;
+  hipLaunchKernelGGL(update_write_kernel, dim3((unsigned)((w.n + 31) / 32)), dim3(256), 0, st, w);
+  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   return XBAR_OK;
 }
 
@@ -1786,33 +1952,58 @@ int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float*
 
 int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
                 float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream) {
-  int rc = xbar_config_validate(cfg);
+  return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream, nullptr);
+}
+
+size_t xbar_conv_workspace_bytes(const xbar_config* cfg, int op, const xbar_conv_geom* geom, int N) {
+  ConvGeom g;
+  int M, K;
+  if (xbar_config_validate(cfg) || conv_dims(geom, &g, &M, &K) || check_shape(M, K, N)) return 0;
+  const Derived d = derive(cfg);
+  if (op == XBAR_OP_FWD) return plan_vmm(cfg, d, M, K, N, false).ws_bytes;
+  if (op == XBAR_OP_BWD) return plan_vmm(cfg, d, M, K, N, true).ws_bytes + align256((size_t)M * K * sizeof(float));
+  if (op == XBAR_OP_UPDATE) return plan_update(M, K, N).ws_bytes;
+  return 0;
+}
+
+int xbar_conv_fwd(const xbar_config* cfg, const void* planes, const float* X, float* Y, const xbar_conv_geom* geom,
+                  int N, float w_max, float x_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream) {
+  ConvGeom g;
+  int M, K;
+  const int rc = conv_dims(geom, &g, &M, &K);
   if (rc) return rc;
+  return run_vmm(cfg, planes, X, Y, M, K, N, w_max, x_scale, ws, ws_bytes, codes, hip_stream, false, &g);
+}
+
+int xbar_conv_bwd(const xbar_config* cfg, const void* planes, const float* dY, float* dX, const xbar_conv_geom* geom,
+                  int N, float w_max, float g_scale, void* ws, size_t ws_bytes, void* hip_stream) {
+  ConvGeom g;
+  int M, K;
+  int rc = conv_dims(geom, &g, &M, &K);
+  if (rc) return rc;
+  if ((rc = xbar_config_validate(cfg))) return rc;
   if ((rc = check_shape(M, K, N))) return rc;
-  if (!aligned16(W) || !aligned16(X) || !aligned16(dY) || !aligned16(ws)) return XBAR_EALIGN;
-  if (!finite_pos(w_max) || !std::isfinite(grad_scale) || !std::isfinite(lr)) return XBAR_EINVAL;
-  const UpdPlan p = plan_update(M, K, N);
-  if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
-  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  GradArgs g;
-  g.X = X; g.D = dY; g.part = reinterpret_cast<float*>(ws);
-  g.M = M; g.K = K; g.N = N; g.KB = p.KB; g.NB = p.NB; g.m_per_chunk = p.m_per_chunk;
-  {
-    const dim3 grid((unsigned)(p.KB * p.NB), (unsigned)p.mchunks), block(256);
-    if (K <= 64 && N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, true>), grid, block, 0, st, g);
-    else if (K <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, false>), grid, block, 0, st, g);
-    else if (N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<false, true>), grid, block, 0, st, g);
-    else hipLaunchKernelGGL((grad_gemm_kernel<false, false>), grid, block, 0, st, g);
-  }
-  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
-  WriteArgs w;
-  w.W = W; w.part = g.part; w.n = (long long)K * N; w.mchunks = p.mchunks * p.parts; w.flags = cfg->flags;
-  w.w_max = (double)w_max; w.grad_scale = (double)grad_scale; w.lr = (double)lr;
-  w.v = (double)cfg->upd_nl_v; w.gamma = (double)cfg->upd_noise_gamma;
-  w.seed = cfg->seed; w.step = step;
-  hipLaunchKernelGGL(update_write_kernel, dim3((unsigned)((w.n + 31) / 32)), dim3(256), 0, st, w);
-  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
-  return XBAR_OK;
+  if (!aligned16(dX) || !aligned16(ws)) return XBAR_EALIGN;
+  const size_t need = xbar_conv_workspace_bytes(cfg, XBAR_OP_BWD, geom, N);
+  if (ws_bytes < need) return XBAR_EWORKSPACE;
+  const size_t col_bytes = align256((size_t)M * K * sizeof(float));
+  float* col = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + (need - col_bytes));
+  if ((rc = run_vmm(cfg, planes, dY, col, M, K, N, w_max, g_scale, ws, need - col_bytes, nullptr, hip_stream, true))) return rc;
+  Col2imArgs c;
+  c.col = col; c.dX = dX; c.conv = g; c.B = geom->batch; c.K = K;
+  c.n = (long long)geom->batch * g.H * g.W * g.C;
+  hipLaunchKernelGGL(col2im_kernel, dim3((unsigned)((c.n + 255) / 256)), dim3(256), 0,
+                     reinterpret_cast<hipStream_t>(hip_stream), c);
+  return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
+}
+
+int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const float* dY, const xbar_conv_geom* geom, int N,
+                     float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream) {
+  ConvGeom g;
+  int M, K;
+  const int rc = conv_dims(geom, &g, &M, &K);
+  if (rc) return rc;
+  return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream, &g);
 }
 
 int xbar_fcm_profile(const xbar_config* cfg, const float* W, int K, int N, float w_max, uint64_t step, float* profile,

@@ -39,6 +39,18 @@ class Config(C.Structure):
     ]
 
 
+class ConvGeom(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("in_h", C.c_int32), ("in_w", C.c_int32), ("in_c", C.c_int32),
+                ("k_h", C.c_int32), ("k_w", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
+                ("out_h", C.c_int32), ("out_w", C.c_int32)]
+
+
+def conv_geom(batch, in_h, in_w, in_c, k_h, k_w, stride=1, pad=0):
+    """xbar_conv_geom with the output size filled in."""
+    return ConvGeom(batch, in_h, in_w, in_c, k_h, k_w, stride, pad,
+                    (in_h + 2 * pad - k_h) // stride + 1, (in_w + 2 * pad - k_w) // stride + 1)
+
+
 def make_config(**kw):
     """Parameter struct with the values the paper states (Sec. V, Sec. VI-B) unless overridden."""
     c = Config()
@@ -76,6 +88,13 @@ _SIGNATURES = {
     "xbar_probe_mfma_rate": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_fcm_profile": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_uint64, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_conv_workspace_bytes": (C.c_size_t, [C.POINTER(Config), C.c_int, C.POINTER(ConvGeom), C.c_int]),
+    "xbar_conv_fwd": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_int,
+                                C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "xbar_conv_bwd": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_int,
+                                C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_conv_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_int,
+                                   C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                               C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
@@ -215,3 +234,51 @@ def fcm_profile(cfg, W, w_max, step=0, ws=None, profile=None):
     _check(lib().xbar_fcm_profile(C.byref(cfg), _dev(W), K, N, w_max, step, _dev(profile), C.c_void_p(ws.data_ptr()),
                                   ws.numel(), _stream()))
     return profile
+
+
+def conv_workspace_bytes(cfg, op, geom, N):
+    return lib().xbar_conv_workspace_bytes(C.byref(cfg), op, C.byref(geom), N)
+
+
+def _conv_ws(cfg, op, geom, N, ws, device):
+    nbytes = conv_workspace_bytes(cfg, op, geom, N)
+    if nbytes == 0:
+        _check(validate(cfg) or -2)
+    return _buffer(nbytes, ws, device)
+
+
+def conv_fwd(cfg, planes, X, geom, N, w_max, x_scale, ws=None, out=None, want_codes=False):
+    """xbar_conv_fwd: Y[batch][out_h][out_w][N] from the NHWC tensor X."""
+    ws = _conv_ws(cfg, OP_FWD, geom, N, ws, X.device)
+    if out is None:
+        out = torch.empty((geom.batch, geom.out_h, geom.out_w, N), dtype=torch.float32, device=X.device)
+    codes = None
+    if want_codes:
+        P = 2 if cfg.flags & INPUT_SIGNED else 1
+        K, M = geom.k_h * geom.k_w * geom.in_c, geom.batch * geom.out_h * geom.out_w
+        T = (K + cfg.xbar_rows - 1) // cfg.xbar_rows
+        codes = torch.zeros((P, cfg.input_bits // cfg.stream_bits, cfg.weight_bits // cfg.slice_bits, T, M, N),
+                            dtype=torch.int16, device=X.device)
+    _check(lib().xbar_conv_fwd(C.byref(cfg), C.c_void_p(planes.data_ptr()), _dev(X), _dev(out), C.byref(geom), N, w_max,
+                               x_scale, C.c_void_p(ws.data_ptr()), ws.numel(),
+                               None if codes is None else C.c_void_p(codes.data_ptr()), _stream()))
+    return (out, codes) if want_codes else out
+
+
+def conv_bwd(cfg, planes, dY, geom, N, w_max, g_scale, ws=None, out=None):
+    """xbar_conv_bwd: dX (NHWC, shape of the layer input) from dY[batch][out_h][out_w][N]."""
+    ws = _conv_ws(cfg, OP_BWD, geom, N, ws, dY.device)
+    if out is None:
+        out = torch.empty((geom.batch, geom.in_h, geom.in_w, geom.in_c), dtype=torch.float32, device=dY.device)
+    _check(lib().xbar_conv_bwd(C.byref(cfg), C.c_void_p(planes.data_ptr()), _dev(dY), _dev(out), C.byref(geom), N, w_max,
+                               g_scale, C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return out
+
+
+def conv_update(cfg, W, X, dY, geom, w_max, grad_scale, lr, step=0, ws=None):
+    """xbar_conv_update: W[k_h k_w in_c][N] in place from the NHWC tensors X and dY."""
+    N = W.shape[1]
+    ws = _conv_ws(cfg, OP_UPDATE, geom, N, ws, W.device)
+    _check(lib().xbar_conv_update(C.byref(cfg), _dev(W), _dev(X), _dev(dY), C.byref(geom), N, w_max, grad_scale, lr, step,
+                                  C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return W

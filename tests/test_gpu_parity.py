@@ -240,6 +240,58 @@ def test_update(xo, xb, M, K, N, kind):
     assert np.abs(Wg).max() <= w_max
 
 
+CONV_CASES = [
+    # name, B, H, W, C, k, stride, pad, N, R(=C of the crossbar), stream bits
+    ("3x3_same", 3, 10, 9, 16, 3, 1, 1, 40, 64, 2),
+    ("3x3_stride2", 2, 11, 11, 24, 3, 2, 1, 33, 128, 1),
+    ("1x1_downsample", 2, 8, 8, 70, 1, 2, 0, 96, 64, 4),
+    ("7x7_rgb", 2, 20, 18, 3, 7, 2, 3, 16, 128, 2),              # K = 147: channels do not fill a chunk of 8
+    ("2x2_nopad", 1, 6, 6, 5, 2, 1, 0, 7, 64, 2),
+]
+
+
+@pytest.mark.parametrize("name,B,H,W,C,k,stride,pad,N,R,sb", CONV_CASES)
+def test_convolution_layer(xo, xb, name, B, H, W, C, k, stride, pad, N, R, sb):
+    from oracle import conv
+    rng = np.random.default_rng(B + 10 * H + 100 * C)
+    K = k * k * C
+    X = np.maximum(rng.normal(size=(B, H, W, C)), -0.5).astype(np.float32)        # signed activations
+    Wm = (rng.standard_t(4, size=(K, N)) * 0.05).astype(np.float32)
+    OH, OW = conv.out_size(H, k, stride, pad), conv.out_size(W, k, stride, pad)
+    dY = (rng.normal(size=(B, OH, OW, N)) * 1e-2).astype(np.float32)
+    kw = dict(xbar_rows=R, xbar_cols=R, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=sb, adc_bits=8,
+              flags=xo.INPUT_SIGNED | xo.WIRE_AAM | xo.UPD_NL | xo.UPD_NOISE, seed=5,
+              adc_fs_fwd=workloads.adc_full_scale(R, sb, 2), adc_fs_bwd=workloads.adc_full_scale(R, sb, 2))
+    co, cg = both_configs(xo, xb, **kw)
+    w_max, x_scale, g_scale = float(np.abs(Wm).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    geom = xb.conv_geom(B, H, W, C, k, k, stride, pad)
+    assert (geom.out_h, geom.out_w) == (OH, OW)
+    planes = xb.tile(cg, dev(Wm), w_max, 2)
+    # forward: the oracle sees the patch matrix, the library gathers it from the image
+    cols = conv.im2col(X, k, k, stride, pad)
+    Yo, codes_o = xo.fwd(co, Wm, cols, w_max, x_scale, step=2, want_codes=True)
+    Yg, codes_g = xb.conv_fwd(cg, planes, dev(X), geom, N, w_max, x_scale, want_codes=True)
+    torch.cuda.synchronize()
+    check_codes(codes_g.cpu().numpy(), codes_o)
+    assert rel_l2(Yg.cpu().numpy().reshape(-1, N), Yo) <= 1e-3
+    # backward: patch errors from the crossbars, then the digital accumulation over overlapping patches
+    dcols_o = xo.bwd(co, Wm, dY.reshape(-1, N), w_max, g_scale, step=2)
+    dXo = conv.col2im(dcols_o, X.shape, k, k, stride, pad)
+    dXg = xb.conv_bwd(cg, planes, dev(dY), geom, N, w_max, g_scale)
+    torch.cuda.synchronize()
+    assert dXg.shape == X.shape
+    assert rel_l2(dXg.cpu().numpy(), dXo) <= 1e-3
+    # update from the image
+    lr, gs = 0.01, 1.0 / w_max
+    Wo = xo.update(co, Wm, cols, dY.reshape(-1, N), w_max, gs, lr, step=9)
+    Wg = dev(Wm.copy())
+    xb.conv_update(cg, Wg, dev(X), dev(dY), geom, w_max, gs, lr, step=9)
+    torch.cuda.synchronize()
+    Wg = Wg.cpu().numpy()
+    assert rel_l2(Wg - Wm, Wo - Wm) <= 1e-3
+    assert np.abs(Wg - Wo).max() <= 1e-5 * w_max
+
+
 def test_config1_fc256_step(xo, xb):
     """First benchmark configuration, whole: one fwd + bwd + update step of a 256x256 layer."""
     g = workloads.fc256_gemms(64)[0]

@@ -116,6 +116,21 @@ def test_argument_checks_precede_any_device_work(xb):
     assert lib.xbar_fcm_profile(C.byref(c), ok, 64, 64, 1.0, 0, odd, ok, big, None) == -3
     assert lib.xbar_fcm_profile(C.byref(c), ok, 64, 64, float("inf"), 0, ok, ok, big, None) == -1
     assert lib.xbar_fcm_profile(C.byref(c), ok, 64, 64, 1.0, 0, ok, ok, 16, None) == -4
+    geom = xb.conv_geom(2, 8, 8, 4, 3, 3, 1, 1)
+    assert lib.xbar_conv_fwd(C.byref(c), ok, ok, ok, None, 16, 1.0, 1.0, ok, big, None, None) == -1
+    assert lib.xbar_conv_fwd(C.byref(c), ok, odd, ok, C.byref(geom), 16, 1.0, 1.0, ok, big, None, None) == -3
+    assert lib.xbar_conv_fwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, 16, None, None) == -4
+    assert lib.xbar_conv_bwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, 16, None) == -4
+    assert lib.xbar_conv_update(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, 0.1, 0, ok, 16, None) == -4
+    assert xb.conv_workspace_bytes(c, xb.OP_BWD, geom, 16) > xb.conv_workspace_bytes(c, xb.OP_FWD, geom, 16) > 0
+    geom.out_h = 9                                             # not what stride and padding give
+    assert xb.conv_workspace_bytes(c, xb.OP_FWD, geom, 16) == 0
+    assert lib.xbar_conv_fwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, big, None, None) == -2
+    geom = xb.conv_geom(2, 8, 8, 4, 3, 3, 1, 1)
+    geom.pad = -1
+    assert lib.xbar_conv_fwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, big, None, None) == -2
+    geom = xb.conv_geom(2, 2, 2, 4, 5, 5, 1, 0)                # kernel larger than the image
+    assert lib.xbar_conv_bwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, big, None) == -2
     for code in range(-6, 1):
         assert xb.strerror(code) and "unknown" not in xb.strerror(code)
     assert "unknown" in xb.strerror(-99)

@@ -651,3 +651,28 @@ def test_update_noise_statistics(xo):
     sub = xo.update(cfg, W[np.ix_(k_idx, n_idx)], X[:, k_idx], dY[:, n_idx], 1.0, gs, lr, step=4,
                     k_idx=k_idx, n_idx=n_idx, N_full=N)
     assert np.array_equal(sub, W2[np.ix_(k_idx, n_idx)])
+
+
+# ------------------------------------------------------------------------------------------------
+# convolution layers: patch gathering and its adjoint
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,H,W,C,k,stride,pad,N", [(2, 7, 6, 3, 3, 1, 1, 5), (1, 9, 9, 4, 3, 2, 1, 2),
+                                                    (2, 8, 8, 5, 1, 2, 0, 3), (1, 11, 10, 3, 7, 2, 3, 4)])
+def test_im2col_matmul_is_the_library_convolution(B, H, W, C, k, stride, pad, N):
+    import torch
+    from oracle import conv
+    rng = np.random.default_rng(B * 100 + H)
+    X = rng.normal(size=(B, H, W, C))
+    Wm = rng.normal(size=(k * k * C, N))                    # rows ordered (kh, kw, c)
+    Y = conv.im2col(X, k, k, stride, pad) @ Wm
+    OH, OW = conv.out_size(H, k, stride, pad), conv.out_size(W, k, stride, pad)
+    w_torch = torch.from_numpy(Wm.reshape(k, k, C, N)).permute(3, 2, 0, 1)         # [N][C][kh][kw]
+    ref = torch.nn.functional.conv2d(torch.from_numpy(X).permute(0, 3, 1, 2), w_torch, stride=stride, padding=pad)
+    assert np.allclose(Y.reshape(B, OH, OW, N), ref.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
+    # col2im is the adjoint: <im2col(x), y> == <x, col2im(y)>, and equals the library's fold
+    Z = rng.normal(size=(B * OH * OW, k * k * C))
+    back = conv.col2im(Z, X.shape, k, k, stride, pad)
+    assert abs(np.vdot(conv.im2col(X, k, k, stride, pad), Z) - np.vdot(X, back)) < 1e-9
+    zt = torch.from_numpy(Z.reshape(B, OH * OW, k, k, C)).permute(0, 4, 2, 3, 1).reshape(B, C * k * k, OH * OW)
+    fold = torch.nn.functional.fold(zt, (H, W), kernel_size=k, stride=stride, padding=pad)
+    assert np.allclose(back, fold.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
