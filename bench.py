@@ -61,6 +61,9 @@ def main():
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
     ap.add_argument("--all-paths", action="store_true",
                     help="wire model with every first-order path instead of the shortest path per device")
+    ap.add_argument("--from-images", action="store_true",
+                    help="convolution layers take NHWC activations and gather their patches on the fly "
+                         "(xbar_conv_*) instead of reading a patch matrix prepared outside the timed region")
     ap.add_argument("--fcm-refresh", action="store_true",
                     help="also time one refresh of the circuit-level distortion profile of every layer "
                          "(reported as fcm_refresh_ms; not part of the step)")
@@ -108,11 +111,20 @@ def main():
         flags = kw["flags"] | (workloads.INPUT_SIGNED if g.signed_input else 0)
         cfg = xb.make_config(**dict(kw, flags=flags))
         W, X, dY = workloads.layer_tensors_torch(g, seed=i, device=device)
+        geom = None
+        if args.from_images and g.conv is not None:
+            X = workloads.image_tensor_torch(g, seed=i, device=device)
+            b_, hw_, cin_, k_, stride_, pad_ = g.conv
+            geom = xb.conv_geom(b_, hw_, hw_, cin_, k_, k_, stride_, pad_)
+            assert geom.batch * geom.out_h * geom.out_w == g.M and k_ * k_ * cin_ == g.K
         w_max = 2.0 * float(W.abs().max())          # head-room: the weights move during the run
-        layers.append(dict(g=g, cfg=cfg, W=W, X=X, dY=dY, w_max=w_max, x_scale=float(X.abs().max()),
+        layers.append(dict(g=g, cfg=cfg, W=W, X=X, dY=dY, w_max=w_max, x_scale=float(X.abs().max()), geom=geom,
                            g_scale=float(dY.abs().max()), macs=workloads.macs(g, S_w, S_in)))
         max_planes = max(max_planes, xb.planes_bytes(cfg, g.K, g.N))
-        max_ws = max(max_ws, *(xb.workspace_bytes(cfg, op, g.M, g.K, g.N) for op in (0, 1, 2)))
+        if geom is None:
+            max_ws = max(max_ws, *(xb.workspace_bytes(cfg, op, g.M, g.K, g.N) for op in (0, 1, 2)))
+        else:
+            max_ws = max(max_ws, *(xb.conv_workspace_bytes(cfg, op, geom, g.N) for op in (0, 1, 2)))
         max_out = max(max_out, g.M * g.N, g.M * g.K)
     planes = torch.empty(max_planes, dtype=torch.uint8, device=device)
     ws = torch.empty(max_ws, dtype=torch.uint8, device=device)
@@ -139,13 +151,24 @@ def main():
                     ev = events.pair()
                     xb.trace_next_vmm(*ev)
                     vmm_records.append((li, "fwd", ev))
-                xb.fwd(cfg, planes, L["X"], g.N, L["w_max"], L["x_scale"], ws=ws, out=out[:g.M * g.N].view(g.M, g.N))
+                geom = L["geom"]
+                if geom is None:
+                    xb.fwd(cfg, planes, L["X"], g.N, L["w_max"], L["x_scale"], ws=ws, out=out[:g.M * g.N].view(g.M, g.N))
+                else:
+                    xb.conv_fwd(cfg, planes, L["X"], geom, g.N, L["w_max"], L["x_scale"], ws=ws,
+                                out=out[:g.M * g.N].view(geom.batch, geom.out_h, geom.out_w, g.N))
                 if timed:
                     ev = events.pair()
                     xb.trace_next_vmm(*ev)
                     vmm_records.append((li, "bwd", ev))
-                xb.bwd(cfg, planes, L["dY"], g.K, L["w_max"], L["g_scale"], ws=ws, out=out[:g.M * g.K].view(g.M, g.K))
-                xb.update(cfg, L["W"], L["X"], L["dY"], L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws)
+                if geom is None:
+                    xb.bwd(cfg, planes, L["dY"], g.K, L["w_max"], L["g_scale"], ws=ws, out=out[:g.M * g.K].view(g.M, g.K))
+                    xb.update(cfg, L["W"], L["X"], L["dY"], L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws)
+                else:
+                    xb.conv_bwd(cfg, planes, L["dY"].view(geom.batch, geom.out_h, geom.out_w, g.N), geom, g.N, L["w_max"],
+                                L["g_scale"], ws=ws, out=out[:L["X"].numel()].view(L["X"].shape))
+                    xb.conv_update(cfg, L["W"], L["X"], L["dY"].view(geom.batch, geom.out_h, geom.out_w, g.N), geom,
+                                   L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws)
 
     for w in range(args.warmup):
         step(w, False)
@@ -194,7 +217,8 @@ def main():
             torch.cuda.synchronize()
             probe[key] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
         roofline["sustained_mfma_tflops_bare_instruction"] = probe
-    if args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal and not args.all_paths:
+    if (args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal and not args.all_paths
+            and not args.from_images):
         roofline["traffic"] = VMM_TRAFFIC_BYTES_RESNET50_B64
     fcm_refresh_ms = None
     if args.fcm_refresh:
@@ -219,7 +243,7 @@ def main():
 
     # ---- CPU oracle on a bounded sample ------------------------------------------------------------
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.from_images:
         from oracle import xbar_oracle as xo
         threads = min(16, os.cpu_count() or 1)
         rows = args.cpu_rows or threads

@@ -181,6 +181,40 @@ int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const flo
                      void* hip_stream);
 
 /*
+ * Digital peripheral operations (Sec. IV-B: ReLU, batch normalisation and pooling are computed in the
+ * digital domain, untouched by the crossbar non-idealities), the loss and the plain SGD step of the
+ * digital parameters, so that a whole training step can stay on the GPU.  Float NHWC tensors, n =
+ * number of elements; `rows` = batch x positions, channels fastest.  Statistics are accumulated in
+ * double precision in a fixed order.
+ *   relu_bwd      takes the forward OUTPUT y (dx = dy where y > 0)
+ *   bn_fwd        training mode: per-channel batch mean and biased variance; writes y, mean and
+ *                 invstd = 1 / sqrt(var + eps) (kept for bn_bwd)
+ *   bn_bwd        dx, dgamma = sum dy xhat, dbeta = sum dy; ws: xbar_bn_workspace_bytes(rows, channels)
+ *   avgpool       global average over the `positions` of every (sample, channel)
+ *   maxpool       square window k_h = k_w with stride and padding from the geometry struct (in_c =
+ *                 channels, 2 pad <= k); argmax[out element] = position ih * in_w + iw of the first
+ *                 maximum, kept for maxpool_bwd
+ *   softmax_xent  loss[b] = -log softmax(logits[b])[labels[b]]; dlogits = scale (softmax - onehot);
+ *                 a label outside [0, classes) gives a NaN loss and no target
+ *   sgd           p <- p - lr g
+ */
+int xbar_relu_fwd(const float* x, float* y, size_t n, void* hip_stream);
+int xbar_relu_bwd(const float* y, const float* dy, float* dx, size_t n, void* hip_stream);
+int xbar_add(const float* a, const float* b, float* y, size_t n, void* hip_stream);
+int xbar_sgd(float* p, const float* g, size_t n, float lr, void* hip_stream);
+size_t xbar_bn_workspace_bytes(size_t rows, int channels);
+int xbar_bn_fwd(const float* x, const float* gamma, const float* beta, float* y, float* mean, float* invstd, size_t rows,
+                int channels, float eps, void* ws, size_t ws_bytes, void* hip_stream);
+int xbar_bn_bwd(const float* x, const float* dy, const float* gamma, const float* mean, const float* invstd, float* dx,
+                float* dgamma, float* dbeta, size_t rows, int channels, void* ws, size_t ws_bytes, void* hip_stream);
+int xbar_avgpool_fwd(const float* x, float* y, int batch, int positions, int channels, void* hip_stream);
+int xbar_avgpool_bwd(const float* dy, float* dx, int batch, int positions, int channels, void* hip_stream);
+int xbar_maxpool_fwd(const float* x, float* y, int32_t* argmax, const xbar_conv_geom* geom, void* hip_stream);
+int xbar_maxpool_bwd(const float* dy, const int32_t* argmax, float* dx, const xbar_conv_geom* geom, void* hip_stream);
+int xbar_softmax_xent(const float* logits, const int32_t* labels, float* loss, float* dlogits, int batch, int classes,
+                      float scale, void* hip_stream);
+
+/*
  * Circuit-level crossbar model (Sec. IV-A: Ohm's and Kirchhoff's laws solved for every crossbar
  * instance; Sec. IV-D: its result kept as the distortion profile D = (G_ideal - G_nonideal) / G_ideal
  * and reused for the following iterations).  For every crossbar tile, slice and array the exact

@@ -488,12 +488,23 @@ __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
         const ConvRow cr = conv_row(a.conv, m);
         int c = l0 % a.conv.C, kk = l0 / a.conv.C;
         int kw = kk % a.conv.KW, kh = kk / a.conv.KW;
+        if ((a.conv.C & 7) == 0 && l0 + 8 <= lend) {   // the 8 inputs are 8 channels of one pixel
+          const int ih = cr.ih0 + kh, iw = cr.iw0 + kw;
+          if (ih >= 0 && ih < a.conv.H && iw >= 0 && iw < a.conv.W) {
+            const float* px = a.X + (cr.off + ((long long)kh * a.conv.W + kw) * a.conv.C + c);
+            const float4 v0 = *reinterpret_cast<const float4*>(px);
+            const float4 v1 = *reinterpret_cast<const float4*>(px + 4);
+            x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
+            x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
+          }
+        } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          if (l0 + e < lend) x[e] = conv_fetch(a.X, a.conv, cr, kh, kw, c);
-          if (++c == a.conv.C) {
-            c = 0;
-            if (++kw == a.conv.KW) { kw = 0; ++kh; }
+          for (int e = 0; e < 8; ++e) {
+            if (l0 + e < lend) x[e] = conv_fetch(a.X, a.conv, cr, kh, kw, c);
+            if (++c == a.conv.C) {
+              c = 0;
+              if (++kw == a.conv.KW) { kw = 0; ++kh; }
+            }
           }
         }
       }

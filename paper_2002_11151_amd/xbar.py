@@ -95,6 +95,19 @@ _SIGNATURES = {
                                 C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_conv_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_int,
                                    C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_relu_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_relu_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_add": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_sgd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_float, C.c_void_p]),
+    "xbar_bn_workspace_bytes": (C.c_size_t, [C.c_size_t, C.c_int]),
+    "xbar_bn_fwd": (C.c_int, [C.c_void_p] * 6 + [C.c_size_t, C.c_int, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_bn_bwd": (C.c_int, [C.c_void_p] * 8 + [C.c_size_t, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_avgpool_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "xbar_avgpool_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]),
+    "xbar_maxpool_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_void_p]),
+    "xbar_maxpool_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_void_p]),
+    "xbar_softmax_xent": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float,
+                                    C.c_void_p]),
     "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                               C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
@@ -282,3 +295,95 @@ def conv_update(cfg, W, X, dY, geom, w_max, grad_scale, lr, step=0, ws=None):
     _check(lib().xbar_conv_update(C.byref(cfg), _dev(W), _dev(X), _dev(dY), C.byref(geom), N, w_max, grad_scale, lr, step,
                                   C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return W
+
+
+# ---- digital peripherals -------------------------------------------------------------------------
+def relu_fwd(x, out=None):
+    out = torch.empty_like(x) if out is None else out
+    _check(lib().xbar_relu_fwd(_dev(x), _dev(out), x.numel(), _stream()))
+    return out
+
+
+def relu_bwd(y, dy, out=None):
+    out = torch.empty_like(dy) if out is None else out
+    _check(lib().xbar_relu_bwd(_dev(y), _dev(dy), _dev(out), y.numel(), _stream()))
+    return out
+
+
+def add(a, b, out=None):
+    out = torch.empty_like(a) if out is None else out
+    _check(lib().xbar_add(_dev(a), _dev(b), _dev(out), a.numel(), _stream()))
+    return out
+
+
+def sgd(p, g, lr):
+    _check(lib().xbar_sgd(_dev(p), _dev(g), p.numel(), lr, _stream()))
+    return p
+
+
+def _bn_ws(rows, channels, ws, device):
+    return _buffer(lib().xbar_bn_workspace_bytes(rows, channels), ws, device)
+
+
+def bn_fwd(x, gamma, beta, eps=1e-5, ws=None):
+    """xbar_bn_fwd on x[..., channels]: returns (y, mean, invstd)."""
+    channels = x.shape[-1]
+    rows = x.numel() // channels
+    ws = _bn_ws(rows, channels, ws, x.device)
+    y = torch.empty_like(x)
+    mean = torch.empty(channels, dtype=torch.float32, device=x.device)
+    invstd = torch.empty_like(mean)
+    _check(lib().xbar_bn_fwd(_dev(x), _dev(gamma), _dev(beta), _dev(y), _dev(mean), _dev(invstd), rows, channels, eps,
+                             C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return y, mean, invstd
+
+
+def bn_bwd(x, dy, gamma, mean, invstd, ws=None):
+    """xbar_bn_bwd: returns (dx, dgamma, dbeta)."""
+    channels = x.shape[-1]
+    rows = x.numel() // channels
+    ws = _bn_ws(rows, channels, ws, x.device)
+    dx = torch.empty_like(x)
+    dgamma = torch.empty(channels, dtype=torch.float32, device=x.device)
+    dbeta = torch.empty_like(dgamma)
+    _check(lib().xbar_bn_bwd(_dev(x), _dev(dy), _dev(gamma), _dev(mean), _dev(invstd), _dev(dx), _dev(dgamma), _dev(dbeta),
+                             rows, channels, C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return dx, dgamma, dbeta
+
+
+def avgpool_fwd(x):
+    """Global average pool of x[batch][h][w][channels] -> [batch][channels]."""
+    b, ch = x.shape[0], x.shape[-1]
+    y = torch.empty((b, ch), dtype=torch.float32, device=x.device)
+    _check(lib().xbar_avgpool_fwd(_dev(x), _dev(y), b, x.numel() // (b * ch), ch, _stream()))
+    return y
+
+
+def avgpool_bwd(dy, shape):
+    dx = torch.empty(shape, dtype=torch.float32, device=dy.device)
+    b, ch = shape[0], shape[-1]
+    _check(lib().xbar_avgpool_bwd(_dev(dy), _dev(dx), b, dx.numel() // (b * ch), ch, _stream()))
+    return dx
+
+
+def maxpool_fwd(x, geom):
+    y = torch.empty((geom.batch, geom.out_h, geom.out_w, geom.in_c), dtype=torch.float32, device=x.device)
+    arg = torch.empty(y.shape, dtype=torch.int32, device=x.device)
+    _check(lib().xbar_maxpool_fwd(_dev(x), _dev(y), _dev(arg, torch.int32), C.byref(geom), _stream()))
+    return y, arg
+
+
+def maxpool_bwd(dy, arg, geom):
+    dx = torch.empty((geom.batch, geom.in_h, geom.in_w, geom.in_c), dtype=torch.float32, device=dy.device)
+    _check(lib().xbar_maxpool_bwd(_dev(dy), _dev(arg, torch.int32), _dev(dx), C.byref(geom), _stream()))
+    return dx
+
+
+def softmax_xent(logits, labels, scale):
+    """xbar_softmax_xent: returns (per-sample loss, dlogits)."""
+    b, classes = logits.shape
+    loss = torch.empty(b, dtype=torch.float32, device=logits.device)
+    dlogits = torch.empty_like(logits)
+    _check(lib().xbar_softmax_xent(_dev(logits), _dev(labels, torch.int32), _dev(loss), _dev(dlogits), b, classes, scale,
+                                   _stream()))
+    return loss, dlogits

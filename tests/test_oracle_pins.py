@@ -676,3 +676,56 @@ def test_im2col_matmul_is_the_library_convolution(B, H, W, C, k, stride, pad, N)
     zt = torch.from_numpy(Z.reshape(B, OH * OW, k, k, C)).permute(0, 4, 2, 3, 1).reshape(B, C * k * k, OH * OW)
     fold = torch.nn.functional.fold(zt, (H, W), kernel_size=k, stride=stride, padding=pad)
     assert np.allclose(back, fold.permute(0, 2, 3, 1).numpy(), rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------------------------------------
+# digital peripherals: definitions against the library's functions and its automatic differentiation
+# ------------------------------------------------------------------------------------------------
+def test_peripheral_definitions_against_library_autograd():
+    import torch
+    from oracle import periph
+    rng = np.random.default_rng(11)
+    B, H, W, C = 3, 6, 5, 7
+    x = rng.normal(size=(B, H, W, C))
+    dy = rng.normal(size=(B, H, W, C))
+    gamma, beta = rng.uniform(0.5, 1.5, size=C), rng.normal(size=C)
+    # batch normalisation (training mode)
+    xt = torch.tensor(x, requires_grad=True)
+    gt, bt = torch.tensor(gamma, requires_grad=True), torch.tensor(beta, requires_grad=True)
+    yt = torch.nn.functional.batch_norm(xt.permute(0, 3, 1, 2), None, None, gt, bt, training=True, eps=1e-5)
+    yt.backward(torch.tensor(dy).permute(0, 3, 1, 2))
+    y, mean, invstd = periph.bn_fwd(x, gamma, beta, 1e-5)
+    dx, dgamma, dbeta = periph.bn_bwd(x, dy, gamma, mean, invstd)
+    assert np.allclose(y, yt.detach().permute(0, 2, 3, 1).numpy(), atol=1e-12)
+    assert np.allclose(dx, xt.grad.numpy(), atol=1e-12)
+    assert np.allclose(dgamma, gt.grad.numpy(), atol=1e-12) and np.allclose(dbeta, bt.grad.numpy(), atol=1e-12)
+    # ReLU
+    xt = torch.tensor(x, requires_grad=True)
+    rt = torch.relu(xt)
+    rt.backward(torch.tensor(dy))
+    assert np.array_equal(periph.relu_fwd(x), rt.detach().numpy())
+    assert np.array_equal(periph.relu_bwd(periph.relu_fwd(x), dy), xt.grad.numpy())
+    # max pooling 3x3 stride 2 pad 1 and 2x2 stride 2
+    for k, stride, pad in ((3, 2, 1), (2, 2, 0)):
+        xt = torch.tensor(x, requires_grad=True)
+        pt = torch.nn.functional.max_pool2d(xt.permute(0, 3, 1, 2), k, stride, pad)
+        d = rng.normal(size=tuple(pt.permute(0, 2, 3, 1).shape))
+        pt.backward(torch.tensor(d).permute(0, 3, 1, 2))
+        y, arg = periph.maxpool_fwd(x, k, stride, pad)
+        assert np.array_equal(y, pt.detach().permute(0, 2, 3, 1).numpy())
+        assert np.allclose(periph.maxpool_bwd(d, arg, x.shape), xt.grad.numpy(), atol=1e-12)
+    # global average pooling
+    xt = torch.tensor(x, requires_grad=True)
+    at = xt.mean(dim=(1, 2))
+    d = rng.normal(size=(B, C))
+    at.backward(torch.tensor(d))
+    assert np.allclose(periph.avgpool_fwd(x), at.detach().numpy(), atol=1e-12)
+    assert np.allclose(periph.avgpool_bwd(d, x.shape), xt.grad.numpy(), atol=1e-12)
+    # softmax cross-entropy, mean over the batch
+    z = rng.normal(size=(5, 10)) * 3
+    labels = rng.integers(0, 10, size=5)
+    zt = torch.tensor(z, requires_grad=True)
+    lt = torch.nn.functional.cross_entropy(zt, torch.tensor(labels), reduction="none")
+    lt.mean().backward()
+    loss, dz = periph.softmax_xent(z, labels, 1.0 / 5)
+    assert np.allclose(loss, lt.detach().numpy(), atol=1e-12) and np.allclose(dz, zt.grad.numpy(), atol=1e-12)

@@ -11,7 +11,8 @@ from collections import namedtuple
 
 import numpy as np
 
-Gemm = namedtuple("Gemm", "name K N M signed_input count")
+# conv: None for a fully connected layer, else (batch, image size, input channels, kernel, stride, pad)
+Gemm = namedtuple("Gemm", "name K N M signed_input count conv", defaults=[None])
 
 # flag bits of the parameter struct (plain numbers, typed here so that this module imports nothing)
 NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2 = (
@@ -23,7 +24,7 @@ def _merge(gemms):
     """Collapses repeated shapes into one entry with a count (keeps first-seen order)."""
     out, pos = [], {}
     for g in gemms:
-        key = (g.K, g.N, g.M, g.signed_input)
+        key = (g.K, g.N, g.M, g.signed_input, g.conv)
         if key in pos:
             i = pos[key]
             out[i] = out[i]._replace(count=out[i].count + 1)
@@ -36,18 +37,18 @@ def _merge(gemms):
 def resnet50_gemms(batch=64, merge=False):
     """im2col GEMMs of every convolution of a ResNet-50 (stride on the 3x3 convolution) on
     224x224x3 inputs, plus the 2048->1000 classifier: 54 GEMMs."""
-    g = [Gemm("conv1_7x7", 3 * 49, 64, batch * 112 * 112, True, 1)]
+    g = [Gemm("conv1_7x7", 3 * 49, 64, batch * 112 * 112, True, 1, (batch, 224, 3, 7, 2, 3))]
     cin, hw = 64, 56
     for stage, (width, blocks) in enumerate(zip((64, 128, 256, 512), (3, 4, 6, 3))):
         for b in range(blocks):
             stride = 2 if (b == 0 and stage > 0) else 1
             hw_out = hw // stride
             p = "s%db%d" % (stage + 1, b)
-            g.append(Gemm(p + "_1x1a", cin, width, batch * hw * hw, False, 1))
-            g.append(Gemm(p + "_3x3", width * 9, width, batch * hw_out * hw_out, False, 1))
-            g.append(Gemm(p + "_1x1b", width, width * 4, batch * hw_out * hw_out, False, 1))
+            g.append(Gemm(p + "_1x1a", cin, width, batch * hw * hw, False, 1, (batch, hw, cin, 1, 1, 0)))
+            g.append(Gemm(p + "_3x3", width * 9, width, batch * hw_out * hw_out, False, 1, (batch, hw, width, 3, stride, 1)))
+            g.append(Gemm(p + "_1x1b", width, width * 4, batch * hw_out * hw_out, False, 1, (batch, hw_out, width, 1, 1, 0)))
             if b == 0:
-                g.append(Gemm(p + "_down", cin, width * 4, batch * hw_out * hw_out, False, 1))
+                g.append(Gemm(p + "_down", cin, width * 4, batch * hw_out * hw_out, False, 1, (batch, hw, cin, 1, stride, 0)))
             cin, hw = width * 4, hw_out
     g.append(Gemm("fc", 2048, 1000, batch, False, 1))
     return _merge(g) if merge else g
@@ -55,14 +56,16 @@ def resnet50_gemms(batch=64, merge=False):
 
 def resnet20_gemms(batch=128, merge=False):
     """3x3 convolution stack of a CIFAR ResNet-20 (16/32/64 channels) on 32x32x3 inputs + 64->10."""
-    g = [Gemm("conv1", 27, 16, batch * 1024, True, 1)]
+    g = [Gemm("conv1", 27, 16, batch * 1024, True, 1, (batch, 32, 3, 3, 1, 1))]
     cin, hw = 16, 32
     for stage, width in enumerate((16, 32, 64)):
         for b in range(3):
             stride = 2 if (b == 0 and stage > 0) else 1
             hw_out = hw // stride
-            g.append(Gemm("s%db%d_a" % (stage + 1, b), cin * 9, width, batch * hw_out * hw_out, False, 1))
-            g.append(Gemm("s%db%d_b" % (stage + 1, b), width * 9, width, batch * hw_out * hw_out, False, 1))
+            g.append(Gemm("s%db%d_a" % (stage + 1, b), cin * 9, width, batch * hw_out * hw_out, False, 1,
+                          (batch, hw, cin, 3, stride, 1)))
+            g.append(Gemm("s%db%d_b" % (stage + 1, b), width * 9, width, batch * hw_out * hw_out, False, 1,
+                          (batch, hw_out, width, 3, 1, 1)))
             cin, hw = width, hw_out
     g.append(Gemm("fc", 64, 10, batch, False, 1))
     return _merge(g) if merge else g
@@ -164,6 +167,16 @@ def layer_tensors_torch(g, seed, device, w_std=None, grad_std=0.01):
         X = X.abs_()
     dY = torch.randn((g.M, g.N), generator=gen, device=device, dtype=torch.float32) * grad_std
     return W, X, dY
+
+
+def image_tensor_torch(g, seed, device):
+    """NHWC input image of a convolution layer, same value distribution as the rows of layer_tensors_torch."""
+    import torch
+    batch, hw, cin, _, _, _ = g.conv
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed + 1000003)
+    X = torch.randn((batch, hw, hw, cin), generator=gen, device=device, dtype=torch.float32)
+    return X if g.signed_input else X.abs_()
 
 
 def macs(g, n_slices, n_cycles):
