@@ -49,6 +49,79 @@ class HipEvents:
         return ms.value
 
 
+def end_to_end(args, torch, workloads, xb, device):
+    """Whole training steps of the CIFAR-size residual network (19 convolutions + classifier)."""
+    from paper_2002_11151_amd import resnet_cifar
+    assert args.workload == "resnet20", "--end-to-end is the resnet20 workload"
+    batch = args.batch or 128
+    kw = workloads.config_kwargs("resnet20")
+    S_w, S_in = kw["weight_bits"] // kw["slice_bits"], kw["input_bits"] // kw["stream_bits"]
+    gemms = workloads.resnet20_gemms(batch)
+    tot = {k: sum(workloads.macs(g, S_w, S_in)[k] for g in gemms) for k in ("fwd", "bwd", "upd", "logical")}
+    tot["bwd"] -= workloads.macs(gemms[0], S_w, S_in)["bwd"]        # no error is propagated to the image
+    gen = torch.Generator(device=device)
+    gen.manual_seed(0)
+    images = torch.randn((batch, 32, 32, 3), generator=gen, device=device)
+    labels = torch.randint(0, 10, (batch,), generator=gen, device=device).to(torch.int32)
+    net = resnet_cifar.ResNetCifar(kw, batch=batch, n_blocks=3, image=32, classes=10, seed=0, device=device)
+    net.calibrate(images, labels)
+
+    events = HipEvents()
+    records = []
+
+    class Traced:                      # the binding, with HIP events around every contraction kernel
+        def __getattr__(self, name):
+            fn = getattr(xb, name)
+            if name not in ("fwd", "bwd", "conv_fwd", "conv_bwd") or not self.timed:
+                return fn
+
+            def wrapped(*a, **k):
+                ev = events.pair()
+                xb.trace_next_vmm(*ev)
+                records.append(ev)
+                return fn(*a, **k)
+            return wrapped
+
+    traced = Traced()
+    traced.timed = False
+    resnet_cifar.xb = traced
+    for _ in range(args.warmup):
+        net.train_step(images, labels, 0.01)
+    torch.cuda.synchronize()
+    traced.timed = True
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        loss = net.train_step(images, labels, 0.01)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    resnet_cifar.xb = xb
+    vmm_ms = sum(events.elapsed_ms(a, b) for a, b in records)
+    emulated = tot["fwd"] + tot["bwd"] + tot["upd"]
+    achieved = 2.0 * (tot["fwd"] + tot["bwd"]) * args.steps / (vmm_ms * 1e-3) / 1e12
+    terms = 2
+    line = {
+        "metric": "emulated crossbar GMAC/s (fwd+bwd+update)", "value": round(emulated / (elapsed / args.steps) / 1e9, 1),
+        "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(elapsed / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f16 operands, f32 accumulate", "data": "synthetic",
+        "config": {"workload": "resnet20 whole training step from 32x32x3 images, batch %d, %dx%d crossbars, %d-bit "
+                               "weights in %d slices, %d-bit inputs in %d cycles, %d-bit ADC, wire parasitics (AAM) + "
+                               "write non-linearity + noise, digital batch norm / ReLU / pooling / loss" %
+                               (batch, kw["xbar_rows"], kw["xbar_cols"], kw["weight_bits"], S_w, kw["input_bits"], S_in,
+                                kw["adc_bits"]),
+                   "emulated_macs_per_step": emulated, "logical_macs_per_step": tot["logical"]},
+        "final_loss": round(float(loss.mean()), 4),
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / FP16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "vmm_kernel (MFMA contraction + ADC + shift-and-add, fwd and bwd launches)",
+                     "operand_terms": terms, "launches": len(records),
+                     "avg_launch_ms": round(vmm_ms / max(1, len(records)), 4),
+                     "kernel_time_share": round(vmm_ms / (elapsed * 1e3), 4)},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -64,6 +137,9 @@ def main():
     ap.add_argument("--from-images", action="store_true",
                     help="convolution layers take NHWC activations and gather their patches on the fly "
                          "(xbar_conv_*) instead of reading a patch matrix prepared outside the timed region")
+    ap.add_argument("--end-to-end", action="store_true",
+                    help="resnet20 only: time whole training steps of the network (crossbar layers from images, "
+                         "digital batch norm / ReLU / pooling / loss) instead of the list of layer GEMMs")
     ap.add_argument("--fcm-refresh", action="store_true",
                     help="also time one refresh of the circuit-level distortion profile of every layer "
                          "(reported as fcm_refresh_ms; not part of the step)")
@@ -87,6 +163,9 @@ def main():
     torch.cuda.set_device(0)
     device = torch.device("cuda:0")
     xb.lib()
+
+    if args.end_to_end:
+        return end_to_end(args, torch, workloads, xb, device)
 
     default_batch = {"fc256": 64, "mlp": 128, "resnet20": 128, "resnet50": 64, "vgg16": 128}[args.workload]
     batch = args.batch or default_batch

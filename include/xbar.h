@@ -197,6 +197,10 @@ int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const flo
  *   softmax_xent  loss[b] = -log softmax(logits[b])[labels[b]]; dlogits = scale (softmax - onehot);
  *                 a label outside [0, classes) gives a NaN loss and no target
  *   sgd           p <- p - lr g
+ *   shortcut      parameter-free residual shortcut across a stage boundary: y[b][oh][ow][:] = x[b][oh stride]
+ *                 [ow stride][:] with (out_channels - channels) zero channels added, half in front
+ *   absmax        result[0] (device) = max |x[i]|; ws: 4096 bytes.  For choosing the input ranges
+ *                 (x_scale, g_scale, w_max) of a layer from data (Sec. IV-B: ranges are data dependent).
  */
 int xbar_relu_fwd(const float* x, float* y, size_t n, void* hip_stream);
 int xbar_relu_bwd(const float* y, const float* dy, float* dx, size_t n, void* hip_stream);
@@ -213,6 +217,11 @@ int xbar_maxpool_fwd(const float* x, float* y, int32_t* argmax, const xbar_conv_
 int xbar_maxpool_bwd(const float* dy, const int32_t* argmax, float* dx, const xbar_conv_geom* geom, void* hip_stream);
 int xbar_softmax_xent(const float* logits, const int32_t* labels, float* loss, float* dlogits, int batch, int classes,
                       float scale, void* hip_stream);
+int xbar_shortcut_fwd(const float* x, float* y, int batch, int h, int w, int channels, int stride, int out_channels,
+                      void* hip_stream);
+int xbar_shortcut_bwd(const float* dy, float* dx, int batch, int h, int w, int channels, int stride, int out_channels,
+                      void* hip_stream);
+int xbar_absmax(const float* x, size_t n, float* result, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Circuit-level crossbar model (Sec. IV-A: Ohm's and Kirchhoff's laws solved for every crossbar

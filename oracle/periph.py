@@ -89,3 +89,20 @@ def softmax_xent(logits, labels, scale):
     d = p.copy()
     d[idx, labels] -= 1.0
     return loss, scale * d
+
+
+def shortcut_fwd(x, stride, out_channels):
+    """Parameter-free residual shortcut: subsample the positions, add zero channels (half in front)."""
+    x = np.asarray(x, dtype=np.float64)[:, ::stride, ::stride, :]
+    lo = (out_channels - x.shape[-1]) // 2
+    y = np.zeros(x.shape[:-1] + (out_channels,))
+    y[..., lo:lo + x.shape[-1]] = x
+    return y
+
+
+def shortcut_bwd(dy, shape, stride):
+    dy = np.asarray(dy, dtype=np.float64)
+    lo = (dy.shape[-1] - shape[-1]) // 2
+    dx = np.zeros(shape)
+    dx[:, ::stride, ::stride, :] = dy[..., lo:lo + shape[-1]]
+    return dx

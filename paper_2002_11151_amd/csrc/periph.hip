@@ -37,20 +37,23 @@ __global__ __launch_bounds__(256) void sgd_kernel(float* p, const float* g, size
   if (i < n) p[i] -= lr * g[i];
 }
 
-// Per-channel sums over a block of rows: part[chunk][channel][2] = (sum a, sum a b) with b = 1 or the
-// second operand.  Thread = (row group of 4, channel of a 64-channel strip).
-template <bool BWD>
+// Per-channel sums over a block of rows: part[chunk][channel][2] = (sum x, sum x^2), or with BWD
+// (sum dy, sum dy xhat).  CT = channels per strip (a power of two, at most 64); the 256 threads are
+// 256 / CT row groups x CT channels, so narrow layers still use every lane.
+template <bool BWD, int CT>
 __global__ __launch_bounds__(256) void bn_partial_kernel(const float* x, const float* dy, const float* mean,
                                                          const float* invstd, double* part, size_t rows, int C) {
-  __shared__ double red[2][4][64];
-  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 6;
-  const int c = blockIdx.y * 64 + lane;
+  constexpr int G = 256 / CT;
+  __shared__ double red[2][G][CT];
+  const int cl = threadIdx.x % CT, grp = threadIdx.x / CT;
+  const int c = blockIdx.y * CT + cl;
   const size_t r0 = (size_t)blockIdx.x * kStatRows;
   const size_t r1 = r0 + kStatRows < rows ? r0 + kStatRows : rows;
   double s0 = 0.0, s1 = 0.0;
   if (c < C) {
     const double mu = BWD ? (double)mean[c] : 0.0, is = BWD ? (double)invstd[c] : 0.0;
-    for (size_t r = r0 + grp; r < r1; r += 4) {
+#pragma unroll 4
+    for (size_t r = r0 + grp; r < r1; r += G) {
       const double v = (double)x[r * C + c];
       if (BWD) {
         const double g = (double)dy[r * C + c];
@@ -62,26 +65,44 @@ __global__ __launch_bounds__(256) void bn_partial_kernel(const float* x, const f
       }
     }
   }
-  red[0][grp][lane] = s0;
-  red[1][grp][lane] = s1;
+  red[0][grp][cl] = s0;
+  red[1][grp][cl] = s1;
   __syncthreads();
   if (grp == 0 && c < C) {
+    double t0 = 0.0, t1 = 0.0;
+    for (int g = 0; g < G; ++g) {      // fixed order
+      t0 += red[0][g][cl];
+      t1 += red[1][g][cl];
+    }
     double* out = part + ((size_t)blockIdx.x * C + c) * 2;
-    out[0] = (red[0][0][lane] + red[0][1][lane]) + (red[0][2][lane] + red[0][3][lane]);
-    out[1] = (red[1][0][lane] + red[1][1][lane]) + (red[1][2][lane] + red[1][3][lane]);
+    out[0] = t0;
+    out[1] = t1;
   }
 }
 
-// One thread per channel adds the chunk sums in chunk order.
-__global__ __launch_bounds__(256) void bn_finalize_fwd_kernel(const double* part, int chunks, int C, size_t rows,
-                                                              float eps, float* mean, float* invstd) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= C) return;
-  double s0 = 0.0, s1 = 0.0;
-  for (int k = 0; k < chunks; ++k) {
+// One wave per channel adds the chunk sums: lane l takes chunks l, l + 64, ..., then a fixed
+// butterfly over the lanes.
+__device__ __forceinline__ void bn_chunk_sums(const double* part, int chunks, int C, int c, double& s0, double& s1) {
+  const int lane = threadIdx.x & 63;
+  s0 = s1 = 0.0;
+  for (int k = lane; k < chunks; k += 64) {
     s0 += part[((size_t)k * C + c) * 2];
     s1 += part[((size_t)k * C + c) * 2 + 1];
   }
+#pragma unroll
+  for (int d = 32; d; d >>= 1) {
+    s0 += __shfl_xor(s0, d, 64);
+    s1 += __shfl_xor(s1, d, 64);
+  }
+}
+
+__global__ __launch_bounds__(256) void bn_finalize_fwd_kernel(const double* part, int chunks, int C, size_t rows,
+                                                              float eps, float* mean, float* invstd) {
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (c >= C) return;                                 // whole waves leave together
+  double s0, s1;
+  bn_chunk_sums(part, chunks, C, c, s0, s1);
+  if ((threadIdx.x & 63) != 0) return;
   const double mu = s0 / (double)rows;
   double var = s1 / (double)rows - mu * mu;        // biased variance of the batch
   if (var < 0.0) var = 0.0;
@@ -91,13 +112,11 @@ __global__ __launch_bounds__(256) void bn_finalize_fwd_kernel(const double* part
 
 __global__ __launch_bounds__(256) void bn_finalize_bwd_kernel(const double* part, int chunks, int C, float* dgamma,
                                                               float* dbeta) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
+  const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (c >= C) return;
-  double s0 = 0.0, s1 = 0.0;
-  for (int k = 0; k < chunks; ++k) {
-    s0 += part[((size_t)k * C + c) * 2];
-    s1 += part[((size_t)k * C + c) * 2 + 1];
-  }
+  double s0, s1;
+  bn_chunk_sums(part, chunks, C, c, s0, s1);
+  if ((threadIdx.x & 63) != 0) return;
   dbeta[c] = (float)s0;
   dgamma[c] = (float)s1;
 }
@@ -217,6 +236,71 @@ __global__ __launch_bounds__(64) void softmax_xent_kernel(const float* logits, c
   }
 }
 
+// Parameter-free residual shortcut across a stage boundary: spatial subsampling by `stride` and zero
+// padding of the new channels, half before and half behind the old ones.
+struct ShortcutGeom {
+  int B, H, W, C, stride, OH, OW, OC, lo;
+};
+
+__global__ __launch_bounds__(256) void shortcut_fwd_kernel(const float* x, float* y, ShortcutGeom g) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)g.B * g.OH * g.OW * g.OC) return;
+  const int oc = (int)(i % g.OC);
+  size_t u = i / g.OC;
+  const int ow = (int)(u % g.OW);
+  u /= g.OW;
+  const int oh = (int)(u % g.OH), b = (int)(u / g.OH);
+  const int c = oc - g.lo;
+  y[i] = (c >= 0 && c < g.C) ? x[(((size_t)b * g.H + oh * g.stride) * g.W + ow * g.stride) * g.C + c] : 0.0f;
+}
+
+__global__ __launch_bounds__(256) void shortcut_bwd_kernel(const float* dy, float* dx, ShortcutGeom g) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)g.B * g.H * g.W * g.C) return;
+  const int c = (int)(i % g.C);
+  size_t u = i / g.C;
+  const int iw = (int)(u % g.W);
+  u /= g.W;
+  const int ih = (int)(u % g.H), b = (int)(u / g.H);
+  const bool kept = ih % g.stride == 0 && iw % g.stride == 0 && ih / g.stride < g.OH && iw / g.stride < g.OW;
+  dx[i] = kept ? dy[(((size_t)b * g.OH + ih / g.stride) * g.OW + iw / g.stride) * g.OC + c + g.lo] : 0.0f;
+}
+
+// max |x|: per-block maxima, then one block over them.  |x| is compared as an unsigned integer (the
+// order of non-negative floats); a NaN input gives a NaN-patterned result.
+__global__ __launch_bounds__(256) void absmax_kernel(const float* x, size_t n, uint32_t* part) {
+  __shared__ uint32_t red[4];
+  uint32_t m = 0;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+    const uint32_t v = __float_as_uint(x[i]) & 0x7FFFFFFFu;
+    m = v > m ? v : m;
+  }
+  for (int d = 32; d; d >>= 1) {
+    const uint32_t o = (uint32_t)__shfl_xor((int)m, d, 64);
+    m = o > m ? o : m;
+  }
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < 4; ++w) m = red[w] > m ? red[w] : m;
+    part[blockIdx.x] = m;
+  }
+}
+
+template <bool BWD>
+void launch_bn_partial(const float* x, const float* dy, const float* mean, const float* invstd, double* part, size_t rows,
+                       int channels, int chunks, hipStream_t st) {
+  if (channels <= 16)
+    hipLaunchKernelGGL((bn_partial_kernel<BWD, 16>), dim3((unsigned)chunks, (unsigned)((channels + 15) / 16)), dim3(256), 0,
+                       st, x, dy, mean, invstd, part, rows, channels);
+  else if (channels <= 32)
+    hipLaunchKernelGGL((bn_partial_kernel<BWD, 32>), dim3((unsigned)chunks, 1u), dim3(256), 0, st, x, dy, mean, invstd, part,
+                       rows, channels);
+  else
+    hipLaunchKernelGGL((bn_partial_kernel<BWD, 64>), dim3((unsigned)chunks, (unsigned)((channels + 63) / 64)), dim3(256), 0,
+                       st, x, dy, mean, invstd, part, rows, channels);
+}
+
 inline int launched() { return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP; }
 
 }  // namespace
@@ -270,10 +354,9 @@ int xbar_bn_fwd(const float* x, const float* gamma, const float* beta, float* y,
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   const int chunks = (int)((rows + kStatRows - 1) / kStatRows);
   double* part = reinterpret_cast<double*>(ws);
-  hipLaunchKernelGGL(bn_partial_kernel<false>, dim3((unsigned)chunks, (unsigned)((channels + 63) / 64)), dim3(256), 0, st, x,
-                     nullptr, nullptr, nullptr, part, rows, channels);
+  launch_bn_partial<false>(x, nullptr, nullptr, nullptr, part, rows, channels, chunks, st);
   if (launched()) return XBAR_EHIP;
-  hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3(blocks_for((size_t)channels)), dim3(256), 0, st, part, chunks, channels,
+  hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3((unsigned)((channels + 3) / 4)), dim3(256), 0, st, part, chunks, channels,
                      rows, eps, mean, invstd);
   if (launched()) return XBAR_EHIP;
   const size_t n = rows * (size_t)channels;
@@ -291,10 +374,9 @@ int xbar_bn_bwd(const float* x, const float* dy, const float* gamma, const float
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   const int chunks = (int)((rows + kStatRows - 1) / kStatRows);
   double* part = reinterpret_cast<double*>(ws);
-  hipLaunchKernelGGL(bn_partial_kernel<true>, dim3((unsigned)chunks, (unsigned)((channels + 63) / 64)), dim3(256), 0, st, x,
-                     dy, mean, invstd, part, rows, channels);
+  launch_bn_partial<true>(x, dy, mean, invstd, part, rows, channels, chunks, st);
   if (launched()) return XBAR_EHIP;
-  hipLaunchKernelGGL(bn_finalize_bwd_kernel, dim3(blocks_for((size_t)channels)), dim3(256), 0, st, part, chunks, channels,
+  hipLaunchKernelGGL(bn_finalize_bwd_kernel, dim3((unsigned)((channels + 3) / 4)), dim3(256), 0, st, part, chunks, channels,
                      dgamma, dbeta);
   if (launched()) return XBAR_EHIP;
   const size_t n = rows * (size_t)channels;
@@ -350,6 +432,51 @@ int xbar_maxpool_bwd(const float* dy, const int32_t* argmax, float* dx, const xb
   if (!aligned16(dy) || !aligned16(dx) || !aligned16(argmax)) return XBAR_EALIGN;
   hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(blocks_for((size_t)g.B * g.H * g.W * g.C)), dim3(256), 0,
                      reinterpret_cast<hipStream_t>(hip_stream), dy, argmax, dx, g);
+  return launched();
+}
+
+static int shortcut_geom(int batch, int h, int w, int channels, int stride, int out_channels, ShortcutGeom* g) {
+  if (batch <= 0 || h <= 0 || w <= 0 || channels <= 0 || stride <= 0 || out_channels < channels) return XBAR_ESHAPE;
+  g->B = batch; g->H = h; g->W = w; g->C = channels; g->stride = stride;
+  g->OH = (h + stride - 1) / stride; g->OW = (w + stride - 1) / stride; g->OC = out_channels;
+  g->lo = (out_channels - channels) / 2;
+  return XBAR_OK;
+}
+
+int xbar_shortcut_fwd(const float* x, float* y, int batch, int h, int w, int channels, int stride, int out_channels,
+                      void* hip_stream) {
+  ShortcutGeom g;
+  const int rc = shortcut_geom(batch, h, w, channels, stride, out_channels, &g);
+  if (rc) return rc;
+  if (!aligned16(x) || !aligned16(y)) return XBAR_EALIGN;
+  hipLaunchKernelGGL(shortcut_fwd_kernel, dim3(blocks_for((size_t)g.B * g.OH * g.OW * g.OC)), dim3(256), 0,
+                     reinterpret_cast<hipStream_t>(hip_stream), x, y, g);
+  return launched();
+}
+
+int xbar_shortcut_bwd(const float* dy, float* dx, int batch, int h, int w, int channels, int stride, int out_channels,
+                      void* hip_stream) {
+  ShortcutGeom g;
+  const int rc = shortcut_geom(batch, h, w, channels, stride, out_channels, &g);
+  if (rc) return rc;
+  if (!aligned16(dy) || !aligned16(dx)) return XBAR_EALIGN;
+  hipLaunchKernelGGL(shortcut_bwd_kernel, dim3(blocks_for((size_t)g.B * g.H * g.W * g.C)), dim3(256), 0,
+                     reinterpret_cast<hipStream_t>(hip_stream), dy, dx, g);
+  return launched();
+}
+
+int xbar_absmax(const float* x, size_t n, float* result, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (n == 0) return XBAR_ESHAPE;
+  if (!aligned16(x) || !aligned16(result) || !aligned16(ws)) return XBAR_EALIGN;
+  if (ws_bytes < 1024 * sizeof(uint32_t)) return XBAR_EWORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  const unsigned blocks = (unsigned)((n + 255) / 256 < 1024 ? (n + 255) / 256 : 1024);
+  uint32_t* part = reinterpret_cast<uint32_t*>(ws);
+  hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, st, x, n, part);
+  if (launched()) return XBAR_EHIP;
+  // the partial maxima are bit patterns of non-negative floats: the same kernel reduces them once more
+  hipLaunchKernelGGL(absmax_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<const float*>(part), (size_t)blocks,
+                     reinterpret_cast<uint32_t*>(result));
   return launched();
 }
 

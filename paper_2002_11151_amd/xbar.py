@@ -108,6 +108,9 @@ _SIGNATURES = {
     "xbar_maxpool_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_void_p]),
     "xbar_softmax_xent": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float,
                                     C.c_void_p]),
+    "xbar_shortcut_fwd": (C.c_int, [C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]),
+    "xbar_shortcut_bwd": (C.c_int, [C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]),
+    "xbar_absmax": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                               C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
@@ -387,3 +390,26 @@ def softmax_xent(logits, labels, scale):
     _check(lib().xbar_softmax_xent(_dev(logits), _dev(labels, torch.int32), _dev(loss), _dev(dlogits), b, classes, scale,
                                    _stream()))
     return loss, dlogits
+
+
+def shortcut_fwd(x, stride, out_channels):
+    b, h, w, ch = x.shape
+    y = torch.empty((b, (h + stride - 1) // stride, (w + stride - 1) // stride, out_channels), dtype=torch.float32,
+                    device=x.device)
+    _check(lib().xbar_shortcut_fwd(_dev(x), _dev(y), b, h, w, ch, stride, out_channels, _stream()))
+    return y
+
+
+def shortcut_bwd(dy, shape, stride):
+    b, h, w, ch = shape
+    dx = torch.empty(shape, dtype=torch.float32, device=dy.device)
+    _check(lib().xbar_shortcut_bwd(_dev(dy), _dev(dx), b, h, w, ch, stride, dy.shape[-1], _stream()))
+    return dx
+
+
+def absmax(x, ws=None):
+    """xbar_absmax: max |x| as a host float (synchronises: meant for calibration, not for the step)."""
+    ws = _buffer(4096, ws, x.device)
+    res = torch.empty(4, dtype=torch.float32, device=x.device)
+    _check(lib().xbar_absmax(_dev(x), x.numel(), _dev(res), C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return float(res[0].item())

@@ -1,0 +1,151 @@
+"""A whole training step of a small residual network on the GPU: every kernel call the step makes is
+recorded and repeated by the oracle on the same inputs (the GPU run drives the trajectory, so one
+flipped ADC code cannot make later comparisons diverge)."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+def rel_l2(a, b):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+class Recorder:
+    """Stands in for the binding module inside the network driver: forwards every call, keeps copies."""
+
+    def __init__(self, real):
+        self.real, self.calls, self.tiled = real, [], {}
+
+    def __getattr__(self, name):
+        fn = getattr(self.real, name)
+        if not callable(fn) or name in ("make_config", "conv_geom", "planes_bytes", "workspace_bytes",
+                                        "conv_workspace_bytes", "lib", "absmax"):
+            return fn
+
+        def wrapped(*args, **kw):
+            host = lambda v: v.detach().cpu().numpy().copy() if isinstance(v, torch.Tensor) and v.dtype != torch.uint8 else v
+            before = [host(a) for a in args]
+            if name == "tile":                        # remember which weights / step a plane buffer holds
+                self.tiled[kw["planes"].data_ptr()] = (before[1], args[2], args[3])
+            out = fn(*args, **kw)
+            torch.cuda.synchronize()
+            after = [host(o) for o in out] if isinstance(out, tuple) else host(out)
+            self.calls.append((name, args, before, after))
+            return out
+        return wrapped
+
+
+def oracle_config(xo, cfg):
+    skip = ("struct_size", "abi_version", "dac_lut")
+    return xo.make_config(**{f: getattr(cfg, f) for f, _ in type(cfg)._fields_ if f not in skip})
+
+
+def test_residual_network_step_op_by_op(xo):
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from oracle import conv, periph
+    from paper_2002_11151_amd import resnet_cifar, xbar as xb
+    kw = workloads.config_kwargs("resnet20")
+    kw.update(xbar_rows=64, xbar_cols=64, weight_bits=8)
+    kw["adc_fs_fwd"] = kw["adc_fs_bwd"] = workloads.adc_full_scale(64, kw["stream_bits"], kw["slice_bits"])
+    B = 3
+    net = resnet_cifar.ResNetCifar(kw, batch=B, n_blocks=1, image=12, classes=10, widths=(8, 16, 16), seed=3)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    images = torch.randn((B, 12, 12, 3), generator=gen, device="cuda")
+    labels = torch.tensor([1, 7, 4], dtype=torch.int32, device="cuda")
+    net.calibrate(images, labels)
+    rec = Recorder(xb)
+    resnet_cifar.xb = rec
+    try:
+        loss = net.train_step(images, labels, 0.05)
+    finally:
+        resnet_cifar.xb = xb
+    assert np.isfinite(loss.cpu().numpy()).all()
+
+    names = [c[0] for c in rec.calls]
+    for want in ("tile", "conv_fwd", "conv_bwd", "conv_update", "fwd", "bwd", "update", "bn_fwd", "bn_bwd", "relu_fwd",
+                 "relu_bwd", "add", "avgpool_fwd", "avgpool_bwd", "shortcut_fwd", "shortcut_bwd", "softmax_xent", "sgd"):
+        assert want in names, want
+    assert names.count("conv_fwd") == 7 and names.count("conv_update") == 7 and names.count("conv_bwd") == 6
+
+    def geom_tuple(g):
+        return g.k_h, g.k_w, g.stride, g.pad
+
+    for name, args, a, out in rec.calls:
+        if name in ("conv_fwd", "fwd", "conv_bwd", "bwd"):
+            cfg, planes = args[0], args[1]
+            W, w_max, step = rec.tiled[planes.data_ptr()]
+            co = oracle_config(xo, cfg)
+        if name == "conv_fwd":
+            g = args[3]
+            want = xo.fwd(co, W, conv.im2col(a[2], *geom_tuple(g)), w_max, args[6], step=step)
+            assert rel_l2(out.reshape(-1, args[4]), want) <= 1e-3, name
+        elif name == "fwd":
+            assert rel_l2(out, xo.fwd(co, W, a[2], w_max, args[5], step=step)) <= 1e-3, name
+        elif name == "conv_bwd":
+            g = args[3]
+            cols = xo.bwd(co, W, a[2].reshape(-1, args[4]), w_max, args[6], step=step)
+            want = conv.col2im(cols, out.shape, *geom_tuple(g))
+            assert rel_l2(out, want) <= 1e-3, name
+        elif name == "bwd":
+            assert rel_l2(out, xo.bwd(co, W, a[2], w_max, args[5], step=step)) <= 1e-3, name
+        elif name in ("conv_update", "update"):
+            co = oracle_config(xo, args[0])
+            W0 = a[1]
+            if name == "conv_update":
+                X, dY = conv.im2col(a[2], *geom_tuple(args[4])), a[3].reshape(-1, W0.shape[1])
+                w_max, gs, lr, step = args[5], args[6], args[7], args[8]
+            else:
+                X, dY = a[2], a[3]
+                w_max, gs, lr, step = args[4], args[5], args[6], args[7]
+            want = xo.update(co, W0, X, dY, w_max, gs, lr, step=step)
+            got = args[1].detach().cpu().numpy()              # W after the step (each layer is written once)
+            assert rel_l2(got - W0, want - W0) <= 1e-3, name
+        elif name == "bn_fwd":
+            y, mean, invstd = periph.bn_fwd(a[0], a[1], a[2], args[3])
+            assert rel_l2(out[0], y) <= 1e-5 and rel_l2(out[1], mean) <= 1e-5 and rel_l2(out[2], invstd) <= 1e-5
+        elif name == "bn_bwd":
+            dx, dgamma, dbeta = periph.bn_bwd(a[0], a[1], a[2], a[3].astype(np.float64), a[4].astype(np.float64))
+            assert rel_l2(out[0], dx) <= 1e-4 and rel_l2(out[1], dgamma) <= 1e-4 and rel_l2(out[2], dbeta) <= 1e-4
+        elif name == "relu_fwd":
+            assert np.array_equal(out, periph.relu_fwd(a[0]).astype(np.float32))
+        elif name == "relu_bwd":
+            assert np.array_equal(out, periph.relu_bwd(a[0], a[1]).astype(np.float32))
+        elif name == "add":
+            assert np.array_equal(out, a[0] + a[1])
+        elif name == "avgpool_fwd":
+            assert rel_l2(out, periph.avgpool_fwd(a[0])) <= 1e-6
+        elif name == "avgpool_bwd":
+            assert rel_l2(out, periph.avgpool_bwd(a[0], args[1])) <= 1e-6
+        elif name == "shortcut_fwd":
+            assert np.array_equal(out, periph.shortcut_fwd(a[0], args[1], args[2]).astype(np.float32))
+        elif name == "shortcut_bwd":
+            assert np.array_equal(out, periph.shortcut_bwd(a[0], args[1], args[2]).astype(np.float32))
+        elif name == "softmax_xent":
+            lo, dz = periph.softmax_xent(a[0], a[1], np.float64(np.float32(args[2])))
+            assert rel_l2(out[0], lo) <= 1e-6 and rel_l2(out[1], dz) <= 1e-6
+
+
+def test_residual_network_learns_a_fixed_batch():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import resnet_cifar
+    kw = workloads.config_kwargs("resnet20")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    B = 16
+    images = torch.randn((B, 16, 16, 3), generator=gen, device="cuda")
+    labels = (torch.arange(B, device="cuda") % 10).to(torch.int32)
+    net = resnet_cifar.ResNetCifar(kw, batch=B, n_blocks=1, image=16, classes=10, widths=(16, 32, 64), seed=1)
+    net.calibrate(images, labels)
+    losses = [float(net.train_step(images, labels, 0.05).mean()) for _ in range(30)]
+    assert np.isfinite(losses).all()
+    assert np.mean(losses[-5:]) < 0.8 * np.mean(losses[:3]), losses       # 8-bit ADCs, wire drops, write noise: slow but steady
