@@ -224,6 +224,22 @@ int xbar_shortcut_bwd(const float* dy, float* dx, int batch, int h, int w, int c
 int xbar_absmax(const float* x, size_t n, float* result, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
+ * ADC range statistics (Sec. IV-B: the maximum current through the ADCs is data dependent and comes
+ * from output distribution statistics).  Runs the input stage and the contraction of xbar_fwd
+ * (op = XBAR_OP_FWD: in = X[M][K]) or xbar_bwd (XBAR_OP_BWD: in = dY[M][N]) and, instead of
+ * converting, counts every column current that an ADC would see: hist[b] += number of conversions
+ * with rne(|I| / bin_width) == b, the last of the 4096 bins takes everything beyond.  I and bin_width
+ * are in the unit of adc_fs (one input level x one device level); adc_bits / adc_fs of cfg are not used.
+ *   hist  4096 uint64 device counters, added to (clear them before the first call)
+ *   ws    the workspace of the same xbar_fwd / xbar_bwd call
+ * The caller picks adc_fs from the histogram (a high quantile, rounded up as it sees fit).
+ */
+#define XBAR_ADC_HIST_BINS 4096
+int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* in, int M, int K, int N,
+                       float in_scale, int op, float bin_width, unsigned long long* hist, void* ws, size_t ws_bytes,
+                       void* hip_stream);
+
+/*
  * Circuit-level crossbar model (Sec. IV-A: Ohm's and Kirchhoff's laws solved for every crossbar
  * instance; Sec. IV-D: its result kept as the distortion profile D = (G_ideal - G_nonideal) / G_ideal
  * and reused for the following iterations).  For every crossbar tile, slice and array the exact

@@ -542,6 +542,7 @@ struct VmmArgs {
   const u32x4* B;      // plane fragments of this direction
   void* part;          // [nchunk][M][Lout] int32 (narrow) or int64 (wide)
   int16_t* codes;      // optional [P][S_in][S_w][T][M][Lout]
+  unsigned long long* hist;   // optional: kStatBins counters of |code| instead of the codes themselves
   int M, Lin, Lout, MP, OP, MB, T, P, VT;
   int S_w, S_in, slice_bits, stream_bits, ks, tile;
   int vt_per_chunk, nchunk, lds_kb;
@@ -552,6 +553,9 @@ struct VmmArgs {
   float* out;                 // final output, written directly when there is a single chunk
   double scale;               // lsb * in_scale * w_max / (Qa * Qw)
 };
+
+constexpr int kStatBins = 4096;
+__shared__ uint32_t stat_hist[kStatBins];   // per-block histogram of the statistics pass (code-tap variants only)
 
 // Asynchronous 16-byte-per-lane copy global -> LDS: `lds_wave_base` is the same for the whole wave.
 __device__ __forceinline__ void copy16_global_to_lds(const u32x4* g, u32x4* lds_wave_base) {
@@ -749,8 +753,12 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
             const int o = op * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
             if (m < a.M && o < a.Lout) {
               int code = (int)(bits - kMagicBits);
-              if (p) code = -code;
-              a.codes[(((((size_t)p * a.S_in + b) * a.S_w + s) * a.T + t) * a.M + m) * a.Lout + o] = (int16_t)code;
+              if (a.hist) {
+                atomicAdd(&stat_hist[min(::abs(code), kStatBins - 1)], 1u);
+              } else {
+                if (p) code = -code;
+                a.codes[(((((size_t)p * a.S_in + b) * a.S_w + s) * a.T + t) * a.M + m) * a.Lout + o] = (int16_t)code;
+              }
             }
           }
         }
@@ -814,6 +822,12 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
   const int mb = grp % a.MB;
   const int op = grp / a.MB;
   const int mp0 = (mb * nw + wave) * PM;
+  if constexpr (CODES) {
+    if (a.hist) {
+      for (int i = threadIdx.x; i < kStatBins; i += blockDim.x) stat_hist[i] = 0;
+      __syncthreads();
+    }
+  }
 
   uint32_t y[PM][16];
   long long y64[PM][16];
@@ -844,6 +858,14 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
       default: break;
     }
 #undef XBAR_NK_CASE
+  }
+  if constexpr (CODES) {
+    if (a.hist) {                                  // statistics pass: the counters are the only result
+      __syncthreads();
+      for (int i = threadIdx.x; i < kStatBins; i += blockDim.x)
+        if (stat_hist[i]) atomicAdd(&a.hist[i], (unsigned long long)stat_hist[i]);
+      return;
+    }
   }
   // partial result of this chunk
   const uint32_t bias = a.bias_per_vt * (uint32_t)(vt1 - vt0);
@@ -1656,11 +1678,11 @@ hipError_t launch_vmm(const VmmArgs& a, const VmmPlan& p, int terms, bool codes,
 
 int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* out, int M, int K, int N,
             float w_max, float in_scale, void* ws, size_t ws_bytes, int16_t* codes, void* stream, bool transposed,
-            const ConvGeom* conv = nullptr) {
+            const ConvGeom* conv = nullptr, unsigned long long* hist = nullptr) {
   int rc = xbar_config_validate(cfg);
   if (rc) return rc;
   if ((rc = check_shape(M, K, N))) return rc;
-  if (!aligned16(planes) || !aligned16(in) || !aligned16(out) || !aligned16(ws)) return XBAR_EALIGN;
+  if (!aligned16(planes) || !aligned16(in) || (!hist && !aligned16(out)) || !aligned16(ws)) return XBAR_EALIGN;
   if (codes && (reinterpret_cast<uintptr_t>(codes) & 1u)) return XBAR_EALIGN;
   if (!finite_pos(w_max) || !finite_pos(in_scale)) return XBAR_EINVAL;
   // DAC level table: with 1-bit cycles (the paper's streaming scheme) and a zero level at 0 V the
@@ -1697,6 +1719,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.B = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(planes) + (transposed ? align256(gf.bytes) : 0));
   a.part = reinterpret_cast<char*>(ws) + p.a_bytes;
   a.codes = codes;
+  a.hist = hist;
   a.M = M; a.Lin = p.Lin; a.Lout = p.Lout; a.MP = p.MP; a.OP = p.g.OP; a.MB = p.MB; a.T = p.g.T; a.P = p.P;
   a.VT = p.VT; a.S_w = d.S_w; a.S_in = d.S_in; a.slice_bits = cfg->slice_bits; a.stream_bits = cfg->stream_bits;
   a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.lds_kb = p.lds_kb;
@@ -1715,8 +1738,9 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   hipEvent_t ev0 = g_trace_before, ev1 = g_trace_after;
   g_trace_before = g_trace_after = nullptr;
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return XBAR_EHIP;
-  if (launch_vmm(a, p, d.terms, codes != nullptr, st) != hipSuccess) return XBAR_EHIP;
+  if (launch_vmm(a, p, d.terms, codes != nullptr || hist != nullptr, st) != hipSuccess) return XBAR_EHIP;
   if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return XBAR_EHIP;
+  if (hist) return XBAR_OK;
 
   if (p.nchunk > 1) {
     FinishArgs f;
@@ -2015,6 +2039,22 @@ int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const flo
   const int rc = conv_dims(geom, &g, &M, &K);
   if (rc) return rc;
   return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream, &g);
+}
+
+int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* in, int M, int K, int N, float in_scale,
+                       int op, float bin_width, unsigned long long* hist, void* ws, size_t ws_bytes, void* hip_stream) {
+  int rc = xbar_config_validate(cfg);
+  if (rc) return rc;
+  if (op != XBAR_OP_FWD && op != XBAR_OP_BWD) return XBAR_EINVAL;
+  if (!finite_pos(bin_width)) return XBAR_EINVAL;
+  if (!aligned16(hist)) return XBAR_EALIGN;
+  // a converter with one code per bin: code = rne(I / bin_width), clamped to the last bin
+  xbar_config c = *cfg;
+  c.adc_bits = 13;
+  c.adc_fs_fwd = c.adc_fs_bwd = (float)(kStatBins - 1) * bin_width;
+  if (!finite_pos(c.adc_fs_fwd)) return XBAR_EINVAL;
+  return run_vmm(&c, planes, in, nullptr, M, K, N, 1.0f, in_scale, ws, ws_bytes, nullptr, hip_stream, op == XBAR_OP_BWD,
+                 nullptr, hist);
 }
 
 int xbar_fcm_profile(const xbar_config* cfg, const float* W, int K, int N, float w_max, uint64_t step, float* profile,

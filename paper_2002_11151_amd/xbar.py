@@ -111,6 +111,8 @@ _SIGNATURES = {
     "xbar_shortcut_fwd": (C.c_int, [C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]),
     "xbar_shortcut_bwd": (C.c_int, [C.c_void_p, C.c_void_p] + [C.c_int] * 6 + [C.c_void_p]),
     "xbar_absmax": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_adc_histogram": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
+                                     C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                               C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
@@ -413,3 +415,17 @@ def absmax(x, ws=None):
     res = torch.empty(4, dtype=torch.float32, device=x.device)
     _check(lib().xbar_absmax(_dev(x), x.numel(), _dev(res), C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return float(res[0].item())
+
+
+ADC_HIST_BINS = 4096
+
+
+def adc_histogram(cfg, planes, inp, K, N, in_scale, op, bin_width, hist=None, ws=None):
+    """xbar_adc_histogram: adds the |column current| counts of this input to hist (int64[4096], device)."""
+    M = inp.shape[0]
+    ws = _buffer(workspace_bytes(cfg, op, M, K, N), ws, inp.device)
+    if hist is None:
+        hist = torch.zeros(ADC_HIST_BINS, dtype=torch.int64, device=inp.device)
+    _check(lib().xbar_adc_histogram(C.byref(cfg), C.c_void_p(planes.data_ptr()), _dev(inp), M, K, N, in_scale, op,
+                                    bin_width, _dev(hist, torch.int64), C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return hist

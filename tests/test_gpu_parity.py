@@ -292,6 +292,38 @@ def test_convolution_layer(xo, xb, name, B, H, W, C, k, stride, pad, N, R, sb):
     assert np.abs(Wg - Wo).max() <= 1e-5 * w_max
 
 
+@pytest.mark.parametrize("ni,R,sb,M,K,N", [("ideal", 64, 2, 50, 200, 70), ("aam", 128, 1, 40, 300, 100),
+                                          ("aam+var", 256, 4, 33, 520, 48)])
+def test_adc_range_statistics(xo, xb, ni, R, sb, M, K, N):
+    g = workloads.Gemm("t", K, N, M, True, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=3 * K + N)
+    flags = xo.INPUT_SIGNED | (xo.WIRE_AAM if "aam" in ni else 0) | (xo.VARIATION if "var" in ni else 0)
+    kw = dict(xbar_rows=R, xbar_cols=R, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=sb, flags=flags,
+              var_sigma=0.1, seed=4)
+    cg = xb.make_config(adc_bits=8, adc_fs_fwd=1.0, adc_fs_bwd=1.0, **kw)          # converter settings are not used
+    bin_width = R * ((1 << sb) - 1) * 3 / 4095.0 / 4                               # the busiest quarter of the range
+    co = xo.make_config(adc_bits=13, adc_fs_fwd=4095 * bin_width, adc_fs_bwd=4095 * bin_width, **kw)
+    w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    planes = xb.tile(cg, dev(W), w_max, 1)
+    for op, inp, scale, oracle_pass in ((xb.OP_FWD, X, x_scale, xo.fwd), (xb.OP_BWD, dY, g_scale, xo.bwd)):
+        hist = xb.adc_histogram(cg, planes, dev(inp), K, N, scale, op, bin_width)
+        hist = xb.adc_histogram(cg, planes, dev(inp), K, N, scale, op, bin_width, hist=hist)      # counters add up
+        torch.cuda.synchronize()
+        hist = hist.cpu().numpy()
+        _, codes = oracle_pass(co, W, inp, w_max, scale, step=1, want_codes=True)
+        want = 2 * np.bincount(np.abs(codes).ravel(), minlength=4096)
+        assert hist.sum() == want.sum() == 2 * codes.size
+        if ni == "ideal":
+            assert np.array_equal(hist, want)
+        else:
+            # one count per bin of a 4096-bin converter: 32 times finer steps than the 8-bit converter that the
+            # 1e-4 code tolerance is stated for; a moved conversion changes two neighbouring bins
+            assert np.abs(hist - want).sum() <= 2 * 32 * 1e-4 * want.sum()
+        for q in (0.99, 0.999):
+            assert workloads.adc_full_scale_from_histogram(hist, bin_width, q) == \
+                workloads.adc_full_scale_from_histogram(want, bin_width, q)
+
+
 def test_config1_fc256_step(xo, xb):
     """First benchmark configuration, whole: one fwd + bwd + update step of a 256x256 layer."""
     g = workloads.fc256_gemms(64)[0]

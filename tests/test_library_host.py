@@ -131,6 +131,10 @@ def test_argument_checks_precede_any_device_work(xb):
     assert lib.xbar_conv_fwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, big, None, None) == -2
     geom = xb.conv_geom(2, 2, 2, 4, 5, 5, 1, 0)                # kernel larger than the image
     assert lib.xbar_conv_bwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, big, None) == -2
+    assert lib.xbar_adc_histogram(C.byref(c), ok, ok, 4, 64, 64, 1.0, 2, 0.5, ok, ok, big, None) == -1       # no such pass
+    assert lib.xbar_adc_histogram(C.byref(c), ok, ok, 4, 64, 64, 1.0, 0, 0.0, ok, ok, big, None) == -1
+    assert lib.xbar_adc_histogram(C.byref(c), ok, ok, 4, 64, 64, 1.0, 0, 0.5, odd, ok, big, None) == -3
+    assert lib.xbar_adc_histogram(C.byref(c), ok, ok, 4, 64, 64, 1.0, 1, 0.5, ok, ok, 16, None) == -4
     for code in range(-6, 1):
         assert xb.strerror(code) and "unknown" not in xb.strerror(code)
     assert "unknown" in xb.strerror(-99)

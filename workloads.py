@@ -103,6 +103,16 @@ def adc_full_scale(rows, stream_bits, slice_bits):
     return float(2 ** math.ceil(math.log2(3.3 * math.sqrt(rows * ev2 * eu2))))
 
 
+def adc_full_scale_from_histogram(hist, bin_width, quantile=0.999):
+    """ADC full scale from measured statistics: the smallest power of two that is at least the
+    `quantile` of the |column current| distribution (hist[b] = count of rne(|I| / bin_width) == b)."""
+    hist = np.asarray(hist, dtype=np.float64)
+    cum = np.cumsum(hist)
+    b = int(np.searchsorted(cum, quantile * cum[-1]))
+    current = max((b + 0.5) * bin_width, bin_width)
+    return float(2.0 ** math.ceil(math.log2(current)))
+
+
 def config_kwargs(name):
     """Parameter presets of the five benchmark configurations (keyword arguments of the config
     constructors of both the library binding and the oracle wrapper)."""
