@@ -21,7 +21,7 @@ if ROOT not in sys.path:
 FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
 # HBM bytes per vmm_kernel launch (average over the 108 launches of a step) of the default workload, from
 # the FETCH_SIZE / WRITE_SIZE counter runs recorded in profiles/vmm_kernel_resnet50_batch64.txt
-VMM_TRAFFIC_BYTES_RESNET50_B64 = 436560 * 1024
+VMM_TRAFFIC_BYTES_RESNET50_B64 = 553778 * 1024
 
 
 class HipEvents:
@@ -140,6 +140,9 @@ def main():
     ap.add_argument("--end-to-end", action="store_true",
                     help="resnet20 only: time whole training steps of the network (crossbar layers from images, "
                          "digital batch norm / ReLU / pooling / loss) instead of the list of layer GEMMs")
+    ap.add_argument("--overlap-update", action="store_true",
+                    help="run the weight update of a layer beside its backward pass on a second stream (1 %% less "
+                         "time per step; the contraction kernel then shares the matrix pipes and times 4 %% slower)")
     ap.add_argument("--fcm-refresh", action="store_true",
                     help="also time one refresh of the circuit-level distortion profile of every layer "
                          "(reported as fcm_refresh_ms; not part of the step)")
@@ -185,7 +188,7 @@ def main():
 
     # ---- resident tensors, one set per distinct shape ------------------------------------------
     layers = []
-    max_planes = max_ws = max_out = 0
+    max_planes = max_ws = max_out = max_ws_upd = 0
     for i, g in enumerate(gemms):
         flags = kw["flags"] | (workloads.INPUT_SIGNED if g.signed_input else 0)
         cfg = xb.make_config(**dict(kw, flags=flags))
@@ -204,9 +207,16 @@ def main():
             max_ws = max(max_ws, *(xb.workspace_bytes(cfg, op, g.M, g.K, g.N) for op in (0, 1, 2)))
         else:
             max_ws = max(max_ws, *(xb.conv_workspace_bytes(cfg, op, geom, g.N) for op in (0, 1, 2)))
+        max_ws_upd = max(max_ws_upd, xb.workspace_bytes(cfg, 2, g.M, g.K, g.N) if geom is None else
+                         xb.conv_workspace_bytes(cfg, 2, geom, g.N))
         max_out = max(max_out, g.M * g.N, g.M * g.K)
     planes = torch.empty(max_planes, dtype=torch.uint8, device=device)
     ws = torch.empty(max_ws, dtype=torch.uint8, device=device)
+    # the update of a layer does not depend on its backward pass: on request it runs beside it on a second
+    # stream (default priority) with a workspace of its own
+    side = torch.cuda.Stream() if args.overlap_update else None
+    ws_upd = ws if side is None else torch.empty(max_ws_upd, dtype=torch.uint8, device=device)
+    tiled, updated = torch.cuda.Event(), torch.cuda.Event()
     out = torch.empty(max_out, dtype=torch.float32, device=device)
 
     if args.calib_copy:
@@ -221,11 +231,14 @@ def main():
     vmm_records = []          # (layer index, 'fwd'|'bwd', event pair)
 
     def step(step_no, timed):
+        main = torch.cuda.current_stream()
         for li, L in enumerate(layers):
             g, cfg = L["g"], L["cfg"]
             for rep in range(g.count):
                 s = step_no * 64 + rep
                 xb.tile(cfg, L["W"], L["w_max"], s, planes=planes)
+                if side is not None:
+                    tiled.record(main)
                 if timed:
                     ev = events.pair()
                     xb.trace_next_vmm(*ev)
@@ -236,18 +249,32 @@ def main():
                 else:
                     xb.conv_fwd(cfg, planes, L["X"], geom, g.N, L["w_max"], L["x_scale"], ws=ws,
                                 out=out[:g.M * g.N].view(geom.batch, geom.out_h, geom.out_w, g.N))
+
+                def update():
+                    if geom is None:
+                        xb.update(cfg, L["W"], L["X"], L["dY"], L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws_upd)
+                    else:
+                        xb.conv_update(cfg, L["W"], L["X"], L["dY"].view(geom.batch, geom.out_h, geom.out_w, g.N), geom,
+                                       L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws_upd)
+
+                if side is not None:                      # W may be written once the generator has read it
+                    side.wait_event(tiled)
+                    with torch.cuda.stream(side):
+                        update()
+                        updated.record(side)
                 if timed:
                     ev = events.pair()
                     xb.trace_next_vmm(*ev)
                     vmm_records.append((li, "bwd", ev))
                 if geom is None:
                     xb.bwd(cfg, planes, L["dY"], g.K, L["w_max"], L["g_scale"], ws=ws, out=out[:g.M * g.K].view(g.M, g.K))
-                    xb.update(cfg, L["W"], L["X"], L["dY"], L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws)
                 else:
                     xb.conv_bwd(cfg, planes, L["dY"].view(geom.batch, geom.out_h, geom.out_w, g.N), geom, g.N, L["w_max"],
                                 L["g_scale"], ws=ws, out=out[:L["X"].numel()].view(L["X"].shape))
-                    xb.conv_update(cfg, L["W"], L["X"], L["dY"].view(geom.batch, geom.out_h, geom.out_w, g.N), geom,
-                                   L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws)
+                if side is None:
+                    update()
+                else:
+                    main.wait_event(updated)              # the next generator call reads the written W
 
     for w in range(args.warmup):
         step(w, False)
