@@ -918,15 +918,27 @@ struct GradArgs {
   ConvGeom conv;
 };
 
-constexpr int kGradMS = 16;   // batch rows per LDS stage
+constexpr int kGradMS = 32;   // batch rows per LDS stage = two k-steps of the bf16 matrix instruction
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-// 128 x 128 tile of X^T dY per block, 4 waves as 2 x 2, each wave 64 x 64 = 2 x 2 MFMA tiles.
-// When the layer has at most 64 rows (SPLIT_K) or columns (SPLIT_N) the waves that would work on
-// padding take a share of the batch rows of every stage instead and write a partial sum of their own.
+// fp32 value as a leading bf16 and a bf16 residual (together 16 significant bits).
+__device__ __forceinline__ void split_bf16(float x, __bf16& hi, __bf16& lo) {
+  hi = (__bf16)x;
+  lo = (__bf16)(x - (float)hi);
+}
+
+// 128 x 128 tile of X^T dY per block, 4 waves as 2 x 2, each wave 64 x 64 = 2 x 2 MFMA tiles of
+// v_mfma_f32_32x32x16_bf16.  Both operands are split into two bf16 terms while they are staged into
+// LDS and hi.hi + hi.lo + lo.hi is accumulated in fp32: three bf16 matrix instructions of 16 rows do
+// the work of eight fp32 ones of 2 rows at a relative error near 2^-16 per product, far inside the
+// tolerance of the update.  When the layer has at most 64 rows (SPLIT_K) or columns (SPLIT_N) the
+// waves that would work on padding take a share of the batch rows instead and write a partial sum of
+// their own.  CONV: X is an NHWC image and the patch rows are gathered on the fly.
 template <bool SPLIT_K, bool SPLIT_N, bool CONV>
 __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
-  __shared__ float xs[kGradMS][128];
-  __shared__ float ds[kGradMS][128];
+  // [term][group of 8 batch rows][column] -> 8 bf16 along the batch
+  __shared__ bf16x8 xs[2][kGradMS / 8][128];
+  __shared__ bf16x8 ds[2][kGradMS / 8][128];
   __shared__ ConvRow crow[2][kGradMS];               // patches of the rows of the stage being fetched
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wk = wave >> 1, wn = wave & 1;
@@ -934,7 +946,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   const int k0 = kb * 128, n0 = nb * 128;
   const int m_begin = blockIdx.y * a.m_per_chunk;
   const int m_end = min(a.M, m_begin + a.m_per_chunk);
-  constexpr int PARTS = (SPLIT_K ? 2 : 1) * (SPLIT_N ? 2 : 1);     // batch shares per stage
+  constexpr int PARTS = (SPLIT_K ? 2 : 1) * (SPLIT_N ? 2 : 1);     // batch shares
   const int share = (SPLIT_K ? wk : 0) * (SPLIT_N ? 2 : 1) + (SPLIT_N ? wn : 0);
   const int koff = SPLIT_K ? 0 : wk * 64, noff = SPLIT_N ? 0 : wn * 64;
   float16v acc[2][2];
@@ -945,30 +957,38 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  float px[8], pd[8];
-  // this thread always fetches contraction column k0 + (tid & 127): its kernel position is fixed
+  // staging: this thread fetches column (tid & 127) of 16 of the 32 rows of a stage: row groups
+  // (tid >> 7) and (tid >> 7) + 2
+  const int col = tid & 127, g_first = tid >> 7;
+  float px[16], pd[16];
   int ckh = 0, ckw = 0, cc = 0;
-  if (CONV) {
-    const int k = min(k0 + (tid & 127), a.K - 1);
+  if (CONV) {                                        // the kernel position of this thread's column is fixed
+    const int k = min(k0 + col, a.K - 1);
     cc = k % a.conv.C;
     ckw = (k / a.conv.C) % a.conv.KW;
     ckh = (k / a.conv.C) / a.conv.KW;
   }
-  int stage = 0;
   auto stage_rows = [&](int m0, int buf) {            // CONV: the first threads decompose the stage's rows
     if (CONV && tid < kGradMS) crow[buf][tid] = conv_row(a.conv, min(m0 + tid, a.M - 1));
   };
   auto prefetch = [&](int m0, int buf) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int i = tid + e * 256;
-      const int row = i >> 7, col = i & 127;
-      const int m = m0 + row;
-      if (CONV) px[e] = (m < m_end && k0 + col < a.K) ? conv_fetch(a.X, a.conv, crow[buf][row], ckh, ckw, cc) : 0.0f;
-      else px[e] = (m < m_end && k0 + col < a.K) ? a.X[(size_t)m * a.K + k0 + col] : 0.0f;
-      pd[e] = (m < m_end && n0 + col < a.N) ? a.D[(size_t)m * a.N + n0 + col] : 0.0f;
-    }
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int row = (g_first + 2 * q) * 8 + e;
+        const int m = m0 + row;
+        float x = 0.0f, d = 0.0f;
+        if (m < m_end) {
+          if (k0 + col < a.K)
+            x = CONV ? conv_fetch(a.X, a.conv, crow[buf][row], ckh, ckw, cc) : a.X[(size_t)m * a.K + k0 + col];
+          if (n0 + col < a.N) d = a.D[(size_t)m * a.N + n0 + col];
+        }
+        px[q * 8 + e] = x;
+        pd[q * 8 + e] = d;
+      }
   };
+  int stage = 0;
   stage_rows(m_begin, 0);
   if (CONV) __syncthreads();
   prefetch(m_begin, 0);
@@ -976,24 +996,45 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     if (m0 + kGradMS < m_end) stage_rows(m0 + kGradMS, stage ^ 1);
     __syncthreads();
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int i = tid + e * 256;
-      xs[i >> 7][i & 127] = px[e];
-      ds[i >> 7][i & 127] = pd[e];
+    for (int q = 0; q < 2; ++q) {
+      bf16x8 xh, xl, dh, dl;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        __bf16 h, l;
+        split_bf16(px[q * 8 + e], h, l);
+        xh[e] = h; xl[e] = l;
+        split_bf16(pd[q * 8 + e], h, l);
+        dh[e] = h; dl[e] = l;
+      }
+      xs[0][g_first + 2 * q][col] = xh;
+      xs[1][g_first + 2 * q][col] = xl;
+      ds[0][g_first + 2 * q][col] = dh;
+      ds[1][g_first + 2 * q][col] = dl;
     }
     __syncthreads();
     if (m0 + kGradMS < m_end) prefetch(m0 + kGradMS, stage ^ 1);
 #pragma unroll
-    for (int q = 0; q < kGradMS / PARTS; q += 2) {
-      const int row = share * (kGradMS / PARTS) + q + (lane >> 5);
-      const float a0 = xs[row][koff + (lane & 31)];
-      const float a1 = xs[row][koff + 32 + (lane & 31)];
-      const float b0 = ds[row][noff + (lane & 31)];
-      const float b1 = ds[row][noff + 32 + (lane & 31)];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    for (int ks = 0; ks < 2; ++ks) {
+      // batch shares: two shares alternate over the k-steps of a stage, four also over the stages
+      if (PARTS == 2 && ks != share) continue;
+      if (PARTS == 4 && (ks != (share & 1) || (stage != (share >> 1)))) continue;
+      const int g8 = 2 * ks + (lane >> 5);
+      bf16x8 ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        ah[i] = xs[0][g8][koff + 32 * i + (lane & 31)];
+        al[i] = xs[1][g8][koff + 32 * i + (lane & 31)];
+        bh[i] = ds[0][g8][noff + 32 * i + (lane & 31)];
+        bl[i] = ds[1][g8][noff + 32 * i + (lane & 31)];
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+        }
     }
   }
   float* out = a.part + ((size_t)blockIdx.y * PARTS + share) * a.K * a.N;
