@@ -70,3 +70,80 @@ def test_layer_full_size_sampled(xo, xb, workload, batch, name):
                    1.0 / w_max, 0.01, step=5, k_idx=k_idx, n_idx=n_idx, N_full=g.N)
     Wg = W_new[kt][:, nt].cpu().numpy()
     assert rel_l2(Wg - Wh[np.ix_(k_idx, n_idx)], Wo - Wh[np.ix_(k_idx, n_idx)]) <= 1e-3
+
+
+def _patch(X, b, oh, ow, k, stride, pad):
+    """Patch of output position (b, oh, ow) of the NHWC host array X, index (kh, kw, c), zeros outside."""
+    H, W, C = X.shape[1:]
+    out = np.zeros((k, k, C), dtype=X.dtype)
+    for kh in range(k):
+        for kw in range(k):
+            ih, iw = oh * stride - pad + kh, ow * stride - pad + kw
+            if 0 <= ih < H and 0 <= iw < W:
+                out[kh, kw] = X[b, ih, iw]
+    return out.reshape(-1)
+
+
+@pytest.mark.parametrize("name", ["s1b0_3x3", "s2b0_3x3", "conv1_7x7"])
+def test_convolution_full_size_sampled(xo, xb, name):
+    """ResNet-50 convolutions at batch 64 straight from the NHWC activations (the launch configuration of
+    `bench.py --from-images`): sampled output positions, input pixels and weights against the oracle."""
+    gemms = {g.name: (i, g) for i, g in enumerate(workloads.resnet50_gemms(64, merge=True))}
+    idx, g = gemms[name]
+    batch, hw, cin, k, stride, pad = g.conv
+    kw = workloads.config_kwargs("resnet50")
+    kw["flags"] |= workloads.INPUT_SIGNED if g.signed_input else 0
+    co, cg = xo.make_config(**kw), xb.make_config(**kw)
+    W, _, dY = workloads.layer_tensors_torch(g, seed=idx, device="cuda")
+    X = workloads.image_tensor_torch(g, seed=idx, device="cuda")
+    geom = xb.conv_geom(batch, hw, hw, cin, k, k, stride, pad)
+    OH, OW = geom.out_h, geom.out_w
+    dY4 = dY.view(batch, OH, OW, g.N)
+    w_max = 2.0 * float(W.abs().max())
+    xs, gs = float(X.abs().max()), float(dY.abs().max())
+    planes = xb.tile(cg, W, w_max, 5)
+    Y = xb.conv_fwd(cg, planes, X, geom, g.N, w_max, xs)
+    dX = xb.conv_bwd(cg, planes, dY4, geom, g.N, w_max, gs)
+    W_new = W.clone()
+    xb.conv_update(cg, W_new, X, dY4, geom, w_max, 1.0 / w_max, 0.01, 5)
+    torch.cuda.synchronize()
+
+    rng = np.random.default_rng(idx)
+    Xh, Wh = X.cpu().numpy(), W.cpu().numpy()
+    U = xo.planes(co, Wh, w_max, 5)
+    # forward: corner positions (padding) and random ones
+    pos = [(0, 0, 0), (batch - 1, OH - 1, OW - 1), (1, 0, OW - 1)] + \
+          [tuple(int(v) for v in (rng.integers(batch), rng.integers(OH), rng.integers(OW))) for _ in range(5)]
+    rows = np.stack([_patch(Xh, b, oh, ow, k, stride, pad) for b, oh, ow in pos])
+    Yo = xo.rows_parallel(lambda u, x: xo.fwd_planes(co, u, x, w_max, xs), U, rows, 8)
+    Yg = np.stack([Y[b, oh, ow].cpu().numpy() for b, oh, ow in pos])
+    assert rel_l2(Yg, Yo) <= 1e-3
+    # backward: an input pixel adds the errors of every patch that contains it
+    dYh = dY4.cpu().numpy()
+    pix = [(0, 0, 0), (batch - 1, hw - 1, hw - 1)] + \
+          [tuple(int(v) for v in (rng.integers(batch), rng.integers(hw), rng.integers(hw))) for _ in range(3)]
+    for b, ih, iw in pix:
+        members = []                                          # (output position, kernel position)
+        for kh in range(k):
+            for kw_ in range(k):
+                oy, ox = ih + pad - kh, iw + pad - kw_
+                if oy >= 0 and ox >= 0 and oy % stride == 0 and ox % stride == 0 and oy // stride < OH and ox // stride < OW:
+                    members.append((oy // stride, ox // stride, kh, kw_))
+        errs = np.stack([dYh[b, oh, ow] for oh, ow, _, _ in members])
+        cols = xo.rows_parallel(lambda u, x: xo.bwd_planes(co, u, x, w_max, gs), U, errs, 8)
+        want = sum(cols[i].reshape(k, k, cin)[kh, kw_].astype(np.float64) for i, (_, _, kh, kw_) in enumerate(members))
+        assert rel_l2(dX[b, ih, iw].cpu().numpy(), want) <= 1e-3
+    # update: sampled weights; their patch-matrix columns are single (kh, kw, c) planes of the padded image
+    k_idx = np.sort(rng.choice(g.K, size=5, replace=False))
+    n_idx = np.sort(rng.choice(g.N, size=4, replace=False))
+    Xp = np.pad(Xh, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
+    cols = []
+    for kk in k_idx:
+        c, kw_, kh = kk % cin, (kk // cin) % k, (kk // cin) // k
+        cols.append(Xp[:, kh:kh + stride * OH:stride, kw_:kw_ + stride * OW:stride, c].reshape(-1))
+    Xsub = np.stack(cols, axis=1)
+    Wsub = Wh[np.ix_(k_idx, n_idx)]
+    Wo = xo.update(co, Wsub, Xsub, dY[:, torch.from_numpy(n_idx).cuda()].cpu().numpy(), w_max, 1.0 / w_max, 0.01, step=5,
+                   k_idx=k_idx, n_idx=n_idx, N_full=g.N)
+    Wg = W_new.cpu().numpy()[np.ix_(k_idx, n_idx)]
+    assert rel_l2(Wg - Wsub, Wo - Wsub) <= 1e-3
