@@ -50,20 +50,25 @@ class HipEvents:
 
 
 def end_to_end(args, torch, workloads, xb, device):
-    """Whole training steps of the CIFAR-size residual network (19 convolutions + classifier)."""
-    from paper_2002_11151_amd import resnet_cifar
-    assert args.workload == "resnet20", "--end-to-end is the resnet20 workload"
-    batch = args.batch or 128
-    kw = workloads.config_kwargs("resnet20")
+    """Whole training steps of a residual network from images: the CIFAR-size ResNet-20 (19 convolutions +
+    classifier) or ResNet-50 (53 convolutions + classifier)."""
+    from paper_2002_11151_amd import resnet_cifar, resnet_imagenet
+    assert args.workload in ("resnet20", "resnet50"), "--end-to-end: resnet20 or resnet50"
+    batch = args.batch or {"resnet20": 128, "resnet50": 64}[args.workload]
+    kw = workloads.config_kwargs(args.workload)
     S_w, S_in = kw["weight_bits"] // kw["slice_bits"], kw["input_bits"] // kw["stream_bits"]
-    gemms = workloads.resnet20_gemms(batch)
+    gemms = workloads.GEMMS[args.workload](batch)
     tot = {k: sum(workloads.macs(g, S_w, S_in)[k] for g in gemms) for k in ("fwd", "bwd", "upd", "logical")}
     tot["bwd"] -= workloads.macs(gemms[0], S_w, S_in)["bwd"]        # no error is propagated to the image
     gen = torch.Generator(device=device)
     gen.manual_seed(0)
-    images = torch.randn((batch, 32, 32, 3), generator=gen, device=device)
-    labels = torch.randint(0, 10, (batch,), generator=gen, device=device).to(torch.int32)
-    net = resnet_cifar.ResNetCifar(kw, batch=batch, n_blocks=3, image=32, classes=10, seed=0, device=device)
+    image, classes = (32, 10) if args.workload == "resnet20" else (224, 1000)
+    images = torch.randn((batch, image, image, 3), generator=gen, device=device)
+    labels = torch.randint(0, classes, (batch,), generator=gen, device=device).to(torch.int32)
+    if args.workload == "resnet20":
+        net = resnet_cifar.ResNetCifar(kw, batch=batch, n_blocks=3, image=32, classes=10, seed=0, device=device)
+    else:
+        net = resnet_imagenet.ResNetBottleneck(kw, batch=batch, seed=0, device=device)
     net.calibrate(images, labels)
 
     events = HipEvents()
@@ -84,7 +89,7 @@ def end_to_end(args, torch, workloads, xb, device):
 
     traced = Traced()
     traced.timed = False
-    resnet_cifar.xb = traced
+    resnet_cifar.xb = resnet_imagenet.xb = traced
     for _ in range(args.warmup):
         net.train_step(images, labels, 0.01)
     torch.cuda.synchronize()
@@ -94,7 +99,7 @@ def end_to_end(args, torch, workloads, xb, device):
         loss = net.train_step(images, labels, 0.01)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    resnet_cifar.xb = xb
+    resnet_cifar.xb = resnet_imagenet.xb = xb
     vmm_ms = sum(events.elapsed_ms(a, b) for a, b in records)
     emulated = tot["fwd"] + tot["bwd"] + tot["upd"]
     achieved = 2.0 * (tot["fwd"] + tot["bwd"]) * args.steps / (vmm_ms * 1e-3) / 1e12
@@ -104,10 +109,10 @@ def end_to_end(args, torch, workloads, xb, device):
         "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 operands, f32 accumulate", "data": "synthetic",
-        "config": {"workload": "resnet20 whole training step from 32x32x3 images, batch %d, %dx%d crossbars, %d-bit "
+        "config": {"workload": "%s whole training step from %dx%dx3 images, batch %d, %dx%d crossbars, %d-bit "
                                "weights in %d slices, %d-bit inputs in %d cycles, %d-bit ADC, wire parasitics (AAM) + "
                                "write non-linearity + noise, digital batch norm / ReLU / pooling / loss" %
-                               (batch, kw["xbar_rows"], kw["xbar_cols"], kw["weight_bits"], S_w, kw["input_bits"], S_in,
+                               (args.workload, image, image, batch, kw["xbar_rows"], kw["xbar_cols"], kw["weight_bits"], S_w, kw["input_bits"], S_in,
                                 kw["adc_bits"]),
                    "emulated_macs_per_step": emulated, "logical_macs_per_step": tot["logical"]},
         "final_loss": round(float(loss.mean()), 4),
@@ -138,7 +143,7 @@ def main():
                     help="convolution layers take NHWC activations and gather their patches on the fly "
                          "(xbar_conv_*) instead of reading a patch matrix prepared outside the timed region")
     ap.add_argument("--end-to-end", action="store_true",
-                    help="resnet20 only: time whole training steps of the network (crossbar layers from images, "
+                    help="resnet20 / resnet50: time whole training steps of the network (crossbar layers from images, "
                          "digital batch norm / ReLU / pooling / loss) instead of the list of layer GEMMs")
     ap.add_argument("--overlap-update", action="store_true",
                     help="run the weight update of a layer beside its backward pass on a second stream (1 %% less "

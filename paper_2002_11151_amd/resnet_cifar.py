@@ -140,41 +140,44 @@ class ResNetCifar:
         self.step_no += 1
         return loss
 
-    # ---- ranges -----------------------------------------------------------------------------------
     def calibrate(self, images, labels):
-        """Fixes x_scale / g_scale of every crossbar layer from one batch: a pass with generous ranges
-        records the maxima each layer sees, the ranges become those maxima times a head-room factor.
-        No weight is changed."""
-        seen_x, seen_g = {}, {}
-        real_fwd, real_bwd = CrossbarLayer.forward, CrossbarLayer.backward
-
-        def probe_fwd(layer, x, step, ws):
-            seen_x[id(layer)] = xb.absmax(x)
-            layer.x_scale = seen_x[id(layer)] or 1.0
-            return real_fwd(layer, x, step, ws)
-
-        def probe_bwd(layer, dy, step, lr, ws, need_dx=True):
-            seen_g[id(layer)] = xb.absmax(dy)
-            layer.g_scale = seen_g[id(layer)] or 1.0
-            saved = layer.W.clone()
-            out = real_bwd(layer, dy, step, 0.0, ws, need_dx)
-            layer.W.copy_(saved)                                   # lr = 0 still writes noise: undo it
-            return out
-
-        bn_state = [(bn, bn.gamma.clone(), bn.beta.clone()) for bn in self._bns()]
-        CrossbarLayer.forward, CrossbarLayer.backward = probe_fwd, probe_bwd
-        try:
-            logits = self.forward(images, 0)
-            _, dlogits = xb.softmax_xent(logits, labels, 1.0 / images.shape[0])
-            self.backward(dlogits, 0, 0.0)
-        finally:
-            CrossbarLayer.forward, CrossbarLayer.backward = real_fwd, real_bwd
-        for bn, gamma, beta in bn_state:
-            bn.gamma.copy_(gamma)
-            bn.beta.copy_(beta)
-        for layer in self.layers:
-            layer.x_scale = HEADROOM_X * (seen_x[id(layer)] or 1.0)
-            layer.g_scale = HEADROOM_G * (seen_g[id(layer)] or 1.0)
+        calibrate_ranges(self, images, labels)
 
     def _bns(self):
         return [self.stem_bn] + [blk[k] for blk in self.blocks for k in ("bn_a", "bn_b")]
+
+
+def calibrate_ranges(net, images, labels):
+    """Fixes x_scale / g_scale of every crossbar layer of `net` from one batch: a pass with generous
+    ranges records the maxima each layer sees, the ranges become those maxima times a head-room factor.
+    No weight is changed."""
+    seen_x, seen_g = {}, {}
+    real_fwd, real_bwd = CrossbarLayer.forward, CrossbarLayer.backward
+
+    def probe_fwd(layer, x, step, ws):
+        seen_x[id(layer)] = xb.absmax(x)
+        layer.x_scale = seen_x[id(layer)] or 1.0
+        return real_fwd(layer, x, step, ws)
+
+    def probe_bwd(layer, dy, step, lr, ws, need_dx=True):
+        seen_g[id(layer)] = xb.absmax(dy)
+        layer.g_scale = seen_g[id(layer)] or 1.0
+        saved = layer.W.clone()
+        out = real_bwd(layer, dy, step, 0.0, ws, need_dx)
+        layer.W.copy_(saved)                                   # lr = 0 still rounds W through its range: undo
+        return out
+
+    bn_state = [(bn, bn.gamma.clone(), bn.beta.clone()) for bn in net._bns()]
+    CrossbarLayer.forward, CrossbarLayer.backward = probe_fwd, probe_bwd
+    try:
+        logits = net.forward(images, 0)
+        _, dlogits = xb.softmax_xent(logits, labels, 1.0 / images.shape[0])
+        net.backward(dlogits, 0, 0.0)
+    finally:
+        CrossbarLayer.forward, CrossbarLayer.backward = real_fwd, real_bwd
+    for bn, gamma, beta in bn_state:
+        bn.gamma.copy_(gamma)
+        bn.beta.copy_(beta)
+    for layer in net.layers:
+        layer.x_scale = HEADROOM_X * (seen_x[id(layer)] or 1.0)
+        layer.g_scale = HEADROOM_G * (seen_g[id(layer)] or 1.0)

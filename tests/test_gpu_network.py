@@ -17,6 +17,23 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
+def crossbar_outputs_match(got, want, cfg, in_scale, w_max, backward, overlaps=1):
+    """Layer outputs against the oracle: an ADC code may differ by one LSB on at most 1e-4 of the
+    conversions, and one such flip in the top slice and cycle moves a single output by up to one top-level
+    LSB.  So: every element within that step (times the patches a pixel collects), and 1e-3 relative L2
+    once the few elements that took a flip are set aside."""
+    got, want = np.asarray(got, dtype=np.float64).ravel(), np.asarray(want, dtype=np.float64).ravel()
+    q_adc = (1 << (cfg.adc_bits - 1)) - 1
+    fs = cfg.adc_fs_bwd if backward else cfg.adc_fs_fwd
+    top_shift = cfg.weight_bits - cfg.slice_bits + cfg.input_bits - cfg.stream_bits
+    step = fs / q_adc * in_scale * w_max / (((1 << cfg.input_bits) - 1) * ((1 << cfg.weight_bits) - 1)) * 2.0 ** top_shift
+    diff = np.abs(got - want)
+    assert diff.max() <= 1.01 * step * overlaps
+    keep = np.argsort(diff)[:max(1, got.size - 1 - int(1e-3 * got.size))]
+    assert np.linalg.norm(diff[keep]) <= 1e-3 * np.linalg.norm(want)
+    return True
+
+
 class Recorder:
     """Stands in for the binding module inside the network driver: forwards every call, keeps copies."""
 
@@ -47,34 +64,45 @@ def oracle_config(xo, cfg):
     return xo.make_config(**{f: getattr(cfg, f) for f, _ in type(cfg)._fields_ if f not in skip})
 
 
-def test_residual_network_step_op_by_op(xo):
+@pytest.mark.parametrize("kind", ["basic_blocks", "bottleneck_blocks"])
+def test_residual_network_step_op_by_op(xo, kind):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from oracle import conv, periph
-    from paper_2002_11151_amd import resnet_cifar, xbar as xb
+    from paper_2002_11151_amd import resnet_cifar, resnet_imagenet, xbar as xb
     kw = workloads.config_kwargs("resnet20")
     kw.update(xbar_rows=64, xbar_cols=64, weight_bits=8)
     kw["adc_fs_fwd"] = kw["adc_fs_bwd"] = workloads.adc_full_scale(64, kw["stream_bits"], kw["slice_bits"])
     B = 3
-    net = resnet_cifar.ResNetCifar(kw, batch=B, n_blocks=1, image=12, classes=10, widths=(8, 16, 16), seed=3)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(1)
-    images = torch.randn((B, 12, 12, 3), generator=gen, device="cuda")
+    if kind == "basic_blocks":
+        net = resnet_cifar.ResNetCifar(kw, batch=B, n_blocks=1, image=12, classes=10, widths=(8, 16, 16), seed=3)
+        images = torch.randn((B, 12, 12, 3), generator=gen, device="cuda")
+        n_conv, n_conv_bwd = 7, 6
+    else:
+        net = resnet_imagenet.ResNetBottleneck(kw, batch=B, image=24, classes=10, blocks=(1, 2), widths=(4, 8), stem=8,
+                                               seed=3)
+        images = torch.randn((B, 24, 24, 3), generator=gen, device="cuda")
+        n_conv, n_conv_bwd = 1 + 3 * 3 + 2, 3 * 3 + 2                    # stem, 3 blocks of 3, 2 projections
     labels = torch.tensor([1, 7, 4], dtype=torch.int32, device="cuda")
     net.calibrate(images, labels)
     rec = Recorder(xb)
-    resnet_cifar.xb = rec
+    resnet_cifar.xb = resnet_imagenet.xb = rec
     try:
         loss = net.train_step(images, labels, 0.05)
     finally:
-        resnet_cifar.xb = xb
+        resnet_cifar.xb = resnet_imagenet.xb = xb
     assert np.isfinite(loss.cpu().numpy()).all()
 
     names = [c[0] for c in rec.calls]
-    for want in ("tile", "conv_fwd", "conv_bwd", "conv_update", "fwd", "bwd", "update", "bn_fwd", "bn_bwd", "relu_fwd",
-                 "relu_bwd", "add", "avgpool_fwd", "avgpool_bwd", "shortcut_fwd", "shortcut_bwd", "softmax_xent", "sgd"):
+    wanted = ["tile", "conv_fwd", "conv_bwd", "conv_update", "fwd", "bwd", "update", "bn_fwd", "bn_bwd", "relu_fwd",
+              "relu_bwd", "add", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd"]
+    wanted += ["shortcut_fwd", "shortcut_bwd"] if kind == "basic_blocks" else ["maxpool_fwd", "maxpool_bwd"]
+    for want in wanted:
         assert want in names, want
-    assert names.count("conv_fwd") == 7 and names.count("conv_update") == 7 and names.count("conv_bwd") == 6
+    assert names.count("conv_fwd") == n_conv and names.count("conv_update") == n_conv
+    assert names.count("conv_bwd") == n_conv_bwd
 
     def geom_tuple(g):
         return g.k_h, g.k_w, g.stride, g.pad
@@ -87,16 +115,16 @@ def test_residual_network_step_op_by_op(xo):
         if name == "conv_fwd":
             g = args[3]
             want = xo.fwd(co, W, conv.im2col(a[2], *geom_tuple(g)), w_max, args[6], step=step)
-            assert rel_l2(out.reshape(-1, args[4]), want) <= 1e-3, name
+            assert crossbar_outputs_match(out, want, cfg, args[6], w_max, False), name
         elif name == "fwd":
-            assert rel_l2(out, xo.fwd(co, W, a[2], w_max, args[5], step=step)) <= 1e-3, name
+            assert crossbar_outputs_match(out, xo.fwd(co, W, a[2], w_max, args[5], step=step), cfg, args[5], w_max, False), name
         elif name == "conv_bwd":
             g = args[3]
             cols = xo.bwd(co, W, a[2].reshape(-1, args[4]), w_max, args[6], step=step)
             want = conv.col2im(cols, out.shape, *geom_tuple(g))
-            assert rel_l2(out, want) <= 1e-3, name
+            assert crossbar_outputs_match(out, want, cfg, args[6], w_max, True, overlaps=g.k_h * g.k_w), name
         elif name == "bwd":
-            assert rel_l2(out, xo.bwd(co, W, a[2], w_max, args[5], step=step)) <= 1e-3, name
+            assert crossbar_outputs_match(out, xo.bwd(co, W, a[2], w_max, args[5], step=step), cfg, args[5], w_max, True), name
         elif name in ("conv_update", "update"):
             co = oracle_config(xo, args[0])
             W0 = a[1]
@@ -129,6 +157,13 @@ def test_residual_network_step_op_by_op(xo):
             assert np.array_equal(out, periph.shortcut_fwd(a[0], args[1], args[2]).astype(np.float32))
         elif name == "shortcut_bwd":
             assert np.array_equal(out, periph.shortcut_bwd(a[0], args[1], args[2]).astype(np.float32))
+        elif name == "maxpool_fwd":
+            g = args[1]
+            y, arg = periph.maxpool_fwd(a[0], g.k_h, g.stride, g.pad)
+            assert np.array_equal(out[0], y.astype(np.float32)) and np.array_equal(out[1], arg)
+        elif name == "maxpool_bwd":
+            g = args[2]
+            assert rel_l2(out, periph.maxpool_bwd(a[0], a[1], (g.batch, g.in_h, g.in_w, g.in_c))) <= 1e-6
         elif name == "softmax_xent":
             lo, dz = periph.softmax_xent(a[0], a[1], np.float64(np.float32(args[2])))
             assert rel_l2(out[0], lo) <= 1e-6 and rel_l2(out[1], dz) <= 1e-6
