@@ -1798,6 +1798,9 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   return XBAR_OK;
 }
 
+// A 1 x 1 convolution with stride 1 and no padding IS its patch matrix: X[batch H W][C].
+inline bool conv_is_dense(const xbar_conv_geom* q) { return q->k_h == 1 && q->k_w == 1 && q->stride == 1 && q->pad == 0; }
+
 // Checks a convolution geometry and derives the layer's matrix shape: M = batch x output positions,
 // K = kernel height x kernel width x input channels.
 int conv_dims(const xbar_conv_geom* q, ConvGeom* g, int* M, int* K) {
@@ -2049,7 +2052,8 @@ int xbar_conv_fwd(const xbar_config* cfg, const void* planes, const float* X, fl
   int M, K;
   const int rc = conv_dims(geom, &g, &M, &K);
   if (rc) return rc;
-  return run_vmm(cfg, planes, X, Y, M, K, N, w_max, x_scale, ws, ws_bytes, codes, hip_stream, false, &g);
+  return run_vmm(cfg, planes, X, Y, M, K, N, w_max, x_scale, ws, ws_bytes, codes, hip_stream, false,
+                 conv_is_dense(geom) ? nullptr : &g);
 }
 
 int xbar_conv_bwd(const xbar_config* cfg, const void* planes, const float* dY, float* dX, const xbar_conv_geom* geom,
@@ -2063,6 +2067,8 @@ int xbar_conv_bwd(const xbar_config* cfg, const void* planes, const float* dY, f
   if (!aligned16(dX) || !aligned16(ws)) return XBAR_EALIGN;
   const size_t need = xbar_conv_workspace_bytes(cfg, XBAR_OP_BWD, geom, N);
   if (ws_bytes < need) return XBAR_EWORKSPACE;
+  if (conv_is_dense(geom))       // every pixel is its own patch: the crossbar output is the result
+    return run_vmm(cfg, planes, dY, dX, M, K, N, w_max, g_scale, ws, ws_bytes, nullptr, hip_stream, true);
   const size_t col_bytes = align256((size_t)M * K * sizeof(float));
   float* col = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + (need - col_bytes));
   if ((rc = run_vmm(cfg, planes, dY, col, M, K, N, w_max, g_scale, ws, need - col_bytes, nullptr, hip_stream, true))) return rc;
@@ -2080,7 +2086,8 @@ int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const flo
   int M, K;
   const int rc = conv_dims(geom, &g, &M, &K);
   if (rc) return rc;
-  return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream, &g);
+  return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream,
+                    conv_is_dense(geom) ? nullptr : &g);
 }
 
 int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* in, int M, int K, int N, float in_scale,

@@ -250,6 +250,7 @@ CONV_CASES = [
     ("3x3_same", 3, 10, 9, 16, 3, 1, 1, 40, 64, 2),
     ("3x3_stride2", 2, 11, 11, 24, 3, 2, 1, 33, 128, 1),
     ("1x1_downsample", 2, 8, 8, 70, 1, 2, 0, 96, 64, 4),
+    ("1x1_dense", 3, 7, 9, 40, 1, 1, 0, 50, 64, 2),               # the patch matrix is the image itself
     ("7x7_rgb", 2, 20, 18, 3, 7, 2, 3, 16, 128, 2),              # K = 147: channels do not fill a chunk of 8
     ("2x2_nopad", 1, 6, 6, 5, 2, 1, 0, 7, 64, 2),
 ]
