@@ -52,9 +52,9 @@ class HipEvents:
 def end_to_end(args, torch, workloads, xb, device):
     """Whole training steps of a residual network from images: the CIFAR-size ResNet-20 (19 convolutions +
     classifier) or ResNet-50 (53 convolutions + classifier)."""
-    from paper_2002_11151_amd import resnet_cifar, resnet_imagenet
-    assert args.workload in ("resnet20", "resnet50"), "--end-to-end: resnet20 or resnet50"
-    batch = args.batch or {"resnet20": 128, "resnet50": 64}[args.workload]
+    from paper_2002_11151_amd import resnet_cifar, resnet_imagenet, sequential
+    assert args.workload in ("mlp", "resnet20", "resnet50", "vgg16"), "--end-to-end: mlp, resnet20, resnet50 or vgg16"
+    batch = args.batch or {"mlp": 128, "resnet20": 128, "resnet50": 64, "vgg16": 128}[args.workload]
     kw = workloads.config_kwargs(args.workload)
     S_w, S_in = kw["weight_bits"] // kw["slice_bits"], kw["input_bits"] // kw["stream_bits"]
     gemms = workloads.GEMMS[args.workload](batch)
@@ -62,13 +62,20 @@ def end_to_end(args, torch, workloads, xb, device):
     tot["bwd"] -= workloads.macs(gemms[0], S_w, S_in)["bwd"]        # no error is propagated to the image
     gen = torch.Generator(device=device)
     gen.manual_seed(0)
-    image, classes = (32, 10) if args.workload == "resnet20" else (224, 1000)
-    images = torch.randn((batch, image, image, 3), generator=gen, device=device)
+    image, classes = {"mlp": (28, 10), "resnet20": (32, 10)}.get(args.workload, (224, 1000))
+    channels = 1 if args.workload == "mlp" else 3
+    images = torch.randn((batch, image, image, channels), generator=gen, device=device)
     labels = torch.randint(0, classes, (batch,), generator=gen, device=device).to(torch.int32)
     if args.workload == "resnet20":
         net = resnet_cifar.ResNetCifar(kw, batch=batch, n_blocks=3, image=32, classes=10, seed=0, device=device)
-    else:
+    elif args.workload == "resnet50":
         net = resnet_imagenet.ResNetBottleneck(kw, batch=batch, seed=0, device=device)
+    elif args.workload == "vgg16":
+        net = sequential.Sequential(kw, sequential.vgg16_spec(), batch, (224, 224, 3), seed=0, device=device)
+    else:
+        images = images.abs_()                               # pixel intensities: the first layer is unsigned
+        net = sequential.Sequential(kw, sequential.mlp_spec(), batch, (28, 28, 1), signed_input=False, seed=0,
+                                    device=device)
     net.calibrate(images, labels)
 
     events = HipEvents()
@@ -89,7 +96,7 @@ def end_to_end(args, torch, workloads, xb, device):
 
     traced = Traced()
     traced.timed = False
-    resnet_cifar.xb = resnet_imagenet.xb = traced
+    resnet_cifar.xb = resnet_imagenet.xb = sequential.xb = traced
     for _ in range(args.warmup):
         net.train_step(images, labels, 0.01)
     torch.cuda.synchronize()
@@ -99,7 +106,7 @@ def end_to_end(args, torch, workloads, xb, device):
         loss = net.train_step(images, labels, 0.01)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    resnet_cifar.xb = resnet_imagenet.xb = xb
+    resnet_cifar.xb = resnet_imagenet.xb = sequential.xb = xb
     vmm_ms = sum(events.elapsed_ms(a, b) for a, b in records)
     emulated = tot["fwd"] + tot["bwd"] + tot["upd"]
     achieved = 2.0 * (tot["fwd"] + tot["bwd"]) * args.steps / (vmm_ms * 1e-3) / 1e12
@@ -109,10 +116,10 @@ def end_to_end(args, torch, workloads, xb, device):
         "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f16 operands, f32 accumulate", "data": "synthetic",
-        "config": {"workload": "%s whole training step from %dx%dx3 images, batch %d, %dx%d crossbars, %d-bit "
+        "config": {"workload": "%s whole training step from %dx%dx%d images, batch %d, %dx%d crossbars, %d-bit "
                                "weights in %d slices, %d-bit inputs in %d cycles, %d-bit ADC, wire parasitics (AAM) + "
                                "write non-linearity + noise, digital batch norm / ReLU / pooling / loss" %
-                               (args.workload, image, image, batch, kw["xbar_rows"], kw["xbar_cols"], kw["weight_bits"], S_w, kw["input_bits"], S_in,
+                               (args.workload, image, image, channels, batch, kw["xbar_rows"], kw["xbar_cols"], kw["weight_bits"], S_w, kw["input_bits"], S_in,
                                 kw["adc_bits"]),
                    "emulated_macs_per_step": emulated, "logical_macs_per_step": tot["logical"]},
         "final_loss": round(float(loss.mean()), 4),
@@ -143,7 +150,7 @@ def main():
                     help="convolution layers take NHWC activations and gather their patches on the fly "
                          "(xbar_conv_*) instead of reading a patch matrix prepared outside the timed region")
     ap.add_argument("--end-to-end", action="store_true",
-                    help="resnet20 / resnet50: time whole training steps of the network (crossbar layers from images, "
+                    help="mlp / resnet20 / resnet50 / vgg16: time whole training steps of the network (crossbar layers from images, "
                          "digital batch norm / ReLU / pooling / loss) instead of the list of layer GEMMs")
     ap.add_argument("--overlap-update", action="store_true",
                     help="run the weight update of a layer beside its backward pass on a second stream (1 %% less "

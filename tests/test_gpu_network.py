@@ -64,12 +64,12 @@ def oracle_config(xo, cfg):
     return xo.make_config(**{f: getattr(cfg, f) for f, _ in type(cfg)._fields_ if f not in skip})
 
 
-@pytest.mark.parametrize("kind", ["basic_blocks", "bottleneck_blocks"])
+@pytest.mark.parametrize("kind", ["basic_blocks", "bottleneck_blocks", "plain_stack"])
 def test_residual_network_step_op_by_op(xo, kind):
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     from oracle import conv, periph
-    from paper_2002_11151_amd import resnet_cifar, resnet_imagenet, xbar as xb
+    from paper_2002_11151_amd import resnet_cifar, resnet_imagenet, sequential, xbar as xb
     kw = workloads.config_kwargs("resnet20")
     kw.update(xbar_rows=64, xbar_cols=64, weight_bits=8)
     kw["adc_fs_fwd"] = kw["adc_fs_bwd"] = workloads.adc_full_scale(64, kw["stream_bits"], kw["slice_bits"])
@@ -80,24 +80,31 @@ def test_residual_network_step_op_by_op(xo, kind):
         net = resnet_cifar.ResNetCifar(kw, batch=B, n_blocks=1, image=12, classes=10, widths=(8, 16, 16), seed=3)
         images = torch.randn((B, 12, 12, 3), generator=gen, device="cuda")
         n_conv, n_conv_bwd = 7, 6
-    else:
+    elif kind == "bottleneck_blocks":
         net = resnet_imagenet.ResNetBottleneck(kw, batch=B, image=24, classes=10, blocks=(1, 2), widths=(4, 8), stem=8,
                                                seed=3)
         images = torch.randn((B, 24, 24, 3), generator=gen, device="cuda")
         n_conv, n_conv_bwd = 1 + 3 * 3 + 2, 3 * 3 + 2                    # stem, 3 blocks of 3, 2 projections
+    else:
+        spec = [("conv", 8, 3, 1, 1), ("relu",), ("maxpool", 2, 2), ("conv", 16, 3, 1, 1), ("relu",), ("conv", 16, 3, 1, 1),
+                ("relu",), ("maxpool", 2, 2), ("flatten",), ("fc", 40), ("relu",), ("fc", 10)]
+        net = sequential.Sequential(kw, spec, batch=B, in_shape=(12, 12, 3), seed=3)
+        images = torch.randn((B, 12, 12, 3), generator=gen, device="cuda")
+        n_conv, n_conv_bwd = 3, 2
     labels = torch.tensor([1, 7, 4], dtype=torch.int32, device="cuda")
     net.calibrate(images, labels)
     rec = Recorder(xb)
-    resnet_cifar.xb = resnet_imagenet.xb = rec
+    resnet_cifar.xb = resnet_imagenet.xb = sequential.xb = rec
     try:
         loss = net.train_step(images, labels, 0.05)
     finally:
-        resnet_cifar.xb = resnet_imagenet.xb = xb
+        resnet_cifar.xb = resnet_imagenet.xb = sequential.xb = xb
     assert np.isfinite(loss.cpu().numpy()).all()
 
     names = [c[0] for c in rec.calls]
-    wanted = ["tile", "conv_fwd", "conv_bwd", "conv_update", "fwd", "bwd", "update", "bn_fwd", "bn_bwd", "relu_fwd",
-              "relu_bwd", "add", "avgpool_fwd", "avgpool_bwd", "softmax_xent", "sgd"]
+    wanted = ["tile", "conv_fwd", "conv_bwd", "conv_update", "fwd", "bwd", "update", "relu_fwd", "relu_bwd", "softmax_xent"]
+    if kind != "plain_stack":
+        wanted += ["bn_fwd", "bn_bwd", "add", "avgpool_fwd", "avgpool_bwd", "sgd"]
     wanted += ["shortcut_fwd", "shortcut_bwd"] if kind == "basic_blocks" else ["maxpool_fwd", "maxpool_bwd"]
     for want in wanted:
         assert want in names, want
