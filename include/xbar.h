@@ -39,8 +39,10 @@ extern "C" {
 #define XBAR_NI_WIRE_PROFILE 4u   /* wire parasitics from a stored distortion profile (Sec. IV-D)       */
 #define XBAR_NI_UPD_NL       8u   /* state-dependent write non-linearity (Sec. IV-C)                    */
 #define XBAR_NI_UPD_NOISE    16u  /* Gaussian write noise (Sec. IV-C)                                   */
-#define XBAR_DAC_LUT         32u  /* DAC levels from dac_lut instead of equidistant (Sec. IV-B); the GPU
-                                     kernels take it for 1-bit cycles with dac_lut[0] == 0, else ENOTSUP */
+#define XBAR_DAC_LUT         32u  /* DAC levels from dac_lut instead of equidistant (Sec. IV-B).  1-bit
+                                     cycles with dac_lut[0] == 0 cost nothing (one factor on the gain);
+                                     other tables up to 4 bits per cycle take one contraction per level
+                                     in the unpipelined kernel variant; 8-bit cycles: ENOTSUP            */
 #define XBAR_INPUT_SIGNED    64u  /* forward inputs are signed (two phases); backward always is         */
 #define XBAR_NI_WIRE_AAM2    128u /* wire parasitics, analytical model with every first-order path: the
                                      drops that all devices of a row / column cause on the wire segments

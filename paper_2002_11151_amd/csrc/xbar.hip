@@ -543,6 +543,8 @@ struct VmmArgs {
   void* part;          // [nchunk][M][Lout] int32 (narrow) or int64 (wide)
   int16_t* codes;      // optional [P][S_in][S_w][T][M][Lout]
   unsigned long long* hist;   // optional: kStatBins counters of |code| instead of the codes themselves
+  int dac_levels;             // 0: equidistant DAC levels; else 2^stream_bits entries of dac_lut are used
+  float dac_lut[16];          //    (general kernel variants only)
   int M, Lin, Lout, MP, OP, MB, T, P, VT;
   int S_w, S_in, slice_bits, stream_bits, ks, tile;
   int vt_per_chunk, nchunk, lds_kb;
@@ -572,6 +574,26 @@ __device__ __forceinline__ half8 digit_fragment(const u32x2 raw, uint32_t mask8)
   v.y = __builtin_amdgcn_perm(0u, m0, 0x0C030C02u);
   v.z = __builtin_amdgcn_perm(0u, m1, 0x0C010C00u);
   v.w = __builtin_amdgcn_perm(0u, m1, 0x0C030C02u);
+  return __builtin_bit_cast(half8, v);
+}
+
+// DAC level table: operand that is 1.0 where the digit of this cycle equals `level`, else 0 (the
+// currents of the levels are weighted with their table voltages afterwards).  Byte-parallel equality
+// test, then the bytes become the high bytes of fp16 lanes (0x3C00 = 1.0).
+__device__ __forceinline__ half8 level_fragment(const u32x2 raw, int in_shift, uint32_t digit_mask8, int level) {
+  const uint32_t want = (uint32_t)level * 0x01010101u;
+  uint32_t m[2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const uint32_t x = (((h ? raw.y : raw.x) >> in_shift) & digit_mask8) ^ want;      // zero byte <=> digit == level
+    const uint32_t nonzero = (((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u;
+    m[h] = ((nonzero ^ 0x80808080u) >> 7) * 0x3Cu;                                    // 0x3C per matching byte
+  }
+  u32x4 v;
+  v.x = __builtin_amdgcn_perm(0u, m[0], 0x010C000Cu);
+  v.y = __builtin_amdgcn_perm(0u, m[0], 0x030C020Cu);
+  v.z = __builtin_amdgcn_perm(0u, m[1], 0x010C000Cu);
+  v.w = __builtin_amdgcn_perm(0u, m[1], 0x030C020Cu);
   return __builtin_bit_cast(half8, v);
 }
 
@@ -731,16 +753,39 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
     for (int pm = 0; pm < PM; ++pm)
 #pragma unroll
       for (int j = 0; j < NK; ++j) ab[pm][j] = digit_fragment(raw[pm][j], mask8);
+    const float gain_lut = p ? -a.gain : a.gain;       // level operands are 1.0: no power of two to undo
     for (int sl = 0; sl < ns; ++sl) {
       const int s = sg0 + sl;
       const int sh = a.slice_bits * s + in_shift;
       float16v acc[PM];
-      vmm_contract<PM, NK, TERMS>(ab, lds + lane + (size_t)sl * NF * 64, acc);
+      if (CODES && a.dac_levels) {
+        // I = sum over levels of V_level x (current of the rows that sit at that level)
+#pragma unroll
+        for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[pm][r] = 0.0f;
+        for (int level = (a.dac_lut[0] != 0.0f ? 0 : 1); level < a.dac_levels; ++level) {
+#pragma unroll
+          for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+            for (int j = 0; j < NK; ++j) ab[pm][j] = level_fragment(raw[pm][j], in_shift, digit_mask8, level);
+          float16v part[PM];
+          vmm_contract<PM, NK, TERMS>(ab, lds + lane + (size_t)sl * NF * 64, part);
+          const float volt = a.dac_lut[level];
+#pragma unroll
+          for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[pm][r] = __builtin_fmaf(volt, part[pm][r], acc[pm][r]);
+        }
+      } else {
+        vmm_contract<PM, NK, TERMS>(ab, lds + lane + (size_t)sl * NF * 64, acc);
+      }
+      const float gain_used = (CODES && a.dac_levels) ? gain_lut : gain_b;
 #pragma unroll
       for (int pm = 0; pm < PM; ++pm) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float f = __builtin_fmaf(acc[pm][r], gain_b, vmagic);
+          float f = __builtin_fmaf(acc[pm][r], gain_used, vmagic);
           f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
           const uint32_t bits = __builtin_bit_cast(uint32_t, f);
           if (WIDE) {
@@ -755,7 +800,7 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
               int code = (int)(bits - kMagicBits);
               if (a.hist) {
                 atomicAdd(&stat_hist[min(::abs(code), kStatBins - 1)], 1u);
-              } else {
+              } else if (a.codes) {
                 if (p) code = -code;
                 a.codes[(((((size_t)p * a.S_in + b) * a.S_w + s) * a.T + t) * a.M + m) * a.Lout + o] = (int16_t)code;
               }
@@ -1728,11 +1773,14 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   if (codes && (reinterpret_cast<uintptr_t>(codes) & 1u)) return XBAR_EALIGN;
   if (!finite_pos(w_max) || !finite_pos(in_scale)) return XBAR_EINVAL;
   // DAC level table: with 1-bit cycles (the paper's streaming scheme) and a zero level at 0 V the
-  // table is one factor on every current, which goes into the ADC gain; other tables are not built.
+  // table is one factor on every current, which goes into the ADC gain.
+  // Other tables run through the general kernel variants, one contraction per level.
   float dac_gain = 1.0f;
+  bool level_table = false;
   if (cfg->flags & XBAR_DAC_LUT) {
-    if (cfg->stream_bits != 1 || cfg->dac_lut[0] != 0.0f) return XBAR_ENOTSUP;
-    dac_gain = cfg->dac_lut[1];
+    if (cfg->stream_bits == 1 && cfg->dac_lut[0] == 0.0f) dac_gain = cfg->dac_lut[1];
+    else if (cfg->stream_bits <= 4) level_table = true;
+    else return XBAR_ENOTSUP;                        // the table has 16 entries
   }
   const Derived d = derive(cfg);
   const VmmPlan p = plan_vmm(cfg, d, M, K, N, transposed);
@@ -1762,6 +1810,9 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.part = reinterpret_cast<char*>(ws) + p.a_bytes;
   a.codes = codes;
   a.hist = hist;
+  a.dac_levels = level_table ? 1 << cfg->stream_bits : 0;
+  // table entries are voltages over v_max; one input level is v_max / (2^stream_bits - 1)
+  for (int i = 0; i < 16; ++i) a.dac_lut[i] = (float)((double)cfg->dac_lut[i] * (double)((1 << cfg->stream_bits) - 1));
   a.M = M; a.Lin = p.Lin; a.Lout = p.Lout; a.MP = p.MP; a.OP = p.g.OP; a.MB = p.MB; a.T = p.g.T; a.P = p.P;
   a.VT = p.VT; a.S_w = d.S_w; a.S_in = d.S_in; a.slice_bits = cfg->slice_bits; a.stream_bits = cfg->stream_bits;
   a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.lds_kb = p.lds_kb;
@@ -1780,7 +1831,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   hipEvent_t ev0 = g_trace_before, ev1 = g_trace_after;
   g_trace_before = g_trace_after = nullptr;
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return XBAR_EHIP;
-  if (launch_vmm(a, p, d.terms, codes != nullptr || hist != nullptr, st) != hipSuccess) return XBAR_EHIP;
+  if (launch_vmm(a, p, d.terms, codes != nullptr || hist != nullptr || level_table, st) != hipSuccess) return XBAR_EHIP;
   if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return XBAR_EHIP;
   if (hist) return XBAR_OK;
 

@@ -424,6 +424,35 @@ def test_one_bit_dac_level_table(xo, xb):
     assert not np.array_equal(base, Yo)
 
 
+@pytest.mark.parametrize("sb,lut_kind,ni", [(2, "compressive", "aam"), (4, "compressive", "ideal"), (2, "offset", "aam"),
+                                            (1, "offset", "aam")])
+def test_dac_level_table(xo, xb, sb, lut_kind, ni):
+    """Non-linear DAC (Sec. IV-B: voltages depend on the user's choice of DAC): the level voltages come
+    from a table; the kernels weight the current of every level with its table entry."""
+    g = workloads.Gemm("t", 200, 70, 33, True, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=91)
+    levels = (1 << sb) - 1
+    lut = [(i / levels) ** 1.15 for i in range(levels + 1)]              # monotone, bowed
+    if lut_kind == "offset":
+        lut = [0.02 + 0.95 * v for v in lut]                              # the zero level leaks a little
+    kw = dict(xbar_rows=64, xbar_cols=128, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=sb, adc_bits=8,
+              flags=(xo.WIRE_AAM if ni == "aam" else 0) | xo.INPUT_SIGNED | xo.DAC_LUT, dac_lut=lut,
+              adc_fs_fwd=workloads.adc_full_scale(64, sb, 2), adc_fs_bwd=workloads.adc_full_scale(128, sb, 2))
+    co, cg = both_configs(xo, xb, **kw)
+    w_max, xs, gs = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    Yo, codes_o = xo.fwd(co, W, X, w_max, xs, want_codes=True)
+    Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, xs)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(Yg, Yo) <= 1e-3
+    assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, xs, codes=False), Yg)         # same kernel without the tap
+    dXo, codes_o = xo.bwd(co, W, dY, w_max, gs, want_codes=True)
+    dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, gs)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(dXg, dXo) <= 1e-3
+    linear = xo.fwd(xo.make_config(**dict(kw, flags=kw["flags"] & ~xo.DAC_LUT)), W, X, w_max, xs)
+    assert not np.array_equal(linear, Yo)
+
+
 def test_error_paths_on_device(xo, xb):
     cg = xb.make_config()
     W = torch.zeros((64, 64), device="cuda")
@@ -434,7 +463,7 @@ def test_error_paths_on_device(xo, xb):
         xb.fwd(cg, planes, X, 64, 1.0, 1.0, ws=small)
     with pytest.raises(xb.XbarError, match="workspace"):
         xb.tile(cg, W, 1.0, planes=small)
-    lut = xb.make_config(flags=xb.DAC_LUT, stream_bits=2, dac_lut=[0.0, 0.3, 0.7, 1.0])
+    lut = xb.make_config(flags=xb.DAC_LUT, stream_bits=8, dac_lut=[0.0, 0.3, 0.7, 1.0])       # 256 levels: no table
     with pytest.raises(xb.XbarError, match="not supported"):
         xb.fwd(lut, planes, X, 64, 1.0, 1.0)
     torch.cuda.synchronize()
