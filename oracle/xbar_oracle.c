@@ -46,6 +46,7 @@
 #define XO_DAC_LUT      32u
 #define XO_INPUT_SIGNED 64u
 #define XO_WIRE_AAM2    128u
+#define XO_ADC_CURVE    256u
 
 #define XO_STREAM_VARIATION 1u
 #define XO_STREAM_WRITE     2u
@@ -65,6 +66,7 @@ typedef struct xo_config {
   float upd_nl_v, upd_noise_gamma;
   float adc_fs_fwd, adc_fs_bwd;
   float dac_lut[16];
+  float adc_curve[17];
   uint64_t seed;
 } xo_config;
 
@@ -136,6 +138,26 @@ int64_t xo_adc(double current, float full_scale, int adc_bits) {
   int64_t q = (1ll << (adc_bits - 1)) - 1;
   float gain = (float)q / full_scale;
   double c = rint(current * (double)gain);
+  if (c > (double)q) c = (double)q;
+  if (c < -(double)q) c = -(double)q;
+  return (int64_t)c;
+}
+
+/* Non-linear converter (Sec. IV-B: the ADC model is the user's; Sec. V: the paper's is calibrated with
+ * SPICE): a monotone transfer curve f on the normalised current x = I / full_scale in [-1, 1], given
+ * by its values at the 17 equidistant points x = -1 + i / 8 and linear in between;
+ * code = clamp(rne(Q f(x)), -Q, Q).  The identity curve is the linear converter above.            */
+int64_t xo_adc_curve(const float* curve, double current, float full_scale, int adc_bits) {
+  int64_t q = (1ll << (adc_bits - 1)) - 1;
+  float gain = (float)q / full_scale;
+  double x = current * (double)gain / (double)q;
+  if (x > 1.0) x = 1.0;
+  if (x < -1.0) x = -1.0;
+  double t = (x + 1.0) * 8.0;
+  int i = (int)floor(t);
+  if (i > 15) i = 15;
+  double f = (double)curve[i] + (t - (double)i) * ((double)curve[i + 1] - (double)curve[i]);
+  double c = rint((double)q * f);
   if (c > (double)q) c = (double)q;
   if (c < -(double)q) c = -(double)q;
   return (int64_t)c;
@@ -330,7 +352,8 @@ static int vmm(const xo_config* cfg, const double* U, int Ks, int Ns, int transp
                 double u = transposed ? U[((size_t)s * Ks + o) * Ns + l] : U[((size_t)s * Ks + l) * Ns + o];
                 current += dac(cfg, digit) * u;
               }
-              int64_t code = xo_adc(current, adc_fs, cfg->adc_bits);
+              int64_t code = (cfg->flags & XO_ADC_CURVE) ? xo_adc_curve(cfg->adc_curve, current, adc_fs, cfg->adc_bits)
+                                                         : xo_adc(current, adc_fs, cfg->adc_bits);
               if (codes)
                 codes[(((((size_t)p * B + b) * S + s) * T + t) * M + m) * L_out + o] = (int32_t)code;
               int64_t weight = 1ll << (cfg->slice_bits * s + cfg->stream_bits * b);

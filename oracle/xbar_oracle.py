@@ -11,7 +11,8 @@ import numpy as np
 
 from . import build as _build
 
-VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED, WIRE_AAM2 = 1, 2, 4, 8, 16, 32, 64, 128
+VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED, WIRE_AAM2, ADC_CURVE = (
+    1, 2, 4, 8, 16, 32, 64, 128, 256)
 STREAM_VARIATION, STREAM_WRITE = 1, 2
 
 
@@ -29,6 +30,7 @@ class Config(C.Structure):
         ("upd_nl_v", C.c_float), ("upd_noise_gamma", C.c_float),
         ("adc_fs_fwd", C.c_float), ("adc_fs_bwd", C.c_float),
         ("dac_lut", C.c_float * 16),
+        ("adc_curve", C.c_float * 17),
         ("seed", C.c_uint64),
     ]
 
@@ -37,15 +39,18 @@ def make_config(**kw):
     """Config with the parameter values the paper states (Sec. V, Sec. VI-B); override by keyword."""
     c = Config()
     c.struct_size = C.sizeof(Config)
-    c.abi_version = 1
+    c.abi_version = 2
     d = dict(xbar_rows=64, xbar_cols=64, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=1,
              adc_bits=8, flags=0, r_min=1e5, r_max=1e6, v_max=1.0, r_row=1.0, r_col=4.6, r_source=0.0,
              r_sense=0.0, var_sigma=0.0, upd_nl_v=0.01, upd_noise_gamma=5.0, adc_fs_fwd=64.0,
              adc_fs_bwd=64.0, seed=0)
     d.update(kw)
     lut = d.pop("dac_lut", None)
+    curve = d.pop("adc_curve", None)
     for k, v in d.items():
         setattr(c, k, v)
+    for i in range(17):
+        c.adc_curve[i] = curve[i] if curve is not None else -1.0 + i / 8.0
     levels = (1 << c.stream_bits) - 1
     for i in range(16):
         c.dac_lut[i] = (lut[i] if lut is not None and i < len(lut) else (i / levels if i <= levels else 0.0))
@@ -68,6 +73,8 @@ def lib():
         _lib.xo_quantize_input.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int]
         _lib.xo_adc.restype = C.c_int64
         _lib.xo_adc.argtypes = [C.c_double, C.c_float, C.c_int]
+        _lib.xo_adc_curve.restype = C.c_int64
+        _lib.xo_adc_curve.argtypes = [C.POINTER(C.c_float), C.c_double, C.c_float, C.c_int]
         assert _lib.xo_config_size() == C.sizeof(Config)
     return _lib
 
@@ -125,6 +132,11 @@ def quantize_input(x, x_scale, bits, is_signed):
 
 def adc(current, full_scale, bits):
     return int(lib().xo_adc(current, full_scale, bits))
+
+
+def adc_curve(curve, current, full_scale, bits):
+    arr = (C.c_float * 17)(*curve)
+    return int(lib().xo_adc_curve(arr, C.c_double(current), C.c_float(full_scale), bits))
 
 
 def planes(cfg, W, w_max, step=0, profile=None, k_idx=None, n_idx=None, K_full=None, N_full=None):

@@ -120,6 +120,36 @@ def _int_grid_tensors(rng, M, K, N, wbits, signed):
     return q, a, W, X, w_max, x_scale
 
 
+def test_adc_transfer_curve(xo):
+    identity = [-1.0 + i / 8.0 for i in range(17)]
+    rng = np.random.default_rng(6)
+    for bits, fs in ((8, 64.0), (6, 100.0), (12, 3.0)):
+        q = (1 << (bits - 1)) - 1
+        for cur in rng.uniform(-1.5 * fs, 1.5 * fs, size=400):
+            assert xo.adc_curve(identity, cur, fs, bits) == xo.adc(cur, fs, bits)
+        # a curve that is linear with slope 1/2: half the code, full range never reached
+        half = [0.5 * v for v in identity]
+        for cur in rng.uniform(-fs, fs, size=200):
+            want = int(np.rint(0.5 * cur * float(np.float32(q) / np.float32(fs))))
+            assert abs(xo.adc_curve(half, cur, fs, bits) - want) <= 1          # rne of a halved value: ties may differ
+        assert xo.adc_curve(half, 10 * fs, fs, bits) == int(np.rint(0.5 * q))
+        # compressive curve: monotone in the current, equal to the knot values at the knots, saturating
+        bowed = [float(np.tanh(1.5 * v) / np.tanh(1.5)) for v in identity]
+        codes = [xo.adc_curve(bowed, cur, fs, bits) for cur in np.linspace(-1.2 * fs, 1.2 * fs, 301)]
+        assert all(b >= a for a, b in zip(codes, codes[1:])) and codes[0] == -q and codes[-1] == q
+        for i, v in enumerate(identity):
+            gain = float(np.float32(q) / np.float32(fs))
+            assert abs(xo.adc_curve(bowed, v * q / gain, fs, bits) - q * bowed[i]) <= 0.5 + 1e-9
+    # the curve is used by the layer: a compressive converter changes the outputs, the identity curve does not
+    W = rng.uniform(-1, 1, size=(40, 12)).astype(np.float32)
+    X = rng.uniform(0, 1, size=(5, 40)).astype(np.float32)
+    base = xo.make_config(xbar_rows=16, xbar_cols=16, adc_bits=6, adc_fs_fwd=8.0)
+    same = xo.make_config(xbar_rows=16, xbar_cols=16, adc_bits=6, adc_fs_fwd=8.0, flags=xo.ADC_CURVE)
+    bent = xo.make_config(xbar_rows=16, xbar_cols=16, adc_bits=6, adc_fs_fwd=8.0, flags=xo.ADC_CURVE, adc_curve=bowed)
+    assert np.array_equal(xo.fwd(base, W, X, 1.0, 1.0), xo.fwd(same, W, X, 1.0, 1.0))
+    assert not np.array_equal(xo.fwd(base, W, X, 1.0, 1.0), xo.fwd(bent, W, X, 1.0, 1.0))
+
+
 @pytest.mark.parametrize("R,C,sb,slb,wb,signed,M,K,N", [
     (8, 8, 1, 2, 8, False, 5, 19, 11),
     (8, 4, 4, 2, 8, True, 3, 8, 9),
