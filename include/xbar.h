@@ -31,7 +31,7 @@
 extern "C" {
 #endif
 
-#define XBAR_ABI_VERSION 1u
+#define XBAR_ABI_VERSION 2u
 
 /* flags */
 #define XBAR_NI_VARIATION    1u   /* per-device multiplicative Gaussian process variation (Sec. IV-A)   */
@@ -44,6 +44,8 @@ extern "C" {
                                      other tables up to 4 bits per cycle take one contraction per level
                                      in the unpipelined kernel variant; 8-bit cycles: ENOTSUP            */
 #define XBAR_INPUT_SIGNED    64u  /* forward inputs are signed (two phases); backward always is         */
+#define XBAR_ADC_CURVE       256u /* non-linear converter: monotone transfer curve adc_curve (Sec. IV-B, V);
+                                     runs in the unpipelined kernel variant                              */
 #define XBAR_NI_WIRE_AAM2    128u /* wire parasitics, analytical model with every first-order path: the
                                      drops that all devices of a row / column cause on the wire segments
                                      they share (Sec. IV-D: more paths than the shortest one); at most one
@@ -76,7 +78,7 @@ typedef struct xbar_config {
   int32_t input_bits;     /* magnitude bits of an input, 1..8                                         */
   int32_t stream_bits;    /* bits per DAC cycle, divides input_bits              paper: 1             */
   int32_t adc_bits;       /* 2..16, signed mid-tread converter with Q = 2^(adc_bits-1) - 1 codes/side */
-  uint32_t flags;         /* XBAR_NI_* | XBAR_DAC_LUT | XBAR_INPUT_SIGNED                             */
+  uint32_t flags;         /* XBAR_NI_* | XBAR_DAC_LUT | XBAR_ADC_CURVE | XBAR_INPUT_SIGNED            */
   float r_min, r_max;     /* device resistance range in Ohm                      paper: 1e5, 1e6      */
   float v_max;            /* input voltage range in V (results do not depend on it) paper: 1          */
   float r_row, r_col;     /* wire resistance per cell in Ohm                     paper: 1, 4.6        */
@@ -89,6 +91,10 @@ typedef struct xbar_config {
                           /*   rne(I * gain), -Q, Q) with gain = float(Q) / adc_fs in single          */
                           /*   precision; LSB = adc_fs / Q.                                           */
   float dac_lut[16];      /* voltage of DAC level i divided by v_max, used with XBAR_DAC_LUT          */
+  float adc_curve[17];    /* with XBAR_ADC_CURVE: values in [-1, 1], non-decreasing, of the converter's  */
+                          /*   transfer curve f at x = -1 + i/8 (x = current / adc_fs, clamped; linear   */
+                          /*   between the points); code = clamp(rne(Q f(x)), -Q, Q).  f(x) = x is the   */
+                          /*   linear converter.  Evaluated in single precision on the GPU.              */
   uint64_t seed;          /* key of the counter-based random numbers (Philox-4x32-10 + Box-Muller)    */
 } xbar_config;
 

@@ -545,6 +545,9 @@ struct VmmArgs {
   unsigned long long* hist;   // optional: kStatBins counters of |code| instead of the codes themselves
   int dac_levels;             // 0: equidistant DAC levels; else 2^stream_bits entries of dac_lut are used
   float dac_lut[16];          //    (general kernel variants only)
+  int adc_curve_on;           // non-linear converter (general kernel variants only)
+  float adc_curve[17];
+  float q_adc, inv_q_adc;
   int M, Lin, Lout, MP, OP, MB, T, P, VT;
   int S_w, S_in, slice_bits, stream_bits, ks, tile;
   int vt_per_chunk, nchunk, lds_kb;
@@ -785,9 +788,22 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
       for (int pm = 0; pm < PM; ++pm) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float f = __builtin_fmaf(acc[pm][r], gain_used, vmagic);
-          f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
-          const uint32_t bits = __builtin_bit_cast(uint32_t, f);
+          uint32_t bits;
+          if (CODES && a.adc_curve_on) {
+            // transfer curve on the true (phase-signed) current: x in [-1, 1], 16 linear pieces
+            const float u = acc[pm][r] * (p ? -gain_used : gain_used);          // ideal code units
+            const float v = fminf(fmaxf(u * a.inv_q_adc * 8.0f, -8.0f), 8.0f);    // x in units of one piece
+            const float start = fminf(floorf(v), 7.0f);                           // v - start is exact
+            const int piece = (int)start + 8;
+            const float lo = a.adc_curve[piece], hi = a.adc_curve[piece + 1];
+            const float fx = __builtin_fmaf(v - start, hi - lo, lo);
+            const float c = fminf(fmaxf(rintf(a.q_adc * fx), -a.q_adc), a.q_adc);
+            bits = kMagicBits + (uint32_t)(p ? -(int)c : (int)c);               // as the linear path leaves it
+          } else {
+            float f = __builtin_fmaf(acc[pm][r], gain_used, vmagic);
+            f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
+            bits = __builtin_bit_cast(uint32_t, f);
+          }
           if (WIDE) {
             y64[pm][r] += (long long)((int)(bits - kMagicBits)) << sh;
           } else {
@@ -1810,6 +1826,10 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.part = reinterpret_cast<char*>(ws) + p.a_bytes;
   a.codes = codes;
   a.hist = hist;
+  a.adc_curve_on = (cfg->flags & XBAR_ADC_CURVE) ? 1 : 0;
+  for (int i = 0; i < 17; ++i) a.adc_curve[i] = cfg->adc_curve[i];
+  a.q_adc = (float)d.q_adc;
+  a.inv_q_adc = 1.0f / (float)d.q_adc;
   a.dac_levels = level_table ? 1 << cfg->stream_bits : 0;
   // table entries are voltages over v_max; one input level is v_max / (2^stream_bits - 1)
   for (int i = 0; i < 16; ++i) a.dac_lut[i] = (float)((double)cfg->dac_lut[i] * (double)((1 << cfg->stream_bits) - 1));
@@ -1831,7 +1851,8 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   hipEvent_t ev0 = g_trace_before, ev1 = g_trace_after;
   g_trace_before = g_trace_after = nullptr;
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return XBAR_EHIP;
-  if (launch_vmm(a, p, d.terms, codes != nullptr || hist != nullptr || level_table, st) != hipSuccess) return XBAR_EHIP;
+  const bool general = codes != nullptr || hist != nullptr || level_table || a.adc_curve_on;
+  if (launch_vmm(a, p, d.terms, general, st) != hipSuccess) return XBAR_EHIP;
   if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return XBAR_EHIP;
   if (hist) return XBAR_OK;
 
@@ -1958,7 +1979,12 @@ int xbar_config_validate(const xbar_config* c) {
   if (c->input_bits < 1 || c->input_bits > 8) return XBAR_EINVAL;
   if (c->stream_bits < 1 || c->stream_bits > c->input_bits || c->input_bits % c->stream_bits) return XBAR_EINVAL;
   if (c->adc_bits < 2 || c->adc_bits > 16) return XBAR_EINVAL;
-  if (c->flags & ~0xFFu) return XBAR_EINVAL;
+  if (c->flags & ~0x1FFu) return XBAR_EINVAL;
+  if (c->flags & XBAR_ADC_CURVE)
+    for (int i = 0; i < 17; ++i) {
+      if (!std::isfinite(c->adc_curve[i]) || c->adc_curve[i] < -1.0f || c->adc_curve[i] > 1.0f) return XBAR_EINVAL;
+      if (i && c->adc_curve[i] < c->adc_curve[i - 1]) return XBAR_EINVAL;     // a converter is monotone
+    }
   {  // at most one wire model
     const uint32_t w = c->flags & (XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE | XBAR_NI_WIRE_AAM2);
     if (w & (w - 1)) return XBAR_EINVAL;
@@ -2150,6 +2176,7 @@ int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* 
   if (!aligned16(hist)) return XBAR_EALIGN;
   // a converter with one code per bin: code = rne(I / bin_width), clamped to the last bin
   xbar_config c = *cfg;
+  c.flags &= ~XBAR_ADC_CURVE;                        // the statistics are of the currents themselves
   c.adc_bits = 13;
   c.adc_fs_fwd = c.adc_fs_bwd = (float)(kStatBins - 1) * bin_width;
   if (!finite_pos(c.adc_fs_fwd)) return XBAR_EINVAL;

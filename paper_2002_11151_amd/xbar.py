@@ -11,10 +11,10 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libxbar.so")
 
-NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2 = (
-    1, 2, 4, 8, 16, 32, 64, 128)
+NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2, ADC_CURVE = (
+    1, 2, 4, 8, 16, 32, 64, 128, 256)
 OP_FWD, OP_BWD, OP_UPDATE, OP_FCM = 0, 1, 2, 3
-ABI_VERSION = 1
+ABI_VERSION = 2
 
 
 class XbarError(RuntimeError):
@@ -35,6 +35,7 @@ class Config(C.Structure):
         ("upd_nl_v", C.c_float), ("upd_noise_gamma", C.c_float),
         ("adc_fs_fwd", C.c_float), ("adc_fs_bwd", C.c_float),
         ("dac_lut", C.c_float * 16),
+        ("adc_curve", C.c_float * 17),
         ("seed", C.c_uint64),
     ]
 
@@ -62,8 +63,11 @@ def make_config(**kw):
              adc_fs_bwd=64.0, seed=0)
     d.update(kw)
     lut = d.pop("dac_lut", None)
+    curve = d.pop("adc_curve", None)
     for k, v in d.items():
         setattr(c, k, v)
+    for i in range(17):
+        c.adc_curve[i] = curve[i] if curve is not None else -1.0 + i / 8.0
     levels = max(1, (1 << max(0, min(4, c.stream_bits))) - 1)
     for i in range(16):
         c.dac_lut[i] = (lut[i] if lut is not None and i < len(lut) else (i / levels if i <= levels else 0.0))

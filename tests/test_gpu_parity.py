@@ -453,6 +453,34 @@ def test_dac_level_table(xo, xb, sb, lut_kind, ni):
     assert not np.array_equal(linear, Yo)
 
 
+@pytest.mark.parametrize("curve_kind,sb,bits", [("compressive", 1, 8), ("compressive", 4, 6), ("asymmetric", 2, 8)])
+def test_adc_transfer_curve(xo, xb, curve_kind, sb, bits):
+    """Non-linear converter (Sec. IV-B): a monotone 17-point transfer curve instead of the linear one."""
+    g = workloads.Gemm("t", 300, 90, 37, True, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=13)
+    xs_ = [-1.0 + i / 8.0 for i in range(17)]
+    if curve_kind == "compressive":
+        curve = [float(np.tanh(1.5 * v) / 1.5) for v in xs_]                  # unit small-signal gain, saturates at 0.6 Q
+    else:
+        curve = [0.9 * v if v < 0 else v ** 1.3 for v in xs_]                 # gain error below zero, bowed above
+    kw = dict(xbar_rows=128, xbar_cols=64, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=sb, adc_bits=bits,
+              flags=xo.WIRE_AAM | xo.INPUT_SIGNED | xo.ADC_CURVE, adc_curve=curve,
+              adc_fs_fwd=workloads.adc_full_scale(128, sb, 2), adc_fs_bwd=workloads.adc_full_scale(64, sb, 2))
+    co, cg = both_configs(xo, xb, **kw)
+    w_max, xs, gs = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    Yo, codes_o = xo.fwd(co, W, X, w_max, xs, want_codes=True)
+    Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, xs)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(Yg, Yo) <= 1e-3
+    assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, xs, codes=False), Yg)
+    dXo, codes_o = xo.bwd(co, W, dY, w_max, gs, want_codes=True)
+    dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, gs)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(dXg, dXo) <= 1e-3
+    linear = xo.fwd(xo.make_config(**dict(kw, flags=kw["flags"] & ~xo.ADC_CURVE)), W, X, w_max, xs)
+    assert rel_l2(linear, Yo) > 3e-3                                           # the curve matters here
+
+
 def test_error_paths_on_device(xo, xb):
     cg = xb.make_config()
     W = torch.zeros((64, 64), device="cuda")
