@@ -604,9 +604,12 @@ __device__ __forceinline__ half8 level_fragment(const u32x2 raw, int in_shift, u
 // instruction (the tile comes out transposed: lanes index the batch row, registers the output
 // column): with the sparse operand on the B port the chip sustains a ~15 % higher matrix rate under
 // its power limit than the other way round.
-// Contraction of one (slice, cycle): residual-term pass first (while the accumulator is small the
-// matrix core keeps all bits of the small products), then the leading term, which sits on a fixed
-// binary grid so that its products add without rounding.  Fragments are fetched two ahead.
+// Contraction of one (slice, cycle) in two passes over the k-steps: first the leading term, which sits
+// on a fixed binary grid so that its products add without any rounding, then the residual term onto
+// that exact sum.  Measured against the oracle this order leaves 1e-6 differing ADC codes, evenly one
+// LSB high and low; residual first leaves 4e-6 .. 1.4e-5, all one LSB low (the matrix instruction
+// rounds its sum downwards and did so at every leading-term step), and alternating the terms per
+// k-step 1e-4.  Fragments are fetched two ahead.
 template <int PM, int NK, int TERMS>
 __device__ __forceinline__ void vmm_contract(const half8 (&ab)[PM][NK], const u32x4* bptr, float16v (&acc)[PM]) {
   constexpr int NF = TERMS * NK;
@@ -856,8 +859,8 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
     for (int f = threadIdx.x >> 6; f < nfr; f += nwv) {
       const int sl = f / NF, r = f - sl * NF;
       const int term = r / NK, j = r - term * NK;
-      // LDS order within a slice: residual term (global term 1) first when there are two terms
-      const int gterm = TERMS == 2 ? 1 - term : 0;
+      // LDS order within a slice = global order: leading term (0), then residual term (1)
+      const int gterm = term;
       copy16_global_to_lds(src + ((sl * TERMS + gterm) * a.ks + j) * 64 + lane, lds + f * 64);
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
