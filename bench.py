@@ -56,6 +56,8 @@ def end_to_end(args, torch, workloads, xb, device):
     assert args.workload in ("mlp", "resnet20", "resnet50", "vgg16"), "--end-to-end: mlp, resnet20, resnet50 or vgg16"
     batch = args.batch or {"mlp": 128, "resnet20": 128, "resnet50": 64, "vgg16": 128}[args.workload]
     kw = workloads.config_kwargs(args.workload)
+    if args.adc_bits:
+        kw["adc_bits"] = args.adc_bits
     S_w, S_in = kw["weight_bits"] // kw["slice_bits"], kw["input_bits"] // kw["stream_bits"]
     gemms = workloads.GEMMS[args.workload](batch)
     tot = {k: sum(workloads.macs(g, S_w, S_in)[k] for g in gemms) for k in ("fwd", "bwd", "upd", "logical")}
@@ -149,6 +151,7 @@ def main():
     ap.add_argument("--from-images", action="store_true",
                     help="convolution layers take NHWC activations and gather their patches on the fly "
                          "(xbar_conv_*) instead of reading a patch matrix prepared outside the timed region")
+    ap.add_argument("--adc-bits", type=int, default=None, help="override the converter resolution of the workload")
     ap.add_argument("--end-to-end", action="store_true",
                     help="mlp / resnet20 / resnet50 / vgg16: time whole training steps of the network (crossbar layers from images, "
                          "digital batch norm / ReLU / pooling / loss) instead of the list of layer GEMMs")
@@ -190,6 +193,8 @@ def main():
         gemms = [g for g in gemms if g.name in args.only.split(",")]
         assert gemms, "no such layer"
     kw = workloads.config_kwargs(args.workload)
+    if args.adc_bits:
+        kw["adc_bits"] = args.adc_bits
     if args.ideal:
         kw["flags"] &= ~(workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE)
     if args.all_paths and kw["flags"] & workloads.NI_WIRE_AAM:
