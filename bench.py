@@ -98,7 +98,7 @@ def end_to_end(args, torch, workloads, xb, device):
 
     traced = Traced()
     traced.timed = False
-    resnet_cifar.xb = resnet_imagenet.xb = sequential.xb = traced
+    net.ops = traced
     for _ in range(args.warmup):
         net.train_step(images, labels, 0.01)
     torch.cuda.synchronize()
@@ -108,7 +108,6 @@ def end_to_end(args, torch, workloads, xb, device):
         loss = net.train_step(images, labels, 0.01)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
-    resnet_cifar.xb = resnet_imagenet.xb = sequential.xb = xb
     vmm_ms = sum(events.elapsed_ms(a, b) for a, b in records)
     emulated = tot["fwd"] + tot["bwd"] + tot["upd"]
     achieved = 2.0 * (tot["fwd"] + tot["bwd"]) * args.steps / (vmm_ms * 1e-3) / 1e12

@@ -10,7 +10,7 @@ A network is a list of layer specs:
 import torch
 
 from . import xbar as xb
-from .resnet_cifar import CrossbarLayer, calibrate_ranges
+from .resnet_cifar import CrossbarLayer, Network
 
 
 def vgg16_spec(classes=1000):
@@ -29,93 +29,76 @@ def mlp_spec(hidden=(500,), classes=10):
     return spec + [("fc", classes)]
 
 
-class Sequential:
+class Sequential(Network):
     def __init__(self, cfg_kwargs, spec, batch, in_shape, signed_input=True, seed=0, device="cuda"):
         """in_shape: (height, width, channels) of one sample, or (features,)."""
         gen = torch.Generator(device=device)
         gen.manual_seed(seed)
-        self.batch, self.ops, self.layers = batch, [], []
+        self.batch, self.stack, self.layers = batch, [], []
         shape = tuple(in_shape)
         signed = signed_input
-        max_rows = 1
         for op in spec:
             kind = op[0]
             if kind == "conv":
                 _, cout, k, stride, pad = op
                 h, w, c = shape
                 geom = xb.conv_geom(batch, h, w, c, k, k, stride, pad)
-                layer = CrossbarLayer(cfg_kwargs, k * k * c, cout, geom, signed, gen, device)
-                self.ops.append(("layer", layer))
+                layer = CrossbarLayer(self, cfg_kwargs, k * k * c, cout, geom, signed, gen, device)
+                self.stack.append(("layer", layer))
                 self.layers.append(layer)
                 shape, signed = (geom.out_h, geom.out_w, cout), True      # a raw layer output is signed
             elif kind == "fc":
                 (features,) = shape
-                layer = CrossbarLayer(cfg_kwargs, features, op[1], None, signed, gen, device)
-                self.ops.append(("layer", layer))
+                layer = CrossbarLayer(self, cfg_kwargs, features, op[1], None, signed, gen, device)
+                self.stack.append(("layer", layer))
                 self.layers.append(layer)
                 shape, signed = (op[1],), True
             elif kind == "relu":
-                self.ops.append(("relu", None))
+                self.stack.append(("relu", None))
                 signed = False
             elif kind == "maxpool":
                 h, w, c = shape
                 geom = xb.conv_geom(batch, h, w, c, op[1], op[1], op[2], 0)
-                self.ops.append(("maxpool", geom))
+                self.stack.append(("maxpool", geom))
                 shape = (geom.out_h, geom.out_w, c)
             elif kind == "flatten":
                 n = 1
                 for d in shape:
                     n *= d
-                self.ops.append(("flatten", shape))
+                self.stack.append(("flatten", shape))
                 shape = (n,)
             else:
                 raise ValueError("unknown layer spec %r" % (op,))
-            max_rows = max(max_rows, batch)
         self.ws = torch.empty(max(max(L.workspace_bytes(batch) for L in self.layers), 4096), dtype=torch.uint8,
                               device=device)
-        self.saved = [None] * len(self.ops)
+        self.saved = [None] * len(self.stack)
         self.step_no = 0
 
     def forward(self, x, step):
-        for i, (kind, arg) in enumerate(self.ops):
+        for i, (kind, arg) in enumerate(self.stack):
             if kind == "layer":
                 x = arg.forward(x, step, self.ws)
             elif kind == "relu":
-                x = xb.relu_fwd(x)
+                x = self.ops.relu_fwd(x)
                 self.saved[i] = x
             elif kind == "maxpool":
-                x, self.saved[i] = xb.maxpool_fwd(x, arg)
+                x, self.saved[i] = self.ops.maxpool_fwd(x, arg)
             else:                                             # flatten: NHWC rows are already contiguous
                 self.saved[i] = tuple(x.shape)
                 x = x.reshape(x.shape[0], -1)
         return x
 
     def backward(self, d, step, lr):
-        first_layer = next(i for i, (kind, _) in enumerate(self.ops) if kind == "layer")
-        for i in range(len(self.ops) - 1, -1, -1):
-            kind, arg = self.ops[i]
+        first_layer = next(i for i, (kind, _) in enumerate(self.stack) if kind == "layer")
+        for i in range(len(self.stack) - 1, -1, -1):
+            kind, arg = self.stack[i]
             if kind == "layer":
                 d = arg.backward(d, step, lr, self.ws, need_dx=i != first_layer)
             elif kind == "relu":
-                d = xb.relu_bwd(self.saved[i], d)
+                d = self.ops.relu_bwd(self.saved[i], d)
             elif kind == "maxpool":
-                d = xb.maxpool_bwd(d, self.saved[i], arg)
+                d = self.ops.maxpool_bwd(d, self.saved[i], arg)
             else:
                 d = d.reshape(self.saved[i])
             if d is None:
                 break
-
-    def train_step(self, x, labels, lr):
-        """One SGD step on a batch: returns the per-sample losses (device tensor)."""
-        step = self.step_no
-        logits = self.forward(x, step)
-        loss, dlogits = xb.softmax_xent(logits, labels, 1.0 / x.shape[0])
-        self.backward(dlogits, step, lr)
-        self.step_no += 1
-        return loss
-
-    def calibrate(self, x, labels):
-        calibrate_ranges(self, x, labels)
-
-    def _bns(self):
-        return []

@@ -94,11 +94,8 @@ def test_residual_network_step_op_by_op(xo, kind):
     labels = torch.tensor([1, 7, 4], dtype=torch.int32, device="cuda")
     net.calibrate(images, labels)
     rec = Recorder(xb)
-    resnet_cifar.xb = resnet_imagenet.xb = sequential.xb = rec
-    try:
-        loss = net.train_step(images, labels, 0.05)
-    finally:
-        resnet_cifar.xb = resnet_imagenet.xb = sequential.xb = xb
+    net.ops = rec
+    loss = net.train_step(images, labels, 0.05)
     assert np.isfinite(loss.cpu().numpy()).all()
 
     names = [c[0] for c in rec.calls]
