@@ -47,6 +47,7 @@
 #define XO_INPUT_SIGNED 64u
 #define XO_WIRE_AAM2    128u
 #define XO_ADC_CURVE    256u
+#define XO_ADC_PER_ARRAY 512u
 
 #define XO_STREAM_VARIATION 1u
 #define XO_STREAM_WRITE     2u
@@ -143,6 +144,18 @@ int64_t xo_adc(double current, float full_scale, int adc_bits) {
   return (int64_t)c;
 }
 
+/* Unsigned converter of one array (variant of Sec. IV-A's pair of arrays: instead of subtracting
+ * the two column currents in front of one signed converter, each array has a converter of its
+ * own and the codes are subtracted digitally): all 2^bits - 1 codes on the positive side.        */
+int64_t xo_adc_unsigned(double current, float full_scale, int adc_bits) {
+  int64_t q = (1ll << adc_bits) - 1;
+  float gain = (float)q / full_scale;
+  double c = rint(current * (double)gain);
+  if (c > (double)q) c = (double)q;
+  if (c < 0.0) c = 0.0;
+  return (int64_t)c;
+}
+
 /* Non-linear converter (Sec. IV-B: the ADC model is the user's; Sec. V: the paper's is calibrated with
  * SPICE): a monotone transfer curve f on the normalised current x = I / full_scale in [-1, 1], given
  * by its values at the 17 equidistant points x = -1 + i / 8 and linear in between;
@@ -218,6 +231,9 @@ int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_
   const double g_max = 1.0 / (double)cfg->r_min;
   const double dg = (g_max - g_min) / (double)levels;
   const uint32_t array_ni = cfg->flags & (XO_VARIATION | XO_WIRE_AAM | XO_WIRE_PROFILE | XO_WIRE_AAM2);
+  /* one converter per array: the two arrays are kept apart, U[pol][s][k][n] = G_ni(pol) / dG       */
+  const int per_array = (cfg->flags & XO_ADC_PER_ARRAY) != 0;
+  const size_t pol_stride = (size_t)S * Ks * Ns;
   int32_t d[64];
   if (S > 64) return -1;
   if (cfg->flags & XO_WIRE_AAM2) {
@@ -260,7 +276,12 @@ int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_
                        ((double)(R - (i > ii ? i : ii)) * (double)cfg->r_col + (double)cfg->r_sense);
                 e[pol] = Gp[(size_t)i * C + j] / (1.0 + a + b);
               }
-              U[((size_t)s * Ks + k0 + i) * Ns + n0 + j] = (e[0] - e[1]) / dg;
+              if (per_array) {
+                U[((size_t)s * Ks + k0 + i) * Ns + n0 + j] = e[0] / dg;
+                U[pol_stride + ((size_t)s * Ks + k0 + i) * Ns + n0 + j] = e[1] / dg;
+              } else {
+                U[((size_t)s * Ks + k0 + i) * Ns + n0 + j] = (e[0] - e[1]) / dg;
+              }
             }
         }
     free(G);
@@ -275,7 +296,7 @@ int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_
       xo_digits((uint64_t)(q < 0 ? -q : q), cfg->slice_bits, S, d);
       for (int s = 0; s < S; ++s) {
         double* out = &U[((size_t)s * Ks + ki) * Ns + ni];
-        if (!array_ni) {            /* ideal arrays: the pair difference is the digit itself */
+        if (!array_ni && !per_array) {   /* ideal arrays: the pair difference is the digit itself */
           *out = (double)(sign * d[s]);
           continue;
         }
@@ -292,7 +313,12 @@ int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_
             g[pol] = g[pol] * (1.0 - dist);
           }
         }
-        *out = (g[0] - g[1]) / dg;
+        if (per_array) {
+          out[0] = g[0] / dg;
+          out[pol_stride] = g[1] / dg;
+        } else {
+          *out = (g[0] - g[1]) / dg;
+        }
       }
     }
   }
@@ -328,7 +354,9 @@ static int vmm(const xo_config* cfg, const double* U, int Ks, int Ns, int transp
   const int L_out = transposed ? Ks : Ns;
   const int tile = transposed ? cfg->xbar_cols : cfg->xbar_rows;
   const int T = (L_in + tile - 1) / tile;
-  const int64_t q_adc = (1ll << (cfg->adc_bits - 1)) - 1;
+  const int per_array = (cfg->flags & XO_ADC_PER_ARRAY) != 0;
+  const int NP = per_array ? 2 : 1;
+  const int64_t q_adc = per_array ? (1ll << cfg->adc_bits) - 1 : (1ll << (cfg->adc_bits - 1)) - 1;
   const double lsb = (double)adc_fs / (double)q_adc;
   const double qa = (double)((1ll << cfg->input_bits) - 1);
   const double qw = (double)((1ll << cfg->weight_bits) - 1);
@@ -343,22 +371,26 @@ static int vmm(const xo_config* cfg, const double* U, int Ks, int Ns, int transp
       for (int p = 0; p < P; ++p)
         for (int b = 0; b < B; ++b)
           for (int s = 0; s < S; ++s)
-            for (int t = 0; t < T; ++t) {
-              int l0 = t * tile, l1 = l0 + tile < L_in ? l0 + tile : L_in;
-              double current = 0.0;
-              for (int l = l0; l < l1; ++l) {
-                int64_t mag = p == 0 ? (a[l] > 0 ? a[l] : 0) : (a[l] < 0 ? -a[l] : 0);
-                int digit = (int)((mag >> (cfg->stream_bits * b)) & ((1 << cfg->stream_bits) - 1));
-                double u = transposed ? U[((size_t)s * Ks + o) * Ns + l] : U[((size_t)s * Ks + l) * Ns + o];
-                current += dac(cfg, digit) * u;
+            for (int pol = 0; pol < NP; ++pol)
+              for (int t = 0; t < T; ++t) {
+                int l0 = t * tile, l1 = l0 + tile < L_in ? l0 + tile : L_in;
+                const double* Up = U + (size_t)pol * S * Ks * Ns;
+                double current = 0.0;
+                for (int l = l0; l < l1; ++l) {
+                  int64_t mag = p == 0 ? (a[l] > 0 ? a[l] : 0) : (a[l] < 0 ? -a[l] : 0);
+                  int digit = (int)((mag >> (cfg->stream_bits * b)) & ((1 << cfg->stream_bits) - 1));
+                  double u = transposed ? Up[((size_t)s * Ks + o) * Ns + l] : Up[((size_t)s * Ks + l) * Ns + o];
+                  current += dac(cfg, digit) * u;
+                }
+                int64_t code;
+                if (per_array) code = xo_adc_unsigned(current, adc_fs, cfg->adc_bits);
+                else if (cfg->flags & XO_ADC_CURVE) code = xo_adc_curve(cfg->adc_curve, current, adc_fs, cfg->adc_bits);
+                else code = xo_adc(current, adc_fs, cfg->adc_bits);
+                if (codes)      /* [phase][cycle][slice][array][tile][m][out] */
+                  codes[((((((size_t)p * B + b) * S + s) * NP + pol) * T + t) * M + m) * L_out + o] = (int32_t)code;
+                int64_t weight = 1ll << (cfg->slice_bits * s + cfg->stream_bits * b);
+                acc += (p == 0 ? 1 : -1) * (pol == 0 ? 1 : -1) * weight * code;
               }
-              int64_t code = (cfg->flags & XO_ADC_CURVE) ? xo_adc_curve(cfg->adc_curve, current, adc_fs, cfg->adc_bits)
-                                                         : xo_adc(current, adc_fs, cfg->adc_bits);
-              if (codes)
-                codes[(((((size_t)p * B + b) * S + s) * T + t) * M + m) * L_out + o] = (int32_t)code;
-              int64_t weight = 1ll << (cfg->slice_bits * s + cfg->stream_bits * b);
-              acc += (p == 0 ? 1 : -1) * weight * code;
-            }
       if (acc_out) acc_out[(size_t)m * L_out + o] = acc;
       out[(size_t)m * L_out + o] = (float)((double)acc * scale);
     }

@@ -11,8 +11,8 @@ import numpy as np
 
 from . import build as _build
 
-VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED, WIRE_AAM2, ADC_CURVE = (
-    1, 2, 4, 8, 16, 32, 64, 128, 256)
+VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED, WIRE_AAM2, ADC_CURVE, ADC_PER_ARRAY = (
+    1, 2, 4, 8, 16, 32, 64, 128, 256, 512)
 STREAM_VARIATION, STREAM_WRITE = 1, 2
 
 
@@ -73,6 +73,8 @@ def lib():
         _lib.xo_quantize_input.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int]
         _lib.xo_adc.restype = C.c_int64
         _lib.xo_adc.argtypes = [C.c_double, C.c_float, C.c_int]
+        _lib.xo_adc_unsigned.restype = C.c_int64
+        _lib.xo_adc_unsigned.argtypes = [C.c_double, C.c_float, C.c_int]
         _lib.xo_adc_curve.restype = C.c_int64
         _lib.xo_adc_curve.argtypes = [C.POINTER(C.c_float), C.c_double, C.c_float, C.c_int]
         assert _lib.xo_config_size() == C.sizeof(Config)
@@ -134,6 +136,10 @@ def adc(current, full_scale, bits):
     return int(lib().xo_adc(current, full_scale, bits))
 
 
+def adc_unsigned(current, full_scale, bits):
+    return int(lib().xo_adc_unsigned(C.c_double(current), C.c_float(full_scale), bits))
+
+
 def adc_curve(curve, current, full_scale, bits):
     arr = (C.c_float * 17)(*curve)
     return int(lib().xo_adc_curve(arr, C.c_double(current), C.c_float(full_scale), bits))
@@ -146,7 +152,9 @@ def planes(cfg, W, w_max, step=0, profile=None, k_idx=None, n_idx=None, K_full=N
     K_full = Ks if K_full is None else K_full
     N_full = Ns if N_full is None else N_full
     prof = None if profile is None else _f32(profile)
-    U = np.empty((n_slices(cfg), Ks, Ns), dtype=np.float64)
+    # one converter per array: the arrays are kept apart, U[array][slice][k][n]
+    shape = (2, n_slices(cfg), Ks, Ns) if cfg.flags & ADC_PER_ARRAY else (n_slices(cfg), Ks, Ns)
+    U = np.empty(shape, dtype=np.float64)
     rc = lib().xo_planes(C.byref(cfg), _p(W, C.c_float), Ks, Ns, _p(k_idx, C.c_int32), _p(n_idx, C.c_int32),
                          K_full, N_full, C.c_float(w_max), C.c_uint64(step), _p(prof, C.c_float),
                          _p(U, C.c_double))
@@ -171,15 +179,18 @@ def _tiles(cfg, length, transposed):
 
 
 def fwd_planes(cfg, U, X, w_max, x_scale, want_codes=False, want_acc=False):
-    """Forward VMM from generated planes U[S][K][Ns]; rows of X are independent."""
+    """Forward VMM from generated planes U[S][K][Ns] ([2][S][K][Ns] with one converter per array);
+    rows of X are independent.  Codes: [phase][cycle][slice][tile][m][n], with per-array converters
+    [phase][cycle][slice][array][tile][m][n]."""
     U = np.ascontiguousarray(U, dtype=np.float64)
     X = _f32(X)
-    S, K, Ns = U.shape
+    S, K, Ns = U.shape[-3:]
     M = X.shape[0]
-    assert X.shape[1] == K
+    assert X.shape[1] == K and U.ndim == (4 if cfg.flags & ADC_PER_ARRAY else 3)
     Y = np.empty((M, Ns), dtype=np.float32)
     P = 2 if cfg.flags & INPUT_SIGNED else 1
-    codes = np.empty((P, n_cycles(cfg), S, _tiles(cfg, K, False), M, Ns), dtype=np.int32) if want_codes else None
+    arrays = (2,) if cfg.flags & ADC_PER_ARRAY else ()
+    codes = np.empty((P, n_cycles(cfg), S) + arrays + (_tiles(cfg, K, False), M, Ns), dtype=np.int32) if want_codes else None
     acc = np.empty((M, Ns), dtype=np.int64) if want_acc else None
     rc = lib().xo_fwd_planes(C.byref(cfg), _p(U, C.c_double), _p(X, C.c_float), _p(Y, C.c_float), M, K, Ns,
                              C.c_float(w_max), C.c_float(x_scale), _p(codes, C.c_int32), _p(acc, C.c_int64))
@@ -191,11 +202,12 @@ def bwd_planes(cfg, U, dY, w_max, g_scale, want_codes=False, want_acc=False):
     """Backward VMM from generated planes U[S][Ks][N]; rows of dY are independent."""
     U = np.ascontiguousarray(U, dtype=np.float64)
     dY = _f32(dY)
-    S, Ks, N = U.shape
+    S, Ks, N = U.shape[-3:]
     M = dY.shape[0]
-    assert dY.shape[1] == N
+    assert dY.shape[1] == N and U.ndim == (4 if cfg.flags & ADC_PER_ARRAY else 3)
     dX = np.empty((M, Ks), dtype=np.float32)
-    codes = np.empty((2, n_cycles(cfg), S, _tiles(cfg, N, True), M, Ks), dtype=np.int32) if want_codes else None
+    arrays = (2,) if cfg.flags & ADC_PER_ARRAY else ()
+    codes = np.empty((2, n_cycles(cfg), S) + arrays + (_tiles(cfg, N, True), M, Ks), dtype=np.int32) if want_codes else None
     acc = np.empty((M, Ks), dtype=np.int64) if want_acc else None
     rc = lib().xo_bwd_planes(C.byref(cfg), _p(U, C.c_double), _p(dY, C.c_float), _p(dX, C.c_float), M, Ks, N,
                              C.c_float(w_max), C.c_float(g_scale), _p(codes, C.c_int32), _p(acc, C.c_int64))

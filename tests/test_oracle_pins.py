@@ -120,6 +120,57 @@ def _int_grid_tensors(rng, M, K, N, wbits, signed):
     return q, a, W, X, w_max, x_scale
 
 
+def test_one_converter_per_array(xo):
+    """Variant: every array has an unsigned converter of its own, the codes are subtracted digitally."""
+    rng = np.random.default_rng(12)
+    # converter closed form: all 2^bits - 1 codes on one side, nothing below zero
+    for bits, fs in ((8, 64.0), (4, 10.0)):
+        q = (1 << bits) - 1
+        assert xo.adc_unsigned(-3.0, fs, bits) == 0 and xo.adc_unsigned(2 * fs, fs, bits) == q
+        for cur in rng.uniform(0, fs, size=200):
+            assert xo.adc_unsigned(cur, fs, bits) == int(np.rint(cur * float(np.float32(q) / np.float32(fs))))
+    K, N, M = 20, 9, 6
+    q_w = rng.integers(-15, 16, size=(K, N))
+    W = (q_w / 15.0).astype(np.float32)
+    X = (rng.integers(-255, 256, size=(M, K)) / 255.0).astype(np.float32)
+    kw = dict(xbar_rows=8, xbar_cols=8, weight_bits=4, slice_bits=2, input_bits=8, stream_bits=4, r_min=1e4, r_max=1e5)
+    # planes: each array on its own, their difference is the merged plane of the one-converter model
+    merged = xo.planes(xo.make_config(flags=xo.WIRE_AAM, **kw), W, 1.0)
+    apart = xo.planes(xo.make_config(flags=xo.WIRE_AAM | xo.ADC_PER_ARRAY, **kw), W, 1.0)
+    assert apart.shape == (2,) + merged.shape and (apart > 0).all()
+    assert np.allclose(apart[0] - apart[1], merged, rtol=0, atol=1e-12)
+    # ideal arrays: the resting conductance of the other array is still there (Gmin / dG = 1/3 here)
+    ideal = xo.planes(xo.make_config(flags=xo.ADC_PER_ARRAY, **kw), W, 1.0)
+    dig = (np.abs(q_w) & 3)
+    assert np.allclose(ideal[0, 0], 1.0 / 3.0 + np.where(q_w > 0, dig, 0), atol=1e-12)
+    assert np.allclose(ideal[1, 0], 1.0 / 3.0 + np.where(q_w < 0, dig, 0), atol=1e-12)
+    # brute force of one output through both converters, codes and sum
+    cfg = xo.make_config(flags=xo.ADC_PER_ARRAY | xo.INPUT_SIGNED, adc_bits=6, adc_fs_fwd=40.0, **kw)
+    Y, codes, acc = xo.fwd(cfg, W, X, 1.0, 1.0, want_codes=True, want_acc=True)
+    assert codes.shape == (2, 2, 2, 2, 3, M, N) and codes.min() >= 0 and codes.max() <= 63
+    a = np.rint(X.astype(np.float64) * 255).astype(int)
+    m, n = 3, 5
+    total = 0
+    for p in range(2):
+        mag = np.where(a[m] > 0, a[m], 0) if p == 0 else np.where(a[m] < 0, -a[m], 0)
+        for b in range(2):
+            digit = (mag >> (4 * b)) & 15
+            for s in range(2):
+                for pol in range(2):
+                    for t in range(3):
+                        rows = slice(8 * t, min(8 * t + 8, K))
+                        cur = float((digit[rows] * ideal[pol, s, rows, n]).sum())
+                        code = min(max(int(np.rint(cur * float(np.float32(63) / np.float32(40.0)))), 0), 63)
+                        assert codes[p, b, s, pol, t, m, n] == code
+                        total += (1 if p == 0 else -1) * (1 if pol == 0 else -1) * code * (1 << (2 * s + 4 * b))
+    assert acc[m, n] == total
+    assert abs(Y[m, n] - total * (40.0 / 63) / (255 * 15)) < 1e-6
+    # with a fine converter the result approaches the one-converter model (the resting currents cancel)
+    fine1 = xo.fwd(xo.make_config(flags=xo.INPUT_SIGNED, adc_bits=16, adc_fs_fwd=400.0, **kw), W, X, 1.0, 1.0)
+    fine2 = xo.fwd(xo.make_config(flags=xo.INPUT_SIGNED | xo.ADC_PER_ARRAY, adc_bits=16, adc_fs_fwd=400.0, **kw), W, X, 1.0, 1.0)
+    assert np.abs(fine1 - fine2).max() < 2e-3 * np.abs(fine1).max()
+
+
 def test_adc_transfer_curve(xo):
     identity = [-1.0 + i / 8.0 for i in range(17)]
     rng = np.random.default_rng(6)
