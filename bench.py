@@ -145,6 +145,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
+    ap.add_argument("--adc-per-array", action="store_true",
+                    help="one unsigned converter per array and digital subtraction instead of one signed converter "
+                         "per array pair: twice the contraction work for the same emulated MACs")
     ap.add_argument("--all-paths", action="store_true",
                     help="wire model with every first-order path instead of the shortest path per device")
     ap.add_argument("--from-images", action="store_true",
@@ -198,9 +201,13 @@ def main():
         kw["flags"] &= ~(workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE)
     if args.all_paths and kw["flags"] & workloads.NI_WIRE_AAM:
         kw["flags"] = (kw["flags"] & ~workloads.NI_WIRE_AAM) | workloads.NI_WIRE_AAM2
+    arrays = 1
+    if args.adc_per_array:
+        kw["flags"] |= workloads.ADC_PER_ARRAY
+        arrays = 2
     S_w, S_in = kw["weight_bits"] // kw["slice_bits"], kw["input_bits"] // kw["stream_bits"]
-    terms = 2 if kw["flags"] & (workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE |
-                                workloads.NI_WIRE_AAM2) else 1
+    terms = 2 if arrays == 2 or kw["flags"] & (workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE |
+                                               workloads.NI_WIRE_AAM2) else 1
 
     # ---- resident tensors, one set per distinct shape ------------------------------------------
     layers = []
@@ -313,7 +320,7 @@ def main():
     for li, kind, (a, b) in vmm_records:
         ms = events.elapsed_ms(a, b)
         vmm_ms += ms
-        fl = 2.0 * layers[li]["macs"][kind]
+        fl = 2.0 * arrays * layers[li]["macs"][kind]          # arrays read one by one are contracted one by one
         vmm_flops += fl
         d = per_layer.setdefault((li, kind), [0.0, 0.0, 0])
         d[0] += ms
@@ -340,7 +347,7 @@ def main():
             probe[key] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
         roofline["sustained_mfma_tflops_bare_instruction"] = probe
     if (args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal and not args.all_paths
-            and not args.from_images):
+            and not args.adc_per_array and not args.from_images):
         roofline["traffic"] = VMM_TRAFFIC_BYTES_RESNET50_B64
     fcm_refresh_ms = None
     if args.fcm_refresh:
@@ -391,6 +398,13 @@ def main():
                "sample": "%d batch rows of each of the %d distinct layer shapes, fwd+bwd+update, %.1f s" %
                          (rows, len(layers), t_cpu)}
 
+    if kw["flags"] & (workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE | workloads.NI_WIRE_AAM2):
+        array_text = "wire parasitics (%s) + write non-linearity + noise" % (
+            "AAM, all first-order paths" if kw["flags"] & workloads.NI_WIRE_AAM2 else "AAM")
+    else:
+        array_text = "ideal arrays"
+    if arrays == 2:
+        array_text += ", one converter per array"
     line = {
         "metric": "emulated crossbar GMAC/s (fwd+bwd+update)", "value": round(value, 1), "unit": "GMAC/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
@@ -400,8 +414,7 @@ def main():
                                "%d-bit weights in %d slices, %d-bit inputs in %d cycles, %d-bit ADC, %s" %
                                (args.workload, sum(g.count for g in gemms), len(gemms), batch, kw["xbar_rows"],
                                 kw["xbar_cols"], kw["weight_bits"], S_w, kw["input_bits"], S_in, kw["adc_bits"],
-                                "ideal arrays" if terms == 1 else "wire parasitics (%s) + write non-linearity + noise" %
-                                ("AAM, all first-order paths" if kw["flags"] & workloads.NI_WIRE_AAM2 else "AAM")),
+                                array_text),
                    "emulated_macs_per_step": emulated, "logical_macs_per_step": tot["logical"]},
         "logical_gmacs": round(tot["logical"] / (elapsed / args.steps) / 1e9, 1),
         "roofline": roofline, "cpu_baseline": cpu,

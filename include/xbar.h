@@ -50,6 +50,12 @@ extern "C" {
                                      drops that all devices of a row / column cause on the wire segments
                                      they share (Sec. IV-D: more paths than the shortest one); at most one
                                      of the three wire flags                                             */
+#define XBAR_ADC_PER_ARRAY   512u /* one unsigned converter per array instead of one signed converter on
+                                     the difference of the array pair (a variant of the pair of Sec. IV-A):
+                                     code = clamp(rne(I_array * gain), 0, Q), Q = 2^adc_bits - 1, gain =
+                                     float(Q) / adc_fs; the codes of the negative array are subtracted
+                                     digitally.  Twice the conversions and contraction work; adc_bits <= 15;
+                                     not with XBAR_ADC_CURVE                                             */
 
 /* status codes */
 #define XBAR_OK          0
@@ -78,7 +84,8 @@ typedef struct xbar_config {
   int32_t input_bits;     /* magnitude bits of an input, 1..8                                         */
   int32_t stream_bits;    /* bits per DAC cycle, divides input_bits              paper: 1             */
   int32_t adc_bits;       /* 2..16, signed mid-tread converter with Q = 2^(adc_bits-1) - 1 codes/side */
-  uint32_t flags;         /* XBAR_NI_* | XBAR_DAC_LUT | XBAR_ADC_CURVE | XBAR_INPUT_SIGNED            */
+  uint32_t flags;         /* XBAR_NI_* | XBAR_DAC_LUT | XBAR_ADC_CURVE | XBAR_INPUT_SIGNED |          */
+                          /*   XBAR_ADC_PER_ARRAY                                                     */
   float r_min, r_max;     /* device resistance range in Ohm                      paper: 1e5, 1e6      */
   float v_max;            /* input voltage range in V (results do not depend on it) paper: 1          */
   float r_row, r_col;     /* wire resistance per cell in Ohm                     paper: 1, 4.6        */
@@ -106,7 +113,8 @@ uint32_t xbar_abi_version(void);
 /*
  * Non-ideal conductance matrix generator (Sec. IV-A, Sec. IV-D): weights -> bit-sliced conductance
  * planes per crossbar tile, stitched as U = (G+ - G-) / (one device level), in the operand layout of
- * the contraction kernels (one copy for the forward, one for the backward direction).
+ * the contraction kernels (one copy for the forward, one for the backward direction); with
+ * XBAR_ADC_PER_ARRAY the planes G+ / level and G- / level are kept apart (twice the bytes).
  *   W        [K][N] float, read only (the preserved ideal copy of Sec. IV-A)
  *   w_max    weights are clamped to [-w_max, w_max] and quantised to weight_bits magnitude bits,
  *            q = rne(clamp(W / w_max) * (2^weight_bits - 1)), evaluated in double precision
@@ -133,7 +141,9 @@ size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N)
  *   XBAR_INPUT_SIGNED else 0; every (row tile, slice, cycle, phase) column current is converted by
  *   its own ADC, the codes are shifted and added over slices, cycles, phases and row tiles in
  *   integers, and Y = float(double(sum) * lsb * x_scale * w_max / ((2^input_bits-1)(2^weight_bits-1))).
- *   codes: NULL, or int16 [phase][cycle][slice][row tile][M][N] receiving every ADC code (testing).
+ *   codes: NULL, or int16 [phase][cycle][slice][row tile][M][N] receiving every ADC code (testing);
+ *   with XBAR_ADC_PER_ARRAY [phase][cycle][slice][array][row tile][M][N], array 0 = positive weights,
+ *   and the sum takes the codes of array 1 negatively.
  */
 int xbar_fwd(const xbar_config* cfg, const void* planes, const float* X, float* Y, int M, int K, int N,
              float w_max, float x_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream);
@@ -142,7 +152,8 @@ int xbar_fwd(const xbar_config* cfg, const void* planes, const float* X, float* 
  * Backward VMM (Sec. IV: same procedure as forward): dX[M][K] from dY[M][N]; the same devices are
  * driven from the columns and read on the rows, one ADC conversion per (column tile, slice, cycle,
  * phase), accumulated over column tiles.  dY / g_scale is quantised like a signed forward input.
- *   codes: NULL, or int16 [phase][cycle][slice][column tile][M][K].
+ *   codes: NULL, or int16 [phase][cycle][slice][column tile][M][K] ([..][slice][array][column tile][..]
+ *   with XBAR_ADC_PER_ARRAY).
  */
 int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float* dX, int M, int K, int N,
              float w_max, float g_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream);
@@ -238,6 +249,7 @@ int xbar_absmax(const float* x, size_t n, float* result, void* ws, size_t ws_byt
  * converting, counts every column current that an ADC would see: hist[b] += number of conversions
  * with rne(|I| / bin_width) == b, the last of the 4096 bins takes everything beyond.  I and bin_width
  * are in the unit of adc_fs (one input level x one device level); adc_bits / adc_fs of cfg are not used.
+ * With XBAR_ADC_PER_ARRAY the currents counted are those of the single arrays.
  *   hist  4096 uint64 device counters, added to (clear them before the first call)
  *   ws    the workspace of the same xbar_fwd / xbar_bwd call
  * The caller picks adc_fs from the histogram (a high quantile, rounded up as it sees fit).

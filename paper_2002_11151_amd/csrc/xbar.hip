@@ -47,6 +47,7 @@ constexpr bool kBarrierPerMfma = false;   // scheduling fence after every MFMA (
 // ---------------------------------------------------------------------------------------------
 struct Derived {
   int S_w, S_in, terms, q_adc;
+  int npol;            // converters per crossbar column: 1 (pair read differentially) or 2 (one per array)
   uint32_t array_ni;
 };
 
@@ -55,8 +56,11 @@ inline Derived derive(const xbar_config* c) {
   d.S_w = c->weight_bits / c->slice_bits;
   d.S_in = c->input_bits / c->stream_bits;
   d.array_ni = c->flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE | XBAR_NI_WIRE_AAM2);
-  d.terms = d.array_ni ? 2 : 1;
-  d.q_adc = (1 << (c->adc_bits - 1)) - 1;
+  d.npol = (c->flags & XBAR_ADC_PER_ARRAY) ? 2 : 1;
+  // one array alone carries the off-state conductance of every device: never whole device levels
+  d.terms = (d.array_ni || d.npol == 2) ? 2 : 1;
+  // signed converter on the difference of the pair, or unsigned converter on one array's current
+  d.q_adc = d.npol == 2 ? (1 << c->adc_bits) - 1 : (1 << (c->adc_bits - 1)) - 1;
   return d;
 }
 
@@ -64,10 +68,11 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 // Plane buffer: forward copy then backward copy.  One copy is
-// [tile][output patch of 32][slice][term][k-step of 16][64 lanes][8 halves].
+// [array][tile][output patch of 32][slice][term][k-step of 16][64 lanes][8 halves]; there is one
+// "array" (the difference of the pair) unless every array has a converter of its own.
 struct PlaneGeom {
   int tile, ks, T, OP;          // contraction tile length, k-steps per tile, tiles, output patches
-  size_t bytes;
+  size_t pol_bytes, bytes;      // one array, all arrays
 };
 
 // Scratch of the all-paths wire model, kept behind the two plane copies.
@@ -81,7 +86,8 @@ inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N
   g.ks = g.tile / 16;
   g.T = cdiv(transposed ? N : K, g.tile);
   g.OP = cdiv(transposed ? K : N, 32);
-  g.bytes = (size_t)g.T * g.OP * d.S_w * d.terms * g.ks * 1024;
+  g.pol_bytes = (size_t)g.T * g.OP * d.S_w * d.terms * g.ks * 1024;
+  g.bytes = g.pol_bytes * d.npol;
   return g;
 }
 
@@ -142,6 +148,7 @@ struct TileArgs {
   uint16_t* planes;  // start of this copy
   int K, N, R, C, S_w, slice_bits, weight_bits, terms;
   int tile, ks, T, OP;
+  int pol_out;       // -1: difference of the pair (array 0 minus array 1); 0 / 1: that array alone
   uint32_t flags;
   double g_min, dg, var_sigma, r_row, r_col, r_source, r_sense, hi_scale, hi_inv_scale;
   float w_max;
@@ -149,11 +156,13 @@ struct TileArgs {
   long long n_threads;
 };
 
-// Signed plane value of slice s of weight (k, n), in units of one device level.
+// Plane value of slice s of weight (k, n), in units of one device level: the signed difference of the
+// device pair, or the conductance of one of the two devices.
 __device__ __forceinline__ double plane_value(const TileArgs& a, NormalStream& rng, int sign, int digit, int s, int k,
                                               int n) {
-  if (a.flags & XBAR_NI_WIRE_AAM2) return a.wire_u[((size_t)(2 * s) * a.K + k) * a.N + n];
-  if (!(a.flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE))) return (double)(sign * digit);
+  if (a.flags & XBAR_NI_WIRE_AAM2) return a.wire_u[((size_t)(2 * s + (a.pol_out > 0 ? 1 : 0)) * a.K + k) * a.N + n];
+  if (a.pol_out < 0 && !(a.flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE)))
+    return (double)(sign * digit);
   double g[2];
   g[0] = a.g_min + (sign > 0 ? digit * a.dg : 0.0);
   g[1] = a.g_min + (sign < 0 ? digit * a.dg : 0.0);
@@ -172,7 +181,7 @@ __device__ __forceinline__ double plane_value(const TileArgs& a, NormalStream& r
       g[pol] = g[pol] * (1.0 - dist);
     }
   }
-  return (g[0] - g[1]) / a.dg;
+  return (a.pol_out < 0 ? g[0] - g[1] : g[a.pol_out]) / a.dg;
 }
 
 // One thread produces the 8 consecutive contraction-index entries of one output column that make up
@@ -242,7 +251,7 @@ __global__ __launch_bounds__(256) void tile_planes_kernel(TileArgs a) {
 // Both sums split into a prefix and a suffix part, so one scan along the row and two walks along
 // the column replace the O(R + C) sum per device.  Scratch: A[S_w][2][K][N] (double) and the quantised
 // weights q[K][N]; the row kernel writes a into A, the column kernel adds b and leaves the plane
-// value in the slot of array 0.
+// value in the slot of array 0 (with one converter per array: each array's value in its own slot).
 // ---------------------------------------------------------------------------------------------
 struct WireArgs {
   const float* W;
@@ -411,7 +420,13 @@ __global__ __launch_bounds__(256) void wire_cols_kernel(WireArgs a) {
           const double b = a.r_col * ((double)(a.R - i) * above[pol] + below[pol]) + a.r_sense * total[pol];
           e[pol] = g[pol] / (1.0 + wa[u][pol] + b);
         }
-        a.A[((size_t)(2 * s) * a.K + k0 + i) * a.N + n0 + j] = (e[0] - e[1]) / a.dg;
+        const size_t at = ((size_t)(2 * s) * a.K + k0 + i) * a.N + n0 + j;
+        if (a.flags & XBAR_ADC_PER_ARRAY) {            // each array is read on its own
+          a.A[at] = e[0] / a.dg;
+          a.A[at + pol_stride] = e[1] / a.dg;
+        } else {
+          a.A[at] = (e[0] - e[1]) / a.dg;
+        }
       }
     }
   }
@@ -541,7 +556,7 @@ struct VmmArgs {
   const u32x2* A;      // quantised input fragments, 8 magnitudes (bytes) per lane
   const u32x4* B;      // plane fragments of this direction
   void* part;          // [nchunk][M][Lout] int32 (narrow) or int64 (wide)
-  int16_t* codes;      // optional [P][S_in][S_w][T][M][Lout]
+  int16_t* codes;      // optional [P][S_in][S_w][npol][T][M][Lout]
   unsigned long long* hist;   // optional: kStatBins counters of |code| instead of the codes themselves
   int dac_levels;             // 0: equidistant DAC levels; else 2^stream_bits entries of dac_lut are used
   float dac_lut[16];          //    (general kernel variants only)
@@ -549,6 +564,8 @@ struct VmmArgs {
   float adc_curve[17];
   float q_adc, inv_q_adc;
   int M, Lin, Lout, MP, OP, MB, T, P, VT;
+  int npol;                   // converters per column (1: differential, 2: one per array); VT = P * npol * T
+  size_t pol_stride;          // 16-byte units between the planes of the two arrays
   int S_w, S_in, slice_bits, stream_bits, ks, tile;
   int vt_per_chunk, nchunk, lds_kb;
   int total_wg, per_xcd;
@@ -697,15 +714,32 @@ __device__ __forceinline__ void vmm_contract_adc(const half8 (&ab)[PM][NK], cons
   }
 }
 
+// Sign with which the converter's code enters the sum (negative-phase inputs subtract, and so does the
+// array of the negative weights when it is read on its own) and the saturation bounds: a differential
+// converter saturates at -+ Q, one on a single array at 0 and Q (mirrored where the code is negated).
+template <bool PER_ARRAY>
+__device__ __forceinline__ void adc_sign_and_range(const VmmArgs& a, int p, int pol, float& gain, float& lo, float& hi) {
+  if constexpr (!PER_ARRAY) {
+    gain = p ? -a.gain : a.gain;
+    lo = a.clamp_lo;
+    hi = a.clamp_hi;
+  } else {
+    const bool neg = (p ^ pol) != 0;
+    gain = neg ? -a.gain : a.gain;
+    lo = neg ? a.clamp_lo : kMagic;
+    hi = neg ? kMagic : a.clamp_hi;
+  }
+}
+
 // Software-pipelined slice group (fast path: 32-bit accumulators, no code tap, even slice count).
-template <int PM, int KSMAX, int NK, int TERMS>
+template <int PM, int KSMAX, int NK, int TERMS, bool PER_ARRAY>
 __device__ __forceinline__ void vmm_tile_group_pipelined(const VmmArgs& a, const u32x4* lds,
-                                                         const u32x2 (&raw)[PM][KSMAX], int ns, int sg0, int p,
+                                                         const u32x2 (&raw)[PM][KSMAX], int ns, int sg0, int p, int pol,
                                                          int lane, uint32_t (&y)[PM][16]) {
   constexpr int NF = TERMS * NK;
   const uint32_t digit_mask8 = ((1u << a.stream_bits) - 1u) * 0x01010101u;
-  const float clamp_lo = a.clamp_lo, clamp_hi = a.clamp_hi;
-  const float gain_p = p ? -a.gain : a.gain;
+  float gain_p, clamp_lo, clamp_hi;
+  adc_sign_and_range<PER_ARRAY>(a, p, pol, gain_p, clamp_lo, clamp_hi);
   const u32x4* bbase = lds + lane;
   half8 ab[PM][NK];
   float16v acc0[PM], acc1[PM];
@@ -742,24 +776,26 @@ __device__ __forceinline__ void vmm_tile_group_pipelined(const VmmArgs& a, const
 
 // General slice group (64-bit accumulators and / or ADC code tap, any slice count): same arithmetic,
 // no software pipelining.
-template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES>
+template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES, bool PER_ARRAY>
 __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* lds, const u32x2 (&raw)[PM][KSMAX],
-                                               int ns, int sg0, int p, int t, int lane, int mp0, int op,
+                                               int ns, int sg0, int p, int pol, int t, int lane, int mp0, int op,
                                                uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
   constexpr int NF = TERMS * NK;
   const uint32_t digit_mask8 = ((1u << a.stream_bits) - 1u) * 0x01010101u;
   const float vmagic = kMagic;
-  const float clamp_lo = a.clamp_lo, clamp_hi = a.clamp_hi;
+  const int neg = PER_ARRAY ? p ^ pol : p;
+  float gain_p, clamp_lo, clamp_hi;
+  adc_sign_and_range<PER_ARRAY>(a, p, pol, gain_p, clamp_lo, clamp_hi);
   for (int b = 0; b < a.S_in; ++b) {
     const int in_shift = a.stream_bits * b;
     const uint32_t mask8 = digit_mask8 << in_shift;
-    const float gain_b = ldexpf(p ? -a.gain : a.gain, 24 - in_shift);
+    const float gain_b = ldexpf(gain_p, 24 - in_shift);
     half8 ab[PM][NK];
 #pragma unroll
     for (int pm = 0; pm < PM; ++pm)
 #pragma unroll
       for (int j = 0; j < NK; ++j) ab[pm][j] = digit_fragment(raw[pm][j], mask8);
-    const float gain_lut = p ? -a.gain : a.gain;       // level operands are 1.0: no power of two to undo
+    const float gain_lut = gain_p;                     // level operands are 1.0: no power of two to undo
     for (int sl = 0; sl < ns; ++sl) {
       const int s = sg0 + sl;
       const int sh = a.slice_bits * s + in_shift;
@@ -820,8 +856,9 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
               if (a.hist) {
                 atomicAdd(&stat_hist[min(::abs(code), kStatBins - 1)], 1u);
               } else if (a.codes) {
-                if (p) code = -code;
-                a.codes[(((((size_t)p * a.S_in + b) * a.S_w + s) * a.T + t) * a.M + m) * a.Lout + o] = (int16_t)code;
+                if (neg) code = -code;                   // what the converter itself read
+                const size_t converter = ((((size_t)p * a.S_in + b) * a.S_w + s) * (PER_ARRAY ? 2 : 1) + pol) * a.T + t;
+                a.codes[(converter * a.M + m) * a.Lout + o] = (int16_t)code;
               }
             }
           }
@@ -833,9 +870,10 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
 
 // One virtual tile (phase, contraction tile): load the raw magnitudes, then loop over slice groups:
 // stage the plane fragments of the group in LDS (compact: only the NK used k-steps), compute.
-template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES>
-__device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, int t, int lane, int mp0, int op,
+template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES, bool PER_ARRAY>
+__device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, int pol, int t, int lane, int mp0, int op,
                                          uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
+
   u32x2 raw[PM][KSMAX];
 #pragma unroll
   for (int pm = 0; pm < PM; ++pm)
@@ -850,6 +888,7 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
   for (int sg0 = 0; sg0 < a.S_w; sg0 += sg) {
     const int ns = min(sg, a.S_w - sg0);
     const u32x4* src = a.B + (((size_t)t * a.OP + op) * a.S_w + sg0) * TERMS * a.ks * 64;
+    if constexpr (PER_ARRAY) src += (size_t)pol * a.pol_stride;
     __syncthreads();                                   // everyone is done with the previous group
     // global [slice][term][ks][64] -> LDS [slice][term * NK + j][64]; one 1 KiB fragment per wave pass
     // Each wave copies whole 1 KiB fragments straight from global memory into LDS (no registers in
@@ -866,13 +905,13 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (!WIDE && !CODES && (ns & 1) == 0)
-      vmm_tile_group_pipelined<PM, KSMAX, NK, TERMS>(a, lds, raw, ns, sg0, p, lane, y);
+      vmm_tile_group_pipelined<PM, KSMAX, NK, TERMS, PER_ARRAY>(a, lds, raw, ns, sg0, p, pol, lane, y);
     else
-      vmm_tile_group<PM, KSMAX, NK, TERMS, WIDE, CODES>(a, lds, raw, ns, sg0, p, t, lane, mp0, op, y, y64);
+      vmm_tile_group<PM, KSMAX, NK, TERMS, WIDE, CODES, PER_ARRAY>(a, lds, raw, ns, sg0, p, pol, t, lane, mp0, op, y, y64);
   }
 }
 
-template <int PM, int KSMAX, int TERMS, bool WIDE, bool CODES>
+template <int PM, int KSMAX, int TERMS, bool WIDE, bool CODES, bool PER_ARRAY>
 __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
   extern __shared__ u32x4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -908,12 +947,14 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
   const int vt0 = chunk * vt_base + min(chunk, vt_rem);
   const int vt1 = vt0 + vt_base + (chunk < vt_rem ? 1 : 0);
   for (int vt = vt0; vt < vt1; ++vt) {
-    const int p = vt / a.T, t = vt - p * a.T;
+    // vt = (phase, array, tile), tile fastest
+    const int pa = vt / a.T, t = vt - pa * a.T;
+    const int p = PER_ARRAY ? pa >> 1 : pa, pol = PER_ARRAY ? pa & 1 : 0;
     const int rows = min(a.tile, a.Lin - t * a.tile);
     const int nk = (rows + 15) >> 4;
 #define XBAR_NK_CASE(n) \
   case n:               \
-    if constexpr (n <= KSMAX) vmm_tile<PM, KSMAX, n, TERMS, WIDE, CODES>(a, lds, p, t, lane, mp0, op, y, y64); \
+    if constexpr (n <= KSMAX) vmm_tile<PM, KSMAX, n, TERMS, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, lane, mp0, op, y, y64); \
     break;
     switch (nk) {
       XBAR_NK_CASE(1) XBAR_NK_CASE(2) XBAR_NK_CASE(3) XBAR_NK_CASE(4) XBAR_NK_CASE(5) XBAR_NK_CASE(6)
@@ -1688,7 +1729,7 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   p.Lout = transposed ? K : N;
   p.MP = cdiv(M, 32);
   p.P = (transposed || (c->flags & XBAR_INPUT_SIGNED)) ? 2 : 1;
-  p.VT = p.P * p.g.T;
+  p.VT = p.P * d.npol * p.g.T;
   // sum of the shift-and-add weights of one virtual tile
   unsigned long long wsum = 0;
   for (int s = 0; s < d.S_w; ++s)
@@ -1761,12 +1802,12 @@ UpdPlan plan_update(int M, int K, int N) {
   return p;
 }
 
-template <int PM, int KSMAX, int TERMS>
+template <int PM, int KSMAX, int TERMS, bool PER_ARRAY>
 hipError_t launch_vmm_variant(const VmmArgs& a, const VmmPlan& p, bool codes, hipStream_t st) {
   const dim3 grid((unsigned)(a.per_xcd * 8)), block((unsigned)(p.nw * 64));
   void (*k)(VmmArgs);
-  if (p.wide) k = codes ? vmm_kernel<PM, KSMAX, TERMS, true, true> : vmm_kernel<PM, KSMAX, TERMS, true, false>;
-  else k = codes ? vmm_kernel<PM, KSMAX, TERMS, false, true> : vmm_kernel<PM, KSMAX, TERMS, false, false>;
+  if (p.wide) k = codes ? vmm_kernel<PM, KSMAX, TERMS, true, true, PER_ARRAY> : vmm_kernel<PM, KSMAX, TERMS, true, false, PER_ARRAY>;
+  else k = codes ? vmm_kernel<PM, KSMAX, TERMS, false, true, PER_ARRAY> : vmm_kernel<PM, KSMAX, TERMS, false, false, PER_ARRAY>;
   if (p.lds_bytes > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)p.lds_bytes);
@@ -1778,8 +1819,10 @@ hipError_t launch_vmm_variant(const VmmArgs& a, const VmmPlan& p, bool codes, hi
 
 hipError_t launch_vmm(const VmmArgs& a, const VmmPlan& p, int terms, bool codes, hipStream_t st) {
   const int ks = p.g.ks;
-  if (ks <= 8) return terms == 2 ? launch_vmm_variant<2, 8, 2>(a, p, codes, st) : launch_vmm_variant<2, 8, 1>(a, p, codes, st);
-  return terms == 2 ? launch_vmm_variant<1, 16, 2>(a, p, codes, st) : launch_vmm_variant<1, 16, 1>(a, p, codes, st);
+  if (a.npol == 2)                                    // planes of single arrays always come in two terms
+    return ks <= 8 ? launch_vmm_variant<2, 8, 2, true>(a, p, codes, st) : launch_vmm_variant<1, 16, 2, true>(a, p, codes, st);
+  if (ks <= 8) return terms == 2 ? launch_vmm_variant<2, 8, 2, false>(a, p, codes, st) : launch_vmm_variant<2, 8, 1, false>(a, p, codes, st);
+  return terms == 2 ? launch_vmm_variant<1, 16, 2, false>(a, p, codes, st) : launch_vmm_variant<1, 16, 1, false>(a, p, codes, st);
 }
 
 int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* out, int M, int K, int N,
@@ -1837,6 +1880,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   // table entries are voltages over v_max; one input level is v_max / (2^stream_bits - 1)
   for (int i = 0; i < 16; ++i) a.dac_lut[i] = (float)((double)cfg->dac_lut[i] * (double)((1 << cfg->stream_bits) - 1));
   a.M = M; a.Lin = p.Lin; a.Lout = p.Lout; a.MP = p.MP; a.OP = p.g.OP; a.MB = p.MB; a.T = p.g.T; a.P = p.P;
+  a.npol = d.npol; a.pol_stride = p.g.pol_bytes / 16;
   a.VT = p.VT; a.S_w = d.S_w; a.S_in = d.S_in; a.slice_bits = cfg->slice_bits; a.stream_bits = cfg->stream_bits;
   a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.lds_kb = p.lds_kb;
   a.total_wg = p.nchunk * p.g.OP * p.MB;
@@ -1982,7 +2026,11 @@ int xbar_config_validate(const xbar_config* c) {
   if (c->input_bits < 1 || c->input_bits > 8) return XBAR_EINVAL;
   if (c->stream_bits < 1 || c->stream_bits > c->input_bits || c->input_bits % c->stream_bits) return XBAR_EINVAL;
   if (c->adc_bits < 2 || c->adc_bits > 16) return XBAR_EINVAL;
-  if (c->flags & ~0x1FFu) return XBAR_EINVAL;
+  if (c->flags & ~0x3FFu) return XBAR_EINVAL;
+  if (c->flags & XBAR_ADC_PER_ARRAY) {
+    if (c->flags & XBAR_ADC_CURVE) return XBAR_EINVAL;     // the curve is that of a signed converter
+    if (c->adc_bits > 15) return XBAR_EINVAL;              // unsigned codes are reported as int16
+  }
   if (c->flags & XBAR_ADC_CURVE)
     for (int i = 0; i < 17; ++i) {
       if (!std::isfinite(c->adc_curve[i]) || c->adc_curve[i] < -1.0f || c->adc_curve[i] > 1.0f) return XBAR_EINVAL;
@@ -2061,13 +2109,15 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   }
   size_t offset = 0;
-  for (int dir = 0; dir < 2; ++dir) {
+  for (int dir = 0; dir < 2; ++dir)
+  for (int pol = 0; pol < d.npol; ++pol) {
     const PlaneGeom g = plane_geom(cfg, d, K, N, dir == 1);
     TileArgs a;
     a.W = W;
     a.profile = profile;
     a.wire_u = wire_u;
-    a.planes = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(planes) + offset);
+    a.pol_out = d.npol == 2 ? pol : -1;
+    a.planes = reinterpret_cast<uint16_t*>(reinterpret_cast<char*>(planes) + offset + (size_t)pol * g.pol_bytes);
     a.K = K; a.N = N; a.R = cfg->xbar_rows; a.C = cfg->xbar_cols; a.S_w = d.S_w;
     a.slice_bits = cfg->slice_bits; a.weight_bits = cfg->weight_bits; a.terms = d.terms;
     a.tile = g.tile; a.ks = g.ks; a.T = g.T; a.OP = g.OP;
@@ -2079,8 +2129,9 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
     a.r_col = (double)cfg->r_col;
     a.r_source = (double)cfg->r_source;
     a.r_sense = (double)cfg->r_sense;
-    {  // |U| < 2^slice_bits: fp16 holds multiples of 2^-(11 - slice_bits) below that bound exactly
-      const int hi_frac = 11 - cfg->slice_bits;
+    {  // |U| < 2^slice_bits: fp16 holds multiples of 2^-(11 - slice_bits) below that bound exactly; one
+       // array alone adds the off-state conductance (below the full range for on/off ratios from 2): one bit less
+      const int hi_frac = (d.npol == 2 ? 10 : 11) - cfg->slice_bits;
       a.hi_scale = std::ldexp(1.0, hi_frac);
       a.hi_inv_scale = std::ldexp(1.0, -hi_frac);
     }
@@ -2095,7 +2146,7 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
     if (dir == 0) hipLaunchKernelGGL(tile_planes_kernel<false>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
     else hipLaunchKernelGGL(tile_planes_kernel<true>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
-    offset += align256(g.bytes);
+    if (pol == d.npol - 1) offset += align256(g.bytes);
   }
   return XBAR_OK;
 }
@@ -2180,7 +2231,7 @@ int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* 
   // a converter with one code per bin: code = rne(I / bin_width), clamped to the last bin
   xbar_config c = *cfg;
   c.flags &= ~XBAR_ADC_CURVE;                        // the statistics are of the currents themselves
-  c.adc_bits = 13;
+  c.adc_bits = (c.flags & XBAR_ADC_PER_ARRAY) ? 12 : 13;   // 4095 codes on the side(s) the converter has
   c.adc_fs_fwd = c.adc_fs_bwd = (float)(kStatBins - 1) * bin_width;
   if (!finite_pos(c.adc_fs_fwd)) return XBAR_EINVAL;
   return run_vmm(&c, planes, in, nullptr, M, K, N, 1.0f, in_scale, ws, ws_bytes, nullptr, hip_stream, op == XBAR_OP_BWD,

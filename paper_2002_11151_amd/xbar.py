@@ -11,8 +11,8 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libxbar.so")
 
-NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2, ADC_CURVE = (
-    1, 2, 4, 8, 16, 32, 64, 128, 256)
+(NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2, ADC_CURVE,
+ ADC_PER_ARRAY) = (1, 2, 4, 8, 16, 32, 64, 128, 256, 512)
 OP_FWD, OP_BWD, OP_UPDATE, OP_FCM = 0, 1, 2, 3
 ABI_VERSION = 2
 
@@ -198,6 +198,12 @@ def tile(cfg, W, w_max, step=0, profile=None, planes=None):
     return planes
 
 
+def _codes_shape(cfg, P, T, M, out_cols):
+    """[phase][cycle][slice][tile][M][out], with an [array] axis before [tile] when every array has its converter."""
+    head = (P, cfg.input_bits // cfg.stream_bits, cfg.weight_bits // cfg.slice_bits)
+    return head + ((2,) if cfg.flags & ADC_PER_ARRAY else ()) + (T, M, out_cols)
+
+
 def _vmm(fn, op, cfg, planes, inp, out_cols, K, N, w_max, in_scale, ws, out, want_codes):
     M = inp.shape[0]
     nbytes = workspace_bytes(cfg, op, M, K, N)
@@ -212,8 +218,7 @@ def _vmm(fn, op, cfg, planes, inp, out_cols, K, N, w_max, in_scale, ws, out, wan
         tile_len = cfg.xbar_cols if op == OP_BWD else cfg.xbar_rows
         lin = N if op == OP_BWD else K
         T = (lin + tile_len - 1) // tile_len
-        codes = torch.zeros((P, cfg.input_bits // cfg.stream_bits, cfg.weight_bits // cfg.slice_bits, T, M, out_cols),
-                            dtype=torch.int16, device=inp.device)
+        codes = torch.zeros(_codes_shape(cfg, P, T, M, out_cols), dtype=torch.int16, device=inp.device)
     _check(fn(C.byref(cfg), C.c_void_p(planes.data_ptr()), _dev(inp), _dev(out), M, K, N, w_max, in_scale,
               C.c_void_p(ws.data_ptr()), ws.numel(), None if codes is None else C.c_void_p(codes.data_ptr()),
               _stream()))
@@ -279,8 +284,7 @@ def conv_fwd(cfg, planes, X, geom, N, w_max, x_scale, ws=None, out=None, want_co
         P = 2 if cfg.flags & INPUT_SIGNED else 1
         K, M = geom.k_h * geom.k_w * geom.in_c, geom.batch * geom.out_h * geom.out_w
         T = (K + cfg.xbar_rows - 1) // cfg.xbar_rows
-        codes = torch.zeros((P, cfg.input_bits // cfg.stream_bits, cfg.weight_bits // cfg.slice_bits, T, M, N),
-                            dtype=torch.int16, device=X.device)
+        codes = torch.zeros(_codes_shape(cfg, P, T, M, N), dtype=torch.int16, device=X.device)
     _check(lib().xbar_conv_fwd(C.byref(cfg), C.c_void_p(planes.data_ptr()), _dev(X), _dev(out), C.byref(geom), N, w_max,
                                x_scale, C.c_void_p(ws.data_ptr()), ws.numel(),
                                None if codes is None else C.c_void_p(codes.data_ptr()), _stream()))

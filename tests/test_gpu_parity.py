@@ -139,6 +139,14 @@ NONIDEAL_CASES = [
     ("aam2_var_256", 256, 256, 1, 2, 16, True, 40, 520, 300, "aam2+var", 0.1),
     ("aam2_narrow", 128, 48, 2, 2, 8, False, 33, 129, 100, "aam2+var", 0.05),
     ("aam2_wide", 32, 208, 1, 4, 8, True, 20, 70, 420, "aam2", 0.0),
+    # one unsigned converter per array, codes of the negative array subtracted digitally
+    ("pa_ideal", 128, 128, 1, 2, 16, True, 45, 300, 100, "pa", 0.0),
+    ("pa_aam_var", 128, 128, 1, 2, 16, True, 45, 147, 64, "pa+aam+var", 0.1),
+    ("pa_aam2", 64, 64, 4, 2, 8, False, 64, 256, 256, "pa+aam2", 0.0),
+    ("pa_aam2_var_256", 256, 256, 1, 2, 16, True, 40, 520, 300, "pa+aam2+var", 0.1),
+    ("pa_profile", 128, 128, 4, 2, 8, True, 20, 200, 96, "pa+profile", 0.0),
+    ("pa_odd_slices", 128, 128, 1, 2, 6, False, 40, 200, 70, "pa+aam", 0.0),
+    ("pa_slice4", 64, 64, 2, 4, 8, False, 30, 100, 50, "pa+aam+var", 0.05),
 ]
 
 
@@ -152,19 +160,27 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
     flags |= xo.WIRE_AAM2 if "aam2" in ni else 0
     flags |= xo.VARIATION if "var" in ni else 0
     flags |= xo.WIRE_PROFILE if "profile" in ni else 0
+    flags |= xo.ADC_PER_ARRAY if "pa" in ni else 0
     profile = None
     if "profile" in ni:
         rng = np.random.default_rng(5)
         profile = rng.uniform(0.0, 0.02, size=(wb // slb, 2, K, N)).astype(np.float32)
+    # Ideal arrays read one by one carry currents that are whole multiples of a third of a device level
+    # (off-state conductance over level spacing = 1/3): with a power-of-two range one conversion in 64
+    # would sit exactly on a code boundary, where the rounding noise of either side decides.  A range
+    # off the binary grid has no such ties.
+    fs_factor = 1.037 if "pa" in ni else 1.0
     co, cg = both_configs(xo, xb, xbar_rows=R, xbar_cols=C, weight_bits=wb, slice_bits=slb, input_bits=8,
                           stream_bits=sb, adc_bits=8, flags=flags, var_sigma=var_sigma, seed=11,
-                          adc_fs_fwd=workloads.adc_full_scale(R, sb, slb),
-                          adc_fs_bwd=workloads.adc_full_scale(C, sb, slb))
+                          adc_fs_fwd=fs_factor * workloads.adc_full_scale(R, sb, slb),
+                          adc_fs_bwd=fs_factor * workloads.adc_full_scale(C, sb, slb))
     w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
     Yo, codes_o = xo.fwd(co, W, X, w_max, x_scale, step=3, profile=profile, want_codes=True)
     Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=3, profile=profile)
     check_codes(codes_g, codes_o)
     assert rel_l2(Yg, Yo) <= 1e-3
+    if "pa" in ni:                                   # unsigned codes (several of the cases saturate at 255)
+        assert codes_o.min() >= 0 and codes_o.max() > 127
     # the production launch (no code tap: software-pipelined, 32-bit accumulators) gives the same bits
     assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, x_scale, step=3, profile=profile, codes=False), Yg)
     dXo, codes_o = xo.bwd(co, W, dY, w_max, g_scale, step=3, profile=profile, want_codes=True)
@@ -299,16 +315,18 @@ def test_convolution_layer(xo, xb, name, B, H, W, C, k, stride, pad, N, R, sb):
 
 
 @pytest.mark.parametrize("ni,R,sb,M,K,N", [("ideal", 64, 2, 50, 200, 70), ("aam", 128, 1, 40, 300, 100),
-                                          ("aam+var", 256, 4, 33, 520, 48)])
+                                          ("aam+var", 256, 4, 33, 520, 48), ("aam+pa", 128, 1, 40, 300, 100)])
 def test_adc_range_statistics(xo, xb, ni, R, sb, M, K, N):
     g = workloads.Gemm("t", K, N, M, True, 1)
     W, X, dY = workloads.layer_tensors_np(g, seed=3 * K + N)
     flags = xo.INPUT_SIGNED | (xo.WIRE_AAM if "aam" in ni else 0) | (xo.VARIATION if "var" in ni else 0)
+    flags |= xo.ADC_PER_ARRAY if "pa" in ni else 0
     kw = dict(xbar_rows=R, xbar_cols=R, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=sb, flags=flags,
               var_sigma=0.1, seed=4)
     cg = xb.make_config(adc_bits=8, adc_fs_fwd=1.0, adc_fs_bwd=1.0, **kw)          # converter settings are not used
     bin_width = R * ((1 << sb) - 1) * 3 / 4095.0 / 4                               # the busiest quarter of the range
-    co = xo.make_config(adc_bits=13, adc_fs_fwd=4095 * bin_width, adc_fs_bwd=4095 * bin_width, **kw)
+    # the same counts from the oracle: a converter with 4095 codes (per side), one per bin
+    co = xo.make_config(adc_bits=12 if "pa" in ni else 13, adc_fs_fwd=4095 * bin_width, adc_fs_bwd=4095 * bin_width, **kw)
     w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
     planes = xb.tile(cg, dev(W), w_max, 1)
     for op, inp, scale, oracle_pass in ((xb.OP_FWD, X, x_scale, xo.fwd), (xb.OP_BWD, dY, g_scale, xo.bwd)):
@@ -425,7 +443,7 @@ def test_one_bit_dac_level_table(xo, xb):
 
 
 @pytest.mark.parametrize("sb,lut_kind,ni", [(2, "compressive", "aam"), (4, "compressive", "ideal"), (2, "offset", "aam"),
-                                            (1, "offset", "aam")])
+                                            (1, "offset", "aam"), (2, "offset", "aam+pa")])
 def test_dac_level_table(xo, xb, sb, lut_kind, ni):
     """Non-linear DAC (Sec. IV-B: voltages depend on the user's choice of DAC): the level voltages come
     from a table; the kernels weight the current of every level with its table entry."""
@@ -436,7 +454,8 @@ def test_dac_level_table(xo, xb, sb, lut_kind, ni):
     if lut_kind == "offset":
         lut = [0.02 + 0.95 * v for v in lut]                              # the zero level leaks a little
     kw = dict(xbar_rows=64, xbar_cols=128, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=sb, adc_bits=8,
-              flags=(xo.WIRE_AAM if ni == "aam" else 0) | xo.INPUT_SIGNED | xo.DAC_LUT, dac_lut=lut,
+              flags=(xo.WIRE_AAM if "aam" in ni else 0) | (xo.ADC_PER_ARRAY if "pa" in ni else 0) | xo.INPUT_SIGNED |
+              xo.DAC_LUT, dac_lut=lut,
               adc_fs_fwd=workloads.adc_full_scale(64, sb, 2), adc_fs_bwd=workloads.adc_full_scale(128, sb, 2))
     co, cg = both_configs(xo, xb, **kw)
     w_max, xs, gs = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
