@@ -48,6 +48,7 @@
 #define XO_WIRE_AAM2    128u
 #define XO_ADC_CURVE    256u
 #define XO_ADC_PER_ARRAY 512u
+#define XO_INPUT_OFFSET 1024u
 
 #define XO_STREAM_VARIATION 1u
 #define XO_STREAM_WRITE     2u
@@ -130,6 +131,34 @@ void xo_digits(uint64_t mag, int digit_bits, int n_digits, int32_t* d) {
 int64_t xo_quantize_input(float x, float x_scale, int input_bits, int is_signed) {
   double qa = (double)((1ll << input_bits) - 1);
   return (int64_t)rint(clampd((double)x / (double)x_scale, is_signed ? -1.0 : 0.0, 1.0) * qa);
+}
+
+/* Offset-binary code of a signed input (variant of the two-phase scheme for signed inputs on
+ * drivers that only supply 0 .. v_max, Sec. V): the range [-scale, scale] is mapped onto the
+ * driver's range, u = rne((x / scale + 1) / 2 * (2^bits - 1)), so that one phase streams the
+ * input and the constant half-range is taken out digitally afterwards.  The coded value is
+ * (2 u - (2^bits - 1)) / (2^bits - 1) * scale.  Zero is not a code: the range has an odd number
+ * of steps, its middle lies half a step from the two nearest codes and rounds to the even one. */
+int64_t xo_quantize_input_offset(float x, float x_scale, int input_bits) {
+  double qa = (double)((1ll << input_bits) - 1);
+  return (int64_t)rint(clampd(((double)x / (double)x_scale + 1.0) * 0.5, 0.0, 1.0) * qa);
+}
+
+/* Sums of the quantised weights over the rows (colsum[n], used by the forward pass) and over the
+ * columns (rowsum[k], backward pass): what the digital correction of the offset-binary scheme
+ * multiplies the half-range with.  The digital side knows the programmed (ideal) weights.      */
+int xo_weight_sums(const xo_config* cfg, const float* W, int K, int N, float w_max, int64_t* colsum, int64_t* rowsum) {
+  if (!cfg || !W || !colsum || !rowsum || K <= 0 || N <= 0) return -1;
+  for (int n = 0; n < N; ++n) colsum[n] = 0;
+  for (int k = 0; k < K; ++k) {
+    rowsum[k] = 0;
+    for (int n = 0; n < N; ++n) {
+      int64_t q = xo_quantize_weight(W[(size_t)k * N + n], w_max, cfg->weight_bits);
+      colsum[n] += q;
+      rowsum[k] += q;
+    }
+  }
+  return 0;
 }
 
 /* ADC of Sec. IV-B with the identity transfer curve: a signed mid-tread quantiser that saturates.
@@ -346,10 +375,13 @@ static double dac(const xo_config* cfg, int digit) {
 /* ------------------------------------------------------------------------------------------- */
 static int vmm(const xo_config* cfg, const double* U, int Ks, int Ns, int transposed, const float* in,
                float* out, int M, float in_scale, float w_max, int is_signed, float adc_fs,
-               int32_t* codes, int64_t* acc_out) {
+               int32_t* codes, int64_t* acc_out, const int64_t* wsum) {
   const int S = cfg->weight_bits / cfg->slice_bits;
   const int B = cfg->input_bits / cfg->stream_bits;
-  const int P = is_signed ? 2 : 1;
+  /* signed inputs: two phases (positive parts, negative parts), or one phase of offset-binary codes */
+  const int offset = is_signed && (cfg->flags & XO_INPUT_OFFSET) != 0;
+  const int P = (is_signed && !offset) ? 2 : 1;
+  if (offset && !wsum) return -3;
   const int L_in = transposed ? Ns : Ks;
   const int L_out = transposed ? Ks : Ns;
   const int tile = transposed ? cfg->xbar_cols : cfg->xbar_rows;
@@ -365,7 +397,8 @@ static int vmm(const xo_config* cfg, const double* U, int Ks, int Ns, int transp
   if (!a) return -2;
   for (int m = 0; m < M; ++m) {
     for (int l = 0; l < L_in; ++l)
-      a[l] = xo_quantize_input(in[(size_t)m * L_in + l], in_scale, cfg->input_bits, is_signed);
+      a[l] = offset ? xo_quantize_input_offset(in[(size_t)m * L_in + l], in_scale, cfg->input_bits)
+                    : xo_quantize_input(in[(size_t)m * L_in + l], in_scale, cfg->input_bits, is_signed);
     for (int o = 0; o < L_out; ++o) {
       int64_t acc = 0;
       for (int p = 0; p < P; ++p)
@@ -392,32 +425,50 @@ static int vmm(const xo_config* cfg, const double* U, int Ks, int Ns, int transp
                 acc += (p == 0 ? 1 : -1) * (pol == 0 ? 1 : -1) * weight * code;
               }
       if (acc_out) acc_out[(size_t)m * L_out + o] = acc;
-      out[(size_t)m * L_out + o] = (float)((double)acc * scale);
+      if (offset) {
+        /* sum_l xhat_l what_l with xhat = (2 u - Qa) / Qa * in_scale, what = q / Qw * w_max and
+         * sum_l u_l q_l read from the converters as acc * lsb: twice the converted sum minus the
+         * half-range times the weight sum, which the digital side knows                            */
+        const double half_range = (double)in_scale * (double)w_max / qw;
+        out[(size_t)m * L_out + o] = (float)((double)acc * (2.0 * scale) - (double)wsum[o] * half_range);
+      } else {
+        out[(size_t)m * L_out + o] = (float)((double)acc * scale);
+      }
     }
   }
   free(a);
   return 0;
 }
 
+/* wsum: with XO_INPUT_OFFSET the weight sums of xo_weight_sums (colsum for the forward, rowsum for
+ * the backward pass), else unused.                                                               */
 int xo_fwd_planes(const xo_config* cfg, const double* U, const float* X, float* Y, int M, int K, int Ns,
-                  float w_max, float x_scale, int32_t* codes, int64_t* acc) {
+                  float w_max, float x_scale, int32_t* codes, int64_t* acc, const int64_t* wsum) {
   return vmm(cfg, U, K, Ns, 0, X, Y, M, x_scale, w_max, (cfg->flags & XO_INPUT_SIGNED) != 0,
-             cfg->adc_fs_fwd, codes, acc);
+             cfg->adc_fs_fwd, codes, acc, wsum);
 }
 
 int xo_bwd_planes(const xo_config* cfg, const double* U, const float* dY, float* dX, int M, int Ks, int N,
-                  float w_max, float g_scale, int32_t* codes, int64_t* acc) {
-  return vmm(cfg, U, Ks, N, 1, dY, dX, M, g_scale, w_max, 1, cfg->adc_fs_bwd, codes, acc);
+                  float w_max, float g_scale, int32_t* codes, int64_t* acc, const int64_t* wsum) {
+  return vmm(cfg, U, Ks, N, 1, dY, dX, M, g_scale, w_max, 1, cfg->adc_fs_bwd, codes, acc, wsum);
+}
+
+/* Plane values of a whole layer: one per (slice, weight), two with one converter per array. */
+static size_t layer_plane_count(const xo_config* cfg, int K, int N) {
+  return (size_t)((cfg->flags & XO_ADC_PER_ARRAY) ? 2 : 1) * (size_t)(cfg->weight_bits / cfg->slice_bits) * K * N;
 }
 
 /* Forward VMM of a whole layer: Y[M][N] from W[K][N] and X[M][K]. */
 int xo_fwd(const xo_config* cfg, const float* W, const float* X, float* Y, int M, int K, int N, float w_max,
            float x_scale, uint64_t step, const float* profile, int32_t* codes, int64_t* acc) {
-  double* U = (double*)malloc(sizeof(double) * (size_t)(cfg->weight_bits / cfg->slice_bits) * K * N);
-  if (!U) return -2;
-  int rc = xo_planes(cfg, W, K, N, NULL, NULL, K, N, w_max, step, profile, U);
-  if (!rc) rc = xo_fwd_planes(cfg, U, X, Y, M, K, N, w_max, x_scale, codes, acc);
+  double* U = (double*)malloc(sizeof(double) * layer_plane_count(cfg, K, N));
+  int64_t* sums = (int64_t*)malloc(sizeof(int64_t) * ((size_t)K + N));
+  int rc = (U && sums) ? 0 : -2;
+  if (!rc) rc = xo_planes(cfg, W, K, N, NULL, NULL, K, N, w_max, step, profile, U);
+  if (!rc) rc = xo_weight_sums(cfg, W, K, N, w_max, sums, sums + N);
+  if (!rc) rc = xo_fwd_planes(cfg, U, X, Y, M, K, N, w_max, x_scale, codes, acc, sums);
   free(U);
+  free(sums);
   return rc;
 }
 
@@ -425,11 +476,14 @@ int xo_fwd(const xo_config* cfg, const float* W, const float* X, float* Y, int M
  * forward pass of the same step.                                                               */
 int xo_bwd(const xo_config* cfg, const float* W, const float* dY, float* dX, int M, int K, int N, float w_max,
            float g_scale, uint64_t step, const float* profile, int32_t* codes, int64_t* acc) {
-  double* U = (double*)malloc(sizeof(double) * (size_t)(cfg->weight_bits / cfg->slice_bits) * K * N);
-  if (!U) return -2;
-  int rc = xo_planes(cfg, W, K, N, NULL, NULL, K, N, w_max, step, profile, U);
-  if (!rc) rc = xo_bwd_planes(cfg, U, dY, dX, M, K, N, w_max, g_scale, codes, acc);
+  double* U = (double*)malloc(sizeof(double) * layer_plane_count(cfg, K, N));
+  int64_t* sums = (int64_t*)malloc(sizeof(int64_t) * ((size_t)K + N));
+  int rc = (U && sums) ? 0 : -2;
+  if (!rc) rc = xo_planes(cfg, W, K, N, NULL, NULL, K, N, w_max, step, profile, U);
+  if (!rc) rc = xo_weight_sums(cfg, W, K, N, w_max, sums, sums + N);
+  if (!rc) rc = xo_bwd_planes(cfg, U, dY, dX, M, K, N, w_max, g_scale, codes, acc, sums + N);
   free(U);
+  free(sums);
   return rc;
 }
 

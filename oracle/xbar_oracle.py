@@ -11,6 +11,7 @@ import numpy as np
 
 from . import build as _build
 
+INPUT_OFFSET = 1024
 VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED, WIRE_AAM2, ADC_CURVE, ADC_PER_ARRAY = (
     1, 2, 4, 8, 16, 32, 64, 128, 256, 512)
 STREAM_VARIATION, STREAM_WRITE = 1, 2
@@ -71,6 +72,8 @@ def lib():
         _lib.xo_quantize_weight.argtypes = [C.c_float, C.c_float, C.c_int]
         _lib.xo_quantize_input.restype = C.c_int64
         _lib.xo_quantize_input.argtypes = [C.c_float, C.c_float, C.c_int, C.c_int]
+        _lib.xo_quantize_input_offset.restype = C.c_int64
+        _lib.xo_quantize_input_offset.argtypes = [C.c_float, C.c_float, C.c_int]
         _lib.xo_adc.restype = C.c_int64
         _lib.xo_adc.argtypes = [C.c_double, C.c_float, C.c_int]
         _lib.xo_adc_unsigned.restype = C.c_int64
@@ -132,6 +135,20 @@ def quantize_input(x, x_scale, bits, is_signed):
     return int(lib().xo_quantize_input(x, x_scale, bits, int(is_signed)))
 
 
+def quantize_input_offset(x, x_scale, bits):
+    return int(lib().xo_quantize_input_offset(x, x_scale, bits))
+
+
+def weight_sums(cfg, W, w_max):
+    """(colsum[N], rowsum[K]) of the quantised weights: the digital correction of offset-binary inputs."""
+    W = _f32(W)
+    K, N = W.shape
+    col, row = np.empty(N, dtype=np.int64), np.empty(K, dtype=np.int64)
+    rc = lib().xo_weight_sums(C.byref(cfg), _p(W, C.c_float), K, N, C.c_float(w_max), _p(col, C.c_int64), _p(row, C.c_int64))
+    assert rc == 0, rc
+    return col, row
+
+
 def adc(current, full_scale, bits):
     return int(lib().xo_adc(current, full_scale, bits))
 
@@ -178,28 +195,33 @@ def _tiles(cfg, length, transposed):
     return (length + t - 1) // t
 
 
-def fwd_planes(cfg, U, X, w_max, x_scale, want_codes=False, want_acc=False):
+def fwd_planes(cfg, U, X, w_max, x_scale, want_codes=False, want_acc=False, wsum=None):
     """Forward VMM from generated planes U[S][K][Ns] ([2][S][K][Ns] with one converter per array);
     rows of X are independent.  Codes: [phase][cycle][slice][tile][m][n], with per-array converters
-    [phase][cycle][slice][array][tile][m][n]."""
+    [phase][cycle][slice][array][tile][m][n].  wsum: column sums of the quantised weights, needed
+    with offset-binary signed inputs."""
     U = np.ascontiguousarray(U, dtype=np.float64)
     X = _f32(X)
     S, K, Ns = U.shape[-3:]
     M = X.shape[0]
     assert X.shape[1] == K and U.ndim == (4 if cfg.flags & ADC_PER_ARRAY else 3)
     Y = np.empty((M, Ns), dtype=np.float32)
-    P = 2 if cfg.flags & INPUT_SIGNED else 1
+    P = 2 if (cfg.flags & INPUT_SIGNED and not cfg.flags & INPUT_OFFSET) else 1
     arrays = (2,) if cfg.flags & ADC_PER_ARRAY else ()
     codes = np.empty((P, n_cycles(cfg), S) + arrays + (_tiles(cfg, K, False), M, Ns), dtype=np.int32) if want_codes else None
     acc = np.empty((M, Ns), dtype=np.int64) if want_acc else None
+    wsum = None if wsum is None else np.ascontiguousarray(wsum, dtype=np.int64)
+    assert wsum is None or wsum.shape == (Ns,)
     rc = lib().xo_fwd_planes(C.byref(cfg), _p(U, C.c_double), _p(X, C.c_float), _p(Y, C.c_float), M, K, Ns,
-                             C.c_float(w_max), C.c_float(x_scale), _p(codes, C.c_int32), _p(acc, C.c_int64))
-    assert rc == 0
+                             C.c_float(w_max), C.c_float(x_scale), _p(codes, C.c_int32), _p(acc, C.c_int64),
+                             _p(wsum, C.c_int64))
+    assert rc == 0, rc
     return _ret(Y, codes, acc)
 
 
-def bwd_planes(cfg, U, dY, w_max, g_scale, want_codes=False, want_acc=False):
-    """Backward VMM from generated planes U[S][Ks][N]; rows of dY are independent."""
+def bwd_planes(cfg, U, dY, w_max, g_scale, want_codes=False, want_acc=False, wsum=None):
+    """Backward VMM from generated planes U[S][Ks][N]; rows of dY are independent.  wsum: row sums of
+    the quantised weights, needed with offset-binary signed inputs."""
     U = np.ascontiguousarray(U, dtype=np.float64)
     dY = _f32(dY)
     S, Ks, N = U.shape[-3:]
@@ -207,11 +229,15 @@ def bwd_planes(cfg, U, dY, w_max, g_scale, want_codes=False, want_acc=False):
     assert dY.shape[1] == N and U.ndim == (4 if cfg.flags & ADC_PER_ARRAY else 3)
     dX = np.empty((M, Ks), dtype=np.float32)
     arrays = (2,) if cfg.flags & ADC_PER_ARRAY else ()
-    codes = np.empty((2, n_cycles(cfg), S) + arrays + (_tiles(cfg, N, True), M, Ks), dtype=np.int32) if want_codes else None
+    P = 1 if cfg.flags & INPUT_OFFSET else 2
+    codes = np.empty((P, n_cycles(cfg), S) + arrays + (_tiles(cfg, N, True), M, Ks), dtype=np.int32) if want_codes else None
     acc = np.empty((M, Ks), dtype=np.int64) if want_acc else None
+    wsum = None if wsum is None else np.ascontiguousarray(wsum, dtype=np.int64)
+    assert wsum is None or wsum.shape == (Ks,)
     rc = lib().xo_bwd_planes(C.byref(cfg), _p(U, C.c_double), _p(dY, C.c_float), _p(dX, C.c_float), M, Ks, N,
-                             C.c_float(w_max), C.c_float(g_scale), _p(codes, C.c_int32), _p(acc, C.c_int64))
-    assert rc == 0
+                             C.c_float(w_max), C.c_float(g_scale), _p(codes, C.c_int32), _p(acc, C.c_int64),
+                             _p(wsum, C.c_int64))
+    assert rc == 0, rc
     return _ret(dX, codes, acc)
 
 
@@ -226,12 +252,12 @@ def _ret(Y, codes, acc):
 
 def fwd(cfg, W, X, w_max, x_scale, step=0, profile=None, want_codes=False, want_acc=False):
     U = planes(cfg, W, w_max, step, profile)
-    return fwd_planes(cfg, U, X, w_max, x_scale, want_codes, want_acc)
+    return fwd_planes(cfg, U, X, w_max, x_scale, want_codes, want_acc, weight_sums(cfg, W, w_max)[0])
 
 
 def bwd(cfg, W, dY, w_max, g_scale, step=0, profile=None, want_codes=False, want_acc=False):
     U = planes(cfg, W, w_max, step, profile)
-    return bwd_planes(cfg, U, dY, w_max, g_scale, want_codes, want_acc)
+    return bwd_planes(cfg, U, dY, w_max, g_scale, want_codes, want_acc, weight_sums(cfg, W, w_max)[1])
 
 
 def update(cfg, W, X, dY, w_max, grad_scale, lr, step=0, k_idx=None, n_idx=None, N_full=None, want_grad=False):

@@ -171,6 +171,81 @@ def test_one_converter_per_array(xo):
     assert np.abs(fine1 - fine2).max() < 2e-3 * np.abs(fine1).max()
 
 
+def test_offset_binary_signed_inputs(xo):
+    """Variant: signed inputs streamed in one phase as offset-binary codes, half-range removed digitally."""
+    rng = np.random.default_rng(21)
+    # the code: ends of the range, the middle (half a step off, to the even code), clamping, monotone,
+    # coded value within half a step (one step = 2 scale / Qa) of the input
+    for bits in (8, 4, 3):
+        qa = (1 << bits) - 1
+        assert xo.quantize_input_offset(-2.0, 2.0, bits) == 0 and xo.quantize_input_offset(2.0, 2.0, bits) == qa
+        assert xo.quantize_input_offset(-9.0, 2.0, bits) == 0 and xo.quantize_input_offset(9.0, 2.0, bits) == qa
+        assert xo.quantize_input_offset(0.0, 2.0, bits) == 2 * int(np.rint((qa / 2.0) / 2.0))       # 128, 8, 4
+        xs = np.sort(rng.uniform(-2, 2, size=300)).astype(np.float32)
+        us = [xo.quantize_input_offset(float(x), 2.0, bits) for x in xs]
+        assert all(b >= a for a, b in zip(us, us[1:]))
+        coded = (2.0 * np.array(us) - qa) / qa * 2.0
+        assert np.abs(coded - xs).max() <= 2.0 / qa + 1e-6
+    K, N, M = 21, 10, 7
+    q_w = rng.integers(-15, 16, size=(K, N))
+    W = (q_w / 15.0).astype(np.float32)
+    X = rng.uniform(-1, 1, size=(M, K)).astype(np.float32)
+    dY = rng.uniform(-1, 1, size=(M, N)).astype(np.float32)
+    kw = dict(xbar_rows=8, xbar_cols=8, weight_bits=4, slice_bits=2, input_bits=8, stream_bits=4, r_min=1e4, r_max=1e5)
+    # weight sums against numpy on the known integers
+    col, row = xo.weight_sums(xo.make_config(**kw), W, 1.0)
+    assert np.array_equal(col, q_w.sum(axis=0)) and np.array_equal(row, q_w.sum(axis=1))
+    # ideal arrays, lossless converters: the product of the coded inputs and the quantised weights, exactly
+    lossless = dict(adc_bits=16, adc_fs_fwd=32767.0, adc_fs_bwd=32767.0)
+    cfg = xo.make_config(flags=xo.INPUT_SIGNED | xo.INPUT_OFFSET, **kw, **lossless)
+    u = np.array([[xo.quantize_input_offset(float(x), 1.0, 8) for x in r] for r in X])
+    Y, codes, acc = xo.fwd(cfg, W, X, 1.0, 1.0, want_codes=True, want_acc=True)
+    assert codes.shape == (1, 2, 2, 3, M, N)                                   # one phase
+    assert np.array_equal(acc, u @ q_w)
+    want = ((2 * u - 255) @ q_w) / (255.0 * 15.0)
+    assert np.abs(Y - want).max() <= 1e-6 * np.abs(want).max()
+    ud = np.array([[xo.quantize_input_offset(float(x), 1.0, 8) for x in r] for r in dY])
+    dX, codes_b = xo.bwd(cfg, W, dY, 1.0, 1.0, want_codes=True)
+    assert codes_b.shape == (1, 2, 2, 2, M, K)
+    want_b = ((2 * ud - 255) @ q_w.T) / (255.0 * 15.0)
+    assert np.abs(dX - want_b).max() <= 1e-6 * np.abs(want_b).max()
+    # against the two-phase scheme: the inputs differ by the two quantisation errors (half of 2/Qa and of 1/Qa)
+    two = xo.fwd(xo.make_config(flags=xo.INPUT_SIGNED, **kw, **lossless), W, X, 1.0, 1.0)
+    bound = 1.5 / 255.0 * np.abs(q_w / 15.0).sum(axis=0)
+    assert (np.abs(Y - two) <= bound + 1e-6).all() and np.abs(Y - two).max() > 0
+    # without the sign flag the forward inputs are unsigned and the scheme does not apply
+    Xp = np.abs(X)
+    assert np.array_equal(xo.fwd(xo.make_config(flags=xo.INPUT_OFFSET, **kw, **lossless), W, Xp, 1.0, 1.0),
+                          xo.fwd(xo.make_config(**kw, **lossless), W, Xp, 1.0, 1.0))
+    # brute force of one output with non-ideal arrays and coarse converters (differential, then one per array)
+    for extra, q_adc in ((0, 31), (xo.ADC_PER_ARRAY, 63)):
+        cfg = xo.make_config(flags=xo.INPUT_SIGNED | xo.INPUT_OFFSET | xo.WIRE_AAM | extra, adc_bits=6, adc_fs_fwd=50.0, **kw)
+        U = xo.planes(cfg, W, 1.0)
+        Y, codes, acc = xo.fwd(cfg, W, X, 1.0, 1.0, want_codes=True, want_acc=True)
+        gain = float(np.float32(q_adc) / np.float32(50.0))
+        m, n = 4, 6
+        total = 0
+        for b in range(2):
+            digit = (u[m] >> (4 * b)) & 15
+            for s in range(2):
+                for pol in range(2 if extra else 1):
+                    for t in range(3):
+                        rows = slice(8 * t, min(8 * t + 8, K))
+                        plane = U[pol, s] if extra else U[s]
+                        cur = float((digit[rows] * plane[rows, n]).sum())
+                        code = int(np.rint(cur * gain))
+                        code = min(max(code, 0 if extra else -q_adc), q_adc)
+                        got = codes[0, b, s, pol, t, m, n] if extra else codes[0, b, s, t, m, n]
+                        assert got == code
+                        total += (-1 if pol else 1) * code * (1 << (2 * s + 4 * b))
+        assert acc[m, n] == total
+        want = (2.0 * total * (50.0 / q_adc) - 255.0 * q_w[:, n].sum()) / (255.0 * 15.0)
+        assert abs(Y[m, n] - want) < 1e-6
+    # the correction needs the weight sums
+    with pytest.raises(AssertionError):
+        xo.fwd_planes(cfg, U, X, 1.0, 1.0)
+
+
 def test_adc_transfer_curve(xo):
     identity = [-1.0 + i / 8.0 for i in range(17)]
     rng = np.random.default_rng(6)
