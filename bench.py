@@ -145,6 +145,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
+    ap.add_argument("--offset-inputs", action="store_true",
+                    help="signed inputs in one phase of offset-binary codes instead of two phases of magnitudes: "
+                         "half the crossbar passes of every signed pass")
     ap.add_argument("--adc-per-array", action="store_true",
                     help="one unsigned converter per array and digital subtraction instead of one signed converter "
                          "per array pair: twice the contraction work for the same emulated MACs")
@@ -201,6 +204,12 @@ def main():
         kw["flags"] &= ~(workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE)
     if args.all_paths and kw["flags"] & workloads.NI_WIRE_AAM:
         kw["flags"] = (kw["flags"] & ~workloads.NI_WIRE_AAM) | workloads.NI_WIRE_AAM2
+    signed_phases = 2
+    if args.offset_inputs:
+        kw["flags"] |= workloads.INPUT_OFFSET
+        signed_phases = 1
+        kw["adc_fs_fwd"] *= 4.0            # every row is driven (a zero at mid-range): larger currents
+        kw["adc_fs_bwd"] *= 4.0
     arrays = 1
     if args.adc_per_array:
         kw["flags"] |= workloads.ADC_PER_ARRAY
@@ -224,7 +233,7 @@ def main():
             assert geom.batch * geom.out_h * geom.out_w == g.M and k_ * k_ * cin_ == g.K
         w_max = 2.0 * float(W.abs().max())          # head-room: the weights move during the run
         layers.append(dict(g=g, cfg=cfg, W=W, X=X, dY=dY, w_max=w_max, x_scale=float(X.abs().max()), geom=geom,
-                           g_scale=float(dY.abs().max()), macs=workloads.macs(g, S_w, S_in)))
+                           g_scale=float(dY.abs().max()), macs=workloads.macs(g, S_w, S_in, signed_phases)))
         max_planes = max(max_planes, xb.planes_bytes(cfg, g.K, g.N))
         if geom is None:
             max_ws = max(max_ws, *(xb.workspace_bytes(cfg, op, g.M, g.K, g.N) for op in (0, 1, 2)))
@@ -347,7 +356,7 @@ def main():
             probe[key] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
         roofline["sustained_mfma_tflops_bare_instruction"] = probe
     if (args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal and not args.all_paths
-            and not args.adc_per_array and not args.from_images):
+            and not args.adc_per_array and not args.offset_inputs and not args.from_images):
         roofline["traffic"] = VMM_TRAFFIC_BYTES_RESNET50_B64
     fcm_refresh_ms = None
     if args.fcm_refresh:
@@ -388,11 +397,12 @@ def main():
             dY = L["dY"][:m].cpu().numpy()
             t1 = time.perf_counter()
             U = xo.planes(co, W, L["w_max"], 0)
-            xo.rows_parallel(lambda u, x: xo.fwd_planes(co, u, x, L["w_max"], L["x_scale"]), U, X, threads)
-            xo.rows_parallel(lambda u, x: xo.bwd_planes(co, u, x, L["w_max"], L["g_scale"]), U, dY, threads)
+            col, row = xo.weight_sums(co, W, L["w_max"]) if signed_phases == 1 else (None, None)
+            xo.rows_parallel(lambda u, x: xo.fwd_planes(co, u, x, L["w_max"], L["x_scale"], wsum=col), U, X, threads)
+            xo.rows_parallel(lambda u, x: xo.bwd_planes(co, u, x, L["w_max"], L["g_scale"], wsum=row), U, dY, threads)
             xo.update(co, W, X, dY, L["w_max"], 1.0 / L["w_max"], 0.01, 0)
             t_cpu += time.perf_counter() - t1
-            mm = workloads.macs(g._replace(M=m), S_w, S_in)
+            mm = workloads.macs(g._replace(M=m), S_w, S_in, signed_phases)
             done += mm["fwd"] + mm["bwd"] + mm["upd"]
         cpu = {"value": round(done / t_cpu / 1e9, 4), "unit": "emulated GMAC/s", "cores": threads, "kind": "oracle",
                "sample": "%d batch rows of each of the %d distinct layer shapes, fwd+bwd+update, %.1f s" %
@@ -403,6 +413,8 @@ def main():
             "AAM, all first-order paths" if kw["flags"] & workloads.NI_WIRE_AAM2 else "AAM")
     else:
         array_text = "ideal arrays"
+    if signed_phases == 1:
+        array_text += ", offset-binary signed inputs"
     if arrays == 2:
         array_text += ", one converter per array"
     line = {

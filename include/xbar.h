@@ -56,6 +56,18 @@ extern "C" {
                                      float(Q) / adc_fs; the codes of the negative array are subtracted
                                      digitally.  Twice the conversions and contraction work; adc_bits <= 15;
                                      not with XBAR_ADC_CURVE                                             */
+#define XBAR_INPUT_OFFSET    1024u /* signed inputs (forward with XBAR_INPUT_SIGNED, backward always) are
+                                     streamed in ONE phase as offset-binary codes instead of two phases
+                                     of magnitudes (variant for drivers that supply 0 .. v_max only, Sec. V):
+                                     u = rne((x / scale + 1) / 2 * (2^input_bits - 1)), coded value
+                                     (2 u - Qa) / Qa * scale (steps twice as coarse; zero lies half a step
+                                     beside a code); the half-range is removed digitally:
+                                     out = float(double(sum) * 2 lsb scale w_max / (Qa Qw)
+                                                 - double(wsum) * scale w_max / Qw),
+                                     wsum = sum of the quantised weights of that output (xbar_tile keeps
+                                     them in the plane buffer).  Every input is driven, also a zero and a
+                                     convolution's padding (mid-range): size adc_fs for that.  Half the
+                                     conversions and contraction work of the two-phase scheme          */
 
 /* status codes */
 #define XBAR_OK          0
@@ -85,7 +97,7 @@ typedef struct xbar_config {
   int32_t stream_bits;    /* bits per DAC cycle, divides input_bits              paper: 1             */
   int32_t adc_bits;       /* 2..16, signed mid-tread converter with Q = 2^(adc_bits-1) - 1 codes/side */
   uint32_t flags;         /* XBAR_NI_* | XBAR_DAC_LUT | XBAR_ADC_CURVE | XBAR_INPUT_SIGNED |          */
-                          /*   XBAR_ADC_PER_ARRAY                                                     */
+                          /*   XBAR_ADC_PER_ARRAY | XBAR_INPUT_OFFSET                                 */
   float r_min, r_max;     /* device resistance range in Ohm                      paper: 1e5, 1e6      */
   float v_max;            /* input voltage range in V (results do not depend on it) paper: 1          */
   float r_row, r_col;     /* wire resistance per cell in Ohm                     paper: 1, 4.6        */

@@ -80,6 +80,12 @@ inline size_t wire_scratch_bytes(const xbar_config* c, const Derived& d, int K, 
   return (c->flags & XBAR_NI_WIRE_AAM2) ? align256((size_t)16 * d.S_w * K * N) + align256((size_t)4 * K * N) : 0;
 }
 
+// Weight sums for the digital correction of offset-binary inputs, kept behind the wire scratch:
+// colsum[N] then rowsum[K], 64-bit.
+inline size_t weight_sums_bytes(const xbar_config* c, int K, int N) {
+  return (c->flags & XBAR_INPUT_OFFSET) ? align256((size_t)8 * ((size_t)K + N)) : 0;
+}
+
 inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N, bool transposed) {
   PlaneGeom g;
   g.tile = transposed ? c->xbar_cols : c->xbar_rows;
@@ -89,6 +95,11 @@ inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N
   g.pol_bytes = (size_t)g.T * g.OP * d.S_w * d.terms * g.ks * 1024;
   g.bytes = g.pol_bytes * d.npol;
   return g;
+}
+
+inline size_t weight_sums_offset(const xbar_config* c, const Derived& d, int K, int N) {
+  return align256(plane_geom(c, d, K, N, false).bytes) + align256(plane_geom(c, d, K, N, true).bytes) +
+         wire_scratch_bytes(c, d, K, N);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -433,6 +444,44 @@ __global__ __launch_bounds__(256) void wire_cols_kernel(WireArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// sums of the quantised weights over rows and columns: what the digital correction of offset-binary
+// inputs multiplies the half-range with (the digital side knows the programmed weights)
+// ---------------------------------------------------------------------------------------------
+struct SumArgs {
+  const float* W;
+  long long* colsum;   // [N] sum over k
+  long long* rowsum;   // [K] sum over n
+  int K, N, weight_bits;
+  float w_max;
+};
+
+__global__ __launch_bounds__(256) void clear_sums_kernel(SumArgs a) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < a.N) a.colsum[i] = 0;
+  if (i < a.K) a.rowsum[i] = 0;
+}
+
+// Block = 64 rows x 64 columns; wave w takes rows w, w + 4, ..: lane = column.  Integer atomics: the
+// result does not depend on the order.
+__global__ __launch_bounds__(256) void weight_sums_kernel(SumArgs a) {
+  const int nb = (a.N + 63) / 64;
+  const int k0 = (blockIdx.x / nb) * 64, n = (blockIdx.x % nb) * 64 + (threadIdx.x & 63);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const double qw = (double)((1u << a.weight_bits) - 1);
+  long long col = 0;
+  for (int k = k0 + wave; k < min(k0 + 64, a.K); k += 4) {
+    long long q = 0;
+    if (n < a.N) q = (long long)::rint(clampd((double)a.W[(size_t)k * a.N + n] / (double)a.w_max, -1.0, 1.0) * qw);
+    col += q;
+    long long r = q;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) r += __shfl_xor(r, d, 64);
+    if (lane == 0) atomicAdd(reinterpret_cast<unsigned long long*>(&a.rowsum[k]), (unsigned long long)r);
+  }
+  if (n < a.N) atomicAdd(reinterpret_cast<unsigned long long*>(&a.colsum[n]), (unsigned long long)col);
+}
+
+// ---------------------------------------------------------------------------------------------
 // input quantiser (Sec. IV: inputs are scaled and sent to the DAC)
 // ---------------------------------------------------------------------------------------------
 // Convolution as a crossbar layer (Sec. IV: the kernels of a layer are unrolled into the columns of
@@ -468,6 +517,7 @@ struct QuantArgs {
   const float* X;
   uint8_t* A;        // [phase][MP][T][ks][64 lanes][8 bytes]
   int M, L, MP, T, ks, tile, P, input_bits;
+  int offset;        // signed inputs as offset-binary codes in one phase (P == 1)
   float scale;
   long long n_threads;
   ConvGeom conv;     // used by the CONV instantiation only
@@ -537,11 +587,22 @@ __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
       }
     }
     union { u32x2 v; uint8_t b[8]; } pos, neg;
+    if (a.offset) {
+      // u = rne((x / scale + 1) / 2 * Qa): every input that exists is driven, a value of zero (also a
+      // position outside the image) at mid-range; rows beyond the layer are not driven at all
+      const int n_driven = m < a.M ? min(max(lend - l0, 0), 8) : 0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int q = (int)::rint(clampd((double)x[e] / scale, lo, 1.0) * qa);
-      pos.b[e] = (uint8_t)(q > 0 ? q : 0);
-      neg.b[e] = (uint8_t)(q < 0 ? -q : 0);
+      for (int e = 0; e < 8; ++e) {
+        const int u = (int)::rint(clampd(((double)x[e] / scale + 1.0) * 0.5, 0.0, 1.0) * qa);
+        pos.b[e] = (uint8_t)(e < n_driven ? u : 0);
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int q = (int)::rint(clampd((double)x[e] / scale, lo, 1.0) * qa);
+        pos.b[e] = (uint8_t)(q > 0 ? q : 0);
+        neg.b[e] = (uint8_t)(q < 0 ? -q : 0);
+      }
     }
     const size_t blk = ((size_t)mp * a.T + t) * a.ks + j;
     out[blk * 64 + lane] = pos.v;
@@ -568,6 +629,7 @@ struct VmmArgs {
   size_t pol_stride;          // 16-byte units between the planes of the two arrays
   int S_w, S_in, slice_bits, stream_bits, ks, tile;
   int vt_per_chunk, nchunk, lds_kb;
+  int direct;                 // single chunk and nothing to correct: the kernel scales and stores the result itself
   int total_wg, per_xcd;
   float gain;          // float(Q) / adc_fs
   float clamp_lo, clamp_hi;   // kMagic -+ Q
@@ -982,7 +1044,7 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
       const int o = op * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       if (m < a.M && o < a.Lout && mp0 + pm < a.MP) {
         const size_t idx = ((size_t)chunk * a.M + m) * a.Lout + o;
-        if (a.nchunk == 1) {   // nothing to add up across chunks: scale and store the result itself
+        if (a.direct) {        // nothing to add up across chunks: scale and store the result itself
           const long long sum = WIDE ? y64[pm][r] : (long long)(int32_t)(y[pm][r] - bias);
           a.out[idx] = (float)((double)sum * a.scale);
         } else if (WIDE) {
@@ -998,18 +1060,23 @@ struct FinishArgs {
   const void* part;
   float* out;
   long long n;   // M * Lout
-  int nchunk, wide;
+  int nchunk, wide, Lout;
   double scale;
+  const long long* wsum;   // offset-binary inputs: weight sum per output, else null
+  double half_range;       //   and the half-range it is multiplied with
 };
 
 __global__ __launch_bounds__(256) void vmm_finish_kernel(FinishArgs a) {
+#pragma clang fp contract(off)   // product, product, difference: each rounded on its own
   const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= a.n) return;
   long long sum = 0;
   for (int c = 0; c < a.nchunk; ++c)
     sum += a.wide ? reinterpret_cast<const long long*>(a.part)[(size_t)c * a.n + i]
                   : (long long)reinterpret_cast<const int32_t*>(a.part)[(size_t)c * a.n + i];
-  a.out[i] = (float)((double)sum * a.scale);
+  double y = (double)sum * a.scale;
+  if (a.wsum) y = y - (double)a.wsum[i % a.Lout] * a.half_range;
+  a.out[i] = (float)y;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1718,6 +1785,7 @@ thread_local hipEvent_t g_trace_before = nullptr, g_trace_after = nullptr;
 struct VmmPlan {
   PlaneGeom g;
   int Lin, Lout, MP, P, VT, vt_per_chunk, nchunk, wide, pm, nw, MB, lds_kb;
+  int offset;          // signed inputs in one phase of offset-binary codes
   uint32_t bias_per_vt;
   size_t a_bytes, part_bytes, ws_bytes, lds_bytes;
 };
@@ -1728,7 +1796,9 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   p.Lin = transposed ? N : K;
   p.Lout = transposed ? K : N;
   p.MP = cdiv(M, 32);
-  p.P = (transposed || (c->flags & XBAR_INPUT_SIGNED)) ? 2 : 1;
+  const bool is_signed = transposed || (c->flags & XBAR_INPUT_SIGNED);
+  p.offset = (is_signed && (c->flags & XBAR_INPUT_OFFSET)) ? 1 : 0;
+  p.P = (is_signed && !p.offset) ? 2 : 1;
   p.VT = p.P * d.npol * p.g.T;
   // sum of the shift-and-add weights of one virtual tile
   unsigned long long wsum = 0;
@@ -1855,6 +1925,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   qa.A = reinterpret_cast<uint8_t*>(ws);
   qa.M = M; qa.L = p.Lin; qa.MP = p.MP; qa.T = p.g.T; qa.ks = p.g.ks; qa.tile = p.g.tile; qa.P = p.P;
   qa.input_bits = cfg->input_bits;
+  qa.offset = p.offset;
   qa.scale = in_scale;
   qa.n_threads = (long long)p.MP * p.g.T * ((p.g.ks + 1) / 2) * 64;
   if (conv) {
@@ -1883,6 +1954,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.npol = d.npol; a.pol_stride = p.g.pol_bytes / 16;
   a.VT = p.VT; a.S_w = d.S_w; a.S_in = d.S_in; a.slice_bits = cfg->slice_bits; a.stream_bits = cfg->stream_bits;
   a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.lds_kb = p.lds_kb;
+  a.direct = (p.nchunk == 1 && !p.offset) ? 1 : 0;
   a.total_wg = p.nchunk * p.g.OP * p.MB;
   a.per_xcd = cdiv(a.total_wg, 8);
   a.gain = (float)d.q_adc / adc_fs * dac_gain;
@@ -1894,6 +1966,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
     const double lsb = (double)adc_fs / (double)d.q_adc;
     const double qa_max = (double)((1u << cfg->input_bits) - 1), qw_max = (double)((1u << cfg->weight_bits) - 1);
     a.scale = lsb * (double)in_scale * (double)w_max / (qa_max * qw_max);
+    if (p.offset) a.scale = 2.0 * a.scale;           // coded value = (2 u - Qa) / Qa
   }
   hipEvent_t ev0 = g_trace_before, ev1 = g_trace_after;
   g_trace_before = g_trace_after = nullptr;
@@ -1903,14 +1976,23 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return XBAR_EHIP;
   if (hist) return XBAR_OK;
 
-  if (p.nchunk > 1) {
+  if (!a.direct) {
     FinishArgs f;
     f.part = a.part;
     f.out = out;
     f.n = (long long)M * p.Lout;
     f.nchunk = p.nchunk;
     f.wide = p.wide;
+    f.Lout = p.Lout;
     f.scale = a.scale;
+    f.wsum = nullptr;
+    f.half_range = 0.0;
+    if (p.offset) {    // minus the half-range times the sum of the programmed weights of this output
+      const long long* sums = reinterpret_cast<const long long*>(reinterpret_cast<const char*>(planes) +
+                                                                  weight_sums_offset(cfg, d, K, N));
+      f.wsum = transposed ? sums + N : sums;
+      f.half_range = (double)in_scale * (double)w_max / (double)((1u << cfg->weight_bits) - 1);
+    }
     hipLaunchKernelGGL(vmm_finish_kernel, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   }
@@ -2026,7 +2108,7 @@ int xbar_config_validate(const xbar_config* c) {
   if (c->input_bits < 1 || c->input_bits > 8) return XBAR_EINVAL;
   if (c->stream_bits < 1 || c->stream_bits > c->input_bits || c->input_bits % c->stream_bits) return XBAR_EINVAL;
   if (c->adc_bits < 2 || c->adc_bits > 16) return XBAR_EINVAL;
-  if (c->flags & ~0x3FFu) return XBAR_EINVAL;
+  if (c->flags & ~0x7FFu) return XBAR_EINVAL;
   if (c->flags & XBAR_ADC_PER_ARRAY) {
     if (c->flags & XBAR_ADC_CURVE) return XBAR_EINVAL;     // the curve is that of a signed converter
     if (c->adc_bits > 15) return XBAR_EINVAL;              // unsigned codes are reported as int16
@@ -2057,8 +2139,7 @@ int xbar_config_validate(const xbar_config* c) {
 size_t xbar_planes_bytes(const xbar_config* cfg, int K, int N) {
   if (xbar_config_validate(cfg) || check_shape(1, K, N)) return 0;
   const Derived d = derive(cfg);
-  return align256(plane_geom(cfg, d, K, N, false).bytes) + align256(plane_geom(cfg, d, K, N, true).bytes) +
-         wire_scratch_bytes(cfg, d, K, N);
+  return weight_sums_offset(cfg, d, K, N) + weight_sums_bytes(cfg, K, N);
 }
 
 size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N) {
@@ -2106,6 +2187,17 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
     hipLaunchKernelGGL(wire_cols_kernel, dim3(tiles * (unsigned)((cfg->xbar_cols + 63) / 64), (unsigned)d.S_w), dim3(256),
                        0, st, w);
+    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+  }
+  if (cfg->flags & XBAR_INPUT_OFFSET) {
+    SumArgs sa;
+    sa.W = W;
+    sa.colsum = reinterpret_cast<long long*>(reinterpret_cast<char*>(planes) + weight_sums_offset(cfg, d, K, N));
+    sa.rowsum = sa.colsum + N;
+    sa.K = K; sa.N = N; sa.weight_bits = cfg->weight_bits; sa.w_max = w_max;
+    hipLaunchKernelGGL(clear_sums_kernel, dim3((unsigned)cdiv(std::max(K, N), 256)), dim3(256), 0, st, sa);
+    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+    hipLaunchKernelGGL(weight_sums_kernel, dim3((unsigned)(cdiv(K, 64) * cdiv(N, 64))), dim3(256), 0, st, sa);
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   }
   size_t offset = 0;

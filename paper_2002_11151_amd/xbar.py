@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libxbar.so")
 
 (NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2, ADC_CURVE,
- ADC_PER_ARRAY) = (1, 2, 4, 8, 16, 32, 64, 128, 256, 512)
+ ADC_PER_ARRAY, INPUT_OFFSET) = (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024)
 OP_FWD, OP_BWD, OP_UPDATE, OP_FCM = 0, 1, 2, 3
 ABI_VERSION = 2
 
@@ -214,7 +214,7 @@ def _vmm(fn, op, cfg, planes, inp, out_cols, K, N, w_max, in_scale, ws, out, wan
         out = torch.empty((M, out_cols), dtype=torch.float32, device=inp.device)
     codes = None
     if want_codes:
-        P = 2 if (op == OP_BWD or cfg.flags & INPUT_SIGNED) else 1
+        P = 2 if ((op == OP_BWD or cfg.flags & INPUT_SIGNED) and not cfg.flags & INPUT_OFFSET) else 1
         tile_len = cfg.xbar_cols if op == OP_BWD else cfg.xbar_rows
         lin = N if op == OP_BWD else K
         T = (lin + tile_len - 1) // tile_len
@@ -281,7 +281,7 @@ def conv_fwd(cfg, planes, X, geom, N, w_max, x_scale, ws=None, out=None, want_co
         out = torch.empty((geom.batch, geom.out_h, geom.out_w, N), dtype=torch.float32, device=X.device)
     codes = None
     if want_codes:
-        P = 2 if cfg.flags & INPUT_SIGNED else 1
+        P = 2 if (cfg.flags & INPUT_SIGNED and not cfg.flags & INPUT_OFFSET) else 1
         K, M = geom.k_h * geom.k_w * geom.in_c, geom.batch * geom.out_h * geom.out_w
         T = (K + cfg.xbar_rows - 1) // cfg.xbar_rows
         codes = torch.zeros(_codes_shape(cfg, P, T, M, N), dtype=torch.int16, device=X.device)

@@ -46,6 +46,32 @@ def check_codes(got, want):
     return frac
 
 
+def outputs_from_codes(xo, cfg, codes, W, w_max, in_scale, adc_fs, transposed):
+    """The digital part of a pass, recomputed from the ADC codes it reported: shift-and-add over
+    phases, cycles, slices, arrays and tiles, scaling, and the half-range correction of offset-binary
+    inputs.  codes: [phase][cycle][slice]([array])[tile][M][out]."""
+    per_array = bool(cfg.flags & xo.ADC_PER_ARRAY)
+    offset = bool(cfg.flags & xo.INPUT_OFFSET) and (transposed or bool(cfg.flags & xo.INPUT_SIGNED))
+    c = codes.astype(np.int64)
+    if not per_array:
+        c = c[:, :, :, None]
+    acc = np.zeros(c.shape[-2:], dtype=np.int64)
+    for p in range(c.shape[0]):
+        for b in range(c.shape[1]):
+            for s in range(c.shape[2]):
+                for pol in range(c.shape[3]):
+                    sign = (-1 if p else 1) * (-1 if pol else 1)
+                    acc += sign * (c[p, b, s, pol].sum(axis=0) << (cfg.slice_bits * s + cfg.stream_bits * b))
+    q_adc = (1 << cfg.adc_bits) - 1 if per_array else (1 << (cfg.adc_bits - 1)) - 1
+    qa, qw = float((1 << cfg.input_bits) - 1), float((1 << cfg.weight_bits) - 1)
+    scale = (float(np.float32(adc_fs)) / q_adc) * float(np.float32(in_scale)) * float(np.float32(w_max)) / (qa * qw)
+    if not offset:
+        return (acc * scale).astype(np.float32)
+    col, row = xo.weight_sums(cfg, W, w_max)
+    half_range = float(np.float32(in_scale)) * float(np.float32(w_max)) / qw
+    return (acc * (2.0 * scale) - (row if transposed else col)[None, :] * half_range).astype(np.float32)
+
+
 def gpu_fwd(xb, cfg, W, X, w_max, x_scale, step=0, profile=None, codes=True):
     planes = xb.tile(cfg, dev(W), w_max, step, None if profile is None else dev(profile))
     out = xb.fwd(cfg, planes, dev(X), W.shape[1], w_max, x_scale, want_codes=codes)
@@ -147,6 +173,12 @@ NONIDEAL_CASES = [
     ("pa_profile", 128, 128, 4, 2, 8, True, 20, 200, 96, "pa+profile", 0.0),
     ("pa_odd_slices", 128, 128, 1, 2, 6, False, 40, 200, 70, "pa+aam", 0.0),
     ("pa_slice4", 64, 64, 2, 4, 8, False, 30, 100, 50, "pa+aam+var", 0.05),
+    # signed inputs in one phase of offset-binary codes, half-range removed digitally
+    ("ob_aam", 128, 128, 1, 2, 16, True, 45, 300, 100, "ob+aam", 0.0),
+    ("ob_aam_var_256", 256, 256, 1, 2, 16, True, 40, 520, 300, "ob+aam+var", 0.1),
+    ("ob_unsigned_fwd", 64, 128, 2, 2, 8, False, 33, 130, 200, "ob+aam", 0.0),     # only the backward pass is signed
+    ("ob_in4_odd", 128, 128, 4, 2, 6, True, 40, 200, 70, "ob+aam", 0.0),
+    ("ob_pa_aam2", 64, 64, 4, 2, 8, True, 64, 256, 256, "ob+pa+aam2", 0.0),
 ]
 
 
@@ -161,6 +193,7 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
     flags |= xo.VARIATION if "var" in ni else 0
     flags |= xo.WIRE_PROFILE if "profile" in ni else 0
     flags |= xo.ADC_PER_ARRAY if "pa" in ni else 0
+    flags |= xo.INPUT_OFFSET if "ob" in ni else 0
     profile = None
     if "profile" in ni:
         rng = np.random.default_rng(5)
@@ -170,6 +203,8 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
     # would sit exactly on a code boundary, where the rounding noise of either side decides.  A range
     # off the binary grid has no such ties.
     fs_factor = 1.037 if "pa" in ni else 1.0
+    if "ob" in ni:          # every row is driven (a zero at mid-range): larger currents
+        fs_factor *= 4.0
     co, cg = both_configs(xo, xb, xbar_rows=R, xbar_cols=C, weight_bits=wb, slice_bits=slb, input_bits=8,
                           stream_bits=sb, adc_bits=8, flags=flags, var_sigma=var_sigma, seed=11,
                           adc_fs_fwd=fs_factor * workloads.adc_full_scale(R, sb, slb),
@@ -178,15 +213,32 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
     Yo, codes_o = xo.fwd(co, W, X, w_max, x_scale, step=3, profile=profile, want_codes=True)
     Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=3, profile=profile)
     check_codes(codes_g, codes_o)
-    assert rel_l2(Yg, Yo) <= 1e-3
+    if "ob" in ni:
+        # The result is a small difference of two large numbers here, so a single differing code of a
+        # high slice and cycle weighs several times more in it than in the two-phase scheme: the relative
+        # L2 bar is stated for that scheme.  Instead: the outputs are the exact digital function of the
+        # codes the pass reported (which the line above holds to the code bar), and where no code of an
+        # output differs, the output is the oracle's bit for bit.
+        assert np.array_equal(Yg, outputs_from_codes(xo, co, codes_g, W, w_max, x_scale, co.adc_fs_fwd, False))
+        same = (codes_g == codes_o).reshape(-1, *Yg.shape).all(axis=0)
+        assert same.mean() > 0.99 and np.array_equal(Yg[same], Yo[same])
+        assert rel_l2(Yg, Yo) <= 1e-2
+    else:
+        assert rel_l2(Yg, Yo) <= 1e-3
     if "pa" in ni:                                   # unsigned codes (several of the cases saturate at 255)
-        assert codes_o.min() >= 0 and codes_o.max() > 127
+        assert codes_o.min() >= 0 and codes_o.max() > (100 if "ob" in ni else 127)
     # the production launch (no code tap: software-pipelined, 32-bit accumulators) gives the same bits
     assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, x_scale, step=3, profile=profile, codes=False), Yg)
     dXo, codes_o = xo.bwd(co, W, dY, w_max, g_scale, step=3, profile=profile, want_codes=True)
     dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=3, profile=profile)
     check_codes(codes_g, codes_o)
-    assert rel_l2(dXg, dXo) <= 1e-3
+    if "ob" in ni:
+        assert np.array_equal(dXg, outputs_from_codes(xo, co, codes_g, W, w_max, g_scale, co.adc_fs_bwd, True))
+        same = (codes_g == codes_o).reshape(-1, *dXg.shape).all(axis=0)
+        assert same.mean() > 0.99 and np.array_equal(dXg[same], dXo[same])
+        assert rel_l2(dXg, dXo) <= 1e-2
+    else:
+        assert rel_l2(dXg, dXo) <= 1e-3
     assert np.array_equal(gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=3, profile=profile, codes=False), dXg)
     # a different step redraws the devices
     if "var" in ni:
@@ -312,6 +364,69 @@ def test_convolution_layer(xo, xb, name, B, H, W, C, k, stride, pad, N, R, sb):
     Wg = Wg.cpu().numpy()
     assert rel_l2(Wg - Wm, Wo - Wm) <= 1e-3
     assert np.abs(Wg - Wo).max() <= 1e-5 * w_max
+
+
+@pytest.mark.parametrize("R,C,sb,slb,wb,M,K,N,adc_bits", [(128, 128, 1, 2, 16, 70, 300, 100, 8), (64, 128, 4, 2, 8, 37, 150, 70, None),
+                                                          (128, 128, 2, 2, 2, 16384, 40, 2048, 8)])
+def test_offset_binary_inputs_ideal_bit_exact(xo, xb, R, C, sb, slb, wb, M, K, N, adc_bits):
+    """Offset-binary signed inputs on ideal arrays: integer path and the corrected outputs, bit for bit.
+    The last case has a single chunk of virtual tiles in the forward pass (the launch that otherwise
+    stores its result directly leaves it to the correcting pass)."""
+    g = workloads.Gemm("t", K, N, M, True, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=K + N)
+    ib = 2 if wb == 2 else 8
+    if adc_bits is None:
+        adc_bits, fs = full_precision_adc(R, C, sb, slb)
+        fs_f = fs_b = fs
+    else:
+        fs_f, fs_b = 4 * workloads.adc_full_scale(R, sb, slb), 4 * workloads.adc_full_scale(C, sb, slb)
+    co, cg = both_configs(xo, xb, xbar_rows=R, xbar_cols=C, weight_bits=wb, slice_bits=slb, input_bits=ib,
+                          stream_bits=min(sb, ib), adc_bits=adc_bits, flags=xo.INPUT_SIGNED | xo.INPUT_OFFSET,
+                          adc_fs_fwd=fs_f, adc_fs_bwd=fs_b)
+    w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    big = M > 1000
+    Yo = xo.fwd(co, W, X, w_max, x_scale, want_codes=not big)
+    Yg = gpu_fwd(xb, cg, W, X, w_max, x_scale, codes=not big)
+    if not big:
+        assert Yg[1].shape[0] == 1 and np.array_equal(Yg[1], Yo[1])
+        Yg, Yo = Yg[0], Yo[0]
+        assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, x_scale, codes=False), Yo)      # production launch
+    assert np.array_equal(Yg, Yo)
+    rows = slice(0, 64) if big else slice(None)
+    dXo, codes_o = xo.bwd(co, W, dY[rows], w_max, g_scale, want_codes=True)
+    dXg, codes_g = gpu_bwd(xb, cg, W, dY[rows], w_max, g_scale)
+    assert codes_g.shape[0] == 1 and np.array_equal(codes_g, codes_o)
+    assert np.array_equal(dXg, dXo)
+    assert np.array_equal(gpu_bwd(xb, cg, W, dY[rows], w_max, g_scale, codes=False), dXo)
+
+
+def test_offset_binary_convolution(xo, xb):
+    """A convolution's padding is an input of value zero: driven at mid-range like any other zero."""
+    from oracle import conv
+    rng = np.random.default_rng(17)
+    B, H, Wd, C, k, stride, pad, N, R = 2, 9, 9, 5, 3, 2, 1, 20, 64
+    X = rng.normal(size=(B, H, Wd, C)).astype(np.float32)
+    Wm = (rng.standard_t(4, size=(k * k * C, N)) * 0.05).astype(np.float32)
+    OH = conv.out_size(H, k, stride, pad)
+    dY = (rng.normal(size=(B, OH, OH, N)) * 1e-2).astype(np.float32)
+    kw = dict(xbar_rows=R, xbar_cols=R, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=2, adc_bits=8,
+              flags=xo.INPUT_SIGNED | xo.INPUT_OFFSET | xo.WIRE_AAM, seed=5,
+              adc_fs_fwd=4 * workloads.adc_full_scale(R, 2, 2), adc_fs_bwd=4 * workloads.adc_full_scale(R, 2, 2))
+    co, cg = both_configs(xo, xb, **kw)
+    w_max, x_scale, g_scale = float(np.abs(Wm).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    geom = xb.conv_geom(B, H, Wd, C, k, k, stride, pad)
+    planes = xb.tile(cg, dev(Wm), w_max, 2)
+    cols = conv.im2col(X, k, k, stride, pad)
+    Yo, codes_o = xo.fwd(co, Wm, cols, w_max, x_scale, step=2, want_codes=True)
+    Yg, codes_g = xb.conv_fwd(cg, planes, dev(X), geom, N, w_max, x_scale, want_codes=True)
+    torch.cuda.synchronize()
+    check_codes(codes_g.cpu().numpy(), codes_o)
+    assert rel_l2(Yg.cpu().numpy().reshape(-1, N), Yo) <= 1e-3
+    dcols_o = xo.bwd(co, Wm, dY.reshape(-1, N), w_max, g_scale, step=2)
+    dXo = conv.col2im(dcols_o, X.shape, k, k, stride, pad)
+    dXg = xb.conv_bwd(cg, planes, dev(dY), geom, N, w_max, g_scale)
+    torch.cuda.synchronize()
+    assert rel_l2(dXg.cpu().numpy(), dXo) <= 1e-3
 
 
 @pytest.mark.parametrize("ni,R,sb,M,K,N", [("ideal", 64, 2, 50, 200, 70), ("aam", 128, 1, 40, 300, 100),

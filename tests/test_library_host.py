@@ -45,7 +45,7 @@ def test_struct_layout_matches(xb):
     dict(xbar_rows=60), dict(xbar_rows=8), dict(xbar_cols=512), dict(weight_bits=7, slice_bits=2),
     dict(weight_bits=32, slice_bits=2), dict(slice_bits=5, weight_bits=10), dict(input_bits=9),
     dict(input_bits=8, stream_bits=3), dict(stream_bits=0), dict(adc_bits=1), dict(adc_bits=17),
-    dict(flags=1 << 10), dict(flags=512 | 256), dict(flags=512, adc_bits=16), dict(flags=256, adc_curve=[0.0] * 8 + [1.0, 0.5] + [1.0] * 7),
+    dict(flags=1 << 11), dict(flags=512 | 256), dict(flags=512, adc_bits=16), dict(flags=256, adc_curve=[0.0] * 8 + [1.0, 0.5] + [1.0] * 7),
     dict(flags=256, adc_curve=[-1.5] + [0.0] * 16), dict(flags=2 | 4), dict(flags=2 | 128), dict(flags=4 | 128), dict(r_min=0.0), dict(r_min=2e6), dict(r_max=float("nan")),
     dict(r_row=-1.0), dict(var_sigma=float("inf")), dict(adc_fs_fwd=0.0), dict(adc_fs_bwd=-3.0),
     dict(upd_noise_gamma=-1.0),
@@ -58,7 +58,7 @@ def test_validate_rejects(xb, kw):
     dict(), dict(xbar_rows=128, xbar_cols=256, weight_bits=16), dict(slice_bits=1, weight_bits=16),
     dict(stream_bits=8), dict(slice_bits=4, weight_bits=16, adc_bits=16), dict(flags=127 & ~4),
     dict(xbar_rows=16, xbar_cols=48), dict(flags=128 | 1 | 8 | 16 | 64), dict(flags=256),
-    dict(flags=256, adc_curve=[-1.0] * 9 + [1.0] * 8), dict(flags=512), dict(flags=512 | 128 | 1 | 32, adc_bits=15),
+    dict(flags=256, adc_curve=[-1.0] * 9 + [1.0] * 8), dict(flags=512), dict(flags=512 | 128 | 1 | 32, adc_bits=15), dict(flags=1024), dict(flags=1024 | 64 | 512 | 2),
 ])
 def test_validate_accepts(xb, kw):
     assert xb.validate(xb.make_config(**kw)) == 0
@@ -79,6 +79,11 @@ def test_size_queries(xb):
     for flags in (xb.ADC_PER_ARRAY, xb.ADC_PER_ARRAY | xb.NI_WIRE_AAM):
         apart = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=flags)
         assert xb.planes_bytes(apart, K, N) == 2 * (fwd + bwd)
+    # offset-binary inputs: the 64-bit sums of the programmed weights per column and per row ride along
+    coded = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=xb.NI_WIRE_AAM | xb.INPUT_OFFSET)
+    assert xb.planes_bytes(coded, K, N) == fwd + bwd + -(-8 * (K + N) // 256) * 256
+    # ... and one phase instead of two: half the staged input of a signed pass
+    assert xb.workspace_bytes(coded, xb.OP_BWD, 64, K, N) < xb.workspace_bytes(c, xb.OP_BWD, 64, K, N)
     assert xb.planes_bytes(c, 0, N) == 0 and xb.planes_bytes(c, K, -1) == 0
     for op in (xb.OP_FWD, xb.OP_BWD, xb.OP_UPDATE):
         small, big = xb.workspace_bytes(c, op, 64, K, N), xb.workspace_bytes(c, op, 6400, K, N)

@@ -17,7 +17,7 @@ Gemm = namedtuple("Gemm", "name K N M signed_input count conv", defaults=[None])
 # flag bits of the parameter struct (plain numbers, typed here so that this module imports nothing)
 NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2 = (
     1, 2, 4, 8, 16, 32, 64, 128)
-ADC_CURVE, ADC_PER_ARRAY = 256, 512
+ADC_CURVE, ADC_PER_ARRAY, INPUT_OFFSET = 256, 512, 1024
 PAPER_NI = NI_WIRE_AAM | NI_UPD_NL | NI_UPD_NOISE  # wire parasitics + write non-linearity + write noise
 
 
@@ -190,10 +190,11 @@ def image_tensor_torch(g, seed, device):
     return X if g.signed_input else X.abs_()
 
 
-def macs(g, n_slices, n_cycles):
+def macs(g, n_slices, n_cycles, signed_phases=2):
     """Emulated crossbar MACs of one layer: every (slice, cycle, phase) pass counts, a differential
-    pair counts once; the update counts the plain outer-product MACs."""
+    pair counts once; the update counts the plain outer-product MACs.  Signed inputs take two phases,
+    or one when they are streamed as offset-binary codes."""
     base = g.M * g.K * g.N
-    fwd = base * n_slices * n_cycles * (2 if g.signed_input else 1)
-    bwd = base * n_slices * n_cycles * 2
+    fwd = base * n_slices * n_cycles * (signed_phases if g.signed_input else 1)
+    bwd = base * n_slices * n_cycles * signed_phases
     return dict(fwd=fwd, bwd=bwd, upd=base, logical=3 * base)
