@@ -52,6 +52,9 @@
 
 #define XO_STREAM_VARIATION 1u
 #define XO_STREAM_WRITE     2u
+#define XO_STREAM_PULSE_ROWS  3u
+#define XO_STREAM_PULSE_COLS  4u
+#define XO_STREAM_PULSE_NOISE 5u
 
 typedef struct xo_config {
   uint32_t struct_size, abi_version;
@@ -526,6 +529,91 @@ int xo_update(const xo_config* cfg, float* W, const float* X, const float* dY, i
       const double g_new = clampd(g - (double)lr * written, -1.0, 1.0);
       W[(size_t)ki * Ns + ni] = (float)((double)w_max * g_new);
     }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------------------------- */
+/* Pulse-level update (Sec. IV-C names the parallel update schemes whose result the aggregate    */
+/* model above describes; this is the stochastic bit-stream scheme of its reference [ibm_RPU]):  */
+/* every sample m applies its inputs to the rows and its errors to the columns as random pulse  */
+/* trains of `bl` slots; a device is pulsed once in every slot in which its row and its column  */
+/* both fire.  A value fires with probability p = min(1, |value| / range) per slot, so the       */
+/* expected number of pulses is bl p_x p_d, proportional to the product: the outer-product       */
+/* update, one sample at a time, without ever forming the gradient.                              */
+/*                                                                                               */
+/* Readings: slot j of element `index` fires when uniform 32-bit word j of the element's Philox   */
+/* blocks (block index*8 + j/4, word j%4, streams 3 / 4 for rows / columns) is below             */
+/* rne(p 2^32).  A pulse moves the state g = W / w_max by dw_min against the sign of x d         */
+/* (descent); with XO_UPD_NL the move is scaled by exp(-v x) going up and exp(-v (1 - x)) going   */
+/* down, x = (g + 1) / 2, evaluated at the state the pulse finds; with XO_UPD_NOISE every pulse   */
+/* adds gamma sqrt(dw_min) times a normal number (the aggregate model's sqrt law for one pulse; */
+/* number m*32 + j of stream 5 keyed with step*2^31 + device index); the state is clamped to      */
+/* [-1, 1] after every pulse.  Samples in order, devices independent.                            */
+/* ------------------------------------------------------------------------------------------- */
+uint32_t xo_pulse_train(uint64_t seed, uint32_t stream, uint64_t step, uint64_t index, double p, int bl) {
+  const uint32_t key[2] = {(uint32_t)seed ^ (0x9E3779B9u * stream), (uint32_t)(seed >> 32) ^ (0xBB67AE85u * stream)};
+  const uint64_t threshold = (uint64_t)rint(clampd(p, 0.0, 1.0) * 4294967296.0);
+  uint32_t bits = 0;
+  for (int j = 0; j < bl; j += 4) {
+    const uint64_t blk = index * 8 + (uint64_t)(j >> 2);
+    const uint32_t ctr[4] = {(uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step, (uint32_t)(step >> 32)};
+    uint32_t w[4];
+    xo_philox4x32_10(ctr, key, w);
+    for (int e = 0; e < 4 && j + e < bl; ++e)
+      if ((uint64_t)w[e] < threshold) bits |= 1u << (j + e);
+  }
+  return bits;
+}
+
+int xo_update_pulsed(const xo_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N,
+                     float w_max, float x_range, float d_range, int bl, float dw_min, uint64_t step,
+                     int64_t* pulses_out) {
+  if (bl < 1 || bl > 31 || M <= 0 || K <= 0 || N <= 0) return -1;
+  double* g = (double*)malloc(sizeof(double) * (size_t)K * N);
+  uint32_t* a = (uint32_t*)malloc(sizeof(uint32_t) * ((size_t)K + N));
+  if (!g || !a) { free(g); free(a); return -2; }
+  uint32_t* b = a + K;
+  for (size_t i = 0; i < (size_t)K * N; ++i) g[i] = (double)W[i] / (double)w_max;
+  if (pulses_out) memset(pulses_out, 0, sizeof(int64_t) * (size_t)K * N);
+  const double sigma = (double)cfg->upd_noise_gamma * sqrt((double)dw_min);
+  for (int m = 0; m < M; ++m) {
+    /* bit 31 of a train carries the sign of its value */
+    for (int k = 0; k < K; ++k) {
+      const double x = (double)X[(size_t)m * K + k];
+      a[k] = xo_pulse_train(cfg->seed, XO_STREAM_PULSE_ROWS, step, (uint64_t)m * K + k, fabs(x) / (double)x_range, bl) |
+             (x < 0.0 ? 0x80000000u : 0u);
+    }
+    for (int n = 0; n < N; ++n) {
+      const double d = (double)dY[(size_t)m * N + n];
+      b[n] = xo_pulse_train(cfg->seed, XO_STREAM_PULSE_COLS, step, (uint64_t)m * N + n, fabs(d) / (double)d_range, bl) |
+             (d < 0.0 ? 0x80000000u : 0u);
+    }
+    for (int k = 0; k < K; ++k)
+      for (int n = 0; n < N; ++n) {
+        const uint32_t both = a[k] & b[n] & 0x7FFFFFFFu;
+        if (!both) continue;
+        int count = 0;
+        for (uint32_t v = both; v; v &= v - 1) ++count;
+        const double dir = ((a[k] ^ b[n]) & 0x80000000u) ? 1.0 : -1.0;   /* against the sign of x d */
+        const uint64_t dev = (uint64_t)k * N + n;
+        double* gs = &g[(size_t)k * N + n];
+        for (int j = 0; j < count; ++j) {
+          double move = (double)dw_min;
+          if (cfg->flags & XO_UPD_NL) {
+            const double x = clampd(0.5 * (*gs + 1.0), 0.0, 1.0);
+            move *= dir > 0.0 ? exp(-(double)cfg->upd_nl_v * x) : exp(-(double)cfg->upd_nl_v * (1.0 - x));
+          }
+          double next = *gs + dir * move;
+          if (cfg->flags & XO_UPD_NOISE)
+            next += sigma * xo_normal(cfg->seed, XO_STREAM_PULSE_NOISE, (step << 31) | dev, (uint64_t)m * 32 + j);
+          *gs = clampd(next, -1.0, 1.0);
+        }
+        if (pulses_out) pulses_out[(size_t)k * N + n] += (dir > 0.0 ? 1 : -1) * count;
+      }
+  }
+  for (size_t i = 0; i < (size_t)K * N; ++i) W[i] = (float)((double)w_max * g[i]);
+  free(g);
+  free(a);
   return 0;
 }
 

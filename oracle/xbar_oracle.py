@@ -260,6 +260,28 @@ def bwd(cfg, W, dY, w_max, g_scale, step=0, profile=None, want_codes=False, want
     return bwd_planes(cfg, U, dY, w_max, g_scale, want_codes, want_acc, weight_sums(cfg, W, w_max)[1])
 
 
+def pulse_train(seed, stream, step, index, p, bl):
+    f = lib().xo_pulse_train
+    f.restype = C.c_uint32
+    return int(f(C.c_uint64(seed), C.c_uint32(stream), C.c_uint64(step), C.c_uint64(index), C.c_double(p), C.c_int(bl)))
+
+
+def update_pulsed(cfg, W, X, dY, w_max, x_range, d_range, bl, dw_min, step=0, want_pulses=False):
+    """Stochastic pulse-train update, one sample at a time: returns the updated copy of W (and the signed
+    number of pulses every device received, if asked)."""
+    W = _f32(W).copy()
+    X, dY = _f32(X), _f32(dY)
+    M, K = X.shape
+    N = dY.shape[1]
+    assert W.shape == (K, N) and dY.shape[0] == M
+    pulses = np.empty((K, N), dtype=np.int64) if want_pulses else None
+    rc = lib().xo_update_pulsed(C.byref(cfg), _p(W, C.c_float), _p(X, C.c_float), _p(dY, C.c_float), M, K, N,
+                                C.c_float(w_max), C.c_float(x_range), C.c_float(d_range), C.c_int(bl),
+                                C.c_float(dw_min), C.c_uint64(step), _p(pulses, C.c_int64))
+    assert rc == 0, rc
+    return (W, pulses) if want_pulses else W
+
+
 def update(cfg, W, X, dY, w_max, grad_scale, lr, step=0, k_idx=None, n_idx=None, N_full=None, want_grad=False):
     """Returns the updated copy of W (and the raw gradient sum if asked)."""
     W = _f32(W).copy()

@@ -885,3 +885,130 @@ def test_peripheral_definitions_against_library_autograd():
     lt.mean().backward()
     loss, dz = periph.softmax_xent(z, labels, 1.0 / 5)
     assert np.allclose(loss, lt.detach().numpy(), atol=1e-12) and np.allclose(dz, zt.grad.numpy(), atol=1e-12)
+
+
+# ------------------------------------------------------------------------------------------------
+# pulse-level update (stochastic pulse trains)
+# ------------------------------------------------------------------------------------------------
+def _train_from_philox(xo, seed, stream, step, index, p, bl):
+    """The documented construction, from the Philox function alone."""
+    key = [(seed & 0xFFFFFFFF) ^ ((0x9E3779B9 * stream) & 0xFFFFFFFF), (seed >> 32) ^ ((0xBB67AE85 * stream) & 0xFFFFFFFF)]
+    thr = int(np.rint(min(max(p, 0.0), 1.0) * 4294967296.0))
+    bits = 0
+    for j in range(bl):
+        blk = index * 8 + j // 4
+        w = xo.philox4x32_10([blk & 0xFFFFFFFF, blk >> 32, step & 0xFFFFFFFF, step >> 32], key)
+        if w[j % 4] < thr:
+            bits |= 1 << j
+    return bits
+
+
+def test_pulse_trains(xo):
+    seed = 0x1234567890ABCDEF
+    for bl in (1, 10, 31):
+        full = (1 << bl) - 1
+        assert xo.pulse_train(seed, 3, 7, 11, 0.0, bl) == 0
+        assert xo.pulse_train(seed, 3, 7, 11, 1.0, bl) == full and xo.pulse_train(seed, 3, 7, 11, 2.5, bl) == full
+        for index, p in ((0, 0.5), (123456789012, 0.3), (5, 0.999)):
+            t = xo.pulse_train(seed, 4, 9, index, p, bl)
+            assert t == _train_from_philox(xo, seed, 4, 9, index, p, bl) and t <= full
+    # a longer train extends a shorter one; rows and columns, steps and elements draw different trains
+    assert xo.pulse_train(seed, 3, 0, 5, 0.5, 31) & 0x3FF == xo.pulse_train(seed, 3, 0, 5, 0.5, 10)
+    base = xo.pulse_train(seed, 3, 0, 5, 0.5, 31)
+    assert len({base, xo.pulse_train(seed, 4, 0, 5, 0.5, 31), xo.pulse_train(seed, 3, 1, 5, 0.5, 31),
+                xo.pulse_train(seed, 3, 0, 6, 0.5, 31)}) == 4
+    # firing frequency = p (4 sigma over 31 * 3000 slots)
+    for p in (0.1, 0.5, 0.83):
+        ones = sum(bin(xo.pulse_train(seed, 3, 2, i, p, 31)).count("1") for i in range(3000))
+        n = 31 * 3000
+        assert abs(ones - n * p) <= 4 * np.sqrt(n * p * (1 - p))
+
+
+def test_pulsed_update_counts_and_linear_device(xo):
+    rng = np.random.default_rng(8)
+    M, K, N, bl, dw = 9, 7, 5, 31, 2.0 ** -12
+    X = rng.uniform(-1.2, 1.2, size=(M, K)).astype(np.float32)
+    dY = rng.uniform(-0.5, 0.5, size=(M, N)).astype(np.float32)
+    W0 = rng.uniform(-0.5, 0.5, size=(K, N)).astype(np.float32)
+    cfg = xo.make_config(seed=77)
+    W1, pulses = xo.update_pulsed(cfg, W0, X, dY, 2.0, 1.0, 0.4, bl, dw, step=3, want_pulses=True)
+    # brute force: trains from the Philox function, coincidences, direction against the sign of x d
+    want = np.zeros((K, N), dtype=np.int64)
+    for m in range(M):
+        a = [_train_from_philox(xo, 77, 3, 3, m * K + k, abs(float(X[m, k])) / 1.0, bl) for k in range(K)]
+        b = [_train_from_philox(xo, 77, 4, 3, m * N + n, abs(float(dY[m, n])) / np.float64(np.float32(0.4)), bl) for n in range(N)]
+        for k in range(K):
+            for n in range(N):
+                c = bin(a[k] & b[n]).count("1")
+                want[k, n] -= c * int(np.sign(X[m, k]) * np.sign(dY[m, n]))
+    assert np.array_equal(pulses, want) and np.abs(want).max() > 3
+    # linear device: every pulse moves the state by dw_min (all quantities here are exact in binary)
+    assert np.array_equal(W1, (W0.astype(np.float64) + 2.0 * dw * want).astype(np.float32))
+    # values at the range: every slot fires on both sides, bl pulses per sample
+    Xf, Df = np.full((4, 2), 1.0, np.float32), np.array([[0.4, -0.4, 1.0]] * 4, dtype=np.float32)
+    _, p = xo.update_pulsed(cfg, np.zeros((2, 3), np.float32), Xf, Df, 2.0, 1.0, 0.4, bl, dw, want_pulses=True)
+    assert np.array_equal(p, np.array([[-4 * bl, 4 * bl, -4 * bl]] * 2))
+    # zero inputs or zero errors: nothing is written
+    assert np.array_equal(xo.update_pulsed(cfg, W0, 0 * X, dY, 2.0, 1.0, 0.4, bl, dw), W0)
+    assert np.array_equal(xo.update_pulsed(cfg, W0, X, 0 * dY, 2.0, 1.0, 0.4, bl, dw), W0)
+
+
+def test_pulsed_update_is_unbiased_outer_product(xo):
+    """Expected pulses = bl p_x p_d: the mean written change is the outer-product update."""
+    rng = np.random.default_rng(9)
+    M, K, N, bl = 6000, 4, 3, 31
+    X = rng.uniform(-1, 1, size=(M, K)).astype(np.float32)
+    dY = rng.uniform(-1, 1, size=(M, N)).astype(np.float32)
+    _, pulses = xo.update_pulsed(xo.make_config(seed=5), np.zeros((K, N), np.float32), X, dY, 1.0, 1.0, 1.0, bl, 1e-6,
+                                 want_pulses=True)
+    px, pd = np.abs(X.astype(np.float64)), np.abs(dY.astype(np.float64))
+    mean = -bl * (X.astype(np.float64).T @ dY.astype(np.float64))
+    # variance of a coincidence count: bl p (1 - p) with p = px pd, independent over samples
+    pp = px[:, :, None] * pd[:, None, :]
+    sigma = np.sqrt((bl * pp * (1 - pp)).sum(axis=0))
+    assert (np.abs(pulses - mean) <= 4.5 * sigma).all()
+    assert np.abs(mean).max() > 20 * sigma.max() / 4.5            # the test can see a wrong factor or sign
+
+
+def test_pulsed_update_device_model(xo):
+    """Per-pulse non-linearity and noise: sequential closed forms, and the aggregate model for one pulse."""
+    bl, dw, v, gamma = 31, 2.0 ** -9, 1.7, 0.6
+    X, D = np.array([[1.0]], np.float32), np.array([[-1.0]], np.float32)         # x d < 0: bl pulses upwards
+    for g0 in (-0.8, 0.1, 0.97):
+        W0 = np.array([[g0]], np.float32)
+        cfg = xo.make_config(flags=xo.UPD_NL, upd_nl_v=v)
+        up = xo.update_pulsed(cfg, W0, X, D, 1.0, 1.0, 1.0, bl, dw)[0, 0]
+        down = xo.update_pulsed(cfg, W0, X, -D, 1.0, 1.0, 1.0, bl, dw)[0, 0]
+        gu = gd = float(W0[0, 0])
+        for _ in range(bl):
+            gu = min(gu + dw * np.exp(-np.float64(np.float32(v)) * (gu + 1) / 2), 1.0)
+            gd = max(gd - dw * np.exp(-np.float64(np.float32(v)) * (1 - (gd + 1) / 2)), -1.0)
+        assert abs(up - gu) < 1e-6 and abs(down - gd) < 1e-6
+        assert up - g0 > 0 > down - g0
+        # one pulse = the aggregate model writing the same ideal change (learning rate 1, delta = -+dw)
+        one_up = xo.update_pulsed(cfg, W0, X, D, 1.0, 1.0, 1.0, 1, dw)[0, 0]
+        agg_up = xo.update(cfg, W0, X, D, 1.0, dw, 1.0)[0, 0]
+        assert abs(one_up - agg_up) < 1e-7
+        one_dn = xo.update_pulsed(cfg, W0, X, -D, 1.0, 1.0, 1.0, 1, dw)[0, 0]
+        agg_dn = xo.update(cfg, W0, X, -D, 1.0, dw, 1.0)[0, 0]
+        assert abs(one_dn - agg_dn) < 1e-7
+    # noise: pulse j of sample m of device dev takes normal number m*32 + j of stream 5 keyed (step << 31) | dev
+    cfg = xo.make_config(flags=xo.UPD_NOISE, upd_noise_gamma=gamma, seed=21)
+    K, N, step = 2, 3, 6
+    Xn, Dn = np.ones((2, K), np.float32), -np.ones((2, N), np.float32)
+    Wn = xo.update_pulsed(cfg, np.zeros((K, N), np.float32), Xn, Dn, 4.0, 1.0, 1.0, 3, dw, step=step)
+    for k in range(K):
+        for n in range(N):
+            g = 0.0
+            for m in range(2):
+                for j in range(3):
+                    g += dw + np.float64(np.float32(gamma)) * np.sqrt(dw) * xo.normal(21, 5, (step << 31) | (k * N + n), m * 32 + j)
+                    g = min(max(g, -1.0), 1.0)
+            assert abs(Wn[k, n] - 4.0 * g) < 1e-6
+    # the sqrt law: n pulses carry the noise the aggregate model gives their sum (standard deviation
+    # gamma sqrt(n dw_min)), checked over many devices
+    K = N = 40
+    Wm = xo.update_pulsed(xo.make_config(flags=xo.UPD_NOISE, upd_noise_gamma=0.05, seed=2), np.zeros((K, N), np.float32),
+                          np.ones((1, K), np.float32), -np.ones((1, N), np.float32), 1.0, 1.0, 1.0, 16, dw)
+    resid = Wm.astype(np.float64) - 16 * dw
+    assert abs(resid.std() / (0.05 * np.sqrt(16 * dw)) - 1) < 0.06 and abs(resid.mean()) < 4 * resid.std() / 40
