@@ -135,6 +135,16 @@ def end_to_end(args, torch, workloads, xb, device):
     print(json.dumps(line))
 
 
+# Pulse-level update of the benchmark: 31-slot trains, a device with about a thousand states over its
+# range, inputs fire in proportion to their size and the error range follows from the learning rate:
+# mean written change = lr x dY / w_max  <=>  x_range d_range = bl dw_min w_max / lr.
+PULSE_DW_MIN, PULSE_LR = 1e-3, 0.01
+
+
+def pulse_d_range(L):
+    return 31 * PULSE_DW_MIN * L["w_max"] / (PULSE_LR * L["x_scale"])
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -145,6 +155,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
+    ap.add_argument("--pulsed-update", action="store_true",
+                    help="pulse-level update (stochastic pulse trains of 31 slots, one sample at a time) instead of "
+                         "the aggregate write")
     ap.add_argument("--offset-inputs", action="store_true",
                     help="signed inputs in one phase of offset-binary codes instead of two phases of magnitudes: "
                          "half the crossbar passes of every signed pass")
@@ -241,6 +254,10 @@ def main():
             max_ws = max(max_ws, *(xb.conv_workspace_bytes(cfg, op, geom, g.N) for op in (0, 1, 2)))
         max_ws_upd = max(max_ws_upd, xb.workspace_bytes(cfg, 2, g.M, g.K, g.N) if geom is None else
                          xb.conv_workspace_bytes(cfg, 2, geom, g.N))
+        if args.pulsed_update:
+            assert geom is None, "the pulse-level update takes the layer's input matrix"
+            max_ws_upd = max(max_ws_upd, xb.workspace_bytes(cfg, xb.OP_UPDATE_PULSED, g.M, g.K, g.N))
+            max_ws = max(max_ws, max_ws_upd)
         max_out = max(max_out, g.M * g.N, g.M * g.K)
     planes = torch.empty(max_planes, dtype=torch.uint8, device=device)
     ws = torch.empty(max_ws, dtype=torch.uint8, device=device)
@@ -259,6 +276,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    pulsed_events = []        # event pairs around the pulse-level updates of the timed steps
     events = HipEvents()
     vmm_records = []          # (layer index, 'fwd'|'bwd', event pair)
 
@@ -283,7 +301,10 @@ def main():
                                 out=out[:g.M * g.N].view(geom.batch, geom.out_h, geom.out_w, g.N))
 
                 def update():
-                    if geom is None:
+                    if args.pulsed_update:
+                        xb.update_pulsed(cfg, L["W"], L["X"], L["dY"], L["w_max"], L["x_scale"], pulse_d_range(L), 31,
+                                         PULSE_DW_MIN, s, ws=ws_upd)
+                    elif geom is None:
                         xb.update(cfg, L["W"], L["X"], L["dY"], L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws_upd)
                     else:
                         xb.conv_update(cfg, L["W"], L["X"], L["dY"].view(geom.batch, geom.out_h, geom.out_w, g.N), geom,
@@ -304,7 +325,14 @@ def main():
                     xb.conv_bwd(cfg, planes, L["dY"].view(geom.batch, geom.out_h, geom.out_w, g.N), geom, g.N, L["w_max"],
                                 L["g_scale"], ws=ws, out=out[:L["X"].numel()].view(L["X"].shape))
                 if side is None:
-                    update()
+                    if timed and args.pulsed_update:
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        update()
+                        e1.record()
+                        pulsed_events.append((e0, e1))
+                    else:
+                        update()
                 else:
                     main.wait_event(updated)              # the next generator call reads the written W
 
@@ -413,6 +441,8 @@ def main():
             "AAM, all first-order paths" if kw["flags"] & workloads.NI_WIRE_AAM2 else "AAM")
     else:
         array_text = "ideal arrays"
+    if args.pulsed_update:
+        array_text += ", pulse-level update (31-slot stochastic trains)"
     if signed_phases == 1:
         array_text += ", offset-binary signed inputs"
     if arrays == 2:
@@ -433,6 +463,20 @@ def main():
     }
     if fcm_refresh_ms is not None:
         line["fcm_refresh_ms"] = fcm_refresh_ms
+    if args.pulsed_update:
+        # pulses of one step, counted in an untimed pass on copies of the weights
+        n_pulses = 0
+        for L in layers:
+            g = L["g"]
+            dw = PULSE_DW_MIN
+            _, cnt = xb.update_pulsed(L["cfg"], L["W"].clone(), L["X"], L["dY"], L["w_max"], L["x_scale"],
+                                      pulse_d_range(L), 31, dw, 0, ws=ws_upd, want_pulses=True)
+            n_pulses += int(cnt.abs().sum().item()) * g.count
+        upd_ms = sum(a.elapsed_time(b) for a, b in pulsed_events) / args.steps
+        line["pulsed_update"] = {"ms_per_step": round(upd_ms, 3), "pulses_per_step": n_pulses,
+                                 "device_samples_per_step": tot["upd"],
+                                 "gpulses_per_s": round(n_pulses / (upd_ms * 1e-3) / 1e9, 3),
+                                 "device_gsamples_per_s": round(tot["upd"] / (upd_ms * 1e-3) / 1e9, 1)}
     print(json.dumps(line))
 
 

@@ -83,6 +83,7 @@ extern "C" {
 #define XBAR_OP_BWD    1
 #define XBAR_OP_UPDATE 2
 #define XBAR_OP_FCM    3   /* pass M = 1 */
+#define XBAR_OP_UPDATE_PULSED 4
 
 /* Parameter struct: plain data, caller-owned, read during the call only (Sec. IV lists the three
  * input groups; Sec. V and VI-B give the values used in the paper, quoted below as "paper:"). */
@@ -181,6 +182,30 @@ int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float*
 int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N,
                 float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes,
                 void* hip_stream);
+
+/*
+ * Pulse-level weight update (Sec. IV-C names the parallel update schemes whose result xbar_update
+ * models in one aggregate write; this is the scheme with stochastic pulse trains): W[K][N] in place,
+ * one sample at a time and one pulse at a time, the gradient is never formed.
+ *   Sample m drives row k with a random train of `bl` slots (1..31) that fires with probability
+ *   min(1, |X[m][k]| / x_range) per slot, column n likewise from dY[m][n] / d_range; device (k, n) is
+ *   pulsed once per slot in which both fire, against the sign of X dY (descent).  Expected pulses:
+ *   bl p_x p_d, so the mean written change is the outer-product update with learning rate
+ *   bl dw_min w_max / (x_range d_range).
+ *   Train: slot j of element i (i = m K + k for rows, m N + n for columns) fires when uniform word j
+ *   of the element (Philox-4x32-10 block 8 i + j / 4, word j % 4, counter words 2, 3 = step, key =
+ *   seed mixed with stream 3 for rows, 4 for columns, as for the normal numbers) is below rne(p 2^32).
+ *   Pulse: state g = W / w_max moves by dw_min; with XBAR_NI_UPD_NL the move is scaled by exp(-v x)
+ *   upwards and exp(-v (1 - x)) downwards, x = (g + 1) / 2 at the state the pulse finds; with
+ *   XBAR_NI_UPD_NOISE every pulse adds upd_noise_gamma sqrt(dw_min) times normal number m 32 + j (j =
+ *   ordinal of the pulse within the sample) of stream 5 of step (step << 31) | (k N + n); g is clamped
+ *   to [-1, 1] after every pulse.  Double precision throughout, W <- float(w_max g) at the end.
+ *   step < 2^33.  pulses: NULL, or int64 [K][N] receiving the signed number of pulses per device.
+ *   ws: xbar_workspace_bytes(cfg, XBAR_OP_UPDATE_PULSED, M, K, N).
+ */
+int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N,
+                       float w_max, float x_range, float d_range, int bl, float dw_min, uint64_t step,
+                       long long* pulses, void* ws, size_t ws_bytes, void* hip_stream);
 
 /*
  * Convolution layers (Sec. IV: a layer's kernels are the columns of its weight matrix, one output

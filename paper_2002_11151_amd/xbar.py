@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(HERE, "libxbar.so")
 
 (NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2, ADC_CURVE,
  ADC_PER_ARRAY, INPUT_OFFSET) = (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024)
-OP_FWD, OP_BWD, OP_UPDATE, OP_FCM = 0, 1, 2, 3
+OP_FWD, OP_BWD, OP_UPDATE, OP_FCM, OP_UPDATE_PULSED = 0, 1, 2, 3, 4
 ABI_VERSION = 2
 
 
@@ -119,6 +119,9 @@ _SIGNATURES = {
                                      C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                               C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_update_pulsed": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                     C.c_float, C.c_float, C.c_float, C.c_int, C.c_float, C.c_uint64, C.c_void_p,
+                                     C.c_void_p, C.c_size_t, C.c_void_p]),
 }
 
 
@@ -247,6 +250,23 @@ def update(cfg, W, X, dY, w_max, grad_scale, lr, step=0, ws=None):
     _check(lib().xbar_update(C.byref(cfg), _dev(W), _dev(X), _dev(dY), M, K, N, w_max, grad_scale, lr, step,
                              C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return W
+
+
+def update_pulsed(cfg, W, X, dY, w_max, x_range, d_range, bl, dw_min, step=0, ws=None, want_pulses=False):
+    """xbar_update_pulsed: W[K][N] in place, one sample and one pulse at a time (stochastic pulse trains).
+    With want_pulses also returns the signed pulse count of every device (int64 [K][N])."""
+    K, N = W.shape
+    M = X.shape[0]
+    assert X.shape == (M, K) and dY.shape == (M, N)
+    nbytes = workspace_bytes(cfg, OP_UPDATE_PULSED, M, K, N)
+    if nbytes == 0:
+        _check(validate(cfg) or -2)
+    ws = _buffer(nbytes, ws, W.device)
+    pulses = torch.empty((K, N), dtype=torch.int64, device=W.device) if want_pulses else None
+    _check(lib().xbar_update_pulsed(C.byref(cfg), _dev(W), _dev(X), _dev(dY), M, K, N, w_max, x_range, d_range, bl,
+                                    dw_min, step, None if pulses is None else C.c_void_p(pulses.data_ptr()),
+                                    C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return (W, pulses) if want_pulses else W
 
 
 def fcm_profile(cfg, W, w_max, step=0, ws=None, profile=None):

@@ -615,6 +615,68 @@ def test_adc_transfer_curve(xo, xb, curve_kind, sb, bits):
     assert rel_l2(linear, Yo) > 3e-3                                           # the curve matters here
 
 
+PULSED_CASES = [
+    # name, M, K, N, bl, x_range, d_range, flags, w_max
+    ("linear_ragged", 130, 70, 100, 31, 2.0, 0.02, "", 1.5),
+    ("linear_dense_pulses", 40, 64, 64, 31, 0.5, 0.005, "", 1.0),        # most probabilities clip at 1
+    ("short_trains", 200, 33, 17, 5, 1.5, 0.02, "", 1.0),
+    ("single", 1, 1, 1, 1, 0.5, 0.005, "", 1.0),
+    ("two_chunks", 2100, 8192, 64, 4, 3.0, 0.03, "", 1.0),               # the trains of 1984 samples are resident at a time
+    ("nl", 130, 70, 100, 31, 2.0, 0.02, "nl", 1.5),
+    ("nl_noise", 90, 128, 65, 31, 1.0, 0.01, "nl+noise", 1.0),
+    ("noise_two_chunks", 2000, 8192, 64, 4, 3.0, 0.03, "noise", 1.0),
+    ("large_layer", 70, 2048, 1030, 31, 2.0, 0.02, "nl+noise", 1.0),     # 4 x 4 devices per thread
+    ("large_layer_linear", 70, 2048, 1030, 31, 2.0, 0.02, "", 1.0),
+    ("large_layer_nl", 300, 2048, 1030, 12, 2.0, 0.02, "nl", 1.0),       # several stages of 64 samples
+    ("large_layer_noise", 70, 2048, 1030, 31, 2.0, 0.02, "noise", 1.0),
+]
+
+
+@pytest.mark.parametrize("name,M,K,N,bl,x_range,d_range,ni,w_max", PULSED_CASES)
+def test_pulsed_update(xo, xb, name, M, K, N, bl, x_range, d_range, ni, w_max):
+    """Pulse-level update: pulse counts bit for bit; a linear, noise-free device then ends in exactly
+    the oracle's state, the exponential and the normal numbers are library functions on both sides."""
+    g = workloads.Gemm("t", K, N, M, True, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=M + K + N)
+    W = np.clip(W * 4, -0.9 * w_max, 0.9 * w_max).astype(np.float32)
+    flags = (xo.UPD_NL if "nl" in ni else 0) | (xo.UPD_NOISE if "noise" in ni else 0)
+    co, cg = both_configs(xo, xb, flags=flags, upd_nl_v=1.3, upd_noise_gamma=0.4, seed=19)
+    dw = 2.0 ** -10
+    Wo, pulses_o = xo.update_pulsed(co, W, X, dY, w_max, x_range, d_range, bl, dw, step=5, want_pulses=True)
+    Wg, pulses_g = xb.update_pulsed(cg, dev(W.copy()), dev(X), dev(dY), w_max, x_range, d_range, bl, dw, step=5,
+                                    want_pulses=True)
+    torch.cuda.synchronize()
+    Wg, pulses_g = Wg.cpu().numpy(), pulses_g.cpu().numpy()
+    assert np.array_equal(pulses_g, pulses_o)
+    assert np.abs(pulses_o).sum() > 0 or name == "single"
+    if not ni:
+        assert np.array_equal(Wg, Wo)
+    else:
+        # exp, log, sin and cos come from two maths libraries: a few units in the last place of a double
+        # per pulse, far below single precision of the state
+        assert np.abs(Wg - Wo).max() <= 2e-7 * w_max
+        assert not np.array_equal(Wo, W)
+    # without the optional counts the same state is written
+    W2 = xb.update_pulsed(cg, dev(W.copy()), dev(X), dev(dY), w_max, x_range, d_range, bl, dw, step=5)
+    torch.cuda.synchronize()
+    assert np.array_equal(W2.cpu().numpy(), Wg)
+
+
+def test_pulsed_update_argument_checks(xb):
+    cg = xb.make_config()
+    W, X, dY = (torch.zeros(s, device="cuda") for s in ((8, 8), (4, 8), (4, 8)))
+    for bl in (0, 32):
+        with pytest.raises(xb.XbarError, match="invalid"):
+            xb.update_pulsed(cg, W, X, dY, 1.0, 1.0, 1.0, bl, 1e-3)
+    with pytest.raises(xb.XbarError, match="invalid"):
+        xb.update_pulsed(cg, W, X, dY, 1.0, 0.0, 1.0, 31, 1e-3)
+    with pytest.raises(xb.XbarError, match="invalid"):
+        xb.update_pulsed(cg, W, X, dY, 1.0, 1.0, 1.0, 31, 1e-3, step=1 << 33)
+    with pytest.raises(xb.XbarError, match="workspace"):
+        xb.update_pulsed(cg, W, X, dY, 1.0, 1.0, 1.0, 31, 1e-3, ws=torch.empty(16, dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+
+
 def test_error_paths_on_device(xo, xb):
     cg = xb.make_config()
     W = torch.zeros((64, 64), device="cuda")

@@ -90,6 +90,12 @@ def test_size_queries(xb):
         assert 0 < small <= big
         assert xb.workspace_bytes(c, op, 0, K, N) == 0
     assert xb.workspace_bytes(c, 7, 64, K, N) == 0
+    # pulse-level update: trains of a chunk of samples (4 bytes per input and error, at most 64 MiB or 64
+    # samples) and the double-precision states between chunks
+    pad = lambda b: -(-b // 256) * 256
+    assert xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 100, K, N) == pad(400 * K) + pad(400 * N) + pad(8 * K * N)
+    big = xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 1 << 22, K, N)
+    assert big - pad(8 * K * N) <= (64 << 20) + 512 and big > xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 100, K, N)
     # circuit-level model: 5 crossbar-sized fp64 vectors per resident block, at most 2048 blocks
     items = 2 * 1 * 8 * 2                                   # (row tiles x column tiles) x slices x arrays
     assert xb.workspace_bytes(c, xb.OP_FCM, 1, K, N) % (5 * 128 * 128 * 8) == 0
