@@ -1,19 +1,30 @@
-"""Builds the HIP library (csrc/*.hip -> libxbar.so beside this file) for gfx950 with hipcc."""
+"""Builds the HIP library (csrc/*.hip -> libxbar.so beside this file) for gfx950 with hipcc: one object
+per source file, compiled side by side, then one link."""
 import os
 import subprocess
+import tempfile
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = [os.path.join(HERE, "csrc", "xbar.hip"), os.path.join(HERE, "csrc", "periph.hip")]
+SRC = [os.path.join(HERE, "csrc", name) for name in ("xbar.hip", "wire.hip", "fcm.hip", "pulse.hip", "periph.hip")]
 LIB = os.path.join(HERE, "libxbar.so")
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include")]
 
 
 def build(verbose=False):
-    cmd = ["hipcc"] + FLAGS + (["-Rpass-analysis=kernel-resource-usage"] if verbose else []) + ["-o", LIB] + SRC
-    subprocess.run(cmd, check=True)
+    extra = ["-Rpass-analysis=kernel-resource-usage"] if verbose else []
+    with tempfile.TemporaryDirectory() as tmp:
+        objects = [os.path.join(tmp, os.path.basename(s) + ".o") for s in SRC]
+
+        def compile_one(pair):
+            subprocess.run(["hipcc"] + FLAGS + extra + ["-c", "-o", pair[1], pair[0]], check=True)
+
+        with ThreadPoolExecutor(max_workers=min(len(SRC), os.cpu_count() or 1)) as pool:
+            list(pool.map(compile_one, zip(SRC, objects)))
+        subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objects, check=True)
     return LIB
 
 

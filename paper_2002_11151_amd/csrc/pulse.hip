@@ -1,0 +1,289 @@
+// Pulse-level weight update with stochastic pulse trains (Sec. IV-C): kernels and xbar_update_pulsed.
+#include "xbar_common.h"
+
+using namespace xbar_detail;
+
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// pulse-level update (Sec. IV-C names the parallel update schemes; this is the one with stochastic
+// pulse trains, whose coincidences multiply): every sample drives rows and columns with random
+// trains of `bl` slots, a value fires with probability min(1, |value| / range) per slot, and a device
+// is pulsed once per slot in which its row and its column both fire, against the sign of x d.
+//   train: slot j of element i fires when uniform word j (Philox block 8 i + j / 4, word j % 4,
+//          stream 3 for rows, 4 for columns) is below rne(p 2^32); bit 31 carries the value's sign
+//   pulse: g += dir dw_min [exp(-v x) up | exp(-v (1 - x)) down, x = (g + 1) / 2]
+//               + gamma sqrt(dw_min) normal(m 32 + j of stream 5 keyed (step << 31) | device),
+//          clamped to [-1, 1]; samples in order, pulses of a sample in order
+// ---------------------------------------------------------------------------------------------
+struct PulseArgs {
+  float* W;
+  const float* X;        // [M][K]
+  const float* D;        // [M][N]
+  uint32_t* rows;        // [mc][K] trains of the current chunk of samples
+  uint32_t* cols;        // [mc][N]
+  double* state;         // [K][N] g between chunks
+  long long* pulses;     // optional [K][N] signed pulse counts
+  int M, K, N, bl, m0, mc, first, last;
+  uint32_t flags;
+  double w_max, x_range, d_range, dw_min, v, sigma;
+  uint64_t seed, step;
+};
+
+__device__ __forceinline__ uint32_t pulse_train(uint32_t k0, uint32_t k1, uint64_t step, uint64_t index, double p, int bl) {
+  const uint64_t threshold = (uint64_t)::rint(clampd(p, 0.0, 1.0) * 4294967296.0);
+  uint32_t bits = 0;
+  for (int j = 0; j < bl; j += 4) {
+    const uint64_t blk = index * 8 + (uint64_t)(j >> 2);
+    uint32_t w[4];
+    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step, (uint32_t)(step >> 32), k0, k1, w);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (j + e < bl && (uint64_t)w[e] < threshold) bits |= 1u << (j + e);
+  }
+  return bits;
+}
+
+// One thread per element of the chunk's inputs, then of its errors.
+__global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
+  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long n_rows = (long long)a.mc * a.K, n_cols = (long long)a.mc * a.N;
+  if (t < n_rows) {
+    const uint64_t index = (uint64_t)a.m0 * a.K + (uint64_t)t;               // m K + k
+    const double x = (double)a.X[index];
+    const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseRows);
+    const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseRows);
+    a.rows[t] = pulse_train(k0, k1, a.step, index, ::fabs(x) / a.x_range, a.bl) | (x < 0.0 ? 0x80000000u : 0u);
+  } else if (t < n_rows + n_cols) {
+    const long long u = t - n_rows;
+    const uint64_t index = (uint64_t)a.m0 * a.N + (uint64_t)u;
+    const double d = (double)a.D[index];
+    const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseCols);
+    const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseCols);
+    a.cols[u] = pulse_train(k0, k1, a.step, index, ::fabs(d) / a.d_range, a.bl) | (d < 0.0 ? 0x80000000u : 0u);
+  }
+}
+
+// One pulse of device `dev` (ordinal `ord` within sample m), upwards when `up`.  The device model is
+// chosen at compile time: nothing that is the same for all lanes is tested inside the per-lane walk.
+template <bool NL, bool NOISE>
+__device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool up, int m, int ord, uint64_t dev) {
+#pragma clang fp contract(off)   // every product and sum rounds on its own
+  double move = a.dw_min;
+  if constexpr (NL) {
+    const double x = clampd(0.5 * (g + 1.0), 0.0, 1.0);
+    move *= up ? ::exp(-a.v * x) : ::exp(-a.v * (1.0 - x));
+  }
+  double next = g + (up ? 1.0 : -1.0) * move;
+  if constexpr (NOISE) {
+    NormalStream rng(a.seed, kStreamPulseNoise, (a.step << 31) | dev);
+    next += a.sigma * rng.get((uint64_t)m * 32 + (uint64_t)ord);
+  }
+  return clampd(next, -1.0, 1.0);
+}
+
+// Block = (16 P) x (16 P) devices, thread = P x P of them with their states in registers; the trains
+// of a stage of samples go through LDS, transposed ([row or column][sample]) so that a lane reads
+// the trains of consecutive samples of its row and of its column with 16-byte loads.
+// A device's pulses are sequential, but devices do not wait for each other sample by sample: all
+// lanes first mark, in step, the samples of the stage in which their row and column share a slot (one
+// bit per sample and device), then every lane works through its own marked samples one pulse per turn,
+// so a wave runs for as long as its busiest device has pulses in the stage, not for the sum over the
+// samples of the busiest device of each.
+template <int P, bool NL, bool NOISE>
+__global__ __launch_bounds__(256) void pulse_apply_kernel(PulseArgs a) {
+  constexpr int TE = 16 * P;              // tile edge
+  constexpr int ST = 4096 / TE;           // samples per stage (a multiple of 16)
+  constexpr int LD = ST + 4;              // words per row or column: 16-byte aligned, spread over the banks
+  __shared__ __align__(16) uint32_t rt[TE * LD];
+  __shared__ __align__(16) uint32_t ct[TE * LD];
+  const int nb = (a.N + TE - 1) / TE;
+  const int kt = (blockIdx.x / nb) * TE, nt = (blockIdx.x % nb) * TE;
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  const int k0 = kt + P * ty, n0 = nt + P * tx;
+  double g[P][P];
+  int cnt[P][P];
+#pragma unroll
+  for (int i = 0; i < P; ++i)
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+      const int k = k0 + i, n = n0 + j;
+      cnt[i][j] = 0;
+      g[i][j] = 0.0;
+      if (k < a.K && n < a.N)
+        g[i][j] = a.first ? (double)a.W[(size_t)k * a.N + n] / a.w_max : a.state[(size_t)k * a.N + n];
+    }
+  for (int s0 = 0; s0 < a.mc; s0 += ST) {
+    const int ns = min(ST, a.mc - s0);
+    const int ns16 = (ns + 15) & ~15;      // whole groups of 16 (ST is a multiple): samples past the end hold no train
+    // the stage's trains: all loads of a thread are issued before the first one is needed
+    constexpr int PER = ST * TE / 256;     // 16 elements of either matrix per thread
+    uint32_t rv[PER], cv[PER];
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int e = threadIdx.x + 256 * u, sm = e / TE, c = e % TE;
+      const bool live = sm < ns;
+      rv[u] = (live && kt + c < a.K) ? a.rows[(size_t)(s0 + sm) * a.K + kt + c] : 0u;
+      cv[u] = (live && nt + c < a.N) ? a.cols[(size_t)(s0 + sm) * a.N + nt + c] : 0u;
+    }
+    __syncthreads();                       // everyone is done with the previous stage
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int e = threadIdx.x + 256 * u, sm = e / TE, c = e % TE;
+      rt[c * LD + sm] = rv[u];
+      ct[c * LD + sm] = cv[u];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < P; ++i)
+#pragma unroll
+      for (int j = 0; j < P; ++j) {
+        const uint64_t dev = (uint64_t)(k0 + i) * a.N + (uint64_t)(n0 + j);
+        const uint32_t* rp = &rt[(P * ty + i) * LD];
+        const uint32_t* cp = &ct[(P * tx + j) * LD];
+        double gs = g[i][j];
+        int moved = 0;
+        // all lanes together: which samples of the stage have a slot in which row and column both fire
+        constexpr int NW = ST / 64;
+        uint64_t live[NW];
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+          live[w] = 0;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int at = 64 * w + 4 * v;
+            if (at < ns16) {
+              const u32x4 r = *reinterpret_cast<const u32x4*>(rp + at);
+              const u32x4 c = *reinterpret_cast<const u32x4*>(cp + at);
+              const uint32_t four = (min(r.x & c.x & 0x7FFFFFFFu, 1u)) | (min(r.y & c.y & 0x7FFFFFFFu, 1u) << 1) |
+                                    (min(r.z & c.z & 0x7FFFFFFFu, 1u) << 2) | (min(r.w & c.w & 0x7FFFFFFFu, 1u) << 3);
+              live[w] |= (uint64_t)four << (4 * v);
+            }
+          }
+        }
+        // every lane for itself, one pulse per turn: its marked samples in order, the pulses of a
+        // sample in order
+        uint32_t q = 0;
+        bool up = false;
+        int m = 0, ord = 0;
+        for (;;) {
+          if (q == 0) {
+            int w = -1;
+            uint64_t word = 0;
+#pragma unroll
+            for (int t = NW - 1; t >= 0; --t)
+              if (live[t]) {
+                w = t;
+                word = live[t];
+              }
+            if (w < 0) break;                          // the stage is done for this device
+            const int e = __builtin_ctzll(word);
+#pragma unroll
+            for (int t = 0; t < NW; ++t)
+              if (t == w) live[t] = word & (word - 1);
+            const int at = 64 * w + e;
+            const uint32_t rw = rp[at], cw = cp[at];
+            q = rw & cw & 0x7FFFFFFFu;
+            up = ((rw ^ cw) >> 31) != 0;               // against the sign of x d
+            m = a.m0 + s0 + at;
+            ord = 0;
+          }
+          q &= q - 1;
+          gs = one_pulse<NL, NOISE>(a, gs, up, m, ord, dev);
+          ++ord;
+          moved += up ? 1 : -1;
+        }
+        g[i][j] = gs;
+        cnt[i][j] += moved;
+      }
+  }
+#pragma unroll
+  for (int i = 0; i < P; ++i)
+#pragma unroll
+    for (int j = 0; j < P; ++j) {
+      const int k = k0 + i, n = n0 + j;
+      if (k < a.K && n < a.N) {
+        const size_t at = (size_t)k * a.N + n;
+        if (a.last) a.W[at] = (float)(a.w_max * g[i][j]);
+        else a.state[at] = g[i][j];
+        if (a.pulses) a.pulses[at] = (a.first ? 0 : a.pulses[at]) + cnt[i][j];
+      }
+    }
+}
+
+struct PulsePlan {
+  int mc;                       // samples per chunk (the trains of one chunk are resident at a time)
+  size_t rows_bytes, cols_bytes, ws_bytes;
+};
+
+PulsePlan plan_pulsed(int M, int K, int N) {
+  PulsePlan p;
+  const long long per_sample = 4ll * ((long long)K + N);
+  long long mc = std::max(64ll, ((64ll << 20) / per_sample) / 64 * 64);
+  p.mc = (int)std::min<long long>(mc, M);
+  p.rows_bytes = align256((size_t)4 * p.mc * K);
+  p.cols_bytes = align256((size_t)4 * p.mc * N);
+  p.ws_bytes = p.rows_bytes + p.cols_bytes + align256((size_t)8 * K * N);
+  return p;
+}
+
+}  // namespace
+
+namespace xbar_detail {
+size_t pulsed_workspace_bytes(int M, int K, int N) { return plan_pulsed(M, K, N).ws_bytes; }
+}  // namespace xbar_detail
+
+extern "C" {
+
+int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
+                       float x_range, float d_range, int bl, float dw_min, uint64_t step, long long* pulses, void* ws,
+                       size_t ws_bytes, void* hip_stream) {
+  int rc = xbar_config_validate(cfg);
+  if (rc) return rc;
+  if ((rc = check_shape(M, K, N))) return rc;
+  if (!aligned16(W) || !aligned16(X) || !aligned16(dY) || !aligned16(ws)) return XBAR_EALIGN;
+  if (pulses && (reinterpret_cast<uintptr_t>(pulses) & 7u)) return XBAR_EALIGN;
+  if (!finite_pos(w_max) || !finite_pos(x_range) || !finite_pos(d_range) || !finite_pos(dw_min)) return XBAR_EINVAL;
+  if (bl < 1 || bl > 31 || step >= (1ull << 33)) return XBAR_EINVAL;
+  const PulsePlan p = plan_pulsed(M, K, N);
+  if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
+  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
+  PulseArgs a;
+  a.W = W; a.X = X; a.D = dY;
+  a.rows = reinterpret_cast<uint32_t*>(ws);
+  a.cols = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(ws) + p.rows_bytes);
+  a.state = reinterpret_cast<double*>(reinterpret_cast<char*>(ws) + p.rows_bytes + p.cols_bytes);
+  a.pulses = pulses;
+  a.M = M; a.K = K; a.N = N; a.bl = bl;
+  a.flags = cfg->flags;
+  a.w_max = (double)w_max; a.x_range = (double)x_range; a.d_range = (double)d_range; a.dw_min = (double)dw_min;
+  a.v = (double)cfg->upd_nl_v;
+  a.sigma = (double)cfg->upd_noise_gamma * std::sqrt((double)dw_min);
+  a.seed = cfg->seed; a.step = step;
+  // 4 x 4 devices per thread when that still fills the chip, else one device per thread
+  const bool patch4 = (long long)cdiv(K, 64) * cdiv(N, 64) >= 512;
+  const int edge = patch4 ? 64 : 16;
+  const unsigned tiles = (unsigned)(cdiv(K, edge) * cdiv(N, edge));
+  for (int m0 = 0; m0 < M; m0 += p.mc) {
+    a.m0 = m0;
+    a.mc = std::min(p.mc, M - m0);
+    a.first = m0 == 0;
+    a.last = m0 + a.mc >= M;
+    const long long elems = (long long)a.mc * ((long long)K + N);
+    hipLaunchKernelGGL(pulse_trains_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+    const bool nl = (cfg->flags & XBAR_NI_UPD_NL) != 0, noise = (cfg->flags & XBAR_NI_UPD_NOISE) != 0;
+    void (*k)(PulseArgs);
+    if (patch4)
+      k = nl ? (noise ? pulse_apply_kernel<4, true, true> : pulse_apply_kernel<4, true, false>)
+             : (noise ? pulse_apply_kernel<4, false, true> : pulse_apply_kernel<4, false, false>);
+    else
+      k = nl ? (noise ? pulse_apply_kernel<1, true, true> : pulse_apply_kernel<1, true, false>)
+             : (noise ? pulse_apply_kernel<1, false, true> : pulse_apply_kernel<1, false, false>);
+    hipLaunchKernelGGL(k, dim3(tiles), dim3(256), 0, st, a);
+    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+  }
+  return XBAR_OK;
+}
+
+}  // extern "C"

@@ -21,136 +21,11 @@
 // read as fp16, the subnormal number digit * 2^(shift-24).  The matrix cores of gfx950 take fp16
 // subnormals exactly, so one AND with a digit mask turns the raw magnitudes into the A operand of
 // any streaming cycle; the power of two is folded into the ADC gain.
-#include <hip/hip_runtime.h>
+#include "xbar_common.h"
 
-#include <algorithm>
-#include <cmath>
-#include <cstdint>
-#include <cstring>
-
-#include "xbar.h"
+using namespace xbar_detail;
 
 namespace {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float float16v __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr uint32_t kMagicBits = 0x4B400000u;  // bits of 1.5 * 2^23: adding it rounds to an integer (RNE)
-constexpr float kMagic = 12582912.0f;
-constexpr int kStreamVariation = 1, kStreamWrite = 2;
-constexpr int kStreamPulseRows = 3, kStreamPulseCols = 4, kStreamPulseNoise = 5;
-constexpr bool kBarrierPerMfma = false;   // scheduling fence after every MFMA (true) or every fragment (false)
-
-// ---------------------------------------------------------------------------------------------
-// host-side geometry shared by the entry points
-// ---------------------------------------------------------------------------------------------
-struct Derived {
-  int S_w, S_in, terms, q_adc;
-  int npol;            // converters per crossbar column: 1 (pair read differentially) or 2 (one per array)
-  uint32_t array_ni;
-};
-
-inline Derived derive(const xbar_config* c) {
-  Derived d;
-  d.S_w = c->weight_bits / c->slice_bits;
-  d.S_in = c->input_bits / c->stream_bits;
-  d.array_ni = c->flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE | XBAR_NI_WIRE_AAM2);
-  d.npol = (c->flags & XBAR_ADC_PER_ARRAY) ? 2 : 1;
-  // one array alone carries the off-state conductance of every device: never whole device levels
-  d.terms = (d.array_ni || d.npol == 2) ? 2 : 1;
-  // signed converter on the difference of the pair, or unsigned converter on one array's current
-  d.q_adc = d.npol == 2 ? (1 << c->adc_bits) - 1 : (1 << (c->adc_bits - 1)) - 1;
-  return d;
-}
-
-inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-inline int cdiv(int a, int b) { return (a + b - 1) / b; }
-
-// Plane buffer: forward copy then backward copy.  One copy is
-// [array][tile][output patch of 32][slice][term][k-step of 16][64 lanes][8 halves]; there is one
-// "array" (the difference of the pair) unless every array has a converter of its own.
-struct PlaneGeom {
-  int tile, ks, T, OP;          // contraction tile length, k-steps per tile, tiles, output patches
-  size_t pol_bytes, bytes;      // one array, all arrays
-};
-
-// Scratch of the all-paths wire model, kept behind the two plane copies.
-inline size_t wire_scratch_bytes(const xbar_config* c, const Derived& d, int K, int N) {
-  return (c->flags & XBAR_NI_WIRE_AAM2) ? align256((size_t)16 * d.S_w * K * N) + align256((size_t)4 * K * N) : 0;
-}
-
-// Weight sums for the digital correction of offset-binary inputs, kept behind the wire scratch:
-// colsum[N] then rowsum[K], 64-bit.
-inline size_t weight_sums_bytes(const xbar_config* c, int K, int N) {
-  return (c->flags & XBAR_INPUT_OFFSET) ? align256((size_t)8 * ((size_t)K + N)) : 0;
-}
-
-inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N, bool transposed) {
-  PlaneGeom g;
-  g.tile = transposed ? c->xbar_cols : c->xbar_rows;
-  g.ks = g.tile / 16;
-  g.T = cdiv(transposed ? N : K, g.tile);
-  g.OP = cdiv(transposed ? K : N, 32);
-  g.pol_bytes = (size_t)g.T * g.OP * d.S_w * d.terms * g.ks * 1024;
-  g.bytes = g.pol_bytes * d.npol;
-  return g;
-}
-
-inline size_t weight_sums_offset(const xbar_config* c, const Derived& d, int K, int N) {
-  return align256(plane_geom(c, d, K, N, false).bytes) + align256(plane_geom(c, d, K, N, true).bytes) +
-         wire_scratch_bytes(c, d, K, N);
-}
-
-// ---------------------------------------------------------------------------------------------
-// device helpers
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
-                                              uint32_t k1, uint32_t out[4]) {
-#pragma unroll
-  for (int r = 0; r < 10; ++r) {
-    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
-    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
-    const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
-    c0 = n0; c1 = l1; c2 = n2; c3 = l0;
-    k0 += 0x9E3779B9u;
-    k1 += 0xBB67AE85u;
-  }
-  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
-
-// Standard normal number i of (seed, stream, step): four consecutive i share one Philox block,
-// words (0,1) -> numbers 0,1 (cosine, sine branch of Box-Muller), words (2,3) -> numbers 2,3.
-struct NormalStream {
-  uint32_t k0, k1, s0, s1;
-  uint64_t cached_blk;
-  uint32_t w[4];
-  __device__ NormalStream(uint64_t seed, uint32_t stream, uint64_t step) {
-    k0 = (uint32_t)seed ^ (0x9E3779B9u * stream);
-    k1 = (uint32_t)(seed >> 32) ^ (0xBB67AE85u * stream);
-    s0 = (uint32_t)step;
-    s1 = (uint32_t)(step >> 32);
-    cached_blk = ~0ull;
-  }
-  __device__ double get(uint64_t i) {
-    const uint64_t blk = i >> 2;
-    if (blk != cached_blk) {
-      philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), s0, s1, k0, k1, w);
-      cached_blk = blk;
-    }
-    const bool second = (i & 2u) != 0;
-    const double u1 = ((double)(second ? w[2] : w[0]) + 0.5) * (1.0 / 4294967296.0);
-    const double u2 = ((double)(second ? w[3] : w[1]) + 0.5) * (1.0 / 4294967296.0);
-    const double r = ::sqrt(-2.0 * ::log(u1));
-    // angle 2 pi u2: the half-turn form reduces the argument exactly and costs a fraction of sin / cos
-    double sn, cs;
-    ::sincospi(2.0 * u2, &sn, &cs);
-    return (i & 1u) ? r * sn : r * cs;
-  }
-};
-
-__device__ __forceinline__ double clampd(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
 // ---------------------------------------------------------------------------------------------
 // generator: weights -> operand planes (Sec. IV-A, IV-D)
@@ -257,194 +132,6 @@ __global__ __launch_bounds__(256) void tile_planes_kernel(TileArgs a) {
   if (a.terms == 2) reinterpret_cast<u32x4*>(a.planes)[chunk + (size_t)a.ks * 64] = lo.v;
 }
 
-// ---------------------------------------------------------------------------------------------
-// wire model with all first-order paths (Sec. IV-D: more paths than the shortest one)
-//   a_ij = sum_j' G_ij' (r_source + (min(j,j') + 1) r_row)      drops on the row wire
-//   b_ij = sum_i' G_i'j ((R - max(i,i')) r_col + r_sense)       rises on the column wire
-//   G_ni = G / (1 + a + b),   plane = (G_ni+ - G_ni-) / dG
-// Both sums split into a prefix and a suffix part, so one scan along the row and two walks along
-// the column replace the O(R + C) sum per device.  Scratch: A[S_w][2][K][N] (double) and the quantised
-// weights q[K][N]; the row kernel writes a into A, the column kernel adds b and leaves the plane
-// value in the slot of array 0 (with one converter per array: each array's value in its own slot).
-// ---------------------------------------------------------------------------------------------
-struct WireArgs {
-  const float* W;
-  double* A;         // [S_w][2][K][N]
-  int32_t* q;        // [K][N] signed quantised weights
-  int K, N, R, C, S_w, slice_bits, weight_bits, tiles_c;
-  uint32_t flags;
-  double g_min, dg, var_sigma, r_row, r_col, r_source, r_sense;
-  float w_max;
-  uint64_t seed, step;
-};
-
-__global__ __launch_bounds__(256) void wire_quantize_kernel(WireArgs a) {
-  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= (size_t)a.K * a.N) return;
-  const double qw = (double)((1u << a.weight_bits) - 1);
-  a.q[t] = (int32_t)::rint(clampd((double)a.W[t] / (double)a.w_max, -1.0, 1.0) * qw);
-}
-
-// Conductances of the device pair (slice s) of weight (k, n) before the wire model.
-__device__ __forceinline__ void wire_device_pair(const WireArgs& a, NormalStream& rng, int q, int k, int n, int s,
-                                                 double g[2]) {
-  const int digit = (int)(((uint32_t)::abs(q) >> (a.slice_bits * s)) & ((1u << a.slice_bits) - 1));
-  g[0] = a.g_min + (q > 0 ? digit * a.dg : 0.0);
-  g[1] = a.g_min + (q < 0 ? digit * a.dg : 0.0);
-  if (a.flags & XBAR_NI_VARIATION) {
-    const uint64_t dev = (((uint64_t)k * (uint64_t)a.N + (uint64_t)n) * (uint64_t)a.S_w + (uint64_t)s) * 2;
-    g[0] *= 1.0 + a.var_sigma * rng.get(dev);
-    g[1] *= 1.0 + a.var_sigma * rng.get(dev + 1);
-  }
-}
-
-__device__ __forceinline__ double wave_inclusive_scan(double x, int lane) {
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const double y = __shfl_up(x, d, 64);
-    if (lane >= d) x += y;
-  }
-  return x;
-}
-
-// grid (tiles x 4 quarters of the tile rows, S_w); a wave scans one tile row at a time (both arrays),
-// lane l holds the ceil(C / 64) consecutive columns that start at l ceil(C / 64).
-__global__ __launch_bounds__(256) void wire_rows_kernel(WireArgs a) {
-  const int tile = blockIdx.x >> 2, quarter = blockIdx.x & 3;
-  const int tr = tile / a.tiles_c, tc = tile % a.tiles_c;
-  const int s = blockIdx.y;
-  const int k0 = tr * a.R, n0 = tc * a.C;
-  const int rows = min(a.R, a.K - k0), cols = min(a.C, a.N - n0);
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int cpl = (a.C + 63) >> 6;
-  const int i_end = min(rows, (quarter + 1) * (a.R / 4));
-  const size_t pol_stride = (size_t)a.K * a.N;
-  NormalStream rng(a.seed, kStreamVariation, a.step);
-  for (int i = quarter * (a.R / 4) + wave; i < i_end; i += 4) {
-    double l0[4][2], l1[4][2];                       // inclusive prefixes inside the lane
-    double run0[2] = {0.0, 0.0}, run1[2] = {0.0, 0.0};
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (u >= cpl) break;
-      const int j = lane * cpl + u;
-      double g[2] = {0.0, 0.0};
-      if (j < cols) wire_device_pair(a, rng, a.q[(size_t)(k0 + i) * a.N + n0 + j], k0 + i, n0 + j, s, g);
-#pragma unroll
-      for (int pol = 0; pol < 2; ++pol) {
-        run0[pol] += g[pol];                         // sum_{j' <= j} G
-        run1[pol] += (double)(j + 1) * g[pol];       // sum_{j' <= j} (j' + 1) G
-        l0[u][pol] = run0[pol];
-        l1[u][pol] = run1[pol];
-      }
-    }
-    double before0[2], before1[2], total[2];         // sums over the lanes to the left, and the row total
-#pragma unroll
-    for (int pol = 0; pol < 2; ++pol) {
-      const double inc0 = wave_inclusive_scan(run0[pol], lane);
-      const double inc1 = wave_inclusive_scan(run1[pol], lane);
-      before0[pol] = inc0 - run0[pol];
-      before1[pol] = inc1 - run1[pol];
-      total[pol] = __shfl(inc0, 63, 64);
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (u >= cpl) break;
-      const int j = lane * cpl + u;
-      if (j < cols) {
-        const size_t at = ((size_t)(2 * s) * a.K + k0 + i) * a.N + n0 + j;
-#pragma unroll
-        for (int pol = 0; pol < 2; ++pol) {
-          const double p0 = before0[pol] + l0[u][pol], p1 = before1[pol] + l1[u][pol];
-          a.A[at + pol * pol_stride] = a.r_source * total[pol] + a.r_row * (p1 + (double)(j + 1) * (total[pol] - p0));
-        }
-      }
-    }
-  }
-}
-
-// grid (tiles x strips of 64 columns, S_w); thread = (quarter of the tile rows, column).  First walk:
-// per-quarter totals; after the exchange a second walk knows, at every row, the sums over all devices
-// above and below and finishes the plane value.
-__global__ __launch_bounds__(256) void wire_cols_kernel(WireArgs a) {
-  __shared__ double tot[2][2][4][64];              // [sum of G | sum of (R - i) G][array][quarter][column]
-  const int strips = (a.C + 63) / 64;
-  const int tile = blockIdx.x / strips, strip = blockIdx.x % strips;
-  const int tr = tile / a.tiles_c, tc = tile % a.tiles_c;
-  const int s = blockIdx.y;
-  const int k0 = tr * a.R, n0 = tc * a.C;
-  const int rows = min(a.R, a.K - k0), cols = min(a.C, a.N - n0);
-  const int seg = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int j = strip * 64 + lane;
-  const bool active = j < cols;
-  const int i_begin = seg * (a.R / 4), i_end = min(rows, i_begin + a.R / 4);
-  NormalStream rng(a.seed, kStreamVariation, a.step);
-  double t0[2] = {0.0, 0.0}, t1[2] = {0.0, 0.0};
-  if (active)
-    for (int i = i_begin; i < i_end; ++i) {
-      double g[2];
-      wire_device_pair(a, rng, a.q[(size_t)(k0 + i) * a.N + n0 + j], k0 + i, n0 + j, s, g);
-#pragma unroll
-      for (int pol = 0; pol < 2; ++pol) {
-        t0[pol] += g[pol];
-        t1[pol] += (double)(a.R - i) * g[pol];
-      }
-    }
-#pragma unroll
-  for (int pol = 0; pol < 2; ++pol) {
-    tot[0][pol][seg][lane] = t0[pol];
-    tot[1][pol][seg][lane] = t1[pol];
-  }
-  __syncthreads();
-  if (!active) return;
-  double above[2], below[2], total[2];
-#pragma unroll
-  for (int pol = 0; pol < 2; ++pol) {
-    above[pol] = 0.0;                                // sum_{i' <= i} G, starts at the quarters above
-    below[pol] = t1[pol];                            // sum_{i' > i} (R - i') G, starts with this and later quarters
-    total[pol] = 0.0;
-    for (int g4 = 0; g4 < 4; ++g4) {
-      const double x0 = tot[0][pol][g4][lane];
-      total[pol] += x0;
-      if (g4 < seg) above[pol] += x0;
-      if (g4 > seg) below[pol] += tot[1][pol][g4][lane];
-    }
-  }
-  const size_t pol_stride = (size_t)a.K * a.N;
-  for (int ib = i_begin; ib < i_end; ib += 4) {      // quarter lengths are multiples of 4
-    int q[4];
-    double wa[4][2];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {                    // loads first: they do not wait for the stores below
-      const int i = min(ib + u, i_end - 1);
-      const size_t at = ((size_t)(2 * s) * a.K + k0 + i) * a.N + n0 + j;
-      q[u] = a.q[(size_t)(k0 + i) * a.N + n0 + j];
-      wa[u][0] = a.A[at];
-      wa[u][1] = a.A[at + pol_stride];
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int i = ib + u;
-      if (i < i_end) {
-        double g[2], e[2];
-        wire_device_pair(a, rng, q[u], k0 + i, n0 + j, s, g);
-#pragma unroll
-        for (int pol = 0; pol < 2; ++pol) {
-          above[pol] += g[pol];
-          below[pol] -= (double)(a.R - i) * g[pol];
-          const double b = a.r_col * ((double)(a.R - i) * above[pol] + below[pol]) + a.r_sense * total[pol];
-          e[pol] = g[pol] / (1.0 + wa[u][pol] + b);
-        }
-        const size_t at = ((size_t)(2 * s) * a.K + k0 + i) * a.N + n0 + j;
-        if (a.flags & XBAR_ADC_PER_ARRAY) {            // each array is read on its own
-          a.A[at] = e[0] / a.dg;
-          a.A[at + pol_stride] = e[1] / a.dg;
-        } else {
-          a.A[at] = (e[0] - e[1]) / a.dg;
-        }
-      }
-    }
-  }
-}
 
 // ---------------------------------------------------------------------------------------------
 // sums of the quantised weights over rows and columns: what the digital correction of offset-binary
@@ -1304,645 +991,7 @@ __global__ __launch_bounds__(256) void update_write_kernel(WriteArgs a) {
   a.W[i] = (float)(a.w_max * g_new);
 }
 
-// ---------------------------------------------------------------------------------------------
-// pulse-level update (Sec. IV-C names the parallel update schemes; this is the one with stochastic
-// pulse trains, whose coincidences multiply): every sample drives rows and columns with random
-// trains of `bl` slots, a value fires with probability min(1, |value| / range) per slot, and a device
-// is pulsed once per slot in which its row and its column both fire, against the sign of x d.
-//   train: slot j of element i fires when uniform word j (Philox block 8 i + j / 4, word j % 4,
-//          stream 3 for rows, 4 for columns) is below rne(p 2^32); bit 31 carries the value's sign
-//   pulse: g += dir dw_min [exp(-v x) up | exp(-v (1 - x)) down, x = (g + 1) / 2]
-//               + gamma sqrt(dw_min) normal(m 32 + j of stream 5 keyed (step << 31) | device),
-//          clamped to [-1, 1]; samples in order, pulses of a sample in order
-// ---------------------------------------------------------------------------------------------
-struct PulseArgs {
-  float* W;
-  const float* X;        // [M][K]
-  const float* D;        // [M][N]
-  uint32_t* rows;        // [mc][K] trains of the current chunk of samples
-  uint32_t* cols;        // [mc][N]
-  double* state;         // [K][N] g between chunks
-  long long* pulses;     // optional [K][N] signed pulse counts
-  int M, K, N, bl, m0, mc, first, last;
-  uint32_t flags;
-  double w_max, x_range, d_range, dw_min, v, sigma;
-  uint64_t seed, step;
-};
 
-__device__ __forceinline__ uint32_t pulse_train(uint32_t k0, uint32_t k1, uint64_t step, uint64_t index, double p, int bl) {
-  const uint64_t threshold = (uint64_t)::rint(clampd(p, 0.0, 1.0) * 4294967296.0);
-  uint32_t bits = 0;
-  for (int j = 0; j < bl; j += 4) {
-    const uint64_t blk = index * 8 + (uint64_t)(j >> 2);
-    uint32_t w[4];
-    philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), (uint32_t)step, (uint32_t)(step >> 32), k0, k1, w);
-#pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (j + e < bl && (uint64_t)w[e] < threshold) bits |= 1u << (j + e);
-  }
-  return bits;
-}
-
-// One thread per element of the chunk's inputs, then of its errors.
-__global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
-  const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long n_rows = (long long)a.mc * a.K, n_cols = (long long)a.mc * a.N;
-  if (t < n_rows) {
-    const uint64_t index = (uint64_t)a.m0 * a.K + (uint64_t)t;               // m K + k
-    const double x = (double)a.X[index];
-    const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseRows);
-    const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseRows);
-    a.rows[t] = pulse_train(k0, k1, a.step, index, ::fabs(x) / a.x_range, a.bl) | (x < 0.0 ? 0x80000000u : 0u);
-  } else if (t < n_rows + n_cols) {
-    const long long u = t - n_rows;
-    const uint64_t index = (uint64_t)a.m0 * a.N + (uint64_t)u;
-    const double d = (double)a.D[index];
-    const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseCols);
-    const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseCols);
-    a.cols[u] = pulse_train(k0, k1, a.step, index, ::fabs(d) / a.d_range, a.bl) | (d < 0.0 ? 0x80000000u : 0u);
-  }
-}
-
-// One pulse of device `dev` (ordinal `ord` within sample m), upwards when `up`.  The device model is
-// chosen at compile time: nothing that is the same for all lanes is tested inside the per-lane walk.
-template <bool NL, bool NOISE>
-__device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool up, int m, int ord, uint64_t dev) {
-#pragma clang fp contract(off)   // every product and sum rounds on its own
-  double move = a.dw_min;
-  if constexpr (NL) {
-    const double x = clampd(0.5 * (g + 1.0), 0.0, 1.0);
-    move *= up ? ::exp(-a.v * x) : ::exp(-a.v * (1.0 - x));
-  }
-  double next = g + (up ? 1.0 : -1.0) * move;
-  if constexpr (NOISE) {
-    NormalStream rng(a.seed, kStreamPulseNoise, (a.step << 31) | dev);
-    next += a.sigma * rng.get((uint64_t)m * 32 + (uint64_t)ord);
-  }
-  return clampd(next, -1.0, 1.0);
-}
-
-// Block = (16 P) x (16 P) devices, thread = P x P of them with their states in registers; the trains
-// of a stage of samples go through LDS, transposed ([row or column][sample]) so that a lane reads
-// the trains of consecutive samples of its row and of its column with 16-byte loads.
-// A device's pulses are sequential, but devices do not wait for each other sample by sample: all
-// lanes first mark, in step, the samples of the stage in which their row and column share a slot (one
-// bit per sample and device), then every lane works through its own marked samples one pulse per turn,
-// so a wave runs for as long as its busiest device has pulses in the stage, not for the sum over the
-// samples of the busiest device of each.
-template <int P, bool NL, bool NOISE>
-__global__ __launch_bounds__(256) void pulse_apply_kernel(PulseArgs a) {
-  constexpr int TE = 16 * P;              // tile edge
-  constexpr int ST = 4096 / TE;           // samples per stage (a multiple of 16)
-  constexpr int LD = ST + 4;              // words per row or column: 16-byte aligned, spread over the banks
-  __shared__ __align__(16) uint32_t rt[TE * LD];
-  __shared__ __align__(16) uint32_t ct[TE * LD];
-  const int nb = (a.N + TE - 1) / TE;
-  const int kt = (blockIdx.x / nb) * TE, nt = (blockIdx.x % nb) * TE;
-  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
-  const int k0 = kt + P * ty, n0 = nt + P * tx;
-  double g[P][P];
-  int cnt[P][P];
-#pragma unroll
-  for (int i = 0; i < P; ++i)
-#pragma unroll
-    for (int j = 0; j < P; ++j) {
-      const int k = k0 + i, n = n0 + j;
-      cnt[i][j] = 0;
-      g[i][j] = 0.0;
-      if (k < a.K && n < a.N)
-        g[i][j] = a.first ? (double)a.W[(size_t)k * a.N + n] / a.w_max : a.state[(size_t)k * a.N + n];
-    }
-  for (int s0 = 0; s0 < a.mc; s0 += ST) {
-    const int ns = min(ST, a.mc - s0);
-    const int ns16 = (ns + 15) & ~15;      // whole groups of 16 (ST is a multiple): samples past the end hold no train
-    // the stage's trains: all loads of a thread are issued before the first one is needed
-    constexpr int PER = ST * TE / 256;     // 16 elements of either matrix per thread
-    uint32_t rv[PER], cv[PER];
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      const int e = threadIdx.x + 256 * u, sm = e / TE, c = e % TE;
-      const bool live = sm < ns;
-      rv[u] = (live && kt + c < a.K) ? a.rows[(size_t)(s0 + sm) * a.K + kt + c] : 0u;
-      cv[u] = (live && nt + c < a.N) ? a.cols[(size_t)(s0 + sm) * a.N + nt + c] : 0u;
-    }
-    __syncthreads();                       // everyone is done with the previous stage
-#pragma unroll
-    for (int u = 0; u < PER; ++u) {
-      const int e = threadIdx.x + 256 * u, sm = e / TE, c = e % TE;
-      rt[c * LD + sm] = rv[u];
-      ct[c * LD + sm] = cv[u];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < P; ++i)
-#pragma unroll
-      for (int j = 0; j < P; ++j) {
-        const uint64_t dev = (uint64_t)(k0 + i) * a.N + (uint64_t)(n0 + j);
-        const uint32_t* rp = &rt[(P * ty + i) * LD];
-        const uint32_t* cp = &ct[(P * tx + j) * LD];
-        double gs = g[i][j];
-        int moved = 0;
-        // all lanes together: which samples of the stage have a slot in which row and column both fire
-        constexpr int NW = ST / 64;
-        uint64_t live[NW];
-#pragma unroll
-        for (int w = 0; w < NW; ++w) {
-          live[w] = 0;
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int at = 64 * w + 4 * v;
-            if (at < ns16) {
-              const u32x4 r = *reinterpret_cast<const u32x4*>(rp + at);
-              const u32x4 c = *reinterpret_cast<const u32x4*>(cp + at);
-              const uint32_t four = (min(r.x & c.x & 0x7FFFFFFFu, 1u)) | (min(r.y & c.y & 0x7FFFFFFFu, 1u) << 1) |
-                                    (min(r.z & c.z & 0x7FFFFFFFu, 1u) << 2) | (min(r.w & c.w & 0x7FFFFFFFu, 1u) << 3);
-              live[w] |= (uint64_t)four << (4 * v);
-            }
-          }
-        }
-        // every lane for itself, one pulse per turn: its marked samples in order, the pulses of a
-        // sample in order
-        uint32_t q = 0;
-        bool up = false;
-        int m = 0, ord = 0;
-        for (;;) {
-          if (q == 0) {
-            int w = -1;
-            uint64_t word = 0;
-#pragma unroll
-            for (int t = NW - 1; t >= 0; --t)
-              if (live[t]) {
-                w = t;
-                word = live[t];
-              }
-            if (w < 0) break;                          // the stage is done for this device
-            const int e = __builtin_ctzll(word);
-#pragma unroll
-            for (int t = 0; t < NW; ++t)
-              if (t == w) live[t] = word & (word - 1);
-            const int at = 64 * w + e;
-            const uint32_t rw = rp[at], cw = cp[at];
-            q = rw & cw & 0x7FFFFFFFu;
-            up = ((rw ^ cw) >> 31) != 0;               // against the sign of x d
-            m = a.m0 + s0 + at;
-            ord = 0;
-          }
-          q &= q - 1;
-          gs = one_pulse<NL, NOISE>(a, gs, up, m, ord, dev);
-          ++ord;
-          moved += up ? 1 : -1;
-        }
-        g[i][j] = gs;
-        cnt[i][j] += moved;
-      }
-  }
-#pragma unroll
-  for (int i = 0; i < P; ++i)
-#pragma unroll
-    for (int j = 0; j < P; ++j) {
-      const int k = k0 + i, n = n0 + j;
-      if (k < a.K && n < a.N) {
-        const size_t at = (size_t)k * a.N + n;
-        if (a.last) a.W[at] = (float)(a.w_max * g[i][j]);
-        else a.state[at] = g[i][j];
-        if (a.pulses) a.pulses[at] = (a.first ? 0 : a.pulses[at]) + cnt[i][j];
-      }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// circuit-level crossbar model (Sec. IV-A: solve Ohm's and Kirchhoff's laws per crossbar instance;
-// Sec. IV-D: the distortion profile D = (G_ideal - G_nonideal) / G_ideal that is stored and reused)
-//
-// Per crossbar, slice and array, with x_ij the device currents for the row voltages v:
-//   x_ij / G_ij + sum_j' x_ij' wr(j,j') + sum_i' x_i'j wc(i,i') = v_i          (D + L) x = P v
-//   wr(j,j') = r_source + (min(j,j') + 1) r_row,   wc(i,i') = (R - max(i,i')) r_col + r_sense
-// L is the resistance matrix of the wires: symmetric, positive semidefinite, and applied in O(R C)
-// by row and column prefix sums.  With x = s y, s = sqrt(G), the system (I + S L S) y = s v is
-// symmetric positive definite with all eigenvalues >= 1 and a small condition number; conjugate
-// gradients solve it for one unit row voltage at a time, and row i of the non-ideal conductance
-// matrix is the column sums of x.  Devices that do not exist have s = 0 and drop out.
-// ---------------------------------------------------------------------------------------------
-struct FcmArgs {
-  const float* W;
-  float* profile;        // [S_w][2][K][N]
-  double* scratch;       // per resident block: s, y, r, p, q of R C doubles each
-  int K, N, R, C, S_w, slice_bits, weight_bits, tiles_c;
-  int groups, rhs_per_group, n_items, max_iter;
-  uint32_t flags;
-  double g_min, dg, var_sigma, r_row, r_col, r_source, r_sense, tol2;
-  float w_max;
-  uint64_t seed, step;
-};
-
-// Sum over the 256 threads of the block, returned to all of them; fixed order.
-__device__ __forceinline__ double block_sum(double v, double* red) {
-#pragma unroll
-  for (int d = 32; d; d >>= 1) v += __shfl_xor(v, d, 64);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  return (red[0] + red[1]) + (red[2] + red[3]);
-}
-
-__global__ __launch_bounds__(256) void fcm_kernel(FcmArgs a) {
-  __shared__ double red[4];
-  __shared__ double tot[2][4][64];                  // column pass: quarter totals per column of a strip
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int R = a.R, C = a.C;
-  const int cpl = (C + 63) >> 6, strips = (C + 63) >> 6;
-  const size_t rc = (size_t)R * C;
-  double* sg = a.scratch + (size_t)blockIdx.x * 5 * rc;
-  double* y = sg + rc;
-  double* r = y + rc;
-  double* p = r + rc;
-  double* q = p + rc;
-  NormalStream rng(a.seed, kStreamVariation, a.step);
-
-  for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
-    const int group = item % a.groups;
-    const int t1 = item / a.groups;
-    const int pol = t1 & 1;
-    const int s = (t1 >> 1) % a.S_w;
-    const int tile = (t1 >> 1) / a.S_w;
-    const int k0 = (tile / a.tiles_c) * R, n0 = (tile % a.tiles_c) * C;
-    const int rows = min(R, a.K - k0), cols = min(C, a.N - n0);
-    const int i_begin = wave * (R / 4), i_end = min(rows, i_begin + R / 4);   // this wave's quarter (column pass)
-
-    __syncthreads();                                 // the previous item is done with the scratch
-    for (int i = wave; i < rows; i += 4)
-      for (int j = lane; j < cols; j += 64) {
-        const double qw = (double)((1u << a.weight_bits) - 1);
-        const double wq = ::rint(clampd((double)a.W[(size_t)(k0 + i) * a.N + n0 + j] / (double)a.w_max, -1.0, 1.0) * qw);
-        const int digit = (int)(((uint32_t)::fabs(wq) >> (a.slice_bits * s)) & ((1u << a.slice_bits) - 1));
-        const bool mine = pol == 0 ? wq > 0.0 : wq < 0.0;
-        double g = a.g_min + (mine ? digit * a.dg : 0.0);
-        if (a.flags & XBAR_NI_VARIATION) {
-          const uint64_t dev =
-              (((uint64_t)(k0 + i) * (uint64_t)a.N + (uint64_t)(n0 + j)) * (uint64_t)a.S_w + (uint64_t)s) * 2 + pol;
-          g *= 1.0 + a.var_sigma * rng.get(dev);
-        }
-        sg[(size_t)i * C + j] = ::sqrt(::fmax(g, 0.0));
-      }
-    __syncthreads();
-
-    const int rhs_end = min(rows, (group + 1) * a.rhs_per_group);
-    for (int rhs = group * a.rhs_per_group; rhs < rhs_end; ++rhs) {
-      // y = 0, r = b = s on the driven row, p = 0 (the first direction is r)
-      double part = 0.0;
-      for (int i = wave; i < rows; i += 4)
-        for (int j = lane; j < cols; j += 64) {
-          const size_t at = (size_t)i * C + j;
-          const double b = i == rhs ? sg[at] : 0.0;
-          y[at] = 0.0;
-          r[at] = b;
-          p[at] = 0.0;
-          part += b * b;
-        }
-      double rr = block_sum(part, red);              // also orders the stores above before the reads below
-      const double stop = a.tol2 * rr;
-      double beta = 0.0;
-      for (int it = 0; it < a.max_iter && rr > stop; ++it) {
-        // rows: p <- r + beta p;  q <- p + s Lr(s p)
-        for (int i = wave; i < rows; i += 4) {
-          const size_t base = (size_t)i * C;
-          double pv[4], sv[4], l0[4], l1[4];
-          double run0 = 0.0, run1 = 0.0;
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            if (u >= cpl) break;
-            const int j = lane * cpl + u;
-            pv[u] = sv[u] = 0.0;
-            if (j < cols) {
-              pv[u] = r[base + j] + beta * p[base + j];
-              sv[u] = sg[base + j];
-              p[base + j] = pv[u];
-            }
-            const double cur = sv[u] * pv[u];
-            run0 += cur;
-            run1 += (double)(j + 1) * cur;
-            l0[u] = run0;
-            l1[u] = run1;
-          }
-          const double inc0 = wave_inclusive_scan(run0, lane), inc1 = wave_inclusive_scan(run1, lane);
-          const double total = __shfl(inc0, 63, 64);
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            if (u >= cpl) break;
-            const int j = lane * cpl + u;
-            if (j < cols) {
-              const double p0 = inc0 - run0 + l0[u], p1 = inc1 - run1 + l1[u];
-              const double lr = a.r_source * total + a.r_row * (p1 + (double)(j + 1) * (total - p0));
-              q[base + j] = pv[u] + sv[u] * lr;
-            }
-          }
-        }
-        __syncthreads();
-        // columns: q <- q + s Lc(s p);  p.q
-        double pq = 0.0;
-        for (int strip = 0; strip < strips; ++strip) {
-          const int j = strip * 64 + lane;
-          const bool active = j < cols;
-          double t0 = 0.0, t1s = 0.0;
-          if (active)
-            for (int i = i_begin; i < i_end; ++i) {
-              const size_t at = (size_t)i * C + j;
-              const double cur = sg[at] * p[at];
-              t0 += cur;
-              t1s += (double)(R - i) * cur;
-            }
-          tot[0][wave][lane] = t0;
-          tot[1][wave][lane] = t1s;
-          __syncthreads();
-          if (active) {
-            double above = 0.0, below = t1s, total = 0.0;
-#pragma unroll
-            for (int g4 = 0; g4 < 4; ++g4) {
-              const double x0 = tot[0][g4][lane];
-              total += x0;
-              if (g4 < wave) above += x0;
-              if (g4 > wave) below += tot[1][g4][lane];
-            }
-            for (int ib = i_begin; ib < i_end; ib += 4) {
-              double sv[4], pv[4], qv[4];
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {            // loads first: they do not wait for the stores below
-                const size_t at = (size_t)min(ib + u, i_end - 1) * C + j;
-                sv[u] = sg[at];
-                pv[u] = p[at];
-                qv[u] = q[at];
-              }
-#pragma unroll
-              for (int u = 0; u < 4; ++u) {
-                const int i = ib + u;
-                if (i < i_end) {
-                  const double cur = sv[u] * pv[u];
-                  above += cur;
-                  below -= (double)(R - i) * cur;
-                  const double lc = a.r_col * ((double)(R - i) * above + below) + a.r_sense * total;
-                  const double qn = qv[u] + sv[u] * lc;
-                  q[(size_t)i * C + j] = qn;
-                  pq += pv[u] * qn;
-                }
-              }
-            }
-          }
-          __syncthreads();                             // tot is reused by the next strip
-        }
-        pq = block_sum(pq, red);
-        const double alpha = rr / pq;
-        // y <- y + alpha p;  r <- r - alpha q
-        part = 0.0;
-        for (int i = wave; i < rows; i += 4)
-          for (int j = lane; j < cols; j += 64) {
-            const size_t at = (size_t)i * C + j;
-            y[at] += alpha * p[at];
-            const double rn = r[at] - alpha * q[at];
-            r[at] = rn;
-            part += rn * rn;
-          }
-        const double rr_new = block_sum(part, red);
-        beta = rr_new / rr;
-        rr = rr_new;
-      }
-      // row rhs of the non-ideal conductance matrix: column sums of x = s y
-      for (int strip = 0; strip < strips; ++strip) {
-        const int j = strip * 64 + lane;
-        double e = 0.0;
-        if (j < cols)
-          for (int i = i_begin; i < i_end; ++i) e += sg[(size_t)i * C + j] * y[(size_t)i * C + j];
-        tot[0][wave][lane] = e;
-        __syncthreads();
-        if (wave == 0 && j < cols) {
-          const double e_all = (tot[0][0][lane] + tot[0][1][lane]) + (tot[0][2][lane] + tot[0][3][lane]);
-          const double sv = sg[(size_t)rhs * C + j];
-          const double g = sv * sv;
-          a.profile[((size_t)(2 * s + pol) * a.K + k0 + rhs) * a.N + n0 + j] = g > 0.0 ? (float)((g - e_all) / g) : 0.0f;
-        }
-        __syncthreads();
-      }
-    }
-  }
-}
-
-// Same solve for 64 x 64 and 128 x 128 crossbars with the whole state on chip.  NT threads form a
-// (NT / 16) x 16 grid; thread (ty, tx) owns the SR x SC devices at rows SR ty.., columns SC tx..;
-// residual and search direction live in its registers, sqrt(G) in LDS.  Prefix sums along a row run
-// over the 16 consecutive lanes that share ty (DPP row shifts), along a column over the 4 lane groups
-// of a wave (shuffles) and over the waves (LDS).  A p is computed twice per iteration (for p.Ap, then
-// for the residual update) instead of being stored: registers and LDS together hold three vectors of
-// crossbar size plus sqrt(G), not four.
-template <int CTRL>
-__device__ __forceinline__ double dpp_row_f64(double x) {   // lanes whose source lies outside the row of 16 get 0
-  union { double d; int i[2]; } v, o;
-  v.d = x;
-  o.i[0] = __builtin_amdgcn_update_dpp(0, v.i[0], CTRL, 0xF, 0xF, false);
-  o.i[1] = __builtin_amdgcn_update_dpp(0, v.i[1], CTRL, 0xF, 0xF, false);
-  return o.d;
-}
-
-__device__ __forceinline__ double row16_inclusive_scan(double x) {
-  x += dpp_row_f64<0x111>(x);                        // row_shr:1
-  x += dpp_row_f64<0x112>(x);                        // row_shr:2
-  x += dpp_row_f64<0x114>(x);                        // row_shr:4
-  x += dpp_row_f64<0x118>(x);                        // row_shr:8
-  return x;
-}
-
-template <int NW>
-__device__ __forceinline__ double block_sum_n(double v, double* red) {
-#pragma unroll
-  for (int d = 32; d; d >>= 1) v += __shfl_xor(v, d, 64);
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-  __syncthreads();
-  double t = 0.0;
-#pragma unroll
-  for (int w = 0; w < NW; ++w) t += red[w];
-  return t;
-}
-
-template <int SR, int SC, int NT>
-__global__ __launch_bounds__(NT) void fcm_onchip_kernel(FcmArgs a) {
-  extern __shared__ double fcm_lds[];
-  constexpr int NW = NT / 64;                        // waves; 4 thread rows (ty) per wave
-  constexpr int R = (NT / 16) * SR, C = 16 * SC;     // == a.R, a.C
-  double* s_lds = fcm_lds;                           // [SR * SC][NT]: element (ar, bc) of thread tid
-  double* xch = fcm_lds + SR * SC * NT;              // [2][NW][16 tx][SC]
-  double* red = xch + 2 * NW * 16 * SC;              // [NW]
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int tx = tid & 15, ty = tid >> 4;
-  const int i0 = ty * SR, j0 = tx * SC;
-  NormalStream rng(a.seed, kStreamVariation, a.step);
-
-  for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
-    const int group = item % a.groups;
-    const int t1 = item / a.groups;
-    const int pol = t1 & 1;
-    const int s = (t1 >> 1) % a.S_w;
-    const int tile = (t1 >> 1) / a.S_w;
-    const int k0 = (tile / a.tiles_c) * R, n0 = (tile % a.tiles_c) * C;
-    const int rows = min(R, a.K - k0), cols = min(C, a.N - n0);
-
-    __syncthreads();
-    for (int ar = 0; ar < SR; ++ar)
-      for (int bc = 0; bc < SC; ++bc) {
-        const int i = i0 + ar, j = j0 + bc;
-        double g = 0.0;
-        if (i < rows && j < cols) {
-          const double qw = (double)((1u << a.weight_bits) - 1);
-          const double wq =
-              ::rint(clampd((double)a.W[(size_t)(k0 + i) * a.N + n0 + j] / (double)a.w_max, -1.0, 1.0) * qw);
-          const int digit = (int)(((uint32_t)::fabs(wq) >> (a.slice_bits * s)) & ((1u << a.slice_bits) - 1));
-          const bool mine = pol == 0 ? wq > 0.0 : wq < 0.0;
-          g = a.g_min + (mine ? digit * a.dg : 0.0);
-          if (a.flags & XBAR_NI_VARIATION) {
-            const uint64_t dev =
-                (((uint64_t)(k0 + i) * (uint64_t)a.N + (uint64_t)(n0 + j)) * (uint64_t)a.S_w + (uint64_t)s) * 2 + pol;
-            g *= 1.0 + a.var_sigma * rng.get(dev);
-          }
-        }
-        s_lds[(ar * SC + bc) * NT + tid] = ::sqrt(::fmax(g, 0.0));
-      }
-    // every thread reads back only what it wrote itself: no barrier needed for s_lds
-
-    const int rhs_end = min(rows, (group + 1) * a.rhs_per_group);
-    for (int rhs = group * a.rhs_per_group; rhs < rhs_end; ++rhs) {
-      double r[SR][SC], p[SR][SC], e_acc[SC];
-      double part = 0.0;
-#pragma unroll
-      for (int ar = 0; ar < SR; ++ar)
-#pragma unroll
-        for (int bc = 0; bc < SC; ++bc) {
-          r[ar][bc] = (i0 + ar == rhs) ? s_lds[(ar * SC + bc) * NT + tid] : 0.0;
-          p[ar][bc] = 0.0;
-          part += r[ar][bc] * r[ar][bc];
-        }
-#pragma unroll
-      for (int bc = 0; bc < SC; ++bc) e_acc[bc] = 0.0;
-      double rr = block_sum_n<NW>(part, red);
-      const double stop = a.tol2 * rr;
-      double beta = 0.0;
-      for (int it = 0; it < a.max_iter && rr > stop; ++it) {
-        // p <- r + beta p, and the sums of u = s p over this thread's part of every row and column
-        double row0[SR], row1[SR], rtot[SR], col0[SC], col1[SC], ctot[SC];
-#pragma unroll
-        for (int x = 0; x < SR; ++x) row0[x] = row1[x] = 0.0;
-#pragma unroll
-        for (int x = 0; x < SC; ++x) col0[x] = col1[x] = 0.0;
-#pragma unroll
-        for (int ar = 0; ar < SR; ++ar)
-#pragma unroll
-          for (int bc = 0; bc < SC; ++bc) {
-            p[ar][bc] = r[ar][bc] + beta * p[ar][bc];
-            const double u = s_lds[(ar * SC + bc) * NT + tid] * p[ar][bc];
-            row0[ar] += u;
-            row1[ar] += (double)(j0 + bc + 1) * u;
-            col0[bc] += u;
-            col1[bc] += (double)(R - (i0 + ar)) * u;
-          }
-        // rows: sums over the threads to the left (same ty = one DPP row of 16 lanes), and the row totals
-#pragma unroll
-        for (int ar = 0; ar < SR; ++ar) {
-          const double inc0 = row16_inclusive_scan(row0[ar]), inc1 = row16_inclusive_scan(row1[ar]);
-          rtot[ar] = dpp_row_f64<0x15F>(inc0);         // row_newbcast:15
-          row0[ar] = inc0 - row0[ar];                  // sum_{j' < j0} u
-          row1[ar] = inc1 - row1[ar];                  // sum_{j' < j0} (j' + 1) u
-        }
-        // columns: sums over the lane groups above inside the wave, then over the waves
-#pragma unroll
-        for (int bc = 0; bc < SC; ++bc) {
-          double inc0 = col0[bc], inc1 = col1[bc];
-          double y0 = __shfl_up(inc0, 16, 64), y1 = __shfl_up(inc1, 16, 64);
-          if (lane >= 16) { inc0 += y0; inc1 += y1; }
-          y0 = __shfl_up(inc0, 32, 64); y1 = __shfl_up(inc1, 32, 64);
-          if (lane >= 32) { inc0 += y0; inc1 += y1; }
-          if (lane >= 48) {                            // last group of the wave holds the wave's sums
-            xch[(0 * NW + wave) * 16 * SC + tx * SC + bc] = inc0;
-            xch[(1 * NW + wave) * 16 * SC + tx * SC + bc] = inc1;
-          }
-          col0[bc] = inc0 - col0[bc];                  // groups above, inside the wave
-          col1[bc] = inc1 - col1[bc];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int bc = 0; bc < SC; ++bc) {
-          double all0 = 0.0, all1 = 0.0, before0 = 0.0, before1 = 0.0;
-#pragma unroll
-          for (int w = 0; w < NW; ++w) {
-            const double w0 = xch[(0 * NW + w) * 16 * SC + tx * SC + bc], w1 = xch[(1 * NW + w) * 16 * SC + tx * SC + bc];
-            all0 += w0;
-            all1 += w1;
-            if (w < wave) { before0 += w0; before1 += w1; }
-          }
-          ctot[bc] = all0;
-          col0[bc] += before0;                         // sum_{i' < i0} u
-          col1[bc] = all1 - (before1 + col1[bc]);      // sum_{i' >= i0} (R - i') u
-        }
-        // A p = p + s (Lr + Lc)(u): first for p.Ap, walking down the rows (the column sums end one
-        // block further down) ...
-        double pq = 0.0;
-#pragma unroll
-        for (int ar = 0; ar < SR; ++ar) {
-          double run0 = row0[ar], run1 = row1[ar];
-#pragma unroll
-          for (int bc = 0; bc < SC; ++bc) {
-            const double sv = s_lds[(ar * SC + bc) * NT + tid];
-            const double u = sv * p[ar][bc];
-            const double jj = (double)(j0 + bc + 1), ii = (double)(R - (i0 + ar));
-            run0 += u;
-            run1 += jj * u;
-            col0[bc] += u;
-            col1[bc] -= ii * u;
-            const double lr = a.r_source * rtot[ar] + a.r_row * (run1 + jj * (rtot[ar] - run0));
-            const double lc = a.r_col * (ii * col0[bc] + col1[bc]) + a.r_sense * ctot[bc];
-            pq += p[ar][bc] * (p[ar][bc] + sv * (lr + lc));
-          }
-        }
-        pq = block_sum_n<NW>(pq, red);
-        const double alpha = rr / pq;
-        // ... then again for r <- r - alpha A p, walking back up and undoing the column sums
-        part = 0.0;
-#pragma unroll
-        for (int ar = SR - 1; ar >= 0; --ar) {
-          double run0 = row0[ar], run1 = row1[ar];
-#pragma unroll
-          for (int bc = 0; bc < SC; ++bc) {
-            const double sv = s_lds[(ar * SC + bc) * NT + tid];
-            const double u = sv * p[ar][bc];
-            const double jj = (double)(j0 + bc + 1), ii = (double)(R - (i0 + ar));
-            run0 += u;
-            run1 += jj * u;
-            const double lr = a.r_source * rtot[ar] + a.r_row * (run1 + jj * (rtot[ar] - run0));
-            const double lc = a.r_col * (ii * col0[bc] + col1[bc]) + a.r_sense * ctot[bc];
-            col0[bc] -= u;
-            col1[bc] += ii * u;
-            const double rn = r[ar][bc] - alpha * (p[ar][bc] + sv * (lr + lc));
-            r[ar][bc] = rn;
-            part += rn * rn;
-          }
-        }
-#pragma unroll
-        for (int bc = 0; bc < SC; ++bc) e_acc[bc] += alpha * ctot[bc];   // column sums of x = s y, y = sum alpha p
-        const double rr_new = block_sum_n<NW>(part, red);
-        beta = rr_new / rr;
-        rr = rr_new;
-      }
-      if (rhs >= i0 && rhs < i0 + SR) {
-#pragma unroll
-        for (int bc = 0; bc < SC; ++bc) {
-          const int j = j0 + bc;
-          if (j < cols) {
-            const double sv = s_lds[((rhs - i0) * SC + bc) * NT + tid];
-            const double g = sv * sv;
-            a.profile[((size_t)(2 * s + pol) * a.K + k0 + rhs) * a.N + n0 + j] =
-                g > 0.0 ? (float)((g - e_acc[bc]) / g) : 0.0f;
-          }
-        }
-      }
-    }
-  }
-}
 
 // ---------------------------------------------------------------------------------------------
 // instrumentation: sustained matrix-instruction rate
@@ -1977,18 +1026,6 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters, 
 // ---------------------------------------------------------------------------------------------
 // host dispatch
 // ---------------------------------------------------------------------------------------------
-inline bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-inline bool finite_pos(float x) { return std::isfinite(x) && x > 0.0f; }
-inline bool finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
-
-int check_shape(int M, int K, int N) {
-  if (M <= 0 || K <= 0 || N <= 0) return XBAR_ESHAPE;
-  // weights are indexed with 32 bits, activations with 64 (bounded to keep grids and buffers sane)
-  if ((long long)K * N >= (1ll << 31)) return XBAR_ESHAPE;
-  if ((long long)M * K >= (1ll << 38) || (long long)M * N >= (1ll << 38)) return XBAR_ESHAPE;
-  return XBAR_OK;
-}
-
 thread_local hipEvent_t g_trace_before = nullptr, g_trace_after = nullptr;
 
 struct VmmPlan {
@@ -2036,32 +1073,6 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   return p;
 }
 
-struct FcmPlan {
-  int n_items, groups, rhs_per_group, blocks;
-  int onchip;            // 0: state in the workspace; 64 / 128: square crossbars of that size, state on chip
-  size_t lds_bytes, ws_bytes;
-};
-
-FcmPlan plan_fcm(const xbar_config* c, const Derived& d, int K, int N) {
-  FcmPlan p;
-  const int per_drive_sets = cdiv(K, c->xbar_rows) * cdiv(N, c->xbar_cols) * d.S_w * 2;   // (tile, slice, array)
-  // split the driven rows of a crossbar over several blocks when there are few crossbars
-  p.groups = std::min(c->xbar_rows / 4, std::max(1, cdiv(2048, per_drive_sets)));
-  p.rhs_per_group = cdiv(c->xbar_rows, p.groups);
-  p.groups = cdiv(c->xbar_rows, p.rhs_per_group);
-  p.n_items = per_drive_sets * p.groups;
-  p.onchip = (c->xbar_rows == c->xbar_cols && (c->xbar_rows == 64 || c->xbar_rows == 128)) ? c->xbar_rows : 0;
-  {  // s, the column exchange area [2][waves][16][SC] and the reduction slots
-    const int nt = 256, sc = p.onchip / 16;
-    p.lds_bytes = ((size_t)p.onchip * p.onchip + 2 * (nt / 64) * 16 * sc + nt / 64) * sizeof(double);
-  }
-  // the workspace is sized for the general kernel in every case (it is the fallback)
-  const size_t slot = (size_t)5 * c->xbar_rows * c->xbar_cols * sizeof(double);
-  p.blocks = std::min(p.n_items, slot > (size_t)1 << 20 ? 1024 : 2048);
-  p.ws_bytes = align256((size_t)p.blocks * slot);
-  return p;
-}
-
 struct UpdPlan {
   int KB, NB, mchunks, m_per_chunk, parts;   // parts: partial sums per batch chunk (padding waves reused)
   size_t ws_bytes;
@@ -2078,22 +1089,6 @@ UpdPlan plan_update(int M, int K, int N) {
   p.mchunks = cdiv(M, per);
   p.parts = (K <= 64 ? 2 : 1) * (N <= 64 ? 2 : 1);
   p.ws_bytes = align256((size_t)p.mchunks * p.parts * K * N * sizeof(float));
-  return p;
-}
-
-struct PulsePlan {
-  int mc;                       // samples per chunk (the trains of one chunk are resident at a time)
-  size_t rows_bytes, cols_bytes, ws_bytes;
-};
-
-PulsePlan plan_pulsed(int M, int K, int N) {
-  PulsePlan p;
-  const long long per_sample = 4ll * ((long long)K + N);
-  long long mc = std::max(64ll, ((64ll << 20) / per_sample) / 64 * 64);
-  p.mc = (int)std::min<long long>(mc, M);
-  p.rows_bytes = align256((size_t)4 * p.mc * K);
-  p.cols_bytes = align256((size_t)4 * p.mc * N);
-  p.ws_bytes = p.rows_bytes + p.cols_bytes + align256((size_t)8 * K * N);
   return p;
 }
 
@@ -2373,8 +1368,8 @@ size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N)
   if (op == XBAR_OP_FWD) return plan_vmm(cfg, d, M, K, N, false).ws_bytes;
   if (op == XBAR_OP_BWD) return plan_vmm(cfg, d, M, K, N, true).ws_bytes;
   if (op == XBAR_OP_UPDATE) return plan_update(M, K, N).ws_bytes;
-  if (op == XBAR_OP_FCM) return plan_fcm(cfg, d, K, N).ws_bytes;
-  if (op == XBAR_OP_UPDATE_PULSED) return plan_pulsed(M, K, N).ws_bytes;
+  if (op == XBAR_OP_FCM) return fcm_workspace_bytes(cfg, K, N);
+  if (op == XBAR_OP_UPDATE_PULSED) return pulsed_workspace_bytes(M, K, N);
   return 0;
 }
 
@@ -2393,27 +1388,7 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
   if (cfg->flags & XBAR_NI_WIRE_AAM2) {
     wire_u = reinterpret_cast<double*>(reinterpret_cast<char*>(planes) + align256(plane_geom(cfg, d, K, N, false).bytes) +
                                        align256(plane_geom(cfg, d, K, N, true).bytes));
-    WireArgs w;
-    w.W = W; w.A = wire_u;
-    w.q = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(wire_u) + align256((size_t)16 * d.S_w * K * N));
-    w.K = K; w.N = N; w.R = cfg->xbar_rows; w.C = cfg->xbar_cols; w.S_w = d.S_w;
-    w.slice_bits = cfg->slice_bits; w.weight_bits = cfg->weight_bits;
-    w.tiles_c = cdiv(N, cfg->xbar_cols);
-    w.flags = cfg->flags;
-    w.g_min = 1.0 / (double)cfg->r_max;
-    w.dg = (1.0 / (double)cfg->r_min - w.g_min) / (double)((1 << cfg->slice_bits) - 1);
-    w.var_sigma = (double)cfg->var_sigma;
-    w.r_row = (double)cfg->r_row; w.r_col = (double)cfg->r_col;
-    w.r_source = (double)cfg->r_source; w.r_sense = (double)cfg->r_sense;
-    w.w_max = w_max; w.seed = cfg->seed; w.step = step;
-    const unsigned tiles = (unsigned)(cdiv(K, cfg->xbar_rows) * w.tiles_c);
-    hipLaunchKernelGGL(wire_quantize_kernel, dim3((unsigned)(((size_t)K * N + 255) / 256)), dim3(256), 0, st, w);
-    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
-    hipLaunchKernelGGL(wire_rows_kernel, dim3(tiles * 4u, (unsigned)d.S_w), dim3(256), 0, st, w);
-    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
-    hipLaunchKernelGGL(wire_cols_kernel, dim3(tiles * (unsigned)((cfg->xbar_cols + 63) / 64), (unsigned)d.S_w), dim3(256),
-                       0, st, w);
-    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+    if ((rc = launch_wire_model(cfg, W, K, N, w_max, step, wire_u, st))) return rc;
   }
   if (cfg->flags & XBAR_INPUT_OFFSET) {
     SumArgs sa;
@@ -2482,57 +1457,6 @@ int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float*
 int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
                 float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream) {
   return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream, nullptr);
-}
-
-int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
-                       float x_range, float d_range, int bl, float dw_min, uint64_t step, long long* pulses, void* ws,
-                       size_t ws_bytes, void* hip_stream) {
-  int rc = xbar_config_validate(cfg);
-  if (rc) return rc;
-  if ((rc = check_shape(M, K, N))) return rc;
-  if (!aligned16(W) || !aligned16(X) || !aligned16(dY) || !aligned16(ws)) return XBAR_EALIGN;
-  if (pulses && (reinterpret_cast<uintptr_t>(pulses) & 7u)) return XBAR_EALIGN;
-  if (!finite_pos(w_max) || !finite_pos(x_range) || !finite_pos(d_range) || !finite_pos(dw_min)) return XBAR_EINVAL;
-  if (bl < 1 || bl > 31 || step >= (1ull << 33)) return XBAR_EINVAL;
-  const PulsePlan p = plan_pulsed(M, K, N);
-  if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
-  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  PulseArgs a;
-  a.W = W; a.X = X; a.D = dY;
-  a.rows = reinterpret_cast<uint32_t*>(ws);
-  a.cols = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(ws) + p.rows_bytes);
-  a.state = reinterpret_cast<double*>(reinterpret_cast<char*>(ws) + p.rows_bytes + p.cols_bytes);
-  a.pulses = pulses;
-  a.M = M; a.K = K; a.N = N; a.bl = bl;
-  a.flags = cfg->flags;
-  a.w_max = (double)w_max; a.x_range = (double)x_range; a.d_range = (double)d_range; a.dw_min = (double)dw_min;
-  a.v = (double)cfg->upd_nl_v;
-  a.sigma = (double)cfg->upd_noise_gamma * std::sqrt((double)dw_min);
-  a.seed = cfg->seed; a.step = step;
-  // 4 x 4 devices per thread when that still fills the chip, else one device per thread
-  const bool patch4 = (long long)cdiv(K, 64) * cdiv(N, 64) >= 512;
-  const int edge = patch4 ? 64 : 16;
-  const unsigned tiles = (unsigned)(cdiv(K, edge) * cdiv(N, edge));
-  for (int m0 = 0; m0 < M; m0 += p.mc) {
-    a.m0 = m0;
-    a.mc = std::min(p.mc, M - m0);
-    a.first = m0 == 0;
-    a.last = m0 + a.mc >= M;
-    const long long elems = (long long)a.mc * ((long long)K + N);
-    hipLaunchKernelGGL(pulse_trains_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
-    const bool nl = (cfg->flags & XBAR_NI_UPD_NL) != 0, noise = (cfg->flags & XBAR_NI_UPD_NOISE) != 0;
-    void (*k)(PulseArgs);
-    if (patch4)
-      k = nl ? (noise ? pulse_apply_kernel<4, true, true> : pulse_apply_kernel<4, true, false>)
-             : (noise ? pulse_apply_kernel<4, false, true> : pulse_apply_kernel<4, false, false>);
-    else
-      k = nl ? (noise ? pulse_apply_kernel<1, true, true> : pulse_apply_kernel<1, true, false>)
-             : (noise ? pulse_apply_kernel<1, false, true> : pulse_apply_kernel<1, false, false>);
-    hipLaunchKernelGGL(k, dim3(tiles), dim3(256), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
-  }
-  return XBAR_OK;
 }
 
 size_t xbar_conv_workspace_bytes(const xbar_config* cfg, int op, const xbar_conv_geom* geom, int N) {
@@ -2605,48 +1529,6 @@ int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* 
   if (!finite_pos(c.adc_fs_fwd)) return XBAR_EINVAL;
   return run_vmm(&c, planes, in, nullptr, M, K, N, 1.0f, in_scale, ws, ws_bytes, nullptr, hip_stream, op == XBAR_OP_BWD,
                  nullptr, hist);
-}
-
-int xbar_fcm_profile(const xbar_config* cfg, const float* W, int K, int N, float w_max, uint64_t step, float* profile,
-                     void* ws, size_t ws_bytes, void* hip_stream) {
-  int rc = xbar_config_validate(cfg);
-  if (rc) return rc;
-  if ((rc = check_shape(1, K, N))) return rc;
-  if (!aligned16(W) || !aligned16(profile) || !aligned16(ws)) return XBAR_EALIGN;
-  if (!finite_pos(w_max)) return XBAR_EINVAL;
-  const Derived d = derive(cfg);
-  const FcmPlan p = plan_fcm(cfg, d, K, N);
-  if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
-  FcmArgs a;
-  a.W = W; a.profile = profile; a.scratch = reinterpret_cast<double*>(ws);
-  a.K = K; a.N = N; a.R = cfg->xbar_rows; a.C = cfg->xbar_cols; a.S_w = d.S_w;
-  a.slice_bits = cfg->slice_bits; a.weight_bits = cfg->weight_bits; a.tiles_c = cdiv(N, cfg->xbar_cols);
-  a.groups = p.groups; a.rhs_per_group = p.rhs_per_group; a.n_items = p.n_items;
-  a.max_iter = 500;
-  a.flags = cfg->flags;
-  a.g_min = 1.0 / (double)cfg->r_max;
-  a.dg = (1.0 / (double)cfg->r_min - a.g_min) / (double)((1 << cfg->slice_bits) - 1);
-  a.var_sigma = (double)cfg->var_sigma;
-  a.r_row = (double)cfg->r_row; a.r_col = (double)cfg->r_col;
-  a.r_source = (double)cfg->r_source; a.r_sense = (double)cfg->r_sense;
-  a.tol2 = 1e-22;                                   // relative residual 1e-11
-  a.w_max = w_max; a.seed = cfg->seed; a.step = step;
-  hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
-  if (p.onchip) {
-    const void* fn = p.onchip == 128 ? reinterpret_cast<const void*>(&fcm_onchip_kernel<8, 8, 256>)
-                                     : reinterpret_cast<const void*>(&fcm_onchip_kernel<4, 4, 256>);
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.lds_bytes) == hipSuccess) {
-      if (p.onchip == 128)
-        hipLaunchKernelGGL((fcm_onchip_kernel<8, 8, 256>), dim3((unsigned)p.blocks), dim3(256), p.lds_bytes, st, a);
-      else
-        hipLaunchKernelGGL((fcm_onchip_kernel<4, 4, 256>), dim3((unsigned)p.blocks), dim3(256), p.lds_bytes, st, a);
-      return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
-    }
-    (void)hipGetLastError();                         // no such LDS size on this device: general kernel
-  }
-  hipLaunchKernelGGL(fcm_kernel, dim3((unsigned)p.blocks), dim3(256), 0, st, a);
-  if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
-  return XBAR_OK;
 }
 
 }  // extern "C"

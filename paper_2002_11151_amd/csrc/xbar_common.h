@@ -1,0 +1,174 @@
+// Shared by the translation units of libxbar.so: constants, the geometry of the plane buffer, the
+// counter-based random numbers and small device helpers.  Internal: the boundary is include/xbar.h.
+#ifndef XBAR_COMMON_H_
+#define XBAR_COMMON_H_
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "xbar.h"
+
+namespace xbar_detail {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr uint32_t kMagicBits = 0x4B400000u;  // bits of 1.5 * 2^23: adding it rounds to an integer (RNE)
+constexpr float kMagic = 12582912.0f;
+constexpr int kStreamVariation = 1, kStreamWrite = 2;
+constexpr int kStreamPulseRows = 3, kStreamPulseCols = 4, kStreamPulseNoise = 5;
+constexpr bool kBarrierPerMfma = false;   // scheduling fence after every MFMA (true) or every fragment (false)
+
+// ---------------------------------------------------------------------------------------------
+// host-side geometry shared by the entry points
+// ---------------------------------------------------------------------------------------------
+struct Derived {
+  int S_w, S_in, terms, q_adc;
+  int npol;            // converters per crossbar column: 1 (pair read differentially) or 2 (one per array)
+  uint32_t array_ni;
+};
+
+static inline Derived derive(const xbar_config* c) {
+  Derived d;
+  d.S_w = c->weight_bits / c->slice_bits;
+  d.S_in = c->input_bits / c->stream_bits;
+  d.array_ni = c->flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE | XBAR_NI_WIRE_AAM2);
+  d.npol = (c->flags & XBAR_ADC_PER_ARRAY) ? 2 : 1;
+  // one array alone carries the off-state conductance of every device: never whole device levels
+  d.terms = (d.array_ni || d.npol == 2) ? 2 : 1;
+  // signed converter on the difference of the pair, or unsigned converter on one array's current
+  d.q_adc = d.npol == 2 ? (1 << c->adc_bits) - 1 : (1 << (c->adc_bits - 1)) - 1;
+  return d;
+}
+
+static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Plane buffer: forward copy then backward copy.  One copy is
+// [array][tile][output patch of 32][slice][term][k-step of 16][64 lanes][8 halves]; there is one
+// "array" (the difference of the pair) unless every array has a converter of its own.
+struct PlaneGeom {
+  int tile, ks, T, OP;          // contraction tile length, k-steps per tile, tiles, output patches
+  size_t pol_bytes, bytes;      // one array, all arrays
+};
+
+// Scratch of the all-paths wire model, kept behind the two plane copies.
+static inline size_t wire_scratch_bytes(const xbar_config* c, const Derived& d, int K, int N) {
+  return (c->flags & XBAR_NI_WIRE_AAM2) ? align256((size_t)16 * d.S_w * K * N) + align256((size_t)4 * K * N) : 0;
+}
+
+// Weight sums for the digital correction of offset-binary inputs, kept behind the wire scratch:
+// colsum[N] then rowsum[K], 64-bit.
+static inline size_t weight_sums_bytes(const xbar_config* c, int K, int N) {
+  return (c->flags & XBAR_INPUT_OFFSET) ? align256((size_t)8 * ((size_t)K + N)) : 0;
+}
+
+static inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N, bool transposed) {
+  PlaneGeom g;
+  g.tile = transposed ? c->xbar_cols : c->xbar_rows;
+  g.ks = g.tile / 16;
+  g.T = cdiv(transposed ? N : K, g.tile);
+  g.OP = cdiv(transposed ? K : N, 32);
+  g.pol_bytes = (size_t)g.T * g.OP * d.S_w * d.terms * g.ks * 1024;
+  g.bytes = g.pol_bytes * d.npol;
+  return g;
+}
+
+static inline size_t weight_sums_offset(const xbar_config* c, const Derived& d, int K, int N) {
+  return align256(plane_geom(c, d, K, N, false).bytes) + align256(plane_geom(c, d, K, N, true).bytes) +
+         wire_scratch_bytes(c, d, K, N);
+}
+
+// ---------------------------------------------------------------------------------------------
+// device helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t out[4]) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const uint32_t h0 = __umulhi(0xD2511F53u, c0), l0 = 0xD2511F53u * c0;
+    const uint32_t h1 = __umulhi(0xCD9E8D57u, c2), l1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = h1 ^ c1 ^ k0, n2 = h0 ^ c3 ^ k1;
+    c0 = n0; c1 = l1; c2 = n2; c3 = l0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Standard normal number i of (seed, stream, step): four consecutive i share one Philox block,
+// words (0,1) -> numbers 0,1 (cosine, sine branch of Box-Muller), words (2,3) -> numbers 2,3.
+struct NormalStream {
+  uint32_t k0, k1, s0, s1;
+  uint64_t cached_blk;
+  uint32_t w[4];
+  __device__ NormalStream(uint64_t seed, uint32_t stream, uint64_t step) {
+    k0 = (uint32_t)seed ^ (0x9E3779B9u * stream);
+    k1 = (uint32_t)(seed >> 32) ^ (0xBB67AE85u * stream);
+    s0 = (uint32_t)step;
+    s1 = (uint32_t)(step >> 32);
+    cached_blk = ~0ull;
+  }
+  __device__ double get(uint64_t i) {
+    const uint64_t blk = i >> 2;
+    if (blk != cached_blk) {
+      philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), s0, s1, k0, k1, w);
+      cached_blk = blk;
+    }
+    const bool second = (i & 2u) != 0;
+    const double u1 = ((double)(second ? w[2] : w[0]) + 0.5) * (1.0 / 4294967296.0);
+    const double u2 = ((double)(second ? w[3] : w[1]) + 0.5) * (1.0 / 4294967296.0);
+    const double r = ::sqrt(-2.0 * ::log(u1));
+    // angle 2 pi u2: the half-turn form reduces the argument exactly and costs a fraction of sin / cos
+    double sn, cs;
+    ::sincospi(2.0 * u2, &sn, &cs);
+    return (i & 1u) ? r * sn : r * cs;
+  }
+};
+
+__device__ __forceinline__ double clampd(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
+
+__device__ __forceinline__ double wave_inclusive_scan(double x, int lane) {
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const double y = __shfl_up(x, d, 64);
+    if (lane >= d) x += y;
+  }
+  return x;
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-side argument checks
+// ---------------------------------------------------------------------------------------------
+static inline bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline bool finite_pos(float x) { return std::isfinite(x) && x > 0.0f; }
+static inline bool finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
+
+static inline int check_shape(int M, int K, int N) {
+  if (M <= 0 || K <= 0 || N <= 0) return XBAR_ESHAPE;
+  // weights are indexed with 32 bits, activations with 64 (bounded to keep grids and buffers sane)
+  if ((long long)K * N >= (1ll << 31)) return XBAR_ESHAPE;
+  if ((long long)M * K >= (1ll << 38) || (long long)M * N >= (1ll << 38)) return XBAR_ESHAPE;
+  return XBAR_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// entry points of one translation unit that another one calls (not exported)
+// ---------------------------------------------------------------------------------------------
+#define XBAR_INTERNAL __attribute__((visibility("hidden")))
+// wire.hip: all-paths wire model of W into the scratch wire_u[S_w][2][K][N] (+ quantised weights behind it)
+XBAR_INTERNAL int launch_wire_model(const xbar_config* cfg, const float* W, int K, int N, float w_max, uint64_t step,
+                                    double* wire_u, hipStream_t st);
+// fcm.hip, pulse.hip: workspace sizes of xbar_fcm_profile and xbar_update_pulsed
+XBAR_INTERNAL size_t fcm_workspace_bytes(const xbar_config* cfg, int K, int N);
+XBAR_INTERNAL size_t pulsed_workspace_bytes(int M, int K, int N);
+
+}  // namespace xbar_detail
+
+#endif  // XBAR_COMMON_H_
