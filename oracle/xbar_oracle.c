@@ -545,10 +545,14 @@ int xo_update(const xo_config* cfg, float* W, const float* X, const float* dY, i
 /* blocks (block index*8 + j/4, word j%4, streams 3 / 4 for rows / columns) is below             */
 /* rne(p 2^32).  A pulse moves the state g = W / w_max by dw_min against the sign of x d         */
 /* (descent); with XO_UPD_NL the move is scaled by exp(-v x) going up and exp(-v (1 - x)) going   */
-/* down, x = (g + 1) / 2, evaluated at the state the pulse finds; with XO_UPD_NOISE every pulse   */
-/* adds gamma sqrt(dw_min) times a normal number (the aggregate model's sqrt law for one pulse; */
-/* number m*32 + j of stream 5 keyed with step*2^31 + device index); the state is clamped to      */
-/* [-1, 1] after every pulse.  Samples in order, devices independent.                            */
+/* down, x = (g + 1) / 2, evaluated at the state the pulse finds.  With XO_UPD_NOISE every pulse   */
+/* carries the noise the aggregate model gives it: there the standard deviation gamma sqrt(dG)   */
+/* belongs to the ideal change BEFORE the learning rate (Sec. IV-C), and the mean written change  */
+/* of this scheme equals the aggregate update at the learning rate                                */
+/* lr = bl dw_min w_max / (x_range d_range); one pulse is the ideal change dw_min / lr, its noise  */
+/* after the learning rate lr gamma sqrt(dw_min / lr) = gamma sqrt(lr dw_min), times a normal     */
+/* number (number m*32 + j of stream 5 keyed with step*2^31 + device index).  The state is        */
+/* clamped to [-1, 1] after every pulse.  Samples in order, devices independent.                  */
 /* ------------------------------------------------------------------------------------------- */
 uint32_t xo_pulse_train(uint64_t seed, uint32_t stream, uint64_t step, uint64_t index, double p, int bl) {
   const uint32_t key[2] = {(uint32_t)seed ^ (0x9E3779B9u * stream), (uint32_t)(seed >> 32) ^ (0xBB67AE85u * stream)};
@@ -575,7 +579,8 @@ int xo_update_pulsed(const xo_config* cfg, float* W, const float* X, const float
   uint32_t* b = a + K;
   for (size_t i = 0; i < (size_t)K * N; ++i) g[i] = (double)W[i] / (double)w_max;
   if (pulses_out) memset(pulses_out, 0, sizeof(int64_t) * (size_t)K * N);
-  const double sigma = (double)cfg->upd_noise_gamma * sqrt((double)dw_min);
+  const double lr_eq = (double)bl * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
+  const double sigma = (double)cfg->upd_noise_gamma * sqrt(lr_eq * (double)dw_min);
   for (int m = 0; m < M; ++m) {
     /* bit 31 of a train carries the sign of its value */
     for (int k = 0; k < K; ++k) {

@@ -992,23 +992,31 @@ def test_pulsed_update_device_model(xo):
         one_dn = xo.update_pulsed(cfg, W0, X, -D, 1.0, 1.0, 1.0, 1, dw)[0, 0]
         agg_dn = xo.update(cfg, W0, X, -D, 1.0, dw, 1.0)[0, 0]
         assert abs(one_dn - agg_dn) < 1e-7
-    # noise: pulse j of sample m of device dev takes normal number m*32 + j of stream 5 keyed (step << 31) | dev
+    # noise: pulse j of sample m of device dev takes normal number m*32 + j of stream 5 keyed (step << 31) | dev;
+    # its size is gamma sqrt(lr dw_min) with lr = bl dw_min w_max / (x_range d_range), the learning rate at which
+    # the aggregate update equals the mean of this scheme
     cfg = xo.make_config(flags=xo.UPD_NOISE, upd_noise_gamma=gamma, seed=21)
     K, N, step = 2, 3, 6
-    Xn, Dn = np.ones((2, K), np.float32), -np.ones((2, N), np.float32)
-    Wn = xo.update_pulsed(cfg, np.zeros((K, N), np.float32), Xn, Dn, 4.0, 1.0, 1.0, 3, dw, step=step)
+    Xn, Dn = np.full((2, K), 2.0, np.float32), np.full((2, N), -0.5, np.float32)       # at the ranges: every slot fires
+    Wn = xo.update_pulsed(cfg, np.zeros((K, N), np.float32), Xn, Dn, 4.0, 2.0, 0.5, 3, dw, step=step)
+    lr_eq = 3 * dw * 4.0 / (2.0 * 0.5)
     for k in range(K):
         for n in range(N):
             g = 0.0
             for m in range(2):
                 for j in range(3):
-                    g += dw + np.float64(np.float32(gamma)) * np.sqrt(dw) * xo.normal(21, 5, (step << 31) | (k * N + n), m * 32 + j)
+                    g += dw + np.float64(np.float32(gamma)) * np.sqrt(lr_eq * dw) * xo.normal(21, 5, (step << 31) | (k * N + n), m * 32 + j)
                     g = min(max(g, -1.0), 1.0)
             assert abs(Wn[k, n] - 4.0 * g) < 1e-6
-    # the sqrt law: n pulses carry the noise the aggregate model gives their sum (standard deviation
-    # gamma sqrt(n dw_min)), checked over many devices
-    K = N = 40
-    Wm = xo.update_pulsed(xo.make_config(flags=xo.UPD_NOISE, upd_noise_gamma=0.05, seed=2), np.zeros((K, N), np.float32),
-                          np.ones((1, K), np.float32), -np.ones((1, N), np.float32), 1.0, 1.0, 1.0, 16, dw)
-    resid = Wm.astype(np.float64) - 16 * dw
-    assert abs(resid.std() / (0.05 * np.sqrt(16 * dw)) - 1) < 0.06 and abs(resid.mean()) < 4 * resid.std() / 40
+    # n pulses carry the noise the aggregate model gives their sum at that learning rate: the same change
+    # written pulse by pulse and in one aggregate write has the same mean and the same spread over many devices
+    K = N = 60
+    bl, g5, xr, dr, wm = 16, 5.0, 1.0, 0.25, 1.0
+    lr_eq = bl * dw * wm / (xr * dr)
+    cn = xo.make_config(flags=xo.UPD_NOISE, upd_noise_gamma=g5, seed=2)
+    ones, minus = np.ones((1, K), np.float32), -np.full((1, N), dr, np.float32)              # every slot fires: bl pulses up
+    Wp = xo.update_pulsed(cn, np.zeros((K, N), np.float32), ones * xr, minus, wm, xr, dr, bl, dw).astype(np.float64)
+    Wa = xo.update(cn, np.zeros((K, N), np.float32), ones * xr, minus, wm, 1.0 / wm, lr_eq).astype(np.float64)
+    assert abs(Wp.mean() - bl * dw) < 5 * Wp.std() / K and abs(Wa.mean() - bl * dw) < 5 * Wa.std() / K
+    assert abs(Wp.std() / Wa.std() - 1) < 0.06
+    assert abs(Wa.std() / (g5 * np.sqrt(lr_eq * bl * dw)) - 1) < 0.06
