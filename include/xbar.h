@@ -197,9 +197,10 @@ int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* d
  *   seed mixed with stream 3 for rows, 4 for columns, as for the normal numbers) is below rne(p 2^32).
  *   Pulse: state g = W / w_max moves by dw_min; with XBAR_NI_UPD_NL the move is scaled by exp(-v x)
  *   upwards and exp(-v (1 - x)) downwards, x = (g + 1) / 2 at the state the pulse finds; with
- *   XBAR_NI_UPD_NOISE every pulse adds upd_noise_gamma sqrt(dw_min) times normal number m 32 + j (j =
- *   ordinal of the pulse within the sample) of stream 5 of step (step << 31) | (k N + n); g is clamped
- *   to [-1, 1] after every pulse.  Double precision throughout, W <- float(w_max g) at the end.
+ *   XBAR_NI_UPD_NOISE every pulse adds upd_noise_gamma sqrt(lr dw_min), lr the learning rate above (the noise
+ *   xbar_update gives the same change: there the standard deviation belongs to the change before the
+ *   learning rate), times normal number m 32 + j (j = ordinal of the pulse within the sample) of stream 5
+ *   of step (step << 31) | (k N + n); g is clamped to [-1, 1] after every pulse.  Double precision throughout, W <- float(w_max g) at the end.
  *   step < 2^33.  pulses: NULL, or int64 [K][N] receiving the signed number of pulses per device.
  *   ws: xbar_workspace_bytes(cfg, XBAR_OP_UPDATE_PULSED, M, K, N).
  */

@@ -13,7 +13,8 @@ namespace {
 //   train: slot j of element i fires when uniform word j (Philox block 8 i + j / 4, word j % 4,
 //          stream 3 for rows, 4 for columns) is below rne(p 2^32); bit 31 carries the value's sign
 //   pulse: g += dir dw_min [exp(-v x) up | exp(-v (1 - x)) down, x = (g + 1) / 2]
-//               + gamma sqrt(dw_min) normal(m 32 + j of stream 5 keyed (step << 31) | device),
+//               + gamma sqrt(lr dw_min) normal(m 32 + j of stream 5 keyed (step << 31) | device),
+//               lr = bl dw_min w_max / (x_range d_range): the aggregate model's noise for one pulse,
 //          clamped to [-1, 1]; samples in order, pulses of a sample in order
 // ---------------------------------------------------------------------------------------------
 struct PulseArgs {
@@ -258,7 +259,10 @@ int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const f
   a.flags = cfg->flags;
   a.w_max = (double)w_max; a.x_range = (double)x_range; a.d_range = (double)d_range; a.dw_min = (double)dw_min;
   a.v = (double)cfg->upd_nl_v;
-  a.sigma = (double)cfg->upd_noise_gamma * std::sqrt((double)dw_min);
+  // the aggregate model's noise for one pulse: its standard deviation gamma sqrt(dG) belongs to the ideal change
+  // before the learning rate, and this scheme's mean equals the aggregate update at lr = bl dw_min w_max / (x_range d_range)
+  const double lr_eq = (double)bl * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
+  a.sigma = (double)cfg->upd_noise_gamma * std::sqrt(lr_eq * (double)dw_min);
   a.seed = cfg->seed; a.step = step;
   // 4 x 4 devices per thread when that still fills the chip, else one device per thread
   const bool patch4 = (long long)cdiv(K, 64) * cdiv(N, 64) >= 512;

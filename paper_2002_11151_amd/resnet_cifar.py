@@ -49,12 +49,21 @@ class CrossbarLayer:
         if self.net.calibrating:
             self.seen_g = self.g_scale = ops.absmax(dy) or 1.0
         dx = None
+        pulse = self.net.pulse
         if self.geom is None:
             if need_dx:
                 dx = ops.bwd(self.cfg, self.planes, dy, self.K, self.w_max, self.g_scale, ws=ws)
-            if not self.net.calibrating:
+            if not self.net.calibrating and pulse is None:
                 ops.update(self.cfg, self.W, self.x, dy, self.w_max, 1.0 / self.w_max, lr, step, ws=ws)
+            elif not self.net.calibrating:
+                # inputs fire in proportion to their size over the calibrated range; the error range then follows
+                # from the learning rate: mean change = lr x dy / w_max  <=>  x_range d_range = bl dw_min w_max / lr
+                bl, dw_min = pulse["bl"], pulse["dw_min"]
+                d_range = bl * dw_min * self.w_max / (lr * self.x_scale)
+                ops.update_pulsed(self.cfg, self.W, self.x, dy, self.w_max, self.x_scale, d_range, bl, dw_min, step, ws=ws)
         else:
+            if pulse is not None:
+                raise NotImplementedError("the pulse-level update takes a layer's input matrix, not an image")
             if need_dx:
                 dx = ops.conv_bwd(self.cfg, self.planes, dy, self.geom, self.N, self.w_max, self.g_scale, ws=ws)
             if not self.net.calibrating:
@@ -63,7 +72,8 @@ class CrossbarLayer:
 
     def workspace_bytes(self, batch_rows):
         if self.geom is None:
-            return max(xb.workspace_bytes(self.cfg, op, batch_rows, self.K, self.N) for op in (0, 1, 2))
+            return max(xb.workspace_bytes(self.cfg, op, batch_rows, self.K, self.N)
+                       for op in (xb.OP_FWD, xb.OP_BWD, xb.OP_UPDATE, xb.OP_UPDATE_PULSED))
         return max(xb.conv_workspace_bytes(self.cfg, op, self.geom, self.N) for op in (0, 1, 2))
 
 
@@ -91,10 +101,12 @@ class BatchNorm:
 
 class Network:
     """What the networks share: the binding they call (`ops`, replaceable by an object with the same
-    functions that records or times the calls), the training step and the range calibration.
+    functions that records or times the calls), the training step, the range calibration and the kind of
+    weight update (aggregate write, or pulse by pulse when `pulse` is set).
     Subclasses provide forward(x, step), backward(dlogits, step, lr) and self.layers."""
     ops = xb
     calibrating = False
+    pulse = None     # dict(bl=slots per train, dw_min=state change per pulse): pulse-level updates of the dense layers
 
     def train_step(self, x, labels, lr):
         """One SGD step on a batch: returns the per-sample losses (device tensor)."""

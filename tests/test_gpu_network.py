@@ -188,3 +188,30 @@ def test_residual_network_learns_a_fixed_batch():
     losses = [float(net.train_step(images, labels, 0.05).mean()) for _ in range(30)]
     assert np.isfinite(losses).all()
     assert np.mean(losses[-5:]) < 0.8 * np.mean(losses[:3]), losses       # 8-bit ADCs, wire drops, write noise: slow but steady
+
+
+def test_perceptron_learns_with_pulse_level_updates():
+    """Second benchmark configuration (784-500-10 perceptron) trained pulse by pulse: stochastic pulse trains on
+    non-ideal devices drive the loss of a fixed batch down like the aggregate write does."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import sequential
+    kw = workloads.config_kwargs("mlp")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    B = 64
+    images = torch.rand((B, 784), generator=gen, device="cuda")
+    labels = (torch.arange(B, device="cuda") % 10).to(torch.int32)
+    runs = {}
+    for kind in ("aggregate", "pulsed"):
+        net = sequential.Sequential(kw, sequential.mlp_spec((500,), 10), batch=B, in_shape=(784,), signed_input=False, seed=2)
+        if kind == "pulsed":
+            net.pulse = dict(bl=31, dw_min=1e-3)
+        net.calibrate(images, labels)
+        runs[kind] = [float(net.train_step(images, labels, 0.01).mean()) for _ in range(60)]
+        assert np.isfinite(runs[kind]).all()
+    for kind, losses in runs.items():
+        assert max(losses) < 1.1 * losses[0], (kind, losses)                      # no excursion
+        assert np.mean(losses[-5:]) < 0.85 * losses[0], (kind, losses)            # 2.45 -> about 1.7 .. 1.9
+    # same mean update and the same noise per written change by construction: the runs stay together
+    assert abs(np.mean(runs["pulsed"][-5:]) - np.mean(runs["aggregate"][-5:])) < 0.12 * runs["aggregate"][0]
