@@ -221,8 +221,6 @@ def main():
     if args.offset_inputs:
         kw["flags"] |= workloads.INPUT_OFFSET
         signed_phases = 1
-        kw["adc_fs_fwd"] *= 4.0            # every row is driven (a zero at mid-range): larger currents
-        kw["adc_fs_bwd"] *= 4.0
     arrays = 1
     if args.adc_per_array:
         kw["flags"] |= workloads.ADC_PER_ARRAY
