@@ -215,3 +215,31 @@ def test_perceptron_learns_with_pulse_level_updates():
         assert np.mean(losses[-5:]) < 0.85 * losses[0], (kind, losses)            # 2.45 -> about 1.7 .. 1.9
     # same mean update and the same noise per written change by construction: the runs stay together
     assert abs(np.mean(runs["pulsed"][-5:]) - np.mean(runs["aggregate"][-5:])) < 0.12 * runs["aggregate"][0]
+
+@pytest.mark.parametrize("variant", ["offset", "per_array", "all_paths"])
+def test_perceptron_learns_under_variants(variant):
+    """The same perceptron with the errors offset-coded (one phase), with one converter per array (range twice as
+    wide: an array alone carries its off-state current) and with the all-paths wire model: each learns the fixed
+    batch like the default configuration does (2.45 -> about 1.7 .. 1.8 in 60 steps)."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import sequential
+    kw = workloads.config_kwargs("mlp")
+    if variant == "offset":
+        kw["flags"] |= workloads.INPUT_OFFSET
+    elif variant == "per_array":
+        kw["flags"] |= workloads.ADC_PER_ARRAY
+        kw["adc_fs_fwd"] *= 2.0
+        kw["adc_fs_bwd"] *= 2.0
+    else:
+        kw["flags"] = (kw["flags"] & ~workloads.NI_WIRE_AAM) | workloads.NI_WIRE_AAM2
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    B = 64
+    images = torch.rand((B, 784), generator=gen, device="cuda")
+    labels = (torch.arange(B, device="cuda") % 10).to(torch.int32)
+    net = sequential.Sequential(kw, sequential.mlp_spec((500,), 10), batch=B, in_shape=(784,), signed_input=False, seed=2)
+    net.calibrate(images, labels)
+    losses = [float(net.train_step(images, labels, 0.01).mean()) for _ in range(60)]
+    assert np.isfinite(losses).all()
+    assert max(losses) < 1.1 * losses[0] and np.mean(losses[-5:]) < 0.85 * losses[0], losses
