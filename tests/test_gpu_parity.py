@@ -621,13 +621,13 @@ PULSED_CASES = [
     ("linear_dense_pulses", 40, 64, 64, 31, 0.5, 0.005, "", 1.0),        # most probabilities clip at 1
     ("short_trains", 200, 33, 17, 5, 1.5, 0.02, "", 1.0),
     ("single", 1, 1, 1, 1, 0.5, 0.005, "", 1.0),
-    ("two_chunks", 2100, 8192, 64, 4, 3.0, 0.03, "", 1.0),               # the trains of 1984 samples are resident at a time
+    ("two_chunks", 2100, 8192, 16, 4, 3.0, 0.03, "", 1.0),               # the trains of 1984 samples are resident at a time
     ("nl", 130, 70, 100, 31, 2.0, 0.02, "nl", 1.5),
     ("nl_noise", 90, 128, 65, 31, 1.0, 0.01, "nl+noise", 1.0),
-    ("noise_two_chunks", 2000, 8192, 64, 4, 3.0, 0.03, "noise", 1.0),
+    ("noise_two_chunks", 2100, 8192, 16, 4, 3.0, 0.03, "noise", 1.0),
     ("large_layer", 70, 2048, 1030, 31, 2.0, 0.02, "nl+noise", 1.0),     # 4 x 4 devices per thread
     ("large_layer_linear", 70, 2048, 1030, 31, 2.0, 0.02, "", 1.0),
-    ("large_layer_nl", 300, 2048, 1030, 12, 2.0, 0.02, "nl", 1.0),       # several stages of 64 samples
+    ("large_layer_nl", 140, 2048, 1030, 12, 2.0, 0.02, "nl", 1.0),       # three stages of 64 samples
     ("large_layer_noise", 70, 2048, 1030, 31, 2.0, 0.02, "noise", 1.0),
 ]
 
