@@ -625,10 +625,10 @@ PULSED_CASES = [
     ("nl", 130, 70, 100, 31, 2.0, 0.02, "nl", 1.5),
     ("nl_noise", 90, 128, 65, 31, 1.0, 0.01, "nl+noise", 1.0),
     ("noise_two_chunks", 2100, 8192, 16, 4, 3.0, 0.03, "noise", 1.0),
-    ("large_layer", 70, 2048, 1030, 31, 2.0, 0.02, "nl+noise", 1.0),     # 4 x 4 devices per thread
-    ("large_layer_linear", 70, 2048, 1030, 31, 2.0, 0.02, "", 1.0),
-    ("large_layer_nl", 140, 2048, 1030, 12, 2.0, 0.02, "nl", 1.0),       # three stages of 64 samples
-    ("large_layer_noise", 70, 2048, 1030, 31, 2.0, 0.02, "noise", 1.0),
+    ("large_layer", 70, 2048, 1030, 31, 4.0, 0.4, "nl+noise", 1.0),      # 4 x 4 devices per thread
+    ("large_layer_linear", 70, 2048, 1030, 31, 2.0, 0.05, "", 1.0),
+    ("large_layer_nl", 140, 2048, 1030, 12, 2.0, 0.1, "nl", 1.0),        # three stages of 64 samples
+    ("large_layer_noise", 70, 2048, 1030, 31, 4.0, 0.4, "noise", 1.0),
 ]
 
 
