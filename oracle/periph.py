@@ -12,6 +12,17 @@ def relu_bwd(y, dy):
     return np.where(np.asarray(y) > 0, np.asarray(dy, dtype=np.float64), 0.0)
 
 
+def sigmoid_fwd(x):
+    """Logistic function 1 / (1 + exp(-x)) (Sec. IV-B lists it with the digital peripherals)."""
+    return 1.0 / (1.0 + np.exp(-np.asarray(x, dtype=np.float64)))
+
+
+def sigmoid_bwd(y, dy):
+    """From the forward output: dx = dy y (1 - y)."""
+    y = np.asarray(y, dtype=np.float64)
+    return np.asarray(dy, dtype=np.float64) * y * (1.0 - y)
+
+
 def bn_fwd(x, gamma, beta, eps):
     """Training-mode batch normalisation over all axes but the last: returns y, mean, invstd."""
     x = np.asarray(x, dtype=np.float64)

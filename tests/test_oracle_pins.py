@@ -861,6 +861,13 @@ def test_peripheral_definitions_against_library_autograd():
     rt.backward(torch.tensor(dy))
     assert np.array_equal(periph.relu_fwd(x), rt.detach().numpy())
     assert np.array_equal(periph.relu_bwd(periph.relu_fwd(x), dy), xt.grad.numpy())
+    # sigmoid against autograd, and its closed-form properties
+    xt = torch.tensor(x, requires_grad=True)
+    st = torch.sigmoid(xt)
+    st.backward(torch.tensor(dy))
+    assert np.allclose(periph.sigmoid_fwd(x), st.detach().numpy(), atol=1e-15)
+    assert np.allclose(periph.sigmoid_bwd(periph.sigmoid_fwd(x), dy), xt.grad.numpy(), atol=1e-15)
+    assert periph.sigmoid_fwd(0.0) == 0.5 and np.allclose(periph.sigmoid_fwd(x) + periph.sigmoid_fwd(-x), 1.0, atol=1e-15)
     # max pooling 3x3 stride 2 pad 1 and 2x2 stride 2
     for k, stride, pad in ((3, 2, 1), (2, 2, 0)):
         xt = torch.tensor(x, requires_grad=True)
