@@ -244,6 +244,7 @@ int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const flo
  * number of elements; `rows` = batch x positions, channels fastest.  Statistics are accumulated in
  * double precision in a fixed order.
  *   relu_bwd      takes the forward OUTPUT y (dx = dy where y > 0)
+ *   sigmoid       y = 1 / (1 + exp(-x)); sigmoid_bwd takes the forward OUTPUT y (dx = dy y (1 - y))
  *   bn_fwd        training mode: per-channel batch mean and biased variance; writes y, mean and
  *                 invstd = 1 / sqrt(var + eps) (kept for bn_bwd)
  *   bn_bwd        dx, dgamma = sum dy xhat, dbeta = sum dy; ws: xbar_bn_workspace_bytes(rows, channels)
@@ -261,6 +262,8 @@ int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const flo
  */
 int xbar_relu_fwd(const float* x, float* y, size_t n, void* hip_stream);
 int xbar_relu_bwd(const float* y, const float* dy, float* dx, size_t n, void* hip_stream);
+int xbar_sigmoid_fwd(const float* x, float* y, size_t n, void* hip_stream);
+int xbar_sigmoid_bwd(const float* y, const float* dy, float* dx, size_t n, void* hip_stream);
 int xbar_add(const float* a, const float* b, float* y, size_t n, void* hip_stream);
 int xbar_sgd(float* p, const float* g, size_t n, float lr, void* hip_stream);
 size_t xbar_bn_workspace_bytes(size_t rows, int channels);

@@ -27,6 +27,21 @@ __global__ __launch_bounds__(256) void relu_bwd_kernel(const float* y, const flo
   if (i < n) dx[i] = y[i] > 0.0f ? dy[i] : 0.0f;
 }
 
+// Logistic function; the exponential is taken in double precision so that the float result is the
+// correctly rounded one in all but rare cases.
+__global__ __launch_bounds__(256) void sigmoid_fwd_kernel(const float* x, float* y, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) y[i] = (float)(1.0 / (1.0 + ::exp(-(double)x[i])));
+}
+
+__global__ __launch_bounds__(256) void sigmoid_bwd_kernel(const float* y, const float* dy, float* dx, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) {
+    const double s = (double)y[i];
+    dx[i] = (float)((double)dy[i] * s * (1.0 - s));
+  }
+}
+
 __global__ __launch_bounds__(256) void add_kernel(const float* a, const float* b, float* y, size_t n) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) y[i] = a[i] + b[i];
@@ -318,6 +333,21 @@ int xbar_relu_bwd(const float* y, const float* dy, float* dx, size_t n, void* hi
   if (n == 0) return XBAR_ESHAPE;
   if (!aligned16(y) || !aligned16(dy) || !aligned16(dx)) return XBAR_EALIGN;
   hipLaunchKernelGGL(relu_bwd_kernel, dim3(blocks_for(n)), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream), y, dy,
+                     dx, n);
+  return launched();
+}
+
+int xbar_sigmoid_fwd(const float* x, float* y, size_t n, void* hip_stream) {
+  if (n == 0) return XBAR_ESHAPE;
+  if (!aligned16(x) || !aligned16(y)) return XBAR_EALIGN;
+  hipLaunchKernelGGL(sigmoid_fwd_kernel, dim3(blocks_for(n)), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream), x, y, n);
+  return launched();
+}
+
+int xbar_sigmoid_bwd(const float* y, const float* dy, float* dx, size_t n, void* hip_stream) {
+  if (n == 0) return XBAR_ESHAPE;
+  if (!aligned16(y) || !aligned16(dy) || !aligned16(dx)) return XBAR_EALIGN;
+  hipLaunchKernelGGL(sigmoid_bwd_kernel, dim3(blocks_for(n)), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream), y, dy,
                      dx, n);
   return launched();
 }

@@ -4,7 +4,7 @@ kernels (Sec. IV), the rest through the digital peripheral kernels (Sec. IV-B). 
 the C-ABI binding.
 
 A network is a list of layer specs:
-    ("conv", out_channels, kernel, stride, pad) | ("relu",) | ("maxpool", kernel, stride) |
+    ("conv", out_channels, kernel, stride, pad) | ("relu",) | ("sigmoid",) | ("maxpool", kernel, stride) |
     ("flatten",) | ("fc", out_features)
 """
 import torch
@@ -22,10 +22,10 @@ def vgg16_spec(classes=1000):
     return spec + [("flatten",), ("fc", 4096), ("relu",), ("fc", 4096), ("relu",), ("fc", classes)]
 
 
-def mlp_spec(hidden=(500,), classes=10):
+def mlp_spec(hidden=(500,), classes=10, activation="relu"):
     spec = [("flatten",)]
     for h in hidden:
-        spec += [("fc", h), ("relu",)]
+        spec += [("fc", h), (activation,)]
     return spec + [("fc", classes)]
 
 
@@ -53,9 +53,9 @@ class Sequential(Network):
                 self.stack.append(("layer", layer))
                 self.layers.append(layer)
                 shape, signed = (op[1],), True
-            elif kind == "relu":
-                self.stack.append(("relu", None))
-                signed = False
+            elif kind in ("relu", "sigmoid"):
+                self.stack.append((kind, None))
+                signed = False                                            # both outputs are non-negative
             elif kind == "maxpool":
                 h, w, c = shape
                 geom = xb.conv_geom(batch, h, w, c, op[1], op[1], op[2], 0)
@@ -81,6 +81,9 @@ class Sequential(Network):
             elif kind == "relu":
                 x = self.ops.relu_fwd(x)
                 self.saved[i] = x
+            elif kind == "sigmoid":
+                x = self.ops.sigmoid_fwd(x)
+                self.saved[i] = x
             elif kind == "maxpool":
                 x, self.saved[i] = self.ops.maxpool_fwd(x, arg)
             else:                                             # flatten: NHWC rows are already contiguous
@@ -96,6 +99,8 @@ class Sequential(Network):
                 d = arg.backward(d, step, lr, self.ws, need_dx=i != first_layer)
             elif kind == "relu":
                 d = self.ops.relu_bwd(self.saved[i], d)
+            elif kind == "sigmoid":
+                d = self.ops.sigmoid_bwd(self.saved[i], d)
             elif kind == "maxpool":
                 d = self.ops.maxpool_bwd(d, self.saved[i], arg)
             else:

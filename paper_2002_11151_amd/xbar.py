@@ -101,6 +101,8 @@ _SIGNATURES = {
                                    C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_relu_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_relu_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_sigmoid_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_sigmoid_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_add": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_sgd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_float, C.c_void_p]),
     "xbar_bn_workspace_bytes": (C.c_size_t, [C.c_size_t, C.c_int]),
@@ -334,6 +336,18 @@ def conv_update(cfg, W, X, dY, geom, w_max, grad_scale, lr, step=0, ws=None):
 def relu_fwd(x, out=None):
     out = torch.empty_like(x) if out is None else out
     _check(lib().xbar_relu_fwd(_dev(x), _dev(out), x.numel(), _stream()))
+    return out
+
+
+def sigmoid_fwd(x, out=None):
+    out = torch.empty_like(x) if out is None else out
+    _check(lib().xbar_sigmoid_fwd(_dev(x), _dev(out), x.numel(), _stream()))
+    return out
+
+
+def sigmoid_bwd(y, dy, out=None):
+    out = torch.empty_like(y) if out is None else out
+    _check(lib().xbar_sigmoid_bwd(_dev(y), _dev(dy), _dev(out), y.numel(), _stream()))
     return out
 
 

@@ -243,3 +243,21 @@ def test_perceptron_learns_under_variants(variant):
     losses = [float(net.train_step(images, labels, 0.01).mean()) for _ in range(60)]
     assert np.isfinite(losses).all()
     assert max(losses) < 1.1 * losses[0] and np.mean(losses[-5:]) < 0.85 * losses[0], losses
+
+def test_sigmoid_perceptron_step():
+    """A perceptron with sigmoid hidden units (Sec. IV-B names sigmoid among the digital peripherals): one training
+    step runs and lowers the loss of a fixed batch over a few steps."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import sequential
+    kw = workloads.config_kwargs("mlp")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(4)
+    B = 64
+    images = torch.rand((B, 784), generator=gen, device="cuda")
+    labels = (torch.arange(B, device="cuda") % 10).to(torch.int32)
+    net = sequential.Sequential(kw, sequential.mlp_spec((500,), 10, activation="sigmoid"), batch=B, in_shape=(784,),
+                                signed_input=False, seed=2)
+    net.calibrate(images, labels)
+    losses = [float(net.train_step(images, labels, 0.02).mean()) for _ in range(60)]
+    assert np.isfinite(losses).all() and np.mean(losses[-5:]) < 0.95 * losses[0], losses

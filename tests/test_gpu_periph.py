@@ -45,6 +45,9 @@ def test_batchnorm_relu_add(xb, B, H, W, C):
     r = xb.relu_fwd(dev(x))
     assert np.array_equal(r.cpu().numpy(), periph.relu_fwd(x).astype(np.float32))
     assert np.array_equal(xb.relu_bwd(r, dev(dy)).cpu().numpy(), periph.relu_bwd(r.cpu().numpy(), dy).astype(np.float32))
+    s = xb.sigmoid_fwd(dev(x))
+    assert np.abs(s.cpu().numpy() - periph.sigmoid_fwd(x)).max() <= 6e-8                  # half a unit in the last place below 1
+    assert np.abs(xb.sigmoid_bwd(s, dev(dy)).cpu().numpy() - periph.sigmoid_bwd(s.cpu().numpy(), dy)).max() <= 1e-7 * np.abs(dy).max()
     assert np.array_equal(xb.add(dev(x), dev(dy)).cpu().numpy(), x + dy)
     p = dev(x.copy())
     xb.sgd(p, dev(dy), 0.1)
