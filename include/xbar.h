@@ -299,6 +299,12 @@ int xbar_absmax(const float* x, size_t n, float* result, void* ws, size_t ws_byt
 int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* in, int M, int K, int N,
                        float in_scale, int op, float bin_width, unsigned long long* hist, void* ws, size_t ws_bytes,
                        void* hip_stream);
+/* The same for a convolution layer: op = XBAR_OP_FWD takes the NHWC image X (patches gathered as in
+ * xbar_conv_fwd), op = XBAR_OP_BWD the errors dY[batch][out_h][out_w][N]; ws as for xbar_conv_fwd / the
+ * crossbar part of xbar_conv_bwd (xbar_conv_workspace_bytes of the same op is enough). */
+int xbar_conv_adc_histogram(const xbar_config* cfg, const void* planes, const float* in, const xbar_conv_geom* geom,
+                            int N, float in_scale, int op, float bin_width, unsigned long long* hist, void* ws,
+                            size_t ws_bytes, void* hip_stream);
 
 /*
  * Circuit-level crossbar model (Sec. IV-A: Ohm's and Kirchhoff's laws solved for every crossbar

@@ -1136,7 +1136,8 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   }
   const Derived d = derive(cfg);
   const VmmPlan p = plan_vmm(cfg, d, M, K, N, transposed);
-  if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
+  // the statistics pass writes no partial sums: the staged input is all it needs
+  if (ws_bytes < (hist ? p.a_bytes : p.ws_bytes)) return XBAR_EWORKSPACE;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const float adc_fs = transposed ? cfg->adc_fs_bwd : cfg->adc_fs_fwd;
 
@@ -1514,8 +1515,31 @@ int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const flo
                     conv_is_dense(geom) ? nullptr : &g);
 }
 
+namespace {
+int run_histogram(const xbar_config* cfg, const void* planes, const float* in, int M, int K, int N, float in_scale, int op,
+                  float bin_width, unsigned long long* hist, void* ws, size_t ws_bytes, void* hip_stream, const ConvGeom* conv);
+}
+
 int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* in, int M, int K, int N, float in_scale,
                        int op, float bin_width, unsigned long long* hist, void* ws, size_t ws_bytes, void* hip_stream) {
+  return run_histogram(cfg, planes, in, M, K, N, in_scale, op, bin_width, hist, ws, ws_bytes, hip_stream, nullptr);
+}
+
+int xbar_conv_adc_histogram(const xbar_config* cfg, const void* planes, const float* in, const xbar_conv_geom* geom, int N,
+                            float in_scale, int op, float bin_width, unsigned long long* hist, void* ws, size_t ws_bytes,
+                            void* hip_stream) {
+  ConvGeom g;
+  int M, K;
+  const int rc = conv_dims(geom, &g, &M, &K);
+  if (rc) return rc;
+  // forward: the patches are gathered from the image; backward: the errors are a plain [M][N] matrix
+  const bool gather = op == XBAR_OP_FWD && !conv_is_dense(geom);
+  return run_histogram(cfg, planes, in, M, K, N, in_scale, op, bin_width, hist, ws, ws_bytes, hip_stream, gather ? &g : nullptr);
+}
+
+namespace {
+int run_histogram(const xbar_config* cfg, const void* planes, const float* in, int M, int K, int N, float in_scale, int op,
+                  float bin_width, unsigned long long* hist, void* ws, size_t ws_bytes, void* hip_stream, const ConvGeom* conv) {
   int rc = xbar_config_validate(cfg);
   if (rc) return rc;
   if (op != XBAR_OP_FWD && op != XBAR_OP_BWD) return XBAR_EINVAL;
@@ -1528,7 +1552,8 @@ int xbar_adc_histogram(const xbar_config* cfg, const void* planes, const float* 
   c.adc_fs_fwd = c.adc_fs_bwd = (float)(kStatBins - 1) * bin_width;
   if (!finite_pos(c.adc_fs_fwd)) return XBAR_EINVAL;
   return run_vmm(&c, planes, in, nullptr, M, K, N, 1.0f, in_scale, ws, ws_bytes, nullptr, hip_stream, op == XBAR_OP_BWD,
-                 nullptr, hist);
+                 conv, hist);
 }
+}  // namespace
 
 }  // extern "C"

@@ -6,7 +6,10 @@ tensors a backward pass needs; it holds no arithmetic of its own.
 
 Input ranges: every crossbar layer needs the range of its inputs (x_scale), of its errors (g_scale) and
 of its weights (w_max).  They are data dependent (Sec. IV-B) and are fixed by `calibrate()` from one
-batch: the observed maxima times a head-room factor.
+batch: the observed maxima times a head-room factor.  The converter ranges (the maximum current through
+the ADCs, which Sec. IV-B takes from output distribution statistics) can be fixed the same way: with
+`calibrate(..., adc_quantile=q)` a second pass histograms the column currents of every layer on the device
+and sets each range to the smallest power of two that holds the fraction q of them.
 """
 import math
 
@@ -15,6 +18,14 @@ import torch
 from . import xbar as xb
 
 HEADROOM_W, HEADROOM_X, HEADROOM_G = 2.0, 1.5, 4.0
+
+
+def range_from_histogram(hist, bin_width, quantile):
+    """Smallest power of two that is at least the `quantile` of the |current| distribution
+    (hist[b] = number of conversions with rne(|I| / bin_width) == b, a device tensor)."""
+    cum = torch.cumsum(hist.to(torch.float64), 0)
+    b = int(torch.searchsorted(cum, quantile * float(cum[-1])).item())
+    return float(2.0 ** math.ceil(math.log2(max((b + 0.5) * bin_width, bin_width))))
 
 
 class CrossbarLayer:
@@ -34,10 +45,12 @@ class CrossbarLayer:
 
     def forward(self, x, step, ws):
         ops = self.net.ops
-        if self.net.calibrating:
+        if self.net.calibrating and self.net.adc_quantile is None:
             self.seen_x = self.x_scale = ops.absmax(x) or 1.0
         ops.tile(self.cfg, self.W, self.w_max, step, planes=self.planes)
         self.x = x
+        if self.net.adc_quantile is not None:
+            self.cfg.adc_fs_fwd = self._measured_range(xb.OP_FWD, x, self.x_scale, self.cfg.xbar_rows, ws)
         if self.geom is None:
             return ops.fwd(self.cfg, self.planes, x, self.N, self.w_max, self.x_scale, ws=ws)
         return ops.conv_fwd(self.cfg, self.planes, x, self.geom, self.N, self.w_max, self.x_scale, ws=ws)
@@ -46,8 +59,10 @@ class CrossbarLayer:
         """Error to the layer input through the same conductances, then the in-place write of W (skipped
         while the ranges are being calibrated)."""
         ops = self.net.ops
-        if self.net.calibrating:
+        if self.net.calibrating and self.net.adc_quantile is None:
             self.seen_g = self.g_scale = ops.absmax(dy) or 1.0
+        if self.net.adc_quantile is not None:
+            self.cfg.adc_fs_bwd = self._measured_range(xb.OP_BWD, dy, self.g_scale, self.cfg.xbar_cols, ws)
         dx = None
         pulse = self.net.pulse
         if self.geom is None:
@@ -69,6 +84,19 @@ class CrossbarLayer:
             if not self.net.calibrating:
                 ops.conv_update(self.cfg, self.W, self.x, dy, self.geom, self.w_max, 1.0 / self.w_max, lr, step, ws=ws)
         return dx
+
+    def _measured_range(self, op, inp, in_scale, driven_lines, ws):
+        """Converter range of one pass from the currents this input causes (statistics pass of the library)."""
+        ops, cfg = self.net.ops, self.cfg
+        # bins over everything a tile can carry: all driven lines at the top input level into full-level devices
+        # (twice that for a single array with its off-state current)
+        top = driven_lines * ((1 << cfg.stream_bits) - 1) * ((1 << cfg.slice_bits) - 1) * (2 if cfg.flags & xb.ADC_PER_ARRAY else 1)
+        bin_width = top / (xb.ADC_HIST_BINS - 1.0)
+        if self.geom is None:
+            hist = ops.adc_histogram(cfg, self.planes, inp, self.K, self.N, in_scale, op, bin_width, ws=ws)
+        else:
+            hist = ops.conv_adc_histogram(cfg, self.planes, inp, self.geom, self.N, in_scale, op, bin_width, ws=ws)
+        return range_from_histogram(hist, bin_width, self.net.adc_quantile)
 
     def workspace_bytes(self, batch_rows):
         if self.geom is None:
@@ -106,6 +134,7 @@ class Network:
     Subclasses provide forward(x, step), backward(dlogits, step, lr) and self.layers."""
     ops = xb
     calibrating = False
+    adc_quantile = None   # set while the converter ranges are being measured
     pulse = None     # dict(bl=slots per train, dw_min=state change per pulse): pulse-level updates of the dense layers
 
     def train_step(self, x, labels, lr):
@@ -117,10 +146,11 @@ class Network:
         self.step_no += 1
         return loss
 
-    def calibrate(self, x, labels):
+    def calibrate(self, x, labels, adc_quantile=None):
         """Fixes x_scale / g_scale of every crossbar layer from one batch: a forward / backward pass in
         which every layer takes the maximum it sees as its range and nothing is written; the ranges
-        then become those maxima times a head-room factor."""
+        then become those maxima times a head-room factor.  With adc_quantile a second such pass
+        measures the column currents of every layer and sets the converter ranges from them."""
         self.calibrating = True
         try:
             logits = self.forward(x, 0)
@@ -132,6 +162,19 @@ class Network:
             layer.x_scale = HEADROOM_X * layer.seen_x
             if layer.seen_g is not None:
                 layer.g_scale = HEADROOM_G * layer.seen_g
+        if adc_quantile is not None:
+            self._measure_adc_ranges(x, labels, adc_quantile)
+
+    def _measure_adc_ranges(self, x, labels, quantile):
+        self.adc_quantile = quantile                    # the layers keep their calibrated input ranges in this pass
+        self.calibrating = True                         # ... and nothing is written
+        try:
+            logits = self.forward(x, 0)
+            _, dlogits = self.ops.softmax_xent(logits, labels, 1.0 / x.shape[0])
+            self.backward(dlogits, 0, 0.0)
+        finally:
+            self.calibrating = False
+            self.adc_quantile = None
 
 
 class ResNetCifar(Network):

@@ -119,6 +119,8 @@ _SIGNATURES = {
     "xbar_absmax": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_adc_histogram": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
                                      C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_conv_adc_histogram": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_int,
+                                          C.c_float, C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                               C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_update_pulsed": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
@@ -460,6 +462,18 @@ def absmax(x, ws=None):
 
 
 ADC_HIST_BINS = 4096
+
+
+def conv_adc_histogram(cfg, planes, inp, geom, N, in_scale, op, bin_width, hist=None, ws=None):
+    """xbar_conv_adc_histogram: as adc_histogram for a convolution layer (inp: the image for OP_FWD, the errors for
+    OP_BWD)."""
+    ws = _conv_ws(cfg, op, geom, N, ws, inp.device)
+    if hist is None:
+        hist = torch.zeros(ADC_HIST_BINS, dtype=torch.int64, device=inp.device)
+    _check(lib().xbar_conv_adc_histogram(C.byref(cfg), C.c_void_p(planes.data_ptr()), _dev(inp), C.byref(geom), N, in_scale,
+                                         op, bin_width, _dev(hist, torch.int64), C.c_void_p(ws.data_ptr()), ws.numel(),
+                                         _stream()))
+    return hist
 
 
 def adc_histogram(cfg, planes, inp, K, N, in_scale, op, bin_width, hist=None, ws=None):

@@ -429,6 +429,31 @@ def test_offset_binary_convolution(xo, xb):
     assert rel_l2(dXg.cpu().numpy(), dXo) <= 1e-3
 
 
+def test_adc_range_statistics_of_a_convolution(xo, xb):
+    """The statistics pass of a convolution layer counts the currents of its patch matrix (forward: gathered from
+    the image) and of its error matrix (backward): the same counters as the dense pass on those matrices."""
+    from oracle import conv
+    rng = np.random.default_rng(23)
+    B, H, Wd, C, k, stride, pad, N, R = 2, 9, 9, 5, 3, 2, 1, 20, 64
+    X = rng.normal(size=(B, H, Wd, C)).astype(np.float32)
+    Wm = (rng.standard_t(4, size=(k * k * C, N)) * 0.05).astype(np.float32)
+    OH = conv.out_size(H, k, stride, pad)
+    dY = (rng.normal(size=(B, OH, OH, N)) * 1e-2).astype(np.float32)
+    cg = xb.make_config(xbar_rows=R, xbar_cols=R, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=2,
+                        flags=xb.INPUT_SIGNED | xb.NI_WIRE_AAM, seed=5)
+    geom = xb.conv_geom(B, H, Wd, C, k, k, stride, pad)
+    planes = xb.tile(cg, dev(Wm), float(np.abs(Wm).max()), 2)
+    cols = conv.im2col(X, k, k, stride, pad)
+    bw = 0.05
+    xs, gs = float(np.abs(X).max()), float(np.abs(dY).max())
+    got_f = xb.conv_adc_histogram(cg, planes, dev(X), geom, N, xs, xb.OP_FWD, bw)
+    want_f = xb.adc_histogram(cg, planes, dev(cols), k * k * C, N, xs, xb.OP_FWD, bw)
+    got_b = xb.conv_adc_histogram(cg, planes, dev(dY), geom, N, gs, xb.OP_BWD, bw)
+    want_b = xb.adc_histogram(cg, planes, dev(dY.reshape(-1, N)), k * k * C, N, gs, xb.OP_BWD, bw)
+    torch.cuda.synchronize()
+    assert torch.equal(got_f, want_f) and torch.equal(got_b, want_b) and int(got_f.sum()) > 0 and int(got_b.sum()) > 0
+
+
 @pytest.mark.parametrize("ni,R,sb,M,K,N", [("ideal", 64, 2, 50, 200, 70), ("aam", 128, 1, 40, 300, 100),
                                           ("aam+var", 256, 4, 33, 520, 48), ("aam+pa", 128, 1, 40, 300, 100)])
 def test_adc_range_statistics(xo, xb, ni, R, sb, M, K, N):
