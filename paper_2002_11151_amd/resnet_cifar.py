@@ -41,13 +41,20 @@ class CrossbarLayer:
         self.x_scale = self.g_scale = 1.0
         self.planes = torch.empty(xb.planes_bytes(self.cfg, K, N), dtype=torch.uint8, device=device)
         self.x = None
+        self.profile = None                # stored wire distortion (with the profile flag), refreshed by forward()
         self.seen_x = self.seen_g = None   # set while the ranges are being calibrated
 
     def forward(self, x, step, ws):
         ops = self.net.ops
         if self.net.calibrating and self.net.adc_quantile is None:
             self.seen_x = self.x_scale = ops.absmax(x) or 1.0
-        ops.tile(self.cfg, self.W, self.w_max, step, planes=self.planes)
+        if self.cfg.flags & xb.NI_WIRE_PROFILE:
+            # the circuit-level model every `fcm_every` steps, its stored distortion profile in between (Sec. IV-D)
+            if self.profile is None or step % self.net.fcm_every == 0:
+                self.profile = ops.fcm_profile(self.cfg, self.W, self.w_max, step, ws=ws, profile=self.profile)
+            ops.tile(self.cfg, self.W, self.w_max, step, self.profile, planes=self.planes)
+        else:
+            ops.tile(self.cfg, self.W, self.w_max, step, planes=self.planes)
         self.x = x
         if self.net.adc_quantile is not None:
             self.cfg.adc_fs_fwd = self._measured_range(xb.OP_FWD, x, self.x_scale, self.cfg.xbar_rows, ws)
@@ -99,10 +106,11 @@ class CrossbarLayer:
         return range_from_histogram(hist, bin_width, self.net.adc_quantile)
 
     def workspace_bytes(self, batch_rows):
+        fcm = xb.workspace_bytes(self.cfg, xb.OP_FCM, 1, self.K, self.N) if self.cfg.flags & xb.NI_WIRE_PROFILE else 0
         if self.geom is None:
-            return max(xb.workspace_bytes(self.cfg, op, batch_rows, self.K, self.N)
-                       for op in (xb.OP_FWD, xb.OP_BWD, xb.OP_UPDATE, xb.OP_UPDATE_PULSED))
-        return max(xb.conv_workspace_bytes(self.cfg, op, self.geom, self.N) for op in (0, 1, 2))
+            return max(fcm, *(xb.workspace_bytes(self.cfg, op, batch_rows, self.K, self.N)
+                              for op in (xb.OP_FWD, xb.OP_BWD, xb.OP_UPDATE, xb.OP_UPDATE_PULSED)))
+        return max(fcm, *(xb.conv_workspace_bytes(self.cfg, op, self.geom, self.N) for op in (0, 1, 2)))
 
 
 class BatchNorm:
@@ -134,6 +142,7 @@ class Network:
     Subclasses provide forward(x, step), backward(dlogits, step, lr) and self.layers."""
     ops = xb
     calibrating = False
+    fcm_every = 1         # with the stored-profile wire model: steps between two runs of the circuit-level model
     adc_quantile = None   # set while the converter ranges are being measured
     pulse = None     # dict(bl=slots per train, dw_min=state change per pulse): pulse-level updates of the dense layers
 

@@ -290,3 +290,36 @@ def test_converter_ranges_from_current_statistics():
         assert np.isfinite(losses).all()
         final[q] = float(np.mean(losses[-5:]))
     assert final[0.999] < final[None] + 0.1, final          # measured here: 1.33 against 1.87
+
+def test_interpolated_circuit_model_in_training():
+    """Sec. IV-D: the circuit-level crossbar model is run every L iterations and its stored distortion profile is
+    reused in between.  The driver does that when the layers use the stored-profile wire model; the profile is
+    computed once per L steps and the network learns the fixed batch."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import sequential, xbar as xb
+
+    class Counting:
+        def __init__(self):
+            self.solves = 0
+
+        def __getattr__(self, name):
+            if name == "fcm_profile":
+                self.solves += 1
+            return getattr(xb, name)
+
+    kw = workloads.config_kwargs("mlp")
+    kw["flags"] = (kw["flags"] & ~workloads.NI_WIRE_AAM) | workloads.NI_WIRE_PROFILE
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    B = 64
+    images = torch.rand((B, 784), generator=gen, device="cuda")
+    labels = (torch.arange(B, device="cuda") % 10).to(torch.int32)
+    net = sequential.Sequential(kw, sequential.mlp_spec((500,), 10), batch=B, in_shape=(784,), signed_input=False, seed=2)
+    net.fcm_every = 10
+    net.calibrate(images, labels)
+    net.ops = Counting()
+    losses = [float(net.train_step(images, labels, 0.01).mean()) for _ in range(40)]
+    assert net.ops.solves == 2 * 4                              # two layers, steps 0, 10, 20, 30
+    assert all(0.0 <= float(layer.profile.min()) and float(layer.profile.max()) < 0.5 for layer in net.layers)
+    assert np.isfinite(losses).all() and np.mean(losses[-5:]) < 0.9 * losses[0], losses
