@@ -155,3 +155,12 @@ def test_argument_checks_precede_any_device_work(xb):
     for code in range(-6, 1):
         assert xb.strerror(code) and "unknown" not in xb.strerror(code)
     assert "unknown" in xb.strerror(-99)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert run.returncode != 0 and "one GPU" in run.stderr and run.stdout.strip() == ""
