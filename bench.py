@@ -108,6 +108,16 @@ def end_to_end(args, torch, workloads, xb, device):
         loss = net.train_step(images, labels, 0.01)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    graph_ms = None
+    if args.graph:                     # the same steps replayed from a captured HIP graph (one launch per step)
+        net.ops = xb
+        net.capture(images, labels, 0.01)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            net.replay(images, labels)
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t1) / args.steps * 1e3
     vmm_ms = sum(events.elapsed_ms(a, b) for a, b in records)
     emulated = tot["fwd"] + tot["bwd"] + tot["upd"]
     achieved = 2.0 * (tot["fwd"] + tot["bwd"]) * args.steps / (vmm_ms * 1e-3) / 1e12
@@ -124,6 +134,7 @@ def end_to_end(args, torch, workloads, xb, device):
                                 kw["adc_bits"]),
                    "emulated_macs_per_step": emulated, "logical_macs_per_step": tot["logical"]},
         "final_loss": round(float(loss.mean()), 4),
+        "ms_per_step_from_hip_graph": None if graph_ms is None else round(graph_ms, 3),
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / FP16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
                      "kernel": "vmm_kernel (MFMA contraction + ADC + shift-and-add, fwd and bwd launches)",
@@ -155,6 +166,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --end-to-end: also time the training step replayed from a captured HIP graph")
     ap.add_argument("--pulsed-update", action="store_true",
                     help="pulse-level update (stochastic pulse trains of 31 slots, one sample at a time) instead of "
                          "the aggregate write")

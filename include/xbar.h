@@ -145,6 +145,18 @@ size_t xbar_planes_bytes(const xbar_config* cfg, int K, int N);
 int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max, uint64_t step,
               const float* profile, void* planes, size_t planes_bytes, void* hip_stream);
 
+/*
+ * Step counter in device memory, for callers that replay a captured HIP graph of a training step: kernel
+ * arguments are frozen in a graph, so the `step` that keys the device variation (Sec. IV-A) and the write
+ * noise (Sec. IV-C) would repeat.  After xbar_set_step_source(p) every later call of this host thread that
+ * takes a `step` (xbar_tile, xbar_update, xbar_conv_update, xbar_update_pulsed, xbar_fcm_profile) uses
+ * step + *p, read by the kernels when they run; NULL switches it off.  p: 8-byte aligned device address that
+ * stays valid while such kernels may run.  xbar_step_advance enqueues *p += 1 on the stream (one thread, no
+ * memset: it can be part of the graph).
+ */
+void xbar_set_step_source(const unsigned long long* device_step);
+int xbar_step_advance(unsigned long long* device_step, void* hip_stream);
+
 /* Bytes of scratch memory that xbar_fwd / xbar_bwd / xbar_update need for this shape. */
 size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N);
 

@@ -29,6 +29,7 @@ struct FcmArgs {
   double g_min, dg, var_sigma, r_row, r_col, r_source, r_sense, tol2;
   float w_max;
   uint64_t seed, step;
+  const unsigned long long* step_add;   // optional device counter added to step
 };
 
 // Sum over the 256 threads of the block, returned to all of them; fixed order.
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(256) void fcm_kernel(FcmArgs a) {
   double* r = y + rc;
   double* p = r + rc;
   double* q = p + rc;
-  NormalStream rng(a.seed, kStreamVariation, a.step);
+  NormalStream rng(a.seed, kStreamVariation, effective_step(a.step, a.step_add));
 
   for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
     const int group = item % a.groups;
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(NT) void fcm_onchip_kernel(FcmArgs a) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int tx = tid & 15, ty = tid >> 4;
   const int i0 = ty * SR, j0 = tx * SC;
-  NormalStream rng(a.seed, kStreamVariation, a.step);
+  NormalStream rng(a.seed, kStreamVariation, effective_step(a.step, a.step_add));
 
   for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
     const int group = item % a.groups;
@@ -497,7 +498,7 @@ int xbar_fcm_profile(const xbar_config* cfg, const float* W, int K, int N, float
   a.r_row = (double)cfg->r_row; a.r_col = (double)cfg->r_col;
   a.r_source = (double)cfg->r_source; a.r_sense = (double)cfg->r_sense;
   a.tol2 = 1e-22;                                   // relative residual 1e-11
-  a.w_max = w_max; a.seed = cfg->seed; a.step = step;
+  a.w_max = w_max; a.seed = cfg->seed; a.step = step; a.step_add = current_step_source();
   hipStream_t st = reinterpret_cast<hipStream_t>(hip_stream);
   if (p.onchip) {
     const void* fn = p.onchip == 128 ? reinterpret_cast<const void*>(&fcm_onchip_kernel<8, 8, 256>)

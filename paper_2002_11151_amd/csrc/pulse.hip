@@ -29,6 +29,7 @@ struct PulseArgs {
   uint32_t flags;
   double w_max, x_range, d_range, dw_min, v, sigma;
   uint64_t seed, step;
+  const unsigned long long* step_add;   // optional device counter added to step
 };
 
 __device__ __forceinline__ uint32_t pulse_train(uint32_t k0, uint32_t k1, uint64_t step, uint64_t index, double p, int bl) {
@@ -54,14 +55,14 @@ __global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
     const double x = (double)a.X[index];
     const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseRows);
     const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseRows);
-    a.rows[t] = pulse_train(k0, k1, a.step, index, ::fabs(x) / a.x_range, a.bl) | (x < 0.0 ? 0x80000000u : 0u);
+    a.rows[t] = pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(x) / a.x_range, a.bl) | (x < 0.0 ? 0x80000000u : 0u);
   } else if (t < n_rows + n_cols) {
     const long long u = t - n_rows;
     const uint64_t index = (uint64_t)a.m0 * a.N + (uint64_t)u;
     const double d = (double)a.D[index];
     const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseCols);
     const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseCols);
-    a.cols[u] = pulse_train(k0, k1, a.step, index, ::fabs(d) / a.d_range, a.bl) | (d < 0.0 ? 0x80000000u : 0u);
+    a.cols[u] = pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(d) / a.d_range, a.bl) | (d < 0.0 ? 0x80000000u : 0u);
   }
 }
 
@@ -77,7 +78,7 @@ __device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool u
   }
   double next = g + (up ? 1.0 : -1.0) * move;
   if constexpr (NOISE) {
-    NormalStream rng(a.seed, kStreamPulseNoise, (a.step << 31) | dev);
+    NormalStream rng(a.seed, kStreamPulseNoise, (effective_step(a.step, a.step_add) << 31) | dev);
     next += a.sigma * rng.get((uint64_t)m * 32 + (uint64_t)ord);
   }
   return clampd(next, -1.0, 1.0);
@@ -263,7 +264,7 @@ int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const f
   // before the learning rate, and this scheme's mean equals the aggregate update at lr = bl dw_min w_max / (x_range d_range)
   const double lr_eq = (double)bl * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
   a.sigma = (double)cfg->upd_noise_gamma * std::sqrt(lr_eq * (double)dw_min);
-  a.seed = cfg->seed; a.step = step;
+  a.seed = cfg->seed; a.step = step; a.step_add = current_step_source();
   // 4 x 4 devices per thread when that still fills the chip, else one device per thread
   const bool patch4 = (long long)cdiv(K, 64) * cdiv(N, 64) >= 512;
   const int edge = patch4 ? 64 : 16;

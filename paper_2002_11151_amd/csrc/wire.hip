@@ -24,6 +24,7 @@ struct WireArgs {
   double g_min, dg, var_sigma, r_row, r_col, r_source, r_sense;
   float w_max;
   uint64_t seed, step;
+  const unsigned long long* step_add;   // optional device counter added to step
 };
 
 __global__ __launch_bounds__(256) void wire_quantize_kernel(WireArgs a) {
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256) void wire_rows_kernel(WireArgs a) {
   const int cpl = (a.C + 63) >> 6;
   const int i_end = min(rows, (quarter + 1) * (a.R / 4));
   const size_t pol_stride = (size_t)a.K * a.N;
-  NormalStream rng(a.seed, kStreamVariation, a.step);
+  NormalStream rng(a.seed, kStreamVariation, effective_step(a.step, a.step_add));
   for (int i = quarter * (a.R / 4) + wave; i < i_end; i += 4) {
     double l0[4][2], l1[4][2];                       // inclusive prefixes inside the lane
     double run0[2] = {0.0, 0.0}, run1[2] = {0.0, 0.0};
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(256) void wire_cols_kernel(WireArgs a) {
   const int j = strip * 64 + lane;
   const bool active = j < cols;
   const int i_begin = seg * (a.R / 4), i_end = min(rows, i_begin + a.R / 4);
-  NormalStream rng(a.seed, kStreamVariation, a.step);
+  NormalStream rng(a.seed, kStreamVariation, effective_step(a.step, a.step_add));
   double t0[2] = {0.0, 0.0}, t1[2] = {0.0, 0.0};
   if (active)
     for (int i = i_begin; i < i_end; ++i) {
@@ -204,7 +205,7 @@ int launch_wire_model(const xbar_config* cfg, const float* W, int K, int N, floa
   w.var_sigma = (double)cfg->var_sigma;
   w.r_row = (double)cfg->r_row; w.r_col = (double)cfg->r_col;
   w.r_source = (double)cfg->r_source; w.r_sense = (double)cfg->r_sense;
-  w.w_max = w_max; w.seed = cfg->seed; w.step = step;
+  w.w_max = w_max; w.seed = cfg->seed; w.step = step; w.step_add = current_step_source();
   const unsigned tiles = (unsigned)(cdiv(K, cfg->xbar_rows) * w.tiles_c);
   hipLaunchKernelGGL(wire_quantize_kernel, dim3((unsigned)(((size_t)K * N + 255) / 256)), dim3(256), 0, st, w);
   if (hipGetLastError() != hipSuccess) return XBAR_EHIP;

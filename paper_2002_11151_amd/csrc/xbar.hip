@@ -42,6 +42,7 @@ struct TileArgs {
   double g_min, dg, var_sigma, r_row, r_col, r_source, r_sense, hi_scale, hi_inv_scale;
   float w_max;
   uint64_t seed, step;
+  const unsigned long long* step_add;   // optional device counter added to step
   long long n_threads;
 };
 
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(256) void tile_planes_kernel(TileArgs a) {
   const int Lc = TRANSPOSED ? a.N : a.K;          // contraction length
   const int Lo = TRANSPOSED ? a.K : a.N;
 
-  NormalStream rng(a.seed, kStreamVariation, a.step);
+  NormalStream rng(a.seed, kStreamVariation, effective_step(a.step, a.step_add));
   const double qw = (double)((1u << a.weight_bits) - 1);
   const uint32_t dmask = (1u << a.slice_bits) - 1;
 
@@ -957,6 +958,7 @@ struct WriteArgs {
   uint32_t flags;
   double w_max, grad_scale, lr, v, gamma;
   uint64_t seed, step;
+  const unsigned long long* step_add;   // optional device counter added to step
 };
 
 // 32 consecutive weights per block; the 8 thread groups of a block add up interleaved subsets of the
@@ -984,7 +986,7 @@ __global__ __launch_bounds__(256) void update_write_kernel(WriteArgs a) {
     else if (change < 0.0) written = delta * ::exp(-a.v * (1.0 - x));
   }
   if (a.flags & XBAR_NI_UPD_NOISE) {
-    NormalStream rng(a.seed, kStreamWrite, a.step);
+    NormalStream rng(a.seed, kStreamWrite, effective_step(a.step, a.step_add));
     written += a.gamma * ::sqrt(::fabs(delta)) * rng.get((uint64_t)i);
   }
   const double g_new = clampd(g - a.lr * written, -1.0, 1.0);
@@ -1027,6 +1029,9 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters, 
 // host dispatch
 // ---------------------------------------------------------------------------------------------
 thread_local hipEvent_t g_trace_before = nullptr, g_trace_after = nullptr;
+thread_local const unsigned long long* g_step_source = nullptr;
+
+__global__ void step_advance_kernel(unsigned long long* counter) { *counter += 1ull; }
 
 struct VmmPlan {
   PlaneGeom g;
@@ -1277,13 +1282,17 @@ int run_update(const xbar_config* cfg, float* W, const float* X, const float* dY
   w.W = W; w.part = g.part; w.n = (long long)K * N; w.mchunks = p.mchunks * p.parts; w.flags = cfg->flags;
   w.w_max = (double)w_max; w.grad_scale = (double)grad_scale; w.lr = (double)lr;
   w.v = (double)cfg->upd_nl_v; w.gamma = (double)cfg->upd_noise_gamma;
-  w.seed = cfg->seed; w.step = step;
+  w.seed = cfg->seed; w.step = step; w.step_add = current_step_source();
   hipLaunchKernelGGL(update_write_kernel, dim3((unsigned)((w.n + 31) / 32)), dim3(256), 0, st, w);
   if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   return XBAR_OK;
 }
 
 }  // namespace
+
+namespace xbar_detail {
+const unsigned long long* current_step_source() { return g_step_source; }
+}  // namespace xbar_detail
 
 // ---------------------------------------------------------------------------------------------
 // C ABI
@@ -1298,6 +1307,14 @@ int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void*
   if (out_bytes < (size_t)512 * 256 * sizeof(float)) return XBAR_EWORKSPACE;
   hipLaunchKernelGGL(mfma_probe_kernel, dim3(512), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
                      reinterpret_cast<float*>(out), iters, mode);
+  return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
+}
+
+void xbar_set_step_source(const unsigned long long* device_step) { g_step_source = device_step; }
+
+int xbar_step_advance(unsigned long long* device_step, void* hip_stream) {
+  if (!device_step || (reinterpret_cast<uintptr_t>(device_step) & 7u)) return XBAR_EALIGN;
+  hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(1), 0, reinterpret_cast<hipStream_t>(hip_stream), device_step);
   return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
 }
 
@@ -1432,6 +1449,7 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
     a.w_max = w_max;
     a.seed = cfg->seed;
     a.step = step;
+    a.step_add = current_step_source();
     // every k-step that the contraction reads is written whole, padding included
     const int Lc = dir == 1 ? N : K;
     const long long chunks = (long long)cdiv(Lc, 16) * 2;

@@ -132,6 +132,13 @@ struct NormalStream {
   }
 };
 
+// Step of the random-number streams: the step argument of the call plus, when the caller has named one,
+// a counter in device memory -- a captured graph of a training step then draws new devices and new write
+// noise on every replay although its kernel arguments are frozen.
+__device__ __forceinline__ uint64_t effective_step(uint64_t step, const unsigned long long* step_add) {
+  return step + (step_add ? (uint64_t)*step_add : 0ull);
+}
+
 __device__ __forceinline__ double clampd(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
 
 __device__ __forceinline__ double wave_inclusive_scan(double x, int lane) {
@@ -168,6 +175,8 @@ XBAR_INTERNAL int launch_wire_model(const xbar_config* cfg, const float* W, int 
 // fcm.hip, pulse.hip: workspace sizes of xbar_fcm_profile and xbar_update_pulsed
 XBAR_INTERNAL size_t fcm_workspace_bytes(const xbar_config* cfg, int K, int N);
 XBAR_INTERNAL size_t pulsed_workspace_bytes(int M, int K, int N);
+// xbar.hip: the device counter named with xbar_set_step_source (this thread), or null
+XBAR_INTERNAL const unsigned long long* current_step_source();
 
 }  // namespace xbar_detail
 

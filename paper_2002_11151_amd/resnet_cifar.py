@@ -155,6 +155,47 @@ class Network:
         self.step_no += 1
         return loss
 
+    # ---- a training step as a HIP graph -----------------------------------------------------------
+    def capture(self, x, labels, lr):
+        """Captures one training step (fixed batch shape and learning rate) into a HIP graph: the step then costs one
+        graph launch instead of several hundred kernel launches, which is what bounds the small networks.  The
+        kernels' arguments are frozen in a graph, so the step number that keys the device variation and the write
+        noise comes from a counter in device memory that the graph itself advances.  Runs one real step (the
+        warm-up of the capture) and returns its losses; every `replay(x, labels)` is the next step."""
+        self._graph_x, self._graph_labels = x.clone(), labels.clone()
+        self._graph_counter = torch.full((1,), self.step_no, dtype=torch.int64, device=x.device)
+        main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+        side.wait_stream(main)
+        xb.set_step_source(self._graph_counter)
+        try:
+            with torch.cuda.stream(side):
+                first = self._counted_step(lr).clone()
+            main.wait_stream(side)
+            self._graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(self._graph, stream=side):
+                self._graph_loss = self._counted_step(lr)
+        finally:
+            xb.set_step_source(None)
+        self.step_no += 1
+        return first
+
+    def replay(self, x, labels):
+        """The next training step from the captured graph; returns the per-sample losses (a buffer that the next
+        replay overwrites)."""
+        self._graph_x.copy_(x)
+        self._graph_labels.copy_(labels)
+        self._graph.replay()
+        self.step_no += 1
+        return self._graph_loss
+
+    def _counted_step(self, lr):
+        # the step argument is 0: the kernels add the device counter, which the last kernel of the step advances
+        logits = self.forward(self._graph_x, 0)
+        loss, dlogits = self.ops.softmax_xent(logits, self._graph_labels, 1.0 / self._graph_x.shape[0])
+        self.backward(dlogits, 0, lr)
+        self.ops.step_advance(self._graph_counter)
+        return loss
+
     def calibrate(self, x, labels, adc_quantile=None):
         """Fixes x_scale / g_scale of every crossbar layer from one batch: a forward / backward pass in
         which every layer takes the maximum it sees as its range and nothing is written; the ranges

@@ -89,6 +89,8 @@ _SIGNATURES = {
     "xbar_bwd": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                            C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "xbar_trace_next_vmm": (None, [C.c_void_p, C.c_void_p]),
+    "xbar_set_step_source": (None, [C.c_void_p]),
+    "xbar_step_advance": (C.c_int, [C.c_void_p, C.c_void_p]),
     "xbar_probe_mfma_rate": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_fcm_profile": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_uint64, C.c_void_p,
                                    C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -271,6 +273,17 @@ def update_pulsed(cfg, W, X, dY, w_max, x_range, d_range, bl, dw_min, step=0, ws
                                     dw_min, step, None if pulses is None else C.c_void_p(pulses.data_ptr()),
                                     C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return (W, pulses) if want_pulses else W
+
+
+def set_step_source(counter):
+    """xbar_set_step_source: `counter` is a one-element int64 CUDA tensor whose value is added to every `step`
+    argument from now on (None switches it off).  Keep the tensor alive while it is in use."""
+    lib().xbar_set_step_source(None if counter is None else C.c_void_p(counter.data_ptr()))
+
+
+def step_advance(counter):
+    """xbar_step_advance: counter += 1 on the current stream."""
+    _check(lib().xbar_step_advance(C.c_void_p(counter.data_ptr()), _stream()))
 
 
 def fcm_profile(cfg, W, w_max, step=0, ws=None, profile=None):

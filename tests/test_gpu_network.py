@@ -323,3 +323,41 @@ def test_interpolated_circuit_model_in_training():
     assert net.ops.solves == 2 * 4                              # two layers, steps 0, 10, 20, 30
     assert all(0.0 <= float(layer.profile.min()) and float(layer.profile.max()) < 0.5 for layer in net.layers)
     assert np.isfinite(losses).all() and np.mean(losses[-5:]) < 0.9 * losses[0], losses
+
+@pytest.mark.parametrize("kind", ["perceptron", "residual"])
+def test_training_steps_from_a_hip_graph(kind):
+    """A captured training step replays as the following steps: the device-side step counter gives every replay
+    its own device variation and write noise, and weights and losses equal those of eagerly run steps bit for bit."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import resnet_cifar, sequential
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(11)
+    if kind == "perceptron":
+        kw = workloads.config_kwargs("mlp")
+        kw["flags"] |= workloads.NI_VARIATION
+        kw["var_sigma"] = 0.05
+        B = 32
+        batches = [torch.rand((B, 784), generator=gen, device="cuda") for _ in range(4)]
+        make = lambda: sequential.Sequential(kw, sequential.mlp_spec((500,), 10), batch=B, in_shape=(784,), signed_input=False, seed=2)
+    else:
+        kw = workloads.config_kwargs("resnet20")
+        B = 8
+        batches = [torch.randn((B, 16, 16, 3), generator=gen, device="cuda") for _ in range(4)]
+        make = lambda: resnet_cifar.ResNetCifar(kw, batch=B, n_blocks=1, image=16, classes=10, widths=(16, 32, 64), seed=1)
+    labels = [((torch.arange(B, device="cuda") + i) % 10).to(torch.int32) for i in range(4)]
+    eager, graphed = make(), make()
+    eager.calibrate(batches[0], labels[0])
+    graphed.calibrate(batches[0], labels[0])
+    want = [eager.train_step(x, l, 0.02).clone() for x, l in zip(batches, labels)]
+    got = [graphed.capture(batches[0], labels[0], 0.02).clone()]
+    for x, l in zip(batches[1:], labels[1:]):
+        torch.cuda.synchronize()                                  # eager work and synchronisation between the replays
+        got.append(graphed.replay(x, l).clone())
+    torch.cuda.synchronize()
+    for a, b in zip(got, want):
+        assert torch.equal(a, b)
+    for la, lb in zip(graphed.layers, eager.layers):
+        assert torch.equal(la.W, lb.W)
+    assert graphed.step_no == eager.step_no == 4
+    assert not torch.equal(want[0], want[1])

@@ -716,3 +716,48 @@ def test_error_paths_on_device(xo, xb):
     with pytest.raises(xb.XbarError, match="not supported"):
         xb.fwd(lut, planes, X, 64, 1.0, 1.0)
     torch.cuda.synchronize()
+
+
+def test_step_replays_from_a_hip_graph(xo, xb):
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset, no synchronisation), so a
+    whole tile / fwd / bwd / update step can be captured into a HIP graph.  Every replay, with eager work and
+    synchronisation in between, must give the eager result bit for bit."""
+    g = workloads.Gemm("t", 300, 100, 70, True, 1)
+    W0, X, dY = workloads.layer_tensors_np(g, seed=31)
+    cg = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, input_bits=8, stream_bits=1, adc_bits=8,
+                        flags=xb.INPUT_SIGNED | xb.NI_WIRE_AAM2 | xb.NI_VARIATION | xb.NI_UPD_NL | xb.NI_UPD_NOISE | xb.INPUT_OFFSET,
+                        var_sigma=0.05, seed=3, adc_fs_fwd=64.0, adc_fs_bwd=64.0)
+    w_max, xs, gs = float(np.abs(W0).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    K, N, M = g.K, g.N, g.M
+    Wm, Xd, Dd = dev(W0), dev(X), dev(dY)
+    W = torch.empty_like(Wm)
+    planes = torch.empty(xb.planes_bytes(cg, K, N), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(xb.workspace_bytes(cg, op, M, K, N) for op in (0, 1, 2)), dtype=torch.uint8, device="cuda")
+    Y, dX = torch.empty((M, N), device="cuda"), torch.empty((M, K), device="cuda")
+
+    def step():
+        W.copy_(Wm)
+        xb.tile(cg, W, w_max, 7, planes=planes)
+        xb.fwd(cg, planes, Xd, N, w_max, xs, ws=ws, out=Y)
+        xb.bwd(cg, planes, Dd, K, w_max, gs, ws=ws, out=dX)
+        xb.update(cg, W, Xd, Dd, w_max, 1.0 / w_max, 0.01, 7, ws=ws)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (Y, dX, W)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                              # warm-up on the capturing stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for replay in range(3):
+        for t in (Y, dX, W):
+            t.fill_(float("nan"))                           # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((Y, dX, W), want):
+            assert torch.equal(got, ref), replay
