@@ -166,6 +166,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=None, help="batch rows per layer for the oracle sample")
     ap.add_argument("--ideal", action="store_true", help="array non-idealities off (single-term operands)")
+    ap.add_argument("--xbar", type=int, default=0,
+                    help="crossbar rows = columns instead of the workload's preset (the paper's own runs use 64)")
     ap.add_argument("--graph", action="store_true",
                     help="with --end-to-end: also time the training step replayed from a captured HIP graph")
     ap.add_argument("--pulsed-update", action="store_true",
@@ -226,6 +228,9 @@ def main():
     kw = workloads.config_kwargs(args.workload)
     if args.adc_bits:
         kw["adc_bits"] = args.adc_bits
+    if args.xbar:
+        kw["xbar_rows"] = kw["xbar_cols"] = args.xbar
+        kw["adc_fs_fwd"] = kw["adc_fs_bwd"] = workloads.adc_full_scale(args.xbar, kw["stream_bits"], kw["slice_bits"])
     if args.ideal:
         kw["flags"] &= ~(workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE)
     if args.all_paths and kw["flags"] & workloads.NI_WIRE_AAM:
