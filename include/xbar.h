@@ -8,14 +8,16 @@
  * in (NULL = the default stream) and returns.  Scratch memory comes from the caller (`ws`); its
  * contents are undefined after a call and two calls that share one workspace must be ordered on one
  * stream.  Return value: XBAR_OK or a negative XBAR_E* code; no exception crosses this boundary and
- * the library keeps no state between calls (the one-shot instrumentation hook at the end aside).
+ * the library keeps no state between calls (two per-thread settings aside: the one-shot instrumentation
+ * hook at the end and the optional step counter of xbar_set_step_source).
  *
  * A layer is the GEMM  Y[M x N] = X[M x K] . W[K x N]:  K = fan-in = crossbar rows, N = fan-out =
  * crossbar columns, M = batch (times output positions after im2col).  The weight matrix is cut into
  * crossbar instances of xbar_rows x xbar_cols devices; every weight is stored as
  * S_w = weight_bits / slice_bits devices of slice_bits each (least significant slice first) in a
  * positive or a negative array; inputs are streamed in S_in = input_bits / stream_bits cycles of
- * stream_bits each; signed inputs are applied in two phases (positive part, negative part).
+ * stream_bits each; signed inputs are applied in two phases (positive part, negative part), or in one
+ * phase of offset-binary codes with XBAR_INPUT_OFFSET.
  * Model after TxSim (arXiv 2002.11151): Sec. IV (layer = DAC -> array -> ADC, forward and
  * backward), Sec. IV-A (non-ideal conductance matrix generator), Sec. IV-B (three-stage model),
  * Sec. IV-C (update model), Sec. IV-D (approximate analytical wire model, stored distortion
