@@ -37,7 +37,7 @@ class CrossbarLayer:
         self.cfg = xb.make_config(**dict(cfg_kwargs, flags=flags))
         self.K, self.N, self.geom = K, N, geom
         self.W = torch.randn((K, N), generator=gen, device=device, dtype=torch.float32) * math.sqrt(2.0 / K)
-        self.w_max = HEADROOM_W * xb.absmax(self.W)
+        self.w_max = HEADROOM_W * net.ops.absmax(self.W)
         self.x_scale = self.g_scale = 1.0
         self.planes = torch.empty(xb.planes_bytes(self.cfg, K, N), dtype=torch.uint8, device=device)
         self.x = None

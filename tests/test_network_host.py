@@ -1,0 +1,167 @@
+"""Host logic of the network drivers (no GPU): what they call, in which order and with which ranges.  The
+binding is replaced by a stand-in with the same functions on CPU tensors; the size queries still come from the
+library (host code)."""
+import math
+
+import numpy as np
+import pytest
+
+import workloads
+
+torch = pytest.importorskip("torch")
+
+
+class StandIn:
+    """Records every call; the crossbar operations are ideal matrix products, enough for the drivers to run."""
+
+    def __init__(self, xb):
+        self.xb, self.calls = xb, []
+
+    def __getattr__(self, name):
+        if name.startswith("OP_") or name in ("ADC_HIST_BINS", "ADC_PER_ARRAY", "NI_WIRE_PROFILE"):
+            return getattr(self.xb, name)
+        raise AttributeError(name)
+
+    def _log(self, name, **kw):
+        self.calls.append((name, kw))
+
+    def absmax(self, x):
+        return float(x.abs().max())
+
+    def tile(self, cfg, W, w_max, step=0, profile=None, planes=None):
+        self._log("tile", step=step, profile=profile is not None)
+        self.W = W
+        return planes
+
+    def fwd(self, cfg, planes, x, N, w_max, x_scale, ws=None):
+        self._log("fwd", x_scale=x_scale, fs=cfg.adc_fs_fwd)
+        return x @ self.W
+
+    def bwd(self, cfg, planes, dy, K, w_max, g_scale, ws=None):
+        self._log("bwd", g_scale=g_scale, fs=cfg.adc_fs_bwd)
+        return dy @ self.W[:, : dy.shape[1]].t() if self.W.shape[1] == dy.shape[1] else torch.zeros((dy.shape[0], K))
+
+    def update(self, cfg, W, x, dy, w_max, grad_scale, lr, step, ws=None):
+        self._log("update", step=step, lr=lr, grad_scale=grad_scale)
+
+    def update_pulsed(self, cfg, W, x, dy, w_max, x_range, d_range, bl, dw_min, step, ws=None):
+        self._log("update_pulsed", x_range=x_range, d_range=d_range, bl=bl, dw_min=dw_min, w_max=w_max)
+
+    def fcm_profile(self, cfg, W, w_max, step=0, ws=None, profile=None):
+        self._log("fcm_profile", step=step)
+        return torch.zeros(1)
+
+    def adc_histogram(self, cfg, planes, inp, K, N, in_scale, op, bin_width, ws=None):
+        self._log("adc_histogram", op=op, bin_width=bin_width)
+        hist = torch.zeros(4096, dtype=torch.int64)
+        hist[10], hist[100], hist[2000] = 900, 99, 1               # 99.9 % of the currents below bin 101
+        return hist
+
+    def relu_fwd(self, x):
+        return torch.relu(x)
+
+    def relu_bwd(self, y, d):
+        return d * (y > 0)
+
+    def softmax_xent(self, logits, labels, scale):
+        p = torch.softmax(logits, 1)
+        onehot = torch.nn.functional.one_hot(labels.long(), logits.shape[1])
+        return -torch.log(p[torch.arange(len(labels)), labels.long()]), scale * (p - onehot)
+
+
+@pytest.fixture()
+def net_and_ops():
+    from paper_2002_11151_amd import resnet_cifar, sequential, xbar as xb
+    xb.lib()
+    ops = StandIn(xb)
+
+    def make(**flags_kw):
+        kw = workloads.config_kwargs("mlp")
+        kw.update(flags_kw)
+        resnet_cifar.Network.ops = ops                       # the layers read their weight range through it
+        try:
+            net = sequential.Sequential(kw, sequential.mlp_spec((20,), 5), batch=6, in_shape=(12,), signed_input=False,
+                                        seed=1, device="cpu")
+        finally:
+            resnet_cifar.Network.ops = xb
+        net.ops = ops
+        return net
+
+    return make, ops
+
+
+def _batch():
+    g = torch.Generator().manual_seed(0)
+    return torch.rand((6, 12), generator=g), (torch.arange(6) % 5).to(torch.int32)
+
+
+def test_calibration_then_step_order(net_and_ops):
+    make, ops = net_and_ops
+    net = make()
+    x, labels = _batch()
+    net.calibrate(x, labels)
+    assert not [c for c in ops.calls if c[0].startswith("update")]                    # nothing is written while calibrating
+    l0, l1 = net.layers
+    assert l0.x_scale == pytest.approx(1.5 * float(x.abs().max())) and l1.g_scale > 0
+    ops.calls.clear()
+    net.train_step(x, labels, 0.05)
+    names = [c[0] for c in ops.calls]
+    assert names == ["tile", "fwd", "tile", "fwd", "bwd", "update", "update"]          # no error goes back to the input
+    assert all(c[1]["step"] == 0 for c in ops.calls if c[0] in ("tile", "update")) and net.step_no == 1
+    assert [c[1]["x_scale"] for c in ops.calls if c[0] == "fwd"] == [l0.x_scale, l1.x_scale]
+    upd = [c[1] for c in ops.calls if c[0] == "update"]
+    assert upd[0]["lr"] == 0.05 and upd[0]["grad_scale"] == pytest.approx(1.0 / l1.w_max)
+
+
+def test_circuit_model_refresh_schedule(net_and_ops):
+    make, ops = net_and_ops
+    flags = (workloads.config_kwargs("mlp")["flags"] & ~workloads.NI_WIRE_AAM) | workloads.NI_WIRE_PROFILE
+    net = make(flags=flags)
+    net.fcm_every = 3
+    x, labels = _batch()
+    net.calibrate(x, labels)
+    ops.calls.clear()
+    for _ in range(7):
+        net.train_step(x, labels, 0.01)
+    assert [c[1]["step"] for c in ops.calls if c[0] == "fcm_profile"] == [0, 0, 3, 3, 6, 6]     # two layers
+    assert all(c[1]["profile"] for c in ops.calls if c[0] == "tile")
+
+
+def test_pulse_ranges_follow_the_learning_rate(net_and_ops):
+    make, ops = net_and_ops
+    net = make()
+    net.pulse = dict(bl=31, dw_min=1e-3)
+    x, labels = _batch()
+    net.calibrate(x, labels)
+    ops.calls.clear()
+    net.train_step(x, labels, 0.02)
+    pulsed = [c[1] for c in ops.calls if c[0] == "update_pulsed"]
+    assert len(pulsed) == 2 and not [c for c in ops.calls if c[0] == "update"]
+    for p, layer in zip(pulsed, reversed(net.layers)):
+        assert p["x_range"] == layer.x_scale
+        # mean written change = lr x dy / w_max  <=>  lr = bl dw_min w_max / (x_range d_range)
+        assert 31 * 1e-3 * p["w_max"] / (p["x_range"] * p["d_range"]) == pytest.approx(0.02)
+
+
+def test_converter_ranges_from_the_histograms(net_and_ops):
+    from paper_2002_11151_amd import resnet_cifar
+    make, ops = net_and_ops
+    net = make()
+    x, labels = _batch()
+    ops.calls.clear()
+    net.calibrate(x, labels, adc_quantile=0.999)
+    hists = [c[1] for c in ops.calls if c[0] == "adc_histogram"]
+    assert [h["op"] for h in hists] == [0, 0, 1, 1]                                    # forward of both layers, then backward
+    kw = workloads.config_kwargs("mlp")
+    bw = 128 * 15 * 3 / 4095.0                                                        # all rows, top input level, full-level devices
+    assert hists[0]["bin_width"] == pytest.approx(bw)
+    want = 2.0 ** math.ceil(math.log2(100.5 * bw))                                    # 99.9 % of the counts end in bin 100
+    for layer in net.layers:
+        assert layer.cfg.adc_fs_fwd == want and layer.cfg.adc_fs_bwd == want
+    assert not [c for c in ops.calls if c[0].startswith("update")]
+    # the rule itself
+    hist = torch.zeros(4096, dtype=torch.int64)
+    hist[3] = 10
+    assert resnet_cifar.range_from_histogram(hist, 0.5, 0.5) == 2.0                   # (3 + 0.5) * 0.5 = 1.75 -> 2
+    hist[4000] = 10
+    assert resnet_cifar.range_from_histogram(hist, 0.5, 0.99) == 2048.0
