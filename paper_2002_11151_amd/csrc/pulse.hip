@@ -67,9 +67,11 @@ __global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
 }
 
 // One pulse of device `dev` (ordinal `ord` within sample m), upwards when `up`.  The device model is
-// chosen at compile time: nothing that is the same for all lanes is tested inside the per-lane walk.
+// chosen at compile time, and the step of the noise stream is read before the walk: nothing that is the
+// same for all lanes is tested (and no pointer that may be null is followed) inside the per-lane walk.
 template <bool NL, bool NOISE>
-__device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool up, int m, int ord, uint64_t dev) {
+__device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool up, int m, int ord, uint64_t dev,
+                                            uint64_t step) {
 #pragma clang fp contract(off)   // every product and sum rounds on its own
   double move = a.dw_min;
   if constexpr (NL) {
@@ -78,7 +80,7 @@ __device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool u
   }
   double next = g + (up ? 1.0 : -1.0) * move;
   if constexpr (NOISE) {
-    NormalStream rng(a.seed, kStreamPulseNoise, (effective_step(a.step, a.step_add) << 31) | dev);
+    NormalStream rng(a.seed, kStreamPulseNoise, (step << 31) | dev);
     next += a.sigma * rng.get((uint64_t)m * 32 + (uint64_t)ord);
   }
   return clampd(next, -1.0, 1.0);
@@ -103,6 +105,7 @@ __global__ __launch_bounds__(256) void pulse_apply_kernel(PulseArgs a) {
   const int kt = (blockIdx.x / nb) * TE, nt = (blockIdx.x % nb) * TE;
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int k0 = kt + P * ty, n0 = nt + P * tx;
+  const uint64_t step = effective_step(a.step, a.step_add);
   double g[P][P];
   int cnt[P][P];
 #pragma unroll
@@ -191,7 +194,7 @@ __global__ __launch_bounds__(256) void pulse_apply_kernel(PulseArgs a) {
             ord = 0;
           }
           q &= q - 1;
-          gs = one_pulse<NL, NOISE>(a, gs, up, m, ord, dev);
+          gs = one_pulse<NL, NOISE>(a, gs, up, m, ord, dev, step);
           ++ord;
           moved += up ? 1 : -1;
         }
