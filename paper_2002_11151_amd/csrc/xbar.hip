@@ -307,7 +307,7 @@ __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
 struct VmmArgs {
   const u32x2* A;      // quantised input fragments, 8 magnitudes (bytes) per lane
   const u32x4* B;      // plane fragments of this direction
-  void* part;          // [nchunk][M][Lout] int32 (narrow) or int64 (wide)
+  void* part;          // [nchunk][M][Lout] int32 (narrow) or int64 (wide, split)
   int16_t* codes;      // optional [P][S_in][S_w][npol][T][M][Lout]
   unsigned long long* hist;   // optional: kStatBins counters of |code| instead of the codes themselves
   int dac_levels;             // 0: equidistant DAC levels; else 2^stream_bits entries of dac_lut are used
@@ -320,6 +320,7 @@ struct VmmArgs {
   size_t pol_stride;          // 16-byte units between the planes of the two arrays
   int S_w, S_in, slice_bits, stream_bits, ks, tile;
   int vt_per_chunk, nchunk, lds_kb;
+  int split_sg;               // slices per 32-bit group of the split wide path
   int direct;                 // single chunk and nothing to correct: the kernel scales and stores the result itself
   int total_wg, per_xcd;
   float gain;          // float(Q) / adc_fs
@@ -487,8 +488,8 @@ __device__ __forceinline__ void adc_sign_and_range(const VmmArgs& a, int p, int 
 // Software-pipelined slice group (fast path: 32-bit accumulators, no code tap, even slice count).
 template <int PM, int KSMAX, int NK, int TERMS, bool PER_ARRAY>
 __device__ __forceinline__ void vmm_tile_group_pipelined(const VmmArgs& a, const u32x4* lds,
-                                                         const u32x2 (&raw)[PM][KSMAX], int ns, int sg0, int p, int pol,
-                                                         int lane, uint32_t (&y)[PM][16]) {
+                                                         const u32x2 (&raw)[PM][KSMAX], int ns, int shift_slice0, int p,
+                                                         int pol, int lane, uint32_t (&y)[PM][16]) {
   constexpr int NF = TERMS * NK;
   const uint32_t digit_mask8 = ((1u << a.stream_bits) - 1u) * 0x01010101u;
   float gain_p, clamp_lo, clamp_hi;
@@ -508,7 +509,7 @@ __device__ __forceinline__ void vmm_tile_group_pipelined(const VmmArgs& a, const
 #pragma unroll
       for (int j = 0; j < NK; ++j) ab[pm][j] = digit_fragment(raw[pm][j], mask8);
     for (int sl = 0; sl < ns; sl += 2) {
-      const int sh0 = a.slice_bits * (sg0 + sl) + in_shift;
+      const int sh0 = a.slice_bits * (shift_slice0 + sl) + in_shift;
       const int sh1 = sh0 + a.slice_bits;
       // even slice -> acc0, while the ADC of the previous odd slice (acc1) runs
       if (b == 0 && sl == 0)
@@ -623,9 +624,12 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
 
 // One virtual tile (phase, contraction tile): load the raw magnitudes, then loop over slice groups:
 // stage the plane fragments of the group in LDS (compact: only the NK used k-steps), compute.
-template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES, bool PER_ARRAY>
+// WIDE: 0 = 32-bit sums, 1 = 64-bit sums in registers (general path), 2 = one slice group per call
+// (the one that starts at slice `only_sg0`) summed in 32 bits with shifts relative to the group; the
+// caller widens and adds up the groups.
+template <int PM, int KSMAX, int NK, int TERMS, int WIDE, bool CODES, bool PER_ARRAY>
 __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, int pol, int t, int lane, int mp0, int op,
-                                         uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
+                                         uint32_t (&y)[PM][16], long long (&y64)[PM][16], int only_sg0) {
 
   u32x2 raw[PM][KSMAX];
 #pragma unroll
@@ -637,8 +641,9 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
       raw[pm][j] = v;
     }
   constexpr int NF = TERMS * NK;
-  const int sg = min(a.S_w, a.lds_kb / NF);            // slices per staged group
-  for (int sg0 = 0; sg0 < a.S_w; sg0 += sg) {
+  const int sg = WIDE == 2 ? a.split_sg : min(a.S_w, a.lds_kb / NF);   // slices per staged group
+  const int sg_first = WIDE == 2 ? only_sg0 : 0, sg_end = WIDE == 2 ? only_sg0 + sg : a.S_w;
+  for (int sg0 = sg_first; sg0 < sg_end; sg0 += sg) {
     const int ns = min(sg, a.S_w - sg0);
     const u32x4* src = a.B + (((size_t)t * a.OP + op) * a.S_w + sg0) * TERMS * a.ks * 64;
     if constexpr (PER_ARRAY) src += (size_t)pol * a.pol_stride;
@@ -657,14 +662,18 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (!WIDE && !CODES && (ns & 1) == 0)
-      vmm_tile_group_pipelined<PM, KSMAX, NK, TERMS, PER_ARRAY>(a, lds, raw, ns, sg0, p, pol, lane, y);
-    else
-      vmm_tile_group<PM, KSMAX, NK, TERMS, WIDE, CODES, PER_ARRAY>(a, lds, raw, ns, sg0, p, pol, t, lane, mp0, op, y, y64);
+    if constexpr (WIDE == 2) {
+      vmm_tile_group_pipelined<PM, KSMAX, NK, TERMS, PER_ARRAY>(a, lds, raw, ns, 0, p, pol, lane, y);
+    } else {
+      if (!WIDE && !CODES && (ns & 1) == 0)
+        vmm_tile_group_pipelined<PM, KSMAX, NK, TERMS, PER_ARRAY>(a, lds, raw, ns, sg0, p, pol, lane, y);
+      else
+        vmm_tile_group<PM, KSMAX, NK, TERMS, WIDE == 1, CODES, PER_ARRAY>(a, lds, raw, ns, sg0, p, pol, t, lane, mp0, op, y, y64);
+    }
   }
 }
 
-template <int PM, int KSMAX, int TERMS, bool WIDE, bool CODES, bool PER_ARRAY>
+template <int PM, int KSMAX, int TERMS, int WIDE, bool CODES, bool PER_ARRAY>
 __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
   extern __shared__ u32x4 lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
@@ -699,24 +708,59 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
   const int vt_base = a.VT / a.nchunk, vt_rem = a.VT - vt_base * a.nchunk;
   const int vt0 = chunk * vt_base + min(chunk, vt_rem);
   const int vt1 = vt0 + vt_base + (chunk < vt_rem ? 1 : 0);
-  for (int vt = vt0; vt < vt1; ++vt) {
-    // vt = (phase, array, tile), tile fastest
-    const int pa = vt / a.T, t = vt - pa * a.T;
-    const int p = PER_ARRAY ? pa >> 1 : pa, pol = PER_ARRAY ? pa & 1 : 0;
-    const int rows = min(a.tile, a.Lin - t * a.tile);
-    const int nk = (rows + 15) >> 4;
 #define XBAR_NK_CASE(n) \
   case n:               \
-    if constexpr (n <= KSMAX) vmm_tile<PM, KSMAX, n, TERMS, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, lane, mp0, op, y, y64); \
+    if constexpr (n <= KSMAX)                                                                                       \
+      vmm_tile<PM, KSMAX, n, TERMS, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, lane, mp0, op, y, y64, only_sg0); \
     break;
-    switch (nk) {
-      XBAR_NK_CASE(1) XBAR_NK_CASE(2) XBAR_NK_CASE(3) XBAR_NK_CASE(4) XBAR_NK_CASE(5) XBAR_NK_CASE(6)
-      XBAR_NK_CASE(7) XBAR_NK_CASE(8) XBAR_NK_CASE(9) XBAR_NK_CASE(10) XBAR_NK_CASE(11) XBAR_NK_CASE(12)
-      XBAR_NK_CASE(13) XBAR_NK_CASE(14) XBAR_NK_CASE(15) XBAR_NK_CASE(16)
-      default: break;
-    }
-#undef XBAR_NK_CASE
+#define XBAR_ALL_VIRTUAL_TILES                                                                              \
+  for (int vt = vt0; vt < vt1; ++vt) {                                                                      \
+    /* vt = (phase, array, tile), tile fastest */                                                           \
+    const int pa = vt / a.T, t = vt - pa * a.T;                                                             \
+    const int p = PER_ARRAY ? pa >> 1 : pa, pol = PER_ARRAY ? pa & 1 : 0;                                   \
+    const int rows = min(a.tile, a.Lin - t * a.tile);                                                       \
+    const int nk = (rows + 15) >> 4;                                                                        \
+    switch (nk) {                                                                                           \
+      XBAR_NK_CASE(1) XBAR_NK_CASE(2) XBAR_NK_CASE(3) XBAR_NK_CASE(4) XBAR_NK_CASE(5) XBAR_NK_CASE(6)       \
+      XBAR_NK_CASE(7) XBAR_NK_CASE(8) XBAR_NK_CASE(9) XBAR_NK_CASE(10) XBAR_NK_CASE(11) XBAR_NK_CASE(12)    \
+      XBAR_NK_CASE(13) XBAR_NK_CASE(14) XBAR_NK_CASE(15) XBAR_NK_CASE(16)                                   \
+      default: break;                                                                                       \
+    }                                                                                                       \
   }
+  if constexpr (WIDE == 2) {
+    // Sums that overflow 32 bits, fast path: one pass over the chunk's virtual tiles per slice group,
+    // each summed in 32 bits with shifts relative to the group's first slice, then widened, shifted
+    // into place and added to the chunk's 64-bit partial result (every element has one owner lane).
+    const uint32_t bias = a.bias_per_vt * (uint32_t)(vt1 - vt0);
+    long long* part = reinterpret_cast<long long*>(a.part) + (size_t)chunk * a.M * a.Lout;
+    for (int only_sg0 = 0; only_sg0 < a.S_w; only_sg0 += a.split_sg) {
+      XBAR_ALL_VIRTUAL_TILES
+      const int up = a.slice_bits * only_sg0;
+      // the element addresses are the same for every group: keep the compiler from computing all of
+      // them ahead of the loop, where they would sit in registers throughout the contraction
+      int lane_now = lane, mp_now = mp0;
+      asm volatile("" : "+v"(lane_now), "+v"(mp_now));
+#pragma unroll
+      for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int m = (mp_now + pm) * 32 + (lane_now & 31);
+          const int o = op * 32 + 8 * (r >> 2) + 4 * (lane_now >> 5) + (r & 3);
+          if (m < a.M && o < a.Lout && mp_now + pm < a.MP) {
+            long long v = (long long)(int32_t)(y[pm][r] - bias) << up;
+            if (only_sg0) v += part[(size_t)m * a.Lout + o];
+            part[(size_t)m * a.Lout + o] = v;
+          }
+          y[pm][r] = 0;
+        }
+    }
+    return;
+  } else {
+    const int only_sg0 = 0;
+    XBAR_ALL_VIRTUAL_TILES
+  }
+#undef XBAR_ALL_VIRTUAL_TILES
+#undef XBAR_NK_CASE
   if constexpr (CODES) {
     if (a.hist) {                                  // statistics pass: the counters are the only result
       __syncthreads();
@@ -1035,7 +1079,10 @@ __global__ void step_advance_kernel(unsigned long long* counter) { *counter += 1
 
 struct VmmPlan {
   PlaneGeom g;
-  int Lin, Lout, MP, P, VT, vt_per_chunk, nchunk, wide, pm, nw, MB, lds_kb;
+  int Lin, Lout, MP, P, VT, vt_per_chunk, nchunk, pm, nw, MB, lds_kb;
+  int wide;            // 0: sums fit 32 bits; 1: 64-bit sums; 2: 32-bit sums per slice group, widened per group
+  int split_sg;        // slices per group of mode 2
+  uint32_t bias_split; // kMagicBits * sum of the shift weights of one such group, mod 2^32
   int offset;          // signed inputs in one phase of offset-binary codes
   uint32_t bias_per_vt;
   size_t a_bytes, part_bytes, ws_bytes, lds_bytes;
@@ -1058,7 +1105,30 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   p.bias_per_vt = (uint32_t)((unsigned long long)kMagicBits * wsum);
   const unsigned long long per_vt = wsum * (unsigned long long)d.q_adc;
   const unsigned long long fit = per_vt ? ((1ull << 31) - 1) / per_vt : (1ull << 31);
-  p.wide = fit < 1;
+  p.wide = fit < 1 ? 1 : 0;
+  const int slice_kb = d.terms * p.g.ks;                   // KiB of operand per slice and output patch
+  p.lds_kb = std::max(slice_kb, std::min(d.S_w * slice_kb, 64));   // staged slice group, at most 64 KiB
+  p.lds_bytes = (size_t)p.lds_kb * 1024;
+  // 64-bit sums: the software-pipelined path still serves if the slices split into equal, even
+  // groups that fit the LDS stage and whose own sum fits 32 bits
+  p.split_sg = 0;
+  p.bias_split = 0;
+  unsigned long long fit_split = 0;
+  if (p.wide) {
+    for (int sg = std::min(d.S_w, p.lds_kb / slice_kb) & ~1; sg >= 2; sg -= 2) {
+      if (d.S_w % sg) continue;
+      unsigned long long wg = 0;
+      for (int s = 0; s < sg; ++s)
+        for (int b = 0; b < d.S_in; ++b) wg += 1ull << (c->slice_bits * s + c->stream_bits * b);
+      const unsigned long long f = ((1ull << 31) - 1) / (wg * (unsigned long long)d.q_adc);
+      if (f < 1) continue;
+      p.wide = 2;
+      p.split_sg = sg;
+      p.bias_split = (uint32_t)((unsigned long long)kMagicBits * wg);
+      fit_split = f;
+      break;
+    }
+  }
   p.pm = p.g.ks > 8 ? 1 : 2;
   p.nw = std::min(4, std::max(1, cdiv(p.MP, p.pm)));
   p.MB = cdiv(p.MP, p.pm * p.nw);
@@ -1067,11 +1137,9 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
                                                           // filled round costs less (measured: 0.8 % per step over 2048)
   int per = std::max(1, cdiv(p.VT, want_chunks));
   if (!p.wide) per = (int)std::min<unsigned long long>((unsigned long long)per, fit);
+  if (p.wide == 2) per = (int)std::min<unsigned long long>((unsigned long long)per, fit_split);
   p.nchunk = cdiv(p.VT, per);
   p.vt_per_chunk = cdiv(p.VT, p.nchunk);                  // same number of chunks, evenly filled
-  const int slice_kb = d.terms * p.g.ks;                   // KiB of operand per slice and output patch
-  p.lds_kb = std::max(slice_kb, std::min(d.S_w * slice_kb, 64));   // staged slice group, at most 64 KiB
-  p.lds_bytes = (size_t)p.lds_kb * 1024;
   p.a_bytes = align256((size_t)p.P * p.MP * p.g.T * p.g.ks * 512);
   p.part_bytes = align256((size_t)p.nchunk * M * p.Lout * (p.wide ? 8 : 4));
   p.ws_bytes = p.a_bytes + p.part_bytes;
@@ -1101,8 +1169,9 @@ template <int PM, int KSMAX, int TERMS, bool PER_ARRAY>
 hipError_t launch_vmm_variant(const VmmArgs& a, const VmmPlan& p, bool codes, hipStream_t st) {
   const dim3 grid((unsigned)(a.per_xcd * 8)), block((unsigned)(p.nw * 64));
   void (*k)(VmmArgs);
-  if (p.wide) k = codes ? vmm_kernel<PM, KSMAX, TERMS, true, true, PER_ARRAY> : vmm_kernel<PM, KSMAX, TERMS, true, false, PER_ARRAY>;
-  else k = codes ? vmm_kernel<PM, KSMAX, TERMS, false, true, PER_ARRAY> : vmm_kernel<PM, KSMAX, TERMS, false, false, PER_ARRAY>;
+  if (p.wide == 2 && !codes) k = vmm_kernel<PM, KSMAX, TERMS, 2, false, PER_ARRAY>;
+  else if (p.wide) k = codes ? vmm_kernel<PM, KSMAX, TERMS, 1, true, PER_ARRAY> : vmm_kernel<PM, KSMAX, TERMS, 1, false, PER_ARRAY>;
+  else k = codes ? vmm_kernel<PM, KSMAX, TERMS, 0, true, PER_ARRAY> : vmm_kernel<PM, KSMAX, TERMS, 0, false, PER_ARRAY>;
   if (p.lds_bytes > 48 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
                                        (int)p.lds_bytes);
@@ -1180,13 +1249,16 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.npol = d.npol; a.pol_stride = p.g.pol_bytes / 16;
   a.VT = p.VT; a.S_w = d.S_w; a.S_in = d.S_in; a.slice_bits = cfg->slice_bits; a.stream_bits = cfg->stream_bits;
   a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.lds_kb = p.lds_kb;
-  a.direct = (p.nchunk == 1 && !p.offset) ? 1 : 0;
+  const bool general = codes != nullptr || hist != nullptr || level_table || a.adc_curve_on;
+  const bool split = p.wide == 2 && !general;          // adds its groups up in the partial-sum buffer
+  a.split_sg = p.split_sg;
+  a.direct = (p.nchunk == 1 && !p.offset && !split) ? 1 : 0;
   a.total_wg = p.nchunk * p.g.OP * p.MB;
   a.per_xcd = cdiv(a.total_wg, 8);
   a.gain = (float)d.q_adc / adc_fs * dac_gain;
   a.clamp_lo = kMagic - (float)d.q_adc;
   a.clamp_hi = kMagic + (float)d.q_adc;
-  a.bias_per_vt = p.bias_per_vt;
+  a.bias_per_vt = split ? p.bias_split : p.bias_per_vt;
   a.out = out;
   {
     const double lsb = (double)adc_fs / (double)d.q_adc;
@@ -1197,7 +1269,6 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   hipEvent_t ev0 = g_trace_before, ev1 = g_trace_after;
   g_trace_before = g_trace_after = nullptr;
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return XBAR_EHIP;
-  const bool general = codes != nullptr || hist != nullptr || level_table || a.adc_curve_on;
   if (launch_vmm(a, p, d.terms, general, st) != hipSuccess) return XBAR_EHIP;
   if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return XBAR_EHIP;
   if (hist) return XBAR_OK;
@@ -1208,7 +1279,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
     f.out = out;
     f.n = (long long)M * p.Lout;
     f.nchunk = p.nchunk;
-    f.wide = p.wide;
+    f.wide = p.wide != 0;
     f.Lout = p.Lout;
     f.scale = a.scale;
     f.wsum = nullptr;

@@ -104,6 +104,14 @@ IDEAL_CASES = [
     (128, 128, 8, 2, 4, False, 3, 1, 1, 8),
     (128, 128, 1, 2, 6, True, 50, 260, 40, 8),          # 3 slices: odd group, unpipelined path
     (32, 48, 1, 1, 5, False, 20, 70, 100, 6),           # 5 one-bit slices, 32-row / 48-column tiles
+    # sums beyond 32 bits: 32-bit sums per group of slices, widened group by group ...
+    (128, 128, 1, 2, 16, False, 70, 600, 64, 12),
+    (64, 64, 1, 2, 16, True, 40, 200, 70, 11),
+    (256, 256, 1, 2, 16, False, 40, 520, 48, 13),
+    (128, 128, 4, 4, 16, True, 33, 260, 50, 16),
+    (128, 128, 1, 2, 16, True, 300, 2100, 40, 10),      # many tiles per chunk
+    # ... and 64-bit sums in registers where the slices do not split into even groups
+    (128, 128, 1, 1, 15, False, 20, 200, 40, 12),
 ]
 
 
@@ -244,6 +252,31 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
     if "var" in ni:
         Y2 = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=4, codes=False)
         assert not np.array_equal(Y2, Yg)
+
+
+@pytest.mark.parametrize("ni,adc_bits", [("aam+var", 12), ("pa+aam2", 12), ("ob+aam", 11)])
+def test_wide_sums_nonideal(xo, xb, ni, adc_bits):
+    """Converters of 10 bits and more with 16-bit weights: the shift-and-add sum exceeds 32 bits.  The
+    production launch (32-bit sums per slice group, widened per group) returns the bits of the code-tap
+    launch (64-bit sums), and both stay within the output bar of the oracle."""
+    M, K, N = 70, 300, 100
+    g = workloads.Gemm("t", K, N, M, True, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=77)
+    ni = ni.split("+")
+    flags = xo.INPUT_SIGNED | (xo.WIRE_AAM if "aam" in ni else 0) | (xo.WIRE_AAM2 if "aam2" in ni else 0)
+    flags |= (xo.VARIATION if "var" in ni else 0) | (xo.ADC_PER_ARRAY if "pa" in ni else 0)
+    flags |= xo.INPUT_OFFSET if "ob" in ni else 0
+    fs = workloads.adc_full_scale(128, 1, 2) * (4.0 if "ob" in ni else 1.037)
+    co, cg = both_configs(xo, xb, xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, input_bits=8,
+                          stream_bits=1, adc_bits=adc_bits, flags=flags, var_sigma=0.1, seed=5, adc_fs_fwd=fs,
+                          adc_fs_bwd=fs)
+    w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    Yg, _ = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=2)
+    assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, x_scale, step=2, codes=False), Yg)
+    assert rel_l2(Yg, xo.fwd(co, W, X, w_max, x_scale, step=2)) <= (1e-2 if "ob" in ni else 1e-3)
+    dXg, _ = gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=2)
+    assert np.array_equal(gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=2, codes=False), dXg)
+    assert rel_l2(dXg, xo.bwd(co, W, dY, w_max, g_scale, step=2)) <= (1e-2 if "ob" in ni else 1e-3)
 
 
 FCM_CASES = [
