@@ -151,7 +151,7 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
  * Step counter in device memory, for callers that replay a captured HIP graph of a training step: kernel
  * arguments are frozen in a graph, so the `step` that keys the device variation (Sec. IV-A) and the write
  * noise (Sec. IV-C) would repeat.  After xbar_set_step_source(p) every later call of this host thread that
- * takes a `step` (xbar_tile, xbar_update, xbar_conv_update, xbar_update_pulsed, xbar_fcm_profile) uses
+ * takes a `step` (xbar_tile, xbar_update, xbar_conv_update, xbar_update_pulsed, xbar_conv_update_pulsed, xbar_fcm_profile) uses
  * step + *p, read by the kernels when they run; NULL switches it off.  p: 8-byte aligned device address that
  * stays valid while such kernels may run.  xbar_step_advance enqueues *p += 1 on the stream (one thread, no
  * memset: it can be part of the graph).
@@ -233,8 +233,11 @@ int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const f
  *                     element into the workspace, every input pixel then adds up, in fp32, the errors
  *                     of the patches it belongs to (a digital accumulation)
  *   xbar_conv_update  W in place from X and dY, as xbar_update on the patch matrix
+ *   xbar_conv_update_pulsed  W in place, as xbar_update_pulsed on the patch matrix: every output position is
+ *                     one sample (its patch drives the rows, its error the columns), element index
+ *                     i = m K + k of the row trains counts in the patch matrix
  * out_h must equal (in_h + 2 pad - k_h) / stride + 1 (likewise out_w), else XBAR_ESHAPE.
- * xbar_conv_workspace_bytes: op = XBAR_OP_FWD / XBAR_OP_BWD / XBAR_OP_UPDATE.
+ * xbar_conv_workspace_bytes: op = XBAR_OP_FWD / XBAR_OP_BWD / XBAR_OP_UPDATE / XBAR_OP_UPDATE_PULSED.
  */
 typedef struct xbar_conv_geom {
   int32_t batch, in_h, in_w, in_c;
@@ -250,6 +253,10 @@ int xbar_conv_bwd(const xbar_config* cfg, const void* planes, const float* dY, f
 int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const float* dY, const xbar_conv_geom* geom,
                      int N, float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes,
                      void* hip_stream);
+int xbar_conv_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY,
+                            const xbar_conv_geom* geom, int N, float w_max, float x_range, float d_range, int bl,
+                            float dw_min, uint64_t step, long long* pulses, void* ws, size_t ws_bytes,
+                            void* hip_stream);
 
 /*
  * Digital peripheral operations (Sec. IV-B: ReLU, batch normalisation and pooling are computed in the

@@ -30,7 +30,8 @@ struct PulseArgs {
   double w_max, x_range, d_range, dw_min, v, sigma;
   uint64_t seed, step;
   const unsigned long long* step_add;   // optional device counter added to step
-};
+  ConvGeom conv;                        // convolution layer: X is the NHWC image and row m of the layer's
+};                                      //   input matrix is gathered from it (CONV variant of the train kernel)
 
 __device__ __forceinline__ uint32_t pulse_train(uint32_t k0, uint32_t k1, uint64_t step, uint64_t index, double p, int bl) {
   const uint64_t threshold = (uint64_t)::rint(clampd(p, 0.0, 1.0) * 4294967296.0);
@@ -47,12 +48,20 @@ __device__ __forceinline__ uint32_t pulse_train(uint32_t k0, uint32_t k1, uint64
 }
 
 // One thread per element of the chunk's inputs, then of its errors.
+template <bool CONV>
 __global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
   const long long n_rows = (long long)a.mc * a.K, n_cols = (long long)a.mc * a.N;
   if (t < n_rows) {
     const uint64_t index = (uint64_t)a.m0 * a.K + (uint64_t)t;               // m K + k
-    const double x = (double)a.X[index];
+    double x;
+    if constexpr (CONV) {        // element (m, k) of the patch matrix: k = (kh KW + kw) C + c
+      const int m = a.m0 + (int)(t / a.K), k = (int)(t % a.K);
+      const int c = k % a.conv.C, kk = k / a.conv.C;
+      x = (double)conv_fetch(a.X, a.conv, conv_row(a.conv, m), kk / a.conv.KW, kk % a.conv.KW, c);
+    } else {
+      x = (double)a.X[index];
+    }
     const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseRows);
     const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseRows);
     a.rows[t] = pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(x) / a.x_range, a.bl) | (x < 0.0 ? 0x80000000u : 0u);
@@ -238,11 +247,10 @@ namespace xbar_detail {
 size_t pulsed_workspace_bytes(int M, int K, int N) { return plan_pulsed(M, K, N).ws_bytes; }
 }  // namespace xbar_detail
 
-extern "C" {
-
-int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
-                       float x_range, float d_range, int bl, float dw_min, uint64_t step, long long* pulses, void* ws,
-                       size_t ws_bytes, void* hip_stream) {
+namespace {
+int run_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
+                      float x_range, float d_range, int bl, float dw_min, uint64_t step, long long* pulses, void* ws,
+                      size_t ws_bytes, void* hip_stream, const ConvGeom* conv) {
   int rc = xbar_config_validate(cfg);
   if (rc) return rc;
   if ((rc = check_shape(M, K, N))) return rc;
@@ -268,6 +276,7 @@ int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const f
   const double lr_eq = (double)bl * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
   a.sigma = (double)cfg->upd_noise_gamma * std::sqrt(lr_eq * (double)dw_min);
   a.seed = cfg->seed; a.step = step; a.step_add = current_step_source();
+  a.conv = conv ? *conv : ConvGeom{};
   // 4 x 4 devices per thread when that still fills the chip, else one device per thread
   const bool patch4 = (long long)cdiv(K, 64) * cdiv(N, 64) >= 512;
   const int edge = patch4 ? 64 : 16;
@@ -278,7 +287,8 @@ int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const f
     a.first = m0 == 0;
     a.last = m0 + a.mc >= M;
     const long long elems = (long long)a.mc * ((long long)K + N);
-    hipLaunchKernelGGL(pulse_trains_kernel, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, a);
+    if (conv) hipLaunchKernelGGL(pulse_trains_kernel<true>, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL(pulse_trains_kernel<false>, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
     const bool nl = (cfg->flags & XBAR_NI_UPD_NL) != 0, noise = (cfg->flags & XBAR_NI_UPD_NOISE) != 0;
     void (*k)(PulseArgs);
@@ -292,6 +302,27 @@ int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const f
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   }
   return XBAR_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int xbar_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
+                       float x_range, float d_range, int bl, float dw_min, uint64_t step, long long* pulses, void* ws,
+                       size_t ws_bytes, void* hip_stream) {
+  return run_update_pulsed(cfg, W, X, dY, M, K, N, w_max, x_range, d_range, bl, dw_min, step, pulses, ws, ws_bytes,
+                           hip_stream, nullptr);
+}
+
+int xbar_conv_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY, const xbar_conv_geom* geom,
+                            int N, float w_max, float x_range, float d_range, int bl, float dw_min, uint64_t step,
+                            long long* pulses, void* ws, size_t ws_bytes, void* hip_stream) {
+  ConvGeom g;
+  int M, K;
+  const int rc = conv_dims(geom, &g, &M, &K);
+  if (rc) return rc;
+  return run_update_pulsed(cfg, W, X, dY, M, K, N, w_max, x_range, d_range, bl, dw_min, step, pulses, ws, ws_bytes,
+                           hip_stream, conv_is_dense(geom) ? nullptr : &g);
 }
 
 }  // extern "C"

@@ -175,35 +175,6 @@ __global__ __launch_bounds__(256) void weight_sums_kernel(SumArgs a) {
 // ---------------------------------------------------------------------------------------------
 // input quantiser (Sec. IV: inputs are scaled and sent to the DAC)
 // ---------------------------------------------------------------------------------------------
-// Convolution as a crossbar layer (Sec. IV: the kernels of a layer are unrolled into the columns of
-// the weight matrix, every output position applies one input patch to the rows): input X in NHWC,
-// row m = (b, oh, ow) of the layer's input matrix is the patch of that output position and its
-// contraction index is l = (kh KW + kw) C + c.  Positions outside the image read 0 V.
-struct ConvGeom {
-  int H, W, C, KH, KW, stride, pad, OH, OW;
-};
-
-struct ConvRow {       // patch of one output position: element (kh, kw, c) is X[off + (kh W + kw) C + c]
-  long long off;
-  int ih0, iw0;
-};
-
-__device__ __forceinline__ ConvRow conv_row(const ConvGeom& g, int m) {
-  const int ow = m % g.OW, t = m / g.OW;
-  const int oh = t % g.OH, b = t / g.OH;
-  ConvRow r;
-  r.ih0 = oh * g.stride - g.pad;
-  r.iw0 = ow * g.stride - g.pad;
-  r.off = (((long long)b * g.H + r.ih0) * g.W + r.iw0) * g.C;
-  return r;
-}
-
-__device__ __forceinline__ float conv_fetch(const float* X, const ConvGeom& g, const ConvRow& r, int kh, int kw, int c) {
-  const int ih = r.ih0 + kh, iw = r.iw0 + kw;
-  if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return 0.0f;
-  return X[r.off + ((long long)kh * g.W + kw) * g.C + c];
-}
-
 struct QuantArgs {
   const float* X;
   uint8_t* A;        // [phase][MP][T][ks][64 lanes][8 bytes]
@@ -1296,29 +1267,6 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   return XBAR_OK;
 }
 
-// A 1 x 1 convolution with stride 1 and no padding IS its patch matrix: X[batch H W][C].
-inline bool conv_is_dense(const xbar_conv_geom* q) { return q->k_h == 1 && q->k_w == 1 && q->stride == 1 && q->pad == 0; }
-
-// Checks a convolution geometry and derives the layer's matrix shape: M = batch x output positions,
-// K = kernel height x kernel width x input channels.
-int conv_dims(const xbar_conv_geom* q, ConvGeom* g, int* M, int* K) {
-  if (!q) return XBAR_EINVAL;
-  if (q->batch <= 0 || q->in_h <= 0 || q->in_w <= 0 || q->in_c <= 0 || q->k_h <= 0 || q->k_w <= 0 || q->stride <= 0 ||
-      q->pad < 0 || q->out_h <= 0 || q->out_w <= 0)
-    return XBAR_ESHAPE;
-  if (q->in_h + 2 * q->pad < q->k_h || q->in_w + 2 * q->pad < q->k_w) return XBAR_ESHAPE;
-  if (q->out_h != (q->in_h + 2 * q->pad - q->k_h) / q->stride + 1 ||
-      q->out_w != (q->in_w + 2 * q->pad - q->k_w) / q->stride + 1)
-    return XBAR_ESHAPE;
-  const long long m = (long long)q->batch * q->out_h * q->out_w, k = (long long)q->k_h * q->k_w * q->in_c;
-  const long long pixels = (long long)q->batch * q->in_h * q->in_w * q->in_c;
-  if (m >= (1ll << 31) || k >= (1ll << 31) || pixels >= (1ll << 38)) return XBAR_ESHAPE;
-  g->H = q->in_h; g->W = q->in_w; g->C = q->in_c; g->KH = q->k_h; g->KW = q->k_w;
-  g->stride = q->stride; g->pad = q->pad; g->OH = q->out_h; g->OW = q->out_w;
-  *M = (int)m;
-  *K = (int)k;
-  return XBAR_OK;
-}
 
 int run_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
                float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream, const ConvGeom* conv) {
@@ -1362,6 +1310,27 @@ int run_update(const xbar_config* cfg, float* W, const float* X, const float* dY
 }  // namespace
 
 namespace xbar_detail {
+// Checks a convolution geometry and derives the layer's matrix shape: M = batch x output positions,
+// K = kernel height x kernel width x input channels.
+int conv_dims(const xbar_conv_geom* q, ConvGeom* g, int* M, int* K) {
+  if (!q) return XBAR_EINVAL;
+  if (q->batch <= 0 || q->in_h <= 0 || q->in_w <= 0 || q->in_c <= 0 || q->k_h <= 0 || q->k_w <= 0 || q->stride <= 0 ||
+      q->pad < 0 || q->out_h <= 0 || q->out_w <= 0)
+    return XBAR_ESHAPE;
+  if (q->in_h + 2 * q->pad < q->k_h || q->in_w + 2 * q->pad < q->k_w) return XBAR_ESHAPE;
+  if (q->out_h != (q->in_h + 2 * q->pad - q->k_h) / q->stride + 1 ||
+      q->out_w != (q->in_w + 2 * q->pad - q->k_w) / q->stride + 1)
+    return XBAR_ESHAPE;
+  const long long m = (long long)q->batch * q->out_h * q->out_w, k = (long long)q->k_h * q->k_w * q->in_c;
+  const long long pixels = (long long)q->batch * q->in_h * q->in_w * q->in_c;
+  if (m >= (1ll << 31) || k >= (1ll << 31) || pixels >= (1ll << 38)) return XBAR_ESHAPE;
+  g->H = q->in_h; g->W = q->in_w; g->C = q->in_c; g->KH = q->k_h; g->KW = q->k_w;
+  g->stride = q->stride; g->pad = q->pad; g->OH = q->out_h; g->OW = q->out_w;
+  *M = (int)m;
+  *K = (int)k;
+  return XBAR_OK;
+}
+
 const unsigned long long* current_step_source() { return g_step_source; }
 }  // namespace xbar_detail
 
@@ -1557,6 +1526,7 @@ size_t xbar_conv_workspace_bytes(const xbar_config* cfg, int op, const xbar_conv
   if (op == XBAR_OP_FWD) return plan_vmm(cfg, d, M, K, N, false).ws_bytes;
   if (op == XBAR_OP_BWD) return plan_vmm(cfg, d, M, K, N, true).ws_bytes + align256((size_t)M * K * sizeof(float));
   if (op == XBAR_OP_UPDATE) return plan_update(M, K, N).ws_bytes;
+  if (op == XBAR_OP_UPDATE_PULSED) return pulsed_workspace_bytes(M, K, N);
   return 0;
 }
 

@@ -151,6 +151,38 @@ __device__ __forceinline__ double wave_inclusive_scan(double x, int lane) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// convolution geometry
+// ---------------------------------------------------------------------------------------------
+// Convolution as a crossbar layer (Sec. IV: the kernels of a layer are unrolled into the columns of
+// the weight matrix, every output position applies one input patch to the rows): input X in NHWC,
+// row m = (b, oh, ow) of the layer's input matrix is the patch of that output position and its
+// contraction index is l = (kh KW + kw) C + c.  Positions outside the image read 0 V.
+struct ConvGeom {
+  int H, W, C, KH, KW, stride, pad, OH, OW;
+};
+
+struct ConvRow {       // patch of one output position: element (kh, kw, c) is X[off + (kh W + kw) C + c]
+  long long off;
+  int ih0, iw0;
+};
+
+__device__ __forceinline__ ConvRow conv_row(const ConvGeom& g, int m) {
+  const int ow = m % g.OW, t = m / g.OW;
+  const int oh = t % g.OH, b = t / g.OH;
+  ConvRow r;
+  r.ih0 = oh * g.stride - g.pad;
+  r.iw0 = ow * g.stride - g.pad;
+  r.off = (((long long)b * g.H + r.ih0) * g.W + r.iw0) * g.C;
+  return r;
+}
+
+__device__ __forceinline__ float conv_fetch(const float* X, const ConvGeom& g, const ConvRow& r, int kh, int kw, int c) {
+  const int ih = r.ih0 + kh, iw = r.iw0 + kw;
+  if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return 0.0f;
+  return X[r.off + ((long long)kh * g.W + kw) * g.C + c];
+}
+
+// ---------------------------------------------------------------------------------------------
 // host-side argument checks
 // ---------------------------------------------------------------------------------------------
 static inline bool aligned16(const void* p) { return p && (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -177,6 +209,11 @@ XBAR_INTERNAL size_t fcm_workspace_bytes(const xbar_config* cfg, int K, int N);
 XBAR_INTERNAL size_t pulsed_workspace_bytes(int M, int K, int N);
 // xbar.hip: the device counter named with xbar_set_step_source (this thread), or null
 XBAR_INTERNAL const unsigned long long* current_step_source();
+// xbar.hip: checks a convolution geometry and derives the layer's matrix shape (M = batch x output
+// positions, K = kernel height x kernel width x input channels)
+XBAR_INTERNAL int conv_dims(const xbar_conv_geom* q, ConvGeom* g, int* M, int* K);
+// A 1 x 1 convolution with stride 1 and no padding IS its patch matrix: X[batch H W][C].
+static inline bool conv_is_dense(const xbar_conv_geom* q) { return q->k_h == 1 && q->k_w == 1 && q->stride == 1 && q->pad == 0; }
 
 }  // namespace xbar_detail
 

@@ -84,12 +84,15 @@ class CrossbarLayer:
                 d_range = bl * dw_min * self.w_max / (lr * self.x_scale)
                 ops.update_pulsed(self.cfg, self.W, self.x, dy, self.w_max, self.x_scale, d_range, bl, dw_min, step, ws=ws)
         else:
-            if pulse is not None:
-                raise NotImplementedError("the pulse-level update takes a layer's input matrix, not an image")
             if need_dx:
                 dx = ops.conv_bwd(self.cfg, self.planes, dy, self.geom, self.N, self.w_max, self.g_scale, ws=ws)
-            if not self.net.calibrating:
+            if not self.net.calibrating and pulse is None:
                 ops.conv_update(self.cfg, self.W, self.x, dy, self.geom, self.w_max, 1.0 / self.w_max, lr, step, ws=ws)
+            elif not self.net.calibrating:     # every output position is one sample of the pulse scheme
+                bl, dw_min = pulse["bl"], pulse["dw_min"]
+                d_range = bl * dw_min * self.w_max / (lr * self.x_scale)
+                ops.conv_update_pulsed(self.cfg, self.W, self.x, dy, self.geom, self.w_max, self.x_scale, d_range, bl,
+                                       dw_min, step, ws=ws)
         return dx
 
     def _measured_range(self, op, inp, in_scale, driven_lines, ws):
@@ -110,7 +113,7 @@ class CrossbarLayer:
         if self.geom is None:
             return max(fcm, *(xb.workspace_bytes(self.cfg, op, batch_rows, self.K, self.N)
                               for op in (xb.OP_FWD, xb.OP_BWD, xb.OP_UPDATE, xb.OP_UPDATE_PULSED)))
-        return max(fcm, *(xb.conv_workspace_bytes(self.cfg, op, self.geom, self.N) for op in (0, 1, 2)))
+        return max(fcm, *(xb.conv_workspace_bytes(self.cfg, op, self.geom, self.N) for op in (xb.OP_FWD, xb.OP_BWD, xb.OP_UPDATE, xb.OP_UPDATE_PULSED)))
 
 
 class BatchNorm:
@@ -144,7 +147,7 @@ class Network:
     calibrating = False
     fcm_every = 1         # with the stored-profile wire model: steps between two runs of the circuit-level model
     adc_quantile = None   # set while the converter ranges are being measured
-    pulse = None     # dict(bl=slots per train, dw_min=state change per pulse): pulse-level updates of the dense layers
+    pulse = None     # dict(bl=slots per train, dw_min=state change per pulse): pulse-level updates of the crossbar layers
 
     def train_step(self, x, labels, lr):
         """One SGD step on a batch: returns the per-sample losses (device tensor)."""

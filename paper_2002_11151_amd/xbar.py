@@ -128,6 +128,9 @@ _SIGNATURES = {
     "xbar_update_pulsed": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                      C.c_float, C.c_float, C.c_float, C.c_int, C.c_float, C.c_uint64, C.c_void_p,
                                      C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_conv_update_pulsed": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom),
+                                          C.c_int, C.c_float, C.c_float, C.c_float, C.c_int, C.c_float, C.c_uint64,
+                                          C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
 }
 
 
@@ -345,6 +348,19 @@ def conv_update(cfg, W, X, dY, geom, w_max, grad_scale, lr, step=0, ws=None):
     _check(lib().xbar_conv_update(C.byref(cfg), _dev(W), _dev(X), _dev(dY), C.byref(geom), N, w_max, grad_scale, lr, step,
                                   C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return W
+
+
+def conv_update_pulsed(cfg, W, X, dY, geom, w_max, x_range, d_range, bl, dw_min, step=0, ws=None, want_pulses=False):
+    """xbar_conv_update_pulsed: W[k_h k_w in_c][N] in place from the NHWC tensors X and dY, one output
+    position and one pulse at a time."""
+    K, N = W.shape
+    ws = _conv_ws(cfg, OP_UPDATE_PULSED, geom, N, ws, W.device)
+    pulses = torch.empty((K, N), dtype=torch.int64, device=W.device) if want_pulses else None
+    _check(lib().xbar_conv_update_pulsed(C.byref(cfg), _dev(W), _dev(X), _dev(dY), C.byref(geom), N, w_max, x_range,
+                                         d_range, bl, dw_min, step,
+                                         None if pulses is None else C.c_void_p(pulses.data_ptr()),
+                                         C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return (W, pulses) if want_pulses else W
 
 
 # ---- digital peripherals -------------------------------------------------------------------------

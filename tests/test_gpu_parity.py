@@ -720,6 +720,52 @@ def test_pulsed_update(xo, xb, name, M, K, N, bl, x_range, d_range, ni, w_max):
     assert np.array_equal(W2.cpu().numpy(), Wg)
 
 
+CONV_PULSED_CASES = [
+    # B, H, W, C, k, stride, pad, N, flags
+    (3, 9, 9, 5, 3, 2, 1, 20, "nl+noise"),          # padded, strided: patches gathered from the image
+    (2, 8, 8, 16, 3, 1, 1, 24, ""),
+    (2, 6, 6, 12, 1, 1, 0, 10, "nl"),               # 1 x 1: the image is the patch matrix
+    (2, 16, 16, 64, 3, 1, 1, 600, "noise"),         # 4 x 4 devices per thread, two stages of samples
+]
+
+
+@pytest.mark.parametrize("B,H,Wd,C,k,stride,pad,N,ni", CONV_PULSED_CASES)
+def test_conv_pulsed_update(xo, xb, B, H, Wd, C, k, stride, pad, N, ni):
+    """Pulse-level update of a convolution layer = the pulse-level update on its patch matrix, one output
+    position per sample: pulse counts bit for bit, state as in the dense case."""
+    from oracle import conv
+    rng = np.random.default_rng(B + H + C + N)
+    X = rng.normal(size=(B, H, Wd, C)).astype(np.float32)
+    Wm = np.clip(rng.normal(size=(k * k * C, N)) * 0.4, -0.9, 0.9).astype(np.float32)
+    OH, OW = conv.out_size(H, k, stride, pad), conv.out_size(Wd, k, stride, pad)
+    dY = (rng.normal(size=(B, OH, OW, N)) * 1e-2).astype(np.float32)
+    flags = (xo.UPD_NL if "nl" in ni else 0) | (xo.UPD_NOISE if "noise" in ni else 0)
+    co, cg = both_configs(xo, xb, flags=flags, upd_nl_v=1.3, upd_noise_gamma=0.4, seed=23)
+    dw, bl, x_range, d_range = 2.0 ** -10, 31, 3.0, 0.04 if N < 100 else 0.4
+    cols = conv.im2col(X, k, k, stride, pad)
+    Wo, pulses_o = xo.update_pulsed(co, Wm, cols, dY.reshape(-1, N), 1.0, x_range, d_range, bl, dw, step=7, want_pulses=True)
+    geom = xb.conv_geom(B, H, Wd, C, k, k, stride, pad)
+    Wg, pulses_g = xb.conv_update_pulsed(cg, dev(Wm.copy()), dev(X), dev(dY), geom, 1.0, x_range, d_range, bl, dw, step=7,
+                                         want_pulses=True)
+    torch.cuda.synchronize()
+    Wg, pulses_g = Wg.cpu().numpy(), pulses_g.cpu().numpy()
+    assert np.array_equal(pulses_g, pulses_o) and np.abs(pulses_o).sum() > 0
+    if not ni:
+        assert np.array_equal(Wg, Wo)
+    else:
+        assert np.abs(Wg - Wo).max() <= 2e-7
+    # same call on the explicit patch matrix
+    W2 = xb.update_pulsed(cg, dev(Wm.copy()), dev(cols.astype(np.float32)), dev(dY.reshape(-1, N)), 1.0, x_range, d_range,
+                          bl, dw, step=7)
+    torch.cuda.synchronize()
+    assert np.array_equal(W2.cpu().numpy(), Wg)
+    with pytest.raises(xb.XbarError):
+        bad = xb.conv_geom(B, H, Wd, C, k, k, stride, pad)
+        bad.out_h += 1
+        xb.conv_update_pulsed(cg, dev(Wm.copy()), dev(X), dev(dY), bad, 1.0, x_range, d_range, bl, dw)
+    torch.cuda.synchronize()
+
+
 def test_pulsed_update_argument_checks(xb):
     cg = xb.make_config()
     W, X, dY = (torch.zeros(s, device="cuda") for s in ((8, 8), (4, 8), (4, 8)))

@@ -140,6 +140,9 @@ def test_argument_checks_precede_any_device_work(xb):
     assert lib.xbar_conv_bwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, 16, None) == -4
     assert lib.xbar_conv_update(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, 0.1, 0, ok, 16, None) == -4
     assert xb.conv_workspace_bytes(c, xb.OP_BWD, geom, 16) > xb.conv_workspace_bytes(c, xb.OP_FWD, geom, 16) > 0
+    assert lib.xbar_conv_update_pulsed(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, 1.0, 31, 1e-3, 0, None, ok, 16, None) == -4
+    assert lib.xbar_conv_update_pulsed(C.byref(c), ok, ok, ok, None, 16, 1.0, 1.0, 1.0, 31, 1e-3, 0, None, ok, big, None) == -1
+    assert xb.conv_workspace_bytes(c, xb.OP_UPDATE_PULSED, geom, 16) == xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 2 * 8 * 8, 36, 16)
     geom.out_h = 9                                             # not what stride and padding give
     assert xb.conv_workspace_bytes(c, xb.OP_FWD, geom, 16) == 0
     assert lib.xbar_conv_fwd(C.byref(c), ok, ok, ok, C.byref(geom), 16, 1.0, 1.0, ok, big, None, None) == -2
