@@ -49,6 +49,7 @@
 #define XO_ADC_CURVE    256u
 #define XO_ADC_PER_ARRAY 512u
 #define XO_INPUT_OFFSET 1024u
+#define XO_PULSE_CODED 2048u
 
 #define XO_STREAM_VARIATION 1u
 #define XO_STREAM_WRITE     2u
@@ -553,7 +554,34 @@ int xo_update(const xo_config* cfg, float* W, const float* X, const float* dY, i
 /* after the learning rate lr gamma sqrt(dw_min / lr) = gamma sqrt(lr dw_min), times a normal     */
 /* number (number m*32 + j of stream 5 keyed with step*2^31 + device index).  The state is        */
 /* clamped to [-1, 1] after every pulse.  Samples in order, devices independent.                  */
+/*                                                                                               */
+/* XO_PULSE_CODED: the deterministic alternative the same passage names (values coded in the      */
+/* timing of the pulses instead of random streams).  Reading: the bl slots form Tx frames of Td    */
+/* sub-slots, Tx = floor(sqrt(bl)), Td = floor(bl / Tx) (slots beyond Tx Td stay unused); a row     */
+/* holds its line for the first nx = rne(p_x Tx) frames (pulse duration codes |x|), a column fires  */
+/* in the first nd = rne(p_d Td) sub-slots of every frame (pulse count per frame codes |d|): the     */
+/* device sees exactly nx nd coincidences, the product of the two coded values.  Everything else    */
+/* (pulse size, device model, order) as above, with Tx Td in place of bl in the learning rate.       */
 /* ------------------------------------------------------------------------------------------- */
+void xo_pulse_frames(int bl, int* tx, int* td) {
+  int t = 1;
+  while ((t + 1) * (t + 1) <= bl) ++t;
+  *tx = t;
+  *td = bl / t;
+}
+
+/* Slot j = frame * Td + sub-slot.  is_col = 0: frames 0 .. nx-1 entirely; 1: sub-slots 0 .. nd-1 of every frame. */
+uint32_t xo_pulse_code(double p, int bl, int is_col) {
+  int tx, td;
+  xo_pulse_frames(bl, &tx, &td);
+  const int level = (int)rint(clampd(p, 0.0, 1.0) * (double)(is_col ? td : tx));
+  uint32_t bits = 0;
+  for (int frame = 0; frame < tx; ++frame)
+    for (int sub = 0; sub < td; ++sub)
+      if (is_col ? sub < level : frame < level) bits |= 1u << (frame * td + sub);
+  return bits;
+}
+
 uint32_t xo_pulse_train(uint64_t seed, uint32_t stream, uint64_t step, uint64_t index, double p, int bl) {
   const uint32_t key[2] = {(uint32_t)seed ^ (0x9E3779B9u * stream), (uint32_t)(seed >> 32) ^ (0xBB67AE85u * stream)};
   const uint64_t threshold = (uint64_t)rint(clampd(p, 0.0, 1.0) * 4294967296.0);
@@ -579,18 +607,27 @@ int xo_update_pulsed(const xo_config* cfg, float* W, const float* X, const float
   uint32_t* b = a + K;
   for (size_t i = 0; i < (size_t)K * N; ++i) g[i] = (double)W[i] / (double)w_max;
   if (pulses_out) memset(pulses_out, 0, sizeof(int64_t) * (size_t)K * N);
-  const double lr_eq = (double)bl * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
+  const int coded = (cfg->flags & XO_PULSE_CODED) != 0;
+  int slots = bl;
+  if (coded) {
+    int tx, td;
+    xo_pulse_frames(bl, &tx, &td);
+    slots = tx * td;
+  }
+  const double lr_eq = (double)slots * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
   const double sigma = (double)cfg->upd_noise_gamma * sqrt(lr_eq * (double)dw_min);
   for (int m = 0; m < M; ++m) {
     /* bit 31 of a train carries the sign of its value */
     for (int k = 0; k < K; ++k) {
       const double x = (double)X[(size_t)m * K + k];
-      a[k] = xo_pulse_train(cfg->seed, XO_STREAM_PULSE_ROWS, step, (uint64_t)m * K + k, fabs(x) / (double)x_range, bl) |
+      a[k] = (coded ? xo_pulse_code(fabs(x) / (double)x_range, bl, 0)
+                    : xo_pulse_train(cfg->seed, XO_STREAM_PULSE_ROWS, step, (uint64_t)m * K + k, fabs(x) / (double)x_range, bl)) |
              (x < 0.0 ? 0x80000000u : 0u);
     }
     for (int n = 0; n < N; ++n) {
       const double d = (double)dY[(size_t)m * N + n];
-      b[n] = xo_pulse_train(cfg->seed, XO_STREAM_PULSE_COLS, step, (uint64_t)m * N + n, fabs(d) / (double)d_range, bl) |
+      b[n] = (coded ? xo_pulse_code(fabs(d) / (double)d_range, bl, 1)
+                    : xo_pulse_train(cfg->seed, XO_STREAM_PULSE_COLS, step, (uint64_t)m * N + n, fabs(d) / (double)d_range, bl)) |
              (d < 0.0 ? 0x80000000u : 0u);
     }
     for (int k = 0; k < K; ++k)

@@ -12,6 +12,7 @@ import numpy as np
 from . import build as _build
 
 INPUT_OFFSET = 1024
+PULSE_CODED = 2048
 VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED, WIRE_AAM2, ADC_CURVE, ADC_PER_ARRAY = (
     1, 2, 4, 8, 16, 32, 64, 128, 256, 512)
 STREAM_VARIATION, STREAM_WRITE = 1, 2
@@ -266,9 +267,22 @@ def pulse_train(seed, stream, step, index, p, bl):
     return int(f(C.c_uint64(seed), C.c_uint32(stream), C.c_uint64(step), C.c_uint64(index), C.c_double(p), C.c_int(bl)))
 
 
+def pulse_code(p, bl, is_col):
+    """Deterministic slot mask of a coded value (rows: whole frames, columns: sub-slots of every frame)."""
+    f = lib().xo_pulse_code
+    f.restype = C.c_uint32
+    return int(f(C.c_double(p), C.c_int(bl), C.c_int(1 if is_col else 0)))
+
+
+def pulse_frames(bl):
+    tx, td = C.c_int(0), C.c_int(0)
+    lib().xo_pulse_frames(C.c_int(bl), C.byref(tx), C.byref(td))
+    return tx.value, td.value
+
+
 def update_pulsed(cfg, W, X, dY, w_max, x_range, d_range, bl, dw_min, step=0, want_pulses=False):
-    """Stochastic pulse-train update, one sample at a time: returns the updated copy of W (and the signed
-    number of pulses every device received, if asked)."""
+    """Pulse-level update, one sample at a time (stochastic trains, or deterministic codes with PULSE_CODED):
+    returns the updated copy of W (and the signed number of pulses every device received, if asked)."""
     W = _f32(W).copy()
     X, dY = _f32(X), _f32(dY)
     M, K = X.shape

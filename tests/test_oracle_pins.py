@@ -977,6 +977,50 @@ def test_pulsed_update_is_unbiased_outer_product(xo):
     assert np.abs(mean).max() > 20 * sigma.max() / 4.5            # the test can see a wrong factor or sign
 
 
+def test_coded_pulses_multiply(xo):
+    """Deterministic pulse coding: rows hold whole frames, columns fire sub-slots of every frame, so a device
+    sees (coded |x|) x (coded |d|) coincidences; on the coding grid the written change IS the outer product."""
+    for bl, frames in ((31, (5, 6)), (30, (5, 6)), (16, (4, 4)), (15, (3, 5)), (1, (1, 1)), (3, (1, 3)), (4, (2, 2))):
+        tx, td = xo.pulse_frames(bl)
+        assert (tx, td) == frames and tx * td <= bl < (tx + 1) * (tx + 1)
+        for px in np.linspace(0, 1.3, 14):
+            for pd in np.linspace(0, 1.3, 11):
+                a, b = xo.pulse_code(px, bl, False), xo.pulse_code(pd, bl, True)
+                nx = int(np.rint(min(px, 1.0) * tx))            # rint: ties to even, like the coder
+                nd = int(np.rint(min(pd, 1.0) * td))
+                assert bin(a).count("1") == nx * td and bin(b).count("1") == nd * tx
+                assert bin(a & b).count("1") == nx * nd and (a | b) < (1 << (tx * td))
+    # on the grid, linear noise-free devices: the update equals the aggregate outer-product update at the
+    # learning rate Tx Td dw_min w_max / (x_range d_range), with no randomness left
+    rng = np.random.default_rng(12)
+    M, K, N, bl, dw = 7, 5, 4, 31, 2.0 ** -12
+    tx, td = 5, 6
+    X = (rng.integers(-tx, tx + 1, size=(M, K)) / tx * 2.0).astype(np.float32)          # x_range 2
+    D = (rng.integers(-td, td + 1, size=(M, N)) / td * 0.5).astype(np.float32)          # d_range 0.5
+    W0 = rng.uniform(-0.3, 0.3, size=(K, N)).astype(np.float32)
+    cfg = xo.make_config(flags=xo.PULSE_CODED, seed=3)
+    W1, pulses = xo.update_pulsed(cfg, W0, X, D, 1.5, 2.0, 0.5, bl, dw, step=1, want_pulses=True)
+    nx = np.rint(X.astype(np.float64) / 2.0 * tx).astype(np.int64)
+    nd = np.rint(D.astype(np.float64) / 0.5 * td).astype(np.int64)
+    assert np.array_equal(pulses, -(nx.T @ nd)) and np.abs(pulses).max() > 20
+    assert np.array_equal(W1, (W0.astype(np.float64) + 1.5 * dw * pulses).astype(np.float32))
+    lr = tx * td * dw * 1.5 / (2.0 * 0.5)
+    Wa = xo.update(xo.make_config(), W0, X, D, 1.5, 1.0 / 1.5, lr)
+    assert np.abs(W1.astype(np.float64) - Wa).max() < 1e-6
+    # the seed and the step do not enter; values below half a level write nothing
+    assert np.array_equal(xo.update_pulsed(xo.make_config(flags=xo.PULSE_CODED, seed=99), W0, X, D, 1.5, 2.0, 0.5, bl, dw, step=8), W1)
+    tiny = xo.update_pulsed(cfg, W0, X * 0.09, D, 1.5, 2.0, 0.5, bl, dw)
+    assert np.array_equal(tiny, W0)
+    # per-pulse noise uses Tx Td slots in its learning rate (31 slots give 30 usable ones)
+    cn = xo.make_config(flags=xo.PULSE_CODED | xo.UPD_NOISE, upd_noise_gamma=0.6, seed=21)
+    Wn = xo.update_pulsed(cn, np.zeros((1, 1), np.float32), np.array([[2.0]], np.float32), np.array([[-0.5]], np.float32),
+                          4.0, 2.0, 0.5, 31, dw, step=6)
+    lr_eq, g = 30 * dw * 4.0 / (2.0 * 0.5), 0.0
+    for j in range(30):
+        g += dw + np.float64(np.float32(0.6)) * np.sqrt(lr_eq * dw) * xo.normal(21, 5, 6 << 31, j)
+    assert abs(Wn[0, 0] - 4.0 * g) < 1e-6
+
+
 def test_pulsed_update_device_model(xo):
     """Per-pulse non-linearity and noise: sequential closed forms, and the aggregate model for one pulse."""
     bl, dw, v, gamma = 31, 2.0 ** -9, 1.7, 0.6
