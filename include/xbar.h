@@ -70,6 +70,14 @@ extern "C" {
                                      them in the plane buffer).  Every input is driven, also a zero and a
                                      convolution's padding (mid-range): size adc_fs for that.  Half the
                                      conversions and contraction work of the two-phase scheme          */
+#define XBAR_PULSE_CODED     2048u /* pulse-level updates use deterministic, time-coded pulses (Sec. IV-C names
+                                     them beside the stochastic streams) instead of random trains: the bl
+                                     slots form Tx frames of Td sub-slots, Tx = floor(sqrt(bl)), Td =
+                                     floor(bl / Tx); a row holds its line for the first rne(p_x Tx) frames, a
+                                     column fires in the first rne(p_d Td) sub-slots of every frame, so a
+                                     device sees exactly rne(p_x Tx) rne(p_d Td) coincidences; Tx Td takes the
+                                     place of bl in the learning rate.  seed and step then only key the
+                                     write noise                                                        */
 
 /* status codes */
 #define XBAR_OK          0
@@ -100,7 +108,7 @@ typedef struct xbar_config {
   int32_t stream_bits;    /* bits per DAC cycle, divides input_bits              paper: 1             */
   int32_t adc_bits;       /* 2..16, signed mid-tread converter with Q = 2^(adc_bits-1) - 1 codes/side */
   uint32_t flags;         /* XBAR_NI_* | XBAR_DAC_LUT | XBAR_ADC_CURVE | XBAR_INPUT_SIGNED |          */
-                          /*   XBAR_ADC_PER_ARRAY | XBAR_INPUT_OFFSET                                 */
+                          /*   XBAR_ADC_PER_ARRAY | XBAR_INPUT_OFFSET | XBAR_PULSE_CODED              */
   float r_min, r_max;     /* device resistance range in Ohm                      paper: 1e5, 1e6      */
   float v_max;            /* input voltage range in V (results do not depend on it) paper: 1          */
   float r_row, r_col;     /* wire resistance per cell in Ohm                     paper: 1, 4.6        */

@@ -31,7 +31,9 @@ struct PulseArgs {
   uint64_t seed, step;
   const unsigned long long* step_add;   // optional device counter added to step
   ConvGeom conv;                        // convolution layer: X is the NHWC image and row m of the layer's
-};                                      //   input matrix is gathered from it (CONV variant of the train kernel)
+                                        //   input matrix is gathered from it (CONV variant of the train kernel)
+  int coded, tx, td;                    // deterministic pulse coding: tx frames of td sub-slots
+};
 
 __device__ __forceinline__ uint32_t pulse_train(uint32_t k0, uint32_t k1, uint64_t step, uint64_t index, double p, int bl) {
   const uint64_t threshold = (uint64_t)::rint(clampd(p, 0.0, 1.0) * 4294967296.0);
@@ -44,6 +46,17 @@ __device__ __forceinline__ uint32_t pulse_train(uint32_t k0, uint32_t k1, uint64
     for (int e = 0; e < 4; ++e)
       if (j + e < bl && (uint64_t)w[e] < threshold) bits |= 1u << (j + e);
   }
+  return bits;
+}
+
+// Deterministic code of a value: slot = frame * td + sub-slot; a row takes the first rne(p tx) frames
+// whole, a column the first rne(p td) sub-slots of every frame.
+__device__ __forceinline__ uint32_t pulse_code(double p, int tx, int td, bool is_col) {
+  const int level = (int)::rint(clampd(p, 0.0, 1.0) * (double)(is_col ? td : tx));
+  if (!is_col) return level * td >= 32 ? 0xFFFFFFFFu : (1u << (level * td)) - 1u;      // level * td <= 31 slots
+  const uint32_t frame = (1u << level) - 1u;                                          // level <= td <= 31
+  uint32_t bits = 0;
+  for (int f = 0; f < tx; ++f) bits |= frame << (f * td);
   return bits;
 }
 
@@ -64,14 +77,18 @@ __global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
     }
     const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseRows);
     const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseRows);
-    a.rows[t] = pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(x) / a.x_range, a.bl) | (x < 0.0 ? 0x80000000u : 0u);
+    const uint32_t train = a.coded ? pulse_code(::fabs(x) / a.x_range, a.tx, a.td, false)
+                                   : pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(x) / a.x_range, a.bl);
+    a.rows[t] = train | (x < 0.0 ? 0x80000000u : 0u);
   } else if (t < n_rows + n_cols) {
     const long long u = t - n_rows;
     const uint64_t index = (uint64_t)a.m0 * a.N + (uint64_t)u;
     const double d = (double)a.D[index];
     const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseCols);
     const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseCols);
-    a.cols[u] = pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(d) / a.d_range, a.bl) | (d < 0.0 ? 0x80000000u : 0u);
+    const uint32_t train = a.coded ? pulse_code(::fabs(d) / a.d_range, a.tx, a.td, true)
+                                   : pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(d) / a.d_range, a.bl);
+    a.cols[u] = train | (d < 0.0 ? 0x80000000u : 0u);
   }
 }
 
@@ -273,7 +290,12 @@ int run_update_pulsed(const xbar_config* cfg, float* W, const float* X, const fl
   a.v = (double)cfg->upd_nl_v;
   // the aggregate model's noise for one pulse: its standard deviation gamma sqrt(dG) belongs to the ideal change
   // before the learning rate, and this scheme's mean equals the aggregate update at lr = bl dw_min w_max / (x_range d_range)
-  const double lr_eq = (double)bl * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
+  a.coded = (cfg->flags & XBAR_PULSE_CODED) ? 1 : 0;
+  a.tx = 1;
+  while ((a.tx + 1) * (a.tx + 1) <= bl) ++a.tx;
+  a.td = bl / a.tx;
+  const int slots = a.coded ? a.tx * a.td : bl;
+  const double lr_eq = (double)slots * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
   a.sigma = (double)cfg->upd_noise_gamma * std::sqrt(lr_eq * (double)dw_min);
   a.seed = cfg->seed; a.step = step; a.step_add = current_step_source();
   a.conv = conv ? *conv : ConvGeom{};

@@ -1386,7 +1386,7 @@ int xbar_config_validate(const xbar_config* c) {
   if (c->input_bits < 1 || c->input_bits > 8) return XBAR_EINVAL;
   if (c->stream_bits < 1 || c->stream_bits > c->input_bits || c->input_bits % c->stream_bits) return XBAR_EINVAL;
   if (c->adc_bits < 2 || c->adc_bits > 16) return XBAR_EINVAL;
-  if (c->flags & ~0x7FFu) return XBAR_EINVAL;
+  if (c->flags & ~0xFFFu) return XBAR_EINVAL;
   if (c->flags & XBAR_ADC_PER_ARRAY) {
     if (c->flags & XBAR_ADC_CURVE) return XBAR_EINVAL;     // the curve is that of a signed converter
     if (c->adc_bits > 15) return XBAR_EINVAL;              // unsigned codes are reported as int16

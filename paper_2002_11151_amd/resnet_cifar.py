@@ -28,6 +28,14 @@ def range_from_histogram(hist, bin_width, quantile):
     return float(2.0 ** math.ceil(math.log2(max((b + 0.5) * bin_width, bin_width))))
 
 
+def pulse_slots(cfg, bl):
+    """Slots of a pulse train that carry pulses: all `bl` of a stochastic train, frames x sub-slots of a coded one."""
+    if not cfg.flags & xb.PULSE_CODED:
+        return bl
+    tx = math.isqrt(bl)
+    return tx * (bl // tx)
+
+
 class CrossbarLayer:
     """One weight layer: W[K][N], its conductance planes of the current step, its ranges."""
 
@@ -80,8 +88,7 @@ class CrossbarLayer:
             elif not self.net.calibrating:
                 # inputs fire in proportion to their size over the calibrated range; the error range then follows
                 # from the learning rate: mean change = lr x dy / w_max  <=>  x_range d_range = bl dw_min w_max / lr
-                bl, dw_min = pulse["bl"], pulse["dw_min"]
-                d_range = bl * dw_min * self.w_max / (lr * self.x_scale)
+                bl, dw_min, d_range = self._pulse_ranges(pulse, lr)
                 ops.update_pulsed(self.cfg, self.W, self.x, dy, self.w_max, self.x_scale, d_range, bl, dw_min, step, ws=ws)
         else:
             if need_dx:
@@ -89,11 +96,20 @@ class CrossbarLayer:
             if not self.net.calibrating and pulse is None:
                 ops.conv_update(self.cfg, self.W, self.x, dy, self.geom, self.w_max, 1.0 / self.w_max, lr, step, ws=ws)
             elif not self.net.calibrating:     # every output position is one sample of the pulse scheme
-                bl, dw_min = pulse["bl"], pulse["dw_min"]
-                d_range = bl * dw_min * self.w_max / (lr * self.x_scale)
+                bl, dw_min, d_range = self._pulse_ranges(pulse, lr)
                 ops.conv_update_pulsed(self.cfg, self.W, self.x, dy, self.geom, self.w_max, self.x_scale, d_range, bl,
                                        dw_min, step, ws=ws)
         return dx
+
+    def _pulse_ranges(self, pulse, lr):
+        """(bl, dw_min, d_range) of a pulse-level update whose mean is the update at learning rate lr:
+        lr = slots dw_min w_max / (x_range d_range) with x_range = the calibrated input range.  Stochastic
+        trains round without bias, so the pulse size is free and the error range follows from it; coded pulses
+        drop what is below half a level, so there the errors use their calibrated range and the pulse size follows."""
+        bl, slots = pulse["bl"], pulse_slots(self.cfg, pulse["bl"])
+        if self.cfg.flags & xb.PULSE_CODED:
+            return bl, lr * self.x_scale * self.g_scale / (slots * self.w_max), self.g_scale
+        return bl, pulse["dw_min"], slots * pulse["dw_min"] * self.w_max / (lr * self.x_scale)
 
     def _measured_range(self, op, inp, in_scale, driven_lines, ws):
         """Converter range of one pass from the currents this input causes (statistics pass of the library)."""

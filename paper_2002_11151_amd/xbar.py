@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libxbar.so")
 
 (NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2, ADC_CURVE,
- ADC_PER_ARRAY, INPUT_OFFSET) = (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024)
+ ADC_PER_ARRAY, INPUT_OFFSET, PULSE_CODED) = (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048)
 OP_FWD, OP_BWD, OP_UPDATE, OP_FCM, OP_UPDATE_PULSED = 0, 1, 2, 3, 4
 ABI_VERSION = 2
 

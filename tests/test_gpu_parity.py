@@ -687,6 +687,11 @@ PULSED_CASES = [
     ("large_layer_linear", 70, 2048, 1030, 31, 2.0, 0.05, "", 1.0),
     ("large_layer_nl", 140, 2048, 1030, 12, 2.0, 0.1, "nl", 1.0),        # three stages of 64 samples
     ("large_layer_noise", 70, 2048, 1030, 31, 4.0, 0.4, "noise", 1.0),
+    # deterministic time-coded pulses: frames x sub-slots instead of random trains
+    ("coded_ragged", 130, 70, 100, 31, 2.0, 0.02, "coded", 1.5),
+    ("coded_nl_noise", 90, 128, 65, 16, 1.0, 0.01, "coded+nl+noise", 1.0),
+    ("coded_one_slot", 50, 20, 30, 1, 0.5, 0.005, "coded", 1.0),
+    ("coded_large_layer", 70, 2048, 1030, 31, 4.0, 0.4, "coded+nl", 1.0),
 ]
 
 
@@ -698,6 +703,7 @@ def test_pulsed_update(xo, xb, name, M, K, N, bl, x_range, d_range, ni, w_max):
     W, X, dY = workloads.layer_tensors_np(g, seed=M + K + N)
     W = np.clip(W * 4, -0.9 * w_max, 0.9 * w_max).astype(np.float32)
     flags = (xo.UPD_NL if "nl" in ni else 0) | (xo.UPD_NOISE if "noise" in ni else 0)
+    flags |= xo.PULSE_CODED if "coded" in ni else 0
     co, cg = both_configs(xo, xb, flags=flags, upd_nl_v=1.3, upd_noise_gamma=0.4, seed=19)
     dw = 2.0 ** -10
     Wo, pulses_o = xo.update_pulsed(co, W, X, dY, w_max, x_range, d_range, bl, dw, step=5, want_pulses=True)
@@ -707,7 +713,7 @@ def test_pulsed_update(xo, xb, name, M, K, N, bl, x_range, d_range, ni, w_max):
     Wg, pulses_g = Wg.cpu().numpy(), pulses_g.cpu().numpy()
     assert np.array_equal(pulses_g, pulses_o)
     assert np.abs(pulses_o).sum() > 0 or name == "single"
-    if not ni:
+    if ni in ("", "coded"):
         assert np.array_equal(Wg, Wo)
     else:
         # exp, log, sin and cos come from two maths libraries: a few units in the last place of a double

@@ -45,7 +45,7 @@ def test_struct_layout_matches(xb):
     dict(xbar_rows=60), dict(xbar_rows=8), dict(xbar_cols=512), dict(weight_bits=7, slice_bits=2),
     dict(weight_bits=32, slice_bits=2), dict(slice_bits=5, weight_bits=10), dict(input_bits=9),
     dict(input_bits=8, stream_bits=3), dict(stream_bits=0), dict(adc_bits=1), dict(adc_bits=17),
-    dict(flags=1 << 11), dict(flags=512 | 256), dict(flags=512, adc_bits=16), dict(flags=256, adc_curve=[0.0] * 8 + [1.0, 0.5] + [1.0] * 7),
+    dict(flags=1 << 12), dict(flags=512 | 256), dict(flags=512, adc_bits=16), dict(flags=256, adc_curve=[0.0] * 8 + [1.0, 0.5] + [1.0] * 7),
     dict(flags=256, adc_curve=[-1.5] + [0.0] * 16), dict(flags=2 | 4), dict(flags=2 | 128), dict(flags=4 | 128), dict(r_min=0.0), dict(r_min=2e6), dict(r_max=float("nan")),
     dict(r_row=-1.0), dict(var_sigma=float("inf")), dict(adc_fs_fwd=0.0), dict(adc_fs_bwd=-3.0),
     dict(upd_noise_gamma=-1.0),

@@ -165,3 +165,10 @@ def test_converter_ranges_from_the_histograms(net_and_ops):
     assert resnet_cifar.range_from_histogram(hist, 0.5, 0.5) == 2.0                   # (3 + 0.5) * 0.5 = 1.75 -> 2
     hist[4000] = 10
     assert resnet_cifar.range_from_histogram(hist, 0.5, 0.99) == 2048.0
+
+
+def test_pulse_slots_of_coded_trains():
+    from paper_2002_11151_amd import resnet_cifar, xbar as xb
+    plain, coded = xb.make_config(), xb.make_config(flags=xb.PULSE_CODED)
+    assert [resnet_cifar.pulse_slots(plain, bl) for bl in (1, 15, 31)] == [1, 15, 31]
+    assert [resnet_cifar.pulse_slots(coded, bl) for bl in (1, 3, 4, 15, 16, 30, 31)] == [1, 3, 4, 15, 16, 30, 30]
