@@ -369,6 +369,8 @@ void xbar_trace_next_vmm(void* before, void* after);
  *   mode 0: both operands pseudo-random fp16;  mode 1: B operand = sparse single-bit patterns as in
  *   the emulation, A pseudo-random.   iters: loop count; the kernel issues 16 * iters MFMAs per wave
  *   on 2048 waves, i.e. 2 * 16 * iters * 2048 * 16384 flops.   out: 2 MiB of device scratch.
+ *   modes 2, 3: the same two operand patterns with the 8-bit integer instruction
+ *   (v_mfma_i32_32x32x32_i8, twice the operations per instruction), for comparison.
  */
 int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void* hip_stream);
 

@@ -1040,6 +1040,35 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters, 
   out[blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// Same loop with the 8-bit integer instruction (32 x 32 x 32 per instruction, twice the products).
+typedef int int4v __attribute__((ext_vector_type(4)));
+typedef int int16v __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void mfma_probe_i8_kernel(int* out, int iters, int mode) {
+  uint32_t x = threadIdx.x * 2654435761u + 12345u;
+  int4v a, b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+    a[i] = (int)(mode == 3 ? (x & 0x01010101u) : x);       // single-bit digits as in the emulation, or any bytes
+    x ^= x << 13; x ^= x >> 17; x ^= x << 5;
+    b[i] = (int)x;
+  }
+  int16v c0, c1;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) c0[r] = c1[r] = 0;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a, c0, 0, 0, 0);
+      c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(b, a, c1, 0, 0, 0);
+    }
+  }
+  int s = 0;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) s += c0[r] + c1[r];
+  out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 // ---------------------------------------------------------------------------------------------
 // host dispatch
 // ---------------------------------------------------------------------------------------------
@@ -1342,9 +1371,14 @@ extern "C" {
 uint32_t xbar_abi_version(void) { return XBAR_ABI_VERSION; }
 
 int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void* hip_stream) {
-  if (mode < 0 || mode > 1 || iters <= 0 || iters > (1 << 24)) return XBAR_EINVAL;
+  if (mode < 0 || mode > 3 || iters <= 0 || iters > (1 << 24)) return XBAR_EINVAL;
   if (!aligned16(out)) return XBAR_EALIGN;
   if (out_bytes < (size_t)512 * 256 * sizeof(float)) return XBAR_EWORKSPACE;
+  if (mode >= 2) {
+    hipLaunchKernelGGL(mfma_probe_i8_kernel, dim3(512), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
+                       reinterpret_cast<int*>(out), iters, mode);
+    return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
+  }
   hipLaunchKernelGGL(mfma_probe_kernel, dim3(512), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream),
                      reinterpret_cast<float*>(out), iters, mode);
   return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;

@@ -166,7 +166,7 @@ def trace_next_vmm(before, after):
 def probe_mfma_rate(mode, iters, scratch):
     """xbar_probe_mfma_rate: enqueue the pure-MFMA probe; returns the flops it performs."""
     _check(lib().xbar_probe_mfma_rate(mode, iters, C.c_void_p(scratch.data_ptr()), scratch.numel(), _stream()))
-    return 2.0 * 16 * iters * 2048 * 16384
+    return 2.0 * 16 * iters * 2048 * 16384 * (2 if mode >= 2 else 1)
 
 
 def validate(cfg):
