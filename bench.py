@@ -271,8 +271,8 @@ def main():
         max_ws_upd = max(max_ws_upd, xb.workspace_bytes(cfg, 2, g.M, g.K, g.N) if geom is None else
                          xb.conv_workspace_bytes(cfg, 2, geom, g.N))
         if args.pulsed_update:
-            assert geom is None, "the pulse-level update takes the layer's input matrix"
-            max_ws_upd = max(max_ws_upd, xb.workspace_bytes(cfg, xb.OP_UPDATE_PULSED, g.M, g.K, g.N))
+            max_ws_upd = max(max_ws_upd, xb.workspace_bytes(cfg, xb.OP_UPDATE_PULSED, g.M, g.K, g.N) if geom is None else
+                             xb.conv_workspace_bytes(cfg, xb.OP_UPDATE_PULSED, geom, g.N))
             max_ws = max(max_ws, max_ws_upd)
         max_out = max(max_out, g.M * g.N, g.M * g.K)
     planes = torch.empty(max_planes, dtype=torch.uint8, device=device)
@@ -317,9 +317,13 @@ def main():
                                 out=out[:g.M * g.N].view(geom.batch, geom.out_h, geom.out_w, g.N))
 
                 def update():
-                    if args.pulsed_update:
+                    if args.pulsed_update and geom is None:
                         xb.update_pulsed(cfg, L["W"], L["X"], L["dY"], L["w_max"], L["x_scale"], pulse_d_range(L), 31,
                                          PULSE_DW_MIN, s, ws=ws_upd)
+                    elif args.pulsed_update:
+                        xb.conv_update_pulsed(cfg, L["W"], L["X"], L["dY"].view(geom.batch, geom.out_h, geom.out_w, g.N),
+                                              geom, L["w_max"], L["x_scale"], pulse_d_range(L), 31, PULSE_DW_MIN, s,
+                                              ws=ws_upd)
                     elif geom is None:
                         xb.update(cfg, L["W"], L["X"], L["dY"], L["w_max"], 1.0 / L["w_max"], 0.01, s, ws=ws_upd)
                     else:
@@ -485,8 +489,14 @@ def main():
         for L in layers:
             g = L["g"]
             dw = PULSE_DW_MIN
-            _, cnt = xb.update_pulsed(L["cfg"], L["W"].clone(), L["X"], L["dY"], L["w_max"], L["x_scale"],
-                                      pulse_d_range(L), 31, dw, 0, ws=ws_upd, want_pulses=True)
+            if L["geom"] is None:
+                _, cnt = xb.update_pulsed(L["cfg"], L["W"].clone(), L["X"], L["dY"], L["w_max"], L["x_scale"],
+                                          pulse_d_range(L), 31, dw, 0, ws=ws_upd, want_pulses=True)
+            else:
+                q = L["geom"]
+                _, cnt = xb.conv_update_pulsed(L["cfg"], L["W"].clone(), L["X"], L["dY"].view(q.batch, q.out_h, q.out_w, g.N),
+                                               q, L["w_max"], L["x_scale"], pulse_d_range(L), 31, dw, 0, ws=ws_upd,
+                                               want_pulses=True)
             n_pulses += int(cnt.abs().sum().item()) * g.count
         upd_ms = sum(a.elapsed_time(b) for a, b in pulsed_events) / args.steps
         line["pulsed_update"] = {"ms_per_step": round(upd_ms, 3), "pulses_per_step": n_pulses,
