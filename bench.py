@@ -484,19 +484,21 @@ def main():
     if fcm_refresh_ms is not None:
         line["fcm_refresh_ms"] = fcm_refresh_ms
     if args.pulsed_update:
-        # pulses of one step, counted in an untimed pass on copies of the weights
+        # pulses of one step, counted in an untimed pass on copies of the weights: the library reports the signed
+        # (net) count per device, and the trains depend on magnitudes only, so the same pass on |X| and |dY| sends
+        # every pulse the same way and its net count is the number of pulses
         n_pulses = 0
         for L in layers:
             g = L["g"]
             dw = PULSE_DW_MIN
             if L["geom"] is None:
-                _, cnt = xb.update_pulsed(L["cfg"], L["W"].clone(), L["X"], L["dY"], L["w_max"], L["x_scale"],
+                _, cnt = xb.update_pulsed(L["cfg"], L["W"].clone(), L["X"].abs(), L["dY"].abs(), L["w_max"], L["x_scale"],
                                           pulse_d_range(L), 31, dw, 0, ws=ws_upd, want_pulses=True)
             else:
                 q = L["geom"]
-                _, cnt = xb.conv_update_pulsed(L["cfg"], L["W"].clone(), L["X"], L["dY"].view(q.batch, q.out_h, q.out_w, g.N),
-                                               q, L["w_max"], L["x_scale"], pulse_d_range(L), 31, dw, 0, ws=ws_upd,
-                                               want_pulses=True)
+                _, cnt = xb.conv_update_pulsed(L["cfg"], L["W"].clone(), L["X"].abs(),
+                                               L["dY"].abs().view(q.batch, q.out_h, q.out_w, g.N), q, L["w_max"],
+                                               L["x_scale"], pulse_d_range(L), 31, dw, 0, ws=ws_upd, want_pulses=True)
             n_pulses += int(cnt.abs().sum().item()) * g.count
         upd_ms = sum(a.elapsed_time(b) for a, b in pulsed_events) / args.steps
         line["pulsed_update"] = {"ms_per_step": round(upd_ms, 3), "pulses_per_step": n_pulses,

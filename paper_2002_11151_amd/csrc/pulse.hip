@@ -33,6 +33,9 @@ struct PulseArgs {
   ConvGeom conv;                        // convolution layer: X is the NHWC image and row m of the layer's
                                         //   input matrix is gathered from it (CONV variant of the train kernel)
   int coded, tx, td;                    // deterministic pulse coding: tx frames of td sub-slots
+  unsigned long long* marks;            // two-phase walk: [n_words][K N] one bit per sample and device
+  unsigned long long* summary;          //   [ceil(n_words / 64)][K N] one bit per word that is not empty
+  int n_words;                          //   64-sample words of the current chunk
 };
 
 __device__ __forceinline__ uint32_t pulse_train(uint32_t k0, uint32_t k1, uint64_t step, uint64_t index, double p, int bl) {
@@ -242,9 +245,110 @@ __global__ __launch_bounds__(256) void pulse_apply_kernel(PulseArgs a) {
     }
 }
 
+// Two-phase walk for layers with few devices and many samples (convolution layers: a 144 x 16 layer has
+// 9 blocks of devices and 131072 samples).  Phase 1, one block per (16 x 16 devices, stage of 256
+// samples at a time, 4096 per block), fills the chip: it marks the samples in which a device's row and
+// column share a slot, one bit per sample and device, plus one summary bit per 64-sample word that is
+// not empty.  Phase 2, one thread per device, walks only the marked samples, in order (summary ->
+// word -> sample), fetching their two trains from memory: the sequential part shrinks to the pulses.
+__global__ __launch_bounds__(256) void pulse_mark_kernel(PulseArgs a) {
+  constexpr int TE = 16, ST = 256, LD = ST + 4, PER = ST * TE / 256, NW = ST / 64, SEG = 64 * 64;
+  __shared__ __align__(16) uint32_t rt[TE * LD];
+  __shared__ __align__(16) uint32_t ct[TE * LD];
+  const int nb = (a.N + TE - 1) / TE, tiles = ((a.K + TE - 1) / TE) * nb;
+  const int tile = blockIdx.x % tiles, seg = blockIdx.x / tiles;     // segment = 64 words = 4096 samples
+  const int kt = (tile / nb) * TE, nt = (tile % nb) * TE;
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  const int k = kt + ty, n = nt + tx;
+  const bool valid = k < a.K && n < a.N;
+  const uint32_t* rp = &rt[ty * LD];
+  const uint32_t* cp = &ct[tx * LD];
+  const size_t kn = (size_t)a.K * a.N, dev = (size_t)k * a.N + n;
+  unsigned long long summary = 0;                  // bit = word of the segment that has a marked sample
+  for (int s0 = seg * SEG; s0 < min(a.mc, (seg + 1) * SEG); s0 += ST) {
+    const int ns = min(ST, a.mc - s0);
+    __syncthreads();                               // everyone is done with the previous stage
+#pragma unroll
+    for (int u = 0; u < PER; ++u) {
+      const int e = threadIdx.x + 256 * u, sm = e / TE, c = e % TE;
+      const bool live = sm < ns;
+      rt[c * LD + sm] = (live && kt + c < a.K) ? a.rows[(size_t)(s0 + sm) * a.K + kt + c] : 0u;
+      ct[c * LD + sm] = (live && nt + c < a.N) ? a.cols[(size_t)(s0 + sm) * a.N + nt + c] : 0u;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const int word = s0 / 64 + w;
+      unsigned long long bits = 0;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int at = 64 * w + 4 * v;
+        const u32x4 r = *reinterpret_cast<const u32x4*>(rp + at);
+        const u32x4 c = *reinterpret_cast<const u32x4*>(cp + at);
+        const uint32_t four = (min(r.x & c.x & 0x7FFFFFFFu, 1u)) | (min(r.y & c.y & 0x7FFFFFFFu, 1u) << 1) |
+                              (min(r.z & c.z & 0x7FFFFFFFu, 1u) << 2) | (min(r.w & c.w & 0x7FFFFFFFu, 1u) << 3);
+        bits |= (unsigned long long)four << (4 * v);
+      }
+      if (valid && word < a.n_words) {
+        a.marks[(size_t)word * kn + dev] = bits;
+        if (bits) summary |= 1ull << (word - 64 * seg);
+      }
+    }
+  }
+  if (valid) a.summary[(size_t)seg * kn + dev] = summary;
+}
+
+template <bool NL, bool NOISE>
+__global__ __launch_bounds__(256) void pulse_walk_kernel(PulseArgs a) {
+  const size_t kn = (size_t)a.K * a.N;
+  const size_t dev = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (dev >= kn) return;
+  const int k = (int)(dev / a.N), n = (int)(dev % a.N);
+  const uint64_t step = effective_step(a.step, a.step_add);
+  const int n_seg = (a.n_words + 63) / 64;
+  double gs = a.first ? (double)a.W[dev] / a.w_max : a.state[dev];
+  int moved = 0, next_seg = 0, word_base = 0, seg_base = 0, m = 0, ord = 0;
+  unsigned long long word = 0, summary = 0;
+  uint32_t q = 0;
+  bool up = false;
+  // every lane for itself, one pulse per turn (as in pulse_apply_kernel)
+  for (;;) {
+    if (q == 0) {
+      if (word == 0) {                               // next word with a marked sample, by way of the summaries
+        while (summary == 0 && next_seg < n_seg) {
+          summary = a.summary[(size_t)next_seg * kn + dev];
+          seg_base = 64 * next_seg;
+          ++next_seg;
+        }
+        if (summary == 0) break;                     // no marked sample left
+        const int wi = seg_base + __builtin_ctzll(summary);
+        summary &= summary - 1;
+        word = a.marks[(size_t)wi * kn + dev];       // not empty: its summary bit is set
+        word_base = 64 * wi;
+      }
+      const int at = word_base + __builtin_ctzll(word);
+      word &= word - 1;
+      const uint32_t rw = a.rows[(size_t)at * a.K + k], cw = a.cols[(size_t)at * a.N + n];
+      q = rw & cw & 0x7FFFFFFFu;                     // not empty: the sample is marked
+      up = ((rw ^ cw) >> 31) != 0;
+      m = a.m0 + at;
+      ord = 0;
+    }
+    q &= q - 1;
+    gs = one_pulse<NL, NOISE>(a, gs, up, m, ord, (uint64_t)dev, step);
+    ++ord;
+    moved += up ? 1 : -1;
+  }
+  if (a.last) a.W[dev] = (float)(a.w_max * gs);
+  else a.state[dev] = gs;
+  if (a.pulses) a.pulses[dev] = (a.first ? 0 : a.pulses[dev]) + moved;
+}
+
 struct PulsePlan {
   int mc;                       // samples per chunk (the trains of one chunk are resident at a time)
   size_t rows_bytes, cols_bytes, ws_bytes;
+  int two_phase;                // mark, then walk the marked samples (few devices, many samples)
+  size_t marks_bytes;
 };
 
 PulsePlan plan_pulsed(int M, int K, int N) {
@@ -255,6 +359,11 @@ PulsePlan plan_pulsed(int M, int K, int N) {
   p.rows_bytes = align256((size_t)4 * p.mc * K);
   p.cols_bytes = align256((size_t)4 * p.mc * N);
   p.ws_bytes = p.rows_bytes + p.cols_bytes + align256((size_t)8 * K * N);
+  // fewer blocks of 16 x 16 devices than compute units, and enough samples for the marking pass to pay
+  p.marks_bytes = align256((size_t)cdiv(p.mc, 64) * 8 * (size_t)K * N) + align256((size_t)cdiv(p.mc, 4096) * 8 * (size_t)K * N);
+  p.two_phase = (long long)cdiv(K, 16) * cdiv(N, 16) < 256 && M >= 2048 && p.marks_bytes <= ((size_t)256 << 20);
+  if (p.two_phase) p.ws_bytes += p.marks_bytes;
+  else p.marks_bytes = 0;
   return p;
 }
 
@@ -284,6 +393,10 @@ int run_update_pulsed(const xbar_config* cfg, float* W, const float* X, const fl
   a.cols = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(ws) + p.rows_bytes);
   a.state = reinterpret_cast<double*>(reinterpret_cast<char*>(ws) + p.rows_bytes + p.cols_bytes);
   a.pulses = pulses;
+  a.marks = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(ws) + p.rows_bytes + p.cols_bytes +
+                                                  align256((size_t)8 * K * N));
+  a.summary = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(a.marks) +
+                                                    align256((size_t)cdiv(p.mc, 64) * 8 * (size_t)K * N));
   a.M = M; a.K = K; a.N = N; a.bl = bl;
   a.flags = cfg->flags;
   a.w_max = (double)w_max; a.x_range = (double)x_range; a.d_range = (double)d_range; a.dw_min = (double)dw_min;
@@ -313,6 +426,17 @@ int run_update_pulsed(const xbar_config* cfg, float* W, const float* X, const fl
     else hipLaunchKernelGGL(pulse_trains_kernel<false>, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
     const bool nl = (cfg->flags & XBAR_NI_UPD_NL) != 0, noise = (cfg->flags & XBAR_NI_UPD_NOISE) != 0;
+    if (p.two_phase) {
+      a.n_words = cdiv(a.mc, 64);
+      const unsigned tiles16 = (unsigned)(cdiv(K, 16) * cdiv(N, 16));
+      hipLaunchKernelGGL(pulse_mark_kernel, dim3(tiles16 * (unsigned)cdiv(a.mc, 4096)), dim3(256), 0, st, a);
+      if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+      void (*walk)(PulseArgs) = nl ? (noise ? pulse_walk_kernel<true, true> : pulse_walk_kernel<true, false>)
+                                   : (noise ? pulse_walk_kernel<false, true> : pulse_walk_kernel<false, false>);
+      hipLaunchKernelGGL(walk, dim3((unsigned)cdiv(K * N, 256)), dim3(256), 0, st, a);
+      if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+      continue;
+    }
     void (*k)(PulseArgs);
     if (patch4)
       k = nl ? (noise ? pulse_apply_kernel<4, true, true> : pulse_apply_kernel<4, true, false>)

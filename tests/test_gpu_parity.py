@@ -687,6 +687,11 @@ PULSED_CASES = [
     ("large_layer_linear", 70, 2048, 1030, 31, 2.0, 0.05, "", 1.0),
     ("large_layer_nl", 140, 2048, 1030, 12, 2.0, 0.1, "nl", 1.0),        # three stages of 64 samples
     ("large_layer_noise", 70, 2048, 1030, 31, 4.0, 0.4, "noise", 1.0),
+    # few devices, many samples: marks first, then a walk over the marked samples only
+    ("marked_walk", 2500, 40, 24, 31, 3.0, 0.03, "nl+noise", 1.0),
+    ("marked_walk_linear", 2048, 17, 70, 9, 3.0, 0.03, "", 1.0),
+    ("marked_walk_dense", 2100, 16, 16, 31, 0.5, 0.005, "nl", 1.0),           # most samples marked
+    ("marked_walk_two_chunks", 140000, 100, 30, 4, 3.0, 0.03, "noise", 1.0),   # 129024 samples resident at a time
     # deterministic time-coded pulses: frames x sub-slots instead of random trains
     ("coded_ragged", 130, 70, 100, 31, 2.0, 0.02, "coded", 1.5),
     ("coded_nl_noise", 90, 128, 65, 16, 1.0, 0.01, "coded+nl+noise", 1.0),
@@ -732,6 +737,7 @@ CONV_PULSED_CASES = [
     (2, 8, 8, 16, 3, 1, 1, 24, ""),
     (2, 6, 6, 12, 1, 1, 0, 10, "nl"),               # 1 x 1: the image is the patch matrix
     (2, 16, 16, 64, 3, 1, 1, 600, "noise"),         # 4 x 4 devices per thread, two stages of samples
+    (9, 16, 16, 4, 3, 1, 1, 20, "nl+noise"),        # 2304 positions on 36 x 20 devices: marks, then the walk
 ]
 
 

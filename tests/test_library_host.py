@@ -95,7 +95,15 @@ def test_size_queries(xb):
     pad = lambda b: -(-b // 256) * 256
     assert xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 100, K, N) == pad(400 * K) + pad(400 * N) + pad(8 * K * N)
     big = xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 1 << 22, K, N)
-    assert big - pad(8 * K * N) <= (64 << 20) + 512 and big > xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 100, K, N)
+    mc_big = ((64 << 20) // (4 * (K + N))) // 64 * 64
+    marks = pad(mc_big // 64 * 8 * K * N) + pad(-(-mc_big // 4096) * 8 * K * N)                       # 40 blocks of devices: the marking pass is used
+    assert big - pad(8 * K * N) - marks <= (64 << 20) + 512 and big > xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 100, K, N)
+    assert xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 1 << 22, 2048, 1030) - pad(8 * 2048 * 1030) <= (64 << 20) + 512
+    # few devices, many samples (a convolution layer): one mark bit per sample and device on top
+    mc = ((64 << 20) // (4 * (144 + 16))) // 64 * 64
+    assert xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 131072, 144, 16) == (
+        pad(4 * mc * 144) + pad(4 * mc * 16) + pad(8 * 144 * 16) + pad(-(-mc // 64) * 8 * 144 * 16) + pad(-(-mc // 4096) * 8 * 144 * 16))
+    assert xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 2047, 144, 16) == pad(4 * 2047 * 144) + pad(4 * 2047 * 16) + pad(8 * 144 * 16)
     # circuit-level model: 5 crossbar-sized fp64 vectors per resident block, at most 2048 blocks
     items = 2 * 1 * 8 * 2                                   # (row tiles x column tiles) x slices x arrays
     assert xb.workspace_bytes(c, xb.OP_FCM, 1, K, N) % (5 * 128 * 128 * 8) == 0
