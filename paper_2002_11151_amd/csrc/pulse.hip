@@ -344,6 +344,8 @@ __global__ __launch_bounds__(256) void pulse_walk_kernel(PulseArgs a) {
   if (a.pulses) a.pulses[dev] = (a.first ? 0 : a.pulses[dev]) + moved;
 }
 
+constexpr int kTwoPhaseBlocks = 4096;
+
 struct PulsePlan {
   int mc;                       // samples per chunk (the trains of one chunk are resident at a time)
   size_t rows_bytes, cols_bytes, ws_bytes;
@@ -355,15 +357,21 @@ PulsePlan plan_pulsed(int M, int K, int N) {
   PulsePlan p;
   const long long per_sample = 4ll * ((long long)K + N);
   long long mc = std::max(64ll, ((64ll << 20) / per_sample) / 64 * 64);
+  // mark-then-walk where one device per thread does not already come in thousands of blocks and there are
+  // enough samples for the marking pass to pay; its marks (one bit per sample and device) stay within 256 MiB
+  const long long kn = (long long)K * N;
+  const long long mark_samples = ((8ll << 28) / kn) / 4096 * 4096;
+  p.two_phase = (long long)cdiv(K, 16) * cdiv(N, 16) < kTwoPhaseBlocks && M >= 2048 && mark_samples >= 4096;
+  if (p.two_phase) mc = std::min(mc, mark_samples);
   p.mc = (int)std::min<long long>(mc, M);
   p.rows_bytes = align256((size_t)4 * p.mc * K);
   p.cols_bytes = align256((size_t)4 * p.mc * N);
   p.ws_bytes = p.rows_bytes + p.cols_bytes + align256((size_t)8 * K * N);
-  // fewer blocks of 16 x 16 devices than compute units, and enough samples for the marking pass to pay
-  p.marks_bytes = align256((size_t)cdiv(p.mc, 64) * 8 * (size_t)K * N) + align256((size_t)cdiv(p.mc, 4096) * 8 * (size_t)K * N);
-  p.two_phase = (long long)cdiv(K, 16) * cdiv(N, 16) < 256 && M >= 2048 && p.marks_bytes <= ((size_t)256 << 20);
-  if (p.two_phase) p.ws_bytes += p.marks_bytes;
-  else p.marks_bytes = 0;
+  p.marks_bytes = 0;
+  if (p.two_phase) {
+    p.marks_bytes = align256((size_t)cdiv(p.mc, 64) * 8 * (size_t)K * N) + align256((size_t)cdiv(p.mc, 4096) * 8 * (size_t)K * N);
+    p.ws_bytes += p.marks_bytes;
+  }
   return p;
 }
 

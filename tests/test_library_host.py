@@ -103,6 +103,9 @@ def test_size_queries(xb):
     mc = ((64 << 20) // (4 * (144 + 16))) // 64 * 64
     assert xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 131072, 144, 16) == (
         pad(4 * mc * 144) + pad(4 * mc * 16) + pad(8 * 144 * 16) + pad(-(-mc // 64) * 8 * 144 * 16) + pad(-(-mc // 4096) * 8 * 144 * 16))
+    # the marks stay within 256 MiB: 512 x 256 devices take 16384 samples at a time
+    assert xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 20000, 512, 256) == (
+        pad(4 * 16384 * 512) + pad(4 * 16384 * 256) + pad(8 * 512 * 256) + pad(256 * 8 * 512 * 256) + pad(4 * 8 * 512 * 256))
     assert xb.workspace_bytes(c, xb.OP_UPDATE_PULSED, 2047, 144, 16) == pad(4 * 2047 * 144) + pad(4 * 2047 * 16) + pad(8 * 144 * 16)
     # circuit-level model: 5 crossbar-sized fp64 vectors per resident block, at most 2048 blocks
     items = 2 * 1 * 8 * 2                                   # (row tiles x column tiles) x slices x arrays
