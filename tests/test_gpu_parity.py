@@ -739,6 +739,8 @@ CONV_PULSED_CASES = [
     (2, 6, 6, 12, 1, 1, 0, 10, "nl"),               # 1 x 1: the image is the patch matrix
     (2, 16, 16, 64, 3, 1, 1, 600, "noise"),         # 4 x 4 devices per thread, two stages of samples
     (9, 16, 16, 4, 3, 1, 1, 20, "nl+noise"),        # 2304 positions on 36 x 20 devices: marks, then the walk
+    (9, 16, 16, 4, 3, 1, 1, 20, "nl"),              # ... without noise: marks, then the staged kernel
+    (3, 9, 9, 5, 3, 2, 1, 20, "coded+nl"),          # deterministic time-coded pulses
 ]
 
 
@@ -753,6 +755,7 @@ def test_conv_pulsed_update(xo, xb, B, H, Wd, C, k, stride, pad, N, ni):
     OH, OW = conv.out_size(H, k, stride, pad), conv.out_size(Wd, k, stride, pad)
     dY = (rng.normal(size=(B, OH, OW, N)) * 1e-2).astype(np.float32)
     flags = (xo.UPD_NL if "nl" in ni else 0) | (xo.UPD_NOISE if "noise" in ni else 0)
+    flags |= xo.PULSE_CODED if "coded" in ni else 0
     co, cg = both_configs(xo, xb, flags=flags, upd_nl_v=1.3, upd_noise_gamma=0.4, seed=23)
     dw, bl, x_range, d_range = 2.0 ** -10, 31, 3.0, 0.04 if N < 100 else 0.4
     cols = conv.im2col(X, k, k, stride, pad)
