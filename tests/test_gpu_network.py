@@ -371,7 +371,7 @@ def test_interpolated_circuit_model_in_training():
     assert all(0.0 <= float(layer.profile.min()) and float(layer.profile.max()) < 0.5 for layer in net.layers)
     assert np.isfinite(losses).all() and np.mean(losses[-5:]) < 0.9 * losses[0], losses
 
-@pytest.mark.parametrize("kind", ["perceptron", "residual"])
+@pytest.mark.parametrize("kind", ["perceptron", "residual", "residual_pulsed"])
 def test_training_steps_from_a_hip_graph(kind):
     """A captured training step replays as the following steps: the device-side step counter gives every replay
     its own device variation and write noise, and weights and losses equal those of eagerly run steps bit for bit."""
@@ -394,6 +394,8 @@ def test_training_steps_from_a_hip_graph(kind):
         make = lambda: resnet_cifar.ResNetCifar(kw, batch=B, n_blocks=1, image=16, classes=10, widths=(16, 32, 64), seed=1)
     labels = [((torch.arange(B, device="cuda") + i) % 10).to(torch.int32) for i in range(4)]
     eager, graphed = make(), make()
+    if kind == "residual_pulsed":        # pulse trains and per-pulse noise are keyed by the step as well
+        eager.pulse = graphed.pulse = dict(bl=31, dw_min=1e-3)
     eager.calibrate(batches[0], labels[0])
     graphed.calibrate(batches[0], labels[0])
     want = [eager.train_step(x, l, 0.02).clone() for x, l in zip(batches, labels)]
