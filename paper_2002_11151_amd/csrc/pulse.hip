@@ -309,7 +309,7 @@ __global__ __launch_bounds__(256) void pulse_mark_kernel(PulseArgs a) {
 template <bool NL, bool NOISE>
 __global__ __launch_bounds__(256) void pulse_walk_kernel(PulseArgs a) {
   const size_t kn = (size_t)a.K * a.N;
-  const size_t dev = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t dev = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (dev >= kn) return;
   const int k = (int)(dev / a.N), n = (int)(dev % a.N);
   const uint64_t step = effective_step(a.step, a.step_add);
@@ -450,7 +450,7 @@ int run_update_pulsed(const xbar_config* cfg, float* W, const float* X, const fl
       if (noise) {
         // lanes decoupled over the whole chunk: with a normal number per pulse every turn counts
         void (*walk)(PulseArgs) = nl ? pulse_walk_kernel<true, true> : pulse_walk_kernel<false, true>;
-        hipLaunchKernelGGL(walk, dim3((unsigned)cdiv(K * N, 256)), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(walk, dim3((unsigned)cdiv(K * N, 64)), dim3(64), 0, st, a);     // one wave per block: spread over the chip
       } else {
         // cheap pulses: the trains of a stage in LDS beat the walk's loads from memory (measured 6.7 against
         // 9.6 ms on a 144 x 16 layer with 131072 samples; with noise 21 against 15 ms)
