@@ -72,15 +72,17 @@ def test_layer_full_size_sampled(xo, xb, workload, batch, name):
     assert rel_l2(Wg - Wh[np.ix_(k_idx, n_idx)], Wo - Wh[np.ix_(k_idx, n_idx)]) <= 1e-3
 
 
-@pytest.mark.parametrize("variant", ["per_array", "offset", "offset+per_array"])
+@pytest.mark.parametrize("variant", ["per_array", "offset", "offset+per_array", "adc12"])
 def test_converter_and_streaming_variants_full_size_sampled(xo, xb, variant):
     """One ResNet-50 layer (4608 x 512, 3136 rows) in the launch configuration of `bench.py --adc-per-array`
-    / `--offset-inputs`: sampled batch rows against the oracle."""
+    / `--offset-inputs` / `--adc-bits 12` (sums beyond 32 bits): sampled batch rows against the oracle."""
     gemms = {g.name: (i, g) for i, g in enumerate(workloads.resnet50_gemms(64, merge=True))}
     idx, g = gemms["s4b0_3x3"]
     kw = workloads.config_kwargs("resnet50")
     if "per_array" in variant:
         kw["flags"] |= workloads.ADC_PER_ARRAY
+    if variant == "adc12":
+        kw["adc_bits"] = 12
     if "offset" in variant:
         kw["flags"] |= workloads.INPUT_OFFSET
         kw["adc_fs_fwd"] *= 4.0
