@@ -693,6 +693,8 @@ PULSED_CASES = [
     ("marked_walk_dense", 2100, 16, 16, 31, 0.5, 0.005, "nl", 1.0),           # most samples marked
     ("marked_walk_two_chunks", 140000, 100, 30, 4, 3.0, 0.03, "noise", 1.0),   # 129024 samples resident at a time
     ("marked_walk_mark_chunks", 20000, 512, 256, 4, 3.0, 0.03, "noise", 1.0),  # marks of 16384 samples at a time
+    # an early convolution layer of ResNet-20 at its full size (batch 128 x 32 x 32 positions), pulse density of the benchmark
+    ("early_conv_full_size", 131072, 144, 16, 31, 5.0, 0.5, "nl+noise", 1.0),
     # deterministic time-coded pulses: frames x sub-slots instead of random trains
     ("coded_ragged", 130, 70, 100, 31, 2.0, 0.02, "coded", 1.5),
     ("coded_nl_noise", 90, 128, 65, 16, 1.0, 0.01, "coded+nl+noise", 1.0),
