@@ -597,10 +597,14 @@ uint32_t xo_pulse_train(uint64_t seed, uint32_t stream, uint64_t step, uint64_t 
   return bits;
 }
 
-int xo_update_pulsed(const xo_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N,
-                     float w_max, float x_range, float d_range, int bl, float dw_min, uint64_t step,
-                     int64_t* pulses_out) {
-  if (bl < 1 || bl > 31 || M <= 0 || K <= 0 || N <= 0) return -1;
+/* Sampled form: W[K][N], X[M][K], dY[M][N] are the devices at absolute rows k_idx[] and columns n_idx[]  */
+/* of a layer with K_full x N_full devices (NULL: the layer itself); devices are independent, so the    */
+/* sampled ones end exactly where they end in the whole layer.                                          */
+int xo_update_pulsed_at(const xo_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N,
+                        const int32_t* k_idx, const int32_t* n_idx, int K_full, int N_full,
+                        float w_max, float x_range, float d_range, int bl, float dw_min, uint64_t step,
+                        int64_t* pulses_out) {
+  if (bl < 1 || bl > 31 || M <= 0 || K <= 0 || N <= 0 || K_full < K || N_full < N) return -1;
   double* g = (double*)malloc(sizeof(double) * (size_t)K * N);
   uint32_t* a = (uint32_t*)malloc(sizeof(uint32_t) * ((size_t)K + N));
   if (!g || !a) { free(g); free(a); return -2; }
@@ -620,14 +624,16 @@ int xo_update_pulsed(const xo_config* cfg, float* W, const float* X, const float
     /* bit 31 of a train carries the sign of its value */
     for (int k = 0; k < K; ++k) {
       const double x = (double)X[(size_t)m * K + k];
+      const uint64_t kf = k_idx ? (uint64_t)k_idx[k] : (uint64_t)k;
       a[k] = (coded ? xo_pulse_code(fabs(x) / (double)x_range, bl, 0)
-                    : xo_pulse_train(cfg->seed, XO_STREAM_PULSE_ROWS, step, (uint64_t)m * K + k, fabs(x) / (double)x_range, bl)) |
+                    : xo_pulse_train(cfg->seed, XO_STREAM_PULSE_ROWS, step, (uint64_t)m * K_full + kf, fabs(x) / (double)x_range, bl)) |
              (x < 0.0 ? 0x80000000u : 0u);
     }
     for (int n = 0; n < N; ++n) {
       const double d = (double)dY[(size_t)m * N + n];
+      const uint64_t nf = n_idx ? (uint64_t)n_idx[n] : (uint64_t)n;
       b[n] = (coded ? xo_pulse_code(fabs(d) / (double)d_range, bl, 1)
-                    : xo_pulse_train(cfg->seed, XO_STREAM_PULSE_COLS, step, (uint64_t)m * N + n, fabs(d) / (double)d_range, bl)) |
+                    : xo_pulse_train(cfg->seed, XO_STREAM_PULSE_COLS, step, (uint64_t)m * N_full + nf, fabs(d) / (double)d_range, bl)) |
              (d < 0.0 ? 0x80000000u : 0u);
     }
     for (int k = 0; k < K; ++k)
@@ -637,7 +643,7 @@ int xo_update_pulsed(const xo_config* cfg, float* W, const float* X, const float
         int count = 0;
         for (uint32_t v = both; v; v &= v - 1) ++count;
         const double dir = ((a[k] ^ b[n]) & 0x80000000u) ? 1.0 : -1.0;   /* against the sign of x d */
-        const uint64_t dev = (uint64_t)k * N + n;
+        const uint64_t dev = (k_idx ? (uint64_t)k_idx[k] : (uint64_t)k) * (uint64_t)N_full + (n_idx ? (uint64_t)n_idx[n] : (uint64_t)n);
         double* gs = &g[(size_t)k * N + n];
         for (int j = 0; j < count; ++j) {
           double move = (double)dw_min;
@@ -657,6 +663,12 @@ int xo_update_pulsed(const xo_config* cfg, float* W, const float* X, const float
   free(g);
   free(a);
   return 0;
+}
+
+int xo_update_pulsed(const xo_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N,
+                     float w_max, float x_range, float d_range, int bl, float dw_min, uint64_t step,
+                     int64_t* pulses_out) {
+  return xo_update_pulsed_at(cfg, W, X, dY, M, K, N, NULL, NULL, K, N, w_max, x_range, d_range, bl, dw_min, step, pulses_out);
 }
 
 unsigned xo_config_size(void) { return (unsigned)sizeof(xo_config); }

@@ -280,18 +280,24 @@ def pulse_frames(bl):
     return tx.value, td.value
 
 
-def update_pulsed(cfg, W, X, dY, w_max, x_range, d_range, bl, dw_min, step=0, want_pulses=False):
+def update_pulsed(cfg, W, X, dY, w_max, x_range, d_range, bl, dw_min, step=0, want_pulses=False, k_idx=None, n_idx=None,
+                  K_full=None, N_full=None):
     """Pulse-level update, one sample at a time (stochastic trains, or deterministic codes with PULSE_CODED):
-    returns the updated copy of W (and the signed number of pulses every device received, if asked)."""
+    returns the updated copy of W (and the signed number of pulses every device received, if asked).  With k_idx /
+    n_idx the arguments are the devices at those rows / columns of a K_full x N_full layer."""
     W = _f32(W).copy()
     X, dY = _f32(X), _f32(dY)
     M, K = X.shape
     N = dY.shape[1]
     assert W.shape == (K, N) and dY.shape[0] == M
     pulses = np.empty((K, N), dtype=np.int64) if want_pulses else None
-    rc = lib().xo_update_pulsed(C.byref(cfg), _p(W, C.c_float), _p(X, C.c_float), _p(dY, C.c_float), M, K, N,
-                                C.c_float(w_max), C.c_float(x_range), C.c_float(d_range), C.c_int(bl),
-                                C.c_float(dw_min), C.c_uint64(step), _p(pulses, C.c_int64))
+    k_idx, n_idx = _idx(k_idx), _idx(n_idx)
+    assert (k_idx is None or len(k_idx) == K) and (n_idx is None or len(n_idx) == N)
+    rc = lib().xo_update_pulsed_at(C.byref(cfg), _p(W, C.c_float), _p(X, C.c_float), _p(dY, C.c_float), M, K, N,
+                                   _p(k_idx, C.c_int32), _p(n_idx, C.c_int32), K if K_full is None else K_full,
+                                   N if N_full is None else N_full, C.c_float(w_max), C.c_float(x_range),
+                                   C.c_float(d_range), C.c_int(bl), C.c_float(dw_min), C.c_uint64(step),
+                                   _p(pulses, C.c_int64))
     assert rc == 0, rc
     return (W, pulses) if want_pulses else W
 

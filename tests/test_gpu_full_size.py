@@ -115,6 +115,34 @@ def test_converter_and_streaming_variants_full_size_sampled(xo, xb, variant):
     assert np.abs(dX[rt].cpu().numpy() - dXo).max() <= 1.01 * lsb_b
 
 
+@pytest.mark.parametrize("name,ni", [("s4b0_3x3", "nl+noise"), ("s3b0_1x1b", "noise")])
+def test_pulsed_update_full_size_sampled(xo, xb, name, ni):
+    """Pulse-level update of whole ResNet-50 layers in the configuration `bench.py --pulsed-update` times
+    (4608 x 512 devices: 4 x 4 per thread; 256 x 1024: marking pass and walk): sampled devices against the oracle."""
+    gemms = {g.name: (i, g) for i, g in enumerate(workloads.resnet50_gemms(64, merge=True))}
+    idx, g = gemms[name]
+    kw = workloads.config_kwargs("resnet50")
+    kw["flags"] = (workloads.NI_UPD_NL if "nl" in ni else 0) | workloads.NI_UPD_NOISE
+    co, cg = xo.make_config(**kw), xb.make_config(**kw)
+    W, X, dY = workloads.layer_tensors_torch(g, seed=idx, device="cuda")
+    w_max, xs = 2.0 * float(W.abs().max()), float(X.abs().max())
+    bl, dw = 31, 1e-3
+    d_range = bl * dw * w_max / (0.01 * xs)
+    W0 = W.clone()
+    _, pulses = xb.update_pulsed(cg, W, X, dY, w_max, xs, d_range, bl, dw, step=2, want_pulses=True)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(idx)
+    ks = np.sort(rng.choice(g.K, size=10, replace=False))
+    ns = np.sort(rng.choice(g.N, size=10, replace=False))
+    ks[0], ks[-1], ns[0], ns[-1] = 0, g.K - 1, 0, g.N - 1
+    kt, nt = torch.from_numpy(ks).cuda(), torch.from_numpy(ns).cuda()
+    Wo, po = xo.update_pulsed(co, W0[kt][:, nt].cpu().numpy(), X[:, kt].cpu().numpy(), dY[:, nt].cpu().numpy(), w_max, xs, d_range,
+                              bl, dw, step=2, want_pulses=True, k_idx=ks, n_idx=ns, K_full=g.K, N_full=g.N)
+    assert np.array_equal(pulses[kt][:, nt].cpu().numpy(), po)
+    assert np.abs(W[kt][:, nt].cpu().numpy() - Wo).max() <= 2e-7 * w_max
+    assert not np.array_equal(Wo, W0[kt][:, nt].cpu().numpy())
+
+
 def _patch(X, b, oh, ow, k, stride, pad):
     """Patch of output position (b, oh, ow) of the NHWC host array X, index (kh, kw, c), zeros outside."""
     H, W, C = X.shape[1:]

@@ -977,6 +977,27 @@ def test_pulsed_update_is_unbiased_outer_product(xo):
     assert np.abs(mean).max() > 20 * sigma.max() / 4.5            # the test can see a wrong factor or sign
 
 
+def test_pulsed_update_of_sampled_devices(xo):
+    """Devices are independent: updating the devices at some rows and columns of a layer gives exactly their
+    entries of the whole layer's update (same trains, same noise numbers)."""
+    rng = np.random.default_rng(31)
+    M, K, N, bl, dw = 40, 23, 17, 31, 2.0 ** -9
+    X = rng.uniform(-1.5, 1.5, size=(M, K)).astype(np.float32)
+    dY = rng.uniform(-0.3, 0.3, size=(M, N)).astype(np.float32)
+    W0 = rng.uniform(-0.5, 0.5, size=(K, N)).astype(np.float32)
+    for flags in (0, xo.UPD_NL | xo.UPD_NOISE, xo.PULSE_CODED | xo.UPD_NOISE):
+        cfg = xo.make_config(flags=flags, upd_nl_v=0.8, upd_noise_gamma=0.7, seed=13)
+        W1, p1 = xo.update_pulsed(cfg, W0, X, dY, 1.2, 1.0, 0.2, bl, dw, step=4, want_pulses=True)
+        ks, ns = np.array([0, 5, 22, 11]), np.array([16, 3, 4])
+        Ws, ps = xo.update_pulsed(cfg, W0[np.ix_(ks, ns)], X[:, ks], dY[:, ns], 1.2, 1.0, 0.2, bl, dw, step=4, want_pulses=True,
+                                  k_idx=ks, n_idx=ns, K_full=K, N_full=N)
+        assert np.array_equal(ps, p1[np.ix_(ks, ns)]) and np.array_equal(Ws, W1[np.ix_(ks, ns)])
+        assert np.abs(p1).max() > 5
+        if not flags & xo.PULSE_CODED:      # without the positions the trains are other trains
+            Wn, pn = xo.update_pulsed(cfg, W0[np.ix_(ks, ns)], X[:, ks], dY[:, ns], 1.2, 1.0, 0.2, bl, dw, step=4, want_pulses=True)
+            assert not np.array_equal(pn, ps)
+
+
 def test_coded_pulses_multiply(xo):
     """Deterministic pulse coding: rows hold whole frames, columns fire sub-slots of every frame, so a device
     sees (coded |x|) x (coded |d|) coincidences; on the coding grid the written change IS the outer product."""
