@@ -21,6 +21,12 @@
 // read as fp16, the subnormal number digit * 2^(shift-24).  The matrix cores of gfx950 take fp16
 // subnormals exactly, so one AND with a digit mask turns the raw magnitudes into the A operand of
 // any streaming cycle; the power of two is folded into the ADC gain.
+//
+// Cycles of 1 or 2 bits (the paper's streaming scheme) run on the block-scaled 6-bit / 4-bit matrix
+// instruction instead (v_mfma_scale_f32_32x32x64_f8f6f4: 64 rows per instruction in the time fp16 takes
+// for 16): a digit d is the E2M1 code d (value d / 2), a plane value is a sum of E2M3 numbers times
+// powers of two that the instruction applies as block scales (xbar_common.h), accumulated in fp32 with
+// the leading term first.
 #include "xbar_common.h"
 
 using namespace xbar_detail;
@@ -44,6 +50,7 @@ struct TileArgs {
   uint64_t seed, step;
   const unsigned long long* step_add;   // optional device counter added to step
   long long n_threads;
+  int term_exp[kMaxTermsF6];            // kFmtF6: power of two of every term
 };
 
 // Plane value of slice s of weight (k, n), in units of one device level: the signed difference of the
@@ -131,6 +138,99 @@ __global__ __launch_bounds__(256) void tile_planes_kernel(TileArgs a) {
   const size_t chunk = ((blk0 + s) * a.terms * a.ks + j) * 64 + lane;   // in 16-byte units
   reinterpret_cast<u32x4*>(a.planes)[chunk] = hi.v;
   if (a.terms == 2) reinterpret_cast<u32x4*>(a.planes)[chunk + (size_t)a.ks * 64] = lo.v;
+}
+
+// E2M3 number (1 sign, 2 exponent, 3 mantissa bits, bias 1: multiples of 1/8 up to 2, of 1/4 up to 4, of
+// 1/2 up to 7.5) nearest to x; returns its 6-bit code and the number itself.
+__device__ __forceinline__ uint32_t e2m3_nearest(double x, double& value) {
+  const double a = ::fabs(x);
+  uint32_t code;
+  double v;
+  if (a < 2.0) {
+    const double k = ::rint(a * 8.0);                 // 0 .. 16; codes continue linearly into the next binade
+    code = (uint32_t)k;
+    v = k * 0.125;
+  } else if (a < 4.0) {
+    const double k = ::rint(a * 4.0);                 // 8 .. 16
+    code = 8u + (uint32_t)k;
+    v = k * 0.25;
+  } else {
+    const double k = ::fmin(::rint(a * 2.0), 15.0);   // 8 .. 15: 7.5 is the largest number
+    code = 16u + (uint32_t)k;
+    v = k * 0.5;
+  }
+  if (x < 0.0 && code) {
+    code |= 32u;
+    v = -v;
+  }
+  value = v;
+  return code;
+}
+
+// Planes in the 6-bit format: one thread produces the 8 contraction entries (48 bits per term) that one
+// byte pair group of the input stage covers, for one output column and one slice (blockIdx.y).
+// Thread -> (output index fastest, then the 8-entry slot of the tile, then the tile); slots of k-steps
+// that the tile does not reach are skipped, slots beyond its rows inside a k-step are written as zeros.
+template <bool TRANSPOSED>
+__global__ __launch_bounds__(256) void tile_planes_f6_kernel(TileArgs a) {
+  const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (tid >= a.n_threads) return;
+  const int out_len_pad = a.OP * 32;
+  const int o = (int)(tid % out_len_pad);
+  const int cg = (int)(tid / out_len_pad);
+  const int slots = a.ks * 8;                       // 8-entry slots per tile (whole k-steps of 64)
+  const int t = cg / slots, slot = cg - t * slots;
+  const int within = slot * 8;
+  const int Lc = TRANSPOSED ? a.N : a.K;
+  const int Lo = TRANSPOSED ? a.K : a.N;
+  const int rows = min(a.tile, Lc - t * a.tile);
+  const int J = within >> 6;
+  if (J * 64 >= rows) return;                       // the contraction never reads this k-step
+  const int w = (within & 63) >> 4, half = (within & 15) >> 3;
+  const int lane = (o & 31) + 32 * half;
+  const int op = o >> 5;
+  const int c0 = t * a.tile + within;
+  const int s = blockIdx.y;
+
+  NormalStream rng(a.seed, kStreamVariation, effective_step(a.step, a.step_add));
+  const double qw = (double)((1u << a.weight_bits) - 1);
+  const uint32_t dmask = (1u << a.slice_bits) - 1;
+  unsigned long long bits[kMaxTermsF6];
+#pragma unroll
+  for (int j = 0; j < kMaxTermsF6; ++j) bits[j] = 0ull;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int c = c0 + e;
+    if (within + e >= rows || o >= Lo) continue;
+    const int k = TRANSPOSED ? o : c, n = TRANSPOSED ? c : o;
+    const double q = ::rint(clampd((double)a.W[(size_t)k * a.N + n] / (double)a.w_max, -1.0, 1.0) * qw);
+    const int sign = (q > 0.0) - (q < 0.0);
+    const uint32_t mag = (uint32_t)::fabs(q);
+    double left = plane_value(a, rng, sign, (int)((mag >> (a.slice_bits * s)) & dmask), s, k, n);
+    const int nibble = 2 * (e & 3) + (e >> 2);       // where the input stage's byte e lands in the digit word
+#pragma unroll
+    for (int j = 0; j < kMaxTermsF6; ++j) {
+      if (j >= a.terms) break;
+      double v;
+      const uint32_t code = e2m3_nearest(::ldexp(left, -a.term_exp[j]), v);
+      left -= ::ldexp(v, a.term_exp[j]);
+      bits[j] |= (unsigned long long)code << (6 * nibble);
+    }
+  }
+  // 24-byte record of the lane: bytes 0..15 in the fragment's first KiB, 16..23 in its last half KiB
+  const size_t frag0 = (((size_t)t * a.OP + op) * a.S_w + s) * a.terms * a.ks + J;
+  uint8_t* base = reinterpret_cast<uint8_t*>(a.planes);
+#pragma unroll
+  for (int j = 0; j < kMaxTermsF6; ++j) {
+    if (j >= a.terms) break;
+    uint8_t* frag = base + (frag0 + (size_t)j * a.ks) * 1536;
+#pragma unroll
+    for (int h = 0; h < 3; ++h) {
+      const int off = 6 * w + 2 * h;
+      uint8_t* dst = off < 16 ? frag + lane * 16 + off : frag + 1024 + lane * 8 + (off - 16);
+      *reinterpret_cast<uint16_t*>(dst) = (uint16_t)(bits[j] >> (16 * h));
+    }
+  }
 }
 
 
@@ -290,6 +390,9 @@ struct VmmArgs {
   int npol;                   // converters per column (1: differential, 2: one per array); VT = P * npol * T
   size_t pol_stride;          // 16-byte units between the planes of the two arrays
   int S_w, S_in, slice_bits, stream_bits, ks, tile;
+  int ks16;                   // k-steps of 16 rows per tile in the staged input (= ks with fp16 planes)
+  int sg;                     // kFmtF6: slices per staged group
+  int scale_lo, scale_hi;     // kFmtF6: block-scale bytes (127 + exponent) of terms 0..3 and of term 4
   int vt_per_chunk, nchunk, lds_kb;
   int split_sg;               // slices per 32-bit group of the split wide path
   int direct;                 // single chunk and nothing to correct: the kernel scales and stores the result itself
@@ -499,6 +602,57 @@ __device__ __forceinline__ void vmm_tile_group_pipelined(const VmmArgs& a, const
   vmm_adc_narrow<PM>(acc1, gain_prev, clamp_lo, clamp_hi, sh_prev, y);   // drain
 }
 
+// ADC + shift-and-add of one (slice, cycle) for the general kernel variants: 32- or 64-bit sums, optional
+// transfer curve, code tap or statistics.  Same code decision as the three-operation form.
+template <int PM, bool WIDE, bool CODES, bool PER_ARRAY>
+__device__ __forceinline__ void vmm_adc_general(const VmmArgs& a, const float16v (&acc)[PM], float gain_used, float clamp_lo,
+                                                float clamp_hi, int sh, int p, int pol, int b, int s, int t, int lane,
+                                                int mp0, int op, uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
+  const float vmagic = kMagic;
+  const int neg = PER_ARRAY ? p ^ pol : p;
+#pragma unroll
+  for (int pm = 0; pm < PM; ++pm) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      uint32_t bits;
+      if (CODES && a.adc_curve_on) {
+        // transfer curve on the true (phase-signed) current: x in [-1, 1], 16 linear pieces
+        const float u = acc[pm][r] * (p ? -gain_used : gain_used);          // ideal code units
+        const float v = fminf(fmaxf(u * a.inv_q_adc * 8.0f, -8.0f), 8.0f);    // x in units of one piece
+        const float start = fminf(floorf(v), 7.0f);                           // v - start is exact
+        const int piece = (int)start + 8;
+        const float lo = a.adc_curve[piece], hi = a.adc_curve[piece + 1];
+        const float fx = __builtin_fmaf(v - start, hi - lo, lo);
+        const float c = fminf(fmaxf(rintf(a.q_adc * fx), -a.q_adc), a.q_adc);
+        bits = kMagicBits + (uint32_t)(p ? -(int)c : (int)c);               // as the linear path leaves it
+      } else {
+        float f = __builtin_fmaf(acc[pm][r], gain_used, vmagic);
+        f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
+        bits = __builtin_bit_cast(uint32_t, f);
+      }
+      if (WIDE) {
+        y64[pm][r] += (long long)((int)(bits - kMagicBits)) << sh;
+      } else {
+        y[pm][r] = (bits << sh) + y[pm][r];
+      }
+      if (CODES) {
+        const int m = (mp0 + pm) * 32 + (lane & 31);
+        const int o = op * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m < a.M && o < a.Lout) {
+          int code = (int)(bits - kMagicBits);
+          if (a.hist) {
+            atomicAdd(&stat_hist[min(::abs(code), kStatBins - 1)], 1u);
+          } else if (a.codes) {
+            if (neg) code = -code;                   // what the converter itself read
+            const size_t converter = ((((size_t)p * a.S_in + b) * a.S_w + s) * (PER_ARRAY ? 2 : 1) + pol) * a.T + t;
+            a.codes[(converter * a.M + m) * a.Lout + o] = (int16_t)code;
+          }
+        }
+      }
+    }
+  }
+}
+
 // General slice group (64-bit accumulators and / or ADC code tap, any slice count): same arithmetic,
 // no software pipelining.
 template <int PM, int KSMAX, int NK, int TERMS, bool WIDE, bool CODES, bool PER_ARRAY>
@@ -507,8 +661,6 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
                                                uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
   constexpr int NF = TERMS * NK;
   const uint32_t digit_mask8 = ((1u << a.stream_bits) - 1u) * 0x01010101u;
-  const float vmagic = kMagic;
-  const int neg = PER_ARRAY ? p ^ pol : p;
   float gain_p, clamp_lo, clamp_hi;
   adc_sign_and_range<PER_ARRAY>(a, p, pol, gain_p, clamp_lo, clamp_hi);
   for (int b = 0; b < a.S_in; ++b) {
@@ -548,47 +700,8 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
         vmm_contract<PM, NK, TERMS>(ab, lds + lane + (size_t)sl * NF * 64, acc);
       }
       const float gain_used = (CODES && a.dac_levels) ? gain_lut : gain_b;
-#pragma unroll
-      for (int pm = 0; pm < PM; ++pm) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          uint32_t bits;
-          if (CODES && a.adc_curve_on) {
-            // transfer curve on the true (phase-signed) current: x in [-1, 1], 16 linear pieces
-            const float u = acc[pm][r] * (p ? -gain_used : gain_used);          // ideal code units
-            const float v = fminf(fmaxf(u * a.inv_q_adc * 8.0f, -8.0f), 8.0f);    // x in units of one piece
-            const float start = fminf(floorf(v), 7.0f);                           // v - start is exact
-            const int piece = (int)start + 8;
-            const float lo = a.adc_curve[piece], hi = a.adc_curve[piece + 1];
-            const float fx = __builtin_fmaf(v - start, hi - lo, lo);
-            const float c = fminf(fmaxf(rintf(a.q_adc * fx), -a.q_adc), a.q_adc);
-            bits = kMagicBits + (uint32_t)(p ? -(int)c : (int)c);               // as the linear path leaves it
-          } else {
-            float f = __builtin_fmaf(acc[pm][r], gain_used, vmagic);
-            f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
-            bits = __builtin_bit_cast(uint32_t, f);
-          }
-          if (WIDE) {
-            y64[pm][r] += (long long)((int)(bits - kMagicBits)) << sh;
-          } else {
-            y[pm][r] = (bits << sh) + y[pm][r];
-          }
-          if (CODES) {
-            const int m = (mp0 + pm) * 32 + (lane & 31);
-            const int o = op * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (m < a.M && o < a.Lout) {
-              int code = (int)(bits - kMagicBits);
-              if (a.hist) {
-                atomicAdd(&stat_hist[min(::abs(code), kStatBins - 1)], 1u);
-              } else if (a.codes) {
-                if (neg) code = -code;                   // what the converter itself read
-                const size_t converter = ((((size_t)p * a.S_in + b) * a.S_w + s) * (PER_ARRAY ? 2 : 1) + pol) * a.T + t;
-                a.codes[(converter * a.M + m) * a.Lout + o] = (int16_t)code;
-              }
-            }
-          }
-        }
-      }
+      vmm_adc_general<PM, WIDE, CODES, PER_ARRAY>(a, acc, gain_used, clamp_lo, clamp_hi, sh, p, pol, b, s, t, lane, mp0, op,
+                                                  y, y64);
     }
   }
 }
@@ -608,7 +721,7 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
 #pragma unroll
     for (int j = 0; j < NK; ++j) {
       u32x2 v = {0, 0};
-      if (mp0 + pm < a.MP) v = a.A[((((size_t)p * a.MP + mp0 + pm) * a.T + t) * a.ks + j) * 64 + lane];
+      if (mp0 + pm < a.MP) v = a.A[((((size_t)p * a.MP + mp0 + pm) * a.T + t) * a.ks16 + j) * 64 + lane];
       raw[pm][j] = v;
     }
   constexpr int NF = TERMS * NK;
@@ -644,9 +757,251 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// the same contraction on the 6-bit / 4-bit block-scaled matrix instruction (cycles of 1 or 2 bits)
+// ---------------------------------------------------------------------------------------------
+typedef int int4v __attribute__((ext_vector_type(4)));
+typedef int int8v __attribute__((ext_vector_type(8)));
+typedef int int16v __attribute__((ext_vector_type(16)));
+
+// LDS bytes of one (slice, term): its fragments of 1.5 KiB, rounded up to the whole KiB that the staging copies move
+__host__ __device__ constexpr int f6_term_stride(int nk64) { return ((nk64 * 1536 + 1023) / 1024) * 1024; }
+
+// Digits of one streaming cycle as E2M1 codes (digit d is code d, value d / 2): the bytes of two input
+// words become the low and the high 4-bit fields of one operand word (2 rotates, 1 AND, 1 AND-OR per
+// 8 inputs).  `low_mask` has the digit mask in every byte.
+template <int NK64>
+__device__ __forceinline__ void digit_codes_f4(const u32x2 (&raw)[4 * NK64], int in_shift, uint32_t low_mask, int4v (&dg)[NK64]) {
+  const uint32_t rot_lo = (uint32_t)in_shift & 31u, rot_hi = (uint32_t)(in_shift - 4) & 31u;
+#pragma unroll
+  for (int J = 0; J < NK64; ++J)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const u32x2 r = raw[4 * J + w];
+      const uint32_t lo = __builtin_amdgcn_alignbit(r.x, r.x, rot_lo) & low_mask;
+      dg[J][w] = (int)((__builtin_amdgcn_alignbit(r.y, r.y, rot_hi) & (low_mask << 4)) | lo);
+    }
+}
+
+// acc = c + 2^(scale of the term) * (E2M3 plane fragment) x (E2M1 digits); the scale byte of term 0..3 is
+// byte 0..3 of scale_lo, that of term 4 byte 0 of scale_hi; the digits carry no scale (127 = 2^0).
+__device__ __forceinline__ float16v mfma_f6_term(int term, const int8v& pa, const int8v& pb, const float16v& c, int scale_lo,
+                                                 int scale_hi) {
+  switch (term) {
+    case 0: return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa, pb, c, 2, 4, 0, scale_lo, 0, 127);
+    case 1: return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa, pb, c, 2, 4, 1, scale_lo, 0, 127);
+    case 2: return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa, pb, c, 2, 4, 2, scale_lo, 0, 127);
+    case 3: return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa, pb, c, 2, 4, 3, scale_lo, 0, 127);
+    default: return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(pa, pb, c, 2, 4, 0, scale_hi, 0, 127);
+  }
+}
+
+// Contraction of one (slice, cycle), terms in order (the leading term's sum is exact, the smaller terms
+// land on it), with the ADC / shift-and-add of the PREVIOUS (slice, cycle) woven in between the matrix
+// instructions.  xb / yb: this lane's address in the first KiB / last half KiB of the slice's first fragment.
+template <int PM, int NK64, int NT, bool DO_ADC>
+__device__ __forceinline__ void vmm6_contract_adc(const int4v (&dg)[PM][NK64], const char* xb, const char* yb,
+                                                  float16v (&acc)[PM], const float16v (&old)[PM], float gain_old,
+                                                  float clamp_lo, float clamp_hi, int sh_old, uint32_t (&y)[PM][16],
+                                                  int scale_lo, int scale_hi) {
+  constexpr int NF = NT * NK64;
+  constexpr int STRIDE = f6_term_stride(NK64);
+  constexpr int NV = 16 * PM;
+  const float vmagic = kMagic;
+  constexpr int PF = NF < 2 ? NF : 2;
+  u32x4 fx[PF];
+  u32x2 fy[PF];
+#pragma unroll
+  for (int i = 0; i < PF; ++i) {
+    const int off = (i / NK64) * STRIDE + (i % NK64) * 1536;
+    fx[i] = *reinterpret_cast<const u32x4*>(xb + off);
+    fy[i] = *reinterpret_cast<const u32x2*>(yb + off);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int i = 0; i < NF; ++i) {
+    const u32x4 cx = fx[i % PF];
+    const u32x2 cy = fy[i % PF];
+    if (i + PF < NF) {
+      const int off = ((i + PF) / NK64) * STRIDE + ((i + PF) % NK64) * 1536;
+      fx[i % PF] = *reinterpret_cast<const u32x4*>(xb + off);
+      fy[i % PF] = *reinterpret_cast<const u32x2*>(yb + off);
+    }
+    const int8v pa = {(int)cx.x, (int)cx.y, (int)cx.z, (int)cx.w, (int)cy.x, (int)cy.y, 0, 0};
+    const int term = i / NK64, J = i % NK64;
+#pragma unroll
+    for (int pm = 0; pm < PM; ++pm) {
+      const int8v pb = {dg[pm][J][0], dg[pm][J][1], dg[pm][J][2], dg[pm][J][3], 0, 0, 0, 0};
+      if (i == 0) {
+        const float16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        acc[pm] = mfma_f6_term(0, pa, pb, zero, scale_lo, scale_hi);
+      } else {
+        acc[pm] = mfma_f6_term(term, pa, pb, acc[pm], scale_lo, scale_hi);
+      }
+      if (DO_ADC) {
+        constexpr int NQ = NF * PM;
+        const int q = i * PM + pm;
+#pragma unroll
+        for (int v = (q * NV) / NQ; v < ((q + 1) * NV) / NQ; ++v) {
+          const int vp = v / 16, r = v % 16;
+          float f = __builtin_fmaf(old[vp][r], gain_old, vmagic);
+          f = __builtin_amdgcn_fmed3f(f, clamp_lo, clamp_hi);
+          y[vp][r] = (__builtin_bit_cast(uint32_t, f) << sh_old) + y[vp][r];
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+// Software-pipelined slice group (32-bit accumulators, no code tap, even slice count).
+template <int PM, int NK64, int NT, bool PER_ARRAY>
+__device__ __forceinline__ void vmm6_tile_group_pipelined(const VmmArgs& a, const char* lds, const u32x2 (&raw)[PM][4 * NK64],
+                                                          int ns, int shift_slice0, int p, int pol, int lane,
+                                                          uint32_t (&y)[PM][16]) {
+  constexpr int SLICE = NT * f6_term_stride(NK64);
+  const uint32_t low_mask = ((1u << a.stream_bits) - 1u) * 0x01010101u;
+  float gain_p, clamp_lo, clamp_hi;
+  adc_sign_and_range<PER_ARRAY>(a, p, pol, gain_p, clamp_lo, clamp_hi);
+  const float gain = 2.0f * gain_p;                   // a digit enters as d / 2
+  const char* xb = lds + lane * 16;
+  const char* yb = lds + 1024 + lane * 8;
+  int4v dg[PM][NK64];
+  float16v acc0[PM], acc1[PM];
+  int sh_prev = 0;
+  for (int b = 0; b < a.S_in; ++b) {
+    const int in_shift = a.stream_bits * b;
+#pragma unroll
+    for (int pm = 0; pm < PM; ++pm) digit_codes_f4<NK64>(raw[pm], in_shift, low_mask, dg[pm]);
+    for (int sl = 0; sl < ns; sl += 2) {
+      const int sh0 = a.slice_bits * (shift_slice0 + sl) + in_shift;
+      const int sh1 = sh0 + a.slice_bits;
+      if (b == 0 && sl == 0)
+        vmm6_contract_adc<PM, NK64, NT, false>(dg, xb + sl * SLICE, yb + sl * SLICE, acc0, acc1, gain, clamp_lo, clamp_hi,
+                                               sh_prev, y, a.scale_lo, a.scale_hi);
+      else
+        vmm6_contract_adc<PM, NK64, NT, true>(dg, xb + sl * SLICE, yb + sl * SLICE, acc0, acc1, gain, clamp_lo, clamp_hi,
+                                              sh_prev, y, a.scale_lo, a.scale_hi);
+      vmm6_contract_adc<PM, NK64, NT, true>(dg, xb + (sl + 1) * SLICE, yb + (sl + 1) * SLICE, acc1, acc0, gain, clamp_lo,
+                                            clamp_hi, sh0, y, a.scale_lo, a.scale_hi);
+      sh_prev = sh1;
+    }
+  }
+  vmm_adc_narrow<PM>(acc1, gain, clamp_lo, clamp_hi, sh_prev, y);   // drain
+}
+
+// General slice group (64-bit sums, code tap, transfer curve, statistics, odd slice counts).
+template <int PM, int NK64, int NT, bool WIDE, bool CODES, bool PER_ARRAY>
+__device__ __forceinline__ void vmm6_tile_group(const VmmArgs& a, const char* lds, const u32x2 (&raw)[PM][4 * NK64], int ns,
+                                                int sg0, int p, int pol, int t, int lane, int mp0, int op,
+                                                uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
+  constexpr int SLICE = NT * f6_term_stride(NK64);
+  const uint32_t low_mask = ((1u << a.stream_bits) - 1u) * 0x01010101u;
+  float gain_p, clamp_lo, clamp_hi;
+  adc_sign_and_range<PER_ARRAY>(a, p, pol, gain_p, clamp_lo, clamp_hi);
+  const float gain = 2.0f * gain_p;
+  const char* xb = lds + lane * 16;
+  const char* yb = lds + 1024 + lane * 8;
+  for (int b = 0; b < a.S_in; ++b) {
+    const int in_shift = a.stream_bits * b;
+    int4v dg[PM][NK64];
+#pragma unroll
+    for (int pm = 0; pm < PM; ++pm) digit_codes_f4<NK64>(raw[pm], in_shift, low_mask, dg[pm]);
+    for (int sl = 0; sl < ns; ++sl) {
+      const int s = sg0 + sl;
+      const int sh = a.slice_bits * s + in_shift;
+      float16v acc[PM], none[PM];
+      uint32_t unused[PM][16];
+      vmm6_contract_adc<PM, NK64, NT, false>(dg, xb + sl * SLICE, yb + sl * SLICE, acc, none, 0.f, 0.f, 0.f, 0, unused,
+                                             a.scale_lo, a.scale_hi);
+      vmm_adc_general<PM, WIDE, CODES, PER_ARRAY>(a, acc, gain, clamp_lo, clamp_hi, sh, p, pol, b, s, t, lane, mp0, op, y, y64);
+    }
+  }
+}
+
+// One virtual tile on the 6-bit path: NK64 k-steps of 64 rows (nk16 staged input steps of 16).
+template <int PM, int NK64, int NT, int WIDE, bool CODES, bool PER_ARRAY>
+__device__ __forceinline__ void vmm6_tile(const VmmArgs& a, u32x4* lds, int p, int pol, int t, int nk16, int lane, int mp0,
+                                          int op, uint32_t (&y)[PM][16], long long (&y64)[PM][16], int only_sg0) {
+  u32x2 raw[PM][4 * NK64];
+#pragma unroll
+  for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+    for (int j = 0; j < 4 * NK64; ++j) {
+      u32x2 v = {0, 0};
+      if (mp0 + pm < a.MP && j < nk16) v = a.A[((((size_t)p * a.MP + mp0 + pm) * a.T + t) * a.ks16 + j) * 64 + lane];
+      raw[pm][j] = v;
+    }
+  constexpr int STRIDE = f6_term_stride(NK64);
+  constexpr int UNITS = STRIDE / 1024;               // KiB copies per (slice, term)
+  const int sg = WIDE == 2 ? a.split_sg : a.sg;
+  const int sg_first = WIDE == 2 ? only_sg0 : 0, sg_end = WIDE == 2 ? only_sg0 + sg : a.S_w;
+  for (int sg0 = sg_first; sg0 < sg_end; sg0 += sg) {
+    const int ns = min(sg, a.S_w - sg0);
+    // global [slice][term][k-steps of the whole tile][1.5 KiB] -> LDS [slice][term][STRIDE]: only the NK64 used steps
+    const u32x4* src = a.B + (((size_t)t * a.OP + op) * a.S_w + sg0) * NT * a.ks * 96;
+    if constexpr (PER_ARRAY) src += (size_t)pol * a.pol_stride;
+    __syncthreads();                                   // everyone is done with the previous group
+    const int nwv = blockDim.x >> 6, ncopy = ns * NT * UNITS;
+    for (int c = threadIdx.x >> 6; c < ncopy; c += nwv) {
+      const int st = c / UNITS, u = c - st * UNITS;    // (slice, term) pair, KiB within it
+      copy16_global_to_lds(src + (size_t)st * a.ks * 96 + u * 64 + lane, lds + (st * UNITS + u) * 64);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    const char* stage = reinterpret_cast<const char*>(lds);
+    if constexpr (WIDE == 2) {
+      vmm6_tile_group_pipelined<PM, NK64, NT, PER_ARRAY>(a, stage, raw, ns, 0, p, pol, lane, y);
+    } else {
+      if (!WIDE && !CODES && (ns & 1) == 0)
+        vmm6_tile_group_pipelined<PM, NK64, NT, PER_ARRAY>(a, stage, raw, ns, sg0, p, pol, lane, y);
+      else
+        vmm6_tile_group<PM, NK64, NT, WIDE == 1, CODES, PER_ARRAY>(a, stage, raw, ns, sg0, p, pol, t, lane, mp0, op, y, y64);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// block-level driver shared by both operand formats: virtual tiles of the chunk, partial results
+// ---------------------------------------------------------------------------------------------
+// Tile functors: run one virtual tile (phase p, array pol, contraction tile t with `rows` rows).
 template <int PM, int KSMAX, int TERMS, int WIDE, bool CODES, bool PER_ARRAY>
-__global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
-  extern __shared__ u32x4 lds[];
+struct TileF16 {
+  __device__ __forceinline__ void operator()(const VmmArgs& a, u32x4* lds, int p, int pol, int t, int rows, int lane, int mp0,
+                                             int op, uint32_t (&y)[PM][16], long long (&y64)[PM][16], int only_sg0) const {
+    const int nk = (rows + 15) >> 4;
+#define XBAR_NK_CASE(n) \
+  case n:               \
+    if constexpr (n <= KSMAX)                                                                                       \
+      vmm_tile<PM, KSMAX, n, TERMS, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, lane, mp0, op, y, y64, only_sg0); \
+    break;
+    switch (nk) {
+      XBAR_NK_CASE(1) XBAR_NK_CASE(2) XBAR_NK_CASE(3) XBAR_NK_CASE(4) XBAR_NK_CASE(5) XBAR_NK_CASE(6)
+      XBAR_NK_CASE(7) XBAR_NK_CASE(8) XBAR_NK_CASE(9) XBAR_NK_CASE(10) XBAR_NK_CASE(11) XBAR_NK_CASE(12)
+      XBAR_NK_CASE(13) XBAR_NK_CASE(14) XBAR_NK_CASE(15) XBAR_NK_CASE(16)
+      default: break;
+    }
+#undef XBAR_NK_CASE
+  }
+};
+
+template <int PM, int NT, int WIDE, bool CODES, bool PER_ARRAY>
+struct TileF6 {
+  __device__ __forceinline__ void operator()(const VmmArgs& a, u32x4* lds, int p, int pol, int t, int rows, int lane, int mp0,
+                                             int op, uint32_t (&y)[PM][16], long long (&y64)[PM][16], int only_sg0) const {
+    const int nk16 = (rows + 15) >> 4;
+    switch ((rows + 63) >> 6) {
+      case 1: vmm6_tile<PM, 1, NT, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, nk16, lane, mp0, op, y, y64, only_sg0); break;
+      case 2: vmm6_tile<PM, 2, NT, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, nk16, lane, mp0, op, y, y64, only_sg0); break;
+      case 3: vmm6_tile<PM, 3, NT, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, nk16, lane, mp0, op, y, y64, only_sg0); break;
+      case 4: vmm6_tile<PM, 4, NT, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, nk16, lane, mp0, op, y, y64, only_sg0); break;
+      default: break;
+    }
+  }
+};
+
+template <int PM, int WIDE, bool CODES, bool PER_ARRAY, class TileFn>
+__device__ __forceinline__ void vmm_block(const VmmArgs& a, u32x4* lds, const TileFn& run_tile) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   // consecutive block ids go to different XCDs; give each XCD a contiguous range of logical work so
   // that blocks sharing the same planes share one L2
@@ -679,24 +1034,13 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
   const int vt_base = a.VT / a.nchunk, vt_rem = a.VT - vt_base * a.nchunk;
   const int vt0 = chunk * vt_base + min(chunk, vt_rem);
   const int vt1 = vt0 + vt_base + (chunk < vt_rem ? 1 : 0);
-#define XBAR_NK_CASE(n) \
-  case n:               \
-    if constexpr (n <= KSMAX)                                                                                       \
-      vmm_tile<PM, KSMAX, n, TERMS, WIDE, CODES, PER_ARRAY>(a, lds, p, pol, t, lane, mp0, op, y, y64, only_sg0); \
-    break;
 #define XBAR_ALL_VIRTUAL_TILES                                                                              \
   for (int vt = vt0; vt < vt1; ++vt) {                                                                      \
     /* vt = (phase, array, tile), tile fastest */                                                           \
     const int pa = vt / a.T, t = vt - pa * a.T;                                                             \
     const int p = PER_ARRAY ? pa >> 1 : pa, pol = PER_ARRAY ? pa & 1 : 0;                                   \
     const int rows = min(a.tile, a.Lin - t * a.tile);                                                       \
-    const int nk = (rows + 15) >> 4;                                                                        \
-    switch (nk) {                                                                                           \
-      XBAR_NK_CASE(1) XBAR_NK_CASE(2) XBAR_NK_CASE(3) XBAR_NK_CASE(4) XBAR_NK_CASE(5) XBAR_NK_CASE(6)       \
-      XBAR_NK_CASE(7) XBAR_NK_CASE(8) XBAR_NK_CASE(9) XBAR_NK_CASE(10) XBAR_NK_CASE(11) XBAR_NK_CASE(12)    \
-      XBAR_NK_CASE(13) XBAR_NK_CASE(14) XBAR_NK_CASE(15) XBAR_NK_CASE(16)                                   \
-      default: break;                                                                                       \
-    }                                                                                                       \
+    run_tile(a, lds, p, pol, t, rows, lane, mp0, op, y, y64, only_sg0);                                     \
   }
   if constexpr (WIDE == 2) {
     // Sums that overflow 32 bits, fast path: one pass over the chunk's virtual tiles per slice group,
@@ -731,7 +1075,6 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
     XBAR_ALL_VIRTUAL_TILES
   }
 #undef XBAR_ALL_VIRTUAL_TILES
-#undef XBAR_NK_CASE
   if constexpr (CODES) {
     if (a.hist) {                                  // statistics pass: the counters are the only result
       __syncthreads();
@@ -760,6 +1103,18 @@ __global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
         }
       }
     }
+}
+
+template <int PM, int KSMAX, int TERMS, int WIDE, bool CODES, bool PER_ARRAY>
+__global__ __launch_bounds__(256, 2) void vmm_kernel(VmmArgs a) {
+  extern __shared__ u32x4 lds[];
+  vmm_block<PM, WIDE, CODES, PER_ARRAY>(a, lds, TileF16<PM, KSMAX, TERMS, WIDE, CODES, PER_ARRAY>());
+}
+
+template <int NT, int WIDE, bool CODES, bool PER_ARRAY>
+__global__ __launch_bounds__(256, 2) void vmm6_kernel(VmmArgs a) {
+  extern __shared__ u32x4 lds[];
+  vmm_block<2, WIDE, CODES, PER_ARRAY>(a, lds, TileF6<2, NT, WIDE, CODES, PER_ARRAY>());
 }
 
 struct FinishArgs {
@@ -1041,8 +1396,6 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(float* out, int iters, 
 }
 
 // Same loop with the 8-bit integer instruction (32 x 32 x 32 per instruction, twice the products).
-typedef int int4v __attribute__((ext_vector_type(4)));
-typedef int int16v __attribute__((ext_vector_type(16)));
 __global__ __launch_bounds__(256) void mfma_probe_i8_kernel(int* out, int iters, int mode) {
   uint32_t x = threadIdx.x * 2654435761u + 12345u;
   int4v a, b;
@@ -1079,6 +1432,8 @@ __global__ void step_advance_kernel(unsigned long long* counter) { *counter += 1
 
 struct VmmPlan {
   PlaneGeom g;
+  int ks16;            // k-steps of 16 rows per tile in the staged input
+  int sg;              // kFmtF6: slices per staged group
   int Lin, Lout, MP, P, VT, vt_per_chunk, nchunk, pm, nw, MB, lds_kb;
   int wide;            // 0: sums fit 32 bits; 1: 64-bit sums; 2: 32-bit sums per slice group, widened per group
   int split_sg;        // slices per group of mode 2
@@ -1106,8 +1461,18 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   const unsigned long long per_vt = wsum * (unsigned long long)d.q_adc;
   const unsigned long long fit = per_vt ? ((1ull << 31) - 1) / per_vt : (1ull << 31);
   p.wide = fit < 1 ? 1 : 0;
-  const int slice_kb = d.terms * p.g.ks;                   // KiB of operand per slice and output patch
-  p.lds_kb = std::max(slice_kb, std::min(d.S_w * slice_kb, 64));   // staged slice group, at most 64 KiB
+  p.ks16 = p.g.tile / 16;
+  // KiB of operand per slice and output patch in the LDS stage
+  const int slice_kb = d.fmt == kFmtF6 ? d.terms * f6_term_stride(p.g.ks) / 1024 : d.terms * p.g.ks;
+  p.sg = d.S_w;
+  if (d.fmt == kFmtF6) {
+    // as many slices per stage as fit 64 KiB; an even number when not all fit (the pipelined path pairs them)
+    const int fit_sg = std::max(1, 64 / slice_kb);
+    if (fit_sg < d.S_w) p.sg = fit_sg >= 2 ? (fit_sg & ~1) : 1;
+    p.lds_kb = p.sg * slice_kb;
+  } else {
+    p.lds_kb = std::max(slice_kb, std::min(d.S_w * slice_kb, 64));   // staged slice group, at most 64 KiB
+  }
   p.lds_bytes = (size_t)p.lds_kb * 1024;
   // 64-bit sums: the software-pipelined path still serves if the slices split into equal, even
   // groups that fit the LDS stage and whose own sum fits 32 bits
@@ -1129,7 +1494,7 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
       break;
     }
   }
-  p.pm = p.g.ks > 8 ? 1 : 2;
+  p.pm = (d.fmt == kFmtF6 || p.g.ks <= 8) ? 2 : 1;
   p.nw = std::min(4, std::max(1, cdiv(p.MP, p.pm)));
   p.MB = cdiv(p.MP, p.pm * p.nw);
   const int groups = p.g.OP * p.MB;
@@ -1140,7 +1505,7 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   if (p.wide == 2) per = (int)std::min<unsigned long long>((unsigned long long)per, fit_split);
   p.nchunk = cdiv(p.VT, per);
   p.vt_per_chunk = cdiv(p.VT, p.nchunk);                  // same number of chunks, evenly filled
-  p.a_bytes = align256((size_t)p.P * p.MP * p.g.T * p.g.ks * 512);
+  p.a_bytes = align256((size_t)p.P * p.MP * p.g.T * p.ks16 * 512);
   p.part_bytes = align256((size_t)p.nchunk * M * p.Lout * (p.wide ? 8 : 4));
   p.ws_bytes = p.a_bytes + p.part_bytes;
   return p;
@@ -1181,6 +1546,32 @@ hipError_t launch_vmm_variant(const VmmArgs& a, const VmmPlan& p, bool codes, hi
   return hipGetLastError();
 }
 
+template <int NT, bool PER_ARRAY>
+hipError_t launch_vmm6_variant(const VmmArgs& a, const VmmPlan& p, bool codes, hipStream_t st) {
+  const dim3 grid((unsigned)(a.per_xcd * 8)), block((unsigned)(p.nw * 64));
+  void (*k)(VmmArgs);
+  if (p.wide == 2 && !codes) k = vmm6_kernel<NT, 2, false, PER_ARRAY>;
+  else if (p.wide) k = codes ? vmm6_kernel<NT, 1, true, PER_ARRAY> : vmm6_kernel<NT, 1, false, PER_ARRAY>;
+  else k = codes ? vmm6_kernel<NT, 0, true, PER_ARRAY> : vmm6_kernel<NT, 0, false, PER_ARRAY>;
+  if (p.lds_bytes > 48 * 1024) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)p.lds_bytes);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(k, grid, block, p.lds_bytes, st, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_vmm6(const VmmArgs& a, const VmmPlan& p, int terms, bool codes, hipStream_t st) {
+  if (a.npol == 2) return launch_vmm6_variant<5, true>(a, p, codes, st);   // single arrays: always the full schedule
+  switch (terms) {
+    case 1: return launch_vmm6_variant<1, false>(a, p, codes, st);
+    case 4: return launch_vmm6_variant<4, false>(a, p, codes, st);
+    case 5: return launch_vmm6_variant<5, false>(a, p, codes, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 hipError_t launch_vmm(const VmmArgs& a, const VmmPlan& p, int terms, bool codes, hipStream_t st) {
   const int ks = p.g.ks;
   if (a.npol == 2)                                    // planes of single arrays always come in two terms
@@ -1218,11 +1609,11 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   QuantArgs qa;
   qa.X = in;
   qa.A = reinterpret_cast<uint8_t*>(ws);
-  qa.M = M; qa.L = p.Lin; qa.MP = p.MP; qa.T = p.g.T; qa.ks = p.g.ks; qa.tile = p.g.tile; qa.P = p.P;
+  qa.M = M; qa.L = p.Lin; qa.MP = p.MP; qa.T = p.g.T; qa.ks = p.ks16; qa.tile = p.g.tile; qa.P = p.P;
   qa.input_bits = cfg->input_bits;
   qa.offset = p.offset;
   qa.scale = in_scale;
-  qa.n_threads = (long long)p.MP * p.g.T * ((p.g.ks + 1) / 2) * 64;
+  qa.n_threads = (long long)p.MP * p.g.T * ((p.ks16 + 1) / 2) * 64;
   if (conv) {
     qa.conv = *conv;
     hipLaunchKernelGGL(quantize_input_kernel<true>, dim3((unsigned)((qa.n_threads + 255) / 256)), dim3(256), 0, st, qa);
@@ -1249,6 +1640,13 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   a.npol = d.npol; a.pol_stride = p.g.pol_bytes / 16;
   a.VT = p.VT; a.S_w = d.S_w; a.S_in = d.S_in; a.slice_bits = cfg->slice_bits; a.stream_bits = cfg->stream_bits;
   a.ks = p.g.ks; a.tile = p.g.tile; a.vt_per_chunk = p.vt_per_chunk; a.nchunk = p.nchunk; a.lds_kb = p.lds_kb;
+  a.ks16 = p.ks16; a.sg = p.sg;
+  a.scale_lo = a.scale_hi = 0;
+  for (int j = 0; j < kMaxTermsF6; ++j) {
+    const int byte = 127 + d.term_exp[j];
+    if (j < 4) a.scale_lo |= byte << (8 * j);
+    else a.scale_hi |= byte;
+  }
   const bool general = codes != nullptr || hist != nullptr || level_table || a.adc_curve_on;
   const bool split = p.wide == 2 && !general;          // adds its groups up in the partial-sum buffer
   a.split_sg = p.split_sg;
@@ -1269,7 +1667,8 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   hipEvent_t ev0 = g_trace_before, ev1 = g_trace_after;
   g_trace_before = g_trace_after = nullptr;
   if (ev0 && hipEventRecord(ev0, st) != hipSuccess) return XBAR_EHIP;
-  if (launch_vmm(a, p, d.terms, general, st) != hipSuccess) return XBAR_EHIP;
+  if ((d.fmt == kFmtF6 ? launch_vmm6(a, p, d.terms, general, st) : launch_vmm(a, p, d.terms, general, st)) != hipSuccess)
+    return XBAR_EHIP;
   if (ev1 && hipEventRecord(ev1, st) != hipSuccess) return XBAR_EHIP;
   if (hist) return XBAR_OK;
 
@@ -1524,8 +1923,18 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
     a.seed = cfg->seed;
     a.step = step;
     a.step_add = current_step_source();
+    for (int j = 0; j < kMaxTermsF6; ++j) a.term_exp[j] = d.term_exp[j];
     // every k-step that the contraction reads is written whole, padding included
     const int Lc = dir == 1 ? N : K;
+    if (d.fmt == kFmtF6) {
+      a.n_threads = (long long)g.T * g.ks * 8 * g.OP * 32;
+      const unsigned blocks = (unsigned)((a.n_threads + 255) / 256);
+      if (dir == 0) hipLaunchKernelGGL(tile_planes_f6_kernel<false>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
+      else hipLaunchKernelGGL(tile_planes_f6_kernel<true>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
+      if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+      if (pol == d.npol - 1) offset += align256(g.bytes);
+      continue;
+    }
     const long long chunks = (long long)cdiv(Lc, 16) * 2;
     a.n_threads = chunks * g.OP * 32;
     const unsigned blocks = (unsigned)((a.n_threads + 255) / 256);

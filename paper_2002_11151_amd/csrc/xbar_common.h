@@ -28,11 +28,48 @@ constexpr bool kBarrierPerMfma = false;   // scheduling fence after every MFMA (
 // ---------------------------------------------------------------------------------------------
 // host-side geometry shared by the entry points
 // ---------------------------------------------------------------------------------------------
+// Operand format of the plane buffer and of the contraction kernel.
+//   kFmtF16: fp16 fragments for v_mfma_f32_32x32x16_f16, one term (exact digits) or two (leading term on
+//            a fixed grid + fp16 residual); input digits as fp16 subnormals.  Serves every configuration.
+//   kFmtF6:  6-bit floating-point (E2M3) fragments for v_mfma_scale_f32_32x32x64_f8f6f4 with the input
+//            digits as 4-bit floating-point (E2M1) codes: a plane value is a sum of up to 5 terms, each
+//            an E2M3 number times a power of two that the instruction applies as a block scale, all
+//            accumulated in one fp32 sum, leading term first.  64 rows per instruction at the time of
+//            16 in fp16.  For cycles of 1 or 2 bits (digit d is the E2M1 code d, value d / 2) without
+//            a general DAC level table.
+constexpr int kFmtF16 = 0, kFmtF6 = 1;
+constexpr int kMaxTermsF6 = 5;
+
 struct Derived {
   int S_w, S_in, terms, q_adc;
   int npol;            // converters per crossbar column: 1 (pair read differentially) or 2 (one per array)
   uint32_t array_ni;
+  int fmt;             // kFmtF16 or kFmtF6
+  int term_exp[kMaxTermsF6];   // kFmtF6: term j of a plane value is (E2M3 number) x 2^term_exp[j]
 };
+
+// kFmtF6 term schedule.  Term 0 is the E2M3 number nearest to U / 2^x0 (|U| up to 7.5 x 2^x0: more than
+// twice the top device level); every later term holds the E2M3 number nearest to what is left, on a
+// grid 32 times finer than the one before (the uniform part of the format is 33 levels wide).  What is
+// left after term 0 is at most a quarter of 2^x0, or `bound` when the plane values are known to stay
+// that close to whole levels (single-path wire model alone); terms are added until the grid reaches
+// 2^-18 of a device level: 4 or 5 terms (1 for ideal arrays).  Returns the number of terms.
+static inline int f6_schedule(int slice_bits, bool ideal, double bound, int* term_exp) {
+  const int x0 = slice_bits - 2;
+  term_exp[0] = x0;
+  for (int j = 1; j < kMaxTermsF6; ++j) term_exp[j] = x0;
+  if (ideal) return 1;
+  double left = std::ldexp(1.0, x0 - 2);
+  if (bound > 0.0 && bound < left) left = bound;
+  int g = (int)std::ceil(std::log2(left / 16.0));       // log2 of the grid of term 1
+  int n = 1;
+  while (n < kMaxTermsF6) {
+    term_exp[n++] = g + 3;                                // an E2M3 number is a multiple of 1/8
+    if (g <= -18 && n >= 4) break;
+    g -= 5;
+  }
+  return n;
+}
 
 static inline Derived derive(const xbar_config* c) {
   Derived d;
@@ -44,6 +81,21 @@ static inline Derived derive(const xbar_config* c) {
   d.terms = (d.array_ni || d.npol == 2) ? 2 : 1;
   // signed converter on the difference of the pair, or unsigned converter on one array's current
   d.q_adc = d.npol == 2 ? (1 << c->adc_bits) - 1 : (1 << (c->adc_bits - 1)) - 1;
+  const bool level_table = (c->flags & XBAR_DAC_LUT) && !(c->stream_bits == 1 && c->dac_lut[0] == 0.0f);
+  d.fmt = (c->stream_bits <= 2 && !level_table) ? kFmtF6 : kFmtF16;
+  for (int j = 0; j < kMaxTermsF6; ++j) d.term_exp[j] = 0;
+  if (d.fmt == kFmtF6) {
+    // single-path wire model alone: |U - digit| <= rho_max (Gmax^2 + Gmin^2) / (one device level)
+    double bound = 0.0;
+    if (d.npol == 1 && d.array_ni == XBAR_NI_WIRE_AAM) {
+      const double g_min = 1.0 / (double)c->r_max, g_max = 1.0 / (double)c->r_min;
+      const double dg = (g_max - g_min) / (double)((1 << c->slice_bits) - 1);
+      const double rho = (double)c->r_source + (double)c->xbar_cols * (double)c->r_row +
+                         (double)c->xbar_rows * (double)c->r_col + (double)c->r_sense;
+      bound = rho * (g_max * g_max + g_min * g_min) / dg;
+    }
+    d.terms = f6_schedule(c->slice_bits, d.terms == 1, bound, d.term_exp);
+  }
   return d;
 }
 
@@ -51,12 +103,20 @@ static inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 // Plane buffer: forward copy then backward copy.  One copy is
-// [array][tile][output patch of 32][slice][term][k-step of 16][64 lanes][8 halves]; there is one
-// "array" (the difference of the pair) unless every array has a converter of its own.
+// [array][tile][output patch of 32][slice][term][k-step][fragment]; there is one "array" (the difference
+// of the pair) unless every array has a converter of its own.  kFmtF16: k-steps of 16 rows, a fragment is
+// 64 lanes x 8 halves (1 KiB).  kFmtF6: k-steps of 64 rows, a fragment is 64 lanes x 16 bytes followed by
+// 64 lanes x 8 bytes (1.5 KiB): the 24 bytes of a lane hold its 32 six-bit codes, code e at bit 6 e.
+// Lane l = (output column l % 32, half l / 32); code e of that lane is contraction row
+//   64 J + 16 (e / 8) + 8 (l / 32) + (e % 8) / 2 + 4 (e % 2)
+// of k-step J, which is where the input stage's bytes land when they are packed into 4-bit digits.
 struct PlaneGeom {
   int tile, ks, T, OP;          // contraction tile length, k-steps per tile, tiles, output patches
+  int frag_bytes;               // bytes of one fragment
   size_t pol_bytes, bytes;      // one array, all arrays
 };
+
+constexpr size_t kPlanePad = 1024;   // behind each copy: staging copies whole KiB and may read past the last fragment
 
 // Scratch of the all-paths wire model, kept behind the two plane copies.
 static inline size_t wire_scratch_bytes(const xbar_config* c, const Derived& d, int K, int N) {
@@ -72,11 +132,12 @@ static inline size_t weight_sums_bytes(const xbar_config* c, int K, int N) {
 static inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N, bool transposed) {
   PlaneGeom g;
   g.tile = transposed ? c->xbar_cols : c->xbar_rows;
-  g.ks = g.tile / 16;
+  g.ks = d.fmt == kFmtF6 ? cdiv(g.tile, 64) : g.tile / 16;
+  g.frag_bytes = d.fmt == kFmtF6 ? 1536 : 1024;
   g.T = cdiv(transposed ? N : K, g.tile);
   g.OP = cdiv(transposed ? K : N, 32);
-  g.pol_bytes = (size_t)g.T * g.OP * d.S_w * d.terms * g.ks * 1024;
-  g.bytes = g.pol_bytes * d.npol;
+  g.pol_bytes = (size_t)g.T * g.OP * d.S_w * d.terms * g.ks * g.frag_bytes;
+  g.bytes = g.pol_bytes * d.npol + (d.fmt == kFmtF6 ? kPlanePad : 0);
   return g;
 }
 

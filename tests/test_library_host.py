@@ -65,20 +65,33 @@ def test_validate_accepts(xb, kw):
 
 
 def test_size_queries(xb):
-    c = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=xb.NI_WIRE_AAM)
-    ideal = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2)
-    # forward copy: ceil(K/128) tiles x ceil(N/32) patches x 8 slices x 2 terms x 8 KiB, same for backward
+    pad256 = lambda b: -(-b // 256) * 256
     K, N = 147, 64
+    # cycles of 4 bits: fp16 planes.  Forward copy: ceil(K/128) tiles x ceil(N/32) patches x 8 slices x 2 terms
+    # x 8 KiB, same for backward
+    base = dict(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, stream_bits=4)
+    c16 = xb.make_config(flags=xb.NI_WIRE_AAM, **base)
     fwd = 2 * 2 * 8 * 2 * 8 * 1024
     bwd = 1 * 5 * 8 * 2 * 8 * 1024
-    assert xb.planes_bytes(c, K, N) == fwd + bwd
-    assert xb.planes_bytes(ideal, K, N) == (fwd + bwd) // 2
-    all_paths = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=xb.NI_WIRE_AAM2)
-    assert xb.planes_bytes(all_paths, K, N) == fwd + bwd + 16 * 8 * K * N + 4 * K * N      # scratch behind the planes
-    # a converter per array: the two arrays' planes apart, in two terms even when the arrays are ideal
-    for flags in (xb.ADC_PER_ARRAY, xb.ADC_PER_ARRAY | xb.NI_WIRE_AAM):
-        apart = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=flags)
-        assert xb.planes_bytes(apart, K, N) == 2 * (fwd + bwd)
+    assert xb.planes_bytes(c16, K, N) == fwd + bwd
+    assert xb.planes_bytes(xb.make_config(**base), K, N) == (fwd + bwd) // 2
+    for flags in (xb.ADC_PER_ARRAY, xb.ADC_PER_ARRAY | xb.NI_WIRE_AAM):      # arrays apart: two terms even when ideal
+        assert xb.planes_bytes(xb.make_config(flags=flags, **base), K, N) == 2 * (fwd + bwd)
+    # cycles of 1 or 2 bits: 6-bit planes, 1.5 KiB per 64 rows x 32 columns and term, + 1 KiB behind each copy.
+    # Single-path wire model alone: 4 terms; with variation (or arrays apart): 5; ideal arrays: 1
+    base = dict(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2)
+    c = xb.make_config(flags=xb.NI_WIRE_AAM, **base)
+    frag = lambda terms, arrays=1: ((2 * 2 + 1 * 5) * 8 * terms * 2 * 1536) * arrays + pad256(1024) * 2
+    assert xb.planes_bytes(c, K, N) == frag(4)
+    assert xb.planes_bytes(xb.make_config(flags=xb.NI_WIRE_AAM | xb.NI_VARIATION, **base), K, N) == frag(5)
+    assert xb.planes_bytes(xb.make_config(**base), K, N) == frag(1)
+    assert xb.planes_bytes(xb.make_config(flags=xb.ADC_PER_ARRAY, **base), K, N) == frag(5, 2)
+    # a general DAC level table runs on the fp16 path
+    lut = xb.make_config(flags=xb.NI_WIRE_AAM | xb.DAC_LUT, stream_bits=2, dac_lut=[0.0, 0.3, 0.7, 1.0], **base)
+    assert xb.planes_bytes(lut, K, N) == fwd + bwd
+    all_paths = xb.make_config(flags=xb.NI_WIRE_AAM2, **base)
+    assert xb.planes_bytes(all_paths, K, N) == frag(5) + 16 * 8 * K * N + 4 * K * N      # scratch behind the planes
+    fwd, bwd = frag(4) // 2, frag(4) // 2
     # offset-binary inputs: the 64-bit sums of the programmed weights per column and per row ride along
     coded = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=xb.NI_WIRE_AAM | xb.INPUT_OFFSET)
     assert xb.planes_bytes(coded, K, N) == fwd + bwd + -(-8 * (K + N) // 256) * 256
