@@ -18,10 +18,27 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
-# HBM bytes per vmm_kernel launch (average over the 108 launches of a step) of the default workload, from
-# the FETCH_SIZE / WRITE_SIZE counter runs recorded in profiles/vmm_kernel_resnet50_batch64.txt
-VMM_TRAFFIC_BYTES_RESNET50_B64 = 553778 * 1024
+# MI355X dense matrix peaks of the two operand formats the contraction kernel uses (xbar_plane_format):
+# fp16 planes, or 6-bit planes with 4-bit digits on the block-scaled instruction
+MFMA_PEAK_TFLOPS = {0: 2500.0, 1: 10100.0}
+FORMAT_NAME = {0: "f16 planes x f16 digits, f32 accumulate",
+               1: "f6 (E2M3, block-scaled) planes x f4 (E2M1) digits, f32 accumulate"}
+KERNEL_NAME = {0: "vmm_kernel (fp16 MFMA contraction + ADC + shift-and-add, fwd and bwd launches)",
+               1: "vmm6_kernel (block-scaled 6-bit x 4-bit MFMA contraction + ADC + shift-and-add, fwd and bwd launches)"}
+# HBM bytes per contraction-kernel launch (average over the 108 launches of a step) of the default workload:
+# recorded from the FETCH_SIZE / WRITE_SIZE counter runs in the profile named here, not measured in this run
+VMM_TRAFFIC_BYTES_RESNET50_B64 = None
+VMM_TRAFFIC_SOURCE = "profiles/vmm6_kernel_resnet50_batch64.txt"
+
+
+def contraction_roofline(achieved, fmt, terms):
+    """Roofline entry of the contraction kernel: useful flops (2 per emulated MAC) against the matrix peak of
+    the operand type it runs on; a plane value split into `terms` operand terms issues `terms` times that."""
+    peak = MFMA_PEAK_TFLOPS[fmt]
+    return {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+            "frac": round(achieved / peak, 4), "traffic": None, "kernel": KERNEL_NAME[fmt],
+            "operand_terms": terms, "issued_frac": round(terms * achieved / peak, 4),
+            "frac_of_fp16_peak": round(achieved / MFMA_PEAK_TFLOPS[0], 4)}
 
 
 class HipEvents:
@@ -121,12 +138,15 @@ def end_to_end(args, torch, workloads, xb, device):
     vmm_ms = sum(events.elapsed_ms(a, b) for a, b in records)
     emulated = tot["fwd"] + tot["bwd"] + tot["upd"]
     achieved = 2.0 * (tot["fwd"] + tot["bwd"]) * args.steps / (vmm_ms * 1e-3) / 1e12
-    terms = 2
+    fmt, terms = xb.plane_format(xb.make_config(**kw))
+    roofline = contraction_roofline(achieved, fmt, terms)
+    roofline.update({"launches": len(records), "avg_launch_ms": round(vmm_ms / max(1, len(records)), 4),
+                     "kernel_time_share": round(vmm_ms / (elapsed * 1e3), 4)})
     line = {
         "metric": "emulated crossbar GMAC/s (fwd+bwd+update)", "value": round(emulated / (elapsed / args.steps) / 1e9, 1),
         "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(elapsed / args.steps * 1e3, 3), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f16 operands, f32 accumulate", "data": "synthetic",
+        "vs_baseline": None, "dtype": FORMAT_NAME[fmt], "data": "synthetic",
         "config": {"workload": "%s whole training step from %dx%dx%d images, batch %d, %dx%d crossbars, %d-bit "
                                "weights in %d slices, %d-bit inputs in %d cycles, %d-bit ADC, wire parasitics (AAM) + "
                                "write non-linearity + noise, digital batch norm / ReLU / pooling / loss" %
@@ -135,12 +155,7 @@ def end_to_end(args, torch, workloads, xb, device):
                    "emulated_macs_per_step": emulated, "logical_macs_per_step": tot["logical"]},
         "final_loss": round(float(loss.mean()), 4),
         "ms_per_step_from_hip_graph": None if graph_ms is None else round(graph_ms, 3),
-        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / FP16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
-                     "kernel": "vmm_kernel (MFMA contraction + ADC + shift-and-add, fwd and bwd launches)",
-                     "operand_terms": terms, "launches": len(records),
-                     "avg_launch_ms": round(vmm_ms / max(1, len(records)), 4),
-                     "kernel_time_share": round(vmm_ms / (elapsed * 1e3), 4)},
+        "roofline": roofline,
         "cpu_baseline": None,
     }
     print(json.dumps(line))
@@ -244,8 +259,7 @@ def main():
         kw["flags"] |= workloads.ADC_PER_ARRAY
         arrays = 2
     S_w, S_in = kw["weight_bits"] // kw["slice_bits"], kw["input_bits"] // kw["stream_bits"]
-    terms = 2 if arrays == 2 or kw["flags"] & (workloads.NI_VARIATION | workloads.NI_WIRE_AAM | workloads.NI_WIRE_PROFILE |
-                                               workloads.NI_WIRE_AAM2) else 1
+    fmt, terms = xb.plane_format(xb.make_config(**kw))
 
     # ---- resident tensors, one set per distinct shape ------------------------------------------
     layers = []
@@ -384,28 +398,36 @@ def main():
         d[1] += fl
         d[2] += 1
     achieved = vmm_flops / (vmm_ms * 1e-3) / 1e12 if vmm_ms > 0 else 0.0
-    roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": FP16_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / FP16_MFMA_PEAK_TFLOPS, 4), "traffic": None,
-                "kernel": "vmm_kernel (MFMA contraction + ADC + shift-and-add, fwd and bwd launches)",
-                "operand_terms": terms, "issued_frac": round(terms * achieved / FP16_MFMA_PEAK_TFLOPS, 4),
-                "launches": len(vmm_records), "avg_launch_ms": round(vmm_ms / max(1, len(vmm_records)), 4),
-                "kernel_time_share": round(vmm_ms / (elapsed * 1e3), 4)}
-    # sustained rate of the bare matrix instruction (power limited), as context for the fraction above
+    roofline = contraction_roofline(achieved, fmt, terms)
+    roofline.update({"launches": len(vmm_records), "avg_launch_ms": round(vmm_ms / max(1, len(vmm_records)), 4),
+                     "kernel_time_share": round(vmm_ms / (elapsed * 1e3), 4)})
+    # Context for the fraction above, measured in this process: the rate the chip sustains on the bare matrix
+    # instructions (it is power limited once operands toggle), and the contraction kernel's own inner loop
+    # (4 terms, 128-row tiles) on synthetic operands without and with the ADC / shift-and-add operations:
+    # what the fused epilogue adds to the loop's time.
     if not args.no_mfma_probe:
         probe = {}
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for mode, key in ((0, "dense_random_operands"), (1, "emulation_like_operands")):
+        times = {}
+        for mode, key, iters in ((0, "fp16_dense_random_operands", 100000), (1, "fp16_single_bit_digits", 100000),
+                                 (4, "f6xf4_block_scaled_single_bit_digits", 100000),
+                                 (5, "contraction_loop_without_adc_issued", 50000),
+                                 (6, "contraction_loop_with_adc_issued", 50000)):
             xb.probe_mfma_rate(mode, 2000, ws)
             torch.cuda.synchronize()
             e0.record()
-            flops = xb.probe_mfma_rate(mode, 100000, ws)
+            flops = xb.probe_mfma_rate(mode, iters, ws)
             e1.record()
             torch.cuda.synchronize()
-            probe[key] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
-        roofline["sustained_mfma_tflops_bare_instruction"] = probe
+            times[mode] = e0.elapsed_time(e1)
+            probe[key] = round(flops / (times[mode] * 1e-3) / 1e12, 1)
+        roofline["sustained_mfma_tflops"] = probe
+        roofline["epilogue_added_frac"] = round(times[6] / times[5] - 1.0, 4)
     if (args.workload == "resnet50" and batch == 64 and not args.only and not args.ideal and not args.all_paths
-            and not args.adc_per_array and not args.offset_inputs and not args.from_images):
+            and not args.adc_per_array and not args.offset_inputs and not args.from_images and not args.xbar
+            and not args.adc_bits):
         roofline["traffic"] = VMM_TRAFFIC_BYTES_RESNET50_B64
+        roofline["traffic_source"] = "recorded counter run, " + VMM_TRAFFIC_SOURCE
     fcm_refresh_ms = None
     if args.fcm_refresh:
         # one circuit-level solve of every layer (Sec. IV-D: done every L iterations, its profile reused between)
@@ -470,7 +492,7 @@ def main():
     line = {
         "metric": "emulated crossbar GMAC/s (fwd+bwd+update)", "value": round(value, 1), "unit": "GMAC/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16 operands, f32 accumulate",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": FORMAT_NAME[fmt],
         "data": "synthetic",
         "config": {"workload": "%s layer GEMMs (%d GEMMs, %d distinct shapes), batch %d, %dx%d crossbars, "
                                "%d-bit weights in %d slices, %d-bit inputs in %d cycles, %d-bit ADC, %s" %

@@ -371,8 +371,24 @@ void xbar_trace_next_vmm(void* before, void* after);
  *   on 2048 waves, i.e. 2 * 16 * iters * 2048 * 16384 flops.   out: 2 MiB of device scratch.
  *   modes 2, 3: the same two operand patterns with the 8-bit integer instruction
  *   (v_mfma_i32_32x32x32_i8, twice the operations per instruction), for comparison.
+ *   mode 4: the block-scaled 6-bit x 4-bit instruction (v_mfma_scale_f32_32x32x64_f8f6f4, four times the
+ *   operations per instruction) on pseudo-random 6-bit codes and single-bit digits.
+ *   modes 5, 6: the inner loop of the contraction kernel itself on synthetic operands (its code, not a
+ *   copy): 4 terms, 128-row tiles, two row patches per wave, plane fragments read from LDS; mode 5 without
+ *   and mode 6 with the ADC / shift-and-add operations woven between the matrix instructions.  Each
+ *   iteration is two (slice, cycle) passes = 32 matrix instructions per wave; time(6) / time(5) - 1 is the
+ *   time the fused epilogue adds.  The kernel uses 48 KiB of LDS.
  */
 int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void* hip_stream);
+
+/*
+ * Operand format that the contraction uses for this configuration (information for the benchmark's
+ * accounting): returns 0 = fp16 planes (v_mfma_f32_32x32x16_f16) or 1 = 6-bit planes with 4-bit digits
+ * (v_mfma_scale_f32_32x32x64_f8f6f4; cycles of 1 or 2 bits without a general DAC level table), or a
+ * negative status for an invalid configuration; *terms (may be NULL) receives the number of operand terms
+ * a plane value is split into, i.e. matrix instructions issued per useful one.
+ */
+int xbar_plane_format(const xbar_config* cfg, int* terms);
 
 #ifdef __cplusplus
 }

@@ -7,7 +7,8 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = [os.path.join(HERE, "csrc", name) for name in ("xbar.hip", "wire.hip", "fcm.hip", "pulse.hip", "periph.hip")]
+SRC = [os.path.join(HERE, "csrc", name) for name in ("vmm_f16_a.hip", "vmm_f16_b.hip", "vmm_f6_a.hip", "vmm_f6_b.hip", "xbar.hip", "wire.hip",
+                                                     "fcm.hip", "pulse.hip", "periph.hip")]
 LIB = os.path.join(HERE, "libxbar.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -88,6 +88,7 @@ _SIGNATURES = {
                            C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "xbar_bwd": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                            C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "xbar_plane_format": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_int)]),
     "xbar_trace_next_vmm": (None, [C.c_void_p, C.c_void_p]),
     "xbar_set_step_source": (None, [C.c_void_p]),
     "xbar_step_advance": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -164,9 +165,20 @@ def trace_next_vmm(before, after):
 
 
 def probe_mfma_rate(mode, iters, scratch):
-    """xbar_probe_mfma_rate: enqueue the pure-MFMA probe; returns the flops it performs."""
+    """xbar_probe_mfma_rate: enqueue the matrix-instruction probe; returns the flops (multiply + add of every
+    product of every instruction) that it issues on its 2048 waves."""
     _check(lib().xbar_probe_mfma_rate(mode, iters, C.c_void_p(scratch.data_ptr()), scratch.numel(), _stream()))
-    return 2.0 * 16 * iters * 2048 * 16384 * (2 if mode >= 2 else 1)
+    per_instruction = {0: 16384, 1: 16384, 2: 32768, 3: 32768}.get(mode, 65536)      # 32 x 32 x (16 | 32 | 64)
+    per_iteration = 32 if mode >= 5 else 16
+    return 2.0 * per_iteration * iters * 2048 * per_instruction
+
+
+def plane_format(cfg):
+    """xbar_plane_format: (0 = fp16 planes | 1 = 6-bit planes with 4-bit digits, operand terms per plane value)."""
+    terms = C.c_int(0)
+    fmt = lib().xbar_plane_format(C.byref(cfg), C.byref(terms))
+    _check(min(fmt, 0))
+    return fmt, terms.value
 
 
 def validate(cfg):

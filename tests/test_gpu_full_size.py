@@ -104,15 +104,25 @@ def test_converter_and_streaming_variants_full_size_sampled(xo, xb, variant):
     col, row = xo.weight_sums(co, Wh, w_max)
     Yo = xo.rows_parallel(lambda u, x: xo.fwd_planes(co, u, x, w_max, xs, wsum=col), U, X[rt].cpu().numpy(), 8)
     dXo = xo.rows_parallel(lambda u, x: xo.bwd_planes(co, u, x, w_max, gs, wsum=row), U, dY[rt].cpu().numpy(), 8)
-    # the forward input of this layer is unsigned (two-phase / offset coding only concern the backward pass);
-    # with offset coding one differing code weighs more in the result (see test_gpu_parity), hence 1e-2 there
+    # the forward input of this layer is unsigned (two-phase / offset coding only concern the backward pass)
     assert rel_l2(Y[rt].cpu().numpy(), Yo) <= 1e-3
-    assert rel_l2(dX[rt].cpu().numpy(), dXo) <= (1e-2 if "offset" in variant else 1e-3)
     q_adc = (1 << kw["adc_bits"]) - 1 if "per_array" in variant else (1 << (kw["adc_bits"] - 1)) - 1
     top_shift = kw["weight_bits"] - kw["slice_bits"] + kw["input_bits"] - kw["stream_bits"]
     lsb_b = kw["adc_fs_bwd"] / q_adc * gs * w_max / (255.0 * ((1 << kw["weight_bits"]) - 1)) * 2 ** top_shift
     lsb_b *= 2.0 if "offset" in variant else 1.0
-    assert np.abs(dX[rt].cpu().numpy() - dXo).max() <= 1.01 * lsb_b
+    got = dX[rt].cpu().numpy()
+    assert np.abs(got - dXo).max() <= 1.01 * lsb_b          # no element is off by more than one top-slice code
+    if "offset" in variant:
+        # Offset coding: the output is an exact linear function of the codes, so it can differ from the oracle's
+        # only by the weights of differing codes.  Under the code bar (at most 1e-4 of the conversions, one LSB
+        # each) at most 1e-4 x (conversions per output) of the outputs are touched, each by at most one
+        # top-slice code: that is the L2 bound asserted here (no codes are reported at this size).
+        conversions = -(-g.N // kw["xbar_cols"]) * (kw["weight_bits"] // kw["slice_bits"]) * (kw["input_bits"] // kw["stream_bits"])
+        touched = min(1.0, 1e-4 * conversions) * got.size
+        assert np.linalg.norm(got - dXo) <= lsb_b * np.sqrt(touched)
+        assert (got != dXo).mean() <= 1e-4 * conversions
+    else:
+        assert rel_l2(got, dXo) <= 1e-3
 
 
 @pytest.mark.parametrize("name,ni", [("s4b0_3x3", "nl+noise"), ("s3b0_1x1b", "noise")])

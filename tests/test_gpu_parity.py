@@ -72,6 +72,29 @@ def outputs_from_codes(xo, cfg, codes, W, w_max, in_scale, adc_fs, transposed):
     return (acc * (2.0 * scale) - (row if transposed else col)[None, :] * half_range).astype(np.float32)
 
 
+def one_code_weight(cfg, in_scale, w_max, adc_fs, top=True):
+    """Change of a layer output when one converter reports one code more: the least significant (slice,
+    cycle) or, with top, the most significant one.  Offset-binary inputs double it (coded steps are twice
+    as coarse)."""
+    per_array = bool(cfg.flags & 512)
+    q_adc = (1 << cfg.adc_bits) - 1 if per_array else (1 << (cfg.adc_bits - 1)) - 1
+    qa, qw = float((1 << cfg.input_bits) - 1), float((1 << cfg.weight_bits) - 1)
+    w = (adc_fs / q_adc) * in_scale * w_max / (qa * qw)
+    if top:
+        w *= 2.0 ** (cfg.weight_bits - cfg.slice_bits + cfg.input_bits - cfg.stream_bits)
+    return w
+
+
+def offset_output_bound(cfg, codes_got, codes_want, ref, in_scale, w_max, adc_fs):
+    """Offset-binary inputs: the output is an exact, linear digital function of the codes, so it differs from
+    the oracle's by the weights of the differing codes and by nothing else.  With n differing codes (each by
+    one LSB: the code bar) the L2 distance is at most n top-code weights; a top code weighs 2^(top shift + 1)
+    LSB-weights here, against a result that is the small difference of two large sums, which is why this
+    variant is held to this derived bound instead of the flat relative 1e-3 of the two-phase scheme."""
+    n = int((codes_got != codes_want).sum())
+    return n * 2.0 * one_code_weight(cfg, in_scale, w_max, adc_fs) / max(float(np.linalg.norm(ref)), 1e-300)
+
+
 def gpu_fwd(xb, cfg, W, X, w_max, x_scale, step=0, profile=None, codes=True):
     planes = xb.tile(cfg, dev(W), w_max, step, None if profile is None else dev(profile))
     out = xb.fwd(cfg, planes, dev(X), W.shape[1], w_max, x_scale, want_codes=codes)
@@ -230,7 +253,7 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
         assert np.array_equal(Yg, outputs_from_codes(xo, co, codes_g, W, w_max, x_scale, co.adc_fs_fwd, False))
         same = (codes_g == codes_o).reshape(-1, *Yg.shape).all(axis=0)
         assert same.mean() > 0.99 and np.array_equal(Yg[same], Yo[same])
-        assert rel_l2(Yg, Yo) <= 1e-2
+        assert rel_l2(Yg, Yo) <= offset_output_bound(co, codes_g, codes_o, Yo, x_scale, w_max, co.adc_fs_fwd)
     else:
         assert rel_l2(Yg, Yo) <= 1e-3
     if "pa" in ni:                                   # unsigned codes (several of the cases saturate at 255)
@@ -244,7 +267,7 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
         assert np.array_equal(dXg, outputs_from_codes(xo, co, codes_g, W, w_max, g_scale, co.adc_fs_bwd, True))
         same = (codes_g == codes_o).reshape(-1, *dXg.shape).all(axis=0)
         assert same.mean() > 0.99 and np.array_equal(dXg[same], dXo[same])
-        assert rel_l2(dXg, dXo) <= 1e-2
+        assert rel_l2(dXg, dXo) <= offset_output_bound(co, codes_g, codes_o, dXo, g_scale, w_max, co.adc_fs_bwd)
     else:
         assert rel_l2(dXg, dXo) <= 1e-3
     assert np.array_equal(gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=3, profile=profile, codes=False), dXg)
@@ -271,12 +294,15 @@ def test_wide_sums_nonideal(xo, xb, ni, adc_bits):
                           stream_bits=1, adc_bits=adc_bits, flags=flags, var_sigma=0.1, seed=5, adc_fs_fwd=fs,
                           adc_fs_bwd=fs)
     w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
-    Yg, _ = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=2)
+    Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=2)
     assert np.array_equal(gpu_fwd(xb, cg, W, X, w_max, x_scale, step=2, codes=False), Yg)
-    assert rel_l2(Yg, xo.fwd(co, W, X, w_max, x_scale, step=2)) <= (1e-2 if "ob" in ni else 1e-3)
-    dXg, _ = gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=2)
+    Yo, codes_o = xo.fwd(co, W, X, w_max, x_scale, step=2, want_codes=True)
+    # offset-binary inputs: bound derived from the differing codes (see offset_output_bound)
+    assert rel_l2(Yg, Yo) <= (offset_output_bound(co, codes_g, codes_o, Yo, x_scale, w_max, fs) if "ob" in ni else 1e-3)
+    dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=2)
     assert np.array_equal(gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=2, codes=False), dXg)
-    assert rel_l2(dXg, xo.bwd(co, W, dY, w_max, g_scale, step=2)) <= (1e-2 if "ob" in ni else 1e-3)
+    dXo, codes_o = xo.bwd(co, W, dY, w_max, g_scale, step=2, want_codes=True)
+    assert rel_l2(dXg, dXo) <= (offset_output_bound(co, codes_g, codes_o, dXo, g_scale, w_max, fs) if "ob" in ni else 1e-3)
 
 
 FCM_CASES = [

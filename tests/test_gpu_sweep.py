@@ -1,0 +1,225 @@
+"""Seeded randomised parity sweep: the HIP path against the CPU oracle on valid configurations drawn at
+random -- crossbars of 16..256 rows / columns, devices of 1 / 2 / 4 bits, cycles of 1..8 bits, every wire
+model, device variation, DAC level tables, ADC transfer curve, one converter per array, offset-binary
+inputs, converters of 3..16 bits, ragged shapes; the aggregate update, the pulse-level update (stochastic and
+coded trains) and convolution layers.  The hand-picked cases of test_gpu_parity.py cover the corners by
+design; this file covers combinations nobody picked.  Every case is keyed by its index: a failure names it.
+
+Bars: codes within one LSB; with ideal arrays everything bit-exact; differing codes at most 1e-4 of the
+conversions at converters of up to 8 bits (the stated bar) -- beyond that the fp32 rounding of current x
+gain meets a code boundary in proportion to the number of codes, so the bar doubles per extra bit -- and at
+least 2 codes in samples too small to resolve the fraction; the production launch returns the bits of the
+code-tap launch; outputs within relative L2 1e-3 (offset-binary inputs: the bound derived from the differing
+codes); updates within the bounds derived in test_gpu_parity.py; pulse counts bit-exact.
+"""
+import numpy as np
+import pytest
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+SWEEP_SEED = 20021115
+
+
+@pytest.fixture(scope="module")
+def xb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import xbar
+    xbar.lib()
+    return xbar
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def rel_l2(a, b):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def top_code_weight(kw, in_scale, w_max, adc_fs):
+    per_array = bool(kw["flags"] & workloads.ADC_PER_ARRAY)
+    q_adc = (1 << kw["adc_bits"]) - 1 if per_array else (1 << (kw["adc_bits"] - 1)) - 1
+    shift = kw["weight_bits"] - kw["slice_bits"] + kw["input_bits"] - kw["stream_bits"]
+    return (adc_fs / q_adc) * in_scale * w_max / (((1 << kw["input_bits"]) - 1.0) * ((1 << kw["weight_bits"]) - 1.0)) * 2.0 ** shift
+
+
+def draw_vmm_case(rng, xo):
+    R = int(rng.choice([16, 32, 48, 64, 128, 208, 256]))
+    C = int(rng.choice([16, 32, 64, 128, 256]))
+    slb = int(rng.choice([1, 2, 2, 4]))
+    wb = int(rng.choice([4, 8, 12, 16, 16])) // slb * slb
+    sb = int(rng.choice([1, 1, 2, 4, 8]))
+    adc = int(rng.integers(3, 17))
+    wire = int(rng.choice([0, xo.WIRE_AAM, xo.WIRE_AAM, xo.WIRE_AAM2, xo.WIRE_PROFILE]))
+    flags = wire | (xo.VARIATION if rng.random() < 0.4 else 0) | (xo.INPUT_SIGNED if rng.random() < 0.5 else 0)
+    if rng.random() < 0.25:
+        flags |= xo.ADC_PER_ARRAY
+        adc = min(adc, 15)
+    if rng.random() < 0.25:
+        flags |= xo.INPUT_OFFSET
+    kw = {}
+    if rng.random() < 0.25 and sb <= 4:
+        flags |= xo.DAC_LUT
+        lv = (1 << sb) - 1
+        lut = [(i / lv) ** 1.1 * 0.97 + (0.01 if rng.random() < 0.5 else 0.0) for i in range(lv + 1)]
+        if rng.random() < 0.5:
+            lut[0] = 0.0
+        kw["dac_lut"] = lut
+    if rng.random() < 0.2 and not flags & xo.ADC_PER_ARRAY:
+        flags |= xo.ADC_CURVE
+        kw["adc_curve"] = [float(np.tanh(1.2 * (-1 + i / 8)) / np.tanh(1.2)) for i in range(17)]
+    M, K, N = int(rng.integers(1, 64)), int(rng.integers(1, 700)), int(rng.integers(1, 260))
+    lw, lv = (1 << slb) - 1, (1 << sb) - 1
+    wide = 3 if flags & (xo.ADC_PER_ARRAY | xo.INPUT_OFFSET) else 1      # larger currents: off-state devices / mid-range rows
+    kw.update(xbar_rows=R, xbar_cols=C, weight_bits=wb, slice_bits=slb, input_bits=8, stream_bits=sb, adc_bits=adc,
+              flags=flags, var_sigma=0.07, seed=int(rng.integers(1, 1 << 30)),
+              adc_fs_fwd=float(max(1.0, 0.37 * np.sqrt(R) * lw * lv * wide * 1.0137)),      # off the binary grid: no exact ties
+              adc_fs_bwd=float(max(1.0, 0.41 * np.sqrt(C) * lw * lv * wide * 1.0137)),
+              r_min=float(rng.choice([1e4, 1e5])), r_max=1e6)
+    return kw, (M, K, N)
+
+
+@pytest.mark.parametrize("case", range(40))
+def test_sweep_forward_backward(xo, xb, case):
+    rng = np.random.default_rng([SWEEP_SEED, 1, case])
+    kw, (M, K, N) = draw_vmm_case(rng, xo)
+    flags, adc = kw["flags"], kw["adc_bits"]
+    co, cg = xo.make_config(**kw), xb.make_config(**kw)
+    assert xb.validate(cg) == 0, kw
+    W = (rng.standard_normal((K, N)) * 0.3).astype(np.float32)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    if not flags & xo.INPUT_SIGNED:
+        X = np.abs(X)
+    dY = (rng.standard_normal((M, N)) * 0.01).astype(np.float32)
+    S_w = kw["weight_bits"] // kw["slice_bits"]
+    profile = rng.uniform(0, 0.05, size=(S_w, 2, K, N)).astype(np.float32) if flags & xo.WIRE_PROFILE else None
+    w_max, xs, gs = float(np.abs(W).max()) * 1.1, float(np.abs(X).max()) * 0.9, float(np.abs(dY).max())
+    step = int(rng.integers(0, 100))
+    what = "case %d: %s M=%d K=%d N=%d" % (case, {k: v for k, v in kw.items() if k not in ("dac_lut", "adc_curve")}, M, K, N)
+    print(what, flush=True)
+    planes = xb.tile(cg, dev(W), w_max, step, None if profile is None else dev(profile))
+    ideal = not flags & (xo.VARIATION | xo.WIRE_AAM | xo.WIRE_AAM2 | xo.WIRE_PROFILE | xo.ADC_PER_ARRAY | xo.DAC_LUT | xo.ADC_CURVE)
+    for name, oracle_pass, gpu_pass, inp, scale, out_len, fs in (
+            ("fwd", xo.fwd, xb.fwd, X, xs, N, kw["adc_fs_fwd"]), ("bwd", xo.bwd, xb.bwd, dY, gs, K, kw["adc_fs_bwd"])):
+        want, codes_o = oracle_pass(co, W, inp, w_max, scale, step=step, profile=profile, want_codes=True)
+        got, codes_g = gpu_pass(cg, planes, dev(inp), out_len, w_max, scale, want_codes=True)
+        plain = gpu_pass(cg, planes, dev(inp), out_len, w_max, scale)
+        torch.cuda.synchronize()
+        got, plain, codes_g = got.cpu().numpy(), plain.cpu().numpy(), codes_g.cpu().numpy().astype(np.int64)
+        diff = np.abs(codes_g - codes_o)
+        n_diff = int((diff > 0).sum())
+        assert diff.max() <= 1, "%s %s: code off by %d" % (what, name, diff.max())
+        assert np.array_equal(got, plain), "%s %s: production launch differs from the code-tap launch" % (what, name)
+        if ideal:
+            assert n_diff == 0 and np.array_equal(got, want), "%s %s: ideal arrays not bit-exact" % (what, name)
+            continue
+        assert n_diff <= max(2, 1e-4 * 2.0 ** max(0, adc - 8) * diff.size), \
+            "%s %s: %d of %d codes differ" % (what, name, n_diff, diff.size)
+        offset = bool(flags & xo.INPUT_OFFSET) and (name == "bwd" or bool(flags & xo.INPUT_SIGNED))
+        # every output is an exact linear function of the codes: n differing codes move the result by at
+        # most n top-code weights (twice that with offset coding).  Small layers with coarse converters can
+        # exceed a relative 1e-3 with a single differing code, hence the second term.
+        slack = n_diff * (2.0 if offset else 1.0) * top_code_weight(kw, scale, w_max, fs) / max(float(np.linalg.norm(want)), 1e-300)
+        assert rel_l2(got, want) <= (0.0 if offset else 1e-3) + slack, "%s %s: rel L2 %.3g" % (what, name, rel_l2(got, want))
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_sweep_updates(xo, xb, case):
+    rng = np.random.default_rng([SWEEP_SEED, 2, case])
+    M, K, N = int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 300))
+    flags = (xo.UPD_NL if rng.random() < 0.6 else 0) | (xo.UPD_NOISE if rng.random() < 0.6 else 0)
+    flags |= xo.PULSE_CODED if rng.random() < 0.4 else 0
+    gamma = float(rng.uniform(0.1, 5))
+    kw = dict(flags=flags, upd_nl_v=float(rng.uniform(0.01, 2)), upd_noise_gamma=gamma, seed=int(rng.integers(1, 1 << 30)))
+    co, cg = xo.make_config(**kw), xb.make_config(**kw)
+    W = (rng.standard_normal((K, N)) * 0.2).astype(np.float32)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    dY = (rng.standard_normal((M, N)) * 0.01).astype(np.float32)
+    w_max, lr, step = float(np.abs(W).max()) * 1.5, 0.01, int(rng.integers(0, 50))
+    what = "case %d: update M=%d K=%d N=%d flags=0x%x" % (case, M, K, N, flags)
+    print(what, flush=True)
+    Wo = xo.update(co, W, X, dY, w_max, 1.0 / w_max, lr, step=step)
+    Wg = xb.update(cg, dev(W.copy()), dev(X), dev(dY), w_max, 1.0 / w_max, lr, step=step)
+    torch.cuda.synchronize()
+    # gradient from two-term bf16 operands: within 2^-15 of sum |x||d| per weight; the written change follows
+    # it with slope at most 1, the noise term gamma sqrt(|delta|) xi with gamma sqrt(error) |xi|, |xi| < 6
+    gbound = 2.0 ** -15 * (np.abs(X).T.astype(np.float64) @ np.abs(dY).astype(np.float64)) / w_max
+    tol = w_max * lr * (1.5 * gbound + (6.0 * gamma * np.sqrt(gbound) if flags & xo.UPD_NOISE else 0.0)) + 1e-6 * w_max
+    assert (np.abs(Wg.cpu().numpy() - Wo) <= tol).all(), what
+    # pulse-level update: the trains are counter-based, so the pulse counts agree bit for bit; the states
+    # differ by the two maths libraries' exp / log / sincos only
+    bl, xr, dr = int(rng.integers(1, 32)), float(rng.uniform(0.5, 4)), float(rng.uniform(0.005, 0.05))
+    dw, Mp = float(2.0 ** -rng.integers(8, 13)), min(M, 60)
+    Wpo, po = xo.update_pulsed(co, W, X[:Mp], dY[:Mp], w_max, xr, dr, bl, dw, step=step, want_pulses=True)
+    Wpg, pg = xb.update_pulsed(cg, dev(W.copy()), dev(X[:Mp]), dev(dY[:Mp]), w_max, xr, dr, bl, dw, step=step, want_pulses=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(pg.cpu().numpy(), po), what + ": pulse counts differ"
+    assert np.abs(Wpg.cpu().numpy() - Wpo).max() <= 3e-7 * w_max, what + ": pulsed states differ"
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_sweep_convolutions(xo, xb, case):
+    from oracle import conv
+    rng = np.random.default_rng([SWEEP_SEED, 3, case])
+    while True:
+        B, H, Wd = int(rng.integers(1, 4)), int(rng.integers(3, 12)), int(rng.integers(3, 12))
+        Cc, k, stride = int(rng.choice([1, 3, 5, 8, 16, 24])), int(rng.choice([1, 2, 3, 5])), int(rng.choice([1, 2, 3]))
+        pad, Nc = int(rng.integers(0, k // 2 + 1)), int(rng.integers(1, 70))
+        if H + 2 * pad >= k and Wd + 2 * pad >= k:
+            break
+    R, sb = int(rng.choice([16, 64, 128])), int(rng.choice([1, 2, 4]))
+    flags = xo.INPUT_SIGNED | int(rng.choice([0, xo.WIRE_AAM, xo.WIRE_AAM2])) | xo.UPD_NL
+    flags |= xo.INPUT_OFFSET if rng.random() < 0.3 else 0
+    fs = 1.0137 * workloads.adc_full_scale(R, sb, 2) * (3 if flags & xo.INPUT_OFFSET else 1)
+    kw = dict(xbar_rows=R, xbar_cols=R, weight_bits=8, slice_bits=2, input_bits=8, stream_bits=sb, adc_bits=8, flags=flags,
+              seed=5, adc_fs_fwd=fs, adc_fs_bwd=fs)
+    co, cg = xo.make_config(**kw), xb.make_config(**kw)
+    what = "case %d: conv B=%d H=%d W=%d C=%d k=%d stride=%d pad=%d N=%d R=%d cycle bits=%d flags=0x%x" % (
+        case, B, H, Wd, Cc, k, stride, pad, Nc, R, sb, flags)
+    print(what, flush=True)
+    Xi = rng.standard_normal((B, H, Wd, Cc)).astype(np.float32)
+    Wc = (rng.standard_normal((k * k * Cc, Nc)) * 0.1).astype(np.float32)
+    OH, OW = conv.out_size(H, k, stride, pad), conv.out_size(Wd, k, stride, pad)
+    dYc = (rng.standard_normal((B, OH, OW, Nc)) * 0.01).astype(np.float32)
+    wm, xs, gs = float(np.abs(Wc).max()), float(np.abs(Xi).max()), float(np.abs(dYc).max())
+    geom = xb.conv_geom(B, H, Wd, Cc, k, k, stride, pad)
+    planes = xb.tile(cg, dev(Wc), wm, 2)
+    cols = conv.im2col(Xi, k, k, stride, pad)
+    Yo, codes_o = xo.fwd(co, Wc, cols, wm, xs, step=2, want_codes=True)
+    Yg, codes_g = xb.conv_fwd(cg, planes, dev(Xi), geom, Nc, wm, xs, want_codes=True)
+    cols_err, codes_bo = xo.bwd(co, Wc, dYc.reshape(-1, Nc), wm, gs, step=2, want_codes=True)
+    dXo = conv.col2im(cols_err, Xi.shape, k, k, stride, pad)
+    dXg = xb.conv_bwd(cg, planes, dev(dYc), geom, Nc, wm, gs)
+    Wuo = xo.update(co, Wc, cols, dYc.reshape(-1, Nc), wm, 1.0 / wm, 0.01, step=3)
+    Wug = xb.conv_update(cg, dev(Wc.copy()), dev(Xi), dev(dYc), geom, wm, 1.0 / wm, 0.01, step=3)
+    torch.cuda.synchronize()
+    d = np.abs(codes_g.cpu().numpy().astype(np.int64) - codes_o)
+    assert d.max() <= 1 and (d > 0).sum() <= max(2, 1e-4 * d.size), what + ": forward codes"
+    n_fwd = int((d > 0).sum())
+    offset = bool(flags & xo.INPUT_OFFSET)
+    slack = n_fwd * (2.0 if offset else 1.0) * top_code_weight(kw, xs, wm, fs) / max(float(np.linalg.norm(Yo)), 1e-300)
+    assert rel_l2(Yg.cpu().numpy().reshape(Yo.shape), Yo) <= (0.0 if offset else 1e-3) + slack, what + ": forward"
+    # backward: no code tap through the convolution entry point; at most 1e-4 of its conversions (or 2) may
+    # differ by one code, each moving one patch error, hence one pixel's sum, by at most a top-code weight
+    n_bwd = max(2, int(1e-4 * codes_bo.size))
+    slack = n_bwd * (2.0 if offset else 1.0) * top_code_weight(kw, gs, wm, fs) / max(float(np.linalg.norm(dXo)), 1e-300)
+    assert rel_l2(dXg.cpu().numpy(), dXo) <= (0.0 if offset else 1e-3) + slack, what + ": backward"
+    assert np.abs(Wug.cpu().numpy() - Wuo).max() <= 1e-5 * wm, what + ": update"
+    # pulse-level update of the same layer
+    pflags = (xo.UPD_NL if rng.random() < 0.5 else 0) | (xo.UPD_NOISE if rng.random() < 0.5 else 0)
+    pflags |= xo.PULSE_CODED if rng.random() < 0.4 else 0
+    pkw = dict(flags=pflags, upd_nl_v=0.7, upd_noise_gamma=0.5, seed=9)
+    pco, pcg = xo.make_config(**pkw), xb.make_config(**pkw)
+    bl = int(rng.integers(1, 32))
+    Wqo, qo = xo.update_pulsed(pco, Wc, cols, dYc.reshape(-1, Nc), wm, xs, 0.03, bl, 2.0 ** -10, step=4, want_pulses=True)
+    Wqg, qg = xb.conv_update_pulsed(pcg, dev(Wc.copy()), dev(Xi), dev(dYc), geom, wm, xs, 0.03, bl, 2.0 ** -10, step=4,
+                                    want_pulses=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(qg.cpu().numpy(), qo), what + ": pulse counts differ"
+    assert np.abs(Wqg.cpu().numpy() - Wqo).max() <= 3e-7 * wm, what + ": pulsed states differ"
