@@ -87,6 +87,7 @@ extern "C" {
 #define XBAR_EWORKSPACE -4   /* workspace / plane buffer smaller than the size query says             */
 #define XBAR_EHIP       -5   /* a HIP call failed (kernel launch)                                     */
 #define XBAR_ENOTSUP    -6   /* valid in the model, not implemented by the GPU kernels                */
+#define XBAR_ESCRATCH   -7   /* xbar_fwd_static: the shape needs more than XBAR_STATIC_SCRATCH_BYTES   */
 
 /* operations, for xbar_workspace_bytes */
 #define XBAR_OP_FWD    0
@@ -182,6 +183,20 @@ size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N)
  */
 int xbar_fwd(const xbar_config* cfg, const void* planes, const float* X, float* Y, int M, int K, int N,
              float w_max, float x_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream);
+
+/*
+ * xbar_fwd for callers that cannot allocate or hand over scratch memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): the same kernels and results as xbar_fwd without
+ * the code tap, with the workspace in an array of XBAR_STATIC_SCRATCH_BYTES that the library holds on every
+ * GPU it runs on until the process ends.  The call allocates and frees nothing; its first call on a device
+ * looks the array's address up (with that device current).  Shapes whose xbar_workspace_bytes(cfg,
+ * XBAR_OP_FWD, M, K, N) exceeds the array return XBAR_ESCRATCH and enqueue nothing.  All calls on one GPU
+ * share the array: two calls must not overlap (order them on one stream, or synchronise between streams);
+ * nothing in it has to start at zero (every byte that is read is written first by the same call).
+ */
+#define XBAR_STATIC_SCRATCH_BYTES (32u << 20)
+int xbar_fwd_static(const xbar_config* cfg, const void* planes, const float* X, float* Y, int M, int K, int N,
+                    float w_max, float x_scale, void* hip_stream);
 
 /*
  * Backward VMM (Sec. IV: same procedure as forward): dX[M][K] from dY[M][N]; the same devices are

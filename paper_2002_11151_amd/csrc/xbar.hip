@@ -776,6 +776,27 @@ thread_local const unsigned long long* g_step_source = nullptr;
 
 __global__ void step_advance_kernel(unsigned long long* counter) { *counter += 1ull; }
 
+// Scratch of xbar_fwd_static: one array per GPU that the library runs on, held until the process ends.
+// The name is a host-side stand-in; host code uses the device address that hipGetSymbolAddress returns.
+static __device__ __align__(256) unsigned char scratch[XBAR_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this GPU's copy of the scratch array (looked up once per device, with that device current).
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return XBAR_EHIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return XBAR_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return XBAR_OK;
+}
+
 VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bool transposed) {
   VmmPlan p;
   p.g = plane_geom(c, d, K, N, transposed);
@@ -1119,6 +1140,7 @@ const char* xbar_strerror(int code) {
     case XBAR_EWORKSPACE: return "workspace or plane buffer too small";
     case XBAR_EHIP: return "HIP kernel launch failed";
     case XBAR_ENOTSUP: return "not supported by the GPU kernels";
+    case XBAR_ESCRATCH: return "shape needs more scratch memory than the library's static array holds (XBAR_STATIC_SCRATCH_BYTES)";
     default: return "unknown xbar status";
   }
 }
@@ -1263,6 +1285,18 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
 int xbar_fwd(const xbar_config* cfg, const void* planes, const float* X, float* Y, int M, int K, int N, float w_max,
              float x_scale, void* ws, size_t ws_bytes, int16_t* codes, void* hip_stream) {
   return run_vmm(cfg, planes, X, Y, M, K, N, w_max, x_scale, ws, ws_bytes, codes, hip_stream, false);
+}
+
+int xbar_fwd_static(const xbar_config* cfg, const void* planes, const float* X, float* Y, int M, int K, int N, float w_max,
+                    float x_scale, void* hip_stream) {
+  int rc = xbar_config_validate(cfg);
+  if (rc) return rc;
+  if ((rc = check_shape(M, K, N))) return rc;
+  const size_t need = plan_vmm(cfg, derive(cfg), M, K, N, false).ws_bytes;
+  if (need > (size_t)XBAR_STATIC_SCRATCH_BYTES) return XBAR_ESCRATCH;
+  void* ws = nullptr;
+  if ((rc = static_scratch(&ws))) return rc;
+  return run_vmm(cfg, planes, X, Y, M, K, N, w_max, x_scale, ws, (size_t)XBAR_STATIC_SCRATCH_BYTES, nullptr, hip_stream, false);
 }
 
 int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float* dX, int M, int K, int N, float w_max,

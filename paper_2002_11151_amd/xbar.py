@@ -88,6 +88,8 @@ _SIGNATURES = {
                            C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "xbar_bwd": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                            C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
+    "xbar_fwd_static": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
+                                  C.c_float, C.c_float, C.c_void_p]),
     "xbar_plane_format": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_int)]),
     "xbar_trace_next_vmm": (None, [C.c_void_p, C.c_void_p]),
     "xbar_set_step_source": (None, [C.c_void_p]),
@@ -252,6 +254,16 @@ def _vmm(fn, op, cfg, planes, inp, out_cols, K, N, w_max, in_scale, ws, out, wan
 def fwd(cfg, planes, X, N, w_max, x_scale, ws=None, out=None, want_codes=False):
     """xbar_fwd: Y[M][N] from X[M][K] through the planes of tile()."""
     return _vmm(lib().xbar_fwd, OP_FWD, cfg, planes, X, N, X.shape[1], N, w_max, x_scale, ws, out, want_codes)
+
+
+def fwd_static(cfg, planes, X, N, w_max, x_scale, out):
+    """xbar_fwd_static: xbar_fwd with the workspace in the library's static per-GPU array (allocates nothing:
+    the caller passes the output tensor)."""
+    M, K = X.shape
+    assert out.shape == (M, N) and out.dtype == torch.float32 and out.is_contiguous()
+    _check(lib().xbar_fwd_static(C.byref(cfg), C.c_void_p(planes.data_ptr()), _dev(X), _dev(out), M, K, N, w_max, x_scale,
+                                 _stream()))
+    return out
 
 
 def bwd(cfg, planes, dY, K, w_max, g_scale, ws=None, out=None, want_codes=False):
