@@ -32,6 +32,7 @@ struct VmmArgs {
   int scale_lo, scale_hi;     // kFmtF6: block-scale bytes (127 + exponent) of terms 0..3 and of term 4
   int vt_per_chunk, nchunk, lds_kb;
   int split_sg;               // slices per 32-bit group of the split wide path
+  int flush_every;            // 32-bit sums: added to the block's own 64-bit partial sum every so many virtual tiles (0: never)
   int direct;                 // single chunk and nothing to correct: the kernel scales and stores the result itself
   int total_wg, per_xcd;
   float gain;          // float(Q) / adc_fs
@@ -707,11 +708,45 @@ __device__ __forceinline__ void vmm_block(const VmmArgs& a, u32x4* lds, const Ti
         }
     }
     return;
-  } else {
-    const int only_sg0 = 0;
-    XBAR_ALL_VIRTUAL_TILES
   }
 #undef XBAR_ALL_VIRTUAL_TILES
+  // 32-bit sums hold only a few virtual tiles (3 with 16-bit weights, 8-bit inputs and an 8-bit converter).
+  // Rather than cutting the contraction into that many more chunks, each with a partial result of its own
+  // in memory, a block with more virtual tiles than that adds its sums to a 64-bit partial result every
+  // `flush_every` tiles: every element has one owner lane, which reads back only what it wrote itself.
+  int since = 0;
+  const bool flushing = WIDE == 0 && a.flush_every > 0 && vt1 - vt0 > a.flush_every;
+  for (int vt = vt0; vt < vt1; ++vt) {
+    /* vt = (phase, array, tile), tile fastest */
+    const int pa = vt / a.T, t = vt - pa * a.T;
+    const int p = PER_ARRAY ? pa >> 1 : pa, pol = PER_ARRAY ? pa & 1 : 0;
+    const int rows = min(a.tile, a.Lin - t * a.tile);
+    run_tile(a, lds, p, pol, t, rows, lane, mp0, op, y, y64, 0);
+    ++since;
+    if constexpr (WIDE == 0) {
+      if (flushing && since == a.flush_every && vt + 1 < vt1) {
+        const bool first = vt + 1 - vt0 == a.flush_every;
+        const uint32_t bias = a.bias_per_vt * (uint32_t)since;
+        long long* part = reinterpret_cast<long long*>(a.part) + (size_t)chunk * a.M * a.Lout;
+        int lane_now = lane, mp_now = mp0;              // as above: no element addresses kept across the contraction
+        asm volatile("" : "+v"(lane_now), "+v"(mp_now));
+#pragma unroll
+        for (int pm = 0; pm < PM; ++pm)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int m = (mp_now + pm) * 32 + (lane_now & 31);
+            const int o = op * 32 + 8 * (r >> 2) + 4 * (lane_now >> 5) + (r & 3);
+            if (m < a.M && o < a.Lout && mp_now + pm < a.MP) {
+              long long v = (long long)(int32_t)(y[pm][r] - bias);
+              if (!first) v += part[(size_t)m * a.Lout + o];
+              part[(size_t)m * a.Lout + o] = v;
+            }
+            y[pm][r] = 0;
+          }
+        since = 0;
+      }
+    }
+  }
   if constexpr (CODES) {
     if (a.hist) {                                  // statistics pass: the counters are the only result
       __syncthreads();
@@ -721,7 +756,7 @@ __device__ __forceinline__ void vmm_block(const VmmArgs& a, u32x4* lds, const Ti
     }
   }
   // partial result of this chunk
-  const uint32_t bias = a.bias_per_vt * (uint32_t)(vt1 - vt0);
+  const uint32_t bias = a.bias_per_vt * (uint32_t)since;
 #pragma unroll
   for (int pm = 0; pm < PM; ++pm)
 #pragma unroll
@@ -730,13 +765,14 @@ __device__ __forceinline__ void vmm_block(const VmmArgs& a, u32x4* lds, const Ti
       const int o = op * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
       if (m < a.M && o < a.Lout && mp0 + pm < a.MP) {
         const size_t idx = ((size_t)chunk * a.M + m) * a.Lout + o;
+        long long sum = WIDE ? y64[pm][r] : (long long)(int32_t)(y[pm][r] - bias);
+        if (flushing) sum += reinterpret_cast<const long long*>(a.part)[idx];
         if (a.direct) {        // nothing to add up across chunks: scale and store the result itself
-          const long long sum = WIDE ? y64[pm][r] : (long long)(int32_t)(y[pm][r] - bias);
           a.out[idx] = (float)((double)sum * a.scale);
-        } else if (WIDE) {
-          reinterpret_cast<long long*>(a.part)[idx] = y64[pm][r];
+        } else if (WIDE || a.flush_every > 0) {
+          reinterpret_cast<long long*>(a.part)[idx] = sum;
         } else {
-          reinterpret_cast<int32_t*>(a.part)[idx] = (int32_t)(y[pm][r] - bias);
+          reinterpret_cast<int32_t*>(a.part)[idx] = (int32_t)sum;
         }
       }
     }
@@ -763,6 +799,7 @@ struct VmmPlan {
   int sg;              // kFmtF6: slices per staged group
   int Lin, Lout, MP, P, VT, vt_per_chunk, nchunk, pm, nw, MB, lds_kb;
   int wide;            // 0: sums fit 32 bits; 1: 64-bit sums; 2: 32-bit sums per slice group, widened per group
+  int flush_every;     // wide == 0: virtual tiles a 32-bit sum holds, when a chunk has more than that (else 0)
   int split_sg;        // slices per group of mode 2
   uint32_t bias_split; // kMagicBits * sum of the shift weights of one such group, mod 2^32
   int offset;          // signed inputs in one phase of offset-binary codes

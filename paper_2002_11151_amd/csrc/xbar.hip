@@ -855,12 +855,14 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   int want_chunks = std::max(1, cdiv(4096, groups));      // 8 rounds of 2 blocks on 256 CUs: the last, partly
                                                           // filled round costs less (measured: 0.8 % per step over 2048)
   int per = std::max(1, cdiv(p.VT, want_chunks));
-  if (!p.wide) per = (int)std::min<unsigned long long>((unsigned long long)per, fit);
+  // 32-bit sums hold `fit` virtual tiles: a chunk with more adds them to a 64-bit partial sum of its own in
+  // between (no extra chunks, so no extra partial results for the adding-up pass to read)
+  p.flush_every = (!p.wide && (unsigned long long)per > fit) ? (int)fit : 0;
   if (p.wide == 2) per = (int)std::min<unsigned long long>((unsigned long long)per, fit_split);
   p.nchunk = cdiv(p.VT, per);
   p.vt_per_chunk = cdiv(p.VT, p.nchunk);                  // same number of chunks, evenly filled
   p.a_bytes = align256((size_t)p.P * p.MP * p.g.T * p.ks16 * 512);
-  p.part_bytes = align256((size_t)p.nchunk * M * p.Lout * (p.wide ? 8 : 4));
+  p.part_bytes = align256((size_t)p.nchunk * M * p.Lout * ((p.wide || p.flush_every) ? 8 : 4));
   p.ws_bytes = p.a_bytes + p.part_bytes;
   return p;
 }
@@ -962,6 +964,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   const bool general = codes != nullptr || hist != nullptr || level_table || a.adc_curve_on;
   const bool split = p.wide == 2 && !general;          // adds its groups up in the partial-sum buffer
   a.split_sg = p.split_sg;
+  a.flush_every = hist ? 0 : p.flush_every;            // the statistics pass keeps no sums
   a.direct = (p.nchunk == 1 && !p.offset && !split) ? 1 : 0;
   a.total_wg = p.nchunk * p.g.OP * p.MB;
   a.per_xcd = cdiv(a.total_wg, 8);
@@ -990,7 +993,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
     f.out = out;
     f.n = (long long)M * p.Lout;
     f.nchunk = p.nchunk;
-    f.wide = p.wide != 0;
+    f.wide = p.wide != 0 || p.flush_every != 0;
     f.Lout = p.Lout;
     f.scale = a.scale;
     f.wsum = nullptr;
