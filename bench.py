@@ -266,7 +266,7 @@ def main():
     max_planes = max_ws = max_out = max_ws_upd = 0
     for i, g in enumerate(gemms):
         flags = kw["flags"] | (workloads.INPUT_SIGNED if g.signed_input else 0)
-        cfg = xb.make_config(**dict(kw, flags=flags))
+        cfg = xb.make_config(**dict(kw, flags=flags, seed=(kw["seed"] << 20) + i))      # every layer keys its own random streams
         W, X, dY = workloads.layer_tensors_torch(g, seed=i, device=device)
         geom = None
         if args.from_images and g.conv is not None:

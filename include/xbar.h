@@ -397,6 +397,22 @@ void xbar_trace_next_vmm(void* before, void* after);
 int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void* hip_stream);
 
 /*
+ * ADC range from measured statistics (Sec. IV-B: the converter's maximum current comes from output
+ * distribution statistics): the smallest power of two that is at least the `quantile` (in (0, 1]) of the
+ * |column current| distribution counted by xbar_adc_histogram, hist[b] = conversions with
+ * rne(|I| / bin_width) == b; the current of bin b is taken as (b + 0.5) bin_width, at least bin_width.
+ * Host-only: `hist` is a HOST copy of the `bins` counters.  Returns 0 for invalid arguments.
+ */
+float xbar_adc_range_from_histogram(const unsigned long long* hist, int bins, float bin_width, double quantile);
+
+/*
+ * Slots of a pulse train of `bl` slots that carry pulses (what takes the place of bl in the learning rate
+ * of xbar_update_pulsed): bl for stochastic trains, Tx Td with XBAR_PULSE_CODED.  Host-only.  Negative status
+ * for an invalid configuration or bl outside 1..31.
+ */
+int xbar_pulse_slots(const xbar_config* cfg, int bl);
+
+/*
  * Operand format that the contraction uses for this configuration (information for the benchmark's
  * accounting): returns 0 = fp16 planes (v_mfma_f32_32x32x16_f16) or 1 = 6-bit planes with 4-bit digits
  * (v_mfma_scale_f32_32x32x64_f8f6f4; cycles of 1 or 2 bits without a general DAC level table), or a

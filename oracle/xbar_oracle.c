@@ -270,7 +270,7 @@ int xo_planes(const xo_config* cfg, const float* W, int Ks, int Ns, const int32_
   int32_t d[64];
   if (S > 64) return -1;
   if (cfg->flags & XO_WIRE_AAM2) {
-    /* All first-order paths (Sec. IV-D: "considering more ... paths"): the voltage at a device
+    /* All first-order paths (Sec. IV-D: the analytical model extended beyond the shortest path): the voltage at a device
      * drops by the current of EVERY device on its row through the row-wire segments they share
      * with it, and rises on the column side by the current of every device on its column through
      * the shared column segments:

@@ -5,6 +5,15 @@ using namespace xbar_detail;
 
 namespace {
 
+// Deterministic pulse coding: the bl slots form tx frames of td sub-slots, tx = floor(sqrt(bl)), td = floor(bl / tx).
+void coded_frames(int bl, int* tx, int* td) {
+  int t = 1;
+  while ((t + 1) * (t + 1) <= bl) ++t;
+  *tx = t;
+  *td = bl / t;
+}
+
+
 // ---------------------------------------------------------------------------------------------
 // pulse-level update (Sec. IV-C names the parallel update schemes; this is the one with stochastic
 // pulse trains, whose coincidences multiply): every sample drives rows and columns with random
@@ -420,9 +429,7 @@ int run_update_pulsed(const xbar_config* cfg, float* W, const float* X, const fl
   // the aggregate model's noise for one pulse: its standard deviation gamma sqrt(dG) belongs to the ideal change
   // before the learning rate, and this scheme's mean equals the aggregate update at lr = bl dw_min w_max / (x_range d_range)
   a.coded = (cfg->flags & XBAR_PULSE_CODED) ? 1 : 0;
-  a.tx = 1;
-  while ((a.tx + 1) * (a.tx + 1) <= bl) ++a.tx;
-  a.td = bl / a.tx;
+  coded_frames(bl, &a.tx, &a.td);
   const int slots = a.coded ? a.tx * a.td : bl;
   const double lr_eq = (double)slots * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
   a.sigma = (double)cfg->upd_noise_gamma * std::sqrt(lr_eq * (double)dw_min);
@@ -492,6 +499,16 @@ int xbar_conv_update_pulsed(const xbar_config* cfg, float* W, const float* X, co
   if (rc) return rc;
   return run_update_pulsed(cfg, W, X, dY, M, K, N, w_max, x_range, d_range, bl, dw_min, step, pulses, ws, ws_bytes,
                            hip_stream, conv_is_dense(geom) ? nullptr : &g);
+}
+
+int xbar_pulse_slots(const xbar_config* cfg, int bl) {
+  const int rc = xbar_config_validate(cfg);
+  if (rc) return rc;
+  if (bl < 1 || bl > 31) return XBAR_EINVAL;
+  if (!(cfg->flags & XBAR_PULSE_CODED)) return bl;
+  int tx, td;
+  coded_frames(bl, &tx, &td);
+  return tx * td;
 }
 
 }  // extern "C"

@@ -1113,6 +1113,20 @@ int xbar_probe_mfma_rate(int mode, int iters, void* out, size_t out_bytes, void*
   return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
 }
 
+float xbar_adc_range_from_histogram(const unsigned long long* hist, int bins, float bin_width, double quantile) {
+  if (!hist || bins <= 0 || !finite_pos(bin_width) || !(quantile > 0.0) || quantile > 1.0) return 0.0f;
+  double total = 0.0;
+  for (int b = 0; b < bins; ++b) total += (double)hist[b];
+  double cum = 0.0;
+  int b = 0;
+  for (; b < bins - 1; ++b) {
+    cum += (double)hist[b];
+    if (cum >= quantile * total) break;
+  }
+  const double current = std::max(((double)b + 0.5) * (double)bin_width, (double)bin_width);
+  return (float)std::exp2(std::ceil(std::log2(current)));
+}
+
 int xbar_plane_format(const xbar_config* cfg, int* terms) {
   const int rc = xbar_config_validate(cfg);
   if (rc) return rc;

@@ -20,29 +20,18 @@ from . import xbar as xb
 HEADROOM_W, HEADROOM_X, HEADROOM_G = 2.0, 1.5, 4.0
 
 
-def range_from_histogram(hist, bin_width, quantile):
-    """Smallest power of two that is at least the `quantile` of the |current| distribution
-    (hist[b] = number of conversions with rne(|I| / bin_width) == b, a device tensor)."""
-    cum = torch.cumsum(hist.to(torch.float64), 0)
-    b = int(torch.searchsorted(cum, quantile * float(cum[-1])).item())
-    return float(2.0 ** math.ceil(math.log2(max((b + 0.5) * bin_width, bin_width))))
-
-
-def pulse_slots(cfg, bl):
-    """Slots of a pulse train that carry pulses: all `bl` of a stochastic train, frames x sub-slots of a coded one."""
-    if not cfg.flags & xb.PULSE_CODED:
-        return bl
-    tx = math.isqrt(bl)
-    return tx * (bl // tx)
-
-
 class CrossbarLayer:
     """One weight layer: W[K][N], its conductance planes of the current step, its ranges."""
 
     def __init__(self, net, cfg_kwargs, K, N, geom, signed_input, gen, device):
         self.net = net                 # supplies `ops` (the binding, or a stand-in that records / times its calls)
         flags = cfg_kwargs["flags"] | (xb.INPUT_SIGNED if signed_input else 0)
-        self.cfg = xb.make_config(**dict(cfg_kwargs, flags=flags))
+        # every layer keys its own random streams (device variation, write noise, pulse trains): layers of equal
+        # shape must not see the same draws at the same step
+        self.index = getattr(net, "n_crossbar_layers", 0)
+        net.n_crossbar_layers = self.index + 1
+        seed = (int(cfg_kwargs.get("seed", 0)) << 20) + self.index
+        self.cfg = xb.make_config(**dict(cfg_kwargs, flags=flags, seed=seed))
         self.K, self.N, self.geom = K, N, geom
         self.W = torch.randn((K, N), generator=gen, device=device, dtype=torch.float32) * math.sqrt(2.0 / K)
         self.w_max = HEADROOM_W * net.ops.absmax(self.W)
@@ -106,7 +95,7 @@ class CrossbarLayer:
         lr = slots dw_min w_max / (x_range d_range) with x_range = the calibrated input range.  Stochastic
         trains round without bias, so the pulse size is free and the error range follows from it; coded pulses
         drop what is below half a level, so there the errors use their calibrated range and the pulse size follows."""
-        bl, slots = pulse["bl"], pulse_slots(self.cfg, pulse["bl"])
+        bl, slots = pulse["bl"], self.net.ops.pulse_slots(self.cfg, pulse["bl"])
         if self.cfg.flags & xb.PULSE_CODED:
             return bl, lr * self.x_scale * self.g_scale / (slots * self.w_max), self.g_scale
         return bl, pulse["dw_min"], slots * pulse["dw_min"] * self.w_max / (lr * self.x_scale)
@@ -122,7 +111,7 @@ class CrossbarLayer:
             hist = ops.adc_histogram(cfg, self.planes, inp, self.K, self.N, in_scale, op, bin_width, ws=ws)
         else:
             hist = ops.conv_adc_histogram(cfg, self.planes, inp, self.geom, self.N, in_scale, op, bin_width, ws=ws)
-        return range_from_histogram(hist, bin_width, self.net.adc_quantile)
+        return ops.adc_range_from_histogram(hist, bin_width, self.net.adc_quantile)
 
     def workspace_bytes(self, batch_rows):
         fcm = xb.workspace_bytes(self.cfg, xb.OP_FCM, 1, self.K, self.N) if self.cfg.flags & xb.NI_WIRE_PROFILE else 0
@@ -181,6 +170,11 @@ class Network:
         kernels' arguments are frozen in a graph, so the step number that keys the device variation and the write
         noise comes from a counter in device memory that the graph itself advances.  Runs one real step (the
         warm-up of the capture) and returns its losses; every `replay(x, labels)` is the next step."""
+        # The circuit-level model runs when step % fcm_every == 0, a test the host makes per step: a graph would
+        # freeze its outcome at capture time (a refresh on every replay, or on none).
+        if self.fcm_every > 1 and any(L.cfg.flags & xb.NI_WIRE_PROFILE for L in self.layers):
+            raise ValueError("capture(): the stored-profile wire model with fcm_every > 1 refreshes its profile on some "
+                             "steps only, which a captured graph cannot express; run those steps eagerly")
         self._graph_x, self._graph_labels = x.clone(), labels.clone()
         self._graph_counter = torch.full((1,), self.step_no, dtype=torch.int64, device=x.device)
         main, side = torch.cuda.current_stream(), torch.cuda.Stream()

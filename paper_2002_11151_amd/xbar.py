@@ -91,6 +91,8 @@ _SIGNATURES = {
     "xbar_fwd_static": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                   C.c_float, C.c_float, C.c_void_p]),
     "xbar_plane_format": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_int)]),
+    "xbar_adc_range_from_histogram": (C.c_float, [C.c_void_p, C.c_int, C.c_float, C.c_double]),
+    "xbar_pulse_slots": (C.c_int, [C.POINTER(Config), C.c_int]),
     "xbar_trace_next_vmm": (None, [C.c_void_p, C.c_void_p]),
     "xbar_set_step_source": (None, [C.c_void_p]),
     "xbar_step_advance": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -173,6 +175,23 @@ def probe_mfma_rate(mode, iters, scratch):
     per_instruction = {0: 16384, 1: 16384, 2: 32768, 3: 32768}.get(mode, 65536)      # 32 x 32 x (16 | 32 | 64)
     per_iteration = 32 if mode >= 5 else 16
     return 2.0 * per_iteration * iters * 2048 * per_instruction
+
+
+def adc_range_from_histogram(hist, bin_width, quantile):
+    """xbar_adc_range_from_histogram: converter range from the counters of adc_histogram (copied to the host)."""
+    host = hist.detach().to("cpu", torch.int64).contiguous()
+    fs = lib().xbar_adc_range_from_histogram(C.c_void_p(host.data_ptr()), host.numel(), bin_width, quantile)
+    if fs <= 0.0:
+        raise XbarError("xbar_adc_range_from_histogram: invalid arguments")
+    return float(fs)
+
+
+def pulse_slots(cfg, bl):
+    """xbar_pulse_slots: slots of a pulse train that carry pulses (all bl of a stochastic train, frames x sub-slots
+    of a coded one)."""
+    n = lib().xbar_pulse_slots(C.byref(cfg), bl)
+    _check(min(n, 0))
+    return n
 
 
 def plane_format(cfg):

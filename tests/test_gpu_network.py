@@ -410,3 +410,42 @@ def test_training_steps_from_a_hip_graph(kind):
         assert torch.equal(la.W, lb.W)
     assert graphed.step_no == eager.step_no == 4
     assert not torch.equal(want[0], want[1])
+
+
+def test_layers_of_equal_shape_draw_their_own_random_numbers():
+    """Device variation, write noise and pulse trains are keyed by (seed, stream, step, element): two layers of
+    one network with the same shape must not see the same draws at the same step, so every layer has a seed of
+    its own."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import sequential, xbar as xb
+    kw = workloads.config_kwargs("mlp")
+    kw.update(flags=kw["flags"] | workloads.NI_VARIATION, var_sigma=0.1, stream_bits=1)
+    kw["adc_fs_fwd"] = kw["adc_fs_bwd"] = workloads.adc_full_scale(128, 1, 2)
+    net = sequential.Sequential(kw, [("fc", 48), ("fc", 48), ("fc", 48)], batch=8, in_shape=(48,), seed=5)
+    first, second = net.layers[1], net.layers[2]                       # both 48 x 48, both with signed inputs
+    assert (first.K, first.N) == (second.K, second.N) and first.cfg.flags == second.cfg.flags
+    assert first.cfg.seed != second.cfg.seed
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2)
+    X = torch.randn((8, 48), generator=gen, device="cuda")
+    dY = torch.randn((8, 48), generator=gen, device="cuda") * 0.01
+    W = first.W.clone()
+    w_max = 2.0 * float(W.abs().max())
+
+    def passes(cfg):
+        planes = xb.tile(cfg, W, w_max, 7)
+        Y = xb.fwd(cfg, planes, X, 48, w_max, 4.0)                      # device variation of step 7
+        Wn = xb.update(cfg, W.clone(), X, dY, w_max, 1.0 / w_max, 0.01, 7)      # write noise of step 7
+        return Y, Wn
+
+    Y1, W1 = passes(first.cfg)
+    Y1b, W1b = passes(first.cfg)
+    Y2, W2 = passes(second.cfg)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y1b) and torch.equal(W1, W1b)                # same key, same draws
+    assert not torch.equal(Y1, Y2) and not torch.equal(W1, W2)          # another layer, other draws
+    # the noise fields are unrelated, not shifted copies: their correlation is that of independent draws
+    n1, n2 = (W1 - W).flatten().double(), (W2 - W).flatten().double()
+    corr = float(torch.dot(n1 - n1.mean(), n2 - n2.mean()) / (n1.std() * n2.std() * (n1.numel() - 1)))
+    assert abs(corr) < 0.1

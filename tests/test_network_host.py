@@ -18,7 +18,9 @@ class StandIn:
         self.xb, self.calls = xb, []
 
     def __getattr__(self, name):
-        if name.startswith("OP_") or name in ("ADC_HIST_BINS", "ADC_PER_ARRAY", "NI_WIRE_PROFILE"):
+        # constants, and the library's host-only rules (converter range from counts, slots of a coded train)
+        if name.startswith("OP_") or name in ("ADC_HIST_BINS", "ADC_PER_ARRAY", "NI_WIRE_PROFILE", "pulse_slots",
+                                              "adc_range_from_histogram"):
             return getattr(self.xb, name)
         raise AttributeError(name)
 
@@ -127,6 +129,20 @@ def test_circuit_model_refresh_schedule(net_and_ops):
     assert all(c[1]["profile"] for c in ops.calls if c[0] == "tile")
 
 
+def test_graph_capture_refused_with_interpolated_profile(net_and_ops):
+    """A captured graph freezes the host's `step % fcm_every == 0` decision: with the stored-profile wire model
+    and fcm_every > 1 replayed steps would differ from eager ones, so capture() refuses; every layer of the
+    network also keys its own random streams."""
+    make, ops = net_and_ops
+    flags = (workloads.config_kwargs("mlp")["flags"] & ~workloads.NI_WIRE_AAM) | workloads.NI_WIRE_PROFILE
+    net = make(flags=flags)
+    assert [L.cfg.seed for L in net.layers] == [0, 1]
+    net.fcm_every = 3
+    x, labels = _batch()
+    with pytest.raises(ValueError, match="fcm_every"):
+        net.capture(x, labels, 0.01)
+
+
 def test_pulse_ranges_follow_the_learning_rate(net_and_ops):
     make, ops = net_and_ops
     net = make()
@@ -162,13 +178,24 @@ def test_converter_ranges_from_the_histograms(net_and_ops):
     # the rule itself
     hist = torch.zeros(4096, dtype=torch.int64)
     hist[3] = 10
-    assert resnet_cifar.range_from_histogram(hist, 0.5, 0.5) == 2.0                   # (3 + 0.5) * 0.5 = 1.75 -> 2
+    from paper_2002_11151_amd import xbar as xb
+    assert xb.adc_range_from_histogram(hist, 0.5, 0.5) == 2.0                         # (3 + 0.5) * 0.5 = 1.75 -> 2
     hist[4000] = 10
-    assert resnet_cifar.range_from_histogram(hist, 0.5, 0.99) == 2048.0
+    assert xb.adc_range_from_histogram(hist, 0.5, 0.99) == 2048.0
+    # ... and against the definition the workload presets and the GPU tests use, on random counts
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        counts = (rng.random(4096) < 0.05) * rng.integers(1, 1000, size=4096)
+        counts[int(rng.integers(0, 4096))] += 1
+        bw, q = float(rng.uniform(0.01, 3.0)), float(rng.choice([0.5, 0.9, 0.99, 0.999, 1.0]))
+        assert xb.adc_range_from_histogram(torch.from_numpy(counts), bw, q) == \
+            workloads.adc_full_scale_from_histogram(counts, np.float32(bw), q)
 
 
 def test_pulse_slots_of_coded_trains():
-    from paper_2002_11151_amd import resnet_cifar, xbar as xb
+    from paper_2002_11151_amd import xbar as xb
     plain, coded = xb.make_config(), xb.make_config(flags=xb.PULSE_CODED)
-    assert [resnet_cifar.pulse_slots(plain, bl) for bl in (1, 15, 31)] == [1, 15, 31]
-    assert [resnet_cifar.pulse_slots(coded, bl) for bl in (1, 3, 4, 15, 16, 30, 31)] == [1, 3, 4, 15, 16, 30, 30]
+    assert [xb.pulse_slots(plain, bl) for bl in (1, 15, 31)] == [1, 15, 31]
+    assert [xb.pulse_slots(coded, bl) for bl in (1, 3, 4, 15, 16, 30, 31)] == [1, 3, 4, 15, 16, 30, 30]
+    with pytest.raises(xb.XbarError):
+        xb.pulse_slots(coded, 32)
