@@ -50,12 +50,14 @@
 #define XO_ADC_PER_ARRAY 512u
 #define XO_INPUT_OFFSET 1024u
 #define XO_PULSE_CODED 2048u
+#define XO_PULSE_MAGNITUDE 4096u
 
 #define XO_STREAM_VARIATION 1u
 #define XO_STREAM_WRITE     2u
 #define XO_STREAM_PULSE_ROWS  3u
 #define XO_STREAM_PULSE_COLS  4u
 #define XO_STREAM_PULSE_NOISE 5u
+#define XO_STREAM_WRITE_PAIR  6u
 
 typedef struct xo_config {
   uint32_t struct_size, abi_version;
@@ -534,6 +536,61 @@ int xo_update(const xo_config* cfg, float* W, const float* X, const float* dY, i
 }
 
 /* ------------------------------------------------------------------------------------------- */
+/* Update with per-polarity device state.  The aggregate model above treats the positive and the  */
+/* negative device of a weight as ONE effective device (Sec. IV-C speaks of "the" conductance G of  */
+/* a weight).  This variant keeps both conductances of the pair (Sec. IV-A: positive and negative   */
+/* conductances in two arrays whose currents are subtracted) as states of their own, gp and gn in   */
+/* [0, 1] (units of Gmax - Gmin above Gmin), with W = w_max (gp - gn).                               */
+/* Reading (the paper gives no rule for how a write is shared by the pair): the ideal change is     */
+/* split evenly and applied in opposite directions, gp <- gp - lr w_p, gn <- gn + lr w_n, where each */
+/* device sees half the ideal change delta / 2, scaled by the write non-linearity at ITS OWN state   */
+/* and direction (exp(-v g) when it rises, exp(-v (1 - g)) when it falls) and with a noise draw of   */
+/* its own, sigma = gamma sqrt(|delta| / 2) (the two variances add up to the effective device's      */
+/* gamma^2 |delta|); each device is clamped to [0, 1] on its own.  Normal number 2 (k N + n) + pol   */
+/* of stream 6.  With v = gamma = 0 and no device at a rail the pair's difference moves exactly as   */
+/* the effective device does.  xo_pair_init places a weight symmetrically about mid-range:           */
+/* gp = (1 + g) / 2, gn = (1 - g) / 2, g = clamp(W / w_max, -1, 1).                                  */
+/* ------------------------------------------------------------------------------------------- */
+void xo_pair_init(const float* W, float* Gp, float* Gn, size_t count, float w_max) {
+  for (size_t i = 0; i < count; ++i) {
+    const double g = clampd((double)W[i] / (double)w_max, -1.0, 1.0);
+    Gp[i] = (float)(0.5 * (1.0 + g));
+    Gn[i] = (float)(0.5 * (1.0 - g));
+  }
+}
+
+int xo_update_pair(const xo_config* cfg, float* Gp, float* Gn, float* W, const float* X, const float* dY, int M, int K,
+                   int N, float w_max, float grad_scale, float lr, uint64_t step) {
+  for (int k = 0; k < K; ++k)
+    for (int n = 0; n < N; ++n) {
+      double grad = 0.0;
+      for (int m = 0; m < M; ++m) grad += (double)X[(size_t)m * K + k] * (double)dY[(size_t)m * N + n];
+      const size_t at = (size_t)k * N + n;
+      const double delta = (double)grad_scale * grad;
+      double state[2] = {(double)Gp[at], (double)Gn[at]};
+      for (int pol = 0; pol < 2; ++pol) {
+        const double half = 0.5 * delta;
+        /* the weight falls when lr delta > 0: then the positive device falls and the negative one rises */
+        const double change = (pol == 0 ? -1.0 : 1.0) * (double)lr * half;
+        double written = half;
+        if (cfg->flags & XO_UPD_NL) {
+          const double x = clampd(state[pol], 0.0, 1.0);
+          if (change > 0.0) written = half * exp(-(double)cfg->upd_nl_v * x);
+          else if (change < 0.0) written = half * exp(-(double)cfg->upd_nl_v * (1.0 - x));
+        }
+        if (cfg->flags & XO_UPD_NOISE)
+          written += (double)cfg->upd_noise_gamma * sqrt(fabs(half)) *
+                     xo_normal(cfg->seed, XO_STREAM_WRITE_PAIR, step, 2 * (uint64_t)at + (uint64_t)pol);
+        state[pol] = clampd(state[pol] + (pol == 0 ? -1.0 : 1.0) * (double)lr * written, 0.0, 1.0);
+      }
+      Gp[at] = (float)state[0];
+      Gn[at] = (float)state[1];
+      W[at] = (float)((double)w_max * ((double)Gp[at] - (double)Gn[at]));
+    }
+  return 0;
+}
+
+/* ------------------------------------------------------------------------------------------- */
 /* Pulse-level update (Sec. IV-C names the parallel update schemes whose result the aggregate    */
 /* model above describes; this is the stochastic bit-stream scheme of its reference [ibm_RPU]):  */
 /* every sample m applies its inputs to the rows and its errors to the columns as random pulse  */
@@ -562,6 +619,16 @@ int xo_update(const xo_config* cfg, float* W, const float* X, const float* dY, i
 /* in the first nd = rne(p_d Td) sub-slots of every frame (pulse count per frame codes |d|): the     */
 /* device sees exactly nx nd coincidences, the product of the two coded values.  Everything else    */
 /* (pulse size, device model, order) as above, with Tx Td in place of bl in the learning rate.       */
+/*                                                                                                   */
+/* XO_PULSE_MAGNITUDE: values coded in the magnitude of ONE pulse per sample (the other coding the   */
+/* passage names).  Reading: a row carries a pulse of height lx = rne(p_x bl) out of bl levels, a     */
+/* column one of height ld = rne(p_d bl); the device answers the product of the two heights: one      */
+/* write of lx ld quanta of dw_min (a full-scale pair writes bl^2 dw_min, so bl^2 takes the place of  */
+/* bl in the learning rate), against the sign of x d.  It is ONE write: the non-linearity is          */
+/* evaluated once, at the state the write finds, and scales all of it; the noise is one draw with     */
+/* the standard deviation the aggregate model gives a change of that size, gamma sqrt(lr lx ld        */
+/* dw_min) (normal number m * 32 of the device's stream); one clamp.  The reported pulse count of a    */
+/* device is its signed number of quanta.                                                              */
 /* ------------------------------------------------------------------------------------------- */
 void xo_pulse_frames(int bl, int* tx, int* td) {
   int t = 1;
@@ -612,12 +679,15 @@ int xo_update_pulsed_at(const xo_config* cfg, float* W, const float* X, const fl
   for (size_t i = 0; i < (size_t)K * N; ++i) g[i] = (double)W[i] / (double)w_max;
   if (pulses_out) memset(pulses_out, 0, sizeof(int64_t) * (size_t)K * N);
   const int coded = (cfg->flags & XO_PULSE_CODED) != 0;
+  const int magnitude = (cfg->flags & XO_PULSE_MAGNITUDE) != 0;
+  if (coded && magnitude) { free(g); free(a); return -1; }
   int slots = bl;
   if (coded) {
     int tx, td;
     xo_pulse_frames(bl, &tx, &td);
     slots = tx * td;
   }
+  if (magnitude) slots = bl * bl;
   const double lr_eq = (double)slots * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
   const double sigma = (double)cfg->upd_noise_gamma * sqrt(lr_eq * (double)dw_min);
   for (int m = 0; m < M; ++m) {
@@ -625,6 +695,8 @@ int xo_update_pulsed_at(const xo_config* cfg, float* W, const float* X, const fl
     for (int k = 0; k < K; ++k) {
       const double x = (double)X[(size_t)m * K + k];
       const uint64_t kf = k_idx ? (uint64_t)k_idx[k] : (uint64_t)k;
+      if (magnitude) a[k] = (uint32_t)rint(clampd(fabs(x) / (double)x_range, 0.0, 1.0) * (double)bl) | (x < 0.0 ? 0x80000000u : 0u);
+      else
       a[k] = (coded ? xo_pulse_code(fabs(x) / (double)x_range, bl, 0)
                     : xo_pulse_train(cfg->seed, XO_STREAM_PULSE_ROWS, step, (uint64_t)m * K_full + kf, fabs(x) / (double)x_range, bl)) |
              (x < 0.0 ? 0x80000000u : 0u);
@@ -632,19 +704,36 @@ int xo_update_pulsed_at(const xo_config* cfg, float* W, const float* X, const fl
     for (int n = 0; n < N; ++n) {
       const double d = (double)dY[(size_t)m * N + n];
       const uint64_t nf = n_idx ? (uint64_t)n_idx[n] : (uint64_t)n;
+      if (magnitude) b[n] = (uint32_t)rint(clampd(fabs(d) / (double)d_range, 0.0, 1.0) * (double)bl) | (d < 0.0 ? 0x80000000u : 0u);
+      else
       b[n] = (coded ? xo_pulse_code(fabs(d) / (double)d_range, bl, 1)
                     : xo_pulse_train(cfg->seed, XO_STREAM_PULSE_COLS, step, (uint64_t)m * N_full + nf, fabs(d) / (double)d_range, bl)) |
              (d < 0.0 ? 0x80000000u : 0u);
     }
     for (int k = 0; k < K; ++k)
       for (int n = 0; n < N; ++n) {
+        const double dir = ((a[k] ^ b[n]) & 0x80000000u) ? 1.0 : -1.0;   /* against the sign of x d */
+        const uint64_t dev = (k_idx ? (uint64_t)k_idx[k] : (uint64_t)k) * (uint64_t)N_full + (n_idx ? (uint64_t)n_idx[n] : (uint64_t)n);
+        double* gs = &g[(size_t)k * N + n];
+        if (magnitude) {                                                  /* one write of lx ld quanta */
+          const int quanta = (int)(a[k] & 0x7FFFFFFFu) * (int)(b[n] & 0x7FFFFFFFu);
+          if (!quanta) continue;
+          double move = (double)dw_min * (double)quanta;
+          if (cfg->flags & XO_UPD_NL) {
+            const double x = clampd(0.5 * (*gs + 1.0), 0.0, 1.0);
+            move *= dir > 0.0 ? exp(-(double)cfg->upd_nl_v * x) : exp(-(double)cfg->upd_nl_v * (1.0 - x));
+          }
+          double next = *gs + dir * move;
+          if (cfg->flags & XO_UPD_NOISE)
+            next += sigma * sqrt((double)quanta) * xo_normal(cfg->seed, XO_STREAM_PULSE_NOISE, (step << 31) | dev, (uint64_t)m * 32);
+          *gs = clampd(next, -1.0, 1.0);
+          if (pulses_out) pulses_out[(size_t)k * N + n] += (dir > 0.0 ? 1 : -1) * quanta;
+          continue;
+        }
         const uint32_t both = a[k] & b[n] & 0x7FFFFFFFu;
         if (!both) continue;
         int count = 0;
         for (uint32_t v = both; v; v &= v - 1) ++count;
-        const double dir = ((a[k] ^ b[n]) & 0x80000000u) ? 1.0 : -1.0;   /* against the sign of x d */
-        const uint64_t dev = (k_idx ? (uint64_t)k_idx[k] : (uint64_t)k) * (uint64_t)N_full + (n_idx ? (uint64_t)n_idx[n] : (uint64_t)n);
-        double* gs = &g[(size_t)k * N + n];
         for (int j = 0; j < count; ++j) {
           double move = (double)dw_min;
           if (cfg->flags & XO_UPD_NL) {

@@ -13,6 +13,7 @@ from . import build as _build
 
 INPUT_OFFSET = 1024
 PULSE_CODED = 2048
+PULSE_MAGNITUDE = 4096
 VARIATION, WIRE_AAM, WIRE_PROFILE, UPD_NL, UPD_NOISE, DAC_LUT, INPUT_SIGNED, WIRE_AAM2, ADC_CURVE, ADC_PER_ARRAY = (
     1, 2, 4, 8, 16, 32, 64, 128, 256, 512)
 STREAM_VARIATION, STREAM_WRITE = 1, 2
@@ -282,7 +283,8 @@ def pulse_frames(bl):
 
 def update_pulsed(cfg, W, X, dY, w_max, x_range, d_range, bl, dw_min, step=0, want_pulses=False, k_idx=None, n_idx=None,
                   K_full=None, N_full=None):
-    """Pulse-level update, one sample at a time (stochastic trains, or deterministic codes with PULSE_CODED):
+    """Pulse-level update, one sample at a time (stochastic trains, deterministic time codes with PULSE_CODED, or
+    one pulse per sample whose height codes the value with PULSE_MAGNITUDE):
     returns the updated copy of W (and the signed number of pulses every device received, if asked).  With k_idx /
     n_idx the arguments are the devices at those rows / columns of a K_full x N_full layer."""
     W = _f32(W).copy()
@@ -317,6 +319,29 @@ def update(cfg, W, X, dY, w_max, grad_scale, lr, step=0, k_idx=None, n_idx=None,
                          C.c_float(grad_scale), C.c_float(lr), C.c_uint64(step), _p(grad, C.c_double))
     assert rc == 0
     return (W, grad) if want_grad else W
+
+
+def pair_init(W, w_max):
+    """Positive / negative device states of a weight matrix, placed symmetrically about mid-range."""
+    W = _f32(W)
+    Gp, Gn = np.empty_like(W), np.empty_like(W)
+    lib().xo_pair_init(_p(W, C.c_float), _p(Gp, C.c_float), _p(Gn, C.c_float), C.c_size_t(W.size), C.c_float(w_max))
+    return Gp, Gn
+
+
+def update_pair(cfg, Gp, Gn, X, dY, w_max, grad_scale, lr, step=0):
+    """Update with per-polarity device state: returns the updated copies (Gp, Gn, W = w_max (Gp - Gn))."""
+    Gp, Gn = _f32(Gp).copy(), _f32(Gn).copy()
+    X, dY = _f32(X), _f32(dY)
+    K, N = Gp.shape
+    M = X.shape[0]
+    assert Gn.shape == (K, N) and X.shape == (M, K) and dY.shape == (M, N)
+    W = np.empty((K, N), dtype=np.float32)
+    rc = lib().xo_update_pair(C.byref(cfg), _p(Gp, C.c_float), _p(Gn, C.c_float), _p(W, C.c_float), _p(X, C.c_float),
+                              _p(dY, C.c_float), M, K, N, C.c_float(w_max), C.c_float(grad_scale), C.c_float(lr),
+                              C.c_uint64(step))
+    assert rc == 0
+    return Gp, Gn, W
 
 
 def rows_parallel(fn, U, X, threads):

@@ -1092,3 +1092,129 @@ def test_pulsed_update_device_model(xo):
     assert abs(Wp.mean() - bl * dw) < 5 * Wp.std() / K and abs(Wa.mean() - bl * dw) < 5 * Wa.std() / K
     assert abs(Wp.std() / Wa.std() - 1) < 0.06
     assert abs(Wa.std() / (g5 * np.sqrt(lr_eq * bl * dw)) - 1) < 0.06
+
+
+def test_magnitude_coded_pulses(xo):
+    """One pulse per sample whose height codes the value: the device writes lx ld quanta in ONE write."""
+    rng = np.random.default_rng(31)
+    M, K, N, bl, dw = 6, 5, 4, 7, 2.0 ** -14
+    X = (rng.integers(-bl, bl + 1, size=(M, K)) / bl * 2.0).astype(np.float32)          # on the level grid, x_range 2
+    D = (rng.integers(-bl, bl + 1, size=(M, N)) / bl * 0.5).astype(np.float32)          # d_range 0.5
+    W0 = rng.uniform(-0.3, 0.3, size=(K, N)).astype(np.float32)
+    cfg = xo.make_config(flags=xo.PULSE_MAGNITUDE, seed=3)
+    W1, quanta = xo.update_pulsed(cfg, W0, X, D, 1.5, 2.0, 0.5, bl, dw, step=1, want_pulses=True)
+    lx = np.rint(X.astype(np.float64) / 2.0 * bl).astype(np.int64)
+    ld = np.rint(D.astype(np.float64) / 0.5 * bl).astype(np.int64)
+    # quanta = product of the two heights, against the sign of x d, summed over the samples
+    assert np.array_equal(quanta, -(lx.T @ ld)) and np.abs(quanta).max() > 20
+    # linear noise-free device: the quanta are all that is written, and that is the aggregate outer-product
+    # update at the learning rate bl^2 dw_min w_max / (x_range d_range)
+    assert np.array_equal(W1, (W0.astype(np.float64) + 1.5 * dw * quanta).astype(np.float32))
+    lr = bl * bl * dw * 1.5 / (2.0 * 0.5)
+    assert np.abs(W1.astype(np.float64) - xo.update(xo.make_config(), W0, X, D, 1.5, 1.0 / 1.5, lr)).max() < 1e-6
+    # the same heights as frames x sub-slots of the time-coded scheme (5 x 5 of 25 slots) give the same counts
+    Xc = (rng.integers(-5, 6, size=(M, K)) / 5 * 2.0).astype(np.float32)
+    Dc = (rng.integers(-5, 6, size=(M, N)) / 5 * 0.5).astype(np.float32)
+    _, q_mag = xo.update_pulsed(cfg, W0, Xc, Dc, 1.5, 2.0, 0.5, 5, dw, want_pulses=True)
+    _, q_time = xo.update_pulsed(xo.make_config(flags=xo.PULSE_CODED), W0, Xc, Dc, 1.5, 2.0, 0.5, 25, dw, want_pulses=True)
+    assert np.array_equal(q_mag, q_time)
+    # off the grid the heights round to the nearest level (ties to even), beyond the range they saturate;
+    # seed and step do not enter a noise-free write
+    x, d = np.array([[0.93], [5.0], [0.1]], np.float32), np.array([[0.31], [-0.2], [0.01]], np.float32)
+    _, q = xo.update_pulsed(xo.make_config(flags=xo.PULSE_MAGNITUDE, seed=77), np.zeros((1, 1), np.float32), x, d, 1.0, 2.0, 0.5,
+                            bl, dw, step=9, want_pulses=True)
+    want = -(int(np.rint(0.93 / 2 * 7)) * int(np.rint(0.31 / 0.5 * 7))) + 7 * int(np.rint(0.2 / 0.5 * 7)) - 0
+    assert q[0, 0] == want
+    # non-linear device: ONE evaluation of the non-linearity per write, at the state the write finds
+    v = 0.8
+    cn = xo.make_config(flags=xo.PULSE_MAGNITUDE | xo.UPD_NL, upd_nl_v=v)
+    g0, w_max = 0.25, 2.0
+    Wn = xo.update_pulsed(cn, np.array([[g0 * w_max]], np.float32), np.array([[2.0], [-2.0]], np.float32),
+                          np.array([[-0.5], [-0.25]], np.float32), w_max, 2.0, 0.5, 4, 2.0 ** -8)
+    g1 = g0 + 16 * 2.0 ** -8 * np.exp(-np.float64(np.float32(v)) * 0.5 * (g0 + 1))                      # up by 4 x 4 quanta
+    g2 = g1 - 8 * 2.0 ** -8 * np.exp(-np.float64(np.float32(v)) * (1 - 0.5 * (g1 + 1)))                 # down by 4 x 2
+    assert Wn[0, 0] == np.float32(w_max * g2)
+    # a time-coded write of the same size evaluates the non-linearity pulse by pulse: not the same number
+    Wt = xo.update_pulsed(xo.make_config(flags=xo.PULSE_CODED | xo.UPD_NL, upd_nl_v=v), np.array([[g0 * w_max]], np.float32),
+                          np.array([[2.0]], np.float32), np.array([[-0.5]], np.float32), w_max, 2.0, 0.5, 16, 2.0 ** -8)
+    Wm = xo.update_pulsed(cn, np.array([[g0 * w_max]], np.float32), np.array([[2.0]], np.float32),
+                          np.array([[-0.5]], np.float32), w_max, 2.0, 0.5, 4, 2.0 ** -8)
+    assert Wt[0, 0] != Wm[0, 0] and abs(float(Wt[0, 0]) - float(Wm[0, 0])) < 1e-2
+    # write noise: one draw per write (normal number m * 32 of the device's stream), standard deviation
+    # gamma sqrt(lr quanta dw_min) with lr = bl^2 dw_min w_max / (x_range d_range)
+    gam = 0.6
+    cz = xo.make_config(flags=xo.PULSE_MAGNITUDE | xo.UPD_NOISE, upd_noise_gamma=gam, seed=21)
+    Wz = xo.update_pulsed(cz, np.zeros((1, 1), np.float32), np.array([[0.0], [1.0]], np.float32), np.array([[0.3], [-0.25]], np.float32),
+                          4.0, 2.0, 0.5, 6, dw, step=6)
+    quanta_1 = 3 * 3
+    lr_eq = 36 * dw * 4.0 / (2.0 * 0.5)
+    g = quanta_1 * dw + np.float64(np.float32(gam)) * np.sqrt(lr_eq * dw) * np.sqrt(quanta_1) * xo.normal(21, 5, 6 << 31, 1 * 32)
+    assert Wz[0, 0] == np.float32(4.0 * g)
+    # time-coded and magnitude-coded pulses exclude each other
+    with pytest.raises(AssertionError):
+        xo.update_pulsed(xo.make_config(flags=xo.PULSE_MAGNITUDE | xo.PULSE_CODED), W0, X, D, 1.5, 2.0, 0.5, bl, dw)
+
+
+def test_pair_update(xo):
+    """Update with the two devices of a weight as states of their own."""
+    rng = np.random.default_rng(5)
+    M, K, N, w_max, lr = 9, 6, 7, 1.5, 0.05
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    D = (rng.standard_normal((M, N)) * 0.1).astype(np.float32)
+    W0 = rng.uniform(-0.8, 0.8, size=(K, N)).astype(np.float32)
+    Gp0, Gn0 = xo.pair_init(W0, w_max)
+    g = W0.astype(np.float64) / w_max
+    assert np.array_equal(Gp0, (0.5 * (1 + g)).astype(np.float32)) and np.array_equal(Gn0, (0.5 * (1 - g)).astype(np.float32))
+    # ideal devices: the pair's difference moves exactly as the one effective device of the aggregate model
+    ideal = xo.make_config(flags=0)
+    Gp, Gn, W1 = xo.update_pair(ideal, Gp0, Gn0, X, D, w_max, 1.0 / w_max, lr, step=2)
+    assert np.array_equal(W1, (w_max * (Gp.astype(np.float64) - Gn)).astype(np.float32))            # W is the stored pair's difference
+    assert np.abs(W1.astype(np.float64) - xo.update(ideal, W0, X, D, w_max, 1.0 / w_max, lr)).max() < 3e-7 * w_max
+    grad = X.astype(np.float64).T @ D.astype(np.float64)
+    assert np.allclose(Gp.astype(np.float64) - Gp0, -lr * 0.5 * grad / w_max, atol=1e-7)             # half the change each,
+    assert np.allclose(Gn.astype(np.float64) - Gn0, +lr * 0.5 * grad / w_max, atol=1e-7)             # in opposite directions
+    # every device clamps on its own
+    gp = np.array([[0.99, 0.99, 0.5]], np.float32)
+    gn = np.array([[0.01, 0.50, 0.02]], np.float32)
+    x, d = np.array([[1.0]], np.float32), np.array([[-1.0, -1.0, 1.0]], np.float32)                 # delta = -1, -1, +1; lr 0.1
+    Cp, Cn, Cw = xo.update_pair(ideal, gp, gn, x, d, 2.0, 1.0, 0.1)
+    assert np.allclose(Cp, [[1.0, 1.0, 0.45]], atol=1e-7) and np.allclose(Cn, [[0.0, 0.45, 0.07]], atol=1e-7)
+    assert np.allclose(Cw, 2.0 * (Cp.astype(np.float64) - Cn), atol=1e-6)
+    assert Cp[0, 0] == 1.0 and Cn[0, 0] == 0.0
+    # write non-linearity: each device at its own state and direction (rising exp(-v g), falling exp(-v (1 - g)))
+    v = 0.7
+    nl = xo.make_config(flags=xo.UPD_NL, upd_nl_v=v)
+    vf = np.float64(np.float32(v))
+    for delta in (0.4, -0.4):
+        Np, Nn, _ = xo.update_pair(nl, np.array([[0.3]], np.float32), np.array([[0.6]], np.float32), np.array([[1.0]], np.float32),
+                                   np.array([[delta]], np.float32), 1.0, 1.0, 0.5)
+        half = 0.5 * np.float64(np.float32(delta))
+        p0, n0 = np.float64(np.float32(0.3)), np.float64(np.float32(0.6))
+        if delta > 0:      # weight falls: positive device falls, negative device rises
+            want_p, want_n = p0 - 0.5 * half * np.exp(-vf * (1 - p0)), n0 + 0.5 * half * np.exp(-vf * n0)
+        else:
+            want_p, want_n = p0 - 0.5 * half * np.exp(-vf * p0), n0 + 0.5 * half * np.exp(-vf * (1 - n0))
+        assert Np[0, 0] == np.float32(want_p) and Nn[0, 0] == np.float32(want_n)
+    # mirror symmetry: swapping the two devices and the sign of the change swaps the results
+    Ap, An, _ = xo.update_pair(nl, np.array([[0.3]], np.float32), np.array([[0.6]], np.float32), np.array([[1.0]], np.float32),
+                               np.array([[0.4]], np.float32), 1.0, 1.0, 0.5)
+    Bp, Bn, _ = xo.update_pair(nl, np.array([[0.6]], np.float32), np.array([[0.3]], np.float32), np.array([[1.0]], np.float32),
+                               np.array([[-0.4]], np.float32), 1.0, 1.0, 0.5)
+    assert Ap[0, 0] == Bn[0, 0] and An[0, 0] == Bp[0, 0]
+    # write noise: a draw per device (numbers 2 i and 2 i + 1 of stream 6), sigma = gamma sqrt(|delta| / 2) each,
+    # so the weight's noise variance is that of the effective device, gamma^2 |delta|
+    gam, n_dev = 0.5, 40000
+    nz = xo.make_config(flags=xo.UPD_NOISE, upd_noise_gamma=gam, seed=17)
+    half_state = np.full((1, n_dev), 0.5, np.float32)
+    delta = 0.02
+    Zp, Zn, Zw = xo.update_pair(nz, half_state, half_state, np.array([[1.0]], np.float32), np.full((1, n_dev), delta, np.float32),
+                                1.0, 1.0, 0.1, step=4)
+    dp = Zp.astype(np.float64) - 0.5 + 0.1 * 0.5 * np.float64(np.float32(delta))
+    dn = Zn.astype(np.float64) - 0.5 - 0.1 * 0.5 * np.float64(np.float32(delta))
+    sigma = 0.1 * gam * np.sqrt(delta / 2)
+    assert abs(dp.std() / sigma - 1) < 0.02 and abs(dn.std() / sigma - 1) < 0.02 and abs(dp.mean()) < 4 * sigma / np.sqrt(n_dev)
+    assert abs(np.corrcoef(dp.ravel(), dn.ravel())[0, 1]) < 0.02
+    assert abs((Zw.astype(np.float64)).std() / (0.1 * gam * np.sqrt(delta)) - 1) < 0.02
+    want0 = 0.5 - 0.1 * (0.5 * np.float64(np.float32(delta)) + np.float64(np.float32(gam)) * np.sqrt(0.5 * np.float64(np.float32(delta))) * xo.normal(17, 6, 4, 0))
+    want1 = 0.5 + 0.1 * (0.5 * np.float64(np.float32(delta)) + np.float64(np.float32(gam)) * np.sqrt(0.5 * np.float64(np.float32(delta))) * xo.normal(17, 6, 4, 2 * 3 + 1))
+    assert Zp[0, 0] == np.float32(want0) and Zn[0, 3] == np.float32(want1)
