@@ -79,6 +79,16 @@ extern "C" {
                                      place of bl in the learning rate.  seed and step then only key the
                                      write noise                                                        */
 
+#define XBAR_PULSE_MAGNITUDE 4096u /* pulse-level updates use ONE pulse per sample and line whose height codes the value
+                                     (the other coding Sec. IV-C names): a row carries a pulse of height
+                                     lx = rne(p_x bl) out of bl levels, a column one of height ld = rne(p_d bl), and the
+                                     device answers the product of the two heights with one write of lx ld quanta of
+                                     dw_min; bl^2 takes the place of bl in the learning rate.  The non-linearity is
+                                     evaluated once per write, at the state it finds; the noise is one draw of standard
+                                     deviation gamma sqrt(lr lx ld dw_min) (normal number m 32 of the device's stream).
+                                     The reported pulse count is the signed number of quanta.  Not with
+                                     XBAR_PULSE_CODED                                                     */
+
 /* status codes */
 #define XBAR_OK          0
 #define XBAR_EINVAL     -1   /* bad parameter struct (sizes, bit widths, NaN/negative physical values) */
@@ -109,7 +119,7 @@ typedef struct xbar_config {
   int32_t stream_bits;    /* bits per DAC cycle, divides input_bits              paper: 1             */
   int32_t adc_bits;       /* 2..16, signed mid-tread converter with Q = 2^(adc_bits-1) - 1 codes/side */
   uint32_t flags;         /* XBAR_NI_* | XBAR_DAC_LUT | XBAR_ADC_CURVE | XBAR_INPUT_SIGNED |          */
-                          /*   XBAR_ADC_PER_ARRAY | XBAR_INPUT_OFFSET | XBAR_PULSE_CODED              */
+                          /*   XBAR_ADC_PER_ARRAY | XBAR_INPUT_OFFSET | XBAR_PULSE_CODED | XBAR_PULSE_MAGNITUDE */
   float r_min, r_max;     /* device resistance range in Ohm                      paper: 1e5, 1e6      */
   float v_max;            /* input voltage range in V (results do not depend on it) paper: 1          */
   float r_row, r_col;     /* wire resistance per cell in Ohm                     paper: 1, 4.6        */
@@ -221,6 +231,25 @@ int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* d
                 void* hip_stream);
 
 /*
+ * Weight update with per-polarity device state (variant of xbar_update; Sec. IV-A keeps the positive and the
+ * negative conductances of the weights in two arrays, Sec. IV-C writes one conductance per weight): the two
+ * devices of a weight are states of their own, Gp[K][N] and Gn[K][N] in [0, 1] (units of Gmax - Gmin above
+ * Gmin), W = w_max (Gp - Gn).  The ideal change delta (as in xbar_update) is split evenly and applied in
+ * opposite directions: gp <- clamp(gp - lr w_p, 0, 1), gn <- clamp(gn + lr w_n, 0, 1), where each device sees
+ * delta / 2, scaled by the write non-linearity at ITS OWN state and direction (exp(-v g) rising,
+ * exp(-v (1 - g)) falling) plus gamma sqrt(|delta| / 2) times normal number 2 (k N + n) + pol (pol 0 =
+ * positive device) of stream 6 of `step`.  Gp, Gn in place; W receives w_max (Gp - Gn) for xbar_tile.
+ * With v = gamma = 0 and no device at a rail the weights move exactly as under xbar_update.
+ * xbar_pair_init places a weight symmetrically about mid-range: gp = (1 + g) / 2, gn = (1 - g) / 2,
+ * g = clamp(W / w_max, -1, 1).  Workspace: xbar_workspace_bytes(cfg, XBAR_OP_UPDATE, ...) (convolution:
+ * xbar_conv_workspace_bytes).
+ */
+int xbar_pair_init(const float* W, float* Gp, float* Gn, int K, int N, float w_max, void* hip_stream);
+int xbar_update_pair(const xbar_config* cfg, float* Gp, float* Gn, float* W, const float* X, const float* dY, int M,
+                     int K, int N, float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes,
+                     void* hip_stream);
+
+/*
  * Pulse-level weight update (Sec. IV-C names the parallel update schemes whose result xbar_update
  * models in one aggregate write; this is the scheme with stochastic pulse trains): W[K][N] in place,
  * one sample at a time and one pulse at a time, the gradient is never formed.
@@ -276,6 +305,9 @@ int xbar_conv_bwd(const xbar_config* cfg, const void* planes, const float* dY, f
 int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const float* dY, const xbar_conv_geom* geom,
                      int N, float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes,
                      void* hip_stream);
+int xbar_conv_update_pair(const xbar_config* cfg, float* Gp, float* Gn, float* W, const float* X, const float* dY,
+                          const xbar_conv_geom* geom, int N, float w_max, float grad_scale, float lr, uint64_t step,
+                          void* ws, size_t ws_bytes, void* hip_stream);   /* as xbar_update_pair on the patch matrix */
 int xbar_conv_update_pulsed(const xbar_config* cfg, float* W, const float* X, const float* dY,
                             const xbar_conv_geom* geom, int N, float w_max, float x_range, float d_range, int bl,
                             float dw_min, uint64_t step, long long* pulses, void* ws, size_t ws_bytes,

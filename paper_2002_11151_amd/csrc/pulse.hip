@@ -41,7 +41,7 @@ struct PulseArgs {
   const unsigned long long* step_add;   // optional device counter added to step
   ConvGeom conv;                        // convolution layer: X is the NHWC image and row m of the layer's
                                         //   input matrix is gathered from it (CONV variant of the train kernel)
-  int coded, tx, td;                    // deterministic pulse coding: tx frames of td sub-slots
+  int coded, tx, td;                    // 1: deterministic time coding, tx frames of td sub-slots; 2: magnitude coding
   unsigned long long* marks;            // two-phase walk: [n_words][K N] one bit per sample and device
   unsigned long long* summary;          //   [ceil(n_words / 64)][K N] one bit per word that is not empty
   int n_words;                          //   64-sample words of the current chunk
@@ -72,6 +72,13 @@ __device__ __forceinline__ uint32_t pulse_code(double p, int tx, int td, bool is
   return bits;
 }
 
+// Magnitude coding: ONE pulse per sample whose height is the level rne(p bl) of bl; bit 30 marks a pulse that
+// is there at all, so that "row and column share a set bit" still means "this device is written".
+__device__ __forceinline__ uint32_t pulse_height(double p, int bl) {
+  const uint32_t level = (uint32_t)::rint(clampd(p, 0.0, 1.0) * (double)bl);
+  return level ? (level | 0x40000000u) : 0u;
+}
+
 // One thread per element of the chunk's inputs, then of its errors.
 template <bool CONV>
 __global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
@@ -89,8 +96,9 @@ __global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
     }
     const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseRows);
     const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseRows);
-    const uint32_t train = a.coded ? pulse_code(::fabs(x) / a.x_range, a.tx, a.td, false)
-                                   : pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(x) / a.x_range, a.bl);
+    const uint32_t train = a.coded == 2 ? pulse_height(::fabs(x) / a.x_range, a.bl)
+                           : a.coded  ? pulse_code(::fabs(x) / a.x_range, a.tx, a.td, false)
+                                      : pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(x) / a.x_range, a.bl);
     a.rows[t] = train | (x < 0.0 ? 0x80000000u : 0u);
   } else if (t < n_rows + n_cols) {
     const long long u = t - n_rows;
@@ -98,8 +106,9 @@ __global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
     const double d = (double)a.D[index];
     const uint32_t k0 = (uint32_t)a.seed ^ (0x9E3779B9u * kStreamPulseCols);
     const uint32_t k1 = (uint32_t)(a.seed >> 32) ^ (0xBB67AE85u * kStreamPulseCols);
-    const uint32_t train = a.coded ? pulse_code(::fabs(d) / a.d_range, a.tx, a.td, true)
-                                   : pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(d) / a.d_range, a.bl);
+    const uint32_t train = a.coded == 2 ? pulse_height(::fabs(d) / a.d_range, a.bl)
+                           : a.coded  ? pulse_code(::fabs(d) / a.d_range, a.tx, a.td, true)
+                                      : pulse_train(k0, k1, effective_step(a.step, a.step_add), index, ::fabs(d) / a.d_range, a.bl);
     a.cols[u] = train | (d < 0.0 ? 0x80000000u : 0u);
   }
 }
@@ -107,11 +116,13 @@ __global__ __launch_bounds__(256) void pulse_trains_kernel(PulseArgs a) {
 // One pulse of device `dev` (ordinal `ord` within sample m), upwards when `up`.  The device model is
 // chosen at compile time, and the step of the noise stream is read before the walk: nothing that is the
 // same for all lanes is tested (and no pointer that may be null is followed) inside the per-lane walk.
-template <bool NL, bool NOISE>
+// `units`: quanta of dw_min that this one write carries (1 for a pulse of a train; the product of the two pulse
+// heights with magnitude coding, where the non-linearity and the noise belong to the write as a whole).
+template <bool NL, bool NOISE, bool MAG = false>
 __device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool up, int m, int ord, uint64_t dev,
-                                            uint64_t step) {
+                                            uint64_t step, int units = 1) {
 #pragma clang fp contract(off)   // every product and sum rounds on its own
-  double move = a.dw_min;
+  double move = MAG ? a.dw_min * (double)units : a.dw_min;
   if constexpr (NL) {
     const double x = clampd(0.5 * (g + 1.0), 0.0, 1.0);
     move *= up ? ::exp(-a.v * x) : ::exp(-a.v * (1.0 - x));
@@ -119,7 +130,8 @@ __device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool u
   double next = g + (up ? 1.0 : -1.0) * move;
   if constexpr (NOISE) {
     NormalStream rng(a.seed, kStreamPulseNoise, (step << 31) | dev);
-    next += a.sigma * rng.get((uint64_t)m * 32 + (uint64_t)ord);
+    if constexpr (MAG) next += a.sigma * ::sqrt((double)units) * rng.get((uint64_t)m * 32 + (uint64_t)ord);
+    else next += a.sigma * rng.get((uint64_t)m * 32 + (uint64_t)ord);
   }
   return clampd(next, -1.0, 1.0);
 }
@@ -134,7 +146,7 @@ __device__ __forceinline__ double one_pulse(const PulseArgs& a, double g, bool u
 // samples of the busiest device of each.
 // MARKED: the marks come from pulse_mark_kernel (layers with few devices: that pass fills the chip, this
 // one cannot) instead of being worked out here, stage by stage.
-template <int P, bool NL, bool NOISE, bool MARKED = false>
+template <int P, bool NL, bool NOISE, bool MARKED = false, bool MAG = false>
 __global__ __launch_bounds__(256) void pulse_apply_kernel(PulseArgs a) {
   constexpr int TE = 16 * P;              // tile edge
   constexpr int ST = 4096 / TE;           // samples per stage (a multiple of 16)
@@ -216,7 +228,7 @@ __global__ __launch_bounds__(256) void pulse_apply_kernel(PulseArgs a) {
         // sample in order
         uint32_t q = 0;
         bool up = false;
-        int m = 0, ord = 0;
+        int m = 0, ord = 0, units = 1;
         for (;;) {
           if (q == 0) {
             int w = -1;
@@ -235,14 +247,18 @@ __global__ __launch_bounds__(256) void pulse_apply_kernel(PulseArgs a) {
             const int at = 64 * w + e;
             const uint32_t rw = rp[at], cw = cp[at];
             q = rw & cw & 0x7FFFFFFFu;
+            if constexpr (MAG) {                        // one write of (row height) x (column height) quanta
+              units = (int)(rw & 31u) * (int)(cw & 31u);
+              q = 1u;
+            }
             up = ((rw ^ cw) >> 31) != 0;               // against the sign of x d
             m = a.m0 + s0 + at;
             ord = 0;
           }
           q &= q - 1;
-          gs = one_pulse<NL, NOISE>(a, gs, up, m, ord, dev, step);
+          gs = one_pulse<NL, NOISE, MAG>(a, gs, up, m, ord, dev, step, units);
           ++ord;
-          moved += up ? 1 : -1;
+          moved += up ? units : -units;
         }
         g[i][j] = gs;
         cnt[i][j] += moved;
@@ -428,9 +444,9 @@ int run_update_pulsed(const xbar_config* cfg, float* W, const float* X, const fl
   a.v = (double)cfg->upd_nl_v;
   // the aggregate model's noise for one pulse: its standard deviation gamma sqrt(dG) belongs to the ideal change
   // before the learning rate, and this scheme's mean equals the aggregate update at lr = bl dw_min w_max / (x_range d_range)
-  a.coded = (cfg->flags & XBAR_PULSE_CODED) ? 1 : 0;
+  a.coded = (cfg->flags & XBAR_PULSE_CODED) ? 1 : (cfg->flags & XBAR_PULSE_MAGNITUDE) ? 2 : 0;
   coded_frames(bl, &a.tx, &a.td);
-  const int slots = a.coded ? a.tx * a.td : bl;
+  const int slots = a.coded == 1 ? a.tx * a.td : a.coded == 2 ? bl * bl : bl;
   const double lr_eq = (double)slots * (double)dw_min * (double)w_max / ((double)x_range * (double)d_range);
   a.sigma = (double)cfg->upd_noise_gamma * std::sqrt(lr_eq * (double)dw_min);
   a.seed = cfg->seed; a.step = step; a.step_add = current_step_source();
@@ -449,6 +465,20 @@ int run_update_pulsed(const xbar_config* cfg, float* W, const float* X, const fl
     else hipLaunchKernelGGL(pulse_trains_kernel<false>, dim3((unsigned)((elems + 255) / 256)), dim3(256), 0, st, a);
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
     const bool nl = (cfg->flags & XBAR_NI_UPD_NL) != 0, noise = (cfg->flags & XBAR_NI_UPD_NOISE) != 0;
+    if (a.coded == 2) {
+      // magnitude coding: a device is written in every sample in which both of its lines carry a pulse, so
+      // there is little for a marking pass to skip; always the staged kernel
+      void (*k)(PulseArgs);
+      if (patch4)
+        k = nl ? (noise ? pulse_apply_kernel<4, true, true, false, true> : pulse_apply_kernel<4, true, false, false, true>)
+               : (noise ? pulse_apply_kernel<4, false, true, false, true> : pulse_apply_kernel<4, false, false, false, true>);
+      else
+        k = nl ? (noise ? pulse_apply_kernel<1, true, true, false, true> : pulse_apply_kernel<1, true, false, false, true>)
+               : (noise ? pulse_apply_kernel<1, false, true, false, true> : pulse_apply_kernel<1, false, false, false, true>);
+      hipLaunchKernelGGL(k, dim3(tiles), dim3(256), 0, st, a);
+      if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+      continue;
+    }
     if (p.two_phase) {
       a.n_words = cdiv(a.mc, 64);
       const unsigned tiles16 = (unsigned)(cdiv(K, 16) * cdiv(N, 16));
@@ -505,6 +535,7 @@ int xbar_pulse_slots(const xbar_config* cfg, int bl) {
   const int rc = xbar_config_validate(cfg);
   if (rc) return rc;
   if (bl < 1 || bl > 31) return XBAR_EINVAL;
+  if (cfg->flags & XBAR_PULSE_MAGNITUDE) return bl * bl;
   if (!(cfg->flags & XBAR_PULSE_CODED)) return bl;
   int tx, td;
   coded_frames(bl, &tx, &td);

@@ -577,6 +577,8 @@ __global__ __launch_bounds__(256) void col2im_kernel(Col2imArgs a) {
 
 struct WriteArgs {
   float* W;
+  float* Gp;        // per-polarity device state (update_pair_write_kernel): positive device, in [0, 1]
+  float* Gn;        //   negative device
   const float* part;
   long long n;      // K * N
   int mchunks;
@@ -619,6 +621,63 @@ __global__ __launch_bounds__(256) void update_write_kernel(WriteArgs a) {
 }
 
 
+
+// The same write with the two devices of a weight as states of their own (a variant of Sec. IV-C's one
+// conductance per weight; Sec. IV-A keeps positive and negative conductances in two arrays): half the ideal
+// change to each, in opposite directions, each with the non-linearity at its own state and direction, a noise
+// draw of its own (sigma = gamma sqrt(|delta| / 2), numbers 2 i and 2 i + 1 of the pair stream) and its own
+// clamp to [0, 1]; W = w_max (gp - gn).
+__global__ __launch_bounds__(256) void update_pair_write_kernel(WriteArgs a) {
+  __shared__ double red[8][32];
+  const int e = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const long long i = (long long)blockIdx.x * 32 + e;
+  double partial = 0.0;
+  if (i < a.n)
+    for (int c = grp; c < a.mchunks; c += 8) partial += (double)a.part[(size_t)c * a.n + i];
+  red[grp][e] = partial;
+  __syncthreads();
+  if (grp != 0 || i >= a.n) return;
+  double grad = 0.0;
+#pragma unroll
+  for (int g = 0; g < 8; ++g) grad += red[g][e];
+  const double half = 0.5 * (a.grad_scale * grad);
+  double state[2] = {(double)a.Gp[i], (double)a.Gn[i]};
+  NormalStream rng(a.seed, kStreamWritePair, effective_step(a.step, a.step_add));
+#pragma unroll
+  for (int pol = 0; pol < 2; ++pol) {
+    const double dir = pol == 0 ? -1.0 : 1.0;        // the positive device falls when the weight falls
+    const double change = dir * a.lr * half;
+    double written = half;
+    if (a.flags & XBAR_NI_UPD_NL) {
+      const double x = clampd(state[pol], 0.0, 1.0);
+      if (change > 0.0) written = half * ::exp(-a.v * x);
+      else if (change < 0.0) written = half * ::exp(-a.v * (1.0 - x));
+    }
+    if (a.flags & XBAR_NI_UPD_NOISE) written += a.gamma * ::sqrt(::fabs(half)) * rng.get(2 * (uint64_t)i + (uint64_t)pol);
+    state[pol] = clampd(state[pol] + dir * a.lr * written, 0.0, 1.0);
+  }
+  const float gp = (float)state[0], gn = (float)state[1];
+  a.Gp[i] = gp;
+  a.Gn[i] = gn;
+  a.W[i] = (float)(a.w_max * ((double)gp - (double)gn));
+}
+
+struct PairInitArgs {
+  const float* W;
+  float* Gp;
+  float* Gn;
+  long long n;
+  double w_max;
+};
+
+// A weight placed symmetrically about mid-range: gp = (1 + g) / 2, gn = (1 - g) / 2, g = clamp(W / w_max).
+__global__ __launch_bounds__(256) void pair_init_kernel(PairInitArgs a) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.n) return;
+  const double g = clampd((double)a.W[i] / a.w_max, -1.0, 1.0);
+  a.Gp[i] = (float)(0.5 * (1.0 + g));
+  a.Gn[i] = (float)(0.5 * (1.0 - g));
+}
 
 // ---------------------------------------------------------------------------------------------
 // instrumentation: sustained matrix-instruction rate
@@ -1012,11 +1071,13 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
 
 
 int run_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
-               float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream, const ConvGeom* conv) {
+               float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream, const ConvGeom* conv,
+               float* Gp = nullptr, float* Gn = nullptr) {
   int rc = xbar_config_validate(cfg);
   if (rc) return rc;
   if ((rc = check_shape(M, K, N))) return rc;
   if (!aligned16(W) || !aligned16(X) || !aligned16(dY) || !aligned16(ws)) return XBAR_EALIGN;
+  if ((Gp || Gn) && (!aligned16(Gp) || !aligned16(Gn))) return XBAR_EALIGN;
   if (!finite_pos(w_max) || !std::isfinite(grad_scale) || !std::isfinite(lr)) return XBAR_EINVAL;
   const UpdPlan p = plan_update(M, K, N);
   if (ws_bytes < p.ws_bytes) return XBAR_EWORKSPACE;
@@ -1041,11 +1102,12 @@ int run_update(const xbar_config* cfg, float* W, const float* X, const float* dY
   }
   if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   WriteArgs w;
-  w.W = W; w.part = g.part; w.n = (long long)K * N; w.mchunks = p.mchunks * p.parts; w.flags = cfg->flags;
+  w.W = W; w.Gp = Gp; w.Gn = Gn; w.part = g.part; w.n = (long long)K * N; w.mchunks = p.mchunks * p.parts; w.flags = cfg->flags;
   w.w_max = (double)w_max; w.grad_scale = (double)grad_scale; w.lr = (double)lr;
   w.v = (double)cfg->upd_nl_v; w.gamma = (double)cfg->upd_noise_gamma;
   w.seed = cfg->seed; w.step = step; w.step_add = current_step_source();
-  hipLaunchKernelGGL(update_write_kernel, dim3((unsigned)((w.n + 31) / 32)), dim3(256), 0, st, w);
+  if (Gp) hipLaunchKernelGGL(update_pair_write_kernel, dim3((unsigned)((w.n + 31) / 32)), dim3(256), 0, st, w);
+  else hipLaunchKernelGGL(update_write_kernel, dim3((unsigned)((w.n + 31) / 32)), dim3(256), 0, st, w);
   if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   return XBAR_OK;
 }
@@ -1172,7 +1234,8 @@ int xbar_config_validate(const xbar_config* c) {
   if (c->input_bits < 1 || c->input_bits > 8) return XBAR_EINVAL;
   if (c->stream_bits < 1 || c->stream_bits > c->input_bits || c->input_bits % c->stream_bits) return XBAR_EINVAL;
   if (c->adc_bits < 2 || c->adc_bits > 16) return XBAR_EINVAL;
-  if (c->flags & ~0xFFFu) return XBAR_EINVAL;
+  if (c->flags & ~0x1FFFu) return XBAR_EINVAL;
+  if ((c->flags & XBAR_PULSE_CODED) && (c->flags & XBAR_PULSE_MAGNITUDE)) return XBAR_EINVAL;   // one pulse coding
   if (c->flags & XBAR_ADC_PER_ARRAY) {
     if (c->flags & XBAR_ADC_CURVE) return XBAR_EINVAL;     // the curve is that of a signed converter
     if (c->adc_bits > 15) return XBAR_EINVAL;              // unsigned codes are reported as int16
@@ -1324,6 +1387,35 @@ int xbar_bwd(const xbar_config* cfg, const void* planes, const float* dY, float*
 int xbar_update(const xbar_config* cfg, float* W, const float* X, const float* dY, int M, int K, int N, float w_max,
                 float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream) {
   return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream, nullptr);
+}
+
+int xbar_pair_init(const float* W, float* Gp, float* Gn, int K, int N, float w_max, void* hip_stream) {
+  const int rc = check_shape(1, K, N);
+  if (rc) return rc;
+  if (!aligned16(W) || !aligned16(Gp) || !aligned16(Gn)) return XBAR_EALIGN;
+  if (!finite_pos(w_max)) return XBAR_EINVAL;
+  PairInitArgs a;
+  a.W = W; a.Gp = Gp; a.Gn = Gn; a.n = (long long)K * N; a.w_max = (double)w_max;
+  hipLaunchKernelGGL(pair_init_kernel, dim3((unsigned)((a.n + 255) / 256)), dim3(256), 0, reinterpret_cast<hipStream_t>(hip_stream), a);
+  return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
+}
+
+int xbar_update_pair(const xbar_config* cfg, float* Gp, float* Gn, float* W, const float* X, const float* dY, int M, int K,
+                     int N, float w_max, float grad_scale, float lr, uint64_t step, void* ws, size_t ws_bytes, void* hip_stream) {
+  if (!Gp || !Gn) return XBAR_EALIGN;
+  return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream, nullptr, Gp, Gn);
+}
+
+int xbar_conv_update_pair(const xbar_config* cfg, float* Gp, float* Gn, float* W, const float* X, const float* dY,
+                          const xbar_conv_geom* geom, int N, float w_max, float grad_scale, float lr, uint64_t step, void* ws,
+                          size_t ws_bytes, void* hip_stream) {
+  if (!Gp || !Gn) return XBAR_EALIGN;
+  ConvGeom g;
+  int M, K;
+  const int rc = conv_dims(geom, &g, &M, &K);
+  if (rc) return rc;
+  return run_update(cfg, W, X, dY, M, K, N, w_max, grad_scale, lr, step, ws, ws_bytes, hip_stream,
+                    conv_is_dense(geom) ? nullptr : &g, Gp, Gn);
 }
 
 size_t xbar_conv_workspace_bytes(const xbar_config* cfg, int op, const xbar_conv_geom* geom, int N) {

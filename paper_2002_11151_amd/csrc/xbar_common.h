@@ -23,7 +23,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr uint32_t kMagicBits = 0x4B400000u;  // bits of 1.5 * 2^23: adding it rounds to an integer (RNE)
 constexpr float kMagic = 12582912.0f;
 constexpr int kStreamVariation = 1, kStreamWrite = 2;
-constexpr int kStreamPulseRows = 3, kStreamPulseCols = 4, kStreamPulseNoise = 5;
+constexpr int kStreamPulseRows = 3, kStreamPulseCols = 4, kStreamPulseNoise = 5, kStreamWritePair = 6;
 constexpr bool kBarrierPerMfma = false;   // scheduling fence after every MFMA (true) or every fragment (false)
 
 // ---------------------------------------------------------------------------------------------

@@ -39,6 +39,7 @@ class CrossbarLayer:
         self.planes = torch.empty(xb.planes_bytes(self.cfg, K, N), dtype=torch.uint8, device=device)
         self.x = None
         self.profile = None                # stored wire distortion (with the profile flag), refreshed by forward()
+        self.pair = None                   # (Gp, Gn) once the network updates the two devices of a weight separately
         self.seen_x = self.seen_g = None   # set while the ranges are being calibrated
 
     def forward(self, x, step, ws):
@@ -72,7 +73,9 @@ class CrossbarLayer:
         if self.geom is None:
             if need_dx:
                 dx = ops.bwd(self.cfg, self.planes, dy, self.K, self.w_max, self.g_scale, ws=ws)
-            if not self.net.calibrating and pulse is None:
+            if not self.net.calibrating and pulse is None and self.net.pair_devices:
+                ops.update_pair(self.cfg, *self._pair(), self.W, self.x, dy, self.w_max, 1.0 / self.w_max, lr, step, ws=ws)
+            elif not self.net.calibrating and pulse is None:
                 ops.update(self.cfg, self.W, self.x, dy, self.w_max, 1.0 / self.w_max, lr, step, ws=ws)
             elif not self.net.calibrating:
                 # inputs fire in proportion to their size over the calibrated range; the error range then follows
@@ -82,7 +85,10 @@ class CrossbarLayer:
         else:
             if need_dx:
                 dx = ops.conv_bwd(self.cfg, self.planes, dy, self.geom, self.N, self.w_max, self.g_scale, ws=ws)
-            if not self.net.calibrating and pulse is None:
+            if not self.net.calibrating and pulse is None and self.net.pair_devices:
+                ops.conv_update_pair(self.cfg, *self._pair(), self.W, self.x, dy, self.geom, self.w_max, 1.0 / self.w_max, lr,
+                                     step, ws=ws)
+            elif not self.net.calibrating and pulse is None:
                 ops.conv_update(self.cfg, self.W, self.x, dy, self.geom, self.w_max, 1.0 / self.w_max, lr, step, ws=ws)
             elif not self.net.calibrating:     # every output position is one sample of the pulse scheme
                 bl, dw_min, d_range = self._pulse_ranges(pulse, lr)
@@ -90,13 +96,20 @@ class CrossbarLayer:
                                        dw_min, step, ws=ws)
         return dx
 
+    def _pair(self):
+        """The two device states of every weight (first use: placed symmetrically about mid-range)."""
+        if self.pair is None:
+            self.pair = self.net.ops.pair_init(self.W, self.w_max)
+        return self.pair
+
     def _pulse_ranges(self, pulse, lr):
         """(bl, dw_min, d_range) of a pulse-level update whose mean is the update at learning rate lr:
         lr = slots dw_min w_max / (x_range d_range) with x_range = the calibrated input range.  Stochastic
-        trains round without bias, so the pulse size is free and the error range follows from it; coded pulses
-        drop what is below half a level, so there the errors use their calibrated range and the pulse size follows."""
+        trains round without bias, so the pulse size is free and the error range follows from it; deterministic
+        codes (in time or in magnitude) drop what is below half a level, so there the errors use their calibrated
+        range and the pulse size follows."""
         bl, slots = pulse["bl"], self.net.ops.pulse_slots(self.cfg, pulse["bl"])
-        if self.cfg.flags & xb.PULSE_CODED:
+        if self.cfg.flags & (xb.PULSE_CODED | xb.PULSE_MAGNITUDE):
             return bl, lr * self.x_scale * self.g_scale / (slots * self.w_max), self.g_scale
         return bl, pulse["dw_min"], slots * pulse["dw_min"] * self.w_max / (lr * self.x_scale)
 
@@ -153,6 +166,7 @@ class Network:
     fcm_every = 1         # with the stored-profile wire model: steps between two runs of the circuit-level model
     adc_quantile = None   # set while the converter ranges are being measured
     pulse = None     # dict(bl=slots per train, dw_min=state change per pulse): pulse-level updates of the crossbar layers
+    pair_devices = False   # aggregate updates keep the positive and the negative device of a weight as states of their own
 
     def train_step(self, x, labels, lr):
         """One SGD step on a batch: returns the per-sample losses (device tensor)."""

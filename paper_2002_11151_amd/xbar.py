@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(HERE, "libxbar.so")
 
 (NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2, ADC_CURVE,
  ADC_PER_ARRAY, INPUT_OFFSET, PULSE_CODED) = (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048)
+PULSE_MAGNITUDE = 4096
 OP_FWD, OP_BWD, OP_UPDATE, OP_FCM, OP_UPDATE_PULSED = 0, 1, 2, 3, 4
 ABI_VERSION = 2
 
@@ -106,6 +107,13 @@ _SIGNATURES = {
                                 C.c_float, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_conv_update": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(ConvGeom), C.c_int,
                                    C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "xbar_pair_init": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float, C.c_void_p]),
+    "xbar_update_pair": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                   C.c_int, C.c_int, C.c_float, C.c_float, C.c_float, C.c_uint64, C.c_void_p, C.c_size_t,
+                                   C.c_void_p]),
+    "xbar_conv_update_pair": (C.c_int, [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.POINTER(ConvGeom), C.c_int, C.c_float, C.c_float, C.c_float, C.c_uint64,
+                                        C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_relu_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_relu_bwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "xbar_sigmoid_fwd": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -390,6 +398,38 @@ def conv_update(cfg, W, X, dY, geom, w_max, grad_scale, lr, step=0, ws=None):
     ws = _conv_ws(cfg, OP_UPDATE, geom, N, ws, W.device)
     _check(lib().xbar_conv_update(C.byref(cfg), _dev(W), _dev(X), _dev(dY), C.byref(geom), N, w_max, grad_scale, lr, step,
                                   C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return W
+
+
+def pair_init(W, w_max, Gp=None, Gn=None):
+    """xbar_pair_init: the two device states of every weight, placed symmetrically about mid-range."""
+    K, N = W.shape
+    Gp = torch.empty_like(W) if Gp is None else Gp
+    Gn = torch.empty_like(W) if Gn is None else Gn
+    _check(lib().xbar_pair_init(_dev(W), _dev(Gp), _dev(Gn), K, N, w_max, _stream()))
+    return Gp, Gn
+
+
+def update_pair(cfg, Gp, Gn, W, X, dY, w_max, grad_scale, lr, step=0, ws=None):
+    """xbar_update_pair: the device states Gp, Gn[K][N] in place from X[M][K] and dY[M][N]; W = w_max (Gp - Gn)."""
+    K, N = W.shape
+    M = X.shape[0]
+    assert X.shape == (M, K) and dY.shape == (M, N) and Gp.shape == (K, N) and Gn.shape == (K, N)
+    nbytes = workspace_bytes(cfg, OP_UPDATE, M, K, N)
+    if nbytes == 0:
+        _check(validate(cfg) or -2)
+    ws = _buffer(nbytes, ws, W.device)
+    _check(lib().xbar_update_pair(C.byref(cfg), _dev(Gp), _dev(Gn), _dev(W), _dev(X), _dev(dY), M, K, N, w_max, grad_scale,
+                                  lr, step, C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
+    return W
+
+
+def conv_update_pair(cfg, Gp, Gn, W, X, dY, geom, w_max, grad_scale, lr, step=0, ws=None):
+    """xbar_conv_update_pair: as update_pair for a convolution layer (NHWC tensors X and dY)."""
+    N = W.shape[1]
+    ws = _conv_ws(cfg, OP_UPDATE, geom, N, ws, W.device)
+    _check(lib().xbar_conv_update_pair(C.byref(cfg), _dev(Gp), _dev(Gn), _dev(W), _dev(X), _dev(dY), C.byref(geom), N, w_max,
+                                       grad_scale, lr, step, C.c_void_p(ws.data_ptr()), ws.numel(), _stream()))
     return W
 
 

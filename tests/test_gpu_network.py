@@ -239,6 +239,42 @@ def test_perceptron_learns_with_coded_pulses():
     assert np.mean(losses[-5:]) < 0.9 * losses[0], losses
 
 
+def test_perceptron_learns_with_magnitude_coded_pulses_and_with_device_pairs():
+    """The two update variants that complete Sec. IV-C's list on the same fixed batch: magnitude-coded pulses (one
+    pulse per sample and line with 8 height levels; errors on their calibrated range, quantum from the learning
+    rate) and the aggregate write with the two devices of every weight as states of their own."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_11151_amd import sequential, xbar as xb
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3)
+    B = 64
+    images = torch.rand((B, 784), generator=gen, device="cuda")
+    labels = (torch.arange(B, device="cuda") % 10).to(torch.int32)
+    runs = {}
+    for kind in ("aggregate", "pairs", "magnitude"):
+        kw = workloads.config_kwargs("mlp")
+        if kind == "magnitude":
+            kw["flags"] |= xb.PULSE_MAGNITUDE
+        net = sequential.Sequential(kw, sequential.mlp_spec((500,), 10), batch=B, in_shape=(784,), signed_input=False, seed=2)
+        if kind == "magnitude":
+            net.pulse = dict(bl=8)
+        net.pair_devices = kind == "pairs"
+        net.calibrate(images, labels)
+        runs[kind] = [float(net.train_step(images, labels, 0.01).mean()) for _ in range(60)]
+        assert np.isfinite(runs[kind]).all() and max(runs[kind]) < 1.1 * runs[kind][0], (kind, runs[kind])
+        if kind == "pairs":       # the weights the generator sees are the pairs' differences
+            for layer in net.layers:
+                gp, gn = layer.pair
+                assert torch.equal(layer.W, (layer.w_max * (gp.double() - gn.double())).float())
+                assert float(gp.min()) >= 0.0 and float(gp.max()) <= 1.0 and float(gn.min()) >= 0.0 and float(gn.max()) <= 1.0
+    assert np.mean(runs["aggregate"][-5:]) < 0.85 * runs["aggregate"][0]
+    # same mean change, and per weight the same noise variance as the effective device: the runs stay together
+    assert abs(np.mean(runs["pairs"][-5:]) - np.mean(runs["aggregate"][-5:])) < 0.12 * runs["aggregate"][0], runs["pairs"]
+    # 8 levels per line: values below half a level write nothing, so slower than the aggregate write
+    assert np.mean(runs["magnitude"][-5:]) < 0.95 * runs["magnitude"][0], runs["magnitude"]
+
+
 def test_residual_network_learns_with_pulse_level_updates():
     """Convolution layers written pulse by pulse (every output position one sample of the pulse scheme): with
     the write non-linearity and no write noise the loss of a fixed batch falls as under the aggregate write."""

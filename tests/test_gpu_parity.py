@@ -726,6 +726,13 @@ PULSED_CASES = [
     ("coded_nl_noise", 90, 128, 65, 16, 1.0, 0.01, "coded+nl+noise", 1.0),
     ("coded_one_slot", 50, 20, 30, 1, 0.5, 0.005, "coded", 1.0),
     ("coded_large_layer", 70, 2048, 1030, 31, 4.0, 0.4, "coded+nl", 1.0),
+    # magnitude-coded pulses: one pulse per sample and line, one write of (row height) x (column height) quanta
+    ("mag_ragged", 130, 70, 100, 7, 2.0, 0.02, "mag", 1.5),
+    ("mag_nl_noise", 90, 128, 65, 5, 1.0, 0.01, "mag+nl+noise", 1.0),
+    ("mag_one_level", 50, 20, 30, 1, 0.5, 0.005, "mag", 1.0),
+    ("mag_saturating", 40, 64, 64, 31, 0.5, 0.005, "mag+nl", 1.0),            # writes of up to 961 quanta: states hit the rails
+    ("mag_large_layer", 70, 2048, 1030, 6, 4.0, 0.4, "mag+nl", 1.0),          # 4 x 4 devices per thread
+    ("mag_many_samples", 2500, 40, 24, 4, 3.0, 0.03, "mag+noise", 1.0),       # few devices, many samples, two chunks of marks skipped
 ]
 
 
@@ -738,6 +745,7 @@ def test_pulsed_update(xo, xb, name, M, K, N, bl, x_range, d_range, ni, w_max):
     W = np.clip(W * 4, -0.9 * w_max, 0.9 * w_max).astype(np.float32)
     flags = (xo.UPD_NL if "nl" in ni else 0) | (xo.UPD_NOISE if "noise" in ni else 0)
     flags |= xo.PULSE_CODED if "coded" in ni else 0
+    flags |= xo.PULSE_MAGNITUDE if "mag" in ni else 0
     co, cg = both_configs(xo, xb, flags=flags, upd_nl_v=1.3, upd_noise_gamma=0.4, seed=19)
     dw = 2.0 ** -10
     Wo, pulses_o = xo.update_pulsed(co, W, X, dY, w_max, x_range, d_range, bl, dw, step=5, want_pulses=True)
@@ -747,7 +755,7 @@ def test_pulsed_update(xo, xb, name, M, K, N, bl, x_range, d_range, ni, w_max):
     Wg, pulses_g = Wg.cpu().numpy(), pulses_g.cpu().numpy()
     assert np.array_equal(pulses_g, pulses_o)
     assert np.abs(pulses_o).sum() > 0 or name == "single"
-    if ni in ("", "coded"):
+    if ni in ("", "coded", "mag"):
         assert np.array_equal(Wg, Wo)
     else:
         # exp, log, sin and cos come from two maths libraries: a few units in the last place of a double
@@ -769,6 +777,7 @@ CONV_PULSED_CASES = [
     (9, 16, 16, 4, 3, 1, 1, 20, "nl+noise"),        # 2304 positions on 36 x 20 devices: marks, then the walk
     (9, 16, 16, 4, 3, 1, 1, 20, "nl"),              # ... without noise: marks, then the staged kernel
     (3, 9, 9, 5, 3, 2, 1, 20, "coded+nl"),          # deterministic time-coded pulses
+    (3, 9, 9, 5, 3, 2, 1, 20, "mag+nl+noise"),      # magnitude-coded pulses
 ]
 
 
@@ -784,8 +793,9 @@ def test_conv_pulsed_update(xo, xb, B, H, Wd, C, k, stride, pad, N, ni):
     dY = (rng.normal(size=(B, OH, OW, N)) * 1e-2).astype(np.float32)
     flags = (xo.UPD_NL if "nl" in ni else 0) | (xo.UPD_NOISE if "noise" in ni else 0)
     flags |= xo.PULSE_CODED if "coded" in ni else 0
+    flags |= xo.PULSE_MAGNITUDE if "mag" in ni else 0
     co, cg = both_configs(xo, xb, flags=flags, upd_nl_v=1.3, upd_noise_gamma=0.4, seed=23)
-    dw, bl, x_range, d_range = 2.0 ** -10, 31, 3.0, 0.04 if N < 100 else 0.4
+    dw, bl, x_range, d_range = 2.0 ** -10, 6 if "mag" in ni else 31, 3.0, 0.04 if N < 100 else 0.4
     cols = conv.im2col(X, k, k, stride, pad)
     Wo, pulses_o = xo.update_pulsed(co, Wm, cols, dY.reshape(-1, N), 1.0, x_range, d_range, bl, dw, step=7, want_pulses=True)
     geom = xb.conv_geom(B, H, Wd, C, k, k, stride, pad)
@@ -808,6 +818,58 @@ def test_conv_pulsed_update(xo, xb, B, H, Wd, C, k, stride, pad, N, ni):
         bad.out_h += 1
         xb.conv_update_pulsed(cg, dev(Wm.copy()), dev(X), dev(dY), bad, 1.0, x_range, d_range, bl, dw)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("M,K,N,kind", [(64, 256, 256, ""), (37, 150, 70, "nl"), (300, 70, 129, "noise"),
+                                         (1000, 128, 64, "nl+noise"), (5, 1, 1, "nl+noise")])
+def test_update_pair(xo, xb, M, K, N, kind):
+    """Update with the two devices of every weight as states of their own: the same gradient kernel, another
+    write.  Bounds as for the aggregate update (test_update), per device with half the change."""
+    g = workloads.Gemm("t", K, N, M, False, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=M + K)
+    flags = (xo.UPD_NL if "nl" in kind else 0) | (xo.UPD_NOISE if "noise" in kind else 0)
+    co, cg = both_configs(xo, xb, flags=flags, upd_nl_v=0.3, upd_noise_gamma=5.0, seed=21)
+    w_max = float(np.float32(np.abs(W).max() * 1.2))          # as the C ABI sees it
+    lr, gs = 0.01, 1.0 / w_max
+    Gp0, Gn0 = xo.pair_init(W, w_max)
+    Gp, Gn = xb.pair_init(dev(W), w_max)
+    torch.cuda.synchronize()
+    assert np.array_equal(Gp.cpu().numpy(), Gp0) and np.array_equal(Gn.cpu().numpy(), Gn0)
+    Po, No, Wo = xo.update_pair(co, Gp0, Gn0, X, dY, w_max, gs, lr, step=7)
+    Wg = torch.empty_like(Gp)
+    xb.update_pair(cg, Gp, Gn, Wg, dev(X), dev(dY), w_max, gs, lr, step=7)
+    torch.cuda.synchronize()
+    Pg, Ng, Wg = Gp.cpu().numpy(), Gn.cpu().numpy(), Wg.cpu().numpy()
+    assert np.array_equal(Wg, (w_max * (Pg.astype(np.float64) - Ng)).astype(np.float32))       # W is the pair's difference
+    grad = np.abs(X.astype(np.float64)).T @ np.abs(dY.astype(np.float64))
+    eps = 2.0 ** -15 * gs * grad + 1e-12                       # gradient from two-term bf16 operands, per weight
+    bound = lr * (0.75 * eps + (5.0 * np.sqrt(0.5 * eps) * 6.0 if "noise" in kind else 0.0)) + 2e-7
+    assert (np.abs(Pg - Po) <= bound).all() and (np.abs(Ng - No) <= bound).all()
+    assert rel_l2(Wg - W, Wo - W) <= 1e-3
+    assert Pg.min() >= 0.0 and Pg.max() <= 1.0 and Ng.min() >= 0.0 and Ng.max() <= 1.0
+    if not kind:      # ideal devices away from the rails: the weights move as under the aggregate update
+        Wa = xb.update(cg, dev(W.copy()), dev(X), dev(dY), w_max, gs, lr, step=7)
+        torch.cuda.synchronize()
+        assert np.abs(Wg - Wa.cpu().numpy()).max() <= 3e-7 * w_max
+
+
+def test_conv_update_pair(xo, xb):
+    from oracle import conv
+    rng = np.random.default_rng(8)
+    B, H, Wd, C, k, stride, pad, N = 3, 9, 8, 6, 3, 2, 1, 20
+    X = rng.normal(size=(B, H, Wd, C)).astype(np.float32)
+    Wm = np.clip(rng.normal(size=(k * k * C, N)) * 0.3, -0.9, 0.9).astype(np.float32)
+    OH, OW = conv.out_size(H, k, stride, pad), conv.out_size(Wd, k, stride, pad)
+    dY = (rng.normal(size=(B, OH, OW, N)) * 1e-2).astype(np.float32)
+    co, cg = both_configs(xo, xb, flags=xo.UPD_NL | xo.UPD_NOISE, upd_nl_v=0.5, upd_noise_gamma=1.0, seed=4)
+    Gp0, Gn0 = xo.pair_init(Wm, 1.0)
+    Po, No, Wo = xo.update_pair(co, Gp0, Gn0, conv.im2col(X, k, k, stride, pad), dY.reshape(-1, N), 1.0, 1.0, 0.05, step=2)
+    Gp, Gn = xb.pair_init(dev(Wm), 1.0)
+    Wg = torch.empty_like(Gp)
+    xb.conv_update_pair(cg, Gp, Gn, Wg, dev(X), dev(dY), xb.conv_geom(B, H, Wd, C, k, k, stride, pad), 1.0, 1.0, 0.05, step=2)
+    torch.cuda.synchronize()
+    assert np.abs(Gp.cpu().numpy() - Po).max() <= 1e-5 and np.abs(Gn.cpu().numpy() - No).max() <= 1e-5
+    assert np.abs(Wg.cpu().numpy() - Wo).max() <= 2e-5
 
 
 def test_pulsed_update_argument_checks(xb):

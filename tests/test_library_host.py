@@ -45,7 +45,7 @@ def test_struct_layout_matches(xb):
     dict(xbar_rows=60), dict(xbar_rows=8), dict(xbar_cols=512), dict(weight_bits=7, slice_bits=2),
     dict(weight_bits=32, slice_bits=2), dict(slice_bits=5, weight_bits=10), dict(input_bits=9),
     dict(input_bits=8, stream_bits=3), dict(stream_bits=0), dict(adc_bits=1), dict(adc_bits=17),
-    dict(flags=1 << 12), dict(flags=512 | 256), dict(flags=512, adc_bits=16), dict(flags=256, adc_curve=[0.0] * 8 + [1.0, 0.5] + [1.0] * 7),
+    dict(flags=1 << 13), dict(flags=2048 | 4096), dict(flags=512 | 256), dict(flags=512, adc_bits=16), dict(flags=256, adc_curve=[0.0] * 8 + [1.0, 0.5] + [1.0] * 7),
     dict(flags=256, adc_curve=[-1.5] + [0.0] * 16), dict(flags=2 | 4), dict(flags=2 | 128), dict(flags=4 | 128), dict(r_min=0.0), dict(r_min=2e6), dict(r_max=float("nan")),
     dict(r_row=-1.0), dict(var_sigma=float("inf")), dict(adc_fs_fwd=0.0), dict(adc_fs_bwd=-3.0),
     dict(upd_noise_gamma=-1.0),
@@ -58,7 +58,7 @@ def test_validate_rejects(xb, kw):
     dict(), dict(xbar_rows=128, xbar_cols=256, weight_bits=16), dict(slice_bits=1, weight_bits=16),
     dict(stream_bits=8), dict(slice_bits=4, weight_bits=16, adc_bits=16), dict(flags=127 & ~4),
     dict(xbar_rows=16, xbar_cols=48), dict(flags=128 | 1 | 8 | 16 | 64), dict(flags=256),
-    dict(flags=256, adc_curve=[-1.0] * 9 + [1.0] * 8), dict(flags=512), dict(flags=512 | 128 | 1 | 32, adc_bits=15), dict(flags=1024), dict(flags=1024 | 64 | 512 | 2),
+    dict(flags=256, adc_curve=[-1.0] * 9 + [1.0] * 8), dict(flags=512), dict(flags=512 | 128 | 1 | 32, adc_bits=15), dict(flags=1024), dict(flags=1024 | 64 | 512 | 2), dict(flags=4096 | 8 | 16),
 ])
 def test_validate_accepts(xb, kw):
     assert xb.validate(xb.make_config(**kw)) == 0

@@ -17,7 +17,7 @@ Gemm = namedtuple("Gemm", "name K N M signed_input count conv", defaults=[None])
 # flag bits of the parameter struct (plain numbers, typed here so that this module imports nothing)
 NI_VARIATION, NI_WIRE_AAM, NI_WIRE_PROFILE, NI_UPD_NL, NI_UPD_NOISE, DAC_LUT, INPUT_SIGNED, NI_WIRE_AAM2 = (
     1, 2, 4, 8, 16, 32, 64, 128)
-ADC_CURVE, ADC_PER_ARRAY, INPUT_OFFSET, PULSE_CODED = 256, 512, 1024, 2048
+ADC_CURVE, ADC_PER_ARRAY, INPUT_OFFSET, PULSE_CODED, PULSE_MAGNITUDE = 256, 512, 1024, 2048, 4096
 PAPER_NI = NI_WIRE_AAM | NI_UPD_NL | NI_UPD_NOISE  # wire parasitics + write non-linearity + write noise
 
 
