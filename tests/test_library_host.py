@@ -191,3 +191,25 @@ def test_bench_refuses_more_than_one_gpu():
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     run = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert run.returncode != 0 and "one GPU" in run.stderr and run.stdout.strip() == ""
+
+
+def test_pulse_walk_keeps_its_device_model_at_compile_time():
+    """Regression guard.  With the device-model flags tested at run time inside the per-lane pulse walk of the
+    4 x 4-devices-per-thread kernel, the compiler (hipcc of ROCm 7.2, -O3) turns the wave-uniform test into a
+    lane mask made by a vector compare under the execution mask of the FIRST device's walk and reuses that mask
+    register in the walks of the thread's other 15 devices, whose active lanes differ: lanes that had left the first
+    walk read as "flag set", so linear devices took the non-linear branch (seen in the generated gfx950 code; wrong
+    weights for every device but the first of a thread, pulse counts right).  The walk therefore takes its device model
+    as template parameters: no wave-uniform condition is live across the per-lane loops.  The GPU cases
+    large_layer_linear / large_layer_noise of test_gpu_parity.py catch the effect; this test keeps the source from
+    drifting back."""
+    import os
+    import re
+    src = open(os.path.join(os.path.dirname(__file__), "..", "paper_2002_11151_amd", "csrc", "pulse.hip")).read()
+    body = src[src.index("__device__ __forceinline__ double one_pulse("):src.index("// Block = (16 P) x (16 P) devices")]
+    assert "if constexpr (NL)" in body and "if constexpr (NOISE)" in body
+    assert not re.search(r"a\.flags", body), "one_pulse must not test run-time flags"
+    for kernel in ("pulse_apply_kernel", "pulse_walk_kernel"):
+        start = src.index("void %s(PulseArgs a)" % kernel)
+        end = src.index("\n}\n", start)
+        assert not re.search(r"a\.flags", src[start:end]), kernel + " must not test run-time flags in its walk"
