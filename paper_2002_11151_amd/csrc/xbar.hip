@@ -39,10 +39,12 @@ namespace {
 struct TileArgs {
   const float* W;
   const float* profile;
+  const uint32_t* codes; // term codes of every plane value (single-path wire model alone), this copy's orientation
   const double* wire_u;  // all-paths wire model: plane values [S_w][2][K][N], array index 0 (else unused)
   uint16_t* planes;  // start of this copy
   int K, N, R, C, S_w, slice_bits, weight_bits, terms;
   int tile, ks, T, OP;
+  int spt;           // table-driven generator: slices per thread
   int pol_out;       // -1: difference of the pair (array 0 minus array 1); 0 / 1: that array alone
   uint32_t flags;
   double g_min, dg, var_sigma, r_row, r_col, r_source, r_sense, hi_scale, hi_inv_scale;
@@ -229,6 +231,107 @@ __global__ __launch_bounds__(256) void tile_planes_f6_kernel(TileArgs a) {
       const int off = 6 * w + 2 * h;
       uint8_t* dst = off < 16 ? frag + lane * 16 + off : frag + 1024 + lane * 8 + (off - 16);
       *reinterpret_cast<uint16_t*>(dst) = (uint16_t)(bits[j] >> (16 * h));
+    }
+  }
+}
+
+
+// Term codes of the plane value of every (sign, digit, row, column): one thread per (digit, row, column)
+// computes the value with the arithmetic of plane_value, splits it into the terms of the schedule and
+// writes both signs in both orientations.
+__global__ __launch_bounds__(256) void code_table_kernel(TileArgs a, uint32_t* table) {
+  const int nd = (1 << a.slice_bits) - 1;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= nd * a.R * a.C) return;
+  const int j = idx % a.C, i = (idx / a.C) % a.R, digit = idx / (a.C * a.R) + 1;
+  NormalStream rng(a.seed, kStreamVariation, 0);    // not drawn from: the table exists without variation only
+  const size_t words = (size_t)2 * nd * a.R * a.C;
+#pragma unroll
+  for (int neg = 0; neg < 2; ++neg) {
+    double left = plane_value(a, rng, neg ? -1 : 1, digit, 0, i, j);
+    uint32_t word = 0;
+    for (int t = 0; t < a.terms; ++t) {
+      double v;
+      const uint32_t code = e2m3_nearest(::ldexp(left, -a.term_exp[t]), v);
+      left -= ::ldexp(v, a.term_exp[t]);
+      word |= code << (6 * t);
+    }
+    const size_t plane = (size_t)(neg * nd + digit - 1) * a.R * a.C;
+    table[plane + (size_t)i * a.C + j] = word;
+    table[words + plane + (size_t)j * a.R + i] = word;
+  }
+}
+
+// Planes in the 6-bit format from the table of term codes: the thread mapping and the records of
+// tile_planes_f6_kernel; a plane value is one table word, looked up by (sign, digit, place in the array).
+template <bool TRANSPOSED>
+__global__ __launch_bounds__(256) void tile_planes_f6_table_kernel(TileArgs a) {
+  const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (tid >= a.n_threads) return;
+  const int out_len_pad = a.OP * 32;
+  const int o = (int)(tid % out_len_pad);
+  const int cg = (int)(tid / out_len_pad);
+  const int slots = a.ks * 8;
+  const int t = cg / slots, slot = cg - t * slots;
+  const int within = slot * 8;
+  const int Lc = TRANSPOSED ? a.N : a.K;
+  const int Lo = TRANSPOSED ? a.K : a.N;
+  const int rows = min(a.tile, Lc - t * a.tile);
+  const int J = within >> 6;
+  if (J * 64 >= rows) return;
+  const int w = (within & 63) >> 4, half = (within & 15) >> 3;
+  const int lane = (o & 31) + 32 * half;
+  const int op = o >> 5;
+  const int c0 = t * a.tile + within;
+  const double qw = (double)((1u << a.weight_bits) - 1);
+  const uint32_t dmask = (1u << a.slice_bits) - 1;
+  const int nd = (int)dmask;
+  // table of this orientation: [sign][digit - 1][contraction place][output place]
+  const int out_len = TRANSPOSED ? a.R : a.C;       // places along the output index
+  const uint32_t* codes = a.codes + (size_t)within * out_len + o % out_len;
+  const size_t plane_words = (size_t)a.R * a.C;
+  uint32_t mag[8];                                  // 0 for padding
+  int first[8];                                     // table plane of digit 1 with the sign of the weight
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    mag[e] = 0;
+    first[e] = 0;
+    if (within + e >= rows || o >= Lo) continue;
+    const int c = c0 + e;
+    const int k = TRANSPOSED ? o : c, n = TRANSPOSED ? c : o;
+    const double q = ::rint(clampd((double)a.W[(size_t)k * a.N + n] / (double)a.w_max, -1.0, 1.0) * qw);
+    mag[e] = (uint32_t)::fabs(q);
+    first[e] = q < 0.0 ? nd : 0;
+  }
+  uint8_t* base = reinterpret_cast<uint8_t*>(a.planes);
+  const int s_end = min(a.S_w, ((int)blockIdx.y + 1) * a.spt);
+  for (int s = (int)blockIdx.y * a.spt; s < s_end; ++s) {
+    unsigned long long bits[kMaxTermsF6];
+#pragma unroll
+    for (int j = 0; j < kMaxTermsF6; ++j) bits[j] = 0ull;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int digit = (int)((mag[e] >> (a.slice_bits * s)) & dmask);
+      if (!digit) continue;                          // both devices of the pair in the same state: exactly zero
+      const uint32_t word = codes[(size_t)(first[e] + digit - 1) * plane_words + (size_t)e * out_len];
+      const int nibble = 2 * (e & 3) + (e >> 2);     // where the input stage's byte e lands in the digit word
+#pragma unroll
+      for (int j = 0; j < kMaxTermsF6; ++j) {
+        if (j >= a.terms) break;
+        bits[j] |= (unsigned long long)((word >> (6 * j)) & 63u) << (6 * nibble);
+      }
+    }
+    const size_t frag0 = (((size_t)t * a.OP + op) * a.S_w + s) * a.terms * a.ks + J;
+#pragma unroll
+    for (int j = 0; j < kMaxTermsF6; ++j) {
+      if (j >= a.terms) break;
+      uint8_t* frag = base + (frag0 + (size_t)j * a.ks) * 1536;
+#pragma unroll
+      for (int h = 0; h < 3; ++h) {
+        const int off = 6 * w + 2 * h;
+        uint8_t* dst = off < 16 ? frag + lane * 16 + off : frag + 1024 + lane * 8 + (off - 16);
+        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)(bits[j] >> (16 * h));
+      }
     }
   }
 }
@@ -1266,7 +1369,7 @@ int xbar_config_validate(const xbar_config* c) {
 size_t xbar_planes_bytes(const xbar_config* cfg, int K, int N) {
   if (xbar_config_validate(cfg) || check_shape(1, K, N)) return 0;
   const Derived d = derive(cfg);
-  return weight_sums_offset(cfg, d, K, N) + weight_sums_bytes(cfg, K, N);
+  return code_table_offset(cfg, d, K, N) + code_table_bytes(cfg, d);
 }
 
 size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N) {
@@ -1345,7 +1448,22 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
     if (d.fmt == kFmtF6) {
       a.n_threads = (long long)g.T * g.ks * 8 * g.OP * 32;
       const unsigned blocks = (unsigned)((a.n_threads + 255) / 256);
-      if (dir == 0) hipLaunchKernelGGL(tile_planes_f6_kernel<false>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
+      a.codes = nullptr;
+      if (uses_code_table(d)) {
+        uint32_t* table = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(planes) + code_table_offset(cfg, d, K, N));
+        if (dir == 0) {
+          const int entries = ((1 << cfg->slice_bits) - 1) * cfg->xbar_rows * cfg->xbar_cols;
+          hipLaunchKernelGGL(code_table_kernel, dim3((unsigned)cdiv(entries, 256)), dim3(256), 0, st, a, table);
+          if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+        }
+        a.codes = table + (dir == 1 ? code_table_words(cfg) : 0);
+        // a thread quantises its weights once for all the slices it covers: as many slices per thread as
+        // still leave about four waves for every SIMD of the chip
+        a.spt = (int)std::min<long long>(d.S_w, std::max<long long>(1, a.n_threads * d.S_w / 262144));
+        const dim3 grid(blocks, (unsigned)cdiv(d.S_w, a.spt));
+        if (dir == 0) hipLaunchKernelGGL(tile_planes_f6_table_kernel<false>, grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(tile_planes_f6_table_kernel<true>, grid, dim3(256), 0, st, a);
+      } else if (dir == 0) hipLaunchKernelGGL(tile_planes_f6_kernel<false>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
       else hipLaunchKernelGGL(tile_planes_f6_kernel<true>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
       if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
       if (pol == d.npol - 1) offset += align256(g.bytes);

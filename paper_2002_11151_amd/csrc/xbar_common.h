@@ -130,6 +130,21 @@ static inline size_t weight_sums_bytes(const xbar_config* c, int K, int N) {
   return (c->flags & XBAR_INPUT_OFFSET) ? align256((size_t)8 * ((size_t)K + N)) : 0;
 }
 
+// Term codes of every plane value that can occur, kept behind the weight sums.  With the single-path wire
+// model alone (kFmtF6, one converter per column) a plane value depends only on the digit, the sign of the
+// weight and the place of the device pair in its array, so xbar_tile computes each once and the plane
+// generators look them up: [orientation][sign][digit - 1][row][column] words of 32 bits, term j's 6-bit
+// code at bit 6 j; orientation 1 is the same table with rows and columns exchanged.
+static inline bool uses_code_table(const Derived& d) {
+  return d.fmt == kFmtF6 && d.npol == 1 && d.array_ni == XBAR_NI_WIRE_AAM;
+}
+static inline size_t code_table_words(const xbar_config* c) {
+  return (size_t)2 * ((1u << c->slice_bits) - 1) * c->xbar_rows * c->xbar_cols;   // one orientation
+}
+static inline size_t code_table_bytes(const xbar_config* c, const Derived& d) {
+  return uses_code_table(d) ? align256(2 * code_table_words(c) * sizeof(uint32_t)) : 0;
+}
+
 static inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N, bool transposed) {
   PlaneGeom g;
   g.tile = transposed ? c->xbar_cols : c->xbar_rows;
@@ -145,6 +160,10 @@ static inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K
 static inline size_t weight_sums_offset(const xbar_config* c, const Derived& d, int K, int N) {
   return align256(plane_geom(c, d, K, N, false).bytes) + align256(plane_geom(c, d, K, N, true).bytes) +
          wire_scratch_bytes(c, d, K, N);
+}
+
+static inline size_t code_table_offset(const xbar_config* c, const Derived& d, int K, int N) {
+  return weight_sums_offset(c, d, K, N) + weight_sums_bytes(c, K, N);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -82,7 +82,10 @@ def test_size_queries(xb):
     base = dict(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2)
     c = xb.make_config(flags=xb.NI_WIRE_AAM, **base)
     frag = lambda terms, arrays=1: ((2 * 2 + 1 * 5) * 8 * terms * 2 * 1536) * arrays + pad256(1024) * 2
-    assert xb.planes_bytes(c, K, N) == frag(4)
+    # single-path wire model alone: the table of term codes (2 orientations x 2 signs x 3 digits x 128 x 128
+    # words) rides behind the planes
+    table = 2 * 2 * 3 * 128 * 128 * 4
+    assert xb.planes_bytes(c, K, N) == frag(4) + table
     assert xb.planes_bytes(xb.make_config(flags=xb.NI_WIRE_AAM | xb.NI_VARIATION, **base), K, N) == frag(5)
     assert xb.planes_bytes(xb.make_config(**base), K, N) == frag(1)
     assert xb.planes_bytes(xb.make_config(flags=xb.ADC_PER_ARRAY, **base), K, N) == frag(5, 2)
@@ -94,7 +97,7 @@ def test_size_queries(xb):
     fwd, bwd = frag(4) // 2, frag(4) // 2
     # offset-binary inputs: the 64-bit sums of the programmed weights per column and per row ride along
     coded = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=xb.NI_WIRE_AAM | xb.INPUT_OFFSET)
-    assert xb.planes_bytes(coded, K, N) == fwd + bwd + -(-8 * (K + N) // 256) * 256
+    assert xb.planes_bytes(coded, K, N) == fwd + bwd + -(-8 * (K + N) // 256) * 256 + table
     # ... and one phase instead of two: half the staged input of a signed pass
     assert xb.workspace_bytes(coded, xb.OP_BWD, 64, K, N) < xb.workspace_bytes(c, xb.OP_BWD, 64, K, N)
     assert xb.planes_bytes(c, 0, N) == 0 and xb.planes_bytes(c, K, -1) == 0
