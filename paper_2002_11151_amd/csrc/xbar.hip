@@ -982,8 +982,9 @@ VmmPlan plan_vmm(const xbar_config* c, const Derived& d, int M, int K, int N, bo
   const int slice_kb = d.fmt == kFmtF6 ? d.terms * f6_term_stride(p.g.ks) / 1024 : d.terms * p.g.ks;
   p.sg = d.S_w;
   if (d.fmt == kFmtF6) {
-    // as many slices per stage as fit 64 KiB; an even number when not all fit (the pipelined path pairs them)
-    const int fit_sg = std::max(1, 64 / slice_kb);
+    // all slices in one stage when they fit 72 KiB (two blocks of a compute unit share its 160 KiB); else as
+    // many as fit 64 KiB, an even number (the pipelined path pairs them)
+    const int fit_sg = d.S_w * slice_kb <= 72 ? d.S_w : std::max(1, 64 / slice_kb);
     if (fit_sg < d.S_w) p.sg = fit_sg >= 2 ? (fit_sg & ~1) : 1;
     p.lds_kb = p.sg * slice_kb;
   } else {

@@ -50,27 +50,43 @@ struct Derived {
 };
 
 // kFmtF6 term schedule.  Term 0 is the E2M3 number nearest to U / 2^x0 (|U| up to 7.5 x 2^x0: more than
-// twice the top device level); every later term holds the E2M3 number nearest to what is left, on a
-// grid 32 times finer than the one before (the uniform part of the format is 33 levels wide).  What is
-// left after term 0 is at most a quarter of 2^x0, or `bound` when the plane values are known to stay
-// that close to whole levels (single-path wire model alone); terms are added until the grid reaches
-// 2^-18 of a device level: 4 or 5 terms (1 for ideal arrays).  Returns the number of terms.
-static inline int f6_schedule(int slice_bits, bool ideal, double bound, int* term_exp) {
+// twice the top device level).  What it leaves is at most a quarter of 2^x0, or `bound` when the plane
+// values are known to stay that close to whole levels (single-path wire model alone).  Every later term
+// holds the E2M3 number nearest to what is left, in units of the smallest power of two whose largest
+// E2M3 number (7.5) still covers it; a number in binade b of the format (b = 0 below 2, 1 below 4, else
+// 2) then leaves at most 2^(b - 4) units.  Terms are added until what is left is at most `max_error`
+// device levels (and there are `min_terms` of them), 5 at most; ideal arrays need term 0 alone.
+// Returns the number of terms.
+static inline int f6_schedule(int slice_bits, bool ideal, double bound, double max_error, int min_terms, int* term_exp) {
   const int x0 = slice_bits - 2;
   term_exp[0] = x0;
   for (int j = 1; j < kMaxTermsF6; ++j) term_exp[j] = x0;
   if (ideal) return 1;
   double left = std::ldexp(1.0, x0 - 2);
   if (bound > 0.0 && bound < left) left = bound;
-  int g = (int)std::ceil(std::log2(left / 16.0));       // log2 of the grid of term 1
   int n = 1;
   while (n < kMaxTermsF6) {
-    term_exp[n++] = g + 3;                                // an E2M3 number is a multiple of 1/8
-    if (g <= -18 && n >= 4) break;
-    g -= 5;
+    int e = (int)std::ceil(std::log2(left / 7.5));
+    if (std::ldexp(7.5, e) < left) ++e;
+    term_exp[n++] = e;
+    const double units = left / std::ldexp(1.0, e);
+    left = std::ldexp(1.0, e - 4 + (units <= 2.0 ? 0 : units <= 4.0 ? 1 : 2));
+    if (left <= max_error && n >= min_terms) break;
   }
   return n;
 }
+
+// Budget of the planes' own representation error, as the share of converter codes that it may move
+// across a rounding boundary: half of the tolerance of 1e-4 on the codes, and no more than keeps the
+// layer outputs within a relative L2 distance of 1e-3 of exact arithmetic on the planes.  A code that
+// changes by one in (slice s, cycle b) moves an output by 2^(slice_bits s + stream_bits b) code weights,
+// so a share f of changed codes gives a relative L2 distance of about
+//   sqrt(1.42 f P / rows) / (8 gain rx rw)
+// (P = 2 input phases, rows per tile, gain in codes per device level, rx and rw the rms of inputs and
+// weights over their scales; the 8 is 2^21 / (255 x 65535) for the sizes that matter): with rx rw = 0.05
+// that is f <= 5.6e-8 gain^2 rows.
+constexpr double kPlaneFlipShare = 5e-5;
+constexpr double kPlaneFlipShareL2 = 5.6e-8;
 
 static inline Derived derive(const xbar_config* c) {
   Derived d;
@@ -95,7 +111,18 @@ static inline Derived derive(const xbar_config* c) {
                          (double)c->xbar_rows * (double)c->r_col + (double)c->r_sense;
       bound = rho * (g_max * g_max + g_min * g_min) / dg;
     }
-    d.terms = f6_schedule(c->slice_bits, d.terms == 1, bound, d.term_exp);
+    // A representation error e of a plane value, uniform within +-left, moves a column current of `rows`
+    // devices, about half of them driven, by about 0.46 left xmax sqrt(rows / 2) device levels (mean
+    // magnitude of the sum); times the converter gain that is the share of codes that change, since a
+    // code changes when a rounding boundary lies within the shift.
+    double gain = (double)d.q_adc / (double)std::min(c->adc_fs_fwd, c->adc_fs_bwd);
+    if ((c->flags & XBAR_DAC_LUT) && !level_table) gain *= std::fabs((double)c->dac_lut[1]);
+    const double packed = (c->flags & XBAR_ADC_CURVE) ? 4.0 : 1.0;   // a converter curve may pack its thresholds closer
+    const double rows = (double)std::max(c->xbar_rows, c->xbar_cols);
+    const double per_level = packed * gain * (double)((1 << c->stream_bits) - 1) * 0.46 * std::sqrt(rows / 2.0);
+    const double share = std::min(kPlaneFlipShare, kPlaneFlipShareL2 * gain * gain * (double)std::min(c->xbar_rows, c->xbar_cols));
+    // kernels exist for 1, 4 and 5 terms; one array alone: for 5 terms only
+    d.terms = f6_schedule(c->slice_bits, d.terms == 1, bound, share / per_level, d.npol == 2 ? 5 : 4, d.term_exp);
   }
   return d;
 }

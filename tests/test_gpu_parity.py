@@ -277,6 +277,33 @@ def test_nonideal_fwd_bwd(xo, xb, name, R, C, sb, slb, wb, signed, M, K, N, ni, 
         assert not np.array_equal(Y2, Yg)
 
 
+@pytest.mark.parametrize("adc_bits,ni,terms", [(6, "aam", 5), (8, "aam", 4), (12, "aam", 5), (6, "aam+var", 5), (10, "aam+var", 5)])
+def test_plane_terms_follow_the_converter(xo, xb, adc_bits, ni, terms):
+    """The 6-bit planes carry as many terms as the converter needs: what the terms leave of a plane value
+    may move at most half of the code bar's share of conversions across a rounding boundary, and few
+    enough that the outputs stay inside their bar (a coarse converter's codes weigh more, a fine one has
+    more boundaries).  The 8-bit converter of the benchmark runs on 4 terms, coarser and finer ones on 5;
+    every one of them stays inside both bars against the oracle, on several million conversions."""
+    R = C = 128
+    flags = xo.INPUT_SIGNED | xo.WIRE_AAM | (xo.VARIATION if "var" in ni else 0)
+    co, cg = both_configs(xo, xb, xbar_rows=R, xbar_cols=C, weight_bits=16, slice_bits=2, input_bits=8, stream_bits=1,
+                          adc_bits=adc_bits, flags=flags, var_sigma=0.1, seed=23,
+                          adc_fs_fwd=workloads.adc_full_scale(R, 1, 2), adc_fs_bwd=workloads.adc_full_scale(C, 1, 2))
+    assert xb.plane_format(cg) == (1, terms)
+    g = workloads.Gemm("t", 384, 160, 96, True, 1)
+    W, X, dY = workloads.layer_tensors_np(g, seed=adc_bits)
+    w_max, x_scale, g_scale = float(np.abs(W).max()), float(np.abs(X).max()), float(np.abs(dY).max())
+    Yo, codes_o = xo.fwd(co, W, X, w_max, x_scale, step=1, want_codes=True)
+    Yg, codes_g = gpu_fwd(xb, cg, W, X, w_max, x_scale, step=1)
+    assert codes_o.size >= 3_000_000
+    check_codes(codes_g, codes_o)
+    assert rel_l2(Yg, Yo) <= 1e-3
+    dXo, codes_o = xo.bwd(co, W, dY, w_max, g_scale, step=1, want_codes=True)
+    dXg, codes_g = gpu_bwd(xb, cg, W, dY, w_max, g_scale, step=1)
+    check_codes(codes_g, codes_o)
+    assert rel_l2(dXg, dXo) <= 1e-3
+
+
 @pytest.mark.parametrize("ni,adc_bits", [("aam+var", 12), ("pa+aam2", 12), ("ob+aam", 11)])
 def test_wide_sums_nonideal(xo, xb, ni, adc_bits):
     """Converters of 10 bits and more with 16-bit weights: the shift-and-add sum exceeds 32 bits.  The

@@ -64,6 +64,24 @@ def test_validate_accepts(xb, kw):
     assert xb.validate(xb.make_config(**kw)) == 0
 
 
+def test_plane_terms_follow_the_converter(xb):
+    """Terms of the 6-bit planes: 4 or 5, enough that what they leave of a plane value moves few enough
+    conversions across a rounding boundary (estimate: converter gain x largest digit x 0.46 x sqrt(rows / 2)
+    x what is left): at most 5e-5 of them, and at most the share that keeps layer outputs within 1e-3
+    (5.6e-8 gain^2 rows: a coarse converter's codes weigh more).  Ideal arrays need 1; 5 with a converter per array."""
+    import workloads
+    base = dict(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, input_bits=8, stream_bits=1,
+                adc_fs_fwd=64.0, adc_fs_bwd=64.0)
+    for bits, flags, want in ((4, xb.NI_WIRE_AAM, 5), (6, xb.NI_WIRE_AAM, 5), (8, xb.NI_WIRE_AAM, 4), (10, xb.NI_WIRE_AAM, 4), (12, xb.NI_WIRE_AAM, 5),
+                              (8, xb.NI_WIRE_AAM | xb.NI_VARIATION, 5), (8, 0, 1), (16, 0, 1),
+                              (8, xb.ADC_PER_ARRAY, 5), (4, xb.ADC_PER_ARRAY | xb.NI_WIRE_AAM, 5)):
+        assert xb.plane_format(xb.make_config(adc_bits=bits, flags=flags, var_sigma=0.1, **base)) == (1, want), (bits, flags)
+    # the benchmark configurations
+    assert xb.plane_format(xb.make_config(**workloads.config_kwargs("resnet50"))) == (1, 4)
+    assert xb.plane_format(xb.make_config(**workloads.config_kwargs("vgg16"))) == (1, 5)
+    assert xb.plane_format(xb.make_config(**workloads.config_kwargs("resnet20")))[0] == 0     # cycles of 4 bits: fp16 planes
+
+
 def test_size_queries(xb):
     pad256 = lambda b: -(-b // 256) * 256
     K, N = 147, 64
