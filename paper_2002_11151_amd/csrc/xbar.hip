@@ -643,24 +643,34 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 
 // Backward pass of a convolution layer: the crossbars give the error of every patch element
 // (dXcol[M][K]); an input pixel collects, digitally, the errors of every patch it belongs to.
-struct Col2imArgs {
-  const float* col;  // [M][K]
+// The adding-up pass of a backward convolution: every input pixel gathers the patch errors that its
+// places in the patches received, straight from the partial sums: the value of a patch entry is the one
+// vmm_finish_kernel would store, and the entries of a pixel are added in single precision in the order
+// (kernel row, kernel column).  The [M][K] matrix of patch errors is never written.
+struct FinishCol2imArgs {
+  FinishArgs f;      // f.out unused; f.n = M * K
   float* dX;         // NHWC
   ConvGeom conv;
-  int B, K;
-  long long n;
+  int K;
+  long long n_img;
 };
 
-__global__ __launch_bounds__(256) void col2im_kernel(Col2imArgs a) {
+// V consecutive channels of a pixel per thread (V = 4 where the channel count allows it: 16-byte loads keep
+// four times the bytes in flight, which is what bounds this pass).
+template <int V>
+__global__ __launch_bounds__(256) void vmm_finish_col2im_kernel(FinishCol2imArgs a) {
+#pragma clang fp contract(off)   // product, product, difference: each rounded on its own
   const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (t >= a.n) return;
+  if (t * V >= a.n_img) return;
   const ConvGeom& g = a.conv;
-  const int c = (int)(t % g.C);
-  long long u = t / g.C;
+  const int c = (int)((t * V) % g.C);
+  long long u = (t * V) / g.C;
   const int iw = (int)(u % g.W);
   u /= g.W;
   const int ih = (int)(u % g.H), b = (int)(u / g.H);
-  float sum = 0.0f;
+  float sum[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) sum[v] = 0.0f;
   for (int kh = 0; kh < g.KH; ++kh) {
     const int oy = ih + g.pad - kh;
     if (oy < 0 || oy % g.stride) continue;
@@ -672,10 +682,47 @@ __global__ __launch_bounds__(256) void col2im_kernel(Col2imArgs a) {
       const int ow = ox / g.stride;
       if (ow >= g.OW) continue;
       const long long m = ((long long)b * g.OH + oh) * g.OW + ow;
-      sum += a.col[m * a.K + (kh * g.KW + kw) * g.C + c];
+      const int k = (kh * g.KW + kw) * g.C + c;
+      const long long i = m * a.K + k;
+      long long acc[V];
+#pragma unroll
+      for (int v = 0; v < V; ++v) acc[v] = 0;
+      for (int ch = 0; ch < a.f.nchunk; ++ch) {
+        if (a.f.wide) {
+          const long long* src = reinterpret_cast<const long long*>(a.f.part) + (size_t)ch * a.f.n + i;
+#pragma unroll
+          for (int v = 0; v < V; v += 2) {
+            if constexpr (V >= 2) {
+              const longlong2 w = *reinterpret_cast<const longlong2*>(src + v);
+              acc[v] += w.x;
+              acc[v + 1] += w.y;
+            } else {
+              acc[v] += src[v];
+            }
+          }
+        } else {
+          const int32_t* src = reinterpret_cast<const int32_t*>(a.f.part) + (size_t)ch * a.f.n + i;
+          if constexpr (V == 4) {
+            const int4 w = *reinterpret_cast<const int4*>(src);
+            acc[0] += w.x; acc[1] += w.y; acc[2] += w.z; acc[3] += w.w;
+          } else {
+            acc[0] += src[0];
+          }
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        double y = (double)acc[v] * a.f.scale;
+        if (a.f.wsum) y = y - (double)a.f.wsum[k + v] * a.f.half_range;
+        sum[v] += (float)y;
+      }
     }
   }
-  a.dX[t] = sum;
+  if constexpr (V == 4) {
+    *reinterpret_cast<float4*>(a.dX + t * 4) = make_float4(sum[0], sum[1], sum[2], sum[3]);
+  } else {
+    a.dX[t] = sum[0];
+  }
 }
 
 struct WriteArgs {
@@ -1059,7 +1106,7 @@ hipError_t launch_vmm(const VmmArgs& a, const VmmPlan& p, int terms, bool codes,
 
 int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* out, int M, int K, int N,
             float w_max, float in_scale, void* ws, size_t ws_bytes, int16_t* codes, void* stream, bool transposed,
-            const ConvGeom* conv = nullptr, unsigned long long* hist = nullptr) {
+            const ConvGeom* conv = nullptr, unsigned long long* hist = nullptr, const ConvGeom* scatter = nullptr) {
   int rc = xbar_config_validate(cfg);
   if (rc) return rc;
   if ((rc = check_shape(M, K, N))) return rc;
@@ -1128,7 +1175,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   const bool split = p.wide == 2 && !general;          // adds its groups up in the partial-sum buffer
   a.split_sg = p.split_sg;
   a.flush_every = hist ? 0 : p.flush_every;            // the statistics pass keeps no sums
-  a.direct = (p.nchunk == 1 && !p.offset && !split) ? 1 : 0;
+  a.direct = (p.nchunk == 1 && !p.offset && !split && !scatter) ? 1 : 0;   // a scatter gathers from the partial sums
   a.total_wg = p.nchunk * p.g.OP * p.MB;
   a.per_xcd = cdiv(a.total_wg, 8);
   a.gain = (float)d.q_adc / adc_fs * dac_gain;
@@ -1167,7 +1214,21 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
       f.wsum = transposed ? sums + N : sums;
       f.half_range = (double)in_scale * (double)w_max / (double)((1u << cfg->weight_bits) - 1);
     }
-    hipLaunchKernelGGL(vmm_finish_kernel, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
+    if (scatter) {     // backward convolution: out is the NHWC image of input errors
+      FinishCol2imArgs fc;
+      fc.f = f;
+      fc.dX = out;
+      fc.conv = *scatter;
+      fc.K = p.Lout;
+      fc.n_img = (long long)(M / (scatter->OH * scatter->OW)) * scatter->H * scatter->W * scatter->C;
+      // 16-byte accesses: channels in fours (then K = kernel positions x channels is a multiple of 4 too)
+      if (scatter->C % 4 == 0)
+        hipLaunchKernelGGL(vmm_finish_col2im_kernel<4>, dim3((unsigned)((fc.n_img / 4 + 255) / 256)), dim3(256), 0, st, fc);
+      else
+        hipLaunchKernelGGL(vmm_finish_col2im_kernel<1>, dim3((unsigned)((fc.n_img + 255) / 256)), dim3(256), 0, st, fc);
+    } else {
+      hipLaunchKernelGGL(vmm_finish_kernel, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
+    }
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   }
   return XBAR_OK;
@@ -1543,7 +1604,7 @@ size_t xbar_conv_workspace_bytes(const xbar_config* cfg, int op, const xbar_conv
   if (xbar_config_validate(cfg) || conv_dims(geom, &g, &M, &K) || check_shape(M, K, N)) return 0;
   const Derived d = derive(cfg);
   if (op == XBAR_OP_FWD) return plan_vmm(cfg, d, M, K, N, false).ws_bytes;
-  if (op == XBAR_OP_BWD) return plan_vmm(cfg, d, M, K, N, true).ws_bytes + align256((size_t)M * K * sizeof(float));
+  if (op == XBAR_OP_BWD) return plan_vmm(cfg, d, M, K, N, true).ws_bytes;
   if (op == XBAR_OP_UPDATE) return plan_update(M, K, N).ws_bytes;
   if (op == XBAR_OP_UPDATE_PULSED) return pulsed_workspace_bytes(M, K, N);
   return 0;
@@ -1572,15 +1633,8 @@ int xbar_conv_bwd(const xbar_config* cfg, const void* planes, const float* dY, f
   if (ws_bytes < need) return XBAR_EWORKSPACE;
   if (conv_is_dense(geom))       // every pixel is its own patch: the crossbar output is the result
     return run_vmm(cfg, planes, dY, dX, M, K, N, w_max, g_scale, ws, ws_bytes, nullptr, hip_stream, true);
-  const size_t col_bytes = align256((size_t)M * K * sizeof(float));
-  float* col = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + (need - col_bytes));
-  if ((rc = run_vmm(cfg, planes, dY, col, M, K, N, w_max, g_scale, ws, need - col_bytes, nullptr, hip_stream, true))) return rc;
-  Col2imArgs c;
-  c.col = col; c.dX = dX; c.conv = g; c.B = geom->batch; c.K = K;
-  c.n = (long long)geom->batch * g.H * g.W * g.C;
-  hipLaunchKernelGGL(col2im_kernel, dim3((unsigned)((c.n + 255) / 256)), dim3(256), 0,
-                     reinterpret_cast<hipStream_t>(hip_stream), c);
-  return hipGetLastError() == hipSuccess ? XBAR_OK : XBAR_EHIP;
+  // the adding-up pass gathers every input pixel's patch errors from the partial sums
+  return run_vmm(cfg, planes, dY, dX, M, K, N, w_max, g_scale, ws, ws_bytes, nullptr, hip_stream, true, nullptr, nullptr, &g);
 }
 
 int xbar_conv_update(const xbar_config* cfg, float* W, const float* X, const float* dY, const xbar_conv_geom* geom, int N,
