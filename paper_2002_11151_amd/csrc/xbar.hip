@@ -485,17 +485,43 @@ struct FinishArgs {
   double half_range;       //   and the half-range it is multiplied with
 };
 
+// V consecutive outputs per thread (V = 4 where the row length allows it: 16-byte loads).
+template <int V>
 __global__ __launch_bounds__(256) void vmm_finish_kernel(FinishArgs a) {
 #pragma clang fp contract(off)   // product, product, difference: each rounded on its own
-  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long i = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * V;
   if (i >= a.n) return;
-  long long sum = 0;
-  for (int c = 0; c < a.nchunk; ++c)
-    sum += a.wide ? reinterpret_cast<const long long*>(a.part)[(size_t)c * a.n + i]
-                  : (long long)reinterpret_cast<const int32_t*>(a.part)[(size_t)c * a.n + i];
-  double y = (double)sum * a.scale;
-  if (a.wsum) y = y - (double)a.wsum[i % a.Lout] * a.half_range;
-  a.out[i] = (float)y;
+  long long sum[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) sum[v] = 0;
+  for (int c = 0; c < a.nchunk; ++c) {
+    if (a.wide) {
+      const long long* src = reinterpret_cast<const long long*>(a.part) + (size_t)c * a.n + i;
+      if constexpr (V == 4) {
+        const longlong2 w0 = *reinterpret_cast<const longlong2*>(src), w1 = *reinterpret_cast<const longlong2*>(src + 2);
+        sum[0] += w0.x; sum[1] += w0.y; sum[2] += w1.x; sum[3] += w1.y;
+      } else {
+        sum[0] += src[0];
+      }
+    } else {
+      const int32_t* src = reinterpret_cast<const int32_t*>(a.part) + (size_t)c * a.n + i;
+      if constexpr (V == 4) {
+        const int4 w = *reinterpret_cast<const int4*>(src);
+        sum[0] += w.x; sum[1] += w.y; sum[2] += w.z; sum[3] += w.w;
+      } else {
+        sum[0] += src[0];
+      }
+    }
+  }
+  float y[V];
+#pragma unroll
+  for (int v = 0; v < V; ++v) {
+    double r = (double)sum[v] * a.scale;
+    if (a.wsum) r = r - (double)a.wsum[(i + v) % a.Lout] * a.half_range;
+    y[v] = (float)r;
+  }
+  if constexpr (V == 4) *reinterpret_cast<float4*>(a.out + i) = make_float4(y[0], y[1], y[2], y[3]);
+  else a.out[i] = y[0];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1227,7 +1253,10 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
       else
         hipLaunchKernelGGL(vmm_finish_col2im_kernel<1>, dim3((unsigned)((fc.n_img + 255) / 256)), dim3(256), 0, st, fc);
     } else {
-      hipLaunchKernelGGL(vmm_finish_kernel, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
+      if (f.n % 4 == 0)
+        hipLaunchKernelGGL(vmm_finish_kernel<4>, dim3((unsigned)((f.n / 4 + 255) / 256)), dim3(256), 0, st, f);
+      else
+        hipLaunchKernelGGL(vmm_finish_kernel<1>, dim3((unsigned)((f.n + 255) / 256)), dim3(256), 0, st, f);
     }
     if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
   }
