@@ -452,21 +452,38 @@ __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
       }
     }
     union { u32x2 v; uint8_t b[8]; } pos, neg;
+    // The code is decided in double precision (as the oracle decides it).  The same expression in single
+    // precision is within 255 x 3 x 2^-24 < 5e-5 of the exact value (one correctly rounded division, one
+    // addition with offset coding, one product), so it rounds to the same code unless it lies within 1e-4 of
+    // half a step: those few inputs (2e-4 of them) are decided again in double precision.
+    int code[8];
+    bool sure = true;
+    const float qa_f = (float)qa, lo_f = (float)lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float r = x[e] / a.scale;
+      const float y = (a.offset ? fminf(fmaxf((r + 1.0f) * 0.5f, 0.0f), 1.0f) : fminf(fmaxf(r, lo_f), 1.0f)) * qa_f;
+      const float k = ::rintf(y);
+      sure = sure && ::fabsf(y - k) <= 0.4999f;      // a NaN is not sure
+      code[e] = (int)k;
+    }
+    if (!sure) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        code[e] = a.offset ? (int)::rint(clampd(((double)x[e] / scale + 1.0) * 0.5, 0.0, 1.0) * qa)
+                           : (int)::rint(clampd((double)x[e] / scale, lo, 1.0) * qa);
+    }
     if (a.offset) {
       // u = rne((x / scale + 1) / 2 * Qa): every input that exists is driven, a value of zero (also a
       // position outside the image) at mid-range; rows beyond the layer are not driven at all
       const int n_driven = m < a.M ? min(max(lend - l0, 0), 8) : 0;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int u = (int)::rint(clampd(((double)x[e] / scale + 1.0) * 0.5, 0.0, 1.0) * qa);
-        pos.b[e] = (uint8_t)(e < n_driven ? u : 0);
-      }
+      for (int e = 0; e < 8; ++e) pos.b[e] = (uint8_t)(e < n_driven ? code[e] : 0);
     } else {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
-        const int q = (int)::rint(clampd((double)x[e] / scale, lo, 1.0) * qa);
-        pos.b[e] = (uint8_t)(q > 0 ? q : 0);
-        neg.b[e] = (uint8_t)(q < 0 ? -q : 0);
+        pos.b[e] = (uint8_t)(code[e] > 0 ? code[e] : 0);
+        neg.b[e] = (uint8_t)(code[e] < 0 ? -code[e] : 0);
       }
     }
     const size_t blk = ((size_t)mp * a.T + t) * a.ks + j;
