@@ -93,15 +93,26 @@ __device__ __forceinline__ half8 level_fragment(const u32x2 raw, int in_shift, u
 // LSB high and low; residual first leaves 4e-6 .. 1.4e-5, all one LSB low (the matrix instruction
 // rounds its sum downwards and did so at every leading-term step), and alternating the terms per
 // k-step 1e-4.  Fragments are fetched two ahead.
-template <int PM, int NK, int TERMS>
+// LOW_FIRST (one converter per array): the smaller terms first, the leading term last.  A single array's
+// current is a sum of positive products that only grows, so the leading sum is large when the residual
+// products land on it and every one of those steps rounds at its magnitude; the other way round the residual
+// sum is small (precise), and the exact leading products round only where the sum crosses into a new binade:
+// about one unit in the last place of the result in all, instead of one per residual step.
+template <int TERMS, int NK, bool LOW_FIRST>
+__device__ __forceinline__ constexpr int fragment_of_step(int i) {
+  return LOW_FIRST ? (TERMS - 1 - i / NK) * NK + i % NK : i;
+}
+
+template <int PM, int NK, int TERMS, bool LOW_FIRST = false>
 __device__ __forceinline__ void vmm_contract(const half8 (&ab)[PM][NK], const u32x4* bptr, float16v (&acc)[PM]) {
   constexpr int NF = TERMS * NK;
-  u32x4 f0 = bptr[0], f1 = NF > 1 ? bptr[64] : f0;
+  u32x4 f0 = bptr[fragment_of_step<TERMS, NK, LOW_FIRST>(0) * 64],
+        f1 = NF > 1 ? bptr[fragment_of_step<TERMS, NK, LOW_FIRST>(1) * 64] : f0;
 #pragma unroll
   for (int i = 0; i < NF; ++i) {
     const u32x4 cur = f0;
     f0 = f1;
-    if (i + 2 < NF) f1 = bptr[(i + 2) * 64];
+    if (i + 2 < NF) f1 = bptr[fragment_of_step<TERMS, NK, LOW_FIRST>(i + 2) * 64];
     const half8 bf = __builtin_bit_cast(half8, cur);
 #pragma unroll
     for (int pm = 0; pm < PM; ++pm) {
@@ -137,7 +148,7 @@ __device__ __forceinline__ void vmm_adc_narrow(const float16v (&acc)[PM], float 
 // previous result is converted.  On gfx950 up to ~5 VALU operations issued between two MFMAs of the
 // same wave run in the shadow of the matrix pipe, whereas VALU work that sits in a block of its own
 // does not overlap reliably; scheduling barriers keep the compiler from regrouping the pattern.
-template <int PM, int NK, int TERMS, bool DO_ADC>
+template <int PM, int NK, int TERMS, bool DO_ADC, bool LOW_FIRST = false>
 __device__ __forceinline__ void vmm_contract_adc(const half8 (&ab)[PM][NK], const u32x4* bptr, float16v (&acc)[PM],
                                                  const float16v (&old)[PM], float gain_old, float clamp_lo,
                                                  float clamp_hi, int sh_old, uint32_t (&y)[PM][16]) {
@@ -147,12 +158,12 @@ __device__ __forceinline__ void vmm_contract_adc(const half8 (&ab)[PM][NK], cons
   constexpr int PF = NF < 2 ? NF : 2;               // fragments in flight from LDS
   u32x4 fr[PF];
 #pragma unroll
-  for (int i = 0; i < PF; ++i) fr[i] = bptr[i * 64];
+  for (int i = 0; i < PF; ++i) fr[i] = bptr[fragment_of_step<TERMS, NK, LOW_FIRST>(i) * 64];
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < NF; ++i) {
     const u32x4 cur = fr[i % PF];
-    if (i + PF < NF) fr[i % PF] = bptr[(i + PF) * 64];
+    if (i + PF < NF) fr[i % PF] = bptr[fragment_of_step<TERMS, NK, LOW_FIRST>(i + PF) * 64];
     const half8 bf = __builtin_bit_cast(half8, cur);
 #pragma unroll
     for (int pm = 0; pm < PM; ++pm) {
@@ -225,13 +236,13 @@ __device__ __forceinline__ void vmm_tile_group_pipelined(const VmmArgs& a, const
       const int sh1 = sh0 + a.slice_bits;
       // even slice -> acc0, while the ADC of the previous odd slice (acc1) runs
       if (b == 0 && sl == 0)
-        vmm_contract_adc<PM, NK, TERMS, false>(ab, bbase + (size_t)sl * NF * 64, acc0, acc1, gain_prev, clamp_lo,
+        vmm_contract_adc<PM, NK, TERMS, false, PER_ARRAY>(ab, bbase + (size_t)sl * NF * 64, acc0, acc1, gain_prev, clamp_lo,
                                                clamp_hi, sh_prev, y);
       else
-        vmm_contract_adc<PM, NK, TERMS, true>(ab, bbase + (size_t)sl * NF * 64, acc0, acc1, gain_prev, clamp_lo,
+        vmm_contract_adc<PM, NK, TERMS, true, PER_ARRAY>(ab, bbase + (size_t)sl * NF * 64, acc0, acc1, gain_prev, clamp_lo,
                                               clamp_hi, sh_prev, y);
       // odd slice -> acc1, while the ADC of the even slice (acc0) runs
-      vmm_contract_adc<PM, NK, TERMS, true>(ab, bbase + (size_t)(sl + 1) * NF * 64, acc1, acc0, gain_b, clamp_lo,
+      vmm_contract_adc<PM, NK, TERMS, true, PER_ARRAY>(ab, bbase + (size_t)(sl + 1) * NF * 64, acc1, acc0, gain_b, clamp_lo,
                                             clamp_hi, sh0, y);
       sh_prev = sh1;
       gain_prev = gain_b;
@@ -327,7 +338,7 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
 #pragma unroll
             for (int j = 0; j < NK; ++j) ab[pm][j] = level_fragment(raw[pm][j], in_shift, digit_mask8, level);
           float16v part[PM];
-          vmm_contract<PM, NK, TERMS>(ab, lds + lane + (size_t)sl * NF * 64, part);
+          vmm_contract<PM, NK, TERMS, PER_ARRAY>(ab, lds + lane + (size_t)sl * NF * 64, part);
           const float volt = a.dac_lut[level];
 #pragma unroll
           for (int pm = 0; pm < PM; ++pm)
@@ -335,7 +346,7 @@ __device__ __forceinline__ void vmm_tile_group(const VmmArgs& a, const u32x4* ld
             for (int r = 0; r < 16; ++r) acc[pm][r] = __builtin_fmaf(volt, part[pm][r], acc[pm][r]);
         }
       } else {
-        vmm_contract<PM, NK, TERMS>(ab, lds + lane + (size_t)sl * NF * 64, acc);
+        vmm_contract<PM, NK, TERMS, PER_ARRAY>(ab, lds + lane + (size_t)sl * NF * 64, acc);
       }
       const float gain_used = (CODES && a.dac_levels) ? gain_lut : gain_b;
       vmm_adc_general<PM, WIDE, CODES, PER_ARRAY>(a, acc, gain_used, clamp_lo, clamp_hi, sh, p, pol, b, s, t, lane, mp0, op,
@@ -437,7 +448,7 @@ __device__ __forceinline__ float16v mfma_f6_term(int term, const int8v& pa, cons
 // Contraction of one (slice, cycle), terms in order (the leading term's sum is exact, the smaller terms
 // land on it), with the ADC / shift-and-add of the PREVIOUS (slice, cycle) woven in between the matrix
 // instructions.  xb / yb: this lane's address in the first KiB / last half KiB of the slice's first fragment.
-template <int PM, int NK64, int NT, bool DO_ADC>
+template <int PM, int NK64, int NT, bool DO_ADC, bool LOW_FIRST = false>
 __device__ __forceinline__ void vmm6_contract_adc(const int4v (&dg)[PM][NK64], const char* xb, const char* yb,
                                                   float16v (&acc)[PM], const float16v (&old)[PM], float gain_old,
                                                   float clamp_lo, float clamp_hi, int sh_old, uint32_t (&y)[PM][16],
@@ -451,7 +462,8 @@ __device__ __forceinline__ void vmm6_contract_adc(const int4v (&dg)[PM][NK64], c
   u32x2 fy[PF];
 #pragma unroll
   for (int i = 0; i < PF; ++i) {
-    const int off = (i / NK64) * STRIDE + (i % NK64) * 1536;
+    const int f = fragment_of_step<NT, NK64, LOW_FIRST>(i);
+    const int off = (f / NK64) * STRIDE + (f % NK64) * 1536;
     fx[i] = *reinterpret_cast<const u32x4*>(xb + off);
     fy[i] = *reinterpret_cast<const u32x2*>(yb + off);
   }
@@ -461,18 +473,19 @@ __device__ __forceinline__ void vmm6_contract_adc(const int4v (&dg)[PM][NK64], c
     const u32x4 cx = fx[i % PF];
     const u32x2 cy = fy[i % PF];
     if (i + PF < NF) {
-      const int off = ((i + PF) / NK64) * STRIDE + ((i + PF) % NK64) * 1536;
+      const int f = fragment_of_step<NT, NK64, LOW_FIRST>(i + PF);
+      const int off = (f / NK64) * STRIDE + (f % NK64) * 1536;
       fx[i % PF] = *reinterpret_cast<const u32x4*>(xb + off);
       fy[i % PF] = *reinterpret_cast<const u32x2*>(yb + off);
     }
     const int8v pa = {(int)cx.x, (int)cx.y, (int)cx.z, (int)cx.w, (int)cy.x, (int)cy.y, 0, 0};
-    const int term = i / NK64, J = i % NK64;
+    const int term = fragment_of_step<NT, NK64, LOW_FIRST>(i) / NK64, J = i % NK64;
 #pragma unroll
     for (int pm = 0; pm < PM; ++pm) {
       const int8v pb = {dg[pm][J][0], dg[pm][J][1], dg[pm][J][2], dg[pm][J][3], 0, 0, 0, 0};
       if (i == 0) {
         const float16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        acc[pm] = mfma_f6_term(0, pa, pb, zero, scale_lo, scale_hi);
+        acc[pm] = mfma_f6_term(term, pa, pb, zero, scale_lo, scale_hi);
       } else {
         acc[pm] = mfma_f6_term(term, pa, pb, acc[pm], scale_lo, scale_hi);
       }
@@ -515,12 +528,12 @@ __device__ __forceinline__ void vmm6_tile_group_pipelined(const VmmArgs& a, cons
       const int sh0 = a.slice_bits * (shift_slice0 + sl) + in_shift;
       const int sh1 = sh0 + a.slice_bits;
       if (b == 0 && sl == 0)
-        vmm6_contract_adc<PM, NK64, NT, false>(dg, xb + sl * SLICE, yb + sl * SLICE, acc0, acc1, gain, clamp_lo, clamp_hi,
+        vmm6_contract_adc<PM, NK64, NT, false, PER_ARRAY>(dg, xb + sl * SLICE, yb + sl * SLICE, acc0, acc1, gain, clamp_lo, clamp_hi,
                                                sh_prev, y, a.scale_lo, a.scale_hi);
       else
-        vmm6_contract_adc<PM, NK64, NT, true>(dg, xb + sl * SLICE, yb + sl * SLICE, acc0, acc1, gain, clamp_lo, clamp_hi,
+        vmm6_contract_adc<PM, NK64, NT, true, PER_ARRAY>(dg, xb + sl * SLICE, yb + sl * SLICE, acc0, acc1, gain, clamp_lo, clamp_hi,
                                               sh_prev, y, a.scale_lo, a.scale_hi);
-      vmm6_contract_adc<PM, NK64, NT, true>(dg, xb + (sl + 1) * SLICE, yb + (sl + 1) * SLICE, acc1, acc0, gain, clamp_lo,
+      vmm6_contract_adc<PM, NK64, NT, true, PER_ARRAY>(dg, xb + (sl + 1) * SLICE, yb + (sl + 1) * SLICE, acc1, acc0, gain, clamp_lo,
                                             clamp_hi, sh0, y, a.scale_lo, a.scale_hi);
       sh_prev = sh1;
     }
@@ -550,7 +563,7 @@ __device__ __forceinline__ void vmm6_tile_group(const VmmArgs& a, const char* ld
       const int sh = a.slice_bits * s + in_shift;
       float16v acc[PM], none[PM];
       uint32_t unused[PM][16];
-      vmm6_contract_adc<PM, NK64, NT, false>(dg, xb + sl * SLICE, yb + sl * SLICE, acc, none, 0.f, 0.f, 0.f, 0, unused,
+      vmm6_contract_adc<PM, NK64, NT, false, PER_ARRAY>(dg, xb + sl * SLICE, yb + sl * SLICE, acc, none, 0.f, 0.f, 0.f, 0, unused,
                                              a.scale_lo, a.scale_hi);
       vmm_adc_general<PM, WIDE, CODES, PER_ARRAY>(a, acc, gain, clamp_lo, clamp_hi, sh, p, pol, b, s, t, lane, mp0, op, y, y64);
     }

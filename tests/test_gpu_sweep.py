@@ -6,9 +6,9 @@ coded trains) and convolution layers.  The hand-picked cases of test_gpu_parity.
 design; this file covers combinations nobody picked.  Every case is keyed by its index: a failure names it.
 
 Bars: codes within one LSB; with ideal arrays everything bit-exact; differing codes at most 1e-4 of the
-conversions at converters of up to 8 bits (the stated bar) -- beyond that the fp32 rounding of current x
-gain meets a code boundary in proportion to the number of codes, so the bar doubles per extra bit -- and at
-least 2 codes in samples too small to resolve the fraction; the production launch returns the bits of the
+conversions (the stated bar) at converters of up to 10 bits -- beyond that the single-precision sums of the
+currents (24-bit significands: 2^-13 of a code step at 11 bits) meet a code boundary in proportion to the
+number of codes, so the share doubles per extra bit -- and at least 2 codes in samples too small to resolve the fraction; the production launch returns the bits of the
 code-tap launch; outputs within relative L2 1e-3 (offset-binary inputs: the bound derived from the differing
 codes); updates within the bounds derived in test_gpu_parity.py; pulse counts bit-exact.
 """
@@ -119,15 +119,17 @@ def test_sweep_forward_backward(xo, xb, case):
         if ideal:
             assert n_diff == 0 and np.array_equal(got, want), "%s %s: ideal arrays not bit-exact" % (what, name)
             continue
-        # the code bar as stated up to 11-bit converters; every bit beyond that halves the room that the
+        # the code bar as stated up to 10-bit converters; every bit beyond that halves the room that the
         # single-precision currents (24-bit significands) leave below a code step, and doubles the share
-        assert n_diff <= max(2, 1e-4 * 2.0 ** max(0, adc - 11) * diff.size), \
+        # (a full-range current of an 11-bit converter is resolved to 2^-13 = 1.2e-4 of a code step)
+        assert n_diff <= max(2, 1e-4 * 2.0 ** max(0, adc - 10) * diff.size), \
             "%s %s: %d of %d codes differ" % (what, name, n_diff, diff.size)
         offset = bool(flags & xo.INPUT_OFFSET) and (name == "bwd" or bool(flags & xo.INPUT_SIGNED))
         # every output is an exact linear function of the codes: n differing codes move the result by at
         # most n top-code weights (twice that with offset coding).  Small layers with coarse converters can
         # exceed a relative 1e-3 with a single differing code, hence the second term.
-        slack = n_diff * (2.0 if offset else 1.0) * top_code_weight(kw, scale, w_max, fs) / max(float(np.linalg.norm(want)), 1e-300)
+        # (attained when every differing code is a top code; 0.1 % for the single-precision rounding of the outputs)
+        slack = 1.001 * n_diff * (2.0 if offset else 1.0) * top_code_weight(kw, scale, w_max, fs) / max(float(np.linalg.norm(want)), 1e-300)
         assert rel_l2(got, want) <= (0.0 if offset else 1e-3) + slack, "%s %s: rel L2 %.3g" % (what, name, rel_l2(got, want))
 
 
