@@ -11,13 +11,13 @@ pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
 
-LAYERS = [("resnet50", 64, "conv1_7x7"), ("resnet50", 64, "s1b0_1x1b"), ("resnet50", 64, "s4b0_3x3"),
-          ("resnet50", 64, "fc"),             # the classifier: 64 batch rows, 2048 x 1000 weights
-          ("resnet50", 64, "s1b0_1x1a"),      # 64 x 64 weights: one half-filled crossbar, 200704 rows
-          ("resnet50", 64, "s2b0_down"),      # 1 x 1 projection shortcut
-          ("resnet50", 64, "s4b0_down"),      # backward pass: more virtual tiles per chunk than 32-bit sums hold
-          ("resnet20", 128, "s1b0_a"),        # 16 output columns: half-empty output patch, 4-bit cycles
-          ("vgg16", 128, "conv1_2")]          # 6.4 M rows (M*K > 2^31), 256x256 tiles, device variation
+# every one of the 24 distinct layer shapes of the benchmarked ResNet-50 workload -- among them the classifier (64
+# batch rows, 2048 x 1000 weights), 64 x 64 weights (one half-filled crossbar, 200704 rows), the 1 x 1 projection
+# shortcuts, and backward passes with more virtual tiles per chunk than 32-bit sums hold -- and one layer each of
+# the ResNet-20 (16 output columns: half-empty output patch, 4-bit cycles) and VGG-16 configurations (6.4 M rows,
+# M*K > 2^31, 256 x 256 tiles, device variation)
+LAYERS = [("resnet50", 64, g.name) for g in workloads.resnet50_gemms(64, merge=True)] + \
+         [("resnet20", 128, "s1b0_a"), ("vgg16", 128, "conv1_2")]
 
 
 @pytest.fixture(scope="module")
