@@ -549,10 +549,12 @@ struct GradArgs {
   const float* D;   // [M][N]
   float* part;      // [mchunks][K][N]
   int M, K, N, KB, NB, m_per_chunk;
+  int total_wg, per_xcd;   // blocks of the launch; logical blocks per XCD (the grid is 8 x per_xcd)
   ConvGeom conv;
 };
 
 constexpr int kGradMS = 32;   // batch rows per LDS stage = two k-steps of the bf16 matrix instruction
+constexpr int kGradKS = kGradMS / 16;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // fp32 value as a leading bf16 and a bf16 residual (together 16 significant bits).
@@ -576,9 +578,14 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   __shared__ ConvRow crow[2][kGradMS];               // patches of the rows of the stage being fetched
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wk = wave >> 1, wn = wave & 1;
-  const int kb = blockIdx.x % a.KB, nb = blockIdx.x / a.KB;
+  // consecutive block ids go to different XCDs; give each XCD a contiguous range of logical blocks, tiles
+  // fastest, so that the tiles of one batch chunk (which read the same rows of X and dY) share one L2
+  const int logical = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
+  if (logical >= a.total_wg) return;
+  const int tile_id = logical % (a.KB * a.NB), chunk_id = logical / (a.KB * a.NB);
+  const int kb = tile_id % a.KB, nb = tile_id / a.KB;
   const int k0 = kb * 128, n0 = nb * 128;
-  const int m_begin = blockIdx.y * a.m_per_chunk;
+  const int m_begin = chunk_id * a.m_per_chunk;
   const int m_end = min(a.M, m_begin + a.m_per_chunk);
   constexpr int PARTS = (SPLIT_K ? 2 : 1) * (SPLIT_N ? 2 : 1);     // batch shares
   const int share = (SPLIT_K ? wk : 0) * (SPLIT_N ? 2 : 1) + (SPLIT_N ? wn : 0);
@@ -591,10 +598,10 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  // staging: this thread fetches column (tid & 127) of 16 of the 32 rows of a stage: row groups
-  // (tid >> 7) and (tid >> 7) + 2
-  const int col = tid & 127, g_first = tid >> 7;
-  float px[16], pd[16];
+  // staging: this thread fetches column (tid & 127) of half the rows of a stage: the groups of 8 rows
+  // (tid >> 7), (tid >> 7) + 2, ...
+  const int col = tid & 127, g_first = __builtin_amdgcn_readfirstlane(tid >> 7);   // the same for a whole wave
+  float px[8 * kGradKS], pd[8 * kGradKS];
   int ckh = 0, ckw = 0, cc = 0;
   if (CONV) {                                        // the kernel position of this thread's column is fixed
     const int k = min(k0 + col, a.K - 1);
@@ -605,21 +612,30 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   auto stage_rows = [&](int m0, int buf) {            // CONV: the first threads decompose the stage's rows
     if (CONV && tid < kGradMS) crow[buf][tid] = conv_row(a.conv, min(m0 + tid, a.M - 1));
   };
+  // Loads without branches (a load behind a per-element bounds test costs two jumps and an execution-mask
+  // round trip each): indices are clamped into the tensors here, and what lies outside is replaced by zero
+  // where the values are used, one stage later, so that no load is waited for before the matrix instructions.
+  const bool k_ok = k0 + col < a.K, n_ok = n0 + col < a.N;
+  const int kc = min(k0 + col, a.K - 1), nc = min(n0 + col, a.N - 1);
+  const long long conv_col = CONV ? ((long long)ckh * a.conv.W + ckw) * a.conv.C + cc : 0;
+  auto inside_image = [&](int buf, int row) {
+    const int ih = crow[buf][row].ih0 + ckh, iw = crow[buf][row].iw0 + ckw;
+    return ih >= 0 && ih < a.conv.H && iw >= 0 && iw < a.conv.W;
+  };
   auto prefetch = [&](int m0, int buf) {
+    // one 64-bit product per stage and operand; the row offsets are the same for every lane (scalar arithmetic)
+    const float* xrow = a.X + (size_t)m0 * a.K + kc;
+    const float* drow = a.D + (size_t)m0 * a.N + nc;
+    const int last = a.M - 1 - m0;
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
+    for (int q = 0; q < kGradKS; ++q)
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = (g_first + 2 * q) * 8 + e;
-        const int m = m0 + row;
-        float x = 0.0f, d = 0.0f;
-        if (m < m_end) {
-          if (k0 + col < a.K)
-            x = CONV ? conv_fetch(a.X, a.conv, crow[buf][row], ckh, ckw, cc) : a.X[(size_t)m * a.K + k0 + col];
-          if (n0 + col < a.N) d = a.D[(size_t)m * a.N + n0 + col];
-        }
-        px[q * 8 + e] = x;
-        pd[q * 8 + e] = d;
+        const int rc = min(row, last);
+        if (CONV) px[q * 8 + e] = a.X[inside_image(buf, row) ? crow[buf][row].off + conv_col : 0];
+        else px[q * 8 + e] = xrow[(size_t)rc * a.K];
+        pd[q * 8 + e] = drow[(size_t)rc * a.N];
       }
   };
   int stage = 0;
@@ -630,14 +646,17 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     if (m0 + kGradMS < m_end) stage_rows(m0 + kGradMS, stage ^ 1);
     __syncthreads();
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < kGradKS; ++q) {
       bf16x8 xh, xl, dh, dl;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
+        const int row = (g_first + 2 * q) * 8 + e;
+        const bool row_ok = m0 + row < m_end;
+        const bool x_ok = row_ok && k_ok && (!CONV || inside_image(stage, row));
         __bf16 h, l;
-        split_bf16(px[q * 8 + e], h, l);
+        split_bf16(x_ok ? px[q * 8 + e] : 0.0f, h, l);
         xh[e] = h; xl[e] = l;
-        split_bf16(pd[q * 8 + e], h, l);
+        split_bf16((row_ok && n_ok) ? pd[q * 8 + e] : 0.0f, h, l);
         dh[e] = h; dl[e] = l;
       }
       xs[0][g_first + 2 * q][col] = xh;
@@ -648,10 +667,10 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
     __syncthreads();
     if (m0 + kGradMS < m_end) prefetch(m0 + kGradMS, stage ^ 1);
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      // batch shares: two shares alternate over the k-steps of a stage, four also over the stages
-      if (PARTS == 2 && ks != share) continue;
-      if (PARTS == 4 && (ks != (share & 1) || (stage != (share >> 1)))) continue;
+    for (int ks = 0; ks < kGradKS; ++ks) {
+      // batch shares: two shares alternate over the k-steps of a stage, four take one k-step in four
+      if (PARTS == 2 && (ks & 1) != share) continue;
+      if (PARTS == 4 && (ks & 3) != share) continue;
       const int g8 = 2 * ks + (lane >> 5);
       bf16x8 ah[2], al[2], bh[2], bl[2];
 #pragma unroll
@@ -671,7 +690,7 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
         }
     }
   }
-  float* out = a.part + ((size_t)blockIdx.y * PARTS + share) * a.K * a.N;
+  float* out = a.part + ((size_t)chunk_id * PARTS + share) * a.K * a.N;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -1130,7 +1149,8 @@ UpdPlan plan_update(int M, int K, int N) {
   p.KB = cdiv(K, 128);
   p.NB = cdiv(N, 128);
   const int tiles = p.KB * p.NB;
-  int want = std::max(1, cdiv(1024, tiles));
+  // two resident blocks per compute unit: more batch chunks only add partial sums (measured: 512 blocks beat 256, 1024, 2048)
+  int want = std::max(1, cdiv(512, tiles));
   int per = std::max(kGradMS, cdiv(cdiv(M, want), kGradMS) * kGradMS);
   p.m_per_chunk = per;
   p.mchunks = cdiv(M, per);
@@ -1297,7 +1317,9 @@ int run_update(const xbar_config* cfg, float* W, const float* X, const float* dY
   g.X = X; g.D = dY; g.part = reinterpret_cast<float*>(ws);
   g.M = M; g.K = K; g.N = N; g.KB = p.KB; g.NB = p.NB; g.m_per_chunk = p.m_per_chunk;
   {
-    const dim3 grid((unsigned)(p.KB * p.NB), (unsigned)p.mchunks), block(256);
+    g.total_wg = p.KB * p.NB * p.mchunks;
+    g.per_xcd = cdiv(g.total_wg, 8);
+    const dim3 grid((unsigned)(g.per_xcd * 8)), block(256);
     if (conv) {
       g.conv = *conv;
       if (K <= 64 && N <= 64) hipLaunchKernelGGL((grad_gemm_kernel<true, true, true>), grid, block, 0, st, g);
