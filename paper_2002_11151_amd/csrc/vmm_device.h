@@ -466,8 +466,10 @@ __device__ __forceinline__ void vmm6_contract_adc(const int4v (&dg)[PM][NK64], c
     const int off = (f / NK64) * STRIDE + (f % NK64) * 1536;
     fx[i] = *reinterpret_cast<const u32x4*>(xb + off);
     fy[i] = *reinterpret_cast<const u32x2*>(yb + off);
+    // keeps the 8-byte reads of the first two fragments apart: merged into one instruction they land in
+    // registers of their own and have to be copied behind the 16-byte parts
+    __builtin_amdgcn_sched_barrier(0);
   }
-  __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
   for (int i = 0; i < NF; ++i) {
     const u32x4 cx = fx[i % PF];
