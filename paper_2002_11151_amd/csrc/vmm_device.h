@@ -6,6 +6,7 @@
 #define XBAR_VMM_DEVICE_H_
 
 #include "xbar_common.h"
+#include <type_traits>
 
 namespace xbar_detail {
 
@@ -416,20 +417,24 @@ typedef int int16v __attribute__((ext_vector_type(16)));
 // LDS bytes of one (slice, term): its fragments of 1.5 KiB, rounded up to the whole KiB that the staging copies move
 __host__ __device__ constexpr int f6_term_stride(int nk64) { return ((nk64 * 1536 + 1023) / 1024) * 1024; }
 
-// Digits of one streaming cycle as E2M1 codes (digit d is code d, value d / 2): the bytes of two input
-// words become the low and the high 4-bit fields of one operand word (2 rotates, 1 AND, 1 AND-OR per
-// 8 inputs).  `low_mask` has the digit mask in every byte.
-template <int NK64>
-__device__ __forceinline__ void digit_codes_f4(const u32x2 (&raw)[4 * NK64], int in_shift, uint32_t low_mask, int4v (&dg)[NK64]) {
-  const uint32_t rot_lo = (uint32_t)in_shift & 31u, rot_hi = (uint32_t)(in_shift - 4) & 31u;
+// Digits of one streaming cycle as E2M1 codes (digit d is code d, value d / 2).  The input stage stores the 8-bit
+// magnitudes of a lane's 8 inputs nibble by nibble: 4-bit field f of word 0 holds the low four bits of input
+// f / 2 of the first (f even) or the second (f odd) group of four, word 1 the high four bits; a cycle's digits are
+// then one shift and one AND per 8 inputs.  HIGH: the cycle's bits lie in the high nibbles (word 1);
+// `shift`: their place within the nibble; `nibble_mask`: the digit mask in every 4-bit field.
+template <int NK64, bool HIGH>
+__device__ __forceinline__ void digit_codes_f4(const u32x2 (&raw)[4 * NK64], int shift, uint32_t nibble_mask, int4v (&dg)[NK64]) {
 #pragma unroll
   for (int J = 0; J < NK64; ++J)
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const u32x2 r = raw[4 * J + w];
-      const uint32_t lo = __builtin_amdgcn_alignbit(r.x, r.x, rot_lo) & low_mask;
-      dg[J][w] = (int)((__builtin_amdgcn_alignbit(r.y, r.y, rot_hi) & (low_mask << 4)) | lo);
-    }
+    for (int w = 0; w < 4; ++w) dg[J][w] = (int)(((HIGH ? raw[4 * J + w].y : raw[4 * J + w].x) >> shift) & nibble_mask);
+}
+
+// The same for a cycle whose place is known at run time only (general path).
+template <int NK64>
+__device__ __forceinline__ void digit_codes_f4_any(const u32x2 (&raw)[4 * NK64], int in_shift, uint32_t nibble_mask, int4v (&dg)[NK64]) {
+  if (in_shift >= 4) digit_codes_f4<NK64, true>(raw, in_shift - 4, nibble_mask, dg);
+  else digit_codes_f4<NK64, false>(raw, in_shift, nibble_mask, dg);
 }
 
 // acc = c + 2^(scale of the term) * (E2M3 plane fragment) x (E2M1 digits); the scale byte of term 0..3 is
@@ -513,7 +518,7 @@ __device__ __forceinline__ void vmm6_tile_group_pipelined(const VmmArgs& a, cons
                                                           int ns, int shift_slice0, int p, int pol, int lane,
                                                           uint32_t (&y)[PM][16]) {
   constexpr int SLICE = NT * f6_term_stride(NK64);
-  const uint32_t low_mask = ((1u << a.stream_bits) - 1u) * 0x01010101u;
+  const uint32_t nibble_mask = ((1u << a.stream_bits) - 1u) * 0x11111111u;
   float gain_p, clamp_lo, clamp_hi;
   adc_sign_and_range<PER_ARRAY>(a, p, pol, gain_p, clamp_lo, clamp_hi);
   const float gain = 2.0f * gain_p;                   // a digit enters as d / 2
@@ -522,10 +527,11 @@ __device__ __forceinline__ void vmm6_tile_group_pipelined(const VmmArgs& a, cons
   int4v dg[PM][NK64];
   float16v acc0[PM], acc1[PM];
   int sh_prev = 0;
-  for (int b = 0; b < a.S_in; ++b) {
+  // one streaming cycle: digits, then every slice pair; `high`: the cycle's bits are in the high nibbles
+  auto cycle = [&](int b, auto high) {
     const int in_shift = a.stream_bits * b;
 #pragma unroll
-    for (int pm = 0; pm < PM; ++pm) digit_codes_f4<NK64>(raw[pm], in_shift, low_mask, dg[pm]);
+    for (int pm = 0; pm < PM; ++pm) digit_codes_f4<NK64, decltype(high)::value>(raw[pm], in_shift & 3, nibble_mask, dg[pm]);
     for (int sl = 0; sl < ns; sl += 2) {
       const int sh0 = a.slice_bits * (shift_slice0 + sl) + in_shift;
       const int sh1 = sh0 + a.slice_bits;
@@ -539,7 +545,10 @@ __device__ __forceinline__ void vmm6_tile_group_pipelined(const VmmArgs& a, cons
                                             clamp_hi, sh0, y, a.scale_lo, a.scale_hi);
       sh_prev = sh1;
     }
-  }
+  };
+  const int b_low = min(a.S_in, 4 / a.stream_bits);   // cycles whose bits lie in the low nibbles
+  for (int b = 0; b < b_low; ++b) cycle(b, std::false_type{});
+  for (int b = b_low; b < a.S_in; ++b) cycle(b, std::true_type{});
   vmm_adc_narrow<PM>(acc1, gain, clamp_lo, clamp_hi, sh_prev, y);   // drain
 }
 
@@ -549,7 +558,7 @@ __device__ __forceinline__ void vmm6_tile_group(const VmmArgs& a, const char* ld
                                                 int sg0, int p, int pol, int t, int lane, int mp0, int op,
                                                 uint32_t (&y)[PM][16], long long (&y64)[PM][16]) {
   constexpr int SLICE = NT * f6_term_stride(NK64);
-  const uint32_t low_mask = ((1u << a.stream_bits) - 1u) * 0x01010101u;
+  const uint32_t nibble_mask = ((1u << a.stream_bits) - 1u) * 0x11111111u;
   float gain_p, clamp_lo, clamp_hi;
   adc_sign_and_range<PER_ARRAY>(a, p, pol, gain_p, clamp_lo, clamp_hi);
   const float gain = 2.0f * gain_p;
@@ -559,7 +568,7 @@ __device__ __forceinline__ void vmm6_tile_group(const VmmArgs& a, const char* ld
     const int in_shift = a.stream_bits * b;
     int4v dg[PM][NK64];
 #pragma unroll
-    for (int pm = 0; pm < PM; ++pm) digit_codes_f4<NK64>(raw[pm], in_shift, low_mask, dg[pm]);
+    for (int pm = 0; pm < PM; ++pm) digit_codes_f4_any<NK64>(raw[pm], in_shift, nibble_mask, dg[pm]);
     for (int sl = 0; sl < ns; ++sl) {
       const int s = sg0 + sl;
       const int sh = a.slice_bits * s + in_shift;

@@ -380,13 +380,24 @@ __global__ __launch_bounds__(256) void weight_sums_kernel(SumArgs a) {
 // ---------------------------------------------------------------------------------------------
 struct QuantArgs {
   const float* X;
-  uint8_t* A;        // [phase][MP][T][ks][64 lanes][8 bytes]
+  uint8_t* A;        // [phase][MP][T][ks][64 lanes][8 bytes]: magnitudes (fp16 path) or their nibbles (6-bit path)
   int M, L, MP, T, ks, tile, P, input_bits;
   int offset;        // signed inputs as offset-binary codes in one phase (P == 1)
+  int nibbles;       // 6-bit path: a lane's 8 bytes nibble by nibble (word 0: low nibbles, word 1: high nibbles)
   float scale;
   long long n_threads;
   ConvGeom conv;     // used by the CONV instantiation only
 };
+
+// The 8 magnitudes of a lane (bytes of v.x, then of v.y) as the contraction kernel of the 6-bit path reads them:
+// 4-bit field 2 j of word 0 holds the low nibble of byte j of v.x, field 2 j + 1 that of byte j of v.y; word 1
+// the high nibbles in the same places.  A streaming cycle's digits are then one shift and one AND away.
+__device__ __forceinline__ u32x2 nibble_words(u32x2 v) {
+  u32x2 z;
+  z.x = (v.x & 0x0f0f0f0fu) | ((v.y & 0x0f0f0f0fu) << 4);
+  z.y = ((v.x >> 4) & 0x0f0f0f0fu) | (v.y & 0xf0f0f0f0u);
+  return z;
+}
 
 template <bool CONV>
 __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
@@ -485,6 +496,10 @@ __global__ __launch_bounds__(256) void quantize_input_kernel(QuantArgs a) {
         pos.b[e] = (uint8_t)(code[e] > 0 ? code[e] : 0);
         neg.b[e] = (uint8_t)(code[e] < 0 ? -code[e] : 0);
       }
+    }
+    if (a.nibbles) {
+      pos.v = nibble_words(pos.v);
+      if (a.P == 2) neg.v = nibble_words(neg.v);
     }
     const size_t blk = ((size_t)mp * a.T + t) * a.ks + j;
     out[blk * 64 + lane] = pos.v;
@@ -1018,7 +1033,7 @@ __global__ __launch_bounds__(256, 2) void contraction_loop_probe_kernel(float* o
     const int sl = (it & 1) * 2;
     if ((it & 1) == 0) {
 #pragma unroll
-      for (int pm = 0; pm < 2; ++pm) digit_codes_f4<2>(raw[pm], (it >> 1) & 7, 0x01010101u, dg[pm]);
+      for (int pm = 0; pm < 2; ++pm) digit_codes_f4<2, false>(raw[pm], (it >> 1) & 3, 0x11111111u, dg[pm]);
     }
     vmm6_contract_adc<2, 2, 4, DO_ADC>(dg, xb + sl * SLICE, yb + sl * SLICE, acc0, acc1, 3.96875f, kMagic - 127.0f,
                                        kMagic + 127.0f, it & 15, y, scale_lo, scale_hi);
@@ -1199,6 +1214,7 @@ int run_vmm(const xbar_config* cfg, const void* planes, const float* in, float* 
   qa.M = M; qa.L = p.Lin; qa.MP = p.MP; qa.T = p.g.T; qa.ks = p.ks16; qa.tile = p.g.tile; qa.P = p.P;
   qa.input_bits = cfg->input_bits;
   qa.offset = p.offset;
+  qa.nibbles = d.fmt == kFmtF6 ? 1 : 0;
   qa.scale = in_scale;
   qa.n_threads = (long long)p.MP * p.g.T * ((p.ks16 + 1) / 2) * 64;
   if (conv) {
