@@ -27,7 +27,7 @@ KERNEL_NAME = {0: "vmm_kernel (fp16 MFMA contraction + ADC + shift-and-add, fwd 
                1: "vmm6_kernel (block-scaled 6-bit x 4-bit MFMA contraction + ADC + shift-and-add, fwd and bwd launches)"}
 # HBM bytes per contraction-kernel launch (average over the 108 launches of a step) of the default workload:
 # recorded from the FETCH_SIZE / WRITE_SIZE counter runs in the profile named here, not measured in this run
-VMM_TRAFFIC_BYTES_RESNET50_B64 = 537208832      # (153293 KiB FETCH_SIZE x 2.00 + 218032 KiB WRITE_SIZE x 1.00) x 1024
+VMM_TRAFFIC_BYTES_RESNET50_B64 = 532760064      # (152244 KiB FETCH_SIZE x 2.00 + 215786 KiB WRITE_SIZE x 1.00) x 1024
 VMM_TRAFFIC_SOURCE = "profiles/vmm6_kernel_resnet50_batch64.txt"
 
 

@@ -633,25 +633,31 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
   const bool k_ok = k0 + col < a.K, n_ok = n0 + col < a.N;
   const int kc = min(k0 + col, a.K - 1), nc = min(n0 + col, a.N - 1);
   const long long conv_col = CONV ? ((long long)ckh * a.conv.W + ckw) * a.conv.C + cc : 0;
-  auto inside_image = [&](int buf, int row) {
-    const int ih = crow[buf][row].ih0 + ckh, iw = crow[buf][row].iw0 + ckw;
-    return ih >= 0 && ih < a.conv.H && iw >= 0 && iw < a.conv.W;
-  };
+  uint32_t inside = 0;       // CONV: bit (q * 8 + e) set when that element of the fetched stage lies inside the image
   auto prefetch = [&](int m0, int buf) {
     // one 64-bit product per stage and operand; the row offsets are the same for every lane (scalar arithmetic)
     const float* xrow = a.X + (size_t)m0 * a.K + kc;
     const float* drow = a.D + (size_t)m0 * a.N + nc;
     const int last = a.M - 1 - m0;
+    uint32_t in = 0;
 #pragma unroll
     for (int q = 0; q < kGradKS; ++q)
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const int row = (g_first + 2 * q) * 8 + e;
         const int rc = min(row, last);
-        if (CONV) px[q * 8 + e] = a.X[inside_image(buf, row) ? crow[buf][row].off + conv_col : 0];
-        else px[q * 8 + e] = xrow[(size_t)rc * a.K];
+        if (CONV) {
+          const ConvRow r = crow[buf][row];
+          const int ih = r.ih0 + ckh, iw = r.iw0 + ckw;
+          const bool ok = (ih >= 0) & (ih < a.conv.H) & (iw >= 0) & (iw < a.conv.W);
+          px[q * 8 + e] = a.X[ok ? r.off + conv_col : 0];
+          in |= (ok ? 1u : 0u) << (q * 8 + e);
+        } else {
+          px[q * 8 + e] = xrow[(size_t)rc * a.K];
+        }
         pd[q * 8 + e] = drow[(size_t)rc * a.N];
       }
+    inside = in;
   };
   int stage = 0;
   stage_rows(m_begin, 0);
@@ -667,11 +673,11 @@ __global__ __launch_bounds__(256) void grad_gemm_kernel(GradArgs a) {
       for (int e = 0; e < 8; ++e) {
         const int row = (g_first + 2 * q) * 8 + e;
         const bool row_ok = m0 + row < m_end;
-        const bool x_ok = row_ok && k_ok && (!CONV || inside_image(stage, row));
+        const bool x_ok = row_ok & k_ok & (!CONV || ((inside >> (q * 8 + e)) & 1u) != 0);
         __bf16 h, l;
         split_bf16(x_ok ? px[q * 8 + e] : 0.0f, h, l);
         xh[e] = h; xl[e] = l;
-        split_bf16((row_ok && n_ok) ? pd[q * 8 + e] : 0.0f, h, l);
+        split_bf16((row_ok & n_ok) ? pd[q * 8 + e] : 0.0f, h, l);
         dh[e] = h; dl[e] = l;
       }
       xs[0][g_first + 2 * q][col] = xh;
