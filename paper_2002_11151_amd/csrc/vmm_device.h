@@ -387,7 +387,7 @@ __device__ __forceinline__ void vmm_tile(const VmmArgs& a, u32x4* lds, int p, in
     // between, all copies of a wave in flight at once): lane l of the wave supplies the address of
     // its 16 bytes, the hardware writes them at fragment base + 16 l.
     const int nwv = blockDim.x >> 6, nfr = ns * NF;
-    for (int f = threadIdx.x >> 6; f < nfr; f += nwv) {
+    for (int f = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); f < nfr; f += nwv) {   // wave index: scalar
       const int sl = f / NF, r = f - sl * NF;
       const int term = r / NK, j = r - term * NK;
       // LDS order within a slice = global order: leading term (0), then residual term (1)
@@ -605,7 +605,7 @@ __device__ __forceinline__ void vmm6_tile(const VmmArgs& a, u32x4* lds, int p, i
     if constexpr (PER_ARRAY) src += (size_t)pol * a.pol_stride;
     __syncthreads();                                   // everyone is done with the previous group
     const int nwv = blockDim.x >> 6, ncopy = ns * NT * UNITS;
-    for (int c = threadIdx.x >> 6; c < ncopy; c += nwv) {
+    for (int c = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6); c < ncopy; c += nwv) {   // wave index: scalar
       const int st = c / UNITS, u = c - st * UNITS;    // (slice, term) pair, KiB within it
       copy16_global_to_lds(src + (size_t)st * a.ks * 96 + u * 64 + lane, lds + (st * UNITS + u) * 64);
     }
@@ -664,7 +664,8 @@ struct TileF6 {
 
 template <int PM, int WIDE, bool CODES, bool PER_ARRAY, class TileFn>
 __device__ __forceinline__ void vmm_block(const VmmArgs& a, u32x4* lds, const TileFn& run_tile) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  // the wave index is the same for all lanes: as a scalar, everything derived from it (row patches, addresses) is scalar too
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nw = blockDim.x >> 6;
   // consecutive block ids go to different XCDs; give each XCD a contiguous range of logical work so
   // that blocks sharing the same planes share one L2
   const int logical = (blockIdx.x & 7) * a.per_xcd + (blockIdx.x >> 3);
