@@ -57,10 +57,11 @@ struct TileArgs {
 
 // Plane value of slice s of weight (k, n), in units of one device level: the signed difference of the
 // device pair, or the conductance of one of the two devices.
+// pol_out: -1: difference of the pair (array 0 minus array 1); 0 / 1: that array alone.
 __device__ __forceinline__ double plane_value(const TileArgs& a, NormalStream& rng, int sign, int digit, int s, int k,
-                                              int n) {
-  if (a.flags & XBAR_NI_WIRE_AAM2) return a.wire_u[((size_t)(2 * s + (a.pol_out > 0 ? 1 : 0)) * a.K + k) * a.N + n];
-  if (a.pol_out < 0 && !(a.flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE)))
+                                              int n, int pol_out) {
+  if (a.flags & XBAR_NI_WIRE_AAM2) return a.wire_u[((size_t)(2 * s + (pol_out > 0 ? 1 : 0)) * a.K + k) * a.N + n];
+  if (pol_out < 0 && !(a.flags & (XBAR_NI_VARIATION | XBAR_NI_WIRE_AAM | XBAR_NI_WIRE_PROFILE)))
     return (double)(sign * digit);
   double g[2];
   g[0] = a.g_min + (sign > 0 ? digit * a.dg : 0.0);
@@ -80,7 +81,12 @@ __device__ __forceinline__ double plane_value(const TileArgs& a, NormalStream& r
       g[pol] = g[pol] * (1.0 - dist);
     }
   }
-  return (a.pol_out < 0 ? g[0] - g[1] : g[a.pol_out]) / a.dg;
+  return (pol_out < 0 ? g[0] - g[1] : g[pol_out]) / a.dg;
+}
+
+__device__ __forceinline__ double plane_value(const TileArgs& a, NormalStream& rng, int sign, int digit, int s, int k,
+                                              int n) {
+  return plane_value(a, rng, sign, digit, s, k, n, a.pol_out);
 }
 
 // One thread produces the 8 consecutive contraction-index entries of one output column that make up
@@ -235,6 +241,103 @@ __global__ __launch_bounds__(256) void tile_planes_f6_kernel(TileArgs a) {
   }
 }
 
+
+// General 6-bit generator, first pass: one thread per device pair (k, n) and slice (blockIdx.y) computes the plane
+// value -- quantisation, variation draw, wire model: the arithmetic of tile_planes_f6_kernel -- once, splits it
+// into the terms of the schedule and stores the codes as one word per array: words[array][slice][k][n].
+__global__ __launch_bounds__(256) void device_words_kernel(TileArgs a, uint32_t* words, int npol) {
+  const long long tid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (tid >= (long long)a.K * a.N) return;
+  const int n = (int)(tid % a.N), k = (int)(tid / a.N);
+  const int s = blockIdx.y;
+  NormalStream rng(a.seed, kStreamVariation, effective_step(a.step, a.step_add));
+  const double qw = (double)((1u << a.weight_bits) - 1);
+  const uint32_t dmask = (1u << a.slice_bits) - 1;
+  const double q = ::rint(clampd((double)a.W[(size_t)k * a.N + n] / (double)a.w_max, -1.0, 1.0) * qw);
+  const int sign = (q > 0.0) - (q < 0.0);
+  const int digit = (int)(((uint32_t)::fabs(q) >> (a.slice_bits * s)) & dmask);
+  for (int pol = 0; pol < npol; ++pol) {
+    double left = plane_value(a, rng, sign, digit, s, k, n, npol == 2 ? pol : -1);
+    uint32_t word = 0;
+#pragma unroll
+    for (int j = 0; j < kMaxTermsF6; ++j) {
+      if (j >= a.terms) break;
+      double v;
+      const uint32_t code = e2m3_nearest(::ldexp(left, -a.term_exp[j]), v);
+      left -= ::ldexp(v, a.term_exp[j]);
+      word |= code << (6 * j);
+    }
+    words[(((size_t)pol * a.S_w + s) * a.K + k) * a.N + n] = word;
+  }
+}
+
+// Second pass: one plane copy from the words of its array (a.codes: [slice][k][n]), integer work only.  One wave
+// per fragment group (tile, output patch of 32, k-step of 64, slice): it reads the 64 x 32 words of its patch with
+// whole-line loads (along n, the fastest index of the words, whichever index this copy contracts over), turns them
+// through LDS, and every lane packs the 32 codes of its record for each term and writes it with one 16-byte and one
+// 8-byte store.  a.n_threads: 64 x the number of fragment groups.
+template <bool TRANSPOSED>
+__global__ __launch_bounds__(256) void tile_planes_f6_words_kernel(TileArgs a) {
+  __shared__ uint32_t turn[4][64][33];              // [wave][contraction entry][output], one word of padding per row
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const long long grp = (long long)blockIdx.x * 4 + wave;
+  if (grp * 64 >= a.n_threads) return;              // whole waves leave: no block-wide barrier below
+  const int J = (int)(grp % a.ks);
+  const int op = (int)((grp / a.ks) % a.OP);
+  const int t = (int)(grp / ((long long)a.ks * a.OP));
+  const int s = blockIdx.y;
+  const int Lc = TRANSPOSED ? a.N : a.K;
+  const int Lo = TRANSPOSED ? a.K : a.N;
+  const int rows = min(a.tile, Lc - t * a.tile);
+  if (J * 64 >= rows) return;                       // the contraction never reads this k-step
+  const int c_first = t * a.tile + J * 64;          // first contraction index of the group
+  const int c_count = min(64, rows - J * 64);       // entries beyond it are padding (zero codes)
+  const int o_first = op * 32;
+  const uint32_t* words = a.codes + (size_t)s * a.K * a.N;
+  uint32_t (&mine)[64][33] = turn[wave];
+  if (TRANSPOSED) {                                 // words[k = output][n = contraction]: a row of 64 entries per output
+    for (int ol = 0; ol < 32; ++ol) {
+      const int o = o_first + ol;
+      mine[lane][ol] = (o < Lo && lane < c_count) ? words[(size_t)o * a.N + c_first + lane] : 0u;
+    }
+  } else {                                          // words[k = contraction][n = output]: two rows of 32 outputs at a time
+    for (int cl = lane >> 5; cl < 64; cl += 2) {
+      const int o = o_first + (lane & 31);
+      mine[cl][lane & 31] = (o < Lo && cl < c_count) ? words[(size_t)(c_first + cl) * a.N + o] : 0u;
+    }
+  }
+  __builtin_amdgcn_wave_barrier();                  // one wave: its LDS writes are ordered before its LDS reads
+  const int ol = lane & 31, half = lane >> 5;
+  uint32_t rec[kMaxTermsF6][6];
+#pragma unroll
+  for (int j = 0; j < kMaxTermsF6; ++j)
+#pragma unroll
+    for (int x = 0; x < 6; ++x) rec[j][x] = 0u;
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t word = mine[w * 16 + half * 8 + e][ol];
+      const int code_at = 8 * w + 2 * (e & 3) + (e >> 2);   // place of this entry among the lane's 32 codes
+      const int bit = 6 * code_at, x = bit >> 5, sh = bit & 31;
+#pragma unroll
+      for (int j = 0; j < kMaxTermsF6; ++j) {
+        if (j >= a.terms) break;
+        const uint32_t code = (word >> (6 * j)) & 63u;
+        rec[j][x] |= code << sh;
+        if (sh > 26) rec[j][x + 1] |= code >> (32 - sh);
+      }
+    }
+  const size_t frag0 = (((size_t)t * a.OP + op) * a.S_w + s) * a.terms * a.ks + J;
+  uint8_t* base = reinterpret_cast<uint8_t*>(a.planes);
+#pragma unroll
+  for (int j = 0; j < kMaxTermsF6; ++j) {
+    if (j >= a.terms) break;
+    uint8_t* frag = base + (frag0 + (size_t)j * a.ks) * 1536;
+    *reinterpret_cast<u32x4*>(frag + lane * 16) = u32x4{rec[j][0], rec[j][1], rec[j][2], rec[j][3]};
+    *reinterpret_cast<u32x2*>(frag + 1024 + lane * 8) = u32x2{rec[j][4], rec[j][5]};
+  }
+}
 
 // Term codes of the plane value of every (sign, digit, row, column): one thread per (digit, row, column)
 // computes the value with the arithmetic of plane_value, splits it into the terms of the schedule and
@@ -1521,7 +1624,7 @@ int xbar_config_validate(const xbar_config* c) {
 size_t xbar_planes_bytes(const xbar_config* cfg, int K, int N) {
   if (xbar_config_validate(cfg) || check_shape(1, K, N)) return 0;
   const Derived d = derive(cfg);
-  return code_table_offset(cfg, d, K, N) + code_table_bytes(cfg, d);
+  return device_words_offset(cfg, d, K, N) + device_words_bytes(d, K, N);
 }
 
 size_t xbar_workspace_bytes(const xbar_config* cfg, int op, int M, int K, int N) {
@@ -1615,6 +1718,18 @@ int xbar_tile(const xbar_config* cfg, const float* W, int K, int N, float w_max,
         const dim3 grid(blocks, (unsigned)cdiv(d.S_w, a.spt));
         if (dir == 0) hipLaunchKernelGGL(tile_planes_f6_table_kernel<false>, grid, dim3(256), 0, st, a);
         else hipLaunchKernelGGL(tile_planes_f6_table_kernel<true>, grid, dim3(256), 0, st, a);
+      } else if (uses_device_words(d)) {
+        uint32_t* words = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(planes) + device_words_offset(cfg, d, K, N));
+        if (dir == 0 && pol == 0) {                  // every device once, for both copies and both arrays
+          const unsigned wblocks = (unsigned)(((long long)K * N + 255) / 256);
+          hipLaunchKernelGGL(device_words_kernel, dim3(wblocks, (unsigned)d.S_w), dim3(256), 0, st, a, words, d.npol);
+          if (hipGetLastError() != hipSuccess) return XBAR_EHIP;
+        }
+        a.codes = words + (size_t)pol * d.S_w * K * N;
+        a.n_threads = (long long)g.T * g.OP * g.ks * 64;   // one wave per fragment group
+        const dim3 pgrid((unsigned)((a.n_threads + 255) / 256), (unsigned)d.S_w);
+        if (dir == 0) hipLaunchKernelGGL(tile_planes_f6_words_kernel<false>, pgrid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL(tile_planes_f6_words_kernel<true>, pgrid, dim3(256), 0, st, a);
       } else if (dir == 0) hipLaunchKernelGGL(tile_planes_f6_kernel<false>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
       else hipLaunchKernelGGL(tile_planes_f6_kernel<true>, dim3(blocks, (unsigned)d.S_w), dim3(256), 0, st, a);
       if (hipGetLastError() != hipSuccess) return XBAR_EHIP;

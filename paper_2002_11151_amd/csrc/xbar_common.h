@@ -172,6 +172,14 @@ static inline size_t code_table_bytes(const xbar_config* c, const Derived& d) {
   return uses_code_table(d) ? align256(2 * code_table_words(c) * sizeof(uint32_t)) : 0;
 }
 
+// General 6-bit generator (variation, stored profile, all-paths model, one array alone): every device is computed
+// once -- its term codes as one 32-bit word (term j at bit 6 j), [array][slice][k][n], kept behind the table -- and
+// both plane copies are packed from those words.
+static inline bool uses_device_words(const Derived& d) { return d.fmt == kFmtF6 && !uses_code_table(d) && d.terms > 1; }
+static inline size_t device_words_bytes(const Derived& d, int K, int N) {
+  return uses_device_words(d) ? align256((size_t)4 * d.npol * d.S_w * K * N) : 0;
+}
+
 static inline PlaneGeom plane_geom(const xbar_config* c, const Derived& d, int K, int N, bool transposed) {
   PlaneGeom g;
   g.tile = transposed ? c->xbar_cols : c->xbar_rows;
@@ -191,6 +199,10 @@ static inline size_t weight_sums_offset(const xbar_config* c, const Derived& d, 
 
 static inline size_t code_table_offset(const xbar_config* c, const Derived& d, int K, int N) {
   return weight_sums_offset(c, d, K, N) + weight_sums_bytes(c, K, N);
+}
+
+static inline size_t device_words_offset(const xbar_config* c, const Derived& d, int K, int N) {
+  return code_table_offset(c, d, K, N) + code_table_bytes(c, d);
 }
 
 // ---------------------------------------------------------------------------------------------

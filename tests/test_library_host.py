@@ -104,14 +104,17 @@ def test_size_queries(xb):
     # words) rides behind the planes
     table = 2 * 2 * 3 * 128 * 128 * 4
     assert xb.planes_bytes(c, K, N) == frag(4) + table
-    assert xb.planes_bytes(xb.make_config(flags=xb.NI_WIRE_AAM | xb.NI_VARIATION, **base), K, N) == frag(5)
+    # any other array non-ideality: every device is computed once into a word of term codes per array, slice and
+    # weight, kept behind the planes, from which both copies are packed
+    words = lambda arrays=1: pad256(4 * arrays * 8 * K * N)
+    assert xb.planes_bytes(xb.make_config(flags=xb.NI_WIRE_AAM | xb.NI_VARIATION, **base), K, N) == frag(5) + words()
     assert xb.planes_bytes(xb.make_config(**base), K, N) == frag(1)
-    assert xb.planes_bytes(xb.make_config(flags=xb.ADC_PER_ARRAY, **base), K, N) == frag(5, 2)
+    assert xb.planes_bytes(xb.make_config(flags=xb.ADC_PER_ARRAY, **base), K, N) == frag(5, 2) + words(2)
     # a general DAC level table runs on the fp16 path
     lut = xb.make_config(flags=xb.NI_WIRE_AAM | xb.DAC_LUT, stream_bits=2, dac_lut=[0.0, 0.3, 0.7, 1.0], **base)
     assert xb.planes_bytes(lut, K, N) == fwd + bwd
     all_paths = xb.make_config(flags=xb.NI_WIRE_AAM2, **base)
-    assert xb.planes_bytes(all_paths, K, N) == frag(5) + 16 * 8 * K * N + 4 * K * N      # scratch behind the planes
+    assert xb.planes_bytes(all_paths, K, N) == frag(5) + 16 * 8 * K * N + 4 * K * N + words()   # scratch behind the planes
     fwd, bwd = frag(4) // 2, frag(4) // 2
     # offset-binary inputs: the 64-bit sums of the programmed weights per column and per row ride along
     coded = xb.make_config(xbar_rows=128, xbar_cols=128, weight_bits=16, slice_bits=2, flags=xb.NI_WIRE_AAM | xb.INPUT_OFFSET)
