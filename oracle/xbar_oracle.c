@@ -80,7 +80,7 @@ typedef struct xo_config {
 
 /* ------------------------------------------------------------------------------------------- */
 /* Counter-based random numbers: Philox-4x32 with 10 rounds (Salmon et al., SC'11), written from */
-/* the published round function; then Box-Muller.  The paper only says "Gaussian".              */
+/* the published round function; then Box-Muller.  The paper names the distribution only.      */
 /* ------------------------------------------------------------------------------------------- */
 void xo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
   uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
