@@ -156,8 +156,10 @@ uint32_t xbar_abi_version(void);
  *   profile  [S_w][2][K][N] float distortion D (index 1: 0 = positive array), G <- G (1 - D);
  *            required with XBAR_NI_WIRE_PROFILE, ignored otherwise
  *   planes   output, xbar_planes_bytes(cfg, K, N) bytes, opaque
- * With XBAR_NI_WIRE_AAM2 the plane buffer also holds (16 S_w + 4) K N bytes of scratch (the size query
- * includes them); tile (i, j) indices count from the tile's first row / column, devices beyond K / N
+ * With XBAR_NI_WIRE_AAM2 the plane buffer also holds (16 S_w + 4) K N bytes of scratch, and wherever 6-bit planes
+ * carry an array non-ideality other than the single-path wire model alone (variation, profile, all-paths model,
+ * XBAR_ADC_PER_ARRAY) 4 S_w K N bytes per array: every device is computed once there and both copies are packed
+ * from it (the size query includes both); tile (i, j) indices count from the tile's first row / column, devices beyond K / N
  * carry no current.
  * Device (slice s, array pol) of weight (k, n) uses normal number ((k N + n) S_w + s) 2 + pol of
  * the variation stream.  Rows / columns beyond K / N hold no device.
